@@ -1,0 +1,28 @@
+"""Compile the CPU oracle (plain C, gcc) into oracle/libmw_oracle.so.
+
+Test infrastructure only: run by the test suite, the smoke check and the
+build step; nothing in the product path depends on it.
+"""
+from __future__ import annotations
+
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(HERE, "mw_oracle.c")
+LIB = os.path.join(HERE, "libmw_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    if (not force and os.path.exists(LIB)
+            and os.path.getmtime(LIB) >= os.path.getmtime(SRC)):
+        return LIB
+    tmp = LIB + ".tmp%d" % os.getpid()
+    subprocess.check_call(["gcc", "-std=c99", "-O2", "-Wall", "-Wextra", "-fPIC", "-shared",
+                           SRC, "-o", tmp])
+    os.replace(tmp, LIB)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(force=True))

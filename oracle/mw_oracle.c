@@ -1,0 +1,477 @@
+/*
+ * mw_oracle.c -- plain, slow, single-threaded CPU oracle for one rank's share
+ * of a MultiWrite dispatch (MoE AlltoAll) or AllGather.
+ *
+ * THIS IS TEST INFRASTRUCTURE.  Only the tests, the smoke check and the
+ * cpu_baseline leg of the benchmark may build, load or call it.  It shares no
+ * code, header, table or helper with the HIP library: the record layouts
+ * below are typed out again here on purpose.
+ *
+ * What the paper fixes (and this file follows):
+ *   - Section 4.3.1: MultiWrite(S, M, B_S) writes the content of the source
+ *     buffer to the target buffer at every destination in M.  For a dispatch
+ *     this means: every token reaches every rank that hosts one of its top-k
+ *     experts, and what arrives is exactly what one unicast write per
+ *     destination would have delivered (Section 4.3.4, "drop-in replacement").
+ *   - Section 4.1, "Encoding scheme of metadata": destinations are a
+ *     fixed-size bitmap indexed by rank, ranks numbered from zero, bit r set
+ *     iff rank r is a target; a preconfigured table maps addresses (here:
+ *     expert ids) to ranks.  Section 6.4 allows wider bitmaps for more than
+ *     64 ranks.
+ *   - Section 1 / Section 2.3.2: one copy of the data is injected however
+ *     many destinations it has; unicast injects one copy per destination.
+ *   - Section 4.1 workflow steps 3-4: the receiver parses the carried
+ *     metadata and, if it is one of the destinations, delivers the payload.
+ *   - Section 5.2: AllGather, every rank's fragment ends up at every rank.
+ * What the paper leaves open (order of groups, record layouts, tie-breaks)
+ * is fixed by the reading stated next to each function.
+ *
+ * Two independent derivations of the receive-side result live here:
+ *   tier 1  ref_dispatch_plain(): the plain definition, straight from
+ *           (peer, token, top-k) with no bitmaps, groups or packed buffers;
+ *   tier 2  ref_plan -> ref_pack -> ref_deliver -> ref_unpack: the method's
+ *           steps.  The tests require both to agree bytewise.
+ *
+ * Pins (tests/test_oracle_*.py): brute force on tiny inputs written
+ * separately in Python, closed forms for E[popcount], the K=1 case against a
+ * library stable sort (plain AlltoAllV), the all-equal-mask case against
+ * memcpy, AllGather against array concatenation, the (token, destination)
+ * exactly-once property, tier 1 == tier 2, and the paper's printed
+ * arithmetic (C(64,8), 128 B vs 8 B metadata, 128 B / 4096 B).
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define REF_OK            0
+#define REF_ERR_ARG      -1
+#define REF_ERR_EXPERT   -2   /* expert id outside {-1} U [0, E) */
+#define REF_ERR_CAPACITY -3
+#define REF_ERR_INPUT    -4   /* inconsistent received buffer */
+
+#define REF_MASK_WORDS 4      /* 256-bit destination bitmap, word w bit b <-> rank 64*w + b */
+#define REF_MAX_RANKS  256
+
+typedef struct {
+    uint64_t mask[REF_MASK_WORDS];
+    uint32_t row_offset;      /* first packed row of the group */
+    uint32_t row_count;       /* rows in the group */
+    uint32_t n_dest;          /* popcount(mask) */
+    uint32_t reserved0;       /* always 0 */
+} ref_group_desc;             /* 48 bytes */
+
+typedef struct {
+    uint32_t n_rows;          /* N: tokens with a non-empty destination set */
+    uint32_t n_groups;        /* G */
+    uint64_t multicast_bytes; /* N * row_bytes */
+    uint64_t unicast_bytes;   /* row_bytes * sum over tokens of |destination set| */
+    uint32_t rows_per_dest[REF_MAX_RANKS];
+    uint32_t error_flags;     /* oracle: always 0 (it returns errors instead) */
+    uint32_t reserved0;
+} ref_send_stats;             /* 1056 bytes */
+
+typedef struct {
+    const ref_group_desc *desc;
+    uint32_t n_desc;
+    uint32_t n_rows;
+    const uint8_t *rows;           /* [n_rows][row_bytes] */
+    const int32_t *row_src_token;  /* [n_rows] */
+    const int32_t *row_topk;       /* [n_rows][K] */
+} ref_recv_peer;
+
+typedef struct {
+    const int32_t *topk;      /* [n_tokens][K] */
+    int32_t n_tokens;
+    const uint8_t *x;         /* [n_tokens][x_row_bytes]; rows not routed to this rank are never read */
+    const uint8_t *scales;    /* [n_tokens][s_row_bytes] or NULL when s_row_bytes == 0 */
+} ref_peer_tokens;
+
+/* ------------------------------------------------------------------------ */
+static int mask_bit(const uint64_t *m, int r) { return (int)((m[r >> 6] >> (r & 63)) & 1u); }
+
+static int mask_popcount(const uint64_t *m)
+{
+    int n = 0;
+    for (int r = 0; r < REF_MAX_RANKS; ++r) n += mask_bit(m, r);
+    return n;
+}
+
+/* compare as unsigned 256-bit integers, word 3 most significant */
+static int mask_cmp(const uint64_t *a, const uint64_t *b)
+{
+    for (int w = REF_MASK_WORDS - 1; w >= 0; --w) {
+        if (a[w] < b[w]) return -1;
+        if (a[w] > b[w]) return 1;
+    }
+    return 0;
+}
+
+/*
+ * Destination bitmap of every token (Section 4.1, bitmap encoding): bit
+ * expert_to_rank[e] is set for every valid id e in the token's top-k list.
+ * -1 means "no expert" and is skipped; duplicates set the same bit again.
+ */
+int ref_masks(const int32_t *topk, int32_t T, int32_t K,
+              const int32_t *expert_to_rank, int32_t E, int32_t R,
+              uint64_t *mask /* [T][4] */)
+{
+    if (R < 1 || R > REF_MAX_RANKS || T < 0 || K < 1 || E < 0) return REF_ERR_ARG;
+    for (int32_t e = 0; e < E; ++e)
+        if (expert_to_rank[e] < 0 || expert_to_rank[e] >= R) return REF_ERR_ARG;
+    for (int32_t t = 0; t < T; ++t) {
+        uint64_t *m = mask + (size_t)t * REF_MASK_WORDS;
+        m[0] = m[1] = m[2] = m[3] = 0;
+        for (int32_t j = 0; j < K; ++j) {
+            int32_t e = topk[(size_t)t * K + j];
+            if (e == -1) continue;
+            if (e < 0 || e >= E) return REF_ERR_EXPERT;
+            int32_t r = expert_to_rank[e];
+            m[r >> 6] |= (uint64_t)1 << (r & 63);
+        }
+    }
+    return REF_OK;
+}
+
+typedef struct { const uint64_t *mask; int32_t token; } sort_item;
+
+static int sort_item_cmp(const void *pa, const void *pb)
+{
+    const sort_item *a = (const sort_item *)pa, *b = (const sort_item *)pb;
+    int c = mask_cmp(a->mask, b->mask);
+    if (c) return c;
+    return (a->token > b->token) - (a->token < b->token);
+}
+
+/*
+ * Send-side plan.  Tokens with an empty destination set are dropped; the
+ * others are ordered by (bitmap as an unsigned 256-bit integer, token index),
+ * both ascending.  A multicast group is a maximal run of equal bitmaps in
+ * that order: one descriptor per group, in that order.  Accounting follows
+ * Section 1: multicast injects each packed row once, unicast once per
+ * destination rank.
+ */
+int ref_plan(const int32_t *topk, int32_t T, int32_t K,
+             const int32_t *expert_to_rank, int32_t E, int32_t R, int64_t row_bytes,
+             uint64_t *mask /* [T][4] out */, int32_t *perm /* [T] out, first N used */,
+             ref_group_desc *desc /* [T] out, first G used */, ref_send_stats *stats)
+{
+    int rc = ref_masks(topk, T, K, expert_to_rank, E, R, mask);
+    if (rc != REF_OK) return rc;
+
+    sort_item *items = (sort_item *)malloc(sizeof(sort_item) * (size_t)(T > 0 ? T : 1));
+    if (!items) return REF_ERR_CAPACITY;
+    int32_t N = 0;
+    for (int32_t t = 0; t < T; ++t) {
+        const uint64_t *m = mask + (size_t)t * REF_MASK_WORDS;
+        if (m[0] | m[1] | m[2] | m[3]) { items[N].mask = m; items[N].token = t; ++N; }
+    }
+    qsort(items, (size_t)N, sizeof(sort_item), sort_item_cmp);   /* keys are unique: (mask, token) */
+
+    memset(stats, 0, sizeof(*stats));
+    int32_t G = 0;
+    uint64_t dest_total = 0;
+    for (int32_t i = 0; i < N; ++i) {
+        perm[i] = items[i].token;
+        if (i == 0 || mask_cmp(items[i].mask, items[i - 1].mask) != 0) {
+            ref_group_desc *d = &desc[G++];
+            memcpy(d->mask, items[i].mask, sizeof(d->mask));
+            d->row_offset = (uint32_t)i;
+            d->row_count = 0;
+            d->n_dest = (uint32_t)mask_popcount(items[i].mask);
+            d->reserved0 = 0;
+        }
+        desc[G - 1].row_count += 1;
+        for (int r = 0; r < REF_MAX_RANKS; ++r)
+            if (mask_bit(items[i].mask, r)) { stats->rows_per_dest[r] += 1; dest_total += 1; }
+    }
+    stats->n_rows = (uint32_t)N;
+    stats->n_groups = (uint32_t)G;
+    stats->multicast_bytes = (uint64_t)N * (uint64_t)row_bytes;
+    stats->unicast_bytes = dest_total * (uint64_t)row_bytes;
+    free(items);
+    return REF_OK;
+}
+
+/*
+ * Accounting written straight from the statement of the problem, without
+ * bitmaps: for every token collect the distinct ranks of its experts.
+ */
+int ref_accounting_plain(const int32_t *topk, int32_t T, int32_t K,
+                         const int32_t *expert_to_rank, int32_t E, int32_t R, int64_t row_bytes,
+                         uint64_t *multicast_bytes, uint64_t *unicast_bytes,
+                         uint32_t *rows_per_dest /* [256] */)
+{
+    if (R < 1 || R > REF_MAX_RANKS || K < 1) return REF_ERR_ARG;
+    int32_t *seen = (int32_t *)malloc(sizeof(int32_t) * (size_t)K);
+    if (!seen) return REF_ERR_CAPACITY;
+    *multicast_bytes = 0; *unicast_bytes = 0;
+    memset(rows_per_dest, 0, sizeof(uint32_t) * REF_MAX_RANKS);
+    for (int32_t t = 0; t < T; ++t) {
+        int n = 0;
+        for (int32_t j = 0; j < K; ++j) {
+            int32_t e = topk[(size_t)t * K + j];
+            if (e == -1) continue;
+            if (e < 0 || e >= E) { free(seen); return REF_ERR_EXPERT; }
+            int32_t r = expert_to_rank[e], dup = 0;
+            for (int i = 0; i < n; ++i) dup |= (seen[i] == r);
+            if (!dup) seen[n++] = r;
+        }
+        if (n > 0) *multicast_bytes += (uint64_t)row_bytes;
+        *unicast_bytes += (uint64_t)n * (uint64_t)row_bytes;
+        for (int i = 0; i < n; ++i) rows_per_dest[seen[i]] += 1;
+    }
+    free(seen);
+    return REF_OK;
+}
+
+/*
+ * Pack: each kept token's payload is written once, in plan order (Section 1:
+ * only one copy of the same data is sent).  A packed row is the token's
+ * x bytes followed by its scale bytes (fp8: H e4m3 codes then H/128 fp32
+ * scales; bf16: 2H bytes and no scales).  The metadata a receiver needs
+ * travels with the row (Section 4.3.4, statelessness): the source token
+ * index and the token's top-k ids, copied unchanged.
+ */
+int ref_pack(const uint8_t *x, int64_t x_row_bytes, const uint8_t *scales, int64_t s_row_bytes,
+             const int32_t *topk, int32_t K, const int32_t *perm, int32_t N,
+             uint8_t *packed /* [N][x_row_bytes + s_row_bytes] */,
+             int32_t *row_src_token /* [N] */, int32_t *row_topk /* [N][K] */)
+{
+    if (x_row_bytes < 0 || s_row_bytes < 0 || (s_row_bytes > 0 && !scales)) return REF_ERR_ARG;
+    const int64_t rb = x_row_bytes + s_row_bytes;
+    for (int32_t i = 0; i < N; ++i) {
+        const int32_t t = perm[i];
+        uint8_t *dst = packed + (size_t)i * (size_t)rb;
+        memcpy(dst, x + (size_t)t * (size_t)x_row_bytes, (size_t)x_row_bytes);
+        if (s_row_bytes > 0)
+            memcpy(dst + x_row_bytes, scales + (size_t)t * (size_t)s_row_bytes, (size_t)s_row_bytes);
+        row_src_token[i] = t;
+        for (int32_t j = 0; j < K; ++j) row_topk[(size_t)i * K + j] = topk[(size_t)t * K + j];
+    }
+    return REF_OK;
+}
+
+/*
+ * Simulated network: what rank `dst_rank` receives from one sender
+ * (Section 4.1 workflow step 4: a payload is delivered only to nodes named
+ * in its bitmap).  Groups whose bitmap has bit dst_rank are kept, in order,
+ * their rows concatenated and row_offset rebased; bitmaps are left as sent.
+ */
+int ref_deliver(const ref_group_desc *desc, int32_t G, const uint8_t *rows, int64_t row_bytes,
+                const int32_t *row_src_token, const int32_t *row_topk, int32_t K, int32_t dst_rank,
+                ref_group_desc *desc_out, uint8_t *rows_out, int32_t *src_token_out, int32_t *topk_out,
+                int32_t *G_out, int32_t *N_out)
+{
+    if (dst_rank < 0 || dst_rank >= REF_MAX_RANKS) return REF_ERR_ARG;
+    int32_t g2 = 0, n2 = 0;
+    for (int32_t g = 0; g < G; ++g) {
+        if (!mask_bit(desc[g].mask, dst_rank)) continue;
+        desc_out[g2] = desc[g];
+        desc_out[g2].row_offset = (uint32_t)n2;
+        for (uint32_t i = 0; i < desc[g].row_count; ++i) {
+            const size_t s = (size_t)desc[g].row_offset + i;
+            memcpy(rows_out + (size_t)n2 * (size_t)row_bytes, rows + s * (size_t)row_bytes, (size_t)row_bytes);
+            src_token_out[n2] = row_src_token[s];
+            for (int32_t j = 0; j < K; ++j) topk_out[(size_t)n2 * K + j] = row_topk[s * K + j];
+            ++n2;
+        }
+        ++g2;
+    }
+    *G_out = g2; *N_out = n2;
+    return REF_OK;
+}
+
+/* slot of expert e among the experts hosted by `rank`, in ascending id order; -1 if elsewhere */
+static int32_t local_slot_of(const int32_t *expert_to_rank, int32_t e, int32_t rank)
+{
+    if (expert_to_rank[e] != rank) return -1;
+    int32_t s = 0;
+    for (int32_t f = 0; f < e; ++f) s += (expert_to_rank[f] == rank);
+    return s;
+}
+
+static int32_t local_count(const int32_t *expert_to_rank, int32_t E, int32_t rank)
+{
+    int32_t L = 0;
+    for (int32_t e = 0; e < E; ++e) L += (expert_to_rank[e] == rank);
+    return L;
+}
+
+/* does this top-k list name the local expert with slot `le`? (set semantics) */
+static int row_hits(const int32_t *topk_row, int32_t K, const int32_t *expert_to_rank, int32_t E,
+                    int32_t rank, int32_t le, int *bad)
+{
+    int hit = 0;
+    for (int32_t j = 0; j < K; ++j) {
+        int32_t e = topk_row[j];
+        if (e == -1) continue;
+        if (e < 0 || e >= E) { *bad = 1; continue; }
+        if (local_slot_of(expert_to_rank, e, rank) == le) hit = 1;
+    }
+    return hit;
+}
+
+/*
+ * Tier 2 receive side (Section 4.1 steps 3-4; Section 5.1, the receive
+ * module's reception, reassembly and delivery).  For every peer in rank
+ * order, rows of groups whose bitmap names this rank are delivered to each
+ * local expert in the row's top-k list.  Output is expert-major; inside an
+ * expert rows are ordered by (source peer, source token index) ascending,
+ * whatever order they were packed in.  The output row is split back into
+ * its x part and its scale part.
+ */
+int ref_unpack(const ref_recv_peer *peers, int32_t P, int32_t K,
+               const int32_t *expert_to_rank, int32_t E, int32_t my_rank,
+               int64_t x_row_bytes, int64_t s_row_bytes, int64_t out_capacity_rows,
+               uint8_t *out_rows /* [cap][x_row_bytes] */, uint8_t *out_scales /* [cap][s_row_bytes] or NULL */,
+               int32_t *out_src_peer, int32_t *out_src_token,
+               int64_t *expert_offsets /* [L+1] */, int64_t *n_recv_rows /* rows addressed to this rank */)
+{
+    if (my_rank < 0 || my_rank >= REF_MAX_RANKS || P < 0) return REF_ERR_ARG;
+    const int32_t L = local_count(expert_to_rank, E, my_rank);
+    const int64_t rb = x_row_bytes + s_row_bytes;
+    int rc = REF_OK, bad = 0;
+
+    /* which rows are addressed to this rank, per peer */
+    uint8_t **addr = (uint8_t **)calloc((size_t)(P > 0 ? P : 1), sizeof(uint8_t *));
+    int64_t *cnt = (int64_t *)calloc((size_t)(L > 0 ? L : 1) * (size_t)(P > 0 ? P : 1), sizeof(int64_t));
+    if (!addr || !cnt) { free(addr); free(cnt); return REF_ERR_CAPACITY; }
+    int64_t M = 0;
+    for (int32_t p = 0; p < P; ++p) {
+        addr[p] = (uint8_t *)calloc((size_t)peers[p].n_rows + 1, 1);
+        for (uint32_t g = 0; g < peers[p].n_desc; ++g) {
+            const ref_group_desc *d = &peers[p].desc[g];
+            if ((uint64_t)d->row_offset + d->row_count > peers[p].n_rows) { rc = REF_ERR_INPUT; goto done; }
+            if (!mask_bit(d->mask, my_rank)) continue;
+            for (uint32_t i = 0; i < d->row_count; ++i) addr[p][d->row_offset + i] = 1;
+        }
+        for (uint32_t i = 0; i < peers[p].n_rows; ++i) {
+            if (!addr[p][i]) continue;
+            ++M;
+            int any = 0;
+            for (int32_t le = 0; le < L; ++le)
+                if (row_hits(peers[p].row_topk + (size_t)i * K, K, expert_to_rank, E, my_rank, le, &bad)) {
+                    cnt[(size_t)le * P + p] += 1; any = 1;
+                }
+            if (!any) { rc = REF_ERR_INPUT; goto done; }   /* bitmap names us but no local expert does */
+        }
+    }
+    if (bad) { rc = REF_ERR_EXPERT; goto done; }
+    *n_recv_rows = M;
+
+    /* expert-major, then peer-major bases */
+    {
+        int64_t run = 0;
+        for (int32_t le = 0; le < L; ++le) {
+            expert_offsets[le] = run;
+            for (int32_t p = 0; p < P; ++p) run += cnt[(size_t)le * P + p];
+        }
+        expert_offsets[L] = run;
+        if (run > out_capacity_rows) { rc = REF_ERR_CAPACITY; goto done; }
+    }
+
+    for (int32_t le = 0; le < L; ++le) {
+        int64_t base = expert_offsets[le];
+        for (int32_t p = 0; p < P; ++p) {
+            const ref_recv_peer *pr = &peers[p];
+            for (uint32_t i = 0; i < pr->n_rows; ++i) {
+                if (!addr[p][i]) continue;
+                if (!row_hits(pr->row_topk + (size_t)i * K, K, expert_to_rank, E, my_rank, le, &bad)) continue;
+                /* rank of this row's source token among the peer's rows for this expert */
+                int64_t before = 0;
+                for (uint32_t i2 = 0; i2 < pr->n_rows; ++i2) {
+                    if (!addr[p][i2] || i2 == i) continue;
+                    if (!row_hits(pr->row_topk + (size_t)i2 * K, K, expert_to_rank, E, my_rank, le, &bad)) continue;
+                    if (pr->row_src_token[i2] == pr->row_src_token[i]) { rc = REF_ERR_INPUT; goto done; }
+                    before += (pr->row_src_token[i2] < pr->row_src_token[i]);
+                }
+                const int64_t pos = base + before;
+                const uint8_t *src = pr->rows + (size_t)i * (size_t)rb;
+                memcpy(out_rows + (size_t)pos * (size_t)x_row_bytes, src, (size_t)x_row_bytes);
+                if (s_row_bytes > 0)
+                    memcpy(out_scales + (size_t)pos * (size_t)s_row_bytes, src + x_row_bytes, (size_t)s_row_bytes);
+                out_src_peer[pos] = p;
+                out_src_token[pos] = pr->row_src_token[i];
+            }
+            base += cnt[(size_t)le * P + p];
+        }
+    }
+done:
+    for (int32_t p = 0; p < P; ++p) free(addr[p]);
+    free(addr); free(cnt);
+    return rc;
+}
+
+/*
+ * Tier 1: the plain definition of what a dispatch delivers to this rank
+ * (Section 4.3.1 applied to every token; Section 2.1, dispatch-style
+ * AlltoAll).  No bitmaps, groups or packed buffers: for each local expert in
+ * ascending id order, for each peer in rank order, for each of its tokens in
+ * index order, the token is delivered iff the expert is in its top-k set.
+ */
+int ref_dispatch_plain(const ref_peer_tokens *peers, int32_t P, int32_t K,
+                       const int32_t *expert_to_rank, int32_t E, int32_t my_rank,
+                       int64_t x_row_bytes, int64_t s_row_bytes, int64_t out_capacity_rows,
+                       uint8_t *out_rows, uint8_t *out_scales,
+                       int32_t *out_src_peer, int32_t *out_src_token, int64_t *expert_offsets)
+{
+    int64_t pos = 0;
+    int32_t le = 0;
+    for (int32_t e = 0; e < E; ++e) {
+        if (expert_to_rank[e] != my_rank) continue;
+        expert_offsets[le++] = pos;
+        for (int32_t p = 0; p < P; ++p)
+            for (int32_t t = 0; t < peers[p].n_tokens; ++t) {
+                int in_set = 0;
+                for (int32_t j = 0; j < K; ++j) in_set |= (peers[p].topk[(size_t)t * K + j] == e);
+                if (!in_set) continue;
+                if (pos >= out_capacity_rows) return REF_ERR_CAPACITY;
+                memcpy(out_rows + (size_t)pos * (size_t)x_row_bytes,
+                       peers[p].x + (size_t)t * (size_t)x_row_bytes, (size_t)x_row_bytes);
+                if (s_row_bytes > 0)
+                    memcpy(out_scales + (size_t)pos * (size_t)s_row_bytes,
+                           peers[p].scales + (size_t)t * (size_t)s_row_bytes, (size_t)s_row_bytes);
+                out_src_peer[pos] = p;
+                out_src_token[pos] = t;
+                ++pos;
+            }
+    }
+    expert_offsets[le] = pos;
+    return REF_OK;
+}
+
+/*
+ * AllGather as a MultiWrite with a static destination set (Section 2.3.3,
+ * Section 5.2): the shard is one packed row, one group, bitmap = all R ranks
+ * (this rank included).
+ */
+int ref_plan_allgather(int32_t R, int64_t shard_bytes, ref_group_desc *desc, ref_send_stats *stats)
+{
+    if (R < 1 || R > REF_MAX_RANKS || shard_bytes < 0) return REF_ERR_ARG;
+    memset(desc, 0, sizeof(*desc));
+    memset(stats, 0, sizeof(*stats));
+    for (int32_t r = 0; r < R; ++r) {
+        desc->mask[r >> 6] |= (uint64_t)1 << (r & 63);
+        stats->rows_per_dest[r] = 1;
+    }
+    desc->row_offset = 0; desc->row_count = 1; desc->n_dest = (uint32_t)R;
+    stats->n_rows = 1; stats->n_groups = 1;
+    stats->multicast_bytes = (uint64_t)shard_bytes;
+    stats->unicast_bytes = (uint64_t)shard_bytes * (uint64_t)R;
+    return REF_OK;
+}
+
+/* Section 5.2 step 1: the local fragment is loaded into the send buffer. */
+int ref_pack_allgather(const uint8_t *shard, int64_t shard_bytes, uint8_t *send_buf)
+{
+    memcpy(send_buf, shard, (size_t)shard_bytes);
+    return REF_OK;
+}
+
+/* Result of AllGather: the fragments of ranks 0..R-1 side by side in rank order. */
+int ref_unpack_allgather(const uint8_t *const *peer_shards, int32_t R, int64_t shard_bytes, uint8_t *out)
+{
+    for (int32_t p = 0; p < R; ++p)
+        memcpy(out + (size_t)p * (size_t)shard_bytes, peer_shards[p], (size_t)shard_bytes);
+    return REF_OK;
+}
