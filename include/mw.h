@@ -1,0 +1,260 @@
+/*
+ * mw.h -- C ABI of the MI355X (gfx950) MultiWrite dispatch / AllGather hot path.
+ *
+ * One rank's local share of a MultiWrite many-to-many operation
+ * (paper Section 4.3.1: MultiWrite(S, M, B_S) delivers the source buffer to
+ * every destination in M, injecting it once).  The send side turns each
+ * token's top-k expert ids into a destination-rank bitmap (Section 4.1,
+ * "Encoding scheme of metadata"), groups tokens by bitmap into multicast
+ * groups, packs every payload row once per group and writes a group
+ * descriptor table (the batched form of Section 4.3.2's "array of remote
+ * buffers").  The receive side parses the carried metadata and delivers each
+ * row to the local experts it names (Section 4.1 workflow steps 3-4;
+ * Section 5.1, receive module).  The network and the other ranks are not
+ * part of this library.
+ *
+ * Conventions for every entry point
+ *   - extern "C"; returns an int32 status: MW_OK (0) or a negative MW_ERR_*.
+ *   - pointers named *_dev are DEVICE pointers (hipMalloc'd memory of the
+ *     current device); everything else is a HOST pointer.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Calls only enqueue work; they never synchronise the stream unless the
+ *     entry point says so, never allocate or free device memory, and never
+ *     take ownership of a caller buffer.  Buffers must stay valid until the
+ *     enqueued work has completed.
+ *   - Errors the host can see (null pointers, sizes out of range, misaligned
+ *     rows) are returned synchronously and nothing is enqueued.  Errors only
+ *     visible on the device (bad expert id, capacity overflow, inconsistent
+ *     received metadata) set MW_FLAG_* bits in the statistics block, the
+ *     offending item is left out, and all kernels still terminate normally.
+ *   - A context may be used from one stream at a time: calls on the same
+ *     context share its workspace and race if they overlap.
+ */
+#ifndef MW_H_
+#define MW_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MW_API __attribute__((visibility("default")))
+
+#define MW_MASK_WORDS 4          /* 256-bit destination bitmap */
+#define MW_MAX_RANKS  256        /* Section 6.4: bitmaps wider than 64 bit; 256 ranks here */
+#define MW_MAX_TOPK   64
+
+/* status codes */
+#define MW_OK                 0
+#define MW_ERR_INVALID_ARG   -1  /* null pointer, negative size, value out of range */
+#define MW_ERR_CAPACITY      -2  /* n_tokens / sizes beyond what the context was created for */
+#define MW_ERR_UNSUPPORTED   -3  /* more than 256 ranks, row not a multiple of 16 bytes, ... */
+#define MW_ERR_HIP           -4  /* a HIP runtime call failed */
+#define MW_ERR_WORKSPACE     -5  /* workspace missing, misaligned or too small */
+
+/* row formats */
+#define MW_ROW_BF16             0  /* row = hidden bf16 values, 2*hidden bytes */
+#define MW_ROW_FP8_E4M3_BLOCK128 1 /* row = hidden e4m3 codes then hidden/128 fp32 scales */
+#define MW_ROW_BYTES            2  /* row = row_bytes opaque bytes (AllGather shards, tests) */
+
+/* device-side error flags (mw_send_stats.error_flags / mw_recv_stats.error_flags) */
+#define MW_FLAG_BAD_EXPERT       0x01u  /* expert id outside {-1} U [0, n_experts): entry ignored */
+#define MW_FLAG_OUT_CAPACITY     0x02u  /* more output rows than out_capacity_rows: surplus rows dropped */
+#define MW_FLAG_NO_LOCAL_EXPERT  0x04u  /* row's group names this rank but none of its experts is local */
+#define MW_FLAG_BAD_SRC_TOKEN    0x08u  /* row_src_token outside [0, max_tokens): row dropped */
+#define MW_FLAG_BAD_DESC         0x10u  /* descriptor row range outside the peer's rows: group dropped */
+#define MW_FLAG_RECV_CAPACITY    0x20u  /* peers hold more rows than max_recv_rows: surplus peers' rows dropped */
+#define MW_FLAG_DUP_SRC_TOKEN    0x40u  /* two rows of one peer carry the same source token for one expert */
+
+/*
+ * Destination bitmap, Section 4.1: ranks are numbered from zero and bit r says
+ * whether rank r is a target.  Fixed width of 4 x 64 bit (Section 6.4 allows
+ * wider fields for more than 64 ranks): rank r <-> mask[r / 64] bit (r % 64);
+ * bits at and above n_ranks are zero.
+ */
+typedef struct mw_group_desc {
+    uint64_t mask[MW_MASK_WORDS];
+    uint32_t row_offset;   /* index of the group's first packed row */
+    uint32_t row_count;    /* rows in the group (>= 1) */
+    uint32_t n_dest;       /* popcount(mask) */
+    uint32_t reserved0;    /* written as 0 */
+} mw_group_desc;           /* 48 bytes, little endian, no padding */
+
+/* Send-side statistics, written by mw_plan / mw_plan_allgather (device resident). */
+typedef struct mw_send_stats {
+    uint32_t n_rows;            /* N: tokens with a non-empty destination set = packed rows */
+    uint32_t n_groups;          /* G: distinct destination sets */
+    uint64_t multicast_bytes;   /* N * row_bytes: every row injected once (Section 1) */
+    uint64_t unicast_bytes;     /* row_bytes * sum over tokens of |destination set| */
+    uint32_t rows_per_dest[MW_MAX_RANKS]; /* rows whose set names rank r (this rank included) */
+    uint32_t error_flags;       /* MW_FLAG_* */
+    uint32_t reserved0;
+} mw_send_stats;                /* 1056 bytes */
+
+/* Receive-side statistics, written by mw_unpack (device resident). */
+typedef struct mw_recv_stats {
+    uint64_t n_recv_rows;       /* M: received rows whose group bitmap names this rank */
+    uint64_t n_out_rows;        /* Q: (row, local expert) pairs = rows of the expert-major output */
+    uint32_t error_flags;       /* MW_FLAG_* */
+    uint32_t reserved0;
+} mw_recv_stats;                /* 24 bytes */
+
+/*
+ * What one peer wrote into this rank's pre-allocated receive region
+ * (Section 6.4, "Memory usage": one region per peer).  The array of these
+ * records lives in device memory; so does everything they point to.
+ * Rows are laid out as mw_pack writes them.  A sender's complete buffer is
+ * accepted as well: groups whose bitmap does not name this rank are skipped.
+ */
+typedef struct mw_recv_peer {
+    const mw_group_desc *desc;      /* [n_desc], row ranges ascending and inside [0, n_rows) */
+    uint32_t n_desc;
+    uint32_t n_rows;                /* <= max_tokens */
+    const void *rows;               /* [n_rows][row_bytes], 16-byte aligned */
+    const int32_t *row_src_token;   /* [n_rows] index of the row's token at the sender */
+    const int32_t *row_topk;        /* [n_rows][top_k] the token's expert ids as the gate emitted them */
+} mw_recv_peer;                     /* 40 bytes */
+
+/*
+ * Context configuration (Section 5.1, initialisation module: topology and
+ * node configuration; Section 4.1: the table that maps addresses -- here
+ * expert ids -- to ranks).  Immutable after mw_ctx_create.
+ */
+typedef struct mw_config {
+    int32_t n_ranks;        /* R, 1..256 */
+    int32_t n_experts;      /* E >= 0 (0: AllGather-only context) */
+    int32_t top_k;          /* K, 1..64 */
+    int32_t my_rank;        /* 0..R-1 */
+    int32_t hidden;         /* H elements per token (ignored for MW_ROW_BYTES) */
+    int32_t row_format;     /* MW_ROW_* */
+    int64_t row_bytes;      /* MW_ROW_BYTES: given.  Otherwise 0 or the derived value:
+                               bf16 2*H; fp8 H + 4*(H/128).  Must be a multiple of 16;
+                               fp8 additionally needs H % 512 == 0 so both parts are. */
+    int32_t max_tokens;     /* capacity for n_tokens and bound on any peer's token indices */
+    int32_t reserved0;
+    int64_t max_recv_rows;  /* capacity for the sum of the peers' n_rows in mw_unpack */
+    const int32_t *expert_to_rank; /* HOST, [E], values in [0, R); copied at create */
+} mw_config;
+
+typedef struct mw_ctx mw_ctx;
+
+/* Bytes of device workspace a context for `cfg` needs. */
+MW_API int32_t mw_workspace_bytes(const mw_config *cfg, int64_t *out_bytes);
+
+/*
+ * Create a context on the current device.  `workspace_dev` (256-byte aligned,
+ * at least mw_workspace_bytes) stays owned by the caller and must outlive the
+ * context.  Copies the rank table to the device and SYNCHRONISES the device
+ * once.  The library owns only the small host-side mw_ctx.
+ */
+MW_API int32_t mw_ctx_create(const mw_config *cfg, void *workspace_dev, int64_t workspace_bytes, mw_ctx **out);
+MW_API int32_t mw_ctx_destroy(mw_ctx *ctx);
+
+/* ---- send side (Section 5.1, send module: task decomposition) -------------------------- */
+
+/*
+ * mw_plan: destination bitmaps, multicast groups, descriptor table.
+ *   mask[t]  = OR over the token's valid expert ids e of bit expert_to_rank[e]
+ *              (Section 4.1); id -1 means "no expert"; duplicates count once.
+ *   perm     = tokens with a non-empty bitmap ordered by (bitmap as unsigned
+ *              256-bit integer with word 3 most significant, token index),
+ *              both ascending; perm[i] = token of packed row i.
+ *   desc[g]  = one record per maximal run of equal bitmaps, in that order.
+ *   stats    = counts and the multicast / unicast byte accounting.
+ * topk_ids_dev [n_tokens][top_k] int32 row-major; mask_dev [n_tokens][4];
+ * perm_dev and desc_dev have room for n_tokens entries (first N / G are
+ * written, the rest is left untouched).  0 <= n_tokens <= max_tokens.
+ */
+MW_API int32_t mw_plan(mw_ctx *ctx, const int32_t *topk_ids_dev, int32_t n_tokens,
+                uint64_t *mask_dev, int32_t *perm_dev, mw_group_desc *desc_dev,
+                mw_send_stats *stats_dev, void *stream);
+
+/*
+ * mw_pack: every kept token's payload written once, in plan order
+ * (Section 1: only one copy of the same data is sent; Section 5.2 step 1:
+ * load the data into the pre-allocated send buffer), together with the
+ * metadata a receiver needs (Section 4.3.4, statelessness):
+ *   packed[i]        = x[perm[i]]  (fp8: the H codes followed by the H/128 scales)
+ *   row_src_token[i] = perm[i]
+ *   row_topk[i][:]   = topk_ids[perm[i]][:]   unchanged
+ * for i < stats->n_rows (read on the device).  x_dev [n_tokens][H] bf16 or
+ * e4m3 bytes, or [n_tokens][row_bytes] for MW_ROW_BYTES; scales_dev
+ * [n_tokens][H/128] fp32 for fp8, else NULL.  Outputs have room for n_tokens
+ * rows.  All payload pointers 16-byte aligned.
+ */
+MW_API int32_t mw_pack(mw_ctx *ctx, const void *x_dev, const float *scales_dev,
+                const int32_t *topk_ids_dev, const int32_t *perm_dev,
+                const mw_send_stats *stats_dev, int32_t n_tokens,
+                void *packed_rows_dev, int32_t *row_src_token_dev, int32_t *row_topk_dev,
+                void *stream);
+
+/*
+ * AllGather as a MultiWrite with a static destination set (Section 2.3.3,
+ * Section 5.2): the shard is one row, one group, bitmap = ranks 0..R-1
+ * (this rank included).  Writes one descriptor and the statistics.
+ */
+MW_API int32_t mw_plan_allgather(mw_ctx *ctx, int64_t shard_bytes, mw_group_desc *desc_dev,
+                          mw_send_stats *stats_dev, void *stream);
+
+/* Section 5.2 step 1: load the local fragment into the send buffer (16-byte multiple). */
+MW_API int32_t mw_pack_allgather(mw_ctx *ctx, const void *shard_dev, int64_t shard_bytes,
+                          void *send_buf_dev, void *stream);
+
+/* ---- receive side (Section 5.1, receive module: reception, reassembly, delivery) ------- */
+
+/*
+ * mw_unpack: expand the peers' packed buffers into per-local-expert
+ * contiguous layouts.  Local experts are the ids e with expert_to_rank[e] ==
+ * my_rank, in ascending id order (slot le = 0..L-1).  A row is delivered to
+ * local expert le iff its group's bitmap names this rank and le's id is in
+ * its row_topk list (set semantics).  Output is expert-major; inside an
+ * expert rows are ordered by (source peer, source token index) ascending,
+ * independent of packing order:
+ *   out_rows[pos]      = the row's x part   ([out_capacity_rows][x bytes per row])
+ *   out_scales[pos]    = the row's scales   (fp8 only, else NULL)
+ *   out_src_peer[pos], out_src_token[pos]
+ *   expert_offsets[le] = first output row of expert le; expert_offsets[L] = Q
+ * peers_dev: device array of n_peers records, 1 <= n_peers <= n_ranks.
+ */
+MW_API int32_t mw_unpack(mw_ctx *ctx, const mw_recv_peer *peers_dev, int32_t n_peers,
+                  void *out_rows_dev, float *out_scales_dev, int64_t out_capacity_rows,
+                  int32_t *out_src_peer_dev, int32_t *out_src_token_dev,
+                  int64_t *expert_offsets_dev, mw_recv_stats *recv_stats_dev, void *stream);
+
+/*
+ * AllGather result (Section 5.2): out = shard of rank 0, rank 1, ... rank R-1
+ * side by side.  peer_shards_dev: device array of n_ranks device pointers.
+ */
+MW_API int32_t mw_unpack_allgather(mw_ctx *ctx, const void *const *peer_shards_dev, int64_t shard_bytes,
+                            void *out_dev, void *stream);
+
+/* ---- simulation and measurement helpers (not part of the dispatch path) ---------------- */
+
+/*
+ * Simulated network (Section 4.1 workflow step 4: a payload reaches only the
+ * nodes named in its bitmap): from a sender's mw_plan/mw_pack output keep the
+ * groups that name dst_rank, in order, rows concatenated, row_offset rebased,
+ * bitmaps unchanged.  counts_out_dev[0] = groups kept, [1] = rows kept.
+ * Outputs have room for n_tokens entries.
+ */
+MW_API int32_t mw_sim_deliver(mw_ctx *ctx, const mw_group_desc *desc_dev, const mw_send_stats *stats_dev,
+                       int32_t n_tokens, const void *packed_rows_dev,
+                       const int32_t *row_src_token_dev, const int32_t *row_topk_dev, int32_t dst_rank,
+                       mw_group_desc *desc_out_dev, void *rows_out_dev, int32_t *src_token_out_dev,
+                       int32_t *topk_out_dev, uint32_t *counts_out_dev, void *stream);
+
+/* Plain streaming device copy of n_bytes (multiple of 16): the copy ceiling the
+ * row movers are compared with, and the reference kernel for counter scaling. */
+MW_API int32_t mw_copy_bytes(void *dst_dev, const void *src_dev, int64_t n_bytes, void *stream);
+
+/* Copy a statistics block to the host.  SYNCHRONISES `stream`. */
+MW_API int32_t mw_get_send_stats(mw_ctx *ctx, const mw_send_stats *stats_dev, mw_send_stats *host_out, void *stream);
+MW_API int32_t mw_get_recv_stats(mw_ctx *ctx, const mw_recv_stats *stats_dev, mw_recv_stats *host_out, void *stream);
+
+MW_API const char *mw_status_string(int32_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MW_H_ */

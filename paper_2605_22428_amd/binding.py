@@ -1,0 +1,232 @@
+"""Thin Python binding of libmw.so (the C ABI declared in include/mw.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels of
+the shared library.  PyTorch is used for device memory and streams, nothing
+else.  There is no CPU fallback: if the library is missing, loading fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libmw.so")
+
+MW_OK = 0
+MW_ERR_INVALID_ARG, MW_ERR_CAPACITY, MW_ERR_UNSUPPORTED, MW_ERR_HIP, MW_ERR_WORKSPACE = -1, -2, -3, -4, -5
+MW_ROW_BF16, MW_ROW_FP8_E4M3_BLOCK128, MW_ROW_BYTES = 0, 1, 2
+MW_FLAG_BAD_EXPERT, MW_FLAG_OUT_CAPACITY, MW_FLAG_NO_LOCAL_EXPERT = 0x01, 0x02, 0x04
+MW_FLAG_BAD_SRC_TOKEN, MW_FLAG_BAD_DESC, MW_FLAG_RECV_CAPACITY, MW_FLAG_DUP_SRC_TOKEN = 0x08, 0x10, 0x20, 0x40
+
+EXPORTS = ["mw_workspace_bytes", "mw_ctx_create", "mw_ctx_destroy", "mw_plan", "mw_pack",
+           "mw_plan_allgather", "mw_pack_allgather", "mw_unpack", "mw_unpack_allgather",
+           "mw_sim_deliver", "mw_copy_bytes", "mw_get_send_stats", "mw_get_recv_stats",
+           "mw_status_string"]
+
+# numpy views of the ABI records (host copies)
+DESC_DTYPE = np.dtype([("mask", "<u8", (4,)), ("row_offset", "<u4"), ("row_count", "<u4"),
+                       ("n_dest", "<u4"), ("reserved0", "<u4")])
+SEND_STATS_DTYPE = np.dtype([("n_rows", "<u4"), ("n_groups", "<u4"), ("multicast_bytes", "<u8"),
+                             ("unicast_bytes", "<u8"), ("rows_per_dest", "<u4", (256,)),
+                             ("error_flags", "<u4"), ("reserved0", "<u4")])
+RECV_STATS_DTYPE = np.dtype([("n_recv_rows", "<u8"), ("n_out_rows", "<u8"), ("error_flags", "<u4"),
+                             ("reserved0", "<u4")])
+RECV_PEER_DTYPE = np.dtype([("desc", "<u8"), ("n_desc", "<u4"), ("n_rows", "<u4"), ("rows", "<u8"),
+                            ("row_src_token", "<u8"), ("row_topk", "<u8")])
+DESC_BYTES, SEND_STATS_BYTES, RECV_STATS_BYTES, RECV_PEER_BYTES = 48, 1056, 24, 40
+assert (DESC_DTYPE.itemsize, SEND_STATS_DTYPE.itemsize, RECV_STATS_DTYPE.itemsize,
+        RECV_PEER_DTYPE.itemsize) == (48, 1056, 24, 40)
+
+
+class MwConfig(C.Structure):
+    _fields_ = [("n_ranks", C.c_int32), ("n_experts", C.c_int32), ("top_k", C.c_int32),
+                ("my_rank", C.c_int32), ("hidden", C.c_int32), ("row_format", C.c_int32),
+                ("row_bytes", C.c_int64), ("max_tokens", C.c_int32), ("reserved0", C.c_int32),
+                ("max_recv_rows", C.c_int64), ("expert_to_rank", C.c_void_p)]
+
+
+class MwError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        super().__init__("%s: %s (%d)" % (where, status_string(status), status))
+        self.status = status
+
+
+_lib = None
+
+
+def load():
+    """Load libmw.so (built by paper_2605_22428_amd.build); raises if it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("HIP library %s is not built (run __graft_entry__.build())" % LIB_PATH)
+        lib = C.CDLL(LIB_PATH)
+        for name in EXPORTS:
+            getattr(lib, name).restype = C.c_int32
+        lib.mw_status_string.restype = C.c_char_p
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load().mw_status_string(C.c_int32(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != MW_OK:
+        raise MwError(status, where)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> C.c_void_p:
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _stream() -> C.c_void_p:
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def mw_copy_bytes(dst: torch.Tensor, src: torch.Tensor, n_bytes: int):
+    _check(load().mw_copy_bytes(_ptr(dst), _ptr(src), C.c_int64(n_bytes), _stream()), "mw_copy_bytes")
+
+
+class Context:
+    """mw_ctx plus the device workspace it uses (a torch tensor, caller-owned in ABI terms)."""
+
+    def __init__(self, n_ranks: int, n_experts: int, top_k: int, my_rank: int, hidden: int,
+                 row_format: int, max_tokens: int, max_recv_rows: int,
+                 expert_to_rank: Optional[np.ndarray], row_bytes: int = 0, device: str = "cuda:0"):
+        lib = load()
+        self.device = torch.device(device)
+        e2r = None if expert_to_rank is None else np.ascontiguousarray(expert_to_rank, dtype=np.int32)
+        self._e2r = e2r
+        cfg = MwConfig(n_ranks, n_experts, top_k, my_rank, hidden, row_format, row_bytes, max_tokens, 0,
+                       max_recv_rows, 0 if e2r is None else e2r.ctypes.data)
+        need = C.c_int64(0)
+        _check(lib.mw_workspace_bytes(C.byref(cfg), C.byref(need)), "mw_workspace_bytes")
+        self.workspace = torch.zeros(need.value + 256, dtype=torch.uint8, device=self.device)
+        off = (-self.workspace.data_ptr()) % 256
+        handle = C.c_void_p(0)
+        with torch.cuda.device(self.device):
+            _check(lib.mw_ctx_create(C.byref(cfg), C.c_void_p(self.workspace.data_ptr() + off),
+                                     C.c_int64(need.value), C.byref(handle)), "mw_ctx_create")
+        self._h = handle
+        self.n_ranks, self.n_experts, self.top_k, self.my_rank = n_ranks, n_experts, top_k, my_rank
+        self.hidden, self.row_format, self.max_tokens, self.max_recv_rows = hidden, row_format, max_tokens, max_recv_rows
+        if row_format == MW_ROW_BF16:
+            self.x_row_bytes, self.s_row_bytes = 2 * hidden, 0
+        elif row_format == MW_ROW_FP8_E4M3_BLOCK128:
+            self.x_row_bytes, self.s_row_bytes = hidden, 4 * (hidden // 128)
+        else:
+            self.x_row_bytes, self.s_row_bytes = row_bytes, 0
+        self.row_bytes = self.x_row_bytes + self.s_row_bytes
+        self.n_local = 0 if e2r is None else int((e2r == my_rank).sum())
+
+    def close(self):
+        if self._h is not None and self._h.value:
+            load().mw_ctx_destroy(self._h)
+        self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- send side -----------------------------------------------------------------------
+    def mw_plan(self, topk_ids: torch.Tensor, mask: torch.Tensor, perm: torch.Tensor,
+                desc: torch.Tensor, stats: torch.Tensor):
+        n_tokens = topk_ids.shape[0]
+        _check(load().mw_plan(self._h, _ptr(topk_ids), C.c_int32(n_tokens), _ptr(mask), _ptr(perm),
+                              _ptr(desc), _ptr(stats), _stream()), "mw_plan")
+
+    def mw_pack(self, x: torch.Tensor, scales: Optional[torch.Tensor], topk_ids: torch.Tensor,
+                perm: torch.Tensor, stats: torch.Tensor, packed: torch.Tensor,
+                row_src_token: torch.Tensor, row_topk: torch.Tensor):
+        n_tokens = topk_ids.shape[0]
+        _check(load().mw_pack(self._h, _ptr(x), _ptr(scales), _ptr(topk_ids), _ptr(perm), _ptr(stats),
+                              C.c_int32(n_tokens), _ptr(packed), _ptr(row_src_token), _ptr(row_topk),
+                              _stream()), "mw_pack")
+
+    def mw_plan_allgather(self, shard_bytes: int, desc: torch.Tensor, stats: torch.Tensor):
+        _check(load().mw_plan_allgather(self._h, C.c_int64(shard_bytes), _ptr(desc), _ptr(stats),
+                                        _stream()), "mw_plan_allgather")
+
+    def mw_pack_allgather(self, shard: torch.Tensor, shard_bytes: int, send_buf: torch.Tensor):
+        _check(load().mw_pack_allgather(self._h, _ptr(shard), C.c_int64(shard_bytes), _ptr(send_buf),
+                                        _stream()), "mw_pack_allgather")
+
+    # ---- receive side --------------------------------------------------------------------
+    def mw_unpack(self, peers: torch.Tensor, n_peers: int, out_rows: torch.Tensor,
+                  out_scales: Optional[torch.Tensor], out_capacity_rows: int, out_src_peer: torch.Tensor,
+                  out_src_token: torch.Tensor, expert_offsets: torch.Tensor, recv_stats: torch.Tensor):
+        _check(load().mw_unpack(self._h, _ptr(peers), C.c_int32(n_peers), _ptr(out_rows), _ptr(out_scales),
+                                C.c_int64(out_capacity_rows), _ptr(out_src_peer), _ptr(out_src_token),
+                                _ptr(expert_offsets), _ptr(recv_stats), _stream()), "mw_unpack")
+
+    def mw_unpack_allgather(self, peer_shards: torch.Tensor, shard_bytes: int, out: torch.Tensor):
+        _check(load().mw_unpack_allgather(self._h, _ptr(peer_shards), C.c_int64(shard_bytes), _ptr(out),
+                                          _stream()), "mw_unpack_allgather")
+
+    # ---- simulation / statistics ---------------------------------------------------------
+    def mw_sim_deliver(self, desc, stats, n_tokens, packed, row_src_token, row_topk, dst_rank,
+                       desc_out, rows_out, src_token_out, topk_out, counts_out):
+        _check(load().mw_sim_deliver(self._h, _ptr(desc), _ptr(stats), C.c_int32(n_tokens), _ptr(packed),
+                                     _ptr(row_src_token), _ptr(row_topk), C.c_int32(dst_rank),
+                                     _ptr(desc_out), _ptr(rows_out), _ptr(src_token_out), _ptr(topk_out),
+                                     _ptr(counts_out), _stream()), "mw_sim_deliver")
+
+    def mw_get_send_stats(self, stats: torch.Tensor) -> np.ndarray:
+        host = np.zeros(1, dtype=SEND_STATS_DTYPE)
+        _check(load().mw_get_send_stats(self._h, _ptr(stats), C.c_void_p(host.ctypes.data), _stream()),
+               "mw_get_send_stats")
+        return host[0]
+
+    def mw_get_recv_stats(self, stats: torch.Tensor) -> np.ndarray:
+        host = np.zeros(1, dtype=RECV_STATS_DTYPE)
+        _check(load().mw_get_recv_stats(self._h, _ptr(stats), C.c_void_p(host.ctypes.data), _stream()),
+               "mw_get_recv_stats")
+        return host[0]
+
+
+# ---- buffer helpers (allocation only) ----------------------------------------------------
+def peers_table(records: Sequence[dict], device) -> torch.Tensor:
+    """Device array of mw_recv_peer records from dicts of device tensors
+    {desc, n_desc, n_rows, rows, row_src_token, row_topk}."""
+    host = np.zeros(max(len(records), 1), dtype=RECV_PEER_DTYPE)
+    for i, r in enumerate(records):
+        host[i] = (r["desc"].data_ptr(), r["n_desc"], r["n_rows"], r["rows"].data_ptr(),
+                   r["row_src_token"].data_ptr(), r["row_topk"].data_ptr())
+    return torch.from_numpy(host.view(np.uint8).reshape(-1)).to(device)
+
+
+class SendBuffers:
+    """Outputs of mw_plan + mw_pack for up to n_tokens tokens."""
+
+    def __init__(self, ctx: Context, n_tokens: int):
+        d, n = ctx.device, max(n_tokens, 1)
+        self.mask = torch.zeros((n, 4), dtype=torch.int64, device=d)
+        self.perm = torch.full((n,), -1, dtype=torch.int32, device=d)
+        self.desc = torch.zeros((n, DESC_BYTES), dtype=torch.uint8, device=d)
+        self.stats = torch.zeros(SEND_STATS_BYTES, dtype=torch.uint8, device=d)
+        self.packed = torch.zeros((n, ctx.row_bytes), dtype=torch.uint8, device=d)
+        self.row_src_token = torch.full((n,), -1, dtype=torch.int32, device=d)
+        self.row_topk = torch.zeros((n, ctx.top_k), dtype=torch.int32, device=d)
+
+
+class RecvBuffers:
+    """Outputs of mw_unpack for up to `capacity` output rows."""
+
+    def __init__(self, ctx: Context, capacity: int):
+        d, n = ctx.device, max(capacity, 1)
+        self.capacity = capacity
+        self.out_rows = torch.zeros((n, ctx.x_row_bytes), dtype=torch.uint8, device=d)
+        self.out_scales = (torch.zeros((n, ctx.s_row_bytes), dtype=torch.uint8, device=d)
+                           if ctx.s_row_bytes else None)
+        self.out_src_peer = torch.full((n,), -1, dtype=torch.int32, device=d)
+        self.out_src_token = torch.full((n,), -1, dtype=torch.int32, device=d)
+        self.expert_offsets = torch.zeros(ctx.n_local + 1, dtype=torch.int64, device=d)
+        self.stats = torch.zeros(RECV_STATS_BYTES, dtype=torch.uint8, device=d)

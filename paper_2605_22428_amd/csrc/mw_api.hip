@@ -1,0 +1,287 @@
+// C ABI of the MultiWrite library: context, argument validation, dispatch to the
+// kernel launchers.  The contract of every entry point is in include/mw.h.
+#include <new>
+#include <vector>
+
+#include "mw_internal.h"
+
+namespace {
+
+struct ws_layout {
+    int64_t e2r, local_slot, pos, flags, cnt, row_base, addr_cnt, hits, row_map, total;
+};
+
+// Derived row geometry; returns a status.
+int32_t row_geometry(const mw_config &c, int64_t *x_bytes, int64_t *s_bytes)
+{
+    switch (c.row_format) {
+    case MW_ROW_BF16:
+        if (c.hidden < 1) return MW_ERR_INVALID_ARG;
+        *x_bytes = 2LL * c.hidden; *s_bytes = 0;
+        break;
+    case MW_ROW_FP8_E4M3_BLOCK128:
+        if (c.hidden < 1) return MW_ERR_INVALID_ARG;
+        if (c.hidden % 512 != 0) return MW_ERR_UNSUPPORTED;   // codes and scales both 16-byte multiples
+        *x_bytes = c.hidden; *s_bytes = 4LL * (c.hidden / 128);
+        break;
+    case MW_ROW_BYTES:
+        if (c.row_bytes < 16) return MW_ERR_INVALID_ARG;
+        *x_bytes = c.row_bytes; *s_bytes = 0;
+        break;
+    default:
+        return MW_ERR_INVALID_ARG;
+    }
+    const int64_t rb = *x_bytes + *s_bytes;
+    if (rb % 16 != 0 || *x_bytes % 16 != 0) return MW_ERR_UNSUPPORTED;
+    if (rb / 16 > 0x7fffffffLL) return MW_ERR_UNSUPPORTED;
+    if (c.row_format != MW_ROW_BYTES && c.row_bytes != 0 && c.row_bytes != rb) return MW_ERR_INVALID_ARG;
+    return MW_OK;
+}
+
+int32_t validate(const mw_config *c, int32_t *n_local)
+{
+    if (!c) return MW_ERR_INVALID_ARG;
+    if (c->n_ranks < 1 || c->n_experts < 0 || c->top_k < 1 || c->max_tokens < 0 || c->max_recv_rows < 0)
+        return MW_ERR_INVALID_ARG;
+    if (c->n_ranks > MW_MAX_RANKS || c->top_k > MW_MAX_TOPK) return MW_ERR_UNSUPPORTED;
+    if (c->max_tokens > 65536 || c->n_experts > 65536) return MW_ERR_UNSUPPORTED;
+    if (c->my_rank < 0 || c->my_rank >= c->n_ranks) return MW_ERR_INVALID_ARG;
+    if (c->n_experts > 0 && !c->expert_to_rank) return MW_ERR_INVALID_ARG;
+    if (c->max_recv_rows > (int64_t)c->n_ranks * 65536) return MW_ERR_UNSUPPORTED;
+    int32_t L = 0;
+    for (int32_t e = 0; e < c->n_experts; ++e) {
+        if (c->expert_to_rank[e] < 0 || c->expert_to_rank[e] >= c->n_ranks) return MW_ERR_INVALID_ARG;
+        L += (c->expert_to_rank[e] == c->my_rank);
+    }
+    if ((int64_t)L * c->n_ranks > 12000) return MW_ERR_UNSUPPORTED;   // (expert, peer) bases live in LDS
+    *n_local = L;
+    return MW_OK;
+}
+
+ws_layout layout(const mw_config &c, int32_t L)
+{
+    const int64_t A = 256;
+    const int64_t Kd = (c.top_k < L ? c.top_k : L) > 0 ? (c.top_k < L ? c.top_k : L) : 1;
+    ws_layout w;
+    int64_t o = 0;
+    w.e2r = o;        o += mw_align_up(4LL * (c.n_experts > 0 ? c.n_experts : 1), A);
+    w.local_slot = o; o += mw_align_up(4LL * (c.n_experts > 0 ? c.n_experts : 1), A);
+    w.pos = o;        o += mw_align_up(4LL * (c.max_tokens > 0 ? c.max_tokens : 1), A);
+    w.flags = o;      o += A;
+    w.cnt = o;        o += mw_align_up(4LL * ((int64_t)L * c.n_ranks > 0 ? (int64_t)L * c.n_ranks : 1), A);
+    w.row_base = o;   o += mw_align_up(4LL * (c.n_ranks + 1), A);
+    w.addr_cnt = o;   o += mw_align_up(4LL * c.n_ranks, A);
+    w.hits = o;       o += mw_align_up((int64_t)sizeof(mw_hit) * Kd * (c.max_recv_rows > 0 ? c.max_recv_rows : 1), A);
+    w.row_map = o;    o += mw_align_up(4LL * (c.max_tokens > 0 ? c.max_tokens : 1), A);
+    w.total = o;
+    return w;
+}
+
+}  // namespace
+
+extern "C" {
+
+MW_API int32_t mw_workspace_bytes(const mw_config *cfg, int64_t *out_bytes)
+{
+    int32_t L = 0;
+    if (!out_bytes) return MW_ERR_INVALID_ARG;
+    int32_t rc = validate(cfg, &L);
+    if (rc != MW_OK) return rc;
+    int64_t xb, sb;
+    rc = row_geometry(*cfg, &xb, &sb);
+    if (rc != MW_OK) return rc;
+    *out_bytes = layout(*cfg, L).total;
+    return MW_OK;
+}
+
+MW_API int32_t mw_ctx_create(const mw_config *cfg, void *workspace_dev, int64_t workspace_bytes, mw_ctx **out)
+{
+    if (!out) return MW_ERR_INVALID_ARG;
+    *out = nullptr;
+    int32_t L = 0;
+    int32_t rc = validate(cfg, &L);
+    if (rc != MW_OK) return rc;
+    int64_t xb = 0, sb = 0;
+    rc = row_geometry(*cfg, &xb, &sb);
+    if (rc != MW_OK) return rc;
+    const ws_layout w = layout(*cfg, L);
+    if (!workspace_dev || ((uintptr_t)workspace_dev & 255u) || workspace_bytes < w.total) return MW_ERR_WORKSPACE;
+
+    mw_ctx *ctx = new (std::nothrow) mw_ctx();
+    if (!ctx) return MW_ERR_INVALID_ARG;
+    ctx->cfg = *cfg;
+    ctx->cfg.expert_to_rank = nullptr;     // the host table is not kept
+    ctx->cfg.row_bytes = xb + sb;
+    ctx->n_local = L;
+    ctx->hit_slots = (cfg->top_k < L ? cfg->top_k : L) > 0 ? (cfg->top_k < L ? cfg->top_k : L) : 1;
+    ctx->mask_words = (cfg->n_ranks + 63) / 64;
+    ctx->x_row_bytes = xb; ctx->s_row_bytes = sb; ctx->row_bytes = xb + sb;
+    char *b = (char *)workspace_dev;
+    ctx->d_e2r = (int32_t *)(b + w.e2r);
+    ctx->d_local_slot = (int32_t *)(b + w.local_slot);
+    ctx->d_pos = (uint32_t *)(b + w.pos);
+    ctx->d_flags = (uint32_t *)(b + w.flags);
+    ctx->d_cnt = (uint32_t *)(b + w.cnt);
+    ctx->d_row_base = (uint32_t *)(b + w.row_base);
+    ctx->d_addr_cnt = (uint32_t *)(b + w.addr_cnt);
+    ctx->d_hits = (mw_hit *)(b + w.hits);
+    ctx->d_row_map = (int32_t *)(b + w.row_map);
+
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&ctx->device) != hipSuccess || hipGetDeviceProperties(&prop, ctx->device) != hipSuccess) {
+        delete ctx; return MW_ERR_HIP;
+    }
+    ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+
+    // rank table and, per expert, its slot among the experts of its own rank
+    std::vector<int32_t> slot((size_t)(cfg->n_experts > 0 ? cfg->n_experts : 1), 0);
+    std::vector<int32_t> seen((size_t)cfg->n_ranks, 0);
+    for (int32_t e = 0; e < cfg->n_experts; ++e) slot[e] = seen[cfg->expert_to_rank[e]]++;
+    bool ok = true;
+    if (cfg->n_experts > 0) {
+        ok = ok && hipMemcpy(ctx->d_e2r, cfg->expert_to_rank, 4u * (size_t)cfg->n_experts, hipMemcpyHostToDevice) == hipSuccess;
+        ok = ok && hipMemcpy(ctx->d_local_slot, slot.data(), 4u * (size_t)cfg->n_experts, hipMemcpyHostToDevice) == hipSuccess;
+    }
+    ok = ok && hipMemset(ctx->d_flags, 0, 256) == hipSuccess;
+    ok = ok && hipDeviceSynchronize() == hipSuccess;
+    if (!ok) { delete ctx; return MW_ERR_HIP; }
+    *out = ctx;
+    return MW_OK;
+}
+
+MW_API int32_t mw_ctx_destroy(mw_ctx *ctx)
+{
+    if (!ctx) return MW_ERR_INVALID_ARG;
+    delete ctx;
+    return MW_OK;
+}
+
+MW_API int32_t mw_plan(mw_ctx *ctx, const int32_t *topk_ids_dev, int32_t n_tokens, uint64_t *mask_dev,
+                int32_t *perm_dev, mw_group_desc *desc_dev, mw_send_stats *stats_dev, void *stream)
+{
+    if (!ctx || !stats_dev || n_tokens < 0) return MW_ERR_INVALID_ARG;
+    if (n_tokens > ctx->cfg.max_tokens) return MW_ERR_CAPACITY;
+    if (n_tokens > 0 && (!topk_ids_dev || !mask_dev || !perm_dev || !desc_dev)) return MW_ERR_INVALID_ARG;
+    if (ctx->cfg.n_experts == 0) return MW_ERR_INVALID_ARG;
+    return mw_launch_plan(ctx, topk_ids_dev, n_tokens, mask_dev, perm_dev, desc_dev, stats_dev, (hipStream_t)stream);
+}
+
+MW_API int32_t mw_pack(mw_ctx *ctx, const void *x_dev, const float *scales_dev, const int32_t *topk_ids_dev,
+                const int32_t *perm_dev, const mw_send_stats *stats_dev, int32_t n_tokens,
+                void *packed_rows_dev, int32_t *row_src_token_dev, int32_t *row_topk_dev, void *stream)
+{
+    if (!ctx || !stats_dev || n_tokens < 0) return MW_ERR_INVALID_ARG;
+    if (n_tokens > ctx->cfg.max_tokens) return MW_ERR_CAPACITY;
+    if (n_tokens == 0) return MW_OK;
+    if (!x_dev || !topk_ids_dev || !perm_dev || !packed_rows_dev || !row_src_token_dev || !row_topk_dev)
+        return MW_ERR_INVALID_ARG;
+    if ((ctx->s_row_bytes > 0) != (scales_dev != nullptr)) return MW_ERR_INVALID_ARG;
+    if (((uintptr_t)x_dev | (uintptr_t)packed_rows_dev | (uintptr_t)scales_dev) & 15u) return MW_ERR_INVALID_ARG;
+    return mw_launch_pack(ctx, x_dev, scales_dev, topk_ids_dev, perm_dev, stats_dev, n_tokens, packed_rows_dev,
+                          row_src_token_dev, row_topk_dev, (hipStream_t)stream);
+}
+
+MW_API int32_t mw_plan_allgather(mw_ctx *ctx, int64_t shard_bytes, mw_group_desc *desc_dev, mw_send_stats *stats_dev,
+                          void *stream)
+{
+    if (!ctx || !desc_dev || !stats_dev || shard_bytes < 0) return MW_ERR_INVALID_ARG;
+    return mw_launch_plan_allgather(ctx, shard_bytes, desc_dev, stats_dev, (hipStream_t)stream);
+}
+
+MW_API int32_t mw_pack_allgather(mw_ctx *ctx, const void *shard_dev, int64_t shard_bytes, void *send_buf_dev,
+                          void *stream)
+{
+    if (!ctx || shard_bytes < 0) return MW_ERR_INVALID_ARG;
+    if (shard_bytes % 16 != 0) return MW_ERR_UNSUPPORTED;
+    if (shard_bytes == 0) return MW_OK;
+    if (!shard_dev || !send_buf_dev || (((uintptr_t)shard_dev | (uintptr_t)send_buf_dev) & 15u))
+        return MW_ERR_INVALID_ARG;
+    return mw_launch_copy(send_buf_dev, shard_dev, shard_bytes, (hipStream_t)stream);
+}
+
+MW_API int32_t mw_unpack(mw_ctx *ctx, const mw_recv_peer *peers_dev, int32_t n_peers, void *out_rows_dev,
+                  float *out_scales_dev, int64_t out_capacity_rows, int32_t *out_src_peer_dev,
+                  int32_t *out_src_token_dev, int64_t *expert_offsets_dev, mw_recv_stats *recv_stats_dev,
+                  void *stream)
+{
+    if (!ctx || !peers_dev || !expert_offsets_dev || !recv_stats_dev || out_capacity_rows < 0)
+        return MW_ERR_INVALID_ARG;
+    if (n_peers < 1 || n_peers > ctx->cfg.n_ranks) return MW_ERR_INVALID_ARG;
+    if (ctx->cfg.n_experts == 0) return MW_ERR_INVALID_ARG;
+    if (out_capacity_rows > 0 && (!out_rows_dev || !out_src_peer_dev || !out_src_token_dev))
+        return MW_ERR_INVALID_ARG;
+    if (out_capacity_rows > 0 && (ctx->s_row_bytes > 0) != (out_scales_dev != nullptr)) return MW_ERR_INVALID_ARG;
+    if (out_capacity_rows > 0xffffffffLL) return MW_ERR_UNSUPPORTED;
+    if (((uintptr_t)out_rows_dev | (uintptr_t)out_scales_dev) & 15u) return MW_ERR_INVALID_ARG;
+    return mw_launch_unpack(ctx, peers_dev, n_peers, out_rows_dev, out_scales_dev, out_capacity_rows,
+                            out_src_peer_dev, out_src_token_dev, expert_offsets_dev, recv_stats_dev,
+                            (hipStream_t)stream);
+}
+
+MW_API int32_t mw_unpack_allgather(mw_ctx *ctx, const void *const *peer_shards_dev, int64_t shard_bytes, void *out_dev,
+                            void *stream)
+{
+    if (!ctx || shard_bytes < 0) return MW_ERR_INVALID_ARG;
+    if (shard_bytes % 16 != 0) return MW_ERR_UNSUPPORTED;
+    if (shard_bytes == 0) return MW_OK;
+    if (!peer_shards_dev || !out_dev || ((uintptr_t)out_dev & 15u)) return MW_ERR_INVALID_ARG;
+    return mw_launch_gather_shards(ctx, peer_shards_dev, shard_bytes, out_dev, (hipStream_t)stream);
+}
+
+MW_API int32_t mw_sim_deliver(mw_ctx *ctx, const mw_group_desc *desc_dev, const mw_send_stats *stats_dev,
+                       int32_t n_tokens, const void *packed_rows_dev, const int32_t *row_src_token_dev,
+                       const int32_t *row_topk_dev, int32_t dst_rank, mw_group_desc *desc_out_dev,
+                       void *rows_out_dev, int32_t *src_token_out_dev, int32_t *topk_out_dev,
+                       uint32_t *counts_out_dev, void *stream)
+{
+    if (!ctx || !stats_dev || !counts_out_dev || n_tokens < 0) return MW_ERR_INVALID_ARG;
+    if (n_tokens > ctx->cfg.max_tokens) return MW_ERR_CAPACITY;
+    if (dst_rank < 0 || dst_rank >= ctx->cfg.n_ranks) return MW_ERR_INVALID_ARG;
+    if (n_tokens > 0 && (!desc_dev || !packed_rows_dev || !row_src_token_dev || !row_topk_dev || !desc_out_dev ||
+                         !rows_out_dev || !src_token_out_dev || !topk_out_dev))
+        return MW_ERR_INVALID_ARG;
+    if (((uintptr_t)packed_rows_dev | (uintptr_t)rows_out_dev) & 15u) return MW_ERR_INVALID_ARG;
+    return mw_launch_sim_deliver(ctx, desc_dev, stats_dev, n_tokens, packed_rows_dev, row_src_token_dev,
+                                 row_topk_dev, dst_rank, desc_out_dev, rows_out_dev, src_token_out_dev,
+                                 topk_out_dev, counts_out_dev, (hipStream_t)stream);
+}
+
+MW_API int32_t mw_copy_bytes(void *dst_dev, const void *src_dev, int64_t n_bytes, void *stream)
+{
+    if (n_bytes < 0) return MW_ERR_INVALID_ARG;
+    if (n_bytes % 16 != 0) return MW_ERR_UNSUPPORTED;
+    if (n_bytes == 0) return MW_OK;
+    if (!dst_dev || !src_dev || (((uintptr_t)dst_dev | (uintptr_t)src_dev) & 15u)) return MW_ERR_INVALID_ARG;
+    return mw_launch_copy(dst_dev, src_dev, n_bytes, (hipStream_t)stream);
+}
+
+MW_API int32_t mw_get_send_stats(mw_ctx *ctx, const mw_send_stats *stats_dev, mw_send_stats *host_out, void *stream)
+{
+    if (!ctx || !stats_dev || !host_out) return MW_ERR_INVALID_ARG;
+    MW_HIP_CHECK(hipMemcpyAsync(host_out, stats_dev, sizeof(mw_send_stats), hipMemcpyDeviceToHost, (hipStream_t)stream));
+    MW_HIP_CHECK(hipStreamSynchronize((hipStream_t)stream));
+    return MW_OK;
+}
+
+MW_API int32_t mw_get_recv_stats(mw_ctx *ctx, const mw_recv_stats *stats_dev, mw_recv_stats *host_out, void *stream)
+{
+    if (!ctx || !stats_dev || !host_out) return MW_ERR_INVALID_ARG;
+    MW_HIP_CHECK(hipMemcpyAsync(host_out, stats_dev, sizeof(mw_recv_stats), hipMemcpyDeviceToHost, (hipStream_t)stream));
+    MW_HIP_CHECK(hipStreamSynchronize((hipStream_t)stream));
+    return MW_OK;
+}
+
+MW_API const char *mw_status_string(int32_t status)
+{
+    switch (status) {
+    case MW_OK: return "ok";
+    case MW_ERR_INVALID_ARG: return "invalid argument";
+    case MW_ERR_CAPACITY: return "size beyond the context's capacity";
+    case MW_ERR_UNSUPPORTED: return "unsupported configuration";
+    case MW_ERR_HIP: return "HIP runtime error";
+    case MW_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,100 @@
+// Internal declarations shared by the HIP sources of the MultiWrite library.
+// Not installed; the public C ABI is include/mw.h.
+#ifndef MW_INTERNAL_H_
+#define MW_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "mw.h"
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// (local expert slot, rank among the peer's rows for that expert); le < 0 = unused slot
+struct mw_hit { int32_t le; int32_t rank; };
+
+// Host-side context.  Every d_* pointer is a slice of the caller's workspace.
+struct mw_ctx {
+    mw_config cfg;
+    int32_t n_local;        // L: experts hosted by my_rank
+    int32_t hit_slots;      // Kd = max(1, min(K, L)): local experts one row can name
+    int32_t mask_words;     // ceil(R / 64): bitmap words that can be non-zero
+    int64_t x_row_bytes;    // payload part of a row
+    int64_t s_row_bytes;    // scale part of a row (fp8) or 0
+    int64_t row_bytes;
+    int device;
+    int n_cu;
+    // workspace slices
+    int32_t *d_e2r;         // [E]
+    int32_t *d_local_slot;  // [E] slot of expert e on its own rank
+    uint32_t *d_pos;        // [max_tokens] plan: predecessors of token t in (bitmap, token) order
+    uint32_t *d_flags;      // [4] 0: plan flags, 1: receive flags
+    uint32_t *d_cnt;        // [L][R] rows of peer p delivered to local expert le
+    uint32_t *d_row_base;   // [R + 1] exclusive prefix of the peers' n_rows
+    uint32_t *d_addr_cnt;   // [R] rows of peer p whose group names this rank
+    mw_hit *d_hits;         // [max_recv_rows][Kd]
+    int32_t *d_row_map;     // [max_tokens] mw_sim_deliver: kept row -> sender row
+};
+
+#define MW_HIP_CHECK(expr)                         \
+    do {                                           \
+        hipError_t e_ = (expr);                    \
+        if (e_ != hipSuccess) return MW_ERR_HIP;   \
+    } while (0)
+
+static inline int64_t mw_align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+// ---- device helpers ---------------------------------------------------------------------
+#ifdef __HIPCC__
+// Streaming 16-byte accesses: payload rows are touched once, keep them out of the way of
+// the small, reused index arrays.
+__device__ __forceinline__ u32x4 mw_ld16(const u32x4 *p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ void mw_st16(u32x4 *p, u32x4 v) { __builtin_nontemporal_store(v, p); }
+
+// Exclusive prefix sum over one value per thread of a block (blockDim.x multiple of 64,
+// at most 1024).  `wave_tot` is LDS scratch of 17 words.  Returns the exclusive prefix;
+// *total receives the block total.  Ends with a barrier so the scratch can be reused.
+__device__ __forceinline__ uint32_t mw_block_exscan(uint32_t v, uint32_t *wave_tot, uint32_t *total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_wave = blockDim.x >> 6;
+    uint32_t inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint32_t o = __shfl_up(inc, d, 64);
+        if (lane >= d) inc += o;
+    }
+    if (lane == 63) wave_tot[wave] = inc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t run = 0;
+        for (int w = 0; w < n_wave; ++w) { uint32_t t = wave_tot[w]; wave_tot[w] = run; run += t; }
+        wave_tot[16] = run;
+    }
+    __syncthreads();
+    const uint32_t ex = wave_tot[wave] + inc - v;
+    *total = wave_tot[16];
+    __syncthreads();
+    return ex;
+}
+#endif
+
+// kernels' host launchers (one per source file)
+int32_t mw_launch_plan(mw_ctx *ctx, const int32_t *topk, int32_t T, uint64_t *mask, int32_t *perm,
+                       mw_group_desc *desc, mw_send_stats *stats, hipStream_t s);
+int32_t mw_launch_pack(mw_ctx *ctx, const void *x, const float *scales, const int32_t *topk,
+                       const int32_t *perm, const mw_send_stats *stats, int32_t T, void *packed,
+                       int32_t *row_src_token, int32_t *row_topk, hipStream_t s);
+int32_t mw_launch_unpack(mw_ctx *ctx, const mw_recv_peer *peers, int32_t P, void *out_rows,
+                         float *out_scales, int64_t cap, int32_t *out_src_peer, int32_t *out_src_token,
+                         int64_t *expert_offsets, mw_recv_stats *stats, hipStream_t s);
+int32_t mw_launch_plan_allgather(mw_ctx *ctx, int64_t shard_bytes, mw_group_desc *desc,
+                                 mw_send_stats *stats, hipStream_t s);
+int32_t mw_launch_copy(void *dst, const void *src, int64_t n_bytes, hipStream_t s);
+int32_t mw_launch_gather_shards(mw_ctx *ctx, const void *const *shards, int64_t shard_bytes, void *out,
+                                hipStream_t s);
+int32_t mw_launch_sim_deliver(mw_ctx *ctx, const mw_group_desc *desc, const mw_send_stats *stats,
+                              int32_t T, const void *rows, const int32_t *src_token, const int32_t *topk,
+                              int32_t dst_rank, mw_group_desc *desc_out, void *rows_out,
+                              int32_t *src_token_out, int32_t *topk_out, uint32_t *counts, hipStream_t s);
+
+#endif  // MW_INTERNAL_H_

@@ -304,3 +304,11 @@ def allgather_shard(w: AllGatherWorkload, seed: int, rank: int) -> np.ndarray:
     """uint16 [shard_elems]: bf16 bit patterns of N(0,1) values of `rank`."""
     k = _key(seed, w.wid, 0xA6, rank)
     return f32_to_bf16_bits(_normal(k, w.shard_elems).astype(np.float32))
+
+
+def topk_ids_many(w: DispatchWorkload, seed: int, peers, threads: int = 8):
+    """topk_ids for several peers (numpy releases the GIL in the heavy parts)."""
+    from concurrent.futures import ThreadPoolExecutor
+    peers = list(peers)
+    with ThreadPoolExecutor(max(1, threads)) as ex:
+        return list(ex.map(lambda p: topk_ids(w, seed, p), peers))

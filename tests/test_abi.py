@@ -1,0 +1,105 @@
+"""Host-only checks of the C-ABI library: it loads without a GPU, exports every symbol
+include/mw.h declares, its records have the documented sizes and offsets, and the
+host-side validation answers without touching a device."""
+import ctypes as C
+import os
+import re
+import subprocess
+import tempfile
+
+import numpy as np
+import pytest
+
+from paper_2605_22428_amd import binding as B
+from paper_2605_22428_amd import build as hip_build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "mw.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        hip_build.build()
+    return B.load()
+
+
+def test_exports_every_declared_symbol(lib):
+    text = open(HEADER).read()
+    declared = re.findall(r"MW_API\s+[\w\s\*]+?\b(mw_\w+)\s*\(", text)
+    assert sorted(set(declared)) == sorted(B.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_record_layouts_match_the_header():
+    src = r'''
+#include <stdio.h>
+#include <stddef.h>
+#include "mw.h"
+int main(void) {
+  printf("%zu %zu %zu %zu %zu\n", sizeof(mw_group_desc), sizeof(mw_send_stats), sizeof(mw_recv_stats),
+         sizeof(mw_recv_peer), sizeof(mw_config));
+  printf("%zu %zu %zu\n", offsetof(mw_group_desc, row_offset), offsetof(mw_group_desc, n_dest),
+         offsetof(mw_send_stats, rows_per_dest));
+  printf("%zu %zu %zu %zu\n", offsetof(mw_send_stats, error_flags), offsetof(mw_recv_peer, rows),
+         offsetof(mw_recv_peer, row_topk), offsetof(mw_config, expert_to_rank));
+  return 0; }
+'''
+    with tempfile.TemporaryDirectory() as d:
+        c = os.path.join(d, "t.c")
+        open(c, "w").write(src)
+        exe = os.path.join(d, "t")
+        subprocess.check_call(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), c, "-o", exe])
+        out = subprocess.check_output([exe]).decode().split()
+    vals = [int(v) for v in out]
+    assert vals[:5] == [48, 1056, 24, 40, C.sizeof(B.MwConfig)]
+    assert vals[5:8] == [B.DESC_DTYPE.fields["row_offset"][1], B.DESC_DTYPE.fields["n_dest"][1],
+                         B.SEND_STATS_DTYPE.fields["rows_per_dest"][1]]
+    assert vals[8:] == [B.SEND_STATS_DTYPE.fields["error_flags"][1], B.RECV_PEER_DTYPE.fields["rows"][1],
+                        B.RECV_PEER_DTYPE.fields["row_topk"][1], B.MwConfig.expert_to_rank.offset]
+
+
+def _cfg(**kw):
+    e2r = np.arange(16, dtype=np.int32) // 2
+    base = dict(n_ranks=8, n_experts=16, top_k=2, my_rank=0, hidden=256, row_format=B.MW_ROW_BF16,
+                row_bytes=0, max_tokens=128, reserved0=0, max_recv_rows=1024,
+                expert_to_rank=e2r.ctypes.data)
+    base.update(kw)
+    return B.MwConfig(**base), e2r
+
+
+def test_workspace_query_and_validation(lib):
+    need = C.c_int64(0)
+    cfg, keep = _cfg()
+    assert lib.mw_workspace_bytes(C.byref(cfg), C.byref(need)) == B.MW_OK and need.value > 0
+    assert need.value % 256 == 0
+    for kw, want in [(dict(n_ranks=257), B.MW_ERR_UNSUPPORTED),          # bitmap is 256 bits wide
+                     (dict(top_k=65), B.MW_ERR_UNSUPPORTED),
+                     (dict(my_rank=8), B.MW_ERR_INVALID_ARG),
+                     (dict(top_k=0), B.MW_ERR_INVALID_ARG),
+                     (dict(hidden=7), B.MW_ERR_UNSUPPORTED),              # 14-byte rows
+                     (dict(row_format=B.MW_ROW_FP8_E4M3_BLOCK128, hidden=256), B.MW_ERR_UNSUPPORTED),
+                     (dict(row_format=B.MW_ROW_FP8_E4M3_BLOCK128, hidden=7168), B.MW_OK),
+                     (dict(row_format=B.MW_ROW_BYTES, row_bytes=24), B.MW_ERR_UNSUPPORTED),
+                     (dict(row_format=B.MW_ROW_BYTES, row_bytes=2 << 20), B.MW_OK),
+                     (dict(row_bytes=100), B.MW_ERR_INVALID_ARG),         # contradicts the bf16 row size
+                     (dict(max_tokens=1 << 20), B.MW_ERR_UNSUPPORTED),
+                     (dict(expert_to_rank=0), B.MW_ERR_INVALID_ARG)]:
+        cfg, keep = _cfg(**kw)
+        assert lib.mw_workspace_bytes(C.byref(cfg), C.byref(need)) == want, kw
+    bad = np.full(16, 9, dtype=np.int32)
+    cfg, keep = _cfg(expert_to_rank=bad.ctypes.data)
+    assert lib.mw_workspace_bytes(C.byref(cfg), C.byref(need)) == B.MW_ERR_INVALID_ARG
+    assert lib.mw_workspace_bytes(None, C.byref(need)) == B.MW_ERR_INVALID_ARG
+    # a context needs a workspace: rejected before any device call
+    cfg, keep = _cfg()
+    h = C.c_void_p(0)
+    assert lib.mw_ctx_create(C.byref(cfg), None, C.c_int64(0), C.byref(h)) == B.MW_ERR_WORKSPACE
+
+
+def test_status_strings(lib):
+    assert B.status_string(0) == "ok"
+    for s in (-1, -2, -3, -4, -5):
+        assert B.status_string(s) not in ("ok", "unknown status")
+    assert B.status_string(-99) == "unknown status"

@@ -1,0 +1,334 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the
+same seeded inputs.  Bar: bit-exact on every index, descriptor, statistic and payload
+byte (the path is pure data movement and integer work; nothing is rounded)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2605_22428_amd import binding as B
+from paper_2605_22428_amd import workloads as W
+
+import gpu_harness as H
+
+pytestmark = pytest.mark.gpu
+
+SEEDS = [W.BASE_SEED, 1, 2]
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def run_dispatch(w, seed, my_rank, check_all_senders=True, lazy=False, tier2=True, also_full=False,
+                 sample_peers=()):
+    """Every simulated peer runs plan+pack (GPU and oracle separately), the simulated network
+    filters to my_rank, then unpack on both sides; compared at every stage."""
+    _say("dispatch", w.name, "seed", seed, "my_rank", my_rank, "T", w.n_tokens, "H", w.hidden)
+    e2r = W.expert_to_rank(w)
+    ctx = H.make_ctx(w, my_rank)
+    recs, full_recs, bufs, toks = [], [], [], []
+    topks = W.topk_ids_many(w, seed, range(w.n_ranks))
+    x_dev = s_dev = None
+    if lazy:
+        xdt = torch.uint8 if w.row_format == "fp8" else torch.int16
+        x_dev = torch.zeros((w.n_tokens, w.hidden), dtype=xdt, device=H.DEV)
+        if w.row_format == "fp8":
+            s_dev = torch.zeros((w.n_tokens, w.hidden // 128), dtype=torch.float32, device=H.DEV)
+    for p in range(w.n_ranks):
+        tk = topks[p]
+        if lazy:
+            tokens = W.tokens_for_rank(w, tk, my_rank)
+            rows, sc_rows = W.payload_rows(w, seed, p, tokens)
+            x = np.zeros((w.n_tokens, w.hidden), dtype=rows.dtype)
+            x[tokens] = rows
+            sc = None
+            idx = torch.from_numpy(tokens).to(H.DEV)
+            x_dev.zero_()
+            x_dev[idx] = H.dev(rows).view(x_dev.dtype)
+            if sc_rows is not None:
+                sc = np.zeros((w.n_tokens, w.hidden // 128), dtype=np.float32)
+                sc[tokens] = sc_rows
+                s_dev.zero_()
+                s_dev[idx] = H.dev(sc_rows)
+            g = H.GpuSend(ctx, tk, x, sc, x_dev=x_dev, scales_dev=s_dev)
+        else:
+            x, sc = W.payload_rows(w, seed, p)
+            g = H.GpuSend(ctx, tk, x, sc)
+        toks.append((tk, x, sc))
+        detailed = check_all_senders or p == my_rank or p in sample_peers
+        if detailed or tier2:
+            if detailed:
+                perm, desc, packed, src, rtk = H.check_send(w, g, tk, x, sc)
+            else:
+                _, perm, desc, _ = ref.plan(tk, e2r, w.n_ranks, w.row_bytes)
+                packed, src, rtk = ref.pack(x, sc, tk, perm)
+            obuf = ref.deliver(desc, packed, src, rtk, my_rank)
+            bufs.append(obuf)
+        rec = H.shrink(g.deliver(my_rank))
+        if detailed:
+            got = H.record_host(rec)
+            for a, b, name in zip(got, obuf, ("desc", "rows", "src_token", "row_topk")):
+                H.assert_same_bytes(a.view(np.uint8) if name == "desc" else a,
+                                    b.view(np.uint8) if name == "desc" else b, "deliver %s peer %d" % (name, p))
+        recs.append(rec)
+        if also_full:
+            fr = g.full_record()
+            full_recs.append(dict(desc=fr["desc"].clone(), rows=fr["rows"].clone(),
+                                  row_src_token=fr["row_src_token"].clone(), row_topk=fr["row_topk"].clone(),
+                                  n_desc=fr["n_desc"], n_rows=fr["n_rows"]))
+        del g
+    xrb = 2 * w.hidden if w.row_format == "bf16" else w.hidden
+    srb = w.row_bytes - xrb
+    m_rows = sum(r["n_rows"] for r in recs)
+    cap = max(1, m_rows * min(w.top_k, w.experts_per_rank))
+    o1 = ref.dispatch_plain(toks, e2r, my_rank, cap)
+    gu = H.GpuUnpack(ctx, recs, cap)
+    H.check_unpack(gu, o1, "vs plain definition")
+    assert int(gu.stats["n_recv_rows"]) == m_rows
+    if tier2:
+        o2 = ref.unpack(bufs, w.top_k, e2r, my_rank, xrb, srb, cap)
+        H.check_unpack(gu, o2, "vs oracle unpack")
+    if also_full:
+        gf = H.GpuUnpack(ctx, full_recs, cap)
+        H.check_unpack(gf, o1, "complete sender buffers")
+    _say("  rows received", m_rows, "output rows", gu.Q)
+    ctx.close()
+    return gu
+
+
+# ------------------------------------------------------------------ configs at oracle-friendly sizes
+@pytest.mark.parametrize("seed", SEEDS)
+@pytest.mark.parametrize("my_rank", [0, 5])
+def test_c0_tiny(seed, my_rank):
+    run_dispatch(W.C0, seed, my_rank, also_full=True)
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_c1_shape_reduced(seed):
+    # 64 ranks, 256 experts, top-8, group-limited routing; 333 tokens (ragged), 1024-wide rows
+    run_dispatch(W.scaled(W.C1, n_tokens=333, hidden=1024), seed, 37, also_full=(seed == 1))
+
+
+@pytest.mark.parametrize("seed", SEEDS[:2])
+def test_c2_shape_reduced_fp8(seed):
+    run_dispatch(W.scaled(W.C2, n_tokens=333, hidden=1024), seed, 0, also_full=(seed == 1))
+
+
+@pytest.mark.parametrize("which", ["median", "hottest"])
+def test_c3_shape_reduced(which):
+    w = W.scaled(W.C3, n_tokens=200, hidden=512)
+    r = W.zipf_median_rank(w, 1) if which == "median" else W.zipf_hottest_rank(w, 1)
+    run_dispatch(w, 1, r, check_all_senders=False, sample_peers=(0, 100, 255))
+
+
+def test_wide_rows_ragged_tail():
+    # full-width bf16 and fp8 rows, token count not a multiple of any tile
+    run_dispatch(W.DispatchWorkload("wide_bf16", 11, 8, 16, 2, 257, 7168, "bf16", "uniform"), 1, 3)
+    run_dispatch(W.DispatchWorkload("wide_fp8", 12, 8, 16, 2, 129, 7168, "fp8", "uniform"), 1, 6)
+
+
+# ------------------------------------------------------------------ full sizes
+def test_c1_full_size():
+    run_dispatch(W.C1, W.BASE_SEED, 0, check_all_senders=False, lazy=True, sample_peers=(7, 63))
+
+
+def test_c2_full_size_fp8():
+    run_dispatch(W.C2, W.BASE_SEED, 0, check_all_senders=False, lazy=True, tier2=False, sample_peers=(31,))
+
+
+def test_c3_full_size_send_side():
+    w = W.C3
+    tk = W.topk_ids(w, W.BASE_SEED, 0)
+    tokens = np.arange(0, w.n_tokens, 7)
+    x, _ = W.payload_full(w, W.BASE_SEED, 0, tokens)
+    ctx = H.make_ctx(w, 0, max_recv_rows=1)
+    g = H.GpuSend(ctx, tk, x, None)
+    H.check_send(w, g, tk, x, None)
+    assert int(g.stats["unicast_bytes"]) == 8 * int(g.stats["multicast_bytes"])
+    ctx.close()
+
+
+def test_c3_full_size_receive_median_rank():
+    w = W.C3
+    r = W.zipf_median_rank(w, W.BASE_SEED)
+    run_dispatch(W.scaled(w, my_rank=r), W.BASE_SEED, r, check_all_senders=False, lazy=True, tier2=False,
+                 sample_peers=(0, 255))
+
+
+# ------------------------------------------------------------------ AllGather
+@pytest.mark.parametrize("w", [W.AllGatherWorkload("ag_small", 41, 8, 1000 * 8), W.C4],
+                         ids=["small", "C4_full"])
+def test_allgather(w):
+    _say("allgather", w.name)
+    ctx = B.Context(w.n_ranks, 0, 1, w.my_rank, 0, B.MW_ROW_BYTES, 1, 0, None, row_bytes=w.shard_bytes,
+                    device=H.DEV)
+    shards = [W.allgather_shard(w, W.BASE_SEED, r) for r in range(w.n_ranks)]
+    desc = torch.zeros(B.DESC_BYTES, dtype=torch.uint8, device=H.DEV)
+    stats = torch.zeros(B.SEND_STATS_BYTES, dtype=torch.uint8, device=H.DEV)
+    ctx.mw_plan_allgather(w.shard_bytes, desc, stats)
+    od, ost = ref.plan_allgather(w.n_ranks, w.shard_bytes)
+    H.assert_same_bytes(H.host(desc), od.view(np.uint8).reshape(-1), "allgather desc")
+    st = ctx.mw_get_send_stats(stats)
+    H.assert_same_bytes(np.array([st]).view(np.uint8), np.array([ost]).view(np.uint8), "allgather stats")
+    mine = H.dev(shards[w.my_rank])
+    send = torch.zeros_like(mine)
+    ctx.mw_pack_allgather(mine, w.shard_bytes, send)
+    H.assert_same_bytes(H.host(send), ref.pack_allgather(shards[w.my_rank]).view(np.uint16), "send buffer")
+    recv = [send if r == w.my_rank else H.dev(shards[r]) for r in range(w.n_ranks)]
+    table = torch.tensor([t.data_ptr() for t in recv], dtype=torch.int64, device=H.DEV)
+    out = torch.zeros(w.n_ranks * w.shard_elems, dtype=torch.int16, device=H.DEV)
+    ctx.mw_unpack_allgather(table, w.shard_bytes, out)
+    torch.cuda.synchronize()
+    H.assert_same_bytes(H.host(out).view(np.uint8), ref.unpack_allgather(shards), "gathered output")
+    ctx.close()
+
+
+def test_allgather_equals_dispatch_with_all_ranks_set():
+    # Section 2.3.3 / 5.2: AllGather is the static destination set "everyone"
+    R, elems = 8, 2048
+    w = W.AllGatherWorkload("ag_as_dispatch", 42, R, elems)
+    shards = [W.allgather_shard(w, 5, r) for r in range(R)]
+    e2r = np.arange(R, dtype=np.int32)
+    ctx = B.Context(R, R, R, 3, elems, B.MW_ROW_BF16, 1, R, e2r, device=H.DEV)
+    tk = np.arange(R, dtype=np.int32).reshape(1, R)
+    recs = []
+    for p in range(R):
+        g = H.GpuSend(ctx, tk, shards[p].reshape(1, -1), None)
+        recs.append(H.shrink(g.deliver(3)))
+    gu = H.GpuUnpack(ctx, recs, R)
+    H.assert_same_bytes(gu.host_out()[0].reshape(-1), np.concatenate(shards).view(np.uint8), "dispatch as allgather")
+    ctx.close()
+
+
+# ------------------------------------------------------------------ edge and degenerate cases
+def _small(fmt="bf16", T=64, K=2, R=8, E=16, H_=256):
+    return W.DispatchWorkload("edge", 77, R, E, K, T, H_, fmt, "uniform")
+
+
+def test_empty_batch_and_tokens_without_experts():
+    w = _small()
+    e2r = W.expert_to_rank(w)
+    ctx = H.make_ctx(w, 0)
+    g = H.GpuSend(ctx, np.zeros((0, 2), np.int32), np.zeros((0, w.hidden), np.uint16), None)
+    assert (g.N, g.G, int(g.stats["unicast_bytes"]), int(g.stats["error_flags"])) == (0, 0, 0, 0)
+    tk = np.full((w.n_tokens, 2), -1, dtype=np.int32)
+    x, _ = W.payload_rows(w, 1, 0)
+    g = H.GpuSend(ctx, tk, x, None)
+    assert (g.N, g.G) == (0, 0)
+    tk[10] = (3, -1); tk[40] = (-1, 2)
+    g = H.GpuSend(ctx, tk, x, None)
+    H.check_send(w, g, tk, x, None)
+    assert g.N == 2
+    # unpack of peers that sent nothing
+    rec = H.shrink(H.GpuSend(ctx, np.full((4, 2), -1, np.int32), x[:4], None).deliver(0))
+    gu = H.GpuUnpack(ctx, [rec, rec], 4)
+    assert gu.Q == 0 and int(gu.stats["error_flags"]) == 0
+    assert H.host(gu.buf.expert_offsets).tolist() == [0, 0, 0]
+    ctx.close()
+
+
+def test_all_masks_equal_single_group_is_memcpy():
+    w = _small(T=300)
+    tk = np.tile(np.array([[5, 0]], dtype=np.int32), (w.n_tokens, 1))
+    x, _ = W.payload_rows(w, 1, 0)
+    ctx = H.make_ctx(w, 0)
+    g = H.GpuSend(ctx, tk, x, None)
+    H.check_send(w, g, tk, x, None)
+    assert g.G == 1
+    H.assert_same_bytes(g.host_pack()[0].reshape(-1), x.view(np.uint8).reshape(-1), "packed == input")
+    ctx.close()
+
+
+def test_single_destination_is_plain_alltoallv():
+    # Section 4.3.3 rule 2: one destination -> a plain write; the plan is a stable sort by rank
+    w = _small(T=500, K=1, R=16, E=32)
+    run_dispatch(w, 3, 9)
+    tk = W.topk_ids(w, 3, 0)
+    x, _ = W.payload_rows(w, 3, 0)
+    ctx = H.make_ctx(w, 0)
+    g = H.GpuSend(ctx, tk, x, None)
+    dest = W.expert_to_rank(w)[tk[:, 0]]
+    assert np.array_equal(g.host_plan()[1], np.argsort(dest, kind="stable"))
+    assert int(g.stats["unicast_bytes"]) == int(g.stats["multicast_bytes"])
+    ctx.close()
+
+
+def test_duplicate_ids_and_padding_inside_tokens():
+    w = _small(T=96, K=4)
+    tk = W.topk_ids(w, 8, 2)
+    tk[::3, 1] = tk[::3, 0]          # duplicate expert
+    tk[1::5, 3] = -1                 # padding
+    x, _ = W.payload_rows(w, 8, 2)
+    for my_rank in (0, 7):
+        e2r = W.expert_to_rank(w)
+        ctx = H.make_ctx(w, my_rank)
+        g = H.GpuSend(ctx, tk, x, None)
+        perm, desc, packed, src, rtk = H.check_send(w, g, tk, x, None)
+        rec = H.shrink(g.deliver(my_rank))
+        o1 = ref.dispatch_plain([(tk, x, None)], e2r, my_rank, 4 * w.n_tokens)
+        gu = H.GpuUnpack(ctx, [rec], 4 * w.n_tokens)
+        H.check_unpack(gu, o1)
+        ctx.close()
+
+
+def test_invalid_expert_ids_set_the_error_flag():
+    w = _small()
+    tk = W.topk_ids(w, 1, 0)
+    x, _ = W.payload_rows(w, 1, 0)
+    bad = tk.copy(); bad[7, 1] = w.n_experts; bad[20, 0] = -5
+    ctx = H.make_ctx(w, 0)
+    g = H.GpuSend(ctx, bad, x, None)
+    assert int(g.stats["error_flags"]) & B.MW_FLAG_BAD_EXPERT
+    with pytest.raises(ref.OracleError):
+        ref.plan(bad, W.expert_to_rank(w), w.n_ranks, w.row_bytes)
+    # the bad entries are ignored: same plan as with -1 in their place
+    ign = bad.copy(); ign[7, 1] = -1; ign[20, 0] = -1
+    m, perm, desc, st = ref.plan(ign, W.expert_to_rank(w), w.n_ranks, w.row_bytes)
+    H.assert_same_bytes(g.host_plan()[1], perm, "perm with ignored ids")
+    # the flag does not stick to the next call
+    g = H.GpuSend(ctx, tk, x, None)
+    assert int(g.stats["error_flags"]) == 0
+    ctx.close()
+
+
+def test_output_capacity_overflow_is_flagged_and_bounded():
+    w = _small(T=128)
+    ctx = H.make_ctx(w, 0)
+    recs, toks = [], []
+    for p in range(w.n_ranks):
+        tk = W.topk_ids(w, 2, p); x, _ = W.payload_rows(w, 2, p)
+        recs.append(H.shrink(H.GpuSend(ctx, tk, x, None).deliver(0)))
+        toks.append((tk, x, None))
+    o1 = ref.dispatch_plain(toks, W.expert_to_rank(w), 0, 10 ** 6)
+    Q = len(o1[2])
+    cap = Q // 2
+    gu = H.GpuUnpack(ctx, recs, cap)
+    assert int(gu.stats["error_flags"]) & B.MW_FLAG_OUT_CAPACITY and gu.Q == Q
+    got = gu.host_out()
+    H.assert_same_bytes(got[0], o1[0][:cap], "rows below capacity are still exact")
+    with pytest.raises(ref.OracleError):
+        ref.unpack([H.record_host(r) for r in recs], w.top_k, W.expert_to_rank(w), 0, w.row_bytes, 0, cap)
+    ctx.close()
+
+
+def test_host_side_argument_errors():
+    lib = B.load()
+    w = _small()
+    with pytest.raises(B.MwError) as ei:
+        B.Context(300, 16, 2, 0, 256, B.MW_ROW_BF16, 8, 8, np.zeros(16, np.int32), device=H.DEV)
+    assert ei.value.status == B.MW_ERR_UNSUPPORTED
+    with pytest.raises(B.MwError) as ei:
+        B.Context(8, 16, 2, 0, 256, B.MW_ROW_FP8_E4M3_BLOCK128, 8, 8, W.expert_to_rank(w), device=H.DEV)
+    assert ei.value.status == B.MW_ERR_UNSUPPORTED          # fp8 rows need H % 512 == 0
+    with pytest.raises(B.MwError) as ei:
+        B.Context(8, 16, 2, 9, 256, B.MW_ROW_BF16, 8, 8, W.expert_to_rank(w), device=H.DEV)
+    assert ei.value.status == B.MW_ERR_INVALID_ARG
+    ctx = H.make_ctx(w, 0, max_tokens=16)
+    tk = H.dev(W.topk_ids(w, 1, 0))
+    sb = B.SendBuffers(ctx, w.n_tokens)
+    with pytest.raises(B.MwError) as ei:
+        ctx.mw_plan(tk, sb.mask, sb.perm, sb.desc, sb.stats)
+    assert ei.value.status == B.MW_ERR_CAPACITY
+    assert lib.mw_plan(None, None, 0, None, None, None, None, None) == B.MW_ERR_INVALID_ARG
+    ctx.close()
