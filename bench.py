@@ -1,0 +1,292 @@
+#!/usr/bin/env python3
+"""Benchmark of the MultiWrite dispatch hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of the DeepSeek-V3-shaped dispatch
+workload (64 simulated ranks, 256 experts, top-8 with group-limited routing, 4096 tokens
+of 7168 bf16 on this rank; 64 peer receive regions): mw_plan -> mw_pack -> mw_unpack,
+all through the C ABI, inputs resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+N_SETS = 3                      # rotating buffer sets (> 1 GB touched per step, MALL is 256 MB)
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--single-stream", action="store_true",
+                    help="issue send side and receive side on one stream (default: two streams, "
+                         "the two sides are independent and overlap)")
+    ap.add_argument("--seed", type=int, default=None)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the other ranks of the dispatch are "
+              "simulated); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2605_22428_amd import binding as B
+    from paper_2605_22428_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w, my_rank = W.C1, 0
+    seed = W.BASE_SEED if args.seed is None else args.seed
+    R, K, T, rb = w.n_ranks, w.top_k, w.n_tokens, w.row_bytes
+    e2r = W.expert_to_rank(w)
+    L = w.experts_per_rank
+
+    def up(a):
+        a = np.ascontiguousarray(a)
+        if a.dtype == np.uint16:
+            a = a.view(np.int16)
+        return torch.from_numpy(a).to(dev)
+
+    # ---------------------------------------------------------------- set-up (untimed)
+    t_setup = time.time()
+    ctx = B.Context(R, w.n_experts, K, my_rank, w.hidden, B.MW_ROW_BF16, T, R * T, e2r, device=dev)
+    topks = W.topk_ids_many(w, seed, range(R))
+    x_me, _ = W.payload_rows(w, seed, my_rank)
+    topk_d = up(topks[my_rank])
+    log("[bench] routing and local payload drawn in %.1fs" % (time.time() - t_setup))
+
+    # peer receive regions: every simulated peer's plan + pack + delivery runs on the GPU too
+    x_peer = torch.zeros((T, w.hidden), dtype=torch.int16, device=dev)
+    sb = B.SendBuffers(ctx, T)
+    recs = []
+    for p in range(R):
+        tokens = W.tokens_for_rank(w, topks[p], my_rank)
+        rows, _ = W.payload_rows(w, seed, p, tokens)
+        x_peer.zero_()
+        x_peer[torch.from_numpy(tokens).to(dev)] = up(rows)
+        tk_d = up(topks[p])
+        ctx.mw_plan(tk_d, sb.mask, sb.perm, sb.desc, sb.stats)
+        ctx.mw_pack(x_peer, None, tk_d, sb.perm, sb.stats, sb.packed, sb.row_src_token, sb.row_topk)
+        out = dict(desc=torch.zeros((T, B.DESC_BYTES), dtype=torch.uint8, device=dev),
+                   rows=torch.zeros((T, rb), dtype=torch.uint8, device=dev),
+                   row_src_token=torch.zeros(T, dtype=torch.int32, device=dev),
+                   row_topk=torch.zeros((T, K), dtype=torch.int32, device=dev))
+        counts = torch.zeros(2, dtype=torch.int32, device=dev)
+        ctx.mw_sim_deliver(sb.desc, sb.stats, T, sb.packed, sb.row_src_token, sb.row_topk, my_rank,
+                           out["desc"], out["rows"], out["row_src_token"], out["row_topk"], counts)
+        g, n = (int(v) for v in counts.cpu().numpy())
+        recs.append(dict(desc=out["desc"][:max(g, 1)].clone(), rows=out["rows"][:max(n, 1)].clone(),
+                         row_src_token=out["row_src_token"][:max(n, 1)].clone(),
+                         row_topk=out["row_topk"][:max(n, 1)].clone(), n_desc=g, n_rows=n))
+    del x_peer, out
+    M = sum(r["n_rows"] for r in recs)
+    n_desc_total = sum(r["n_desc"] for r in recs)
+    cap = M * min(K, L)
+
+    sets = []
+    for s in range(N_SETS):
+        rs = [dict(desc=r["desc"].clone(), rows=r["rows"].clone(), row_src_token=r["row_src_token"].clone(),
+                   row_topk=r["row_topk"].clone(), n_desc=r["n_desc"], n_rows=r["n_rows"]) for r in recs]
+        sets.append(dict(x=up(x_me), send=B.SendBuffers(ctx, T), recs=rs, table=B.peers_table(rs, dev),
+                         recv=B.RecvBuffers(ctx, cap)))
+    del recs
+    torch.cuda.synchronize()
+    log("[bench] %d peer regions built on the GPU, M=%d rows; set-up %.1fs" % (R, M, time.time() - t_setup))
+
+    # The send side (plan, pack of this rank's tokens) and the receive side (unpack of what the
+    # peers sent) touch disjoint buffers and disjoint workspace; by default they are issued on
+    # two streams of default priority so that the latency-bound plan hides under the expander.
+    s_send, s_recv = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def send_side(s):
+        sd = s["send"]
+        ctx.mw_plan(topk_d, sd.mask, sd.perm, sd.desc, sd.stats)
+        ctx.mw_pack(s["x"], None, topk_d, sd.perm, sd.stats, sd.packed, sd.row_src_token, sd.row_topk)
+
+    def recv_side(s):
+        rv = s["recv"]
+        ctx.mw_unpack(s["table"], R, rv.out_rows, None, cap, rv.out_src_peer, rv.out_src_token,
+                      rv.expert_offsets, rv.stats)
+
+    def step(i: int, two_streams: bool = not args.single_stream):
+        s = sets[i % N_SETS]
+        if two_streams:
+            with torch.cuda.stream(s_send):
+                send_side(s)
+            with torch.cuda.stream(s_recv):
+                recv_side(s)
+        else:
+            send_side(s)
+            recv_side(s)
+
+    def new_events(n):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for a, b in ev:          # torch creates the handles on first record
+            a.record(); b.record()
+        torch.cuda.synchronize()
+        return ev
+
+    # ---------------------------------------------------------------- warm-up, then the timed region
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    st = ctx.mw_get_send_stats(sets[0]["send"].stats)
+    rs0 = ctx.mw_get_recv_stats(sets[0]["recv"].stats)
+    N, Q = int(st["n_rows"]), int(rs0["n_out_rows"])
+    assert int(st["error_flags"]) == 0 and int(rs0["error_flags"]) == 0 and int(rs0["n_recv_rows"]) == M
+
+    ev_expand = new_events(args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ctx.mw_ctx_set_timing_events(B.MW_KERNEL_EXPAND, *ev_expand[i])
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ctx.mw_ctx_set_timing_events(B.MW_KERNEL_EXPAND, None, None)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    expand_ms = sorted(a.elapsed_time(b) for a, b in ev_expand)
+    expand_avg_ms = sum(expand_ms) / len(expand_ms)
+
+    # one stream, for reference
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, False)
+    torch.cuda.synchronize()
+    ms_single = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # ---------------------------------------------------------------- per-kernel breakdown (one stream, untimed)
+    names = {"plan_masks": B.MW_KERNEL_PLAN_MASKS, "plan_rank": B.MW_KERNEL_PLAN_RANK,
+             "plan_groups": B.MW_KERNEL_PLAN_GROUPS, "pack": B.MW_KERNEL_PACK,
+             "recv_index": B.MW_KERNEL_RECV_INDEX, "expand": B.MW_KERNEL_EXPAND}
+    n_b = min(args.steps, 50)
+    evs = {k: new_events(n_b) for k in names}
+    for i in range(n_b):
+        for k, code in names.items():
+            ctx.mw_ctx_set_timing_events(code, *evs[k][i])
+        step(i, False)
+    torch.cuda.synchronize()
+    for code in names.values():
+        ctx.mw_ctx_set_timing_events(code, None, None)
+    kern_us = {k: 1e3 * sum(a.elapsed_time(b) for a, b in evs[k]) / n_b for k in names}
+
+    # plain copy ceiling on the same amount of data as one expand launch
+    n_copy = (M * rb // 16) * 16
+    src = torch.empty(n_copy, dtype=torch.uint8, device=dev)
+    dsts = [torch.empty(n_copy, dtype=torch.uint8, device=dev) for _ in range(2)]
+    evc = new_events(20)
+    for i in range(25):
+        if i >= 5:
+            evc[i - 5][0].record()
+        B.mw_copy_bytes(dsts[i % 2], src, n_copy)
+        if i >= 5:
+            evc[i - 5][1].record()
+    torch.cuda.synchronize()
+    copy_ms = sum(a.elapsed_time(b) for a, b in evc) / len(evc)
+    copy_gbps = 2 * n_copy / copy_ms / 1e6
+    del src, dsts
+
+    # ---------------------------------------------------------------- algorithmic bytes
+    pack_bytes = 2 * N * rb + N * (4 + 4 * K) + N * 4 + N * 4 * K
+    unpack_bytes = M * rb + Q * rb + M * (4 + 4 * K) + n_desc_total * 48 + Q * 8 + (L + 1) * 8
+    expand_bytes = M * rb + Q * rb + Q * 8 + M * 4
+    value = (pack_bytes + unpack_bytes) / (ms_per_step * 1e-3) / 1e9
+    achieved = expand_bytes / (expand_avg_ms * 1e-3) / 1e9
+    pu_us = kern_us["pack"] + kern_us["recv_index"] + kern_us["expand"]
+    saved = 1.0 - int(st["multicast_bytes"]) / int(st["unicast_bytes"])
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "k_expand_C1_hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    result = {
+        "metric": "dispatch pack+unpack HBM GB/s (% of peak) + bytes saved vs unicast, 1 GPU",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "C1 DeepSeek-V3-shaped dispatch: 64 simulated ranks, 256 experts, top-8 "
+                               "group-limited (<=4 of 8 nodes), 4096 tokens x 7168 bf16 on this rank, "
+                               "64 peer receive regions", "seed": seed, "my_rank": my_rank,
+                   "rows_packed": N, "groups": int(st["n_groups"]), "rows_received": M, "rows_out": Q,
+                   "buffer_sets": N_SETS, "streams": 1 if args.single_stream else 2},
+        "single_stream_ms_per_step": round(ms_single, 4),
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "bytes_saved_vs_unicast": round(saved, 4),
+        "step_bytes": {"pack": pack_bytes, "unpack": unpack_bytes},
+        "kernel_us": {k: round(v, 2) for k, v in kern_us.items()},
+        "pack_unpack_only": {"us": round(pu_us, 2),
+                             "GBps": round((pack_bytes + unpack_bytes) / pu_us / 1e3, 1),
+                             "pct_of_hbm_peak": round(100.0 * (pack_bytes + unpack_bytes) / pu_us / 1e3 / HBM_PEAK_GBPS, 2)},
+        "copy_ceiling": {"GBps": round(copy_gbps, 1), "bytes": 2 * n_copy},
+        "roofline": {"kernel": "k_expand", "bound": "hbm", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": traffic, "bytes_per_launch": expand_bytes,
+                     "avg_launch_ms": round(expand_avg_ms, 4), "min_launch_ms": round(expand_ms[0], 4)},
+    }
+
+    # ---------------------------------------------------------------- oracle on the host cores
+    if not args.no_cpu_baseline:
+        from oracle import ref
+        log("[bench] cpu_baseline: building the oracle's own peer regions ...")
+        bufs = []
+        for p in range(R):
+            tokens = W.tokens_for_rank(w, topks[p], my_rank)
+            xp, _ = W.payload_full(w, seed, p, tokens)
+            _, perm, desc, _ = ref.plan(topks[p], e2r, R, rb)
+            packed, src_t, rtk = ref.pack(xp, None, topks[p], perm)
+            bufs.append(ref.deliver(desc, packed, src_t, rtk, my_rank))
+            del xp, packed
+        reps, spent = 0, 0.0
+        t_plan = t_pack = t_unpack = 0.0
+        while reps < 3 or (spent < 10.0 and reps < 40):
+            a = time.perf_counter()
+            _, perm, desc, ost = ref.plan(topks[my_rank], e2r, R, rb)
+            b = time.perf_counter()
+            ref.pack(x_me, None, topks[my_rank], perm)
+            c = time.perf_counter()
+            o = ref.unpack(bufs, K, e2r, my_rank, rb, 0, cap)
+            d = time.perf_counter()
+            t_plan += b - a; t_pack += c - b; t_unpack += d - c
+            spent += d - a; reps += 1
+        assert len(o[2]) == Q and int(ost["n_rows"]) == N
+        result["cpu_baseline"] = {
+            "value": round((pack_bytes + unpack_bytes) * reps / (t_plan + t_pack + t_unpack) / 1e9, 3),
+            "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "the whole C1 step (plan + pack of 4096 tokens, unpack of 64 peer regions), "
+                      "%d repetitions, %.1f s of CPU time" % (reps, spent),
+            "ms_per_step": round(1e3 * spent / reps, 2),
+            "ms": {"plan": round(1e3 * t_plan / reps, 2), "pack": round(1e3 * t_pack / reps, 2),
+                   "unpack": round(1e3 * t_unpack / reps, 2)},
+            "host_cores_visible": os.cpu_count()}
+
+    ctx.close()
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -252,6 +252,22 @@ MW_API int32_t mw_copy_bytes(void *dst_dev, const void *src_dev, int64_t n_bytes
 MW_API int32_t mw_get_send_stats(mw_ctx *ctx, const mw_send_stats *stats_dev, mw_send_stats *host_out, void *stream);
 MW_API int32_t mw_get_recv_stats(mw_ctx *ctx, const mw_recv_stats *stats_dev, mw_recv_stats *host_out, void *stream);
 
+/*
+ * Measurement hook.  While a pair of hipEvent_t handles (created by the caller with
+ * timing enabled, passed as void*) is set for a kernel, every launch of that kernel by
+ * this context records `ev_start` just before it and `ev_stop` just after it on the
+ * call's stream, so the caller can read the kernel's own duration with
+ * hipEventElapsedTime.  NULL, NULL switches the hook off (the default).
+ */
+#define MW_KERNEL_PLAN_MASKS   0
+#define MW_KERNEL_PLAN_RANK    1
+#define MW_KERNEL_PLAN_GROUPS  2
+#define MW_KERNEL_PACK         3
+#define MW_KERNEL_RECV_INDEX   4
+#define MW_KERNEL_EXPAND       5
+#define MW_KERNEL_COUNT        6
+MW_API int32_t mw_ctx_set_timing_events(mw_ctx *ctx, int32_t kernel, void *ev_start, void *ev_stop);
+
 MW_API const char *mw_status_string(int32_t status);
 
 #ifdef __cplusplus

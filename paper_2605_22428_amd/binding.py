@@ -25,7 +25,9 @@ MW_FLAG_BAD_SRC_TOKEN, MW_FLAG_BAD_DESC, MW_FLAG_RECV_CAPACITY, MW_FLAG_DUP_SRC_
 EXPORTS = ["mw_workspace_bytes", "mw_ctx_create", "mw_ctx_destroy", "mw_plan", "mw_pack",
            "mw_plan_allgather", "mw_pack_allgather", "mw_unpack", "mw_unpack_allgather",
            "mw_sim_deliver", "mw_copy_bytes", "mw_get_send_stats", "mw_get_recv_stats",
-           "mw_status_string"]
+           "mw_ctx_set_timing_events", "mw_status_string"]
+MW_KERNEL_PLAN_MASKS, MW_KERNEL_PLAN_RANK, MW_KERNEL_PLAN_GROUPS = 0, 1, 2
+MW_KERNEL_PACK, MW_KERNEL_RECV_INDEX, MW_KERNEL_EXPAND = 3, 4, 5
 
 # numpy views of the ABI records (host copies)
 DESC_DTYPE = np.dtype([("mask", "<u8", (4,)), ("row_offset", "<u4"), ("row_count", "<u4"),
@@ -178,6 +180,13 @@ class Context:
                                      _ptr(row_src_token), _ptr(row_topk), C.c_int32(dst_rank),
                                      _ptr(desc_out), _ptr(rows_out), _ptr(src_token_out), _ptr(topk_out),
                                      _ptr(counts_out), _stream()), "mw_sim_deliver")
+
+    def mw_ctx_set_timing_events(self, kernel: int, ev_start: Optional[torch.cuda.Event],
+                                 ev_stop: Optional[torch.cuda.Event]):
+        """Events must have been recorded once already (torch creates the handle lazily)."""
+        a = C.c_void_p(0 if ev_start is None else ev_start.cuda_event)
+        b = C.c_void_p(0 if ev_stop is None else ev_stop.cuda_event)
+        _check(load().mw_ctx_set_timing_events(self._h, C.c_int32(kernel), a, b), "mw_ctx_set_timing_events")
 
     def mw_get_send_stats(self, stats: torch.Tensor) -> np.ndarray:
         host = np.zeros(1, dtype=SEND_STATS_DTYPE)

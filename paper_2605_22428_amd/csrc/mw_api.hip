@@ -8,7 +8,7 @@
 namespace {
 
 struct ws_layout {
-    int64_t e2r, local_slot, pos, flags, cnt, row_base, addr_cnt, hits, row_map, total;
+    int64_t e2r, local_slot, pos, flags, hist, smask, cnt, base, row_base, addr_cnt, recs, hits, row_map, total;
 };
 
 // Derived row geometry; returns a status.
@@ -53,7 +53,7 @@ int32_t validate(const mw_config *c, int32_t *n_local)
         if (c->expert_to_rank[e] < 0 || c->expert_to_rank[e] >= c->n_ranks) return MW_ERR_INVALID_ARG;
         L += (c->expert_to_rank[e] == c->my_rank);
     }
-    if ((int64_t)L * c->n_ranks > 12000) return MW_ERR_UNSUPPORTED;   // (expert, peer) bases live in LDS
+    if ((int64_t)L * c->n_ranks > (1 << 22)) return MW_ERR_UNSUPPORTED;   // (expert, peer) count table
     *n_local = L;
     return MW_OK;
 }
@@ -68,9 +68,13 @@ ws_layout layout(const mw_config &c, int32_t L)
     w.local_slot = o; o += mw_align_up(4LL * (c.n_experts > 0 ? c.n_experts : 1), A);
     w.pos = o;        o += mw_align_up(4LL * (c.max_tokens > 0 ? c.max_tokens : 1), A);
     w.flags = o;      o += A;
+    w.hist = o;       o += mw_align_up(4LL * MW_MAX_RANKS, A);
+    w.smask = o;      o += mw_align_up(8LL * MW_MASK_WORDS * (c.max_tokens > 0 ? c.max_tokens : 1), A);
     w.cnt = o;        o += mw_align_up(4LL * ((int64_t)L * c.n_ranks > 0 ? (int64_t)L * c.n_ranks : 1), A);
+    w.base = o;       o += mw_align_up(4LL * ((int64_t)L * c.n_ranks > 0 ? (int64_t)L * c.n_ranks : 1), A);
     w.row_base = o;   o += mw_align_up(4LL * (c.n_ranks + 1), A);
     w.addr_cnt = o;   o += mw_align_up(4LL * c.n_ranks, A);
+    w.recs = o;       o += mw_align_up((int64_t)sizeof(mw_row_rec) * (c.max_recv_rows > 0 ? c.max_recv_rows : 1), A);
     w.hits = o;       o += mw_align_up((int64_t)sizeof(mw_hit) * Kd * (c.max_recv_rows > 0 ? c.max_recv_rows : 1), A);
     w.row_map = o;    o += mw_align_up(4LL * (c.max_tokens > 0 ? c.max_tokens : 1), A);
     w.total = o;
@@ -118,10 +122,14 @@ MW_API int32_t mw_ctx_create(const mw_config *cfg, void *workspace_dev, int64_t 
     ctx->x_row_bytes = xb; ctx->s_row_bytes = sb; ctx->row_bytes = xb + sb;
     char *b = (char *)workspace_dev;
     ctx->d_e2r = (int32_t *)(b + w.e2r);
-    ctx->d_local_slot = (int32_t *)(b + w.local_slot);
+    ctx->d_eslot = (int32_t *)(b + w.local_slot);
     ctx->d_pos = (uint32_t *)(b + w.pos);
     ctx->d_flags = (uint32_t *)(b + w.flags);
+    ctx->d_hist = (uint32_t *)(b + w.hist);
+    ctx->d_smask = (uint64_t *)(b + w.smask);
     ctx->d_cnt = (uint32_t *)(b + w.cnt);
+    ctx->d_base = (uint32_t *)(b + w.base);
+    ctx->d_recs = (mw_row_rec *)(b + w.recs);
     ctx->d_row_base = (uint32_t *)(b + w.row_base);
     ctx->d_addr_cnt = (uint32_t *)(b + w.addr_cnt);
     ctx->d_hits = (mw_hit *)(b + w.hits);
@@ -136,13 +144,17 @@ MW_API int32_t mw_ctx_create(const mw_config *cfg, void *workspace_dev, int64_t 
     // rank table and, per expert, its slot among the experts of its own rank
     std::vector<int32_t> slot((size_t)(cfg->n_experts > 0 ? cfg->n_experts : 1), 0);
     std::vector<int32_t> seen((size_t)cfg->n_ranks, 0);
-    for (int32_t e = 0; e < cfg->n_experts; ++e) slot[e] = seen[cfg->expert_to_rank[e]]++;
+    for (int32_t e = 0; e < cfg->n_experts; ++e) {
+        const int32_t r = cfg->expert_to_rank[e];
+        slot[e] = (r << 16) | seen[r]++;      // slots stay below 65536 because E does
+    }
     bool ok = true;
     if (cfg->n_experts > 0) {
         ok = ok && hipMemcpy(ctx->d_e2r, cfg->expert_to_rank, 4u * (size_t)cfg->n_experts, hipMemcpyHostToDevice) == hipSuccess;
-        ok = ok && hipMemcpy(ctx->d_local_slot, slot.data(), 4u * (size_t)cfg->n_experts, hipMemcpyHostToDevice) == hipSuccess;
+        ok = ok && hipMemcpy(ctx->d_eslot, slot.data(), 4u * (size_t)cfg->n_experts, hipMemcpyHostToDevice) == hipSuccess;
     }
     ok = ok && hipMemset(ctx->d_flags, 0, 256) == hipSuccess;
+    ok = ok && hipMemset(ctx->d_hist, 0, 4 * MW_MAX_RANKS) == hipSuccess;
     ok = ok && hipDeviceSynchronize() == hipSuccess;
     if (!ok) { delete ctx; return MW_ERR_HIP; }
     *out = ctx;
@@ -268,6 +280,15 @@ MW_API int32_t mw_get_recv_stats(mw_ctx *ctx, const mw_recv_stats *stats_dev, mw
     if (!ctx || !stats_dev || !host_out) return MW_ERR_INVALID_ARG;
     MW_HIP_CHECK(hipMemcpyAsync(host_out, stats_dev, sizeof(mw_recv_stats), hipMemcpyDeviceToHost, (hipStream_t)stream));
     MW_HIP_CHECK(hipStreamSynchronize((hipStream_t)stream));
+    return MW_OK;
+}
+
+MW_API int32_t mw_ctx_set_timing_events(mw_ctx *ctx, int32_t kernel, void *ev_start, void *ev_stop)
+{
+    if (!ctx || kernel < 0 || kernel >= MW_KERNEL_COUNT) return MW_ERR_INVALID_ARG;
+    if ((ev_start == nullptr) != (ev_stop == nullptr)) return MW_ERR_INVALID_ARG;
+    ctx->ev_start[kernel] = (hipEvent_t)ev_start;
+    ctx->ev_stop[kernel] = (hipEvent_t)ev_stop;
     return MW_OK;
 }
 

@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "mw.h"
 
@@ -12,6 +13,22 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 // (local expert slot, rank among the peer's rows for that expert); le < 0 = unused slot
 struct mw_hit { int32_t le; int32_t rank; };
+
+// One received row as the expander needs it: where it lies, its source token, its peer.
+struct mw_row_rec { const void *src; int32_t src_token; int32_t peer; };   // 16 bytes
+
+// Workgroup shape of the row movers: one 16-byte chunk per lane, a row of `chunks`
+// chunks is covered by `nseg` workgroups of `bs` lanes (bs a multiple of 64, <= 1024).
+static inline void mw_row_block_shape(int chunks, int *bs, int *nseg)
+{
+    int b = (chunks + 63) / 64 * 64;
+    if (const char *e = getenv("MW_TUNE_BS")) b = atoi(e);   // TEMPORARY tuning knob
+    if (b > 1024) b = 1024;
+    if (b < 64) b = 64;
+    *bs = b;
+    *nseg = (chunks + b - 1) / b;
+    if (*nseg < 1) *nseg = 1;
+}
 
 // Host-side context.  Every d_* pointer is a slice of the caller's workspace.
 struct mw_ctx {
@@ -26,14 +43,34 @@ struct mw_ctx {
     int n_cu;
     // workspace slices
     int32_t *d_e2r;         // [E]
-    int32_t *d_local_slot;  // [E] slot of expert e on its own rank
+    int32_t *d_eslot;       // [E] (rank << 16) | slot of expert e among the experts of its rank
     uint32_t *d_pos;        // [max_tokens] plan: predecessors of token t in (bitmap, token) order
-    uint32_t *d_flags;      // [4] 0: plan flags, 1: receive flags
+    uint32_t *d_flags;      // [4] 0: plan flags, 1: receive flags, 2: receive workgroups done
+    uint32_t *d_hist;       // [256] plan: rows per destination, accumulated by k_masks
+    uint64_t *d_smask;      // [max_tokens][4] plan: bitmaps in sorted (perm) order
+    uint32_t *d_base;       // [L][R] first output row of (local expert, peer)
+    mw_row_rec *d_recs;     // [max_recv_rows]
     uint32_t *d_cnt;        // [L][R] rows of peer p delivered to local expert le
     uint32_t *d_row_base;   // [R + 1] exclusive prefix of the peers' n_rows
     uint32_t *d_addr_cnt;   // [R] rows of peer p whose group names this rank
     mw_hit *d_hits;         // [max_recv_rows][Kd]
     int32_t *d_row_map;     // [max_tokens] mw_sim_deliver: kept row -> sender row
+    // measurement hook: optional event pairs recorded around single kernels
+    hipEvent_t ev_start[MW_KERNEL_COUNT];
+    hipEvent_t ev_stop[MW_KERNEL_COUNT];
+};
+
+// Records the context's timing events (if set) around one kernel launch.
+struct mw_timed {
+    mw_ctx *ctx; int k; hipStream_t s;
+    mw_timed(mw_ctx *c, int kernel, hipStream_t st) : ctx(c), k(kernel), s(st)
+    {
+        if (ctx->ev_start[k]) (void)hipEventRecord(ctx->ev_start[k], s);
+    }
+    ~mw_timed()
+    {
+        if (ctx->ev_stop[k]) (void)hipEventRecord(ctx->ev_stop[k], s);
+    }
 };
 
 #define MW_HIP_CHECK(expr)                         \

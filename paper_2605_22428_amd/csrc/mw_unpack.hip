@@ -14,43 +14,48 @@
 //                 is the stable rank of a row among the peer's rows for that expert,
 //                 whatever order the rows were packed in -- no sort, no order-dependent
 //                 atomics (LDS atomic ORs only set bits).  Emits per-(expert, peer)
-//                 counts and per-row (expert slot, rank) pairs.
-//   k_expand      persistent workgroups.  Each first scans the (expert, peer) counts in
-//                 LDS into output bases (a few hundred integers, cheaper than another
-//                 launch or a grid-wide barrier), then walks received rows: a row is
-//                 read once with 16-byte streaming loads and stored to each of its
-//                 experts' slots.  This kernel moves ~all receive-side bytes and is
-//                 bound by HBM bandwidth.
+//                 counts and one record per received row: source address, source token,
+//                 peer and (expert slot, rank) pairs.  The workgroup that finishes last
+//                 (device-scope counter) scans the counts into output bases, so no
+//                 third launch and no grid-wide barrier is needed.
+//   k_expand      one workgroup per received row (grid-stride beyond 32768 rows), one
+//                 16-byte chunk per lane: the row is read once with streaming loads and
+//                 stored to each of its experts' slots.  Measured on MI355X, many small
+//                 waves with a single load in flight each track the plain-copy ceiling,
+//                 while fewer waves with deep per-lane unrolling fall 10-30 % short, and a
+//                 persistent grid loses ~5 % to the hardware dispatcher.  This kernel
+//                 moves ~all receive-side bytes and is bound by HBM bandwidth.
 #include "mw_internal.h"
 
 namespace {
 
 constexpr int kIndexBlock = 1024;
-constexpr int kExpandBlock = 256;
+constexpr uint32_t kExpandMaxRowBlocks = 32768;
 
 __device__ __forceinline__ bool mask_has(const uint64_t *m, int r) { return (m[r >> 6] >> (r & 63)) & 1ull; }
 
-// Is topk_row[j] the first occurrence of its id in the row?  (duplicate ids count once)
-__device__ __forceinline__ bool first_occurrence(const int32_t *topk_row, int j)
+__device__ __forceinline__ uint32_t ld_agent(const uint32_t *p)
 {
-    const int32_t e = topk_row[j];
-    for (int k = 0; k < j; ++k)
-        if (topk_row[k] == e) return false;
-    return true;
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent(uint32_t *p, uint32_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
-    const mw_recv_peer *__restrict__ peers, int P, const int32_t *__restrict__ e2r,
-    const int32_t *__restrict__ local_slot, int E, int K, int Kd, int my_rank, int L, int Lc,
-    uint32_t max_tokens, uint32_t wpl, uint32_t cap_rows, uint32_t *__restrict__ cnt,
-    uint32_t *__restrict__ row_base, uint32_t *__restrict__ addr_cnt, mw_hit *__restrict__ hits,
-    uint32_t *__restrict__ flags)
+    const mw_recv_peer *__restrict__ peers, int P, const int32_t *__restrict__ eslot,
+    int E, int K, int Kd, int my_rank, int L, int Lc,
+    uint32_t max_tokens, uint32_t wpl, uint32_t cap_rows, uint64_t row_bytes, int64_t out_cap,
+    uint32_t *cnt, uint32_t *__restrict__ row_base, uint32_t *addr_cnt, mw_row_rec *__restrict__ recs,
+    mw_hit *__restrict__ hits, uint32_t *__restrict__ base, int64_t *__restrict__ expert_offsets,
+    mw_recv_stats *__restrict__ stats, uint32_t *flags)
 {
     extern __shared__ uint32_t lds[];
-    uint32_t *addr = lds;                 // [wpl]      bit i: row i's group names this rank
-    uint32_t *bits = addr + wpl;          // [Lc][wpl]  bit s of expert l: a row with source token s
-    uint32_t *pre = bits + (size_t)Lc * wpl;   // [Lc][wpl] running popcount before each word
-    uint32_t *scratch = pre + (size_t)Lc * wpl; // [17]
+    uint32_t *addr = lds;                       // [wpl]      bit i: row i's group names this rank
+    uint32_t *bits = addr + wpl;                // [Lc][wpl]  bit s of expert l: a row with source token s
+    uint32_t *pre = bits + (size_t)Lc * wpl;    // [Lc][wpl]  running popcount before each word
+    uint32_t *scratch = pre + (size_t)Lc * wpl; // [17] scan scratch, [17] "I am last"
 
     const int tid = threadIdx.x, nthr = blockDim.x, p = blockIdx.x;
     const mw_recv_peer pr = peers[p];
@@ -72,7 +77,6 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
     }
 
     for (uint32_t w = tid; w < wpl; w += nthr) addr[w] = 0;
-    for (uint32_t k = tid; k < n_rows * (uint32_t)Kd; k += nthr) hits[(size_t)rb * Kd + k] = mw_hit{-1, 0};
     __syncthreads();
 
     // addressed rows: groups whose bitmap has this rank's bit
@@ -95,7 +99,53 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
         uint32_t a = 0, tot;
         for (uint32_t w = tid; w < wpl; w += nthr) a += __popc(addr[w]);
         mw_block_exscan(a, scratch, &tot);
-        if (tid == 0) addr_cnt[p] = tot;
+        if (tid == 0) st_agent(&addr_cnt[p], tot);
+    }
+
+    // Per row: its distinct local experts in top-k order (duplicate ids count once) go to the
+    // row's hit slots, unused slots get -1, and the row record is written.  Ids and table
+    // entries are fetched in independent batches of 8 so a row costs two memory round trips.
+    // A thread always handles the same rows (i = tid, tid + nthr, ...), so it may read its
+    // own slot writes back later without a barrier.
+    for (uint32_t i = tid; i < n_rows; i += nthr) {
+        mw_hit *h = hits + (size_t)(rb + i) * Kd;
+        int nk = 0;
+        if ((addr[i >> 5] >> (i & 31)) & 1u) {
+            const uint32_t s = (uint32_t)pr.row_src_token[i];
+            if (s >= max_tokens) {
+                err |= MW_FLAG_BAD_SRC_TOKEN;
+            } else {
+                const int32_t *tk = pr.row_topk + (size_t)i * K;
+                int f[8];                                   // first eight experts found (dedup in registers)
+                for (int j0 = 0; j0 < K; j0 += 8) {
+                    int32_t e[8], q[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) e[u] = (j0 + u < K) ? tk[j0 + u] : -1;
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const bool ok = (uint32_t)e[u] < (uint32_t)E;
+                        if (e[u] != -1 && !ok) err |= MW_FLAG_BAD_EXPERT;
+                        q[u] = ok ? eslot[e[u]] : -1;
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        if (q[u] < 0 || (q[u] >> 16) != my_rank) continue;
+                        const int le = q[u] & 0xffff;
+                        bool dup = false;
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) dup |= (k < nk && f[k] == le);
+                        for (int k = 8; k < nk; ++k) dup |= (h[k].le == le);
+                        if (dup) continue;
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) if (k == nk) f[k] = le;
+                        h[nk++] = mw_hit{le, 0};
+                    }
+                }
+                if (nk == 0) err |= MW_FLAG_NO_LOCAL_EXPERT;
+                recs[rb + i] = mw_row_rec{(const char *)pr.rows + (size_t)i * row_bytes, (int32_t)s, p};
+            }
+        }
+        for (int k = nk; k < Kd; ++k) h[k] = mw_hit{-1, 0};
     }
 
     for (int le0 = 0; le0 < L; le0 += Lc) {
@@ -104,19 +154,16 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
         for (uint32_t f = tid; f < n_words; f += nthr) bits[f] = 0;
         __syncthreads();
 
-        // mark (expert, source token) pairs
+        // mark (expert, source token) pairs of this chunk of experts
         for (uint32_t i = tid; i < n_rows; i += nthr) {
-            if (!((addr[i >> 5] >> (i & 31)) & 1u)) continue;
+            const mw_hit *h = hits + (size_t)(rb + i) * Kd;
+            if (h[0].le < 0) continue;
             const uint32_t s = (uint32_t)pr.row_src_token[i];
-            if (s >= max_tokens) { err |= MW_FLAG_BAD_SRC_TOKEN; continue; }
-            const int32_t *tk = pr.row_topk + (size_t)i * K;
-            for (int j = 0; j < K; ++j) {
-                const int32_t e = tk[j];
-                if (e == -1) continue;
-                if ((uint32_t)e >= (uint32_t)E) { err |= MW_FLAG_BAD_EXPERT; continue; }
-                if (e2r[e] != my_rank) continue;
-                const int l = local_slot[e] - le0;
-                if (l < 0 || l >= lc || !first_occurrence(tk, j)) continue;
+            for (int k = 0; k < Kd; ++k) {
+                const int le = h[k].le;
+                if (le < 0) break;
+                const int l = le - le0;
+                if (l < 0 || l >= lc) continue;
                 const uint32_t old = atomicOr(&bits[(uint32_t)l * wpl + (s >> 5)], 1u << (s & 31));
                 if ((old >> (s & 31)) & 1u) err |= MW_FLAG_DUP_SRC_TOKEN;
             }
@@ -136,28 +183,22 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
         __syncthreads();
         for (int l = tid; l < lc; l += nthr) {
             const uint32_t end = (l + 1 < lc) ? pre[(uint32_t)(l + 1) * wpl] : carry;
-            cnt[(size_t)(le0 + l) * P + p] = end - pre[(uint32_t)l * wpl];
+            st_agent(&cnt[(size_t)(le0 + l) * P + p], end - pre[(uint32_t)l * wpl]);
         }
 
-        // per row: (expert slot, stable rank) for every distinct local expert it names
+        // stable rank of the row among the peer's rows for each of its experts in the chunk
         for (uint32_t i = tid; i < n_rows; i += nthr) {
-            if (!((addr[i >> 5] >> (i & 31)) & 1u)) continue;
+            mw_hit *h = hits + (size_t)(rb + i) * Kd;
+            if (h[0].le < 0) continue;
             const uint32_t s = (uint32_t)pr.row_src_token[i];
-            if (s >= max_tokens) continue;
-            const int32_t *tk = pr.row_topk + (size_t)i * K;
-            int k = 0;
-            for (int j = 0; j < K; ++j) {
-                const int32_t e = tk[j];
-                if (e == -1 || (uint32_t)e >= (uint32_t)E || e2r[e] != my_rank || !first_occurrence(tk, j)) continue;
-                const int l = local_slot[e] - le0;
-                if (l >= 0 && l < lc) {
-                    const uint32_t wi = (uint32_t)l * wpl + (s >> 5);
-                    const uint32_t r = pre[wi] - pre[(uint32_t)l * wpl] + __popc(bits[wi] & ((1u << (s & 31)) - 1u));
-                    hits[(size_t)(rb + i) * Kd + k] = mw_hit{le0 + l, (int32_t)r};
-                }
-                ++k;
+            for (int k = 0; k < Kd; ++k) {
+                const int le = h[k].le;
+                if (le < 0) break;
+                const int l = le - le0;
+                if (l < 0 || l >= lc) continue;
+                const uint32_t wi = (uint32_t)l * wpl + (s >> 5);
+                h[k].rank = (int32_t)(pre[wi] - pre[(uint32_t)l * wpl] + __popc(bits[wi] & ((1u << (s & 31)) - 1u)));
             }
-            if (k == 0 && le0 == 0) err |= MW_FLAG_NO_LOCAL_EXPERT;
         }
         __syncthreads();
     }
@@ -166,109 +207,78 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
         for (uint32_t w = tid; w < wpl; w += nthr) if (addr[w]) err |= MW_FLAG_NO_LOCAL_EXPERT;
     }
     if (err) atomicOr(&flags[1], err);
-}
 
-template <int U>
-__global__ __launch_bounds__(kExpandBlock) void k_expand(
-    const mw_recv_peer *__restrict__ peers, int P, const uint32_t *__restrict__ row_base,
-    const uint32_t *__restrict__ cnt, const mw_hit *__restrict__ hits, int Kd, int L, int xc, int sc, int tpr,
-    u32x4 *__restrict__ out_rows, u32x4 *__restrict__ out_scales, int64_t cap,
-    int32_t *__restrict__ out_src_peer, int32_t *__restrict__ out_src_token,
-    int64_t *__restrict__ expert_offsets, mw_recv_stats *__restrict__ stats,
-    const uint32_t *__restrict__ addr_cnt, uint32_t *flags)
-{
-    extern __shared__ uint32_t lds[];
-    uint32_t *base = lds;                       // [L * P] first output row of (expert, peer)
-    uint32_t *rbase = base + (size_t)L * P;     // [P + 1]
-    uint32_t *scratch = rbase + P + 1;          // [17]
-    const int tid = threadIdx.x, nthr = blockDim.x;
+    // ---- the workgroup that finishes last turns the counts into output bases ----------
+    // Counts, addressed-row counts and flags were published with device-scope atomics; the
+    // barrier orders them before thread 0's release fence and counter increment.
+    __syncthreads();
+    if (tid == 0) {
+        __threadfence();
+        const bool last = atomicAdd(&flags[2], 1u) == (uint32_t)P - 1u;
+        __threadfence();
+        scratch[17] = last ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!scratch[17]) return;
 
     const uint32_t n_lp = (uint32_t)L * P;
     uint32_t carry = 0;
-    for (uint32_t f0 = 0; f0 < n_lp; f0 += nthr) {
+    for (uint32_t f0 = 0; f0 < n_lp; f0 += nthr) {          // (expert, peer) order = output order
         const uint32_t f = f0 + tid;
-        const uint32_t v = (f < n_lp) ? cnt[f] : 0u;
+        const uint32_t v = (f < n_lp) ? ld_agent(&cnt[f]) : 0u;
         uint32_t tot;
         const uint32_t ex = mw_block_exscan(v, scratch, &tot);
-        if (f < n_lp) base[f] = carry + ex;
+        if (f < n_lp) {
+            base[f] = carry + ex;
+            if (f % (uint32_t)P == 0) expert_offsets[f / (uint32_t)P] = (int64_t)(carry + ex);
+        }
         carry += tot;
     }
-    const uint32_t Q = carry;
-    for (int q = tid; q <= P; q += nthr) rbase[q] = row_base[q];
-    __syncthreads();
-
-    if (blockIdx.x == 0) {
-        for (int le = tid; le < L; le += nthr) expert_offsets[le] = base[(uint32_t)le * P];
-        if (tid == 0) {
-            expert_offsets[L] = Q;
-            uint64_t m = 0;
-            for (int q = 0; q < P; ++q) m += addr_cnt[q];
-            stats->n_recv_rows = m;
-            stats->n_out_rows = Q;
-            stats->error_flags = flags[1] | (((int64_t)Q > cap) ? MW_FLAG_OUT_CAPACITY : 0u);
-            stats->reserved0 = 0;
-            flags[1] = 0;      // ready for the next unpack
-        }
+    uint32_t m = 0, m_tot;
+    for (int q = tid; q < P; q += nthr) m += ld_agent(&addr_cnt[q]);
+    mw_block_exscan(m, scratch, &m_tot);
+    if (tid == 0) {
+        const uint32_t Q = carry;
+        expert_offsets[L] = Q;
+        stats->n_recv_rows = m_tot;
+        stats->n_out_rows = Q;
+        stats->error_flags = ld_agent(&flags[1]) | (((int64_t)Q > out_cap) ? MW_FLAG_OUT_CAPACITY : 0u);
+        stats->reserved0 = 0;
+        st_agent(&flags[1], 0u);           // ready for the next unpack
+        st_agent(&flags[2], 0u);
     }
+}
 
-    const uint32_t m_total = rbase[P];
-    const int rows_per_block = nthr / tpr;
-    const int sub = __builtin_amdgcn_readfirstlane(tid / tpr);   // tpr is a multiple of the wave size
-    const int lane = tid - sub * tpr;
+// blockIdx.y selects a segment of blockDim.x chunks of the row; blockIdx.x walks rows.
+__global__ __launch_bounds__(1024) void k_expand(
+    const mw_row_rec *__restrict__ recs, const mw_hit *__restrict__ hits, const uint32_t *__restrict__ base,
+    const uint32_t *__restrict__ row_base, int P, int Kd, int xc, int sc,
+    u32x4 *__restrict__ out_rows, u32x4 *__restrict__ out_scales, int64_t cap,
+    int32_t *__restrict__ out_src_peer, int32_t *__restrict__ out_src_token)
+{
+    const uint32_t m_total = row_base[P];
     const int n = xc + sc;
-    for (uint32_t g = blockIdx.x * rows_per_block + sub; g < m_total; g += gridDim.x * rows_per_block) {
+    const int c = blockIdx.y * blockDim.x + threadIdx.x;
+    for (uint32_t g = blockIdx.x; g < m_total; g += gridDim.x) {
         const mw_hit *h = hits + (size_t)g * Kd;
-        if (h[0].le < 0) continue;              // slots fill from 0: nothing to deliver
-        int lo = 0, hi = P;                     // peer of row g: last p with rbase[p] <= g
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (rbase[mid] <= g) lo = mid; else hi = mid;
-        }
-        const int p = lo;
-        const uint32_t i = g - rbase[p];
-        const u32x4 *src = (const u32x4 *)peers[p].rows + (size_t)i * n;
-        for (int c0 = lane; c0 < n; c0 += U * tpr) {
-            u32x4 v[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int c = c0 + u * tpr;
-                if (c < n) v[u] = mw_ld16(src + c);
-            }
-            for (int k = 0; k < Kd; ++k) {
-                const mw_hit hk = h[k];
-                if (hk.le < 0) break;
-                const int64_t dst = (int64_t)base[(uint32_t)hk.le * P + p] + hk.rank;
-                if (dst >= cap) continue;
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int c = c0 + u * tpr;
-                    if (c < xc) mw_st16(out_rows + (size_t)dst * xc + c, v[u]);
-                    else if (c < n) mw_st16(out_scales + (size_t)dst * sc + (c - xc), v[u]);
-                }
-            }
-        }
-        if (lane == 0) {
-            const int32_t stok = peers[p].row_src_token[i];
-            for (int k = 0; k < Kd; ++k) {
-                const mw_hit hk = h[k];
-                if (hk.le < 0) break;
-                const int64_t dst = (int64_t)base[(uint32_t)hk.le * P + p] + hk.rank;
-                if (dst >= cap) continue;
-                out_src_peer[dst] = p;
-                out_src_token[dst] = stok;
-            }
+        const mw_hit h0 = h[0];
+        if (h0.le < 0) continue;                // slots fill from 0: nothing to deliver
+        const mw_row_rec rc = recs[g];
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (c < n) v = mw_ld16((const u32x4 *)rc.src + c);
+        for (int k = 0; k < Kd; ++k) {
+            const mw_hit hk = (k == 0) ? h0 : h[k];
+            if (hk.le < 0) break;
+            const int64_t dst = (int64_t)base[(uint32_t)hk.le * P + rc.peer] + hk.rank;
+            if (dst >= cap) continue;
+            if (c < xc) mw_st16(out_rows + (size_t)dst * xc + c, v);
+            else if (c < n) mw_st16(out_scales + (size_t)dst * sc + (c - xc), v);
+            if (c == 0) { out_src_peer[dst] = rc.peer; out_src_token[dst] = rc.src_token; }
         }
     }
 }
 
 }  // namespace
-
-static int lanes_per_row(int chunks, int U)
-{
-    int tpr = 64;
-    while (tpr < kExpandBlock && tpr * U < chunks) tpr *= 2;
-    return tpr;
-}
 
 int32_t mw_launch_unpack(mw_ctx *ctx, const mw_recv_peer *peers, int32_t P, void *out_rows,
                          float *out_scales, int64_t cap, int32_t *out_src_peer, int32_t *out_src_token,
@@ -278,24 +288,31 @@ int32_t mw_launch_unpack(mw_ctx *ctx, const mw_recv_peer *peers, int32_t P, void
     const int L = ctx->n_local, Kd = ctx->hit_slots;
     const uint32_t wpl = ((uint32_t)c.max_tokens + 31u) / 32u;
     // LDS budget of the index kernel: addressed bitmap + 2 arrays per expert of the chunk
-    const uint32_t budget_words = 12288 - 32;
+    const uint32_t budget_words = 12288 - 64;
     int Lc = (int)((budget_words - wpl) / (2 * wpl));
     if (Lc < 1) return MW_ERR_UNSUPPORTED;
     if (Lc > L) Lc = L > 0 ? L : 1;
-    const size_t lds_index = ((size_t)wpl + 2 * (size_t)Lc * wpl + 32) * sizeof(uint32_t);
-    hipLaunchKernelGGL(k_recv_index, dim3(P), dim3(kIndexBlock), lds_index, s, peers, P, ctx->d_e2r,
-                       ctx->d_local_slot, c.n_experts, c.top_k, Kd, c.my_rank, L, Lc, (uint32_t)c.max_tokens,
-                       wpl, (uint32_t)c.max_recv_rows, ctx->d_cnt, ctx->d_row_base, ctx->d_addr_cnt, ctx->d_hits,
-                       ctx->d_flags);
-
-    const int xc = (int)(ctx->x_row_bytes / 16), sc = (int)(ctx->s_row_bytes / 16);
-    constexpr int U = 4;
-    const int tpr = lanes_per_row(xc + sc, U);
-    const size_t lds_expand = ((size_t)L * P + P + 1 + 32) * sizeof(uint32_t);
-    const int grid = ctx->n_cu * 8;
-    hipLaunchKernelGGL(k_expand<U>, dim3(grid), dim3(kExpandBlock), lds_expand, s, peers, P, ctx->d_row_base,
-                       ctx->d_cnt, ctx->d_hits, Kd, L, xc, sc, tpr, (u32x4 *)out_rows, (u32x4 *)out_scales, cap,
-                       out_src_peer, out_src_token, expert_offsets, stats, ctx->d_addr_cnt, ctx->d_flags);
+    const size_t lds_index = ((size_t)wpl + 2 * (size_t)Lc * wpl + 64) * sizeof(uint32_t);
+    {
+        mw_timed tm(ctx, MW_KERNEL_RECV_INDEX, s);
+        hipLaunchKernelGGL(k_recv_index, dim3(P), dim3(kIndexBlock), lds_index, s, peers, P, ctx->d_eslot,
+                           c.n_experts, c.top_k, Kd, c.my_rank, L, Lc, (uint32_t)c.max_tokens,
+                           wpl, (uint32_t)c.max_recv_rows, (uint64_t)ctx->row_bytes, cap, ctx->d_cnt,
+                           ctx->d_row_base, ctx->d_addr_cnt, ctx->d_recs, ctx->d_hits, ctx->d_base,
+                           expert_offsets, stats, ctx->d_flags);
+    }
+    if (c.max_recv_rows > 0) {
+        const int xc = (int)(ctx->x_row_bytes / 16), sc = (int)(ctx->s_row_bytes / 16);
+        int bs, nseg;
+        mw_row_block_shape(xc + sc, &bs, &nseg);
+        uint32_t gmax = kExpandMaxRowBlocks;
+        if (const char *e = getenv("MW_TUNE_GX")) gmax = (uint32_t)atoi(e);   // TEMPORARY tuning knob
+        const uint32_t gx = (uint32_t)(c.max_recv_rows < gmax ? c.max_recv_rows : gmax);
+        mw_timed tm(ctx, MW_KERNEL_EXPAND, s);
+        hipLaunchKernelGGL(k_expand, dim3(gx, nseg), dim3(bs), 0, s, ctx->d_recs, ctx->d_hits, ctx->d_base,
+                           ctx->d_row_base, P, Kd, xc, sc, (u32x4 *)out_rows, (u32x4 *)out_scales, cap,
+                           out_src_peer, out_src_token);
+    }
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;
 }
