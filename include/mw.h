@@ -259,13 +259,12 @@ MW_API int32_t mw_get_recv_stats(mw_ctx *ctx, const mw_recv_stats *stats_dev, mw
  * call's stream, so the caller can read the kernel's own duration with
  * hipEventElapsedTime.  NULL, NULL switches the hook off (the default).
  */
-#define MW_KERNEL_PLAN_MASKS   0
-#define MW_KERNEL_PLAN_RANK    1
-#define MW_KERNEL_PLAN_GROUPS  2
-#define MW_KERNEL_PACK         3
-#define MW_KERNEL_RECV_INDEX   4
-#define MW_KERNEL_EXPAND       5
-#define MW_KERNEL_COUNT        6
+#define MW_KERNEL_PLAN_RANK    0
+#define MW_KERNEL_PLAN_GROUPS  1
+#define MW_KERNEL_PACK         2
+#define MW_KERNEL_RECV_INDEX   3
+#define MW_KERNEL_EXPAND       4
+#define MW_KERNEL_COUNT        5
 MW_API int32_t mw_ctx_set_timing_events(mw_ctx *ctx, int32_t kernel, void *ev_start, void *ev_stop);
 
 MW_API const char *mw_status_string(int32_t status);

@@ -8,7 +8,7 @@
 namespace {
 
 struct ws_layout {
-    int64_t e2r, local_slot, pos, flags, hist, smask, cnt, base, row_base, addr_cnt, recs, hits, row_map, total;
+    int64_t eslot, plan_cnt[2], plan_state[2], flags, cnt, base, row_base, addr_cnt, recs, hits, row_map, total;
 };
 
 // Derived row geometry; returns a status.
@@ -64,12 +64,11 @@ ws_layout layout(const mw_config &c, int32_t L)
     const int64_t Kd = (c.top_k < L ? c.top_k : L) > 0 ? (c.top_k < L ? c.top_k : L) : 1;
     ws_layout w;
     int64_t o = 0;
-    w.e2r = o;        o += mw_align_up(4LL * (c.n_experts > 0 ? c.n_experts : 1), A);
-    w.local_slot = o; o += mw_align_up(4LL * (c.n_experts > 0 ? c.n_experts : 1), A);
-    w.pos = o;        o += mw_align_up(4LL * (c.max_tokens > 0 ? c.max_tokens : 1), A);
+    const int64_t ntok = c.max_tokens > 0 ? c.max_tokens : 1;
+    w.eslot = o;      o += mw_align_up(4LL * (c.n_experts > 0 ? c.n_experts : 1), A);
+    for (int q = 0; q < 2; ++q) { w.plan_cnt[q] = o; o += mw_align_up(8LL * ntok, A); }
+    for (int q = 0; q < 2; ++q) { w.plan_state[q] = o; o += mw_align_up(4LL * MW_PLAN_STATE_WORDS, A); }
     w.flags = o;      o += A;
-    w.hist = o;       o += mw_align_up(4LL * MW_MAX_RANKS, A);
-    w.smask = o;      o += mw_align_up(8LL * MW_MASK_WORDS * (c.max_tokens > 0 ? c.max_tokens : 1), A);
     w.cnt = o;        o += mw_align_up(4LL * ((int64_t)L * c.n_ranks > 0 ? (int64_t)L * c.n_ranks : 1), A);
     w.base = o;       o += mw_align_up(4LL * ((int64_t)L * c.n_ranks > 0 ? (int64_t)L * c.n_ranks : 1), A);
     w.row_base = o;   o += mw_align_up(4LL * (c.n_ranks + 1), A);
@@ -121,12 +120,14 @@ MW_API int32_t mw_ctx_create(const mw_config *cfg, void *workspace_dev, int64_t 
     ctx->mask_words = (cfg->n_ranks + 63) / 64;
     ctx->x_row_bytes = xb; ctx->s_row_bytes = sb; ctx->row_bytes = xb + sb;
     char *b = (char *)workspace_dev;
-    ctx->d_e2r = (int32_t *)(b + w.e2r);
-    ctx->d_eslot = (int32_t *)(b + w.local_slot);
-    ctx->d_pos = (uint32_t *)(b + w.pos);
+    ctx->d_eslot = (int32_t *)(b + w.eslot);
+    for (int q = 0; q < 2; ++q) {
+        ctx->d_plan_cnt[q] = (uint64_t *)(b + w.plan_cnt[q]);
+        ctx->d_plan_state[q] = (uint32_t *)(b + w.plan_state[q]);
+        ctx->plan_T[q] = 0;
+    }
+    ctx->plan_parity = 0;
     ctx->d_flags = (uint32_t *)(b + w.flags);
-    ctx->d_hist = (uint32_t *)(b + w.hist);
-    ctx->d_smask = (uint64_t *)(b + w.smask);
     ctx->d_cnt = (uint32_t *)(b + w.cnt);
     ctx->d_base = (uint32_t *)(b + w.base);
     ctx->d_recs = (mw_row_rec *)(b + w.recs);
@@ -149,12 +150,13 @@ MW_API int32_t mw_ctx_create(const mw_config *cfg, void *workspace_dev, int64_t 
         slot[e] = (r << 16) | seen[r]++;      // slots stay below 65536 because E does
     }
     bool ok = true;
-    if (cfg->n_experts > 0) {
-        ok = ok && hipMemcpy(ctx->d_e2r, cfg->expert_to_rank, 4u * (size_t)cfg->n_experts, hipMemcpyHostToDevice) == hipSuccess;
+    if (cfg->n_experts > 0)
         ok = ok && hipMemcpy(ctx->d_eslot, slot.data(), 4u * (size_t)cfg->n_experts, hipMemcpyHostToDevice) == hipSuccess;
-    }
     ok = ok && hipMemset(ctx->d_flags, 0, 256) == hipSuccess;
-    ok = ok && hipMemset(ctx->d_hist, 0, 4 * MW_MAX_RANKS) == hipSuccess;
+    for (int q = 0; q < 2; ++q) {
+        ok = ok && hipMemset(ctx->d_plan_cnt[q], 0, 8u * (size_t)(cfg->max_tokens > 0 ? cfg->max_tokens : 1)) == hipSuccess;
+        ok = ok && hipMemset(ctx->d_plan_state[q], 0, 4u * MW_PLAN_STATE_WORDS) == hipSuccess;
+    }
     ok = ok && hipDeviceSynchronize() == hipSuccess;
     if (!ok) { delete ctx; return MW_ERR_HIP; }
     *out = ctx;

@@ -11,6 +11,8 @@
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+#define MW_PLAN_STATE_WORDS 264   // 256 histogram bins + kept tokens + flags (+ padding)
+
 // (local expert slot, rank among the peer's rows for that expert); le < 0 = unused slot
 struct mw_hit { int32_t le; int32_t rank; };
 
@@ -42,12 +44,12 @@ struct mw_ctx {
     int device;
     int n_cu;
     // workspace slices
-    int32_t *d_e2r;         // [E]
     int32_t *d_eslot;       // [E] (rank << 16) | slot of expert e among the experts of its rank
-    uint32_t *d_pos;        // [max_tokens] plan: predecessors of token t in (bitmap, token) order
-    uint32_t *d_flags;      // [4] 0: plan flags, 1: receive flags, 2: receive workgroups done
-    uint32_t *d_hist;       // [256] plan: rows per destination, accumulated by k_masks
-    uint64_t *d_smask;      // [max_tokens][4] plan: bitmaps in sorted (perm) order
+    uint64_t *d_plan_cnt[2];    // [max_tokens] packed per-token counters, double-buffered between plans
+    uint32_t *d_plan_state[2];  // [MW_PLAN_STATE_WORDS] rows per destination, kept tokens, flags
+    int plan_parity;            // which buffer pair the next mw_plan accumulates into
+    int plan_T[2];              // tokens whose counters in that buffer still need clearing
+    uint32_t *d_flags;      // [4] 1: receive flags, 2: receive workgroups done
     uint32_t *d_base;       // [L][R] first output row of (local expert, peer)
     mw_row_rec *d_recs;     // [max_recv_rows]
     uint32_t *d_cnt;        // [L][R] rows of peer p delivered to local expert le

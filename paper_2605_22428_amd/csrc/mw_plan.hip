@@ -7,86 +7,116 @@
 // C(64,8) sets at EP=64/top-8); the accounting is Section 1's "one copy however many
 // destinations" against one copy per destination.
 //
-// Three launches on the caller's stream, no host synchronisation:
-//   k_masks   one lane per token, ORs the K rank bits into four 64-bit words; wavefront
-//             ballots + popcounts turn 64 tokens' bitmaps into per-rank counts.
-//   k_rank    position of every kept token in (bitmap, token) order by counting its
-//             predecessors.  A lane owns one token and walks a slice of all tokens whose
-//             bitmaps are wave-uniform (scalar loads), so a step is a handful of 64-bit
-//             compares; slices are spread over the whole chip and combined with integer
-//             atomic adds (a sum, so the result does not depend on arrival order).
-//             For the batch sizes of a dispatch (<= 8k tokens) this beats a multi-pass
-//             radix sort of 256-bit keys, which would be launch- and barrier-bound.
-//   k_groups  one workgroup: scatter perm, mark bitmap changes, scan them into group ids,
-//             write descriptors and statistics.
+// Two launches on the caller's stream, no host synchronisation:
+//   k_rank    A workgroup owns 256 tokens and a slice of all tokens.  It builds the
+//             bitmaps of both from the top-k ids (one lane per token, K rank bits ORed
+//             into four 64-bit words; the slice goes to LDS), then every lane counts, over
+//             the slice, the tokens whose (bitmap, index) is smaller than its own, and how
+//             many carry an equal bitmap before / at-or-after it.  Slices are spread over
+//             the whole chip and combined with one 64-bit integer atomic add per lane (a
+//             sum, so the result does not depend on arrival order).  For the batch sizes
+//             of a dispatch (<= 8k tokens) this beats a multi-pass radix sort of 256-bit
+//             keys, which would be launch- and barrier-bound.  The workgroups of slice 0
+//             also write the bitmaps out and turn 64 tokens' bitmaps into per-rank counts
+//             with wavefront ballots and popcounts.
+//   k_groups  Workgroup b owns packed rows [256 b, 256 b + 256): it finds their tokens
+//             from the counts (predecessor count = packed row), writes perm, ranks the
+//             group starts (tokens with no equal bitmap before them) and writes their
+//             descriptors; a group's row count is the number of equal bitmaps.  Writing is
+//             spread over many workgroups because one CU retires only about one cache line
+//             of scattered stores per cycle.
+// The count and histogram buffers are double-buffered between consecutive plans: a plan
+// clears the buffers the previous plan used, so no extra clearing launch is needed.
 #include "mw_internal.h"
 
 namespace {
 
-constexpr int kRankBlock = 256;
-constexpr int kGroupsBlock = 1024;
+constexpr int kBlock = 256;
+constexpr uint64_t kField = 0x1fffffull;      // 21-bit fields of the packed counter
+constexpr int kPsKept = 256, kPsFlags = 257;  // plan state words after the 256 histogram bins
 
-__global__ __launch_bounds__(256) void k_masks(const int32_t *__restrict__ topk, int T, int K,
-                                               const int32_t *__restrict__ e2r, int E,
-                                               uint64_t *__restrict__ mask, uint32_t *__restrict__ pos,
-                                               uint32_t *__restrict__ hist, uint32_t *__restrict__ flags)
+// Destination bitmap of one token (Section 4.1): ids are fetched in independent batches.
+__device__ __forceinline__ void token_mask(const int32_t *__restrict__ row, int K,
+                                           const int32_t *__restrict__ eslot, int E, uint64_t m[MW_MASK_WORDS],
+                                           bool &bad)
 {
-    const int t = blockIdx.x * blockDim.x + threadIdx.x;
-    const int lane = threadIdx.x & 63;
-    uint64_t m[MW_MASK_WORDS] = {0, 0, 0, 0};
-    bool bad = false;
-    if (t < T) {
-        const int32_t *row = topk + (size_t)t * K;
-        for (int j = 0; j < K; ++j) {
-            const int32_t e = row[j];
-            if (e == -1) continue;
-            if ((uint32_t)e >= (uint32_t)E) { bad = true; continue; }
-            const int r = e2r[e];
+#pragma unroll
+    for (int q = 0; q < MW_MASK_WORDS; ++q) m[q] = 0;
+    for (int j0 = 0; j0 < K; j0 += 8) {
+        int32_t e[8], s[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) e[u] = (j0 + u < K) ? row[j0 + u] : -1;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const bool ok = (uint32_t)e[u] < (uint32_t)E;
+            bad |= (e[u] != -1 && !ok);
+            s[u] = ok ? eslot[e[u]] : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (s[u] < 0) continue;
+            const int r = s[u] >> 16;
             const uint64_t bit = 1ull << (r & 63);
             const int w = r >> 6;
 #pragma unroll
             for (int q = 0; q < MW_MASK_WORDS; ++q) m[q] |= (w == q) ? bit : 0ull;
         }
-        uint64_t *o = mask + (size_t)t * MW_MASK_WORDS;
-#pragma unroll
-        for (int q = 0; q < MW_MASK_WORDS; ++q) o[q] = m[q];
-        pos[t] = 0;
-        if (bad) atomicOr(flags, MW_FLAG_BAD_EXPERT);
-    }
-    // rows per destination: a wavefront ballot of bit b over 64 tokens, popcounted, is the
-    // number of those tokens that name rank 64*q + b; lane b keeps it and adds it once.
-#pragma unroll
-    for (int q = 0; q < MW_MASK_WORDS; ++q) {
-        if (__ballot(m[q] != 0) == 0) continue;      // wave-uniform
-        uint32_t mine = 0;
-        for (int b = 0; b < 64; ++b) {
-            const uint32_t c = (uint32_t)__popcll(__ballot((m[q] >> b) & 1ull));
-            if (lane == b) mine = c;
-        }
-        if (mine) atomicAdd(&hist[q * 64 + lane], mine);
     }
 }
 
-// pos[t] += #{u in this block's slice : (mask[u], u) < (mask[t], t)}.  Tokens with an
-// empty bitmap compare below every kept token; k_groups subtracts their number.
+// cnt[t] += (#smaller | #equal before << 21 | #equal at-or-after << 42) over this slice, where
+// "smaller" means (bitmap, index) < (bitmap[t], t).  Empty bitmaps compare below every kept
+// token; k_groups subtracts their number.  A kept token always has a non-zero third field.
 template <int W>
-__global__ __launch_bounds__(kRankBlock) void k_rank(const uint64_t *__restrict__ mask, int T, int slice,
-                                                     uint32_t *__restrict__ pos)
+__global__ __launch_bounds__(kBlock) void k_rank(const int32_t *__restrict__ topk, int T, int K,
+                                                 const int32_t *__restrict__ eslot, int E, int slice,
+                                                 uint64_t *__restrict__ mask_out,
+                                                 unsigned long long *__restrict__ cnt,
+                                                 uint32_t *__restrict__ pstate)
 {
-    const int t = blockIdx.x * kRankBlock + threadIdx.x;
-    const int u0 = blockIdx.y * slice;
-    const int u1 = min(u0 + slice, T);
-    uint64_t m[W];
-    bool any = false;
+    extern __shared__ uint64_t smask[];           // [slice][W]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int u0 = blockIdx.y * slice, u1 = min(u0 + slice, T);
+    bool bad = false, bad_slice = false;
+    for (int u = u0 + tid; u < u1; u += kBlock) {
+        uint64_t q[MW_MASK_WORDS];
+        token_mask(topk + (size_t)u * K, K, eslot, E, q, bad_slice);
 #pragma unroll
-    for (int w = 0; w < W; ++w) {
-        m[w] = (t < T) ? mask[(size_t)t * MW_MASK_WORDS + w] : 0ull;
-        any |= (m[w] != 0);
+        for (int w = 0; w < W; ++w) smask[(size_t)(u - u0) * W + w] = q[w];
     }
-    uint32_t c = 0;
+    const int t = blockIdx.x * kBlock + tid;
+    uint64_t m[MW_MASK_WORDS] = {0, 0, 0, 0};
+    if (t < T) token_mask(topk + (size_t)t * K, K, eslot, E, m, bad);
+    const bool any = (m[0] | m[1] | m[2] | m[3]) != 0;
+
+    if (blockIdx.y == 0) {
+        if (t < T) {
+            uint64_t *o = mask_out + (size_t)t * MW_MASK_WORDS;
+#pragma unroll
+            for (int q = 0; q < MW_MASK_WORDS; ++q) o[q] = m[q];
+            if (bad) atomicOr(&pstate[kPsFlags], MW_FLAG_BAD_EXPERT);
+        }
+        const uint32_t kept = (uint32_t)__popcll(__ballot(any));
+        if (lane == 0 && kept) atomicAdd(&pstate[kPsKept], kept);
+        // rows per destination: a wavefront ballot of bit b over 64 tokens, popcounted, is the
+        // number of those tokens that name rank 64*q + b; lane b keeps it and adds it once.
+#pragma unroll
+        for (int q = 0; q < MW_MASK_WORDS; ++q) {
+            if (__ballot(m[q] != 0) == 0) continue;      // wave-uniform
+            uint32_t mine = 0;
+            for (int b = 0; b < 64; ++b) {
+                const uint32_t c = (uint32_t)__popcll(__ballot((m[q] >> b) & 1ull));
+                if (lane == b) mine = c;
+            }
+            if (mine) atomicAdd(&pstate[q * 64 + lane], mine);
+        }
+    }
+    __syncthreads();
+
+    uint32_t c_lt = 0, c_eqb = 0, c_eqa = 0;
 #pragma unroll 4
     for (int u = u0; u < u1; ++u) {
-        const uint64_t *q = mask + (size_t)u * MW_MASK_WORDS;   // wave-uniform address
+        const uint64_t *q = smask + (size_t)(u - u0) * W;      // same address in every lane: LDS broadcast
         bool lt = false, eq = true;
 #pragma unroll
         for (int w = W - 1; w >= 0; --w) {
@@ -94,117 +124,94 @@ __global__ __launch_bounds__(kRankBlock) void k_rank(const uint64_t *__restrict_
             lt = lt || (eq && qw < m[w]);
             eq = eq && (qw == m[w]);
         }
-        lt = lt || (eq && u < t);
-        c += lt ? 1u : 0u;
+        c_lt += lt ? 1u : 0u;
+        c_eqb += (eq && u < t) ? 1u : 0u;
+        c_eqa += (eq && u >= t) ? 1u : 0u;
     }
-    if (any && c) atomicAdd(&pos[t], c);
+    if (any) {
+        const unsigned long long add = (unsigned long long)(c_lt + c_eqb) | ((unsigned long long)c_eqb << 21) |
+                                       ((unsigned long long)c_eqa << 42);
+        if (add) atomicAdd(&cnt[t], add);
+    }
 }
 
-__device__ __forceinline__ bool mask_equal(const uint64_t *a, const uint64_t *b)
+__global__ __launch_bounds__(kBlock) void k_groups(const uint64_t *__restrict__ mask, int T, uint64_t row_bytes,
+                                                   const unsigned long long *__restrict__ cnt,
+                                                   uint32_t *__restrict__ pstate,
+                                                   unsigned long long *__restrict__ cnt_other, int T_other,
+                                                   uint32_t *__restrict__ pstate_other,
+                                                   int32_t *__restrict__ perm, mw_group_desc *__restrict__ desc,
+                                                   mw_send_stats *__restrict__ stats)
 {
-    return a[0] == b[0] && a[1] == b[1] && a[2] == b[2] && a[3] == b[3];
-}
-
-// One workgroup.  Loads are batched (independent, unrolled) and the sorted bitmaps go
-// through a scratch array so that every phase costs one memory round trip, not one per row.
-__global__ __launch_bounds__(kGroupsBlock) void k_groups(const uint64_t *__restrict__ mask,
-                                                         const uint32_t *__restrict__ pos, int T,
-                                                         uint64_t row_bytes, int32_t *__restrict__ perm,
-                                                         uint64_t *__restrict__ smask, mw_group_desc *desc,
-                                                         mw_send_stats *stats, uint32_t *hist, uint32_t *flags)
-{
+    __shared__ int32_t tok[kBlock];
     __shared__ uint32_t scratch[17];
     const int tid = threadIdx.x;
+    const uint32_t N = min(pstate[kPsKept], (uint32_t)T), n_empty = (uint32_t)T - N;
+    const uint32_t i0 = blockIdx.x * kBlock;
 
-    // kept tokens; total destinations from the histogram k_masks accumulated
-    uint32_t kept = 0;
+    // every workgroup walks all tokens' counters (coalesced): which of them land in its rows,
+    // how many groups start before its first row, how many groups there are
+    uint32_t starts_before = 0, starts_total = 0;
 #pragma unroll 4
-    for (int t = tid; t < T; t += kGroupsBlock) {
+    for (int t = tid; t < T; t += kBlock) {
+        const unsigned long long c = cnt[t];
+        if ((c >> 42) == 0) continue;                         // empty bitmap
+        const uint32_t p = (uint32_t)(c & kField) - n_empty;  // packed row of token t
+        const uint32_t st = ((c >> 21) & kField) == 0 ? 1u : 0u;
+        starts_total += st;
+        starts_before += (st && p < i0) ? 1u : 0u;
+        if (p - i0 < (uint32_t)kBlock && p < N) tok[p - i0] = t;
+    }
+    uint32_t g_base, G;
+    mw_block_exscan(starts_before, scratch, &g_base);
+    mw_block_exscan(starts_total, scratch, &G);                // ends with a barrier: tok[] is complete
+
+    // clear what the previous plan used, for the plan after this one
+    for (int z = blockIdx.x * kBlock + tid; z < T_other; z += gridDim.x * kBlock) cnt_other[z] = 0;
+
+    const uint32_t i = i0 + tid;
+    uint32_t st = 0;
+    int32_t t = 0;
+    unsigned long long c = 0;
+    if (i < N) {
+        t = tok[tid];
+        perm[i] = t;
+        c = cnt[t];
+        st = ((c >> 21) & kField) == 0 ? 1u : 0u;
+    }
+    uint32_t local_total;
+    const uint32_t g = g_base + mw_block_exscan(st, scratch, &local_total);
+    if (st) {
         const uint64_t *m = mask + (size_t)t * MW_MASK_WORDS;
-        kept += (m[0] | m[1] | m[2] | m[3]) ? 1u : 0u;
-    }
-    uint32_t dests = 0;
-    for (int r = tid; r < MW_MAX_RANKS; r += kGroupsBlock) {
-        const uint32_t h = hist[r];
-        stats->rows_per_dest[r] = h;
-        dests += h;
-        hist[r] = 0;           // ready for the next plan
-    }
-    uint32_t N, D;
-    mw_block_exscan(kept, scratch, &N);
-    mw_block_exscan(dests, scratch, &D);
-    const uint32_t n_empty = (uint32_t)T - N;
-
-    // perm and the bitmaps in sorted order: token t goes to its predecessor count among kept tokens
-#pragma unroll 4
-    for (int t = tid; t < T; t += kGroupsBlock) {
-        const uint64_t *m = mask + (size_t)t * MW_MASK_WORDS;
-        const uint64_t m0 = m[0], m1 = m[1], m2 = m[2], m3 = m[3];
-        const uint32_t i = pos[t] - n_empty;
-        if ((m0 | m1 | m2 | m3) && i < N) {
-            perm[i] = t;
-            uint64_t *o = smask + (size_t)i * MW_MASK_WORDS;
-            o[0] = m0; o[1] = m1; o[2] = m2; o[3] = m3;
-        }
-    }
-    __syncthreads();
-
-    // group starts: row i opens a group when its bitmap differs from row i-1's
-    const uint32_t per = (N + kGroupsBlock - 1) / kGroupsBlock;
-    const uint32_t i0 = min((uint32_t)tid * per, N), i1 = min(i0 + per, N);
-    uint64_t p0 = 0, p1 = 0, p2 = 0, p3 = 0;                      // bitmap of row i0 - 1, if there is one
-    bool have_prev = false;
-    if (i0 > 0 && i0 < i1) {
-        const uint64_t *q = smask + (size_t)(i0 - 1) * MW_MASK_WORDS;
-        p0 = q[0]; p1 = q[1]; p2 = q[2]; p3 = q[3];
-        have_prev = true;
-    }
-    uint32_t starts = 0;
-    {
-        uint64_t a0 = p0, a1 = p1, a2 = p2, a3 = p3;
-        bool hp = have_prev;
-#pragma unroll 4
-        for (uint32_t i = i0; i < i1; ++i) {
-            const uint64_t *q = smask + (size_t)i * MW_MASK_WORDS;
-            const uint64_t c0 = q[0], c1 = q[1], c2 = q[2], c3 = q[3];
-            starts += (!hp || c0 != a0 || c1 != a1 || c2 != a2 || c3 != a3) ? 1u : 0u;
-            a0 = c0; a1 = c1; a2 = c2; a3 = c3; hp = true;
-        }
-    }
-    uint32_t G;
-    uint32_t g = mw_block_exscan(starts, scratch, &G);
-    {
-        uint64_t a0 = p0, a1 = p1, a2 = p2, a3 = p3;
-        bool hp = have_prev;
-        for (uint32_t i = i0; i < i1; ++i) {
-            const uint64_t *q = smask + (size_t)i * MW_MASK_WORDS;
-            const uint64_t c0 = q[0], c1 = q[1], c2 = q[2], c3 = q[3];
-            if (!hp || c0 != a0 || c1 != a1 || c2 != a2 || c3 != a3) {
-                mw_group_desc d;
-                d.mask[0] = c0; d.mask[1] = c1; d.mask[2] = c2; d.mask[3] = c3;
-                d.row_offset = i; d.row_count = 0;
-                d.n_dest = (uint32_t)(__popcll(c0) + __popcll(c1) + __popcll(c2) + __popcll(c3));
-                d.reserved0 = 0;
-                desc[g++] = d;
-            }
-            a0 = c0; a1 = c1; a2 = c2; a3 = c3; hp = true;
-        }
-    }
-    __syncthreads();
-#pragma unroll 4
-    for (uint32_t k = tid; k < G; k += kGroupsBlock) {
-        const uint32_t next = (k + 1 < G) ? desc[k + 1].row_offset : N;
-        desc[k].row_count = next - desc[k].row_offset;
+        mw_group_desc d;
+        uint32_t nd = 0;
+#pragma unroll
+        for (int w = 0; w < MW_MASK_WORDS; ++w) { d.mask[w] = m[w]; nd += (uint32_t)__popcll(m[w]); }
+        d.row_offset = i;
+        d.row_count = (uint32_t)((c >> 42) & kField);          // equal bitmaps, this token included
+        d.n_dest = nd;
+        d.reserved0 = 0;
+        desc[g] = d;
     }
 
-    if (tid == 0) {
-        stats->n_rows = N;
-        stats->n_groups = G;
-        stats->multicast_bytes = (uint64_t)N * row_bytes;
-        stats->unicast_bytes = (uint64_t)D * row_bytes;
-        stats->error_flags = flags[0];
-        stats->reserved0 = 0;
-        flags[0] = 0;      // ready for the next plan
+    if (blockIdx.x == 0) {
+        uint32_t dests = 0;
+        for (int r = tid; r < MW_MAX_RANKS; r += kBlock) {
+            const uint32_t h = pstate[r];
+            stats->rows_per_dest[r] = h;
+            dests += h;
+        }
+        uint32_t D;
+        mw_block_exscan(dests, scratch, &D);
+        if (tid == 0) {
+            stats->n_rows = N;
+            stats->n_groups = G;
+            stats->multicast_bytes = (uint64_t)N * row_bytes;
+            stats->unicast_bytes = (uint64_t)D * row_bytes;
+            stats->error_flags = pstate[kPsFlags];
+            stats->reserved0 = 0;
+        }
+        for (int r = tid; r < MW_PLAN_STATE_WORDS; r += kBlock) pstate_other[r] = 0;
     }
 }
 
@@ -235,33 +242,38 @@ int32_t mw_launch_plan(mw_ctx *ctx, const int32_t *topk, int32_t T, uint64_t *ma
                        mw_group_desc *desc, mw_send_stats *stats, hipStream_t s)
 {
     const int K = ctx->cfg.top_k, E = ctx->cfg.n_experts;
+    const int cur = ctx->plan_parity, oth = cur ^ 1;
+    unsigned long long *cnt = (unsigned long long *)ctx->d_plan_cnt[cur];
+    unsigned long long *cnt_o = (unsigned long long *)ctx->d_plan_cnt[oth];
+    const int tb = (T + kBlock - 1) / kBlock;
     if (T > 0) {
-        {
-            mw_timed tm(ctx, MW_KERNEL_PLAN_MASKS, s);
-            hipLaunchKernelGGL(k_masks, dim3((T + 255) / 256), dim3(256), 0, s, topk, T, K, ctx->d_e2r, E, mask,
-                               ctx->d_pos, ctx->d_hist, ctx->d_flags);
-        }
-        // split the predecessor walk into slices so that about 4 workgroups land on every CU
-        const int tb = (T + kRankBlock - 1) / kRankBlock;
+        // split the predecessor walk into slices so that about 4 workgroups land on every CU;
+        // a slice's bitmaps must fit in LDS
         int ns = (4 * ctx->n_cu + tb - 1) / tb;
         if (ns < 1) ns = 1;
         int slice = (T + ns - 1) / ns;
         if (slice < 64) slice = 64;
+        if (slice > 1024) slice = 1024;
         ns = (T + slice - 1) / slice;
-        const dim3 grid(tb, ns), block(kRankBlock);
+        const dim3 grid(tb, ns), block(kBlock);
+        const int W = ctx->mask_words;
+        const size_t lds = (size_t)slice * W * sizeof(uint64_t);
         mw_timed tm(ctx, MW_KERNEL_PLAN_RANK, s);
-        switch (ctx->mask_words) {
-        case 1: hipLaunchKernelGGL(k_rank<1>, grid, block, 0, s, mask, T, slice, ctx->d_pos); break;
-        case 2: hipLaunchKernelGGL(k_rank<2>, grid, block, 0, s, mask, T, slice, ctx->d_pos); break;
-        case 3: hipLaunchKernelGGL(k_rank<3>, grid, block, 0, s, mask, T, slice, ctx->d_pos); break;
-        default: hipLaunchKernelGGL(k_rank<4>, grid, block, 0, s, mask, T, slice, ctx->d_pos); break;
+        switch (W) {
+        case 1: hipLaunchKernelGGL(k_rank<1>, grid, block, lds, s, topk, T, K, ctx->d_eslot, E, slice, mask, cnt, ctx->d_plan_state[cur]); break;
+        case 2: hipLaunchKernelGGL(k_rank<2>, grid, block, lds, s, topk, T, K, ctx->d_eslot, E, slice, mask, cnt, ctx->d_plan_state[cur]); break;
+        case 3: hipLaunchKernelGGL(k_rank<3>, grid, block, lds, s, topk, T, K, ctx->d_eslot, E, slice, mask, cnt, ctx->d_plan_state[cur]); break;
+        default: hipLaunchKernelGGL(k_rank<4>, grid, block, lds, s, topk, T, K, ctx->d_eslot, E, slice, mask, cnt, ctx->d_plan_state[cur]); break;
         }
     }
     {
         mw_timed tm(ctx, MW_KERNEL_PLAN_GROUPS, s);
-        hipLaunchKernelGGL(k_groups, dim3(1), dim3(kGroupsBlock), 0, s, mask, ctx->d_pos, T,
-                           (uint64_t)ctx->row_bytes, perm, ctx->d_smask, desc, stats, ctx->d_hist, ctx->d_flags);
+        hipLaunchKernelGGL(k_groups, dim3(tb > 0 ? tb : 1), dim3(kBlock), 0, s, mask, T, (uint64_t)ctx->row_bytes, cnt,
+                           ctx->d_plan_state[cur], cnt_o, ctx->plan_T[oth], ctx->d_plan_state[oth], perm, desc, stats);
     }
+    ctx->plan_T[oth] = 0;        // cleared by this plan
+    ctx->plan_T[cur] = T;        // to be cleared by the next one
+    ctx->plan_parity = oth;
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;
 }
