@@ -264,7 +264,9 @@ MW_API int32_t mw_get_recv_stats(mw_ctx *ctx, const mw_recv_stats *stats_dev, mw
 #define MW_KERNEL_PACK         2
 #define MW_KERNEL_RECV_INDEX   3
 #define MW_KERNEL_EXPAND       4
-#define MW_KERNEL_COUNT        5
+#define MW_KERNEL_AG_PACK      5   /* mw_pack_allgather's copy */
+#define MW_KERNEL_AG_GATHER    6   /* mw_unpack_allgather's shard assembly */
+#define MW_KERNEL_COUNT        7
 MW_API int32_t mw_ctx_set_timing_events(mw_ctx *ctx, int32_t kernel, void *ev_start, void *ev_stop);
 
 MW_API const char *mw_status_string(int32_t status);

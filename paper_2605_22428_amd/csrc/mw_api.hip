@@ -210,7 +210,7 @@ MW_API int32_t mw_pack_allgather(mw_ctx *ctx, const void *shard_dev, int64_t sha
     if (shard_bytes == 0) return MW_OK;
     if (!shard_dev || !send_buf_dev || (((uintptr_t)shard_dev | (uintptr_t)send_buf_dev) & 15u))
         return MW_ERR_INVALID_ARG;
-    return mw_launch_copy(send_buf_dev, shard_dev, shard_bytes, (hipStream_t)stream);
+    return mw_launch_copy(ctx, send_buf_dev, shard_dev, shard_bytes, (hipStream_t)stream);
 }
 
 MW_API int32_t mw_unpack(mw_ctx *ctx, const mw_recv_peer *peers_dev, int32_t n_peers, void *out_rows_dev,
@@ -266,7 +266,7 @@ MW_API int32_t mw_copy_bytes(void *dst_dev, const void *src_dev, int64_t n_bytes
     if (n_bytes % 16 != 0) return MW_ERR_UNSUPPORTED;
     if (n_bytes == 0) return MW_OK;
     if (!dst_dev || !src_dev || (((uintptr_t)dst_dev | (uintptr_t)src_dev) & 15u)) return MW_ERR_INVALID_ARG;
-    return mw_launch_copy(dst_dev, src_dev, n_bytes, (hipStream_t)stream);
+    return mw_launch_copy(nullptr, dst_dev, src_dev, n_bytes, (hipStream_t)stream);
 }
 
 MW_API int32_t mw_get_send_stats(mw_ctx *ctx, const mw_send_stats *stats_dev, mw_send_stats *host_out, void *stream)

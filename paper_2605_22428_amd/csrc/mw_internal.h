@@ -5,7 +5,6 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-#include <stdlib.h>
 
 #include "mw.h"
 
@@ -24,7 +23,6 @@ struct mw_row_rec { const void *src; int32_t src_token; int32_t peer; };   // 16
 static inline void mw_row_block_shape(int chunks, int *bs, int *nseg)
 {
     int b = (chunks + 63) / 64 * 64;
-    if (const char *e = getenv("MW_TUNE_BS")) b = atoi(e);   // TEMPORARY tuning knob
     if (b > 1024) b = 1024;
     if (b < 64) b = 64;
     *bs = b;
@@ -128,7 +126,7 @@ int32_t mw_launch_unpack(mw_ctx *ctx, const mw_recv_peer *peers, int32_t P, void
                          int64_t *expert_offsets, mw_recv_stats *stats, hipStream_t s);
 int32_t mw_launch_plan_allgather(mw_ctx *ctx, int64_t shard_bytes, mw_group_desc *desc,
                                  mw_send_stats *stats, hipStream_t s);
-int32_t mw_launch_copy(void *dst, const void *src, int64_t n_bytes, hipStream_t s);
+int32_t mw_launch_copy(mw_ctx *ctx, void *dst, const void *src, int64_t n_bytes, hipStream_t s);
 int32_t mw_launch_gather_shards(mw_ctx *ctx, const void *const *shards, int64_t shard_bytes, void *out,
                                 hipStream_t s);
 int32_t mw_launch_sim_deliver(mw_ctx *ctx, const mw_group_desc *desc, const mw_send_stats *stats,

@@ -75,13 +75,18 @@ int32_t mw_launch_pack(mw_ctx *ctx, const void *x, const float *scales, const in
     return MW_OK;
 }
 
-int32_t mw_launch_copy(void *dst, const void *src, int64_t n_bytes, hipStream_t s)
+int32_t mw_launch_copy(mw_ctx *ctx, void *dst, const void *src, int64_t n_bytes, hipStream_t s)
 {
     const int64_t n_chunks = n_bytes / 16;
     if (n_chunks == 0) return MW_OK;
     const int64_t grid = (n_chunks + 255) / 256;
     if (grid > 0x7fffffffLL) return MW_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(k_copy, dim3((uint32_t)grid), dim3(256), 0, s, (const u32x4 *)src, (u32x4 *)dst, n_chunks);
+    if (ctx) {
+        mw_timed tm(ctx, MW_KERNEL_AG_PACK, s);
+        hipLaunchKernelGGL(k_copy, dim3((uint32_t)grid), dim3(256), 0, s, (const u32x4 *)src, (u32x4 *)dst, n_chunks);
+    } else {
+        hipLaunchKernelGGL(k_copy, dim3((uint32_t)grid), dim3(256), 0, s, (const u32x4 *)src, (u32x4 *)dst, n_chunks);
+    }
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;
 }
@@ -93,8 +98,11 @@ int32_t mw_launch_gather_shards(mw_ctx *ctx, const void *const *shards, int64_t 
     if (shard_chunks == 0) return MW_OK;
     const int64_t gx = (shard_chunks + 255) / 256;
     if (gx > 0x7fffffffLL) return MW_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(k_gather_shards, dim3((uint32_t)gx, ctx->cfg.n_ranks), dim3(256), 0, s,
-                       (const u32x4 *const *)shards, shard_chunks, (u32x4 *)out);
+    {
+        mw_timed tm(ctx, MW_KERNEL_AG_GATHER, s);
+        hipLaunchKernelGGL(k_gather_shards, dim3((uint32_t)gx, ctx->cfg.n_ranks), dim3(256), 0, s,
+                           (const u32x4 *const *)shards, shard_chunks, (u32x4 *)out);
+    }
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;
 }

@@ -305,9 +305,7 @@ int32_t mw_launch_unpack(mw_ctx *ctx, const mw_recv_peer *peers, int32_t P, void
         const int xc = (int)(ctx->x_row_bytes / 16), sc = (int)(ctx->s_row_bytes / 16);
         int bs, nseg;
         mw_row_block_shape(xc + sc, &bs, &nseg);
-        uint32_t gmax = kExpandMaxRowBlocks;
-        if (const char *e = getenv("MW_TUNE_GX")) gmax = (uint32_t)atoi(e);   // TEMPORARY tuning knob
-        const uint32_t gx = (uint32_t)(c.max_recv_rows < gmax ? c.max_recv_rows : gmax);
+        const uint32_t gx = (uint32_t)(c.max_recv_rows < kExpandMaxRowBlocks ? c.max_recv_rows : kExpandMaxRowBlocks);
         mw_timed tm(ctx, MW_KERNEL_EXPAND, s);
         hipLaunchKernelGGL(k_expand, dim3(gx, nseg), dim3(bs), 0, s, ctx->d_recs, ctx->d_hits, ctx->d_base,
                            ctx->d_row_base, P, Kd, xc, sc, (u32x4 *)out_rows, (u32x4 *)out_scales, cap,
