@@ -15,8 +15,18 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 // (local expert slot, rank among the peer's rows for that expert); le < 0 = unused slot
 struct mw_hit { int32_t le; int32_t rank; };
 
-// One received row as the expander needs it: where it lies, its source token, its peer.
-struct mw_row_rec { const void *src; int32_t src_token; int32_t peer; };   // 16 bytes
+// One received row as the expander needs it, in one 32-byte record: where it lies, its
+// source token and peer, how many local experts it goes to and the first of them.  Further
+// (expert slot, rank) pairs are in the row's hit slots 1 .. n_hits - 1.
+struct mw_row_rec {
+    const void *src;
+    int32_t src_token;
+    int32_t peer;
+    int32_t n_hits;     // 0: nothing to deliver
+    int32_t le0;        // first local expert slot
+    int32_t rank0;      // rank among the peer's rows for that expert
+    int32_t reserved0;
+};
 
 // Workgroup shape of the row movers: one 16-byte chunk per lane, a row of `chunks`
 // chunks is covered by `nseg` workgroups of `bs` lanes (bs a multiple of 64, <= 1024).

@@ -110,13 +110,14 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
     for (uint32_t i = tid; i < n_rows; i += nthr) {
         mw_hit *h = hits + (size_t)(rb + i) * Kd;
         int nk = 0;
+        mw_row_rec rec = {nullptr, 0, p, 0, 0, 0, 0};
         if ((addr[i >> 5] >> (i & 31)) & 1u) {
             const uint32_t s = (uint32_t)pr.row_src_token[i];
             if (s >= max_tokens) {
                 err |= MW_FLAG_BAD_SRC_TOKEN;
             } else {
                 const int32_t *tk = pr.row_topk + (size_t)i * K;
-                int f[8];                                   // first eight experts found (dedup in registers)
+                int f[8] = {0, 0, 0, 0, 0, 0, 0, 0};          // first eight experts found (dedup in registers)
                 for (int j0 = 0; j0 < K; j0 += 8) {
                     int32_t e[8], q[8];
 #pragma unroll
@@ -142,9 +143,13 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
                     }
                 }
                 if (nk == 0) err |= MW_FLAG_NO_LOCAL_EXPERT;
-                recs[rb + i] = mw_row_rec{(const char *)pr.rows + (size_t)i * row_bytes, (int32_t)s, p};
+                rec.src = (const char *)pr.rows + (size_t)i * row_bytes;
+                rec.src_token = (int32_t)s;
+                rec.n_hits = nk;
+                rec.le0 = f[0];
             }
         }
+        recs[rb + i] = rec;
         for (int k = nk; k < Kd; ++k) h[k] = mw_hit{-1, 0};
     }
 
@@ -197,7 +202,9 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
                 const int l = le - le0;
                 if (l < 0 || l >= lc) continue;
                 const uint32_t wi = (uint32_t)l * wpl + (s >> 5);
-                h[k].rank = (int32_t)(pre[wi] - pre[(uint32_t)l * wpl] + __popc(bits[wi] & ((1u << (s & 31)) - 1u)));
+                const int32_t rk = (int32_t)(pre[wi] - pre[(uint32_t)l * wpl] + __popc(bits[wi] & ((1u << (s & 31)) - 1u)));
+                if (k == 0) recs[rb + i].rank0 = rk;
+                else h[k].rank = rk;
             }
         }
         __syncthreads();
@@ -249,7 +256,10 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
     }
 }
 
-// blockIdx.y selects a segment of blockDim.x chunks of the row; blockIdx.x walks rows.
+// blockIdx.y selects a segment of blockDim.x chunks of the row; blockIdx.x walks rows.  All
+// index reads are wave-uniform.  The row's record is fetched first and alone decides the
+// payload load, which is issued before anything else is looked up: the output position
+// (one small table read) resolves while the payload is in flight.
 __global__ __launch_bounds__(1024) void k_expand(
     const mw_row_rec *__restrict__ recs, const mw_hit *__restrict__ hits, const uint32_t *__restrict__ base,
     const uint32_t *__restrict__ row_base, int P, int Kd, int xc, int sc,
@@ -260,20 +270,21 @@ __global__ __launch_bounds__(1024) void k_expand(
     const int n = xc + sc;
     const int c = blockIdx.y * blockDim.x + threadIdx.x;
     for (uint32_t g = blockIdx.x; g < m_total; g += gridDim.x) {
-        const mw_hit *h = hits + (size_t)g * Kd;
-        const mw_hit h0 = h[0];
-        if (h0.le < 0) continue;                // slots fill from 0: nothing to deliver
         const mw_row_rec rc = recs[g];
+        if (rc.n_hits == 0) continue;
         u32x4 v = {0u, 0u, 0u, 0u};
         if (c < n) v = mw_ld16((const u32x4 *)rc.src + c);
-        for (int k = 0; k < Kd; ++k) {
-            const mw_hit hk = (k == 0) ? h0 : h[k];
-            if (hk.le < 0) break;
-            const int64_t dst = (int64_t)base[(uint32_t)hk.le * P + rc.peer] + hk.rank;
-            if (dst >= cap) continue;
-            if (c < xc) mw_st16(out_rows + (size_t)dst * xc + c, v);
-            else if (c < n) mw_st16(out_scales + (size_t)dst * sc + (c - xc), v);
-            if (c == 0) { out_src_peer[dst] = rc.peer; out_src_token[dst] = rc.src_token; }
+        int le = rc.le0, rank = rc.rank0;
+        for (int k = 0;;) {
+            const int64_t dst = (int64_t)base[(uint32_t)le * P + rc.peer] + rank;
+            if (dst < cap) {
+                if (c < xc) mw_st16(out_rows + (size_t)dst * xc + c, v);
+                else if (c < n) mw_st16(out_scales + (size_t)dst * sc + (c - xc), v);
+                if (c == 0) { out_src_peer[dst] = rc.peer; out_src_token[dst] = rc.src_token; }
+            }
+            if (++k >= rc.n_hits) break;
+            const mw_hit hk = hits[(size_t)g * Kd + k];
+            le = hk.le; rank = hk.rank;
         }
     }
 }
