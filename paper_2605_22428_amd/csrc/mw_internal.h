@@ -97,6 +97,21 @@ static inline int64_t mw_align_up(int64_t v, int64_t a) { return (v + a - 1) / a
 // the small, reused index arrays.
 __device__ __forceinline__ u32x4 mw_ld16(const u32x4 *p) { return __builtin_nontemporal_load(p); }
 __device__ __forceinline__ void mw_st16(u32x4 *p, u32x4 v) { __builtin_nontemporal_store(v, p); }
+// The same load through a pointer that was read from memory: saying that it is a global
+// address keeps it off the flat path, whose loads also count as LDS traffic and would make
+// every later wait for a scalar load wait for the payload too.
+typedef const __attribute__((address_space(1))) u32x4 *mw_gptr16;
+__device__ __forceinline__ u32x4 mw_ld16_global(const void *row, int chunk)
+{
+    return __builtin_nontemporal_load((mw_gptr16)row + chunk);
+}
+
+// Wave-uniform values: "the value is needed in scalar registers here".  The compiler
+// otherwise sinks every scalar load to its first use, one wait per load; pinning several
+// values side by side makes it issue their loads together and wait once.
+#define MW_PIN_S(x) asm volatile("" : "+s"(x))
+#define MW_PIN_PTR(p) do { uint32_t lo_ = (uint32_t)(uintptr_t)(p); asm volatile("" : "+s"(lo_)); } while (0)
+#define MW_PIN_S4(v) asm volatile("" : "+s"((v).x), "+s"((v).y), "+s"((v).z), "+s"((v).w))
 
 // Exclusive prefix sum over one value per thread of a block (blockDim.x multiple of 64,
 // at most 1024).  `wave_tot` is LDS scratch of 17 words.  Returns the exclusive prefix;

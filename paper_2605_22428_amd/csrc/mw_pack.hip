@@ -15,7 +15,9 @@
 namespace {
 
 // blockIdx.x = packed row, blockIdx.y = segment of blockDim.x chunks.  Chunks [0, xc)
-// come from x, chunks [xc, xc + sc) from the fp8 scale rows (sc == 0 otherwise).
+// come from x, chunks [xc, xc + sc) from the fp8 scale rows (sc == 0 otherwise).  The row
+// count and the row's token are wave-uniform and fetched together (perm has room for
+// gridDim.x entries, so the read is in bounds even past the last kept row).
 __global__ __launch_bounds__(1024) void k_pack(const u32x4 *__restrict__ x, const u32x4 *__restrict__ scales,
                                                int xc, int sc, const int32_t *__restrict__ topk, int K,
                                                const int32_t *__restrict__ perm,
@@ -23,18 +25,24 @@ __global__ __launch_bounds__(1024) void k_pack(const u32x4 *__restrict__ x, cons
                                                u32x4 *__restrict__ packed, int32_t *__restrict__ row_src_token,
                                                int32_t *__restrict__ row_topk)
 {
+    uint32_t bdim = blockDim.x;
+    MW_PIN_S(bdim); MW_PIN_S(xc); MW_PIN_S(sc); MW_PIN_S(K);
+    MW_PIN_PTR(x); MW_PIN_PTR(scales); MW_PIN_PTR(topk); MW_PIN_PTR(packed); MW_PIN_PTR(row_src_token);
+    MW_PIN_PTR(row_topk);
     const uint32_t i = blockIdx.x;
-    if (i >= stats->n_rows) return;
-    const int32_t t = perm[i];
+    int32_t t = perm[i];
+    uint32_t n_rows = stats->n_rows;
+    MW_PIN_S(t); MW_PIN_S(n_rows);
+    if (i >= n_rows) return;
     const int n = xc + sc;
-    const int c = blockIdx.y * blockDim.x + threadIdx.x;
+    const int c = blockIdx.y * bdim + threadIdx.x;
     if (c < n) {
         const u32x4 v = (c < xc) ? mw_ld16(x + (size_t)t * xc + c) : mw_ld16(scales + (size_t)t * sc + (c - xc));
         mw_st16(packed + (size_t)i * n + c, v);
     }
     if (blockIdx.y == 0) {
         if (threadIdx.x == 0) row_src_token[i] = t;
-        for (int j = threadIdx.x; j < K; j += blockDim.x) row_topk[(size_t)i * K + j] = topk[(size_t)t * K + j];
+        for (int j = threadIdx.x; j < K; j += bdim) row_topk[(size_t)i * K + j] = topk[(size_t)t * K + j];
     }
 }
 

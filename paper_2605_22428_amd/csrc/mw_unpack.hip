@@ -257,35 +257,55 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
 }
 
 // blockIdx.y selects a segment of blockDim.x chunks of the row; blockIdx.x walks rows.  All
-// index reads are wave-uniform.  The row's record is fetched first and alone decides the
-// payload load, which is issued before anything else is looked up: the output position
-// (one small table read) resolves while the payload is in flight.
+// index reads are wave-uniform (scalar loads).  The dependent chain in front of a row's
+// payload is what a one-shot workgroup cannot hide, so it is kept to two steps: the row
+// record and the row count are fetched together, then the payload load and the lookup of
+// the first output position are issued together; the position is there long before the
+// payload is.
 __global__ __launch_bounds__(1024) void k_expand(
     const mw_row_rec *__restrict__ recs, const mw_hit *__restrict__ hits, const uint32_t *__restrict__ base,
     const uint32_t *__restrict__ row_base, int P, int Kd, int xc, int sc,
-    u32x4 *__restrict__ out_rows, u32x4 *__restrict__ out_scales, int64_t cap,
+    u32x4 *__restrict__ out_rows, u32x4 *__restrict__ out_scales, uint32_t cap,
     int32_t *__restrict__ out_src_peer, int32_t *__restrict__ out_src_token)
 {
-    const uint32_t m_total = row_base[P];
+    // Every kernel argument is fetched in the first batch, not after the first branch.
+    // Pointers are pinned through a copy of their low half, so the originals keep their
+    // address space.
+    uint32_t bdim = blockDim.x, gdim = gridDim.x;
+    MW_PIN_S(bdim); MW_PIN_S(gdim); MW_PIN_S(Kd); MW_PIN_S(xc); MW_PIN_S(sc); MW_PIN_S(cap);
+    MW_PIN_PTR(hits); MW_PIN_PTR(out_rows); MW_PIN_PTR(out_scales); MW_PIN_PTR(out_src_peer);
+    MW_PIN_PTR(out_src_token);
     const int n = xc + sc;
-    const int c = blockIdx.y * blockDim.x + threadIdx.x;
-    for (uint32_t g = blockIdx.x; g < m_total; g += gridDim.x) {
-        const mw_row_rec rc = recs[g];
-        if (rc.n_hits == 0) continue;
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (c < n) v = mw_ld16((const u32x4 *)rc.src + c);
-        int le = rc.le0, rank = rc.rank0;
-        for (int k = 0;;) {
-            const int64_t dst = (int64_t)base[(uint32_t)le * P + rc.peer] + rank;
-            if (dst < cap) {
-                if (c < xc) mw_st16(out_rows + (size_t)dst * xc + c, v);
-                else if (c < n) mw_st16(out_scales + (size_t)dst * sc + (c - xc), v);
-                if (c == 0) { out_src_peer[dst] = rc.peer; out_src_token[dst] = rc.src_token; }
+    const int c = blockIdx.y * bdim + threadIdx.x;
+    uint32_t g = blockIdx.x;
+    // gridDim.x <= max_recv_rows, so the first record read is always inside the workspace
+    const u32x4 *rp = (const u32x4 *)(recs + g);
+    u32x4 r0 = rp[0], r1 = rp[1];
+    uint32_t m_total = row_base[P];
+    MW_PIN_S4(r0); MW_PIN_S4(r1); MW_PIN_S(m_total);     // all three fetched together, one wait
+    while (g < m_total) {
+        const int n_hits = (int)r1.x;
+        if (n_hits > 0) {
+            const int peer = (int)r0.w;
+            const void *src = (const void *)(((uint64_t)r0.y << 32) | r0.x);
+            uint32_t b0 = base[r1.y * (uint32_t)P + (uint32_t)peer];
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (c < n) v = mw_ld16_global(src, c);
+            MW_PIN_S(b0);                                  // position lookup in flight with the payload
+            uint32_t dst = b0 + r1.z;                      // below 2^30: 2^24 rows, 64 experts each
+            for (int k = 1;; ++k) {
+                if (dst < cap) {
+                    if (c < xc) mw_st16(out_rows + (size_t)dst * xc + c, v);
+                    else if (c < n) mw_st16(out_scales + (size_t)dst * sc + (c - xc), v);
+                    if (c == 0) { out_src_peer[dst] = peer; out_src_token[dst] = (int32_t)r0.z; }
+                }
+                if (k >= n_hits) break;
+                const mw_hit hk = hits[(size_t)g * Kd + k];
+                dst = base[(uint32_t)hk.le * P + (uint32_t)peer] + (uint32_t)hk.rank;
             }
-            if (++k >= rc.n_hits) break;
-            const mw_hit hk = hits[(size_t)g * Kd + k];
-            le = hk.le; rank = hk.rank;
         }
+        g += gdim;
+        if (g < m_total) { rp = (const u32x4 *)(recs + g); r0 = rp[0]; r1 = rp[1]; }
     }
 }
 
@@ -319,8 +339,8 @@ int32_t mw_launch_unpack(mw_ctx *ctx, const mw_recv_peer *peers, int32_t P, void
         const uint32_t gx = (uint32_t)(c.max_recv_rows < kExpandMaxRowBlocks ? c.max_recv_rows : kExpandMaxRowBlocks);
         mw_timed tm(ctx, MW_KERNEL_EXPAND, s);
         hipLaunchKernelGGL(k_expand, dim3(gx, nseg), dim3(bs), 0, s, ctx->d_recs, ctx->d_hits, ctx->d_base,
-                           ctx->d_row_base, P, Kd, xc, sc, (u32x4 *)out_rows, (u32x4 *)out_scales, cap,
-                           out_src_peer, out_src_token);
+                           ctx->d_row_base, P, Kd, xc, sc, (u32x4 *)out_rows, (u32x4 *)out_scales,
+                           (uint32_t)(cap < 0x7fffffffLL ? cap : 0x7fffffffLL), out_src_peer, out_src_token);
     }
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;
