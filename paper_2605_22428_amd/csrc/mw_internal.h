@@ -113,9 +113,20 @@ __device__ __forceinline__ u32x4 mw_ld16_global(const void *row, int chunk)
 #define MW_PIN_PTR(p) do { uint32_t lo_ = (uint32_t)(uintptr_t)(p); asm volatile("" : "+s"(lo_)); } while (0)
 #define MW_PIN_S4(v) asm volatile("" : "+s"((v).x), "+s"((v).y), "+s"((v).z), "+s"((v).w))
 
+// Workgroup barrier for data exchanged through LDS only.  __syncthreads() also waits until
+// every global load and store of the wave has completed (about a microsecond each time a
+// store or a prefetch is outstanding); this one orders LDS accesses and nothing else.
+__device__ __forceinline__ void mw_lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // Exclusive prefix sum over one value per thread of a block (blockDim.x multiple of 64,
 // at most 1024).  `wave_tot` is LDS scratch of 17 words.  Returns the exclusive prefix;
-// *total receives the block total.  Ends with a barrier so the scratch can be reused.
+// *total receives the block total.  Ends with a barrier so the scratch can be reused.  The
+// barriers order LDS only.
 __device__ __forceinline__ uint32_t mw_block_exscan(uint32_t v, uint32_t *wave_tot, uint32_t *total)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_wave = blockDim.x >> 6;
@@ -126,16 +137,16 @@ __device__ __forceinline__ uint32_t mw_block_exscan(uint32_t v, uint32_t *wave_t
         if (lane >= d) inc += o;
     }
     if (lane == 63) wave_tot[wave] = inc;
-    __syncthreads();
+    mw_lds_barrier();
     if (threadIdx.x == 0) {
         uint32_t run = 0;
         for (int w = 0; w < n_wave; ++w) { uint32_t t = wave_tot[w]; wave_tot[w] = run; run += t; }
         wave_tot[16] = run;
     }
-    __syncthreads();
+    mw_lds_barrier();
     const uint32_t ex = wave_tot[wave] + inc - v;
     *total = wave_tot[16];
-    __syncthreads();
+    mw_lds_barrier();
     return ex;
 }
 #endif

@@ -111,7 +111,7 @@ __global__ __launch_bounds__(kBlock) void k_rank(const int32_t *__restrict__ top
             if (mine) atomicAdd(&pstate[q * 64 + lane], mine);
         }
     }
-    __syncthreads();
+    mw_lds_barrier();
 
     uint32_t c_lt = 0, c_eqb = 0, c_eqa = 0;
 #pragma unroll 4

@@ -77,7 +77,7 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
     }
 
     for (uint32_t w = tid; w < wpl; w += nthr) addr[w] = 0;
-    __syncthreads();
+    mw_lds_barrier();
 
     // addressed rows: groups whose bitmap has this rank's bit
     for (uint32_t g = tid; g < pr.n_desc; g += nthr) {
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
             atomicOr(&addr[w], m);
         }
     }
-    __syncthreads();
+    mw_lds_barrier();
     {
         uint32_t a = 0, tot;
         for (uint32_t w = tid; w < wpl; w += nthr) a += __popc(addr[w]);
@@ -157,7 +157,7 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
         const int lc = min(Lc, L - le0);
         const uint32_t n_words = (uint32_t)lc * wpl;
         for (uint32_t f = tid; f < n_words; f += nthr) bits[f] = 0;
-        __syncthreads();
+        mw_lds_barrier();
 
         // mark (expert, source token) pairs of this chunk of experts
         for (uint32_t i = tid; i < n_rows; i += nthr) {
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
                 if ((old >> (s & 31)) & 1u) err |= MW_FLAG_DUP_SRC_TOKEN;
             }
         }
-        __syncthreads();
+        mw_lds_barrier();
 
         // running popcounts over the chunk's words (expert-major), one flat scan
         uint32_t carry = 0;
@@ -185,7 +185,7 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
             if (f < n_words) pre[f] = carry + ex;
             carry += tot;
         }
-        __syncthreads();
+        mw_lds_barrier();
         for (int l = tid; l < lc; l += nthr) {
             const uint32_t end = (l + 1 < lc) ? pre[(uint32_t)(l + 1) * wpl] : carry;
             st_agent(&cnt[(size_t)(le0 + l) * P + p], end - pre[(uint32_t)l * wpl]);
@@ -207,7 +207,7 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
                 else h[k].rank = rk;
             }
         }
-        __syncthreads();
+        mw_lds_barrier();
     }
     if (L == 0) {
         // no expert lives here: any addressed row is inconsistent
