@@ -34,9 +34,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--single-stream", action="store_true",
-                    help="issue send side and receive side on one stream (default: two streams, "
-                         "the two sides are independent and overlap)")
+    ap.add_argument("--schedule", choices=["aligned", "free", "single"], default="aligned",
+                    help="how the send side and the receive side of a step are issued (see step())")
     ap.add_argument("--seed", type=int, default=None)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -128,16 +127,36 @@ def main() -> int:
         ctx.mw_unpack(s["table"], R, rv.out_rows, None, cap, rv.out_src_peer, rv.out_src_token,
                       rv.expert_offsets, rv.stats)
 
-    def step(i: int, two_streams: bool = not args.single_stream):
+    # Default schedule ("aligned"): two streams and one cross-stream wait per step.  The packer
+    # (bandwidth-bound, short) is held back until the previous batch's expander has finished, so it
+    # runs beside the receive index (latency-bound, moves almost nothing) instead of competing
+    # with the expander for HBM; the plan of the next batch (latency-bound) runs beside the
+    # expander.  "free" lets the two streams drift, "single" issues everything on one stream.
+    ev_unpack_done = [torch.cuda.Event() for _ in range(2)]
+    state = {"n": 0}
+
+    def step(i: int, schedule: str = args.schedule):
         s = sets[i % N_SETS]
-        if two_streams:
+        if schedule == "single":
+            send_side(s)
+            recv_side(s)
+        elif schedule == "free":
             with torch.cuda.stream(s_send):
                 send_side(s)
             with torch.cuda.stream(s_recv):
                 recv_side(s)
         else:
-            send_side(s)
-            recv_side(s)
+            n = state["n"]
+            state["n"] = n + 1
+            sd = s["send"]
+            with torch.cuda.stream(s_send):
+                ctx.mw_plan(topk_d, sd.mask, sd.perm, sd.desc, sd.stats)
+                if n > 0:
+                    s_send.wait_event(ev_unpack_done[(n - 1) % 2])
+                ctx.mw_pack(s["x"], None, topk_d, sd.perm, sd.stats, sd.packed, sd.row_src_token, sd.row_topk)
+            with torch.cuda.stream(s_recv):
+                recv_side(s)
+                ev_unpack_done[n % 2].record(s_recv)
 
     def new_events(n):
         ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
@@ -178,9 +197,16 @@ def main() -> int:
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(i, False)
+        step(i, "single")
     torch.cuda.synchronize()
     ms_single = (time.perf_counter() - t0) * 1e3 / args.steps
+    # two streams left to drift, for reference
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, "free")
+    torch.cuda.synchronize()
+    ms_free = (time.perf_counter() - t0) * 1e3 / args.steps
 
     # ---------------------------------------------------------------- per-kernel breakdown (one stream, untimed)
     names = {"plan_rank": B.MW_KERNEL_PLAN_RANK,
@@ -191,7 +217,7 @@ def main() -> int:
     for i in range(n_b):
         for k, code in names.items():
             ctx.mw_ctx_set_timing_events(code, *evs[k][i])
-        step(i, False)
+        step(i, "single")
     torch.cuda.synchronize()
     for code in names.values():
         ctx.mw_ctx_set_timing_events(code, None, None)
@@ -222,13 +248,14 @@ def main() -> int:
     pu_us = kern_us["pack"] + kern_us["recv_index"] + kern_us["expand"]
     saved = 1.0 - int(st["multicast_bytes"]) / int(st["unicast_bytes"])
 
+    # HBM bytes per expander launch from the committed rocprofv3 counter summary (FETCH_SIZE and
+    # WRITE_SIZE runs of this same command, scaled by what the plain copy kernel reads)
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "k_expand_C1_hbm_traffic.json")
+    tpath = os.path.join(ROOT, "profiles", "k_expand_C1_hbm_traffic.md")
     if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
-        except Exception:
-            traffic = None
+        for line in open(tpath):
+            if line.startswith("traffic_bytes_per_launch k_expand:"):
+                traffic = int(line.split(":")[1])
 
     result = {
         "metric": "dispatch pack+unpack HBM GB/s (% of peak) + bytes saved vs unicast, 1 GPU",
@@ -239,8 +266,8 @@ def main() -> int:
                                "group-limited (<=4 of 8 nodes), 4096 tokens x 7168 bf16 on this rank, "
                                "64 peer receive regions", "seed": seed, "my_rank": my_rank,
                    "rows_packed": N, "groups": int(st["n_groups"]), "rows_received": M, "rows_out": Q,
-                   "buffer_sets": N_SETS, "streams": 1 if args.single_stream else 2},
-        "single_stream_ms_per_step": round(ms_single, 4),
+                   "buffer_sets": N_SETS, "schedule": args.schedule, "streams": 1 if args.schedule == "single" else 2},
+        "single_stream_ms_per_step": round(ms_single, 4), "free_streams_ms_per_step": round(ms_free, 4),
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "bytes_saved_vs_unicast": round(saved, 4),
         "step_bytes": {"pack": pack_bytes, "unpack": unpack_bytes},

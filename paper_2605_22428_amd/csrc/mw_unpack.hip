@@ -43,6 +43,45 @@ __device__ __forceinline__ void st_agent(uint32_t *p, uint32_t v)
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// One workgroup: exclusive scan of the (expert, peer) counts in output order, expert
+// offsets, totals and flags.  `scratch` is LDS scan scratch of 17 words.  Every device-scope
+// read that does not depend on another is issued before the first scan.
+__device__ __forceinline__ void mw_finish_counts(const uint32_t *cnt, const uint32_t *addr_cnt, uint32_t *flags,
+                                                 uint32_t L, uint32_t P, int64_t out_cap, uint32_t *base,
+                                                 int64_t *expert_offsets, mw_recv_stats *stats, uint32_t *scratch)
+{
+    const uint32_t tid = threadIdx.x, nthr = blockDim.x;
+    const uint32_t n_lp = L * P;
+    uint32_t m = 0;
+    for (uint32_t q = tid; q < P; q += nthr) m += ld_agent(&addr_cnt[q]);
+    const uint32_t err = (tid == 0) ? ld_agent(&flags[1]) : 0u;
+    uint32_t v_next = (tid < n_lp) ? ld_agent(&cnt[tid]) : 0u;
+    uint32_t carry = 0;
+    for (uint32_t f0 = 0; f0 < n_lp; f0 += nthr) {          // (expert, peer) order = output order
+        const uint32_t f = f0 + tid, v = v_next;
+        v_next = (f + nthr < n_lp) ? ld_agent(&cnt[f + nthr]) : 0u;
+        uint32_t tot;
+        const uint32_t ex = mw_block_exscan(v, scratch, &tot);
+        if (f < n_lp) {
+            base[f] = carry + ex;
+            if (f % P == 0) expert_offsets[f / P] = (int64_t)(carry + ex);
+        }
+        carry += tot;
+    }
+    uint32_t m_tot;
+    mw_block_exscan(m, scratch, &m_tot);
+    if (tid == 0) {
+        const uint32_t Q = carry;
+        expert_offsets[L] = Q;
+        stats->n_recv_rows = m_tot;
+        stats->n_out_rows = Q;
+        stats->error_flags = err | (((int64_t)Q > out_cap) ? MW_FLAG_OUT_CAPACITY : 0u);
+        stats->reserved0 = 0;
+        st_agent(&flags[1], 0u);           // ready for the next unpack
+        st_agent(&flags[2], 0u);
+    }
+}
+
 __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
     const mw_recv_peer *__restrict__ peers, int P, const int32_t *__restrict__ eslot,
     int E, int K, int Kd, int my_rank, int L, int Lc,
@@ -55,19 +94,60 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
     uint32_t *addr = lds;                       // [wpl]      bit i: row i's group names this rank
     uint32_t *bits = addr + wpl;                // [Lc][wpl]  bit s of expert l: a row with source token s
     uint32_t *pre = bits + (size_t)Lc * wpl;    // [Lc][wpl]  running popcount before each word
-    uint32_t *scratch = pre + (size_t)Lc * wpl; // [17] scan scratch, [17] "I am last"
+    uint32_t *scratch = pre + (size_t)Lc * wpl; // [17] scan scratch, [17] "I am last", [18] addressed rows,
+                                                // [19] rows of the peers before this one
 
     const int tid = threadIdx.x, nthr = blockDim.x, p = blockIdx.x;
     const mw_recv_peer pr = peers[p];
+    const uint32_t mine = min(pr.n_rows, max_tokens);
+    // All experts' bitmaps fit in LDS at once (the usual case): marking is fused into the row
+    // parse and the thread's first row never leaves its registers.
+    const bool one_chunk = Lc >= L;
     uint32_t err = 0;
 
-    // rows of the peers before this one (each clamped to max_tokens, the total to cap_rows);
-    // at most 256 peers of at most 65536 rows, so 32 bits are enough
+    // ---- everything that depends on the peer record alone is requested before the first wait:
+    // the thread's first row (source token, first eight expert ids), its first descriptor and
+    // the row counts of the peers before this one.  The kernel is a chain of memory round
+    // trips; beside a bandwidth-bound kernel each of them takes several times longer.
+    const int32_t *tk_c = pr.row_topk + (size_t)tid * K;
+    uint32_t s_c = 0;
+    int32_t e_c[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) e_c[u] = -1;
+    if ((uint32_t)tid < mine) {
+        s_c = (uint32_t)pr.row_src_token[tid];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) if (u < K) e_c[u] = tk_c[u];
+    }
+    uint64_t dmask_c = 0;
+    uint32_t doff_c = 0, dcnt_c = 0;
+    if ((uint32_t)tid < pr.n_desc) {
+        const mw_group_desc *d = pr.desc + tid;
+        dmask_c = d->mask[my_rank >> 6];
+        doff_c = d->row_offset;
+        dcnt_c = d->row_count;
+    }
     uint32_t part = 0;
     for (int q = tid; q < p; q += nthr) part += min(peers[q].n_rows, max_tokens);
-    uint32_t before;
-    mw_block_exscan(part, scratch, &before);
-    const uint32_t mine = min(pr.n_rows, max_tokens);
+
+    for (uint32_t w = tid; w < wpl; w += nthr) addr[w] = 0;
+    if (one_chunk) for (uint32_t w = tid; w < (uint32_t)L * wpl; w += nthr) bits[w] = 0;
+    if (tid < 2) scratch[18 + tid] = 0;
+    mw_lds_barrier();
+    // at most 256 peers of at most 65536 rows, so 32 bits are enough; a sum, so order-free
+    if (part) atomicAdd(&scratch[19], part);
+
+    // rank-table entries of the first row's ids (second round trip)
+    int32_t q_c[8];
+    bool bad_c = false;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const bool ok = (uint32_t)e_c[u] < (uint32_t)E;
+        bad_c |= (e_c[u] != -1 && !ok);
+        q_c[u] = ok ? eslot[e_c[u]] : -1;
+    }
+    mw_lds_barrier();
+    const uint32_t before = scratch[19];
     if (pr.n_rows > max_tokens || before + mine > cap_rows) err |= MW_FLAG_RECV_CAPACITY;
     const uint32_t rb = min(before, cap_rows);
     const uint32_t n_rows = min(before + mine, cap_rows) - rb;
@@ -76,14 +156,16 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
         if (p == P - 1) row_base[P] = rb + n_rows;
     }
 
-    for (uint32_t w = tid; w < wpl; w += nthr) addr[w] = 0;
-    mw_lds_barrier();
-
-    // addressed rows: groups whose bitmap has this rank's bit
+    // ---- addressed rows: groups whose bitmap has this rank's bit
     for (uint32_t g = tid; g < pr.n_desc; g += nthr) {
-        const mw_group_desc *d = pr.desc + g;
-        if (!mask_has(d->mask, my_rank)) continue;
-        const uint64_t b = d->row_offset, e = b + d->row_count;
+        uint64_t dm = dmask_c;
+        uint64_t b = doff_c, e = (uint64_t)doff_c + dcnt_c;
+        if (g != (uint32_t)tid) {
+            const mw_group_desc *d = pr.desc + g;
+            dm = d->mask[my_rank >> 6];
+            b = d->row_offset; e = b + d->row_count;
+        }
+        if (!((dm >> (my_rank & 63)) & 1ull)) continue;
         if (e > n_rows) { err |= MW_FLAG_BAD_DESC; continue; }
         if (e <= b) continue;
         for (uint64_t w = b >> 5; w <= ((e - 1) >> 5); ++w) {
@@ -96,81 +178,116 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
     }
     mw_lds_barrier();
     {
-        uint32_t a = 0, tot;
+        uint32_t a = 0;
         for (uint32_t w = tid; w < wpl; w += nthr) a += __popc(addr[w]);
-        mw_block_exscan(a, scratch, &tot);
-        if (tid == 0) st_agent(&addr_cnt[p], tot);
+        if (a) atomicAdd(&scratch[18], a);
     }
 
-    // Per row: its distinct local experts in top-k order (duplicate ids count once) go to the
-    // row's hit slots, unused slots get -1, and the row record is written.  Ids and table
-    // entries are fetched in independent batches of 8 so a row costs two memory round trips.
-    // A thread always handles the same rows (i = tid, tid + nthr, ...), so it may read its
-    // own slot writes back later without a barrier.
-    for (uint32_t i = tid; i < n_rows; i += nthr) {
+    // ---- per row: its distinct local experts in top-k order (duplicate ids count once).
+    // Slot k of the row's hit slots receives expert k; the first eight also stay in f[].
+    // A thread always handles the same rows (i = tid, tid + nthr, ...), so what it wrote for a
+    // row it may read back later without a barrier.
+    auto parse = [&](uint32_t i, bool first, int (&f)[8]) -> int {
         mw_hit *h = hits + (size_t)(rb + i) * Kd;
+        const int32_t *tk = pr.row_topk + (size_t)i * K;
         int nk = 0;
+        for (int j0 = 0; j0 < K; j0 += 8) {
+            int32_t q[8];
+            if (first && j0 == 0) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) q[u] = q_c[u];
+                if (bad_c) err |= MW_FLAG_BAD_EXPERT;
+            } else {
+                int32_t e[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) e[u] = (j0 + u < K) ? tk[j0 + u] : -1;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const bool ok = (uint32_t)e[u] < (uint32_t)E;
+                    if (e[u] != -1 && !ok) err |= MW_FLAG_BAD_EXPERT;
+                    q[u] = ok ? eslot[e[u]] : -1;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (q[u] < 0 || (q[u] >> 16) != my_rank) continue;
+                const int le = q[u] & 0xffff;
+                bool dup = false;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) dup |= (k < nk && f[k] == le);
+                for (int k = 8; k < nk; ++k) dup |= (h[k].le == le);
+                if (dup) continue;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) if (k == nk) f[k] = le;
+                h[nk++] = mw_hit{le, 0};
+            }
+        }
+        return nk;
+    };
+    // sets the (expert, source token) bits of one row for the experts [le0, le0 + lc)
+    auto mark = [&](uint32_t i, uint32_t s, int nk, const int (&f)[8], int le0, int lc) {
+        const mw_hit *h = hits + (size_t)(rb + i) * Kd;
+        for (int k = 0; k < nk; ++k) {
+            int le = 0;
+#pragma unroll
+            for (int k8 = 0; k8 < 8; ++k8) if (k8 == k) le = f[k8];
+            if (k >= 8) le = h[k].le;
+            const int l = le - le0;
+            if (l < 0 || l >= lc) continue;
+            const uint32_t old = atomicOr(&bits[(uint32_t)l * wpl + (s >> 5)], 1u << (s & 31));
+            if ((old >> (s & 31)) & 1u) err |= MW_FLAG_DUP_SRC_TOKEN;
+        }
+    };
+    // a row's state as the parse left it in memory
+    auto reload = [&](uint32_t i, uint32_t &s, int &nk, int (&f)[8]) {
+        const mw_row_rec *rc = recs + rb + i;
+        const mw_hit *h = hits + (size_t)(rb + i) * Kd;
+        s = (uint32_t)rc->src_token; nk = rc->n_hits;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) f[k] = (k < nk) ? h[k].le : 0;
+    };
+
+    int nk_c = 0;
+    int f_c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    mw_row_rec rec_c = {nullptr, 0, p, 0, 0, 0, 0};
+    for (uint32_t i = tid; i < n_rows; i += nthr) {
+        const bool first = i == (uint32_t)tid;
         mw_row_rec rec = {nullptr, 0, p, 0, 0, 0, 0};
         if ((addr[i >> 5] >> (i & 31)) & 1u) {
-            const uint32_t s = (uint32_t)pr.row_src_token[i];
+            const uint32_t s = first ? s_c : (uint32_t)pr.row_src_token[i];
             if (s >= max_tokens) {
                 err |= MW_FLAG_BAD_SRC_TOKEN;
             } else {
-                const int32_t *tk = pr.row_topk + (size_t)i * K;
-                int f[8] = {0, 0, 0, 0, 0, 0, 0, 0};          // first eight experts found (dedup in registers)
-                for (int j0 = 0; j0 < K; j0 += 8) {
-                    int32_t e[8], q[8];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) e[u] = (j0 + u < K) ? tk[j0 + u] : -1;
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        const bool ok = (uint32_t)e[u] < (uint32_t)E;
-                        if (e[u] != -1 && !ok) err |= MW_FLAG_BAD_EXPERT;
-                        q[u] = ok ? eslot[e[u]] : -1;
-                    }
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        if (q[u] < 0 || (q[u] >> 16) != my_rank) continue;
-                        const int le = q[u] & 0xffff;
-                        bool dup = false;
-#pragma unroll
-                        for (int k = 0; k < 8; ++k) dup |= (k < nk && f[k] == le);
-                        for (int k = 8; k < nk; ++k) dup |= (h[k].le == le);
-                        if (dup) continue;
-#pragma unroll
-                        for (int k = 0; k < 8; ++k) if (k == nk) f[k] = le;
-                        h[nk++] = mw_hit{le, 0};
-                    }
-                }
+                int f[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+                const int nk = parse(i, first, f);
                 if (nk == 0) err |= MW_FLAG_NO_LOCAL_EXPERT;
                 rec.src = (const char *)pr.rows + (size_t)i * row_bytes;
                 rec.src_token = (int32_t)s;
                 rec.n_hits = nk;
                 rec.le0 = f[0];
+                if (one_chunk) mark(i, s, nk, f, 0, L);
+                if (first) {
+                    nk_c = nk;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) f_c[k] = f[k];
+                }
             }
         }
-        recs[rb + i] = rec;
-        for (int k = nk; k < Kd; ++k) h[k] = mw_hit{-1, 0};
+        if (first && one_chunk) rec_c = rec;     // written once its rank is known
+        else recs[rb + i] = rec;
     }
 
     for (int le0 = 0; le0 < L; le0 += Lc) {
         const int lc = min(Lc, L - le0);
         const uint32_t n_words = (uint32_t)lc * wpl;
-        for (uint32_t f = tid; f < n_words; f += nthr) bits[f] = 0;
-        mw_lds_barrier();
-
-        // mark (expert, source token) pairs of this chunk of experts
-        for (uint32_t i = tid; i < n_rows; i += nthr) {
-            const mw_hit *h = hits + (size_t)(rb + i) * Kd;
-            if (h[0].le < 0) continue;
-            const uint32_t s = (uint32_t)pr.row_src_token[i];
-            for (int k = 0; k < Kd; ++k) {
-                const int le = h[k].le;
-                if (le < 0) break;
-                const int l = le - le0;
-                if (l < 0 || l >= lc) continue;
-                const uint32_t old = atomicOr(&bits[(uint32_t)l * wpl + (s >> 5)], 1u << (s & 31));
-                if ((old >> (s & 31)) & 1u) err |= MW_FLAG_DUP_SRC_TOKEN;
+        if (!one_chunk) {
+            if (le0 > 0) mw_lds_barrier();           // the previous chunk's ranks have been read
+            for (uint32_t f = tid; f < n_words; f += nthr) bits[f] = 0;
+            mw_lds_barrier();
+            for (uint32_t i = tid; i < n_rows; i += nthr) {
+                uint32_t s; int nk; int f[8];
+                reload(i, s, nk, f);
+                mark(i, s, nk, f, le0, lc);
             }
         }
         mw_lds_barrier();
@@ -193,30 +310,37 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
 
         // stable rank of the row among the peer's rows for each of its experts in the chunk
         for (uint32_t i = tid; i < n_rows; i += nthr) {
+            const bool cached = one_chunk && i == (uint32_t)tid;
             mw_hit *h = hits + (size_t)(rb + i) * Kd;
-            if (h[0].le < 0) continue;
-            const uint32_t s = (uint32_t)pr.row_src_token[i];
-            for (int k = 0; k < Kd; ++k) {
-                const int le = h[k].le;
-                if (le < 0) break;
+            uint32_t s = s_c; int nk = nk_c; int f[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) f[k] = f_c[k];
+            if (!cached) reload(i, s, nk, f);
+            for (int k = 0; k < nk; ++k) {
+                int le = 0;
+#pragma unroll
+                for (int k8 = 0; k8 < 8; ++k8) if (k8 == k) le = f[k8];
+                if (k >= 8) le = h[k].le;
                 const int l = le - le0;
                 if (l < 0 || l >= lc) continue;
                 const uint32_t wi = (uint32_t)l * wpl + (s >> 5);
                 const int32_t rk = (int32_t)(pre[wi] - pre[(uint32_t)l * wpl] + __popc(bits[wi] & ((1u << (s & 31)) - 1u)));
-                if (k == 0) recs[rb + i].rank0 = rk;
-                else h[k].rank = rk;
+                if (k > 0) h[k].rank = rk;
+                else if (cached) rec_c.rank0 = rk;
+                else recs[rb + i].rank0 = rk;
             }
         }
-        mw_lds_barrier();
     }
+    if (one_chunk && (uint32_t)tid < n_rows) recs[rb + tid] = rec_c;
     if (L == 0) {
         // no expert lives here: any addressed row is inconsistent
         for (uint32_t w = tid; w < wpl; w += nthr) if (addr[w]) err |= MW_FLAG_NO_LOCAL_EXPERT;
     }
     if (err) atomicOr(&flags[1], err);
+    if (tid == 0) st_agent(&addr_cnt[p], scratch[18]);
 
     // ---- the workgroup that finishes last turns the counts into output bases ----------
-    // Counts, addressed-row counts and flags were published with device-scope atomics; the
+    // Counts, addressed-row counts and flags are published with device-scope atomics; the
     // barrier orders them before thread 0's release fence and counter increment.
     __syncthreads();
     if (tid == 0) {
@@ -227,33 +351,7 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
     }
     __syncthreads();
     if (!scratch[17]) return;
-
-    const uint32_t n_lp = (uint32_t)L * P;
-    uint32_t carry = 0;
-    for (uint32_t f0 = 0; f0 < n_lp; f0 += nthr) {          // (expert, peer) order = output order
-        const uint32_t f = f0 + tid;
-        const uint32_t v = (f < n_lp) ? ld_agent(&cnt[f]) : 0u;
-        uint32_t tot;
-        const uint32_t ex = mw_block_exscan(v, scratch, &tot);
-        if (f < n_lp) {
-            base[f] = carry + ex;
-            if (f % (uint32_t)P == 0) expert_offsets[f / (uint32_t)P] = (int64_t)(carry + ex);
-        }
-        carry += tot;
-    }
-    uint32_t m = 0, m_tot;
-    for (int q = tid; q < P; q += nthr) m += ld_agent(&addr_cnt[q]);
-    mw_block_exscan(m, scratch, &m_tot);
-    if (tid == 0) {
-        const uint32_t Q = carry;
-        expert_offsets[L] = Q;
-        stats->n_recv_rows = m_tot;
-        stats->n_out_rows = Q;
-        stats->error_flags = ld_agent(&flags[1]) | (((int64_t)Q > out_cap) ? MW_FLAG_OUT_CAPACITY : 0u);
-        stats->reserved0 = 0;
-        st_agent(&flags[1], 0u);           // ready for the next unpack
-        st_agent(&flags[2], 0u);
-    }
+    mw_finish_counts(cnt, addr_cnt, flags, (uint32_t)L, (uint32_t)P, out_cap, base, expert_offsets, stats, scratch);
 }
 
 // blockIdx.y selects a segment of blockDim.x chunks of the row; blockIdx.x walks rows.  All
