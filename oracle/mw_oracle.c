@@ -37,7 +37,12 @@
  * library stable sort (plain AlltoAllV), the all-equal-mask case against
  * memcpy, AllGather against array concatenation, the (token, destination)
  * exactly-once property, tier 1 == tier 2, and the paper's printed
- * arithmetic (C(64,8), 128 B vs 8 B metadata, 128 B / 4096 B).
+ * arithmetic (C(64,8), 128 B vs 8 B metadata, 128 B / 4096 B).  The relay
+ * step (ref_relay_child, ref_relay_accounting) is pinned in
+ * tests/test_oracle_relay.py: children partition every parent bitmap, an
+ * identity forwarding table reduces to ref_deliver with single-bit bitmaps,
+ * a one-hop table returns the parent, delivery through relays equals direct
+ * delivery bytewise, and the copy count against a closed form.
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -282,6 +287,102 @@ int ref_deliver(const ref_group_desc *desc, int32_t G, const uint8_t *rows, int6
 }
 
 /* slot of expert e among the experts hosted by `rank`, in ascending id order; -1 if elsewhere */
+/* ------------------------------------------------------------------------ */
+/*
+ * Relay step.  Section 4.3.3 (recursive execution model): a node that holds
+ * a MultiWrite for a destination set M partitions M by next hop and starts
+ * one child MultiWrite per subset; |M_i| == 1 is an ordinary write.
+ * Section 4.1, "Local forwarding table": the next hop of every destination
+ * comes from the node's unicast forwarding table, and the number of distinct
+ * next hops is the number of copies made.  Section 4.1, "Replication and
+ * forwarding": the metadata of each copy is updated so that it names only
+ * the destinations served through that hop -- no destination is served twice.
+ *
+ * Reading used here (the paper gives no buffer format): `next_hop[r]` in
+ * [0, n_hops) is the forwarding table entry of destination rank r.  The child
+ * for hop h keeps, in the parent's order, the groups whose bitmap names at
+ * least one rank with next_hop == h; the child's bitmap is the parent's
+ * restricted to those ranks, its rows are the group's rows concatenated,
+ * row_offset is rebased, n_dest is the popcount of the restricted bitmap.
+ * Row metadata is copied unchanged.  A destination named by a bitmap whose
+ * rank is >= n_ranks is an input error.
+ */
+int ref_relay_child(const ref_group_desc *desc, int32_t G, const uint8_t *rows, int64_t row_bytes,
+                    const int32_t *row_src_token, const int32_t *row_topk, int32_t K,
+                    const int32_t *next_hop, int32_t R, int32_t n_hops, int32_t hop,
+                    ref_group_desc *desc_out, uint8_t *rows_out, int32_t *src_token_out, int32_t *topk_out,
+                    int32_t *G_out, int32_t *N_out)
+{
+    if (R < 1 || R > REF_MAX_RANKS || n_hops < 1 || hop < 0 || hop >= n_hops) return REF_ERR_ARG;
+    for (int32_t r = 0; r < R; ++r)
+        if (next_hop[r] < 0 || next_hop[r] >= n_hops) return REF_ERR_ARG;
+    int32_t g2 = 0, n2 = 0;
+    for (int32_t g = 0; g < G; ++g) {
+        uint64_t sub[REF_MASK_WORDS] = {0, 0, 0, 0};
+        int n_sub = 0;
+        for (int r = 0; r < REF_MAX_RANKS; ++r) {
+            if (!mask_bit(desc[g].mask, r)) continue;
+            if (r >= R) return REF_ERR_INPUT;
+            if (next_hop[r] != hop) continue;
+            sub[r >> 6] |= (uint64_t)1 << (r & 63);
+            ++n_sub;
+        }
+        if (n_sub == 0) continue;
+        for (int w = 0; w < REF_MASK_WORDS; ++w) desc_out[g2].mask[w] = sub[w];
+        desc_out[g2].row_offset = (uint32_t)n2;
+        desc_out[g2].row_count = desc[g].row_count;
+        desc_out[g2].n_dest = (uint32_t)n_sub;
+        desc_out[g2].reserved0 = 0;
+        for (uint32_t i = 0; i < desc[g].row_count; ++i) {
+            const size_t s = (size_t)desc[g].row_offset + i;
+            memcpy(rows_out + (size_t)n2 * (size_t)row_bytes, rows + s * (size_t)row_bytes, (size_t)row_bytes);
+            src_token_out[n2] = row_src_token[s];
+            for (int32_t j = 0; j < K; ++j) topk_out[(size_t)n2 * K + j] = row_topk[s * K + j];
+            ++n2;
+        }
+        ++g2;
+    }
+    *G_out = g2; *N_out = n2;
+    return REF_OK;
+}
+
+/*
+ * Copies a relay makes, plainly (Section 4.1: the number of unique egress
+ * ports determines how many copies of the packet are made): per group, the
+ * number of distinct next hops among its destinations.
+ *   forward_bytes = row_bytes * sum over groups of rows * distinct hops
+ *   unicast_bytes = row_bytes * sum over groups of rows * destinations
+ *   rows_per_hop[h] = rows of the groups that use hop h
+ */
+int ref_relay_accounting(const ref_group_desc *desc, int32_t G, int64_t row_bytes,
+                         const int32_t *next_hop, int32_t R, int32_t n_hops,
+                         uint64_t *forward_bytes, uint64_t *unicast_bytes, uint32_t *rows_per_hop /* [n_hops] */)
+{
+    if (R < 1 || R > REF_MAX_RANKS || n_hops < 1) return REF_ERR_ARG;
+    for (int32_t r = 0; r < R; ++r)
+        if (next_hop[r] < 0 || next_hop[r] >= n_hops) return REF_ERR_ARG;
+    uint64_t fwd = 0, uni = 0;
+    for (int32_t h = 0; h < n_hops; ++h) rows_per_hop[h] = 0;
+    for (int32_t g = 0; g < G; ++g) {
+        int n_dest = 0;
+        for (int32_t h = 0; h < n_hops; ++h) {
+            int used = 0;
+            for (int r = 0; r < R; ++r)
+                if (mask_bit(desc[g].mask, r) && next_hop[r] == h) used = 1;
+            if (used) { rows_per_hop[h] += desc[g].row_count; fwd += desc[g].row_count; }
+        }
+        for (int r = 0; r < REF_MAX_RANKS; ++r) {
+            if (!mask_bit(desc[g].mask, r)) continue;
+            if (r >= R) return REF_ERR_INPUT;
+            ++n_dest;
+        }
+        uni += (uint64_t)desc[g].row_count * (uint64_t)n_dest;
+    }
+    *forward_bytes = fwd * (uint64_t)row_bytes;
+    *unicast_bytes = uni * (uint64_t)row_bytes;
+    return REF_OK;
+}
+
 static int32_t local_slot_of(const int32_t *expert_to_rank, int32_t e, int32_t rank)
 {
     if (expert_to_rank[e] != rank) return -1;

@@ -50,7 +50,8 @@ def lib():
         _lib = C.CDLL(_build.build())
         for name in ("ref_masks", "ref_plan", "ref_accounting_plain", "ref_pack", "ref_deliver",
                      "ref_unpack", "ref_dispatch_plain", "ref_plan_allgather",
-                     "ref_pack_allgather", "ref_unpack_allgather"):
+                     "ref_pack_allgather", "ref_unpack_allgather",
+                     "ref_relay_child", "ref_relay_accounting"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -144,6 +145,38 @@ def deliver(desc: np.ndarray, rows: np.ndarray, src_token, row_topk, dst_rank: i
                              _p(s2), _p(t2), C.byref(g_out), C.byref(n_out)), "ref_deliver")
     g, n = g_out.value, n_out.value
     return d2[:g].copy(), r2[:n].copy(), s2[:n].copy(), t2[:n].copy()
+
+
+def relay_child(desc: np.ndarray, rows: np.ndarray, src_token, row_topk, next_hop, n_hops: int, hop: int):
+    """The child MultiWrite a relay starts towards next hop `hop` (same tuple layout as deliver)."""
+    desc = np.ascontiguousarray(desc, dtype=DESC)
+    rows = np.ascontiguousarray(rows, dtype=np.uint8)
+    src_token, row_topk, next_hop = _i32(src_token), _i32(row_topk), _i32(next_hop)
+    G, N = len(desc), rows.shape[0]
+    rb, K = rows.shape[1], row_topk.shape[1]
+    d2 = np.zeros(max(G, 1), dtype=DESC)
+    r2 = np.zeros((max(N, 1), rb), dtype=np.uint8)
+    s2 = np.zeros(max(N, 1), dtype=np.int32)
+    t2 = np.zeros((max(N, 1), K), dtype=np.int32)
+    g_out, n_out = C.c_int32(0), C.c_int32(0)
+    _check(lib().ref_relay_child(_p(desc), C.c_int32(G), _p(rows), C.c_int64(rb), _p(src_token),
+                                 _p(row_topk), C.c_int32(K), _p(next_hop), C.c_int32(len(next_hop)),
+                                 C.c_int32(n_hops), C.c_int32(hop), _p(d2), _p(r2), _p(s2), _p(t2),
+                                 C.byref(g_out), C.byref(n_out)), "ref_relay_child")
+    g, n = g_out.value, n_out.value
+    return d2[:g].copy(), r2[:n].copy(), s2[:n].copy(), t2[:n].copy()
+
+
+def relay_accounting(desc: np.ndarray, row_bytes: int, next_hop, n_hops: int):
+    """(forward_bytes, unicast_bytes, rows_per_hop[n_hops]) of a relay holding `desc`."""
+    desc = np.ascontiguousarray(desc, dtype=DESC)
+    next_hop = _i32(next_hop)
+    fwd, uni = C.c_uint64(0), C.c_uint64(0)
+    rph = np.zeros(n_hops, dtype=np.uint32)
+    _check(lib().ref_relay_accounting(_p(desc), C.c_int32(len(desc)), C.c_int64(row_bytes), _p(next_hop),
+                                      C.c_int32(len(next_hop)), C.c_int32(n_hops), C.byref(fwd),
+                                      C.byref(uni), _p(rph)), "ref_relay_accounting")
+    return fwd.value, uni.value, rph
 
 
 PeerBuf = Tuple[np.ndarray, np.ndarray, np.ndarray, np.ndarray]   # (desc, rows, src_token, row_topk)
