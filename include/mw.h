@@ -44,6 +44,7 @@ extern "C" {
 #define MW_MASK_WORDS 4          /* 256-bit destination bitmap */
 #define MW_MAX_RANKS  256        /* Section 6.4: bitmaps wider than 64 bit; 256 ranks here */
 #define MW_MAX_TOPK   64
+#define MW_MAX_HOPS   64         /* next hops (egress ports) a relay's forwarding table may name */
 
 /* status codes */
 #define MW_OK                 0
@@ -66,6 +67,7 @@ extern "C" {
 #define MW_FLAG_BAD_DESC         0x10u  /* descriptor row range outside the peer's rows: group dropped */
 #define MW_FLAG_RECV_CAPACITY    0x20u  /* peers hold more rows than max_recv_rows: surplus peers' rows dropped */
 #define MW_FLAG_DUP_SRC_TOKEN    0x40u  /* two rows of one peer carry the same source token for one expert */
+#define MW_FLAG_BAD_RANK         0x80u  /* relay: a bitmap names a rank >= n_ranks: that bit is not forwarded */
 
 /*
  * Destination bitmap, Section 4.1: ranks are numbered from zero and bit r says
@@ -132,7 +134,7 @@ typedef struct mw_config {
                                bf16 2*H; fp8 H + 4*(H/128).  Must be a multiple of 16;
                                fp8 additionally needs H % 512 == 0 so both parts are. */
     int32_t max_tokens;     /* capacity for n_tokens and bound on any peer's token indices */
-    int32_t reserved0;
+    int32_t max_hops;       /* 0..MW_MAX_HOPS: next hops mw_relay may fan out to (0: relay not used) */
     int64_t max_recv_rows;  /* capacity for the sum of the peers' n_rows in mw_unpack */
     const int32_t *expert_to_rank; /* HOST, [E], values in [0, R); copied at create */
 } mw_config;
@@ -229,6 +231,59 @@ MW_API int32_t mw_unpack(mw_ctx *ctx, const mw_recv_peer *peers_dev, int32_t n_p
 MW_API int32_t mw_unpack_allgather(mw_ctx *ctx, const void *const *peer_shards_dev, int64_t shard_bytes,
                             void *out_dev, void *stream);
 
+/* ---- relay (Section 4.3.3, recursive execution model; Section 4.1, local forwarding table,
+ *      replication and forwarding, update of in-packet metadata) ------------------------------ */
+
+/*
+ * Where mw_relay writes the child MultiWrite of one next hop: the same layout mw_pack
+ * writes and mw_unpack / mw_relay read.  Device array of n_hops records; every buffer has
+ * room for child_capacity_rows rows (descriptors: as many entries).
+ */
+typedef struct mw_relay_child {
+    mw_group_desc *desc;
+    void *rows;                 /* [capacity][row_bytes], 16-byte aligned */
+    int32_t *row_src_token;     /* [capacity] */
+    int32_t *row_topk;          /* [capacity][top_k] */
+} mw_relay_child;               /* 32 bytes */
+
+typedef struct mw_relay_stats {
+    uint32_t n_groups_in;       /* groups of the input taken (row range valid) */
+    uint32_t n_rows_in;         /* their rows */
+    uint64_t forward_bytes;     /* row_bytes * rows written to all children: one copy per distinct next hop */
+    uint64_t unicast_bytes;     /* row_bytes * sum over groups of rows * destinations: one copy per destination */
+    uint32_t groups_per_hop[MW_MAX_HOPS];
+    uint32_t rows_per_hop[MW_MAX_HOPS];
+    uint32_t error_flags;       /* MW_FLAG_BAD_DESC | MW_FLAG_OUT_CAPACITY | MW_FLAG_BAD_RANK */
+    uint32_t reserved0;
+} mw_relay_stats;               /* 544 bytes */
+
+/*
+ * The node's unicast forwarding table (Section 4.1): next_hop[r] in [0, n_hops) is the egress
+ * port / next-hop id towards destination rank r, for every r < n_ranks.  HOST array, copied;
+ * 1 <= n_hops <= max_hops.  SYNCHRONISES the device.  Must not be called while work of this
+ * context is in flight.
+ */
+MW_API int32_t mw_set_forwarding(mw_ctx *ctx, const int32_t *next_hop, int32_t n_hops);
+
+/*
+ * mw_relay: one step of the recursive model.  The node holds a MultiWrite buffer `in_dev`
+ * (one device record: what mw_pack wrote at the source, or what a previous relay wrote)
+ * and starts one child MultiWrite per next hop:
+ *   child h keeps, in order, the groups whose bitmap names a rank with next_hop == h;
+ *   its bitmap is the parent's restricted to those ranks (so no destination is served
+ *   twice, Section 4.1), n_dest its popcount, rows concatenated, row_offset rebased;
+ *   row_src_token and row_topk travel unchanged.
+ * A group's rows are read once and written once per distinct next hop (the number of
+ * unique egress ports is the number of copies, Section 4.1).  A child with one destination
+ * left is an ordinary write of that buffer (Section 4.3.3 rule 2); a child for this rank
+ * itself is what mw_unpack takes as a peer region.  Groups must have ascending, disjoint
+ * row ranges inside [0, n_rows); others are dropped with MW_FLAG_BAD_DESC.  Groups that do
+ * not fit child_capacity_rows are dropped from that child with MW_FLAG_OUT_CAPACITY.
+ * The input's n_desc and n_rows may not exceed max_tokens.
+ */
+MW_API int32_t mw_relay(mw_ctx *ctx, const mw_recv_peer *in_dev, const mw_relay_child *children_dev,
+                 int64_t child_capacity_rows, mw_relay_stats *stats_dev, void *stream);
+
 /* ---- simulation and measurement helpers (not part of the dispatch path) ---------------- */
 
 /*
@@ -251,6 +306,7 @@ MW_API int32_t mw_copy_bytes(void *dst_dev, const void *src_dev, int64_t n_bytes
 /* Copy a statistics block to the host.  SYNCHRONISES `stream`. */
 MW_API int32_t mw_get_send_stats(mw_ctx *ctx, const mw_send_stats *stats_dev, mw_send_stats *host_out, void *stream);
 MW_API int32_t mw_get_recv_stats(mw_ctx *ctx, const mw_recv_stats *stats_dev, mw_recv_stats *host_out, void *stream);
+MW_API int32_t mw_get_relay_stats(mw_ctx *ctx, const mw_relay_stats *stats_dev, mw_relay_stats *host_out, void *stream);
 
 /*
  * Measurement hook.  While a pair of hipEvent_t handles (created by the caller with
@@ -266,7 +322,9 @@ MW_API int32_t mw_get_recv_stats(mw_ctx *ctx, const mw_recv_stats *stats_dev, mw
 #define MW_KERNEL_EXPAND       4
 #define MW_KERNEL_AG_PACK      5   /* mw_pack_allgather's copy */
 #define MW_KERNEL_AG_GATHER    6   /* mw_unpack_allgather's shard assembly */
-#define MW_KERNEL_COUNT        7
+#define MW_KERNEL_RELAY_INDEX  7
+#define MW_KERNEL_RELAY_COPY   8
+#define MW_KERNEL_COUNT        9
 MW_API int32_t mw_ctx_set_timing_events(mw_ctx *ctx, int32_t kernel, void *ev_start, void *ev_stop);
 
 MW_API const char *mw_status_string(int32_t status);

@@ -25,9 +25,12 @@ MW_FLAG_BAD_SRC_TOKEN, MW_FLAG_BAD_DESC, MW_FLAG_RECV_CAPACITY, MW_FLAG_DUP_SRC_
 EXPORTS = ["mw_workspace_bytes", "mw_ctx_create", "mw_ctx_destroy", "mw_plan", "mw_pack",
            "mw_plan_allgather", "mw_pack_allgather", "mw_unpack", "mw_unpack_allgather",
            "mw_sim_deliver", "mw_copy_bytes", "mw_get_send_stats", "mw_get_recv_stats",
+           "mw_set_forwarding", "mw_relay", "mw_get_relay_stats",
            "mw_ctx_set_timing_events", "mw_status_string"]
 MW_KERNEL_PLAN_RANK, MW_KERNEL_PLAN_GROUPS, MW_KERNEL_PACK, MW_KERNEL_RECV_INDEX, MW_KERNEL_EXPAND = 0, 1, 2, 3, 4
-MW_KERNEL_AG_PACK, MW_KERNEL_AG_GATHER = 5, 6
+MW_KERNEL_AG_PACK, MW_KERNEL_AG_GATHER, MW_KERNEL_RELAY_INDEX, MW_KERNEL_RELAY_COPY = 5, 6, 7, 8
+MW_MAX_HOPS = 64
+MW_FLAG_BAD_RANK = 0x80
 
 # numpy views of the ABI records (host copies)
 DESC_DTYPE = np.dtype([("mask", "<u8", (4,)), ("row_offset", "<u4"), ("row_count", "<u4"),
@@ -39,7 +42,13 @@ RECV_STATS_DTYPE = np.dtype([("n_recv_rows", "<u8"), ("n_out_rows", "<u8"), ("er
                              ("reserved0", "<u4")])
 RECV_PEER_DTYPE = np.dtype([("desc", "<u8"), ("n_desc", "<u4"), ("n_rows", "<u4"), ("rows", "<u8"),
                             ("row_src_token", "<u8"), ("row_topk", "<u8")])
+RELAY_CHILD_DTYPE = np.dtype([("desc", "<u8"), ("rows", "<u8"), ("row_src_token", "<u8"), ("row_topk", "<u8")])
+RELAY_STATS_DTYPE = np.dtype([("n_groups_in", "<u4"), ("n_rows_in", "<u4"), ("forward_bytes", "<u8"),
+                              ("unicast_bytes", "<u8"), ("groups_per_hop", "<u4", (64,)),
+                              ("rows_per_hop", "<u4", (64,)), ("error_flags", "<u4"), ("reserved0", "<u4")])
 DESC_BYTES, SEND_STATS_BYTES, RECV_STATS_BYTES, RECV_PEER_BYTES = 48, 1056, 24, 40
+RELAY_CHILD_BYTES, RELAY_STATS_BYTES = 32, 544
+assert (RELAY_CHILD_DTYPE.itemsize, RELAY_STATS_DTYPE.itemsize) == (32, 544)
 assert (DESC_DTYPE.itemsize, SEND_STATS_DTYPE.itemsize, RECV_STATS_DTYPE.itemsize,
         RECV_PEER_DTYPE.itemsize) == (48, 1056, 24, 40)
 
@@ -47,7 +56,7 @@ assert (DESC_DTYPE.itemsize, SEND_STATS_DTYPE.itemsize, RECV_STATS_DTYPE.itemsiz
 class MwConfig(C.Structure):
     _fields_ = [("n_ranks", C.c_int32), ("n_experts", C.c_int32), ("top_k", C.c_int32),
                 ("my_rank", C.c_int32), ("hidden", C.c_int32), ("row_format", C.c_int32),
-                ("row_bytes", C.c_int64), ("max_tokens", C.c_int32), ("reserved0", C.c_int32),
+                ("row_bytes", C.c_int64), ("max_tokens", C.c_int32), ("max_hops", C.c_int32),
                 ("max_recv_rows", C.c_int64), ("expert_to_rank", C.c_void_p)]
 
 
@@ -100,12 +109,13 @@ class Context:
 
     def __init__(self, n_ranks: int, n_experts: int, top_k: int, my_rank: int, hidden: int,
                  row_format: int, max_tokens: int, max_recv_rows: int,
-                 expert_to_rank: Optional[np.ndarray], row_bytes: int = 0, device: str = "cuda:0"):
+                 expert_to_rank: Optional[np.ndarray], row_bytes: int = 0, device: str = "cuda:0",
+                 max_hops: int = 0):
         lib = load()
         self.device = torch.device(device)
         e2r = None if expert_to_rank is None else np.ascontiguousarray(expert_to_rank, dtype=np.int32)
         self._e2r = e2r
-        cfg = MwConfig(n_ranks, n_experts, top_k, my_rank, hidden, row_format, row_bytes, max_tokens, 0,
+        cfg = MwConfig(n_ranks, n_experts, top_k, my_rank, hidden, row_format, row_bytes, max_tokens, max_hops,
                        max_recv_rows, 0 if e2r is None else e2r.ctypes.data)
         need = C.c_int64(0)
         _check(lib.mw_workspace_bytes(C.byref(cfg), C.byref(need)), "mw_workspace_bytes")
@@ -173,6 +183,22 @@ class Context:
         _check(load().mw_unpack_allgather(self._h, _ptr(peer_shards), C.c_int64(shard_bytes), _ptr(out),
                                           _stream()), "mw_unpack_allgather")
 
+    # ---- relay ---------------------------------------------------------------------------
+    def mw_set_forwarding(self, next_hop: np.ndarray, n_hops: int):
+        t = np.ascontiguousarray(next_hop, dtype=np.int32)
+        _check(load().mw_set_forwarding(self._h, C.c_void_p(t.ctypes.data), C.c_int32(n_hops)), "mw_set_forwarding")
+
+    def mw_relay(self, in_record: torch.Tensor, children: torch.Tensor, child_capacity_rows: int,
+                 stats: torch.Tensor):
+        _check(load().mw_relay(self._h, _ptr(in_record), _ptr(children), C.c_int64(child_capacity_rows),
+                               _ptr(stats), _stream()), "mw_relay")
+
+    def mw_get_relay_stats(self, stats: torch.Tensor) -> np.ndarray:
+        host = np.zeros(1, dtype=RELAY_STATS_DTYPE)
+        _check(load().mw_get_relay_stats(self._h, _ptr(stats), C.c_void_p(host.ctypes.data), _stream()),
+               "mw_get_relay_stats")
+        return host[0]
+
     # ---- simulation / statistics ---------------------------------------------------------
     def mw_sim_deliver(self, desc, stats, n_tokens, packed, row_src_token, row_topk, dst_rank,
                        desc_out, rows_out, src_token_out, topk_out, counts_out):
@@ -210,6 +236,29 @@ def peers_table(records: Sequence[dict], device) -> torch.Tensor:
         host[i] = (r["desc"].data_ptr(), r["n_desc"], r["n_rows"], r["rows"].data_ptr(),
                    r["row_src_token"].data_ptr(), r["row_topk"].data_ptr())
     return torch.from_numpy(host.view(np.uint8).reshape(-1)).to(device)
+
+
+class RelayChildren:
+    """Output buffers of mw_relay for n_hops children of `capacity` rows each."""
+
+    def __init__(self, ctx: Context, n_hops: int, capacity: int):
+        d, n = ctx.device, max(capacity, 1)
+        self.n_hops, self.capacity = n_hops, capacity
+        self.desc = [torch.zeros((n, DESC_BYTES), dtype=torch.uint8, device=d) for _ in range(n_hops)]
+        self.rows = [torch.zeros((n, ctx.row_bytes), dtype=torch.uint8, device=d) for _ in range(n_hops)]
+        self.row_src_token = [torch.full((n,), -1, dtype=torch.int32, device=d) for _ in range(n_hops)]
+        self.row_topk = [torch.zeros((n, ctx.top_k), dtype=torch.int32, device=d) for _ in range(n_hops)]
+        host = np.zeros(max(n_hops, 1), dtype=RELAY_CHILD_DTYPE)
+        for h in range(n_hops):
+            host[h] = (self.desc[h].data_ptr(), self.rows[h].data_ptr(), self.row_src_token[h].data_ptr(),
+                       self.row_topk[h].data_ptr())
+        self.table = torch.from_numpy(host.view(np.uint8).reshape(-1)).to(d)
+        self.stats = torch.zeros(RELAY_STATS_BYTES, dtype=torch.uint8, device=d)
+
+    def record(self, h: int, n_desc: int, n_rows: int) -> dict:
+        """Child h as a peer record (for peers_table / a further relay)."""
+        return dict(desc=self.desc[h], rows=self.rows[h], row_src_token=self.row_src_token[h],
+                    row_topk=self.row_topk[h], n_desc=n_desc, n_rows=n_rows)
 
 
 class SendBuffers:

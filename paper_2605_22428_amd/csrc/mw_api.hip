@@ -8,7 +8,8 @@
 namespace {
 
 struct ws_layout {
-    int64_t eslot, plan_cnt[2], plan_state[2], flags, cnt, base, row_base, addr_cnt, recs, hits, row_map, total;
+    int64_t eslot, plan_cnt[2], plan_state[2], flags, cnt, base, row_base, addr_cnt, recs, hits, row_map,
+        hop_bits, group_of_row, child_pos, total;
 };
 
 // Derived row geometry; returns a status.
@@ -48,6 +49,8 @@ int32_t validate(const mw_config *c, int32_t *n_local)
     if (c->my_rank < 0 || c->my_rank >= c->n_ranks) return MW_ERR_INVALID_ARG;
     if (c->n_experts > 0 && !c->expert_to_rank) return MW_ERR_INVALID_ARG;
     if (c->max_recv_rows > (int64_t)c->n_ranks * 65536) return MW_ERR_UNSUPPORTED;
+    if (c->max_hops < 0) return MW_ERR_INVALID_ARG;
+    if (c->max_hops > MW_MAX_HOPS) return MW_ERR_UNSUPPORTED;
     int32_t L = 0;
     for (int32_t e = 0; e < c->n_experts; ++e) {
         if (c->expert_to_rank[e] < 0 || c->expert_to_rank[e] >= c->n_ranks) return MW_ERR_INVALID_ARG;
@@ -76,6 +79,12 @@ ws_layout layout(const mw_config &c, int32_t L)
     w.recs = o;       o += mw_align_up((int64_t)sizeof(mw_row_rec) * (c.max_recv_rows > 0 ? c.max_recv_rows : 1), A);
     w.hits = o;       o += mw_align_up((int64_t)sizeof(mw_hit) * Kd * (c.max_recv_rows > 0 ? c.max_recv_rows : 1), A);
     w.row_map = o;    o += mw_align_up(4LL * (c.max_tokens > 0 ? c.max_tokens : 1), A);
+    w.hop_bits = w.group_of_row = w.child_pos = o;
+    if (c.max_hops > 0) {
+        w.hop_bits = o;     o += mw_align_up(8LL * MW_MASK_WORDS * MW_MAX_HOPS + 256, A);   // + relay flags
+        w.group_of_row = o; o += mw_align_up(4LL * ntok, A);
+        w.child_pos = o;    o += mw_align_up(4LL * MW_MAX_HOPS * ntok, A);
+    }
     w.total = o;
     return w;
 }
@@ -135,6 +144,11 @@ MW_API int32_t mw_ctx_create(const mw_config *cfg, void *workspace_dev, int64_t 
     ctx->d_addr_cnt = (uint32_t *)(b + w.addr_cnt);
     ctx->d_hits = (mw_hit *)(b + w.hits);
     ctx->d_row_map = (int32_t *)(b + w.row_map);
+    ctx->n_hops = 0;
+    ctx->d_hop_bits = (uint64_t *)(b + w.hop_bits);
+    ctx->d_relay_flags = (uint32_t *)(b + w.hop_bits + 8LL * MW_MASK_WORDS * MW_MAX_HOPS);
+    ctx->d_group_of_row = (int32_t *)(b + w.group_of_row);
+    ctx->d_child_pos = (uint32_t *)(b + w.child_pos);
 
     hipDeviceProp_t prop;
     if (hipGetDevice(&ctx->device) != hipSuccess || hipGetDeviceProperties(&prop, ctx->device) != hipSuccess) {
@@ -157,6 +171,7 @@ MW_API int32_t mw_ctx_create(const mw_config *cfg, void *workspace_dev, int64_t 
         ok = ok && hipMemset(ctx->d_plan_cnt[q], 0, 8u * (size_t)(cfg->max_tokens > 0 ? cfg->max_tokens : 1)) == hipSuccess;
         ok = ok && hipMemset(ctx->d_plan_state[q], 0, 4u * MW_PLAN_STATE_WORDS) == hipSuccess;
     }
+    if (cfg->max_hops > 0) ok = ok && hipMemset(ctx->d_relay_flags, 0, 256) == hipSuccess;
     ok = ok && hipDeviceSynchronize() == hipSuccess;
     if (!ok) { delete ctx; return MW_ERR_HIP; }
     *out = ctx;
@@ -281,6 +296,41 @@ MW_API int32_t mw_get_recv_stats(mw_ctx *ctx, const mw_recv_stats *stats_dev, mw
 {
     if (!ctx || !stats_dev || !host_out) return MW_ERR_INVALID_ARG;
     MW_HIP_CHECK(hipMemcpyAsync(host_out, stats_dev, sizeof(mw_recv_stats), hipMemcpyDeviceToHost, (hipStream_t)stream));
+    MW_HIP_CHECK(hipStreamSynchronize((hipStream_t)stream));
+    return MW_OK;
+}
+
+MW_API int32_t mw_set_forwarding(mw_ctx *ctx, const int32_t *next_hop, int32_t n_hops)
+{
+    if (!ctx || !next_hop) return MW_ERR_INVALID_ARG;
+    if (n_hops < 1) return MW_ERR_INVALID_ARG;
+    if (n_hops > ctx->cfg.max_hops) return MW_ERR_CAPACITY;
+    std::vector<uint64_t> bits((size_t)MW_MASK_WORDS * MW_MAX_HOPS, 0);
+    for (int32_t r = 0; r < ctx->cfg.n_ranks; ++r) {
+        const int32_t h = next_hop[r];
+        if (h < 0 || h >= n_hops) return MW_ERR_INVALID_ARG;
+        bits[(size_t)h * MW_MASK_WORDS + (r >> 6)] |= 1ull << (r & 63);
+    }
+    MW_HIP_CHECK(hipDeviceSynchronize());
+    MW_HIP_CHECK(hipMemcpy(ctx->d_hop_bits, bits.data(), bits.size() * sizeof(uint64_t), hipMemcpyHostToDevice));
+    MW_HIP_CHECK(hipDeviceSynchronize());
+    ctx->n_hops = n_hops;
+    return MW_OK;
+}
+
+MW_API int32_t mw_relay(mw_ctx *ctx, const mw_recv_peer *in_dev, const mw_relay_child *children_dev,
+                 int64_t child_capacity_rows, mw_relay_stats *stats_dev, void *stream)
+{
+    if (!ctx || !in_dev || !children_dev || !stats_dev || child_capacity_rows < 0) return MW_ERR_INVALID_ARG;
+    if (ctx->cfg.max_hops < 1 || ctx->n_hops < 1) return MW_ERR_INVALID_ARG;      // no forwarding table
+    if (child_capacity_rows > 0x7fffffffLL) return MW_ERR_UNSUPPORTED;
+    return mw_launch_relay(ctx, in_dev, children_dev, child_capacity_rows, stats_dev, (hipStream_t)stream);
+}
+
+MW_API int32_t mw_get_relay_stats(mw_ctx *ctx, const mw_relay_stats *stats_dev, mw_relay_stats *host_out, void *stream)
+{
+    if (!ctx || !stats_dev || !host_out) return MW_ERR_INVALID_ARG;
+    MW_HIP_CHECK(hipMemcpyAsync(host_out, stats_dev, sizeof(mw_relay_stats), hipMemcpyDeviceToHost, (hipStream_t)stream));
     MW_HIP_CHECK(hipStreamSynchronize((hipStream_t)stream));
     return MW_OK;
 }

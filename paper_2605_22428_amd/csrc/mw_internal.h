@@ -65,6 +65,12 @@ struct mw_ctx {
     uint32_t *d_addr_cnt;   // [R] rows of peer p whose group names this rank
     mw_hit *d_hits;         // [max_recv_rows][Kd]
     int32_t *d_row_map;     // [max_tokens] mw_sim_deliver: kept row -> sender row
+    // relay (only with cfg.max_hops > 0)
+    int32_t n_hops;         // 0 until mw_set_forwarding
+    uint64_t *d_hop_bits;   // [MW_MAX_HOPS][4] ranks served through each next hop
+    int32_t *d_group_of_row;// [max_tokens]
+    uint32_t *d_child_pos;  // [max_tokens][MW_MAX_HOPS] first child row of (group, hop) or kNoChild
+    uint32_t *d_relay_flags;// [1]
     // measurement hook: optional event pairs recorded around single kernels
     hipEvent_t ev_start[MW_KERNEL_COUNT];
     hipEvent_t ev_stop[MW_KERNEL_COUNT];
@@ -165,6 +171,8 @@ int32_t mw_launch_plan_allgather(mw_ctx *ctx, int64_t shard_bytes, mw_group_desc
 int32_t mw_launch_copy(mw_ctx *ctx, void *dst, const void *src, int64_t n_bytes, hipStream_t s);
 int32_t mw_launch_gather_shards(mw_ctx *ctx, const void *const *shards, int64_t shard_bytes, void *out,
                                 hipStream_t s);
+int32_t mw_launch_relay(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay_child *children, int64_t cap,
+                        mw_relay_stats *stats, hipStream_t s);
 int32_t mw_launch_sim_deliver(mw_ctx *ctx, const mw_group_desc *desc, const mw_send_stats *stats,
                               int32_t T, const void *rows, const int32_t *src_token, const int32_t *topk,
                               int32_t dst_rank, mw_group_desc *desc_out, void *rows_out,

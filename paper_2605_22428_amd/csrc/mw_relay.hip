@@ -1,0 +1,243 @@
+// Relay step: one node's part of the recursive MultiWrite execution model.
+//
+// Paper hooks: Section 4.3.3 -- a node holding a MultiWrite for a destination set M
+// partitions M by next hop and starts one child MultiWrite per subset, a subset of one
+// destination being an ordinary write; Section 4.1, "Local forwarding table" -- the next
+// hop of every destination comes from the node's unicast forwarding table and the number
+// of distinct next hops is the number of copies; Section 4.1, "Replication and
+// forwarding" -- each copy carries updated metadata naming only the destinations served
+// through its hop, so nothing is delivered twice; Section 3.2 -- the same-index device of
+// the remote server replicates a token to the targets inside that server.
+//
+// Two launches on the caller's stream:
+//   k_relay_index  workgroup h < n_hops builds child h's descriptor table: a group is kept
+//                  if its bitmap intersects the hop's rank set; kept groups are ranked with
+//                  block scans (group index, first row), so the child is in parent order
+//                  whatever the timing.  The (group, hop) -> first child row table feeds the
+//                  copy.  One more workgroup maps rows to groups (group starts marked, then a
+//                  running maximum) and does the byte accounting.
+//   k_relay_copy   one workgroup per input row, one 16-byte chunk per lane: the row is read
+//                  once and stored once per next hop that keeps its group (lane h of every
+//                  wave holds hop h's position; a ballot lists the hops).  Bound by HBM
+//                  bandwidth: rows * row_bytes read, rows * copies * row_bytes written.
+#include "mw_internal.h"
+
+namespace {
+
+constexpr int kBlock = 1024;
+constexpr uint32_t kNoChild = 0xffffffffu;
+constexpr uint32_t kCopyMaxRowBlocks = 32768;
+
+struct grp_view { uint64_t m[MW_MASK_WORDS]; uint32_t off, cnt; bool valid; };
+
+// Descriptor g of the input with its validity: a non-empty row range inside the buffer that
+// starts at or after the end of the previous descriptor's range.
+__device__ __forceinline__ grp_view load_group(const mw_group_desc *desc, uint32_t g, uint32_t G, uint32_t n_rows)
+{
+    grp_view v;
+#pragma unroll
+    for (int w = 0; w < MW_MASK_WORDS; ++w) v.m[w] = 0;
+    v.off = v.cnt = 0; v.valid = false;
+    if (g >= G) return v;
+    const mw_group_desc *d = desc + g;
+#pragma unroll
+    for (int w = 0; w < MW_MASK_WORDS; ++w) v.m[w] = d->mask[w];
+    v.off = d->row_offset; v.cnt = d->row_count;
+    uint64_t prev_end = 0;
+    if (g > 0) prev_end = (uint64_t)desc[g - 1].row_offset + desc[g - 1].row_count;
+    v.valid = v.cnt >= 1 && (uint64_t)v.off + v.cnt <= n_rows && v.off >= prev_end;
+    return v;
+}
+
+__global__ __launch_bounds__(kBlock) void k_relay_index(
+    const mw_recv_peer *__restrict__ in, const mw_relay_child *__restrict__ children, int n_hops, int n_ranks,
+    uint32_t max_tokens, uint32_t cap, uint64_t row_bytes, const uint64_t *__restrict__ hop_bits,
+    int32_t *__restrict__ group_of_row, uint32_t *__restrict__ child_pos, uint32_t *relay_flags,
+    mw_relay_stats *__restrict__ stats)
+{
+    __shared__ uint32_t scratch[17];
+    __shared__ uint32_t fit[2];                  // groups, rows of the child that fit its capacity
+    __shared__ unsigned long long acc[2];        // rows taken, rows * destinations
+    const uint32_t tid = threadIdx.x;
+    const mw_recv_peer src = in[0];
+    const uint32_t G = min(src.n_desc, max_tokens), n_rows = min(src.n_rows, max_tokens);
+    uint32_t err = (src.n_desc > max_tokens || src.n_rows > max_tokens) ? MW_FLAG_BAD_DESC : 0u;
+
+    if ((int)blockIdx.x < n_hops) {
+        // ---- child descriptor table of next hop h
+        const int h = blockIdx.x;
+        uint64_t hb[MW_MASK_WORDS];
+#pragma unroll
+        for (int w = 0; w < MW_MASK_WORDS; ++w) hb[w] = hop_bits[(size_t)h * MW_MASK_WORDS + w];
+        mw_group_desc *cdesc = children[h].desc;
+        if (tid < 2) fit[tid] = 0;
+        mw_lds_barrier();
+        uint32_t carry_g = 0, carry_r = 0;
+        for (uint32_t g0 = 0; g0 < G; g0 += kBlock) {
+            const uint32_t g = g0 + tid;
+            const grp_view v = load_group(src.desc, g, G, n_rows);
+            uint64_t sub[MW_MASK_WORDS];
+            uint32_t nd = 0;
+#pragma unroll
+            for (int w = 0; w < MW_MASK_WORDS; ++w) { sub[w] = v.m[w] & hb[w]; nd += (uint32_t)__popcll(sub[w]); }
+            const bool keep = v.valid && nd > 0;
+            uint32_t tot_g, tot_r;
+            const uint32_t cg = carry_g + mw_block_exscan(keep ? 1u : 0u, scratch, &tot_g);
+            const uint32_t cr = carry_r + mw_block_exscan(keep ? v.cnt : 0u, scratch, &tot_r);
+            if (g < G) {
+                uint32_t pos = kNoChild;
+                if (keep) {
+                    if ((uint64_t)cr + v.cnt <= cap) {
+                        mw_group_desc d;
+#pragma unroll
+                        for (int w = 0; w < MW_MASK_WORDS; ++w) d.mask[w] = sub[w];
+                        d.row_offset = cr; d.row_count = v.cnt; d.n_dest = nd; d.reserved0 = 0;
+                        cdesc[cg] = d;
+                        pos = cr;
+                        // kept groups that fit are a prefix of the kept groups: the largest
+                        // (index + 1, end row) pair describes the child
+                        atomicMax(&fit[0], cg + 1u);
+                        atomicMax(&fit[1], cr + v.cnt);
+                    } else {
+                        err |= MW_FLAG_OUT_CAPACITY;
+                    }
+                }
+                child_pos[(size_t)g * MW_MAX_HOPS + h] = pos;
+            }
+            carry_g += tot_g; carry_r += tot_r;
+        }
+        mw_lds_barrier();
+        if (tid == 0) { stats->groups_per_hop[h] = fit[0]; stats->rows_per_hop[h] = fit[1]; }
+    } else {
+        // ---- rows -> groups, accounting
+        if (tid < 2) acc[tid] = 0;
+        for (uint32_t i = tid; i < n_rows; i += kBlock) group_of_row[i] = -1;
+        __syncthreads();                         // (global memory is exchanged inside this workgroup)
+        uint64_t valid_ranks[MW_MASK_WORDS];
+#pragma unroll
+        for (int w = 0; w < MW_MASK_WORDS; ++w) {
+            const int lo = w * 64;
+            valid_ranks[w] = (n_ranks >= lo + 64) ? ~0ull : (n_ranks > lo ? ((1ull << (n_ranks - lo)) - 1ull) : 0ull);
+        }
+        unsigned long long rows_in = 0, dest_rows = 0;
+        uint32_t groups_in = 0;
+        for (uint32_t g = tid; g < G; g += kBlock) {
+            const grp_view v = load_group(src.desc, g, G, n_rows);
+            if (!v.valid) { err |= MW_FLAG_BAD_DESC; continue; }
+            uint32_t nd = 0;
+#pragma unroll
+            for (int w = 0; w < MW_MASK_WORDS; ++w) {
+                if (v.m[w] & ~valid_ranks[w]) err |= MW_FLAG_BAD_RANK;
+                nd += (uint32_t)__popcll(v.m[w] & valid_ranks[w]);
+            }
+            group_of_row[v.off] = (int32_t)g;
+            rows_in += v.cnt; dest_rows += (unsigned long long)v.cnt * nd; ++groups_in;
+        }
+        if (rows_in) atomicAdd(&acc[0], rows_in);            // integer sums: order-free
+        if (dest_rows) atomicAdd(&acc[1], dest_rows);
+        uint32_t tot_groups;
+        mw_block_exscan(groups_in, scratch, &tot_groups);
+        __syncthreads();
+        // running maximum of the marked group starts = group of every row (descriptor row
+        // ranges ascend); rows behind a group's end are filtered by the copy kernel
+        int32_t carry = -1;
+        for (uint32_t i0 = 0; i0 < n_rows; i0 += kBlock) {
+            const uint32_t i = i0 + tid;
+            int32_t v = (i < n_rows) ? group_of_row[i] : -1;
+            const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int32_t o = __shfl_up(v, d, 64);
+                if (lane >= d) v = max(v, o);
+            }
+            if (lane == 63) scratch[wave] = (uint32_t)v;
+            mw_lds_barrier();
+            int32_t before = carry;
+            for (int w = 0; w < wave; ++w) before = max(before, (int32_t)scratch[w]);
+            int32_t all = carry;
+            for (int w = 0; w < kBlock / 64; ++w) all = max(all, (int32_t)scratch[w]);
+            v = max(v, before);
+            if (i < n_rows) group_of_row[i] = v;
+            carry = all;
+            mw_lds_barrier();
+        }
+        if (tid == 0) {
+            stats->n_groups_in = tot_groups;
+            stats->n_rows_in = (uint32_t)acc[0];
+            stats->unicast_bytes = (uint64_t)acc[1] * row_bytes;
+            stats->reserved0 = 0;
+        }
+        for (int h = n_hops + tid; h < MW_MAX_HOPS; h += kBlock) { stats->groups_per_hop[h] = 0; stats->rows_per_hop[h] = 0; }
+    }
+    if (err) atomicOr(relay_flags, err);
+}
+
+// blockIdx.x walks input rows, blockIdx.y the segments of blockDim.x chunks of a row.
+__global__ __launch_bounds__(1024) void k_relay_copy(
+    const mw_recv_peer *__restrict__ in, const mw_relay_child *__restrict__ children, int n_hops, int K, int n_chunks,
+    uint32_t max_tokens, uint64_t row_bytes, const int32_t *__restrict__ group_of_row,
+    const uint32_t *__restrict__ child_pos, uint32_t *relay_flags, mw_relay_stats *__restrict__ stats)
+{
+    const mw_recv_peer src = in[0];
+    const uint32_t n_rows = min(src.n_rows, max_tokens);
+    const int c = blockIdx.y * blockDim.x + threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    for (uint32_t i = blockIdx.x; i < n_rows; i += gridDim.x) {
+        const int32_t g = group_of_row[i];
+        if (g < 0) continue;
+        const uint32_t off = i - src.desc[g].row_offset;
+        if (off >= src.desc[g].row_count) continue;          // behind its group's end: in no valid group
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (c < n_chunks) v = mw_ld16((const u32x4 *)src.rows + (size_t)i * n_chunks + c);
+        const uint32_t p = (lane < n_hops) ? child_pos[(size_t)g * MW_MAX_HOPS + lane] : kNoChild;
+        const int32_t st = src.row_src_token[i];
+        int32_t tk = 0;
+        if ((int)threadIdx.x < K && blockIdx.y == 0) tk = src.row_topk[(size_t)i * K + threadIdx.x];
+        uint64_t hops = __ballot(p != kNoChild);              // the same in every wave
+        while (hops) {
+            const int h = __ffsll((unsigned long long)hops) - 1;
+            hops &= hops - 1;
+            const uint32_t dst = (uint32_t)__shfl((int)p, h, 64) + off;
+            const mw_relay_child ch = children[h];
+            if (c < n_chunks) mw_st16((u32x4 *)ch.rows + (size_t)dst * n_chunks + c, v);
+            if (blockIdx.y == 0) {
+                if (threadIdx.x == 0) ch.row_src_token[dst] = st;
+                if ((int)threadIdx.x < K) ch.row_topk[(size_t)dst * K + threadIdx.x] = tk;
+            }
+        }
+    }
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+        unsigned long long rows_out = 0;
+        for (int h = 0; h < n_hops; ++h) rows_out += stats->rows_per_hop[h];
+        stats->forward_bytes = rows_out * row_bytes;
+        stats->error_flags = __hip_atomic_load(relay_flags, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(relay_flags, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next relay
+    }
+}
+
+}  // namespace
+
+int32_t mw_launch_relay(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay_child *children, int64_t cap,
+                        mw_relay_stats *stats, hipStream_t s)
+{
+    const mw_config &c = ctx->cfg;
+    const int n_chunks = (int)(ctx->row_bytes / 16);
+    {
+        mw_timed tm(ctx, MW_KERNEL_RELAY_INDEX, s);
+        hipLaunchKernelGGL(k_relay_index, dim3(ctx->n_hops + 1), dim3(kBlock), 0, s, in, children, ctx->n_hops,
+                           c.n_ranks, (uint32_t)c.max_tokens, (uint32_t)cap, (uint64_t)ctx->row_bytes,
+                           ctx->d_hop_bits, ctx->d_group_of_row, ctx->d_child_pos, ctx->d_relay_flags, stats);
+    }
+    {
+        int bs, nseg;
+        mw_row_block_shape(n_chunks, &bs, &nseg);
+        uint32_t gx = (uint32_t)c.max_tokens < kCopyMaxRowBlocks ? (uint32_t)c.max_tokens : kCopyMaxRowBlocks;
+        if (gx < 1) gx = 1;
+        mw_timed tm(ctx, MW_KERNEL_RELAY_COPY, s);
+        hipLaunchKernelGGL(k_relay_copy, dim3(gx, nseg), dim3(bs), 0, s, in, children, ctx->n_hops, c.top_k, n_chunks,
+                           (uint32_t)c.max_tokens, (uint64_t)ctx->row_bytes, ctx->d_group_of_row, ctx->d_child_pos,
+                           ctx->d_relay_flags, stats);
+    }
+    MW_HIP_CHECK(hipGetLastError());
+    return MW_OK;
+}

@@ -40,6 +40,8 @@ def test_record_layouts_match_the_header():
 int main(void) {
   printf("%zu %zu %zu %zu %zu\n", sizeof(mw_group_desc), sizeof(mw_send_stats), sizeof(mw_recv_stats),
          sizeof(mw_recv_peer), sizeof(mw_config));
+  printf("%zu %zu %zu %zu\n", sizeof(mw_relay_child), sizeof(mw_relay_stats), offsetof(mw_relay_stats, rows_per_hop),
+         offsetof(mw_relay_stats, error_flags));
   printf("%zu %zu %zu\n", offsetof(mw_group_desc, row_offset), offsetof(mw_group_desc, n_dest),
          offsetof(mw_send_stats, rows_per_dest));
   printf("%zu %zu %zu %zu\n", offsetof(mw_send_stats, error_flags), offsetof(mw_recv_peer, rows),
@@ -54,6 +56,9 @@ int main(void) {
         out = subprocess.check_output([exe]).decode().split()
     vals = [int(v) for v in out]
     assert vals[:5] == [48, 1056, 24, 40, C.sizeof(B.MwConfig)]
+    assert vals[5:9] == [32, 544, B.RELAY_STATS_DTYPE.fields["rows_per_hop"][1],
+                         B.RELAY_STATS_DTYPE.fields["error_flags"][1]]
+    vals = vals[:5] + vals[9:]
     assert vals[5:8] == [B.DESC_DTYPE.fields["row_offset"][1], B.DESC_DTYPE.fields["n_dest"][1],
                          B.SEND_STATS_DTYPE.fields["rows_per_dest"][1]]
     assert vals[8:] == [B.SEND_STATS_DTYPE.fields["error_flags"][1], B.RECV_PEER_DTYPE.fields["rows"][1],
@@ -63,7 +68,7 @@ int main(void) {
 def _cfg(**kw):
     e2r = np.arange(16, dtype=np.int32) // 2
     base = dict(n_ranks=8, n_experts=16, top_k=2, my_rank=0, hidden=256, row_format=B.MW_ROW_BF16,
-                row_bytes=0, max_tokens=128, reserved0=0, max_recv_rows=1024,
+                row_bytes=0, max_tokens=128, max_hops=0, max_recv_rows=1024,
                 expert_to_rank=e2r.ctypes.data)
     base.update(kw)
     return B.MwConfig(**base), e2r
@@ -85,6 +90,9 @@ def test_workspace_query_and_validation(lib):
                      (dict(row_format=B.MW_ROW_BYTES, row_bytes=2 << 20), B.MW_OK),
                      (dict(row_bytes=100), B.MW_ERR_INVALID_ARG),         # contradicts the bf16 row size
                      (dict(max_tokens=1 << 20), B.MW_ERR_UNSUPPORTED),
+                     (dict(max_hops=65), B.MW_ERR_UNSUPPORTED),
+                     (dict(max_hops=-1), B.MW_ERR_INVALID_ARG),
+                     (dict(max_hops=16), B.MW_OK),
                      (dict(expert_to_rank=0), B.MW_ERR_INVALID_ARG)]:
         cfg, keep = _cfg(**kw)
         assert lib.mw_workspace_bytes(C.byref(cfg), C.byref(need)) == want, kw
