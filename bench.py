@@ -67,7 +67,7 @@ def main() -> int:
 
     # ---------------------------------------------------------------- set-up (untimed)
     t_setup = time.time()
-    ctx = B.Context(R, w.n_experts, K, my_rank, w.hidden, B.MW_ROW_BF16, T, R * T, e2r, device=dev)
+    ctx = B.Context(R, w.n_experts, K, my_rank, w.hidden, B.MW_ROW_BF16, T, R * T, e2r, device=dev, max_hops=16)
     topks = W.topk_ids_many(w, seed, range(R))
     x_me, _ = W.payload_rows(w, seed, my_rank)
     topk_d = up(topks[my_rank])
@@ -239,6 +239,43 @@ def main() -> int:
     copy_gbps = 2 * n_copy / copy_ms / 1e6
     del src, dsts
 
+    # ---------------------------------------------------------------- relay step (extra, untimed region)
+    # This rank as the first relay of its own packed buffer in a two-level topology: 8 servers
+    # of 8 devices, direct links inside the server, one link per remote server (to its
+    # same-index device).  One read of every row, one write per distinct next hop.
+    n_per = 8
+    next_hop = np.array([(r % n_per) if r // n_per == my_rank // n_per else n_per + (r // n_per) -
+                         (1 if r // n_per > my_rank // n_per else 0) for r in range(R)], dtype=np.int32)
+    n_hops = n_per + R // n_per - 1
+    ctx.mw_set_forwarding(next_hop, n_hops)
+    children = B.RelayChildren(ctx, n_hops, T)
+    sd0 = sets[0]["send"]
+    in_rec = B.peers_table([dict(desc=sd0.desc, rows=sd0.packed, row_src_token=sd0.row_src_token,
+                                 row_topk=sd0.row_topk, n_desc=int(st["n_groups"]), n_rows=N)], dev)
+    relay_names = {"relay_index": B.MW_KERNEL_RELAY_INDEX, "relay_copy": B.MW_KERNEL_RELAY_COPY}
+    n_r = 20
+    evr = {k: new_events(n_r) for k in relay_names}
+    for i in range(n_r + 3):
+        if i >= 3:
+            for k, code in relay_names.items():
+                ctx.mw_ctx_set_timing_events(code, *evr[k][i - 3])
+        ctx.mw_relay(in_rec, children.table, T, children.stats)
+    torch.cuda.synchronize()
+    for code in relay_names.values():
+        ctx.mw_ctx_set_timing_events(code, None, None)
+    rst = ctx.mw_get_relay_stats(children.stats)
+    assert int(rst["error_flags"]) == 0 and int(rst["n_rows_in"]) == N
+    relay_us = {k: 1e3 * sum(a.elapsed_time(b) for a, b in evr[k]) / n_r for k in relay_names}
+    rows_fwd = int(rst["forward_bytes"]) // rb
+    relay_bytes = N * rb + rows_fwd * rb + N * (4 + 4 * K) + rows_fwd * (4 + 4 * K)
+    relay = {"workload": "rank 0 relays its own C1 packed buffer: 8 servers x 8 devices, %d next hops" % n_hops,
+             "us": {k: round(v, 2) for k, v in relay_us.items()},
+             "copies_per_row": round(rows_fwd / N, 4),
+             "bytes_saved_vs_unicast": round(1.0 - int(rst["forward_bytes"]) / int(rst["unicast_bytes"]), 4),
+             "copy_bytes": relay_bytes, "copy_GBps": round(relay_bytes / relay_us["relay_copy"] / 1e3, 1),
+             "copy_pct_of_hbm_peak": round(100.0 * relay_bytes / relay_us["relay_copy"] / 1e3 / HBM_PEAK_GBPS, 2)}
+    del children
+
     # ---------------------------------------------------------------- algorithmic bytes
     pack_bytes = 2 * N * rb + N * (4 + 4 * K) + N * 4 + N * 4 * K
     unpack_bytes = M * rb + Q * rb + M * (4 + 4 * K) + n_desc_total * 48 + Q * 8 + (L + 1) * 8
@@ -276,6 +313,7 @@ def main() -> int:
                              "GBps": round((pack_bytes + unpack_bytes) / pu_us / 1e3, 1),
                              "pct_of_hbm_peak": round(100.0 * (pack_bytes + unpack_bytes) / pu_us / 1e3 / HBM_PEAK_GBPS, 2)},
         "copy_ceiling": {"GBps": round(copy_gbps, 1), "bytes": 2 * n_copy},
+        "relay": relay,
         "roofline": {"kernel": "k_expand", "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": traffic, "bytes_per_launch": expand_bytes,
