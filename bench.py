@@ -1,12 +1,16 @@
 #!/usr/bin/env python3
 """Benchmark of the MultiWrite dispatch hot path on one MI355X.
 
-A step is one pass of the whole path over one batch of the DeepSeek-V3-shaped dispatch
-workload (64 simulated ranks, 256 experts, top-8 with group-limited routing, 4096 tokens
-of 7168 bf16 on this rank; 64 peer receive regions): mw_plan -> mw_pack -> mw_unpack,
-all through the C ABI, inputs resident in HBM.  Prints ONE JSON line.
+A step is one pass of the whole path over one batch: mw_plan -> mw_pack -> mw_unpack, all
+through the C ABI, inputs resident in HBM.  The default workload is the DeepSeek-V3-shaped
+dispatch (64 simulated ranks, 256 experts, top-8 with group-limited routing, 4096 tokens of
+7168 bf16 on this rank; 64 peer receive regions).  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c0|c1|c2|c3|c4]
+                  [--schedule aligned|free|single] [--no-cpu-baseline]
+
+The other workloads (tiny, fp8, 256-rank Zipf, AllGather) are parity-test configurations;
+they can be timed with the same harness for the per-configuration table in the design doc.
 """
 from __future__ import annotations
 
@@ -22,42 +26,75 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 N_SETS = 3                      # rotating buffer sets (> 1 GB touched per step, MALL is 256 MB)
+METRIC = "dispatch pack+unpack HBM GB/s (% of peak) + bytes saved vs unicast, 1 GPU"
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--schedule", choices=["aligned", "free", "single"], default="aligned",
-                    help="how the send side and the receive side of a step are issued (see step())")
-    ap.add_argument("--seed", type=int, default=None)
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (the other ranks of the dispatch are "
-              "simulated); --gpus %d is not supported" % args.gpus, file=sys.stderr)
-        return 2
+def new_events(torch, n):
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    for a, b in ev:          # torch creates the handles on first record
+        a.record(); b.record()
+    torch.cuda.synchronize()
+    return ev
 
+
+def copy_ceiling(torch, B, n_bytes, dev):
+    """Plain streaming copy of n_bytes with the library's own copy kernel (GB/s read + written)."""
+    n_copy = max(16, (n_bytes // 16) * 16)
+    src = torch.empty(n_copy, dtype=torch.uint8, device=dev)
+    dsts = [torch.empty(n_copy, dtype=torch.uint8, device=dev) for _ in range(2)]
+    evc = new_events(torch, 20)
+    for i in range(25):
+        if i >= 5:
+            evc[i - 5][0].record()
+        B.mw_copy_bytes(dsts[i % 2], src, n_copy)
+        if i >= 5:
+            evc[i - 5][1].record()
+    torch.cuda.synchronize()
+    copy_ms = sum(a.elapsed_time(b) for a, b in evc) / len(evc)
+    return {"GBps": round(2 * n_copy / copy_ms / 1e6, 1), "bytes": 2 * n_copy}
+
+
+def traffic_from_profile(kernel: str, workload: str):
+    """HBM bytes per launch from the committed rocprofv3 counter summary (FETCH_SIZE and
+    WRITE_SIZE runs of this same command, scaled by what the plain copy kernel reads)."""
+    path = os.path.join(ROOT, "profiles", "%s_%s_hbm_traffic.md" % (kernel, workload))
+    if os.path.exists(path):
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch %s:" % kernel):
+                return int(line.split(":")[1])
+    return None
+
+
+# ------------------------------------------------------------------------------------------ dispatch
+def bench_dispatch(args, name: str) -> dict:
     import numpy as np
     import torch
     from paper_2605_22428_amd import binding as B
     from paper_2605_22428_amd import workloads as W
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 2
     dev = "cuda:0"
-    torch.cuda.set_device(0)
-    w, my_rank = W.C1, 0
     seed = W.BASE_SEED if args.seed is None else args.seed
+    w = {"c0": W.C0, "c1": W.C1, "c2": W.C2, "c3": W.C3}[name]
+    my_rank = W.zipf_median_rank(w, seed) if name == "c3" else 0
+    describe = {
+        "c0": "C0 tiny dispatch: 8 simulated ranks, 16 experts, top-2 uniform, 128 tokens x 256 bf16, 8 peer "
+              "receive regions (launch-latency bound, cache resident: its % of peak is not meaningful)",
+        "c1": "C1 DeepSeek-V3-shaped dispatch: 64 simulated ranks, 256 experts, top-8 group-limited (<=4 of 8 "
+              "nodes), 4096 tokens x 7168 bf16 on this rank, 64 peer receive regions",
+        "c2": "C2 = C1 with fp8 e4m3 payload + one fp32 scale per 128 elements (7392-byte rows)",
+        "c3": "C3 large-EP skewed dispatch: 256 simulated ranks, 256 experts (1 per rank), 8192 tokens x 7168 "
+              "bf16, top-8 Zipf(1.1); receive side at the rank of the median-popularity expert",
+    }[name]
     R, K, T, rb = w.n_ranks, w.top_k, w.n_tokens, w.row_bytes
     e2r = W.expert_to_rank(w)
     L = w.experts_per_rank
+    fp8 = w.row_format == "fp8"
+    fmt = B.MW_ROW_FP8_E4M3_BLOCK128 if fp8 else B.MW_ROW_BF16
+    xdt = torch.uint8 if fp8 else torch.int16
 
     def up(a):
         a = np.ascontiguousarray(a)
@@ -67,64 +104,67 @@ def main() -> int:
 
     # ---------------------------------------------------------------- set-up (untimed)
     t_setup = time.time()
-    ctx = B.Context(R, w.n_experts, K, my_rank, w.hidden, B.MW_ROW_BF16, T, R * T, e2r, device=dev, max_hops=16)
+    ctx = B.Context(R, w.n_experts, K, my_rank, w.hidden, fmt, T, R * T, e2r, device=dev, max_hops=16)
     topks = W.topk_ids_many(w, seed, range(R))
-    x_me, _ = W.payload_rows(w, seed, my_rank)
+    x_me, s_me = W.payload_rows(w, seed, my_rank)
     topk_d = up(topks[my_rank])
     log("[bench] routing and local payload drawn in %.1fs" % (time.time() - t_setup))
 
     # peer receive regions: every simulated peer's plan + pack + delivery runs on the GPU too
-    x_peer = torch.zeros((T, w.hidden), dtype=torch.int16, device=dev)
+    x_peer = torch.zeros((T, w.hidden), dtype=xdt, device=dev)
+    s_peer = torch.zeros((T, w.hidden // 128), dtype=torch.float32, device=dev) if fp8 else None
     sb = B.SendBuffers(ctx, T)
+    out = dict(desc=torch.zeros((T, B.DESC_BYTES), dtype=torch.uint8, device=dev),
+               rows=torch.zeros((T, rb), dtype=torch.uint8, device=dev),
+               row_src_token=torch.zeros(T, dtype=torch.int32, device=dev),
+               row_topk=torch.zeros((T, K), dtype=torch.int32, device=dev))
+    counts = torch.zeros(2, dtype=torch.int32, device=dev)
     recs = []
     for p in range(R):
         tokens = W.tokens_for_rank(w, topks[p], my_rank)
-        rows, _ = W.payload_rows(w, seed, p, tokens)
+        rows, sc = W.payload_rows(w, seed, p, tokens)
+        idx = torch.from_numpy(tokens).to(dev)
         x_peer.zero_()
-        x_peer[torch.from_numpy(tokens).to(dev)] = up(rows)
+        x_peer[idx] = up(rows).view(xdt)
+        if fp8:
+            s_peer.zero_()
+            s_peer[idx] = up(sc)
         tk_d = up(topks[p])
         ctx.mw_plan(tk_d, sb.mask, sb.perm, sb.desc, sb.stats)
-        ctx.mw_pack(x_peer, None, tk_d, sb.perm, sb.stats, sb.packed, sb.row_src_token, sb.row_topk)
-        out = dict(desc=torch.zeros((T, B.DESC_BYTES), dtype=torch.uint8, device=dev),
-                   rows=torch.zeros((T, rb), dtype=torch.uint8, device=dev),
-                   row_src_token=torch.zeros(T, dtype=torch.int32, device=dev),
-                   row_topk=torch.zeros((T, K), dtype=torch.int32, device=dev))
-        counts = torch.zeros(2, dtype=torch.int32, device=dev)
+        ctx.mw_pack(x_peer, s_peer, tk_d, sb.perm, sb.stats, sb.packed, sb.row_src_token, sb.row_topk)
         ctx.mw_sim_deliver(sb.desc, sb.stats, T, sb.packed, sb.row_src_token, sb.row_topk, my_rank,
                            out["desc"], out["rows"], out["row_src_token"], out["row_topk"], counts)
         g, n = (int(v) for v in counts.cpu().numpy())
         recs.append(dict(desc=out["desc"][:max(g, 1)].clone(), rows=out["rows"][:max(n, 1)].clone(),
                          row_src_token=out["row_src_token"][:max(n, 1)].clone(),
                          row_topk=out["row_topk"][:max(n, 1)].clone(), n_desc=g, n_rows=n))
-    del x_peer, out
+    del x_peer, s_peer, out
     M = sum(r["n_rows"] for r in recs)
     n_desc_total = sum(r["n_desc"] for r in recs)
-    cap = M * min(K, L)
+    cap = max(1, M * min(K, L))
 
     sets = []
     for s in range(N_SETS):
         rs = [dict(desc=r["desc"].clone(), rows=r["rows"].clone(), row_src_token=r["row_src_token"].clone(),
                    row_topk=r["row_topk"].clone(), n_desc=r["n_desc"], n_rows=r["n_rows"]) for r in recs]
-        sets.append(dict(x=up(x_me), send=B.SendBuffers(ctx, T), recs=rs, table=B.peers_table(rs, dev),
-                         recv=B.RecvBuffers(ctx, cap)))
+        sets.append(dict(x=up(x_me).view(xdt), sc=up(s_me) if fp8 else None, send=B.SendBuffers(ctx, T), recs=rs,
+                         table=B.peers_table(rs, dev), recv=B.RecvBuffers(ctx, cap)))
     del recs
     torch.cuda.synchronize()
     log("[bench] %d peer regions built on the GPU, M=%d rows; set-up %.1fs" % (R, M, time.time() - t_setup))
 
     # The send side (plan, pack of this rank's tokens) and the receive side (unpack of what the
-    # peers sent) are independent operations on disjoint buffers and disjoint workspace; by
-    # default they are issued on two streams of default priority, so the latency-bound plan
-    # runs under the expander instead of in front of it.
+    # peers sent) are independent operations on disjoint buffers and disjoint workspace.
     s_send, s_recv = torch.cuda.Stream(), torch.cuda.Stream()
 
     def send_side(s):
         sd = s["send"]
         ctx.mw_plan(topk_d, sd.mask, sd.perm, sd.desc, sd.stats)
-        ctx.mw_pack(s["x"], None, topk_d, sd.perm, sd.stats, sd.packed, sd.row_src_token, sd.row_topk)
+        ctx.mw_pack(s["x"], s["sc"], topk_d, sd.perm, sd.stats, sd.packed, sd.row_src_token, sd.row_topk)
 
     def recv_side(s):
         rv = s["recv"]
-        ctx.mw_unpack(s["table"], R, rv.out_rows, None, cap, rv.out_src_peer, rv.out_src_token,
+        ctx.mw_unpack(s["table"], R, rv.out_rows, rv.out_scales, cap, rv.out_src_peer, rv.out_src_token,
                       rv.expert_offsets, rv.stats)
 
     # Default schedule ("aligned"): two streams and one cross-stream wait per step.  The packer
@@ -153,17 +193,10 @@ def main() -> int:
                 ctx.mw_plan(topk_d, sd.mask, sd.perm, sd.desc, sd.stats)
                 if n > 0:
                     s_send.wait_event(ev_unpack_done[(n - 1) % 2])
-                ctx.mw_pack(s["x"], None, topk_d, sd.perm, sd.stats, sd.packed, sd.row_src_token, sd.row_topk)
+                ctx.mw_pack(s["x"], s["sc"], topk_d, sd.perm, sd.stats, sd.packed, sd.row_src_token, sd.row_topk)
             with torch.cuda.stream(s_recv):
                 recv_side(s)
                 ev_unpack_done[n % 2].record(s_recv)
-
-    def new_events(n):
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
-        for a, b in ev:          # torch creates the handles on first record
-            a.record(); b.record()
-        torch.cuda.synchronize()
-        return ev
 
     # ---------------------------------------------------------------- warm-up, then the timed region
     for i in range(args.warmup):
@@ -177,7 +210,7 @@ def main() -> int:
     # An event pair costs a few microseconds of bubble on this platform, so the expander is
     # bracketed on every EV_STRIDE-th step of the timed region only.
     EV_STRIDE = 4
-    ev_expand = new_events((args.steps + EV_STRIDE - 1) // EV_STRIDE)
+    ev_expand = new_events(torch, (args.steps + EV_STRIDE - 1) // EV_STRIDE)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -193,27 +226,23 @@ def main() -> int:
     expand_ms = sorted(a.elapsed_time(b) for a, b in ev_expand)
     expand_avg_ms = sum(expand_ms) / len(expand_ms)
 
-    # one stream, for reference
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i, "single")
-    torch.cuda.synchronize()
-    ms_single = (time.perf_counter() - t0) * 1e3 / args.steps
-    # two streams left to drift, for reference
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i, "free")
-    torch.cuda.synchronize()
-    ms_free = (time.perf_counter() - t0) * 1e3 / args.steps
+    other = {}
+    for sched in ("single", "free", "aligned"):      # the other schedules, for reference
+        if sched == args.schedule:
+            continue
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(i, sched)
+        torch.cuda.synchronize()
+        other[sched] = round((time.perf_counter() - t0) * 1e3 / args.steps, 4)
 
     # ---------------------------------------------------------------- per-kernel breakdown (one stream, untimed)
     names = {"plan_rank": B.MW_KERNEL_PLAN_RANK,
              "plan_groups": B.MW_KERNEL_PLAN_GROUPS, "pack": B.MW_KERNEL_PACK,
              "recv_index": B.MW_KERNEL_RECV_INDEX, "expand": B.MW_KERNEL_EXPAND}
     n_b = min(args.steps, 50)
-    evs = {k: new_events(n_b) for k in names}
+    evs = {k: new_events(torch, n_b) for k in names}
     for i in range(n_b):
         for k, code in names.items():
             ctx.mw_ctx_set_timing_events(code, *evs[k][i])
@@ -223,58 +252,47 @@ def main() -> int:
         ctx.mw_ctx_set_timing_events(code, None, None)
     kern_us = {k: 1e3 * sum(a.elapsed_time(b) for a, b in evs[k]) / n_b for k in names}
 
-    # plain copy ceiling on the same amount of data as one expand launch
-    n_copy = (M * rb // 16) * 16
-    src = torch.empty(n_copy, dtype=torch.uint8, device=dev)
-    dsts = [torch.empty(n_copy, dtype=torch.uint8, device=dev) for _ in range(2)]
-    evc = new_events(20)
-    for i in range(25):
-        if i >= 5:
-            evc[i - 5][0].record()
-        B.mw_copy_bytes(dsts[i % 2], src, n_copy)
-        if i >= 5:
-            evc[i - 5][1].record()
-    torch.cuda.synchronize()
-    copy_ms = sum(a.elapsed_time(b) for a, b in evc) / len(evc)
-    copy_gbps = 2 * n_copy / copy_ms / 1e6
-    del src, dsts
+    ceiling = copy_ceiling(torch, B, M * rb, dev)    # plain copy of as many bytes as one expand launch reads
 
     # ---------------------------------------------------------------- relay step (extra, untimed region)
-    # This rank as the first relay of its own packed buffer in a two-level topology: 8 servers
+    # This rank as the first relay of its own packed buffer in a two-level topology: servers
     # of 8 devices, direct links inside the server, one link per remote server (to its
     # same-index device).  One read of every row, one write per distinct next hop.
-    n_per = 8
-    next_hop = np.array([(r % n_per) if r // n_per == my_rank // n_per else n_per + (r // n_per) -
-                         (1 if r // n_per > my_rank // n_per else 0) for r in range(R)], dtype=np.int32)
-    n_hops = n_per + R // n_per - 1
-    ctx.mw_set_forwarding(next_hop, n_hops)
-    children = B.RelayChildren(ctx, n_hops, T)
-    sd0 = sets[0]["send"]
-    in_rec = B.peers_table([dict(desc=sd0.desc, rows=sd0.packed, row_src_token=sd0.row_src_token,
-                                 row_topk=sd0.row_topk, n_desc=int(st["n_groups"]), n_rows=N)], dev)
-    relay_names = {"relay_index": B.MW_KERNEL_RELAY_INDEX, "relay_copy": B.MW_KERNEL_RELAY_COPY}
-    n_r = 20
-    evr = {k: new_events(n_r) for k in relay_names}
-    for i in range(n_r + 3):
-        if i >= 3:
-            for k, code in relay_names.items():
-                ctx.mw_ctx_set_timing_events(code, *evr[k][i - 3])
-        ctx.mw_relay(in_rec, children.table, T, children.stats)
-    torch.cuda.synchronize()
-    for code in relay_names.values():
-        ctx.mw_ctx_set_timing_events(code, None, None)
-    rst = ctx.mw_get_relay_stats(children.stats)
-    assert int(rst["error_flags"]) == 0 and int(rst["n_rows_in"]) == N
-    relay_us = {k: 1e3 * sum(a.elapsed_time(b) for a, b in evr[k]) / n_r for k in relay_names}
-    rows_fwd = int(rst["forward_bytes"]) // rb
-    relay_bytes = N * rb + rows_fwd * rb + N * (4 + 4 * K) + rows_fwd * (4 + 4 * K)
-    relay = {"workload": "rank 0 relays its own C1 packed buffer: 8 servers x 8 devices, %d next hops" % n_hops,
-             "us": {k: round(v, 2) for k, v in relay_us.items()},
-             "copies_per_row": round(rows_fwd / N, 4),
-             "bytes_saved_vs_unicast": round(1.0 - int(rst["forward_bytes"]) / int(rst["unicast_bytes"]), 4),
-             "copy_bytes": relay_bytes, "copy_GBps": round(relay_bytes / relay_us["relay_copy"] / 1e3, 1),
-             "copy_pct_of_hbm_peak": round(100.0 * relay_bytes / relay_us["relay_copy"] / 1e3 / HBM_PEAK_GBPS, 2)}
-    del children
+    relay = None
+    if name in ("c1", "c2"):
+        n_per = 8
+        next_hop = np.array([(r % n_per) if r // n_per == my_rank // n_per else n_per + (r // n_per) -
+                             (1 if r // n_per > my_rank // n_per else 0) for r in range(R)], dtype=np.int32)
+        n_hops = n_per + R // n_per - 1
+        ctx.mw_set_forwarding(next_hop, n_hops)
+        children = B.RelayChildren(ctx, n_hops, T)
+        sd0 = sets[0]["send"]
+        in_rec = B.peers_table([dict(desc=sd0.desc, rows=sd0.packed, row_src_token=sd0.row_src_token,
+                                     row_topk=sd0.row_topk, n_desc=int(st["n_groups"]), n_rows=N)], dev)
+        relay_names = {"relay_index": B.MW_KERNEL_RELAY_INDEX, "relay_copy": B.MW_KERNEL_RELAY_COPY}
+        n_r = 20
+        evr = {k: new_events(torch, n_r) for k in relay_names}
+        for i in range(n_r + 3):
+            if i >= 3:
+                for k, code in relay_names.items():
+                    ctx.mw_ctx_set_timing_events(code, *evr[k][i - 3])
+            ctx.mw_relay(in_rec, children.table, T, children.stats)
+        torch.cuda.synchronize()
+        for code in relay_names.values():
+            ctx.mw_ctx_set_timing_events(code, None, None)
+        rst = ctx.mw_get_relay_stats(children.stats)
+        assert int(rst["error_flags"]) == 0 and int(rst["n_rows_in"]) == N
+        relay_us = {k: 1e3 * sum(a.elapsed_time(b) for a, b in evr[k]) / n_r for k in relay_names}
+        rows_fwd = int(rst["forward_bytes"]) // rb
+        relay_bytes = N * rb + rows_fwd * rb + N * (4 + 4 * K) + rows_fwd * (4 + 4 * K)
+        relay = {"workload": "rank 0 relays its own packed buffer: %d servers x 8 devices, %d next hops"
+                             % (R // n_per, n_hops),
+                 "us": {k: round(v, 2) for k, v in relay_us.items()},
+                 "copies_per_row": round(rows_fwd / N, 4),
+                 "bytes_saved_vs_unicast": round(1.0 - int(rst["forward_bytes"]) / int(rst["unicast_bytes"]), 4),
+                 "copy_bytes": relay_bytes, "copy_GBps": round(relay_bytes / relay_us["relay_copy"] / 1e3, 1),
+                 "copy_pct_of_hbm_peak": round(100.0 * relay_bytes / relay_us["relay_copy"] / 1e3 / HBM_PEAK_GBPS, 2)}
+        del children
 
     # ---------------------------------------------------------------- algorithmic bytes
     pack_bytes = 2 * N * rb + N * (4 + 4 * K) + N * 4 + N * 4 * K
@@ -285,26 +303,16 @@ def main() -> int:
     pu_us = kern_us["pack"] + kern_us["recv_index"] + kern_us["expand"]
     saved = 1.0 - int(st["multicast_bytes"]) / int(st["unicast_bytes"])
 
-    # HBM bytes per expander launch from the committed rocprofv3 counter summary (FETCH_SIZE and
-    # WRITE_SIZE runs of this same command, scaled by what the plain copy kernel reads)
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "k_expand_C1_hbm_traffic.md")
-    if os.path.exists(tpath):
-        for line in open(tpath):
-            if line.startswith("traffic_bytes_per_launch k_expand:"):
-                traffic = int(line.split(":")[1])
-
     result = {
-        "metric": "dispatch pack+unpack HBM GB/s (% of peak) + bytes saved vs unicast, 1 GPU",
+        "metric": METRIC,
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u8", "data": "synthetic",
-        "config": {"workload": "C1 DeepSeek-V3-shaped dispatch: 64 simulated ranks, 256 experts, top-8 "
-                               "group-limited (<=4 of 8 nodes), 4096 tokens x 7168 bf16 on this rank, "
-                               "64 peer receive regions", "seed": seed, "my_rank": my_rank,
+        "config": {"workload": describe, "seed": seed, "my_rank": my_rank,
                    "rows_packed": N, "groups": int(st["n_groups"]), "rows_received": M, "rows_out": Q,
-                   "buffer_sets": N_SETS, "schedule": args.schedule, "streams": 1 if args.schedule == "single" else 2},
-        "single_stream_ms_per_step": round(ms_single, 4), "free_streams_ms_per_step": round(ms_free, 4),
+                   "buffer_sets": N_SETS, "schedule": args.schedule,
+                   "streams": 1 if args.schedule == "single" else 2},
+        "other_schedules_ms_per_step": other,
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "bytes_saved_vs_unicast": round(saved, 4),
         "step_bytes": {"pack": pack_bytes, "unpack": unpack_bytes},
@@ -312,17 +320,18 @@ def main() -> int:
         "pack_unpack_only": {"us": round(pu_us, 2),
                              "GBps": round((pack_bytes + unpack_bytes) / pu_us / 1e3, 1),
                              "pct_of_hbm_peak": round(100.0 * (pack_bytes + unpack_bytes) / pu_us / 1e3 / HBM_PEAK_GBPS, 2)},
-        "copy_ceiling": {"GBps": round(copy_gbps, 1), "bytes": 2 * n_copy},
-        "relay": relay,
+        "copy_ceiling": ceiling,
         "roofline": {"kernel": "k_expand", "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": traffic, "bytes_per_launch": expand_bytes,
+                     "traffic": traffic_from_profile("k_expand", name.upper()), "bytes_per_launch": expand_bytes,
                      "avg_launch_ms": round(expand_avg_ms, 4), "min_launch_ms": round(expand_ms[0], 4),
                      "launches_timed": len(expand_ms)},
     }
+    if relay is not None:
+        result["relay"] = relay
 
     # ---------------------------------------------------------------- oracle on the host cores
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and name == "c1":
         from oracle import ref
         log("[bench] cpu_baseline: building the oracle's own peer regions ...")
         bufs = []
@@ -357,6 +366,115 @@ def main() -> int:
             "host_cores_visible": os.cpu_count()}
 
     ctx.close()
+    return result
+
+
+# ------------------------------------------------------------------------------------------ AllGather
+def bench_allgather(args) -> dict:
+    import numpy as np
+    import torch
+    from paper_2605_22428_amd import binding as B
+    from paper_2605_22428_amd import workloads as W
+
+    dev = "cuda:0"
+    seed = W.BASE_SEED if args.seed is None else args.seed
+    w = W.C4
+    R, sbytes = w.n_ranks, w.shard_bytes
+    ctx = B.Context(R, 0, 1, w.my_rank, 0, B.MW_ROW_BYTES, 1, R, None, row_bytes=sbytes, device=dev)
+    shard = torch.from_numpy(W.allgather_shard(w, seed, w.my_rank).view(np.int16)).to(dev)
+    # received shards: all ranks' (own included), three rotating sets
+    sets = []
+    for s in range(N_SETS):
+        shards = [torch.from_numpy(W.allgather_shard(w, seed, r).view(np.int16)).to(dev) for r in range(R)]
+        ptrs = torch.tensor([t.data_ptr() for t in shards], dtype=torch.int64, device=dev)
+        sets.append(dict(shards=shards, ptrs=ptrs, send=torch.empty(sbytes, dtype=torch.uint8, device=dev),
+                         desc=torch.zeros(B.DESC_BYTES, dtype=torch.uint8, device=dev),
+                         stats=torch.zeros(B.SEND_STATS_BYTES, dtype=torch.uint8, device=dev),
+                         out=torch.empty(R * sbytes, dtype=torch.uint8, device=dev)))
+    torch.cuda.synchronize()
+
+    def step(i):
+        s = sets[i % N_SETS]
+        ctx.mw_plan_allgather(sbytes, s["desc"], s["stats"])
+        ctx.mw_pack_allgather(shard, sbytes, s["send"])
+        ctx.mw_unpack_allgather(s["ptrs"], sbytes, s["out"])
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    st = ctx.mw_get_send_stats(sets[0]["stats"])
+    EV_STRIDE = 4
+    ev = new_events(torch, (args.steps + EV_STRIDE - 1) // EV_STRIDE)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        if i % EV_STRIDE == 0:
+            ctx.mw_ctx_set_timing_events(B.MW_KERNEL_AG_GATHER, *ev[i // EV_STRIDE])
+        elif i % EV_STRIDE == 1:
+            ctx.mw_ctx_set_timing_events(B.MW_KERNEL_AG_GATHER, None, None)
+        step(i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ctx.mw_ctx_set_timing_events(B.MW_KERNEL_AG_GATHER, None, None)
+    g_ms = sorted(a.elapsed_time(b) for a, b in ev)
+    g_avg = sum(g_ms) / len(g_ms)
+    names = {"pack_copy": B.MW_KERNEL_AG_PACK, "gather": B.MW_KERNEL_AG_GATHER}
+    n_b = min(args.steps, 50)
+    evs = {k: new_events(torch, n_b) for k in names}
+    for i in range(n_b):
+        for k, code in names.items():
+            ctx.mw_ctx_set_timing_events(code, *evs[k][i])
+        step(i)
+    torch.cuda.synchronize()
+    for code in names.values():
+        ctx.mw_ctx_set_timing_events(code, None, None)
+    kern_us = {k: 1e3 * sum(a.elapsed_time(b) for a, b in evs[k]) / n_b for k in names}
+    pack_bytes, unpack_bytes = 2 * sbytes, 2 * R * sbytes
+    value = (pack_bytes + unpack_bytes) / (ms_per_step * 1e-3) / 1e9
+    achieved = unpack_bytes / (g_avg * 1e-3) / 1e9
+    result = {
+        "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "C4 AllGather receive assembly: 128-rank group, 2 MiB bf16 shard per rank, one "
+                               "descriptor naming all ranks, 128 received shards -> 256 MiB in rank order "
+                               "(the 4 MiB pack is launch-latency bound)", "seed": seed, "buffer_sets": N_SETS,
+                   "schedule": "single", "streams": 1},
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "bytes_saved_vs_unicast": round(1.0 - int(st["multicast_bytes"]) / int(st["unicast_bytes"]), 4),
+        "step_bytes": {"pack": pack_bytes, "unpack": unpack_bytes},
+        "kernel_us": {k: round(v, 2) for k, v in kern_us.items()},
+        "copy_ceiling": copy_ceiling(torch, B, R * sbytes, dev),
+        "roofline": {"kernel": "k_gather_shards", "bound": "hbm", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": traffic_from_profile("k_gather_shards", "C4"), "bytes_per_launch": unpack_bytes,
+                     "avg_launch_ms": round(g_avg, 4), "min_launch_ms": round(g_ms[0], 4),
+                     "launches_timed": len(g_ms)},
+    }
+    ctx.close()
+    return result
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", choices=["c0", "c1", "c2", "c3", "c4"], default="c1")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--schedule", choices=["aligned", "free", "single"], default="aligned",
+                    help="how the send side and the receive side of a step are issued (see step())")
+    ap.add_argument("--seed", type=int, default=None)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the other ranks of the dispatch are "
+              "simulated); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    result = bench_allgather(args) if args.workload == "c4" else bench_dispatch(args, args.workload)
     print(json.dumps(result), flush=True)
     return 0
 
