@@ -28,17 +28,15 @@ struct mw_row_rec {
     int32_t reserved0;
 };
 
-// Workgroup shape of the row movers: one 16-byte chunk per lane, a row of `chunks`
-// chunks is covered by `nseg` workgroups of `bs` lanes (bs a multiple of 64, <= 1024).
-static inline void mw_row_block_shape(int chunks, int *bs, int *nseg)
-{
-    int b = (chunks + 63) / 64 * 64;
-    if (b > 1024) b = 1024;
-    if (b < 64) b = 64;
-    *bs = b;
-    *nseg = (chunks + b - 1) / b;
-    if (*nseg < 1) *nseg = 1;
-}
+// Launch shape of the row movers: single-wave workgroups, one 16-byte chunk per lane.  A row
+// of `chunks` chunks is covered by `nseg` consecutive workgroups (grid x = segment, grid y =
+// row, so workgroups are dispatched in address order along a row and then row by row).
+// Measured on MI355X this is the shape that follows the plain-copy ceiling most closely:
+// whole-row workgroups of 14 waves leave an eighth of a CU's wave slots empty, several
+// chunks per lane and row-major segment order (all rows' first segments first) are slower.
+constexpr int kRowBlock = 64;
+constexpr uint32_t kRowGridMax = 32768;       // grid y; further rows by striding
+static inline int mw_row_segments(int chunks) { return chunks > 0 ? (chunks + kRowBlock - 1) / kRowBlock : 1; }
 
 // Host-side context.  Every d_* pointer is a slice of the caller's workspace.
 struct mw_ctx {

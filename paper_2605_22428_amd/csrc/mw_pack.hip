@@ -6,43 +6,46 @@
 // source token index and top-k ids travel with it.
 //
 // The packer is a row gather bound by HBM bandwidth: packed[i] = x[perm[i]].  Rows are
-// multiples of 16 bytes.  One workgroup per packed row (per row segment for rows longer
-// than 16 KiB), one 16-byte chunk per lane, a single streaming load and store per lane:
-// on MI355X many light waves follow the plain-copy ceiling more closely than fewer waves
-// with several loads in flight.  Nothing is reused, so accesses are non-temporal.
+// multiples of 16 bytes.  Single-wave workgroups, each moving 64 consecutive 16-byte chunks
+// of one row with a single streaming load and store per lane: on MI355X many light waves
+// follow the plain-copy ceiling more closely than fewer waves with several loads in flight.
+// Nothing is reused, so accesses are non-temporal.
 #include "mw_internal.h"
 
 namespace {
 
-// blockIdx.x = packed row, blockIdx.y = segment of blockDim.x chunks.  Chunks [0, xc)
-// come from x, chunks [xc, xc + sc) from the fp8 scale rows (sc == 0 otherwise).  The row
-// count and the row's token are wave-uniform and fetched together (perm has room for
-// gridDim.x entries, so the read is in bounds even past the last kept row).
-__global__ __launch_bounds__(1024) void k_pack(const u32x4 *__restrict__ x, const u32x4 *__restrict__ scales,
-                                               int xc, int sc, const int32_t *__restrict__ topk, int K,
-                                               const int32_t *__restrict__ perm,
-                                               const mw_send_stats *__restrict__ stats,
-                                               u32x4 *__restrict__ packed, int32_t *__restrict__ row_src_token,
-                                               int32_t *__restrict__ row_topk)
+// blockIdx.x = segment of 64 chunks, blockIdx.y walks packed rows.  Chunks [0, xc) come
+// from x, chunks [xc, xc + sc) from the fp8 scale rows (sc == 0 otherwise).  The row count
+// and the row's token are wave-uniform and fetched together (perm has room for every row
+// the grid can reach, so the read is in bounds even past the last kept row).
+__global__ __launch_bounds__(kRowBlock) void k_pack(const u32x4 *__restrict__ x, const u32x4 *__restrict__ scales,
+                                                    int xc, int sc, const int32_t *__restrict__ topk, int K,
+                                                    const int32_t *__restrict__ perm,
+                                                    const mw_send_stats *__restrict__ stats,
+                                                    u32x4 *__restrict__ packed, int32_t *__restrict__ row_src_token,
+                                                    int32_t *__restrict__ row_topk)
 {
-    uint32_t bdim = blockDim.x;
-    MW_PIN_S(bdim); MW_PIN_S(xc); MW_PIN_S(sc); MW_PIN_S(K);
+    uint32_t gdim = gridDim.y;
+    MW_PIN_S(gdim); MW_PIN_S(xc); MW_PIN_S(sc); MW_PIN_S(K);
     MW_PIN_PTR(x); MW_PIN_PTR(scales); MW_PIN_PTR(topk); MW_PIN_PTR(packed); MW_PIN_PTR(row_src_token);
     MW_PIN_PTR(row_topk);
-    const uint32_t i = blockIdx.x;
+    uint32_t i = blockIdx.y;
     int32_t t = perm[i];
     uint32_t n_rows = stats->n_rows;
     MW_PIN_S(t); MW_PIN_S(n_rows);
-    if (i >= n_rows) return;
     const int n = xc + sc;
-    const int c = blockIdx.y * bdim + threadIdx.x;
-    if (c < n) {
-        const u32x4 v = (c < xc) ? mw_ld16(x + (size_t)t * xc + c) : mw_ld16(scales + (size_t)t * sc + (c - xc));
-        mw_st16(packed + (size_t)i * n + c, v);
-    }
-    if (blockIdx.y == 0) {
-        if (threadIdx.x == 0) row_src_token[i] = t;
-        for (int j = threadIdx.x; j < K; j += bdim) row_topk[(size_t)i * K + j] = topk[(size_t)t * K + j];
+    const int c = blockIdx.x * kRowBlock + threadIdx.x;
+    while (i < n_rows) {
+        if (c < n) {
+            const u32x4 v = (c < xc) ? mw_ld16(x + (size_t)t * xc + c) : mw_ld16(scales + (size_t)t * sc + (c - xc));
+            mw_st16(packed + (size_t)i * n + c, v);
+        }
+        if (blockIdx.x == 0) {
+            if (threadIdx.x == 0) row_src_token[i] = t;
+            for (int j = threadIdx.x; j < K; j += kRowBlock) row_topk[(size_t)i * K + j] = topk[(size_t)t * K + j];
+        }
+        i += gdim;
+        if (i < n_rows) t = perm[i];
     }
 }
 
@@ -72,11 +75,11 @@ int32_t mw_launch_pack(mw_ctx *ctx, const void *x, const float *scales, const in
 {
     if (T == 0) return MW_OK;
     const int xc = (int)(ctx->x_row_bytes / 16), sc = (int)(ctx->s_row_bytes / 16);
-    int bs, nseg;
-    mw_row_block_shape(xc + sc, &bs, &nseg);
+    const int nseg = mw_row_segments(xc + sc);
+    const uint32_t gy = (uint32_t)T < kRowGridMax ? (uint32_t)T : kRowGridMax;
     {
         mw_timed tm(ctx, MW_KERNEL_PACK, s);
-        hipLaunchKernelGGL(k_pack, dim3(T, nseg), dim3(bs), 0, s, (const u32x4 *)x, (const u32x4 *)scales, xc, sc,
+        hipLaunchKernelGGL(k_pack, dim3(nseg, gy), dim3(kRowBlock), 0, s, (const u32x4 *)x, (const u32x4 *)scales, xc, sc,
                            topk, ctx->cfg.top_k, perm, stats, (u32x4 *)packed, row_src_token, row_topk);
     }
     MW_HIP_CHECK(hipGetLastError());

@@ -16,9 +16,9 @@
 //                  whatever the timing.  The (group, hop) -> first child row table feeds the
 //                  copy.  One more workgroup maps rows to groups (group starts marked, then a
 //                  running maximum) and does the byte accounting.
-//   k_relay_copy   one workgroup per input row, one 16-byte chunk per lane: the row is read
-//                  once and stored once per next hop that keeps its group (lane h of every
-//                  wave holds hop h's position; a ballot lists the hops).  Bound by HBM
+//   k_relay_copy   single-wave workgroups, each moving 64 consecutive 16-byte chunks of one
+//                  input row: read once, stored once per next hop that keeps the row's group
+//                  (lane h holds hop h's position; a ballot lists the hops).  Bound by HBM
 //                  bandwidth: rows * row_bytes read, rows * copies * row_bytes written.
 #include "mw_internal.h"
 
@@ -26,7 +26,6 @@ namespace {
 
 constexpr int kBlock = 1024;
 constexpr uint32_t kNoChild = 0xffffffffu;
-constexpr uint32_t kCopyMaxRowBlocks = 32768;
 
 struct grp_view { uint64_t m[MW_MASK_WORDS]; uint32_t off, cnt; bool valid; };
 
@@ -172,17 +171,17 @@ __global__ __launch_bounds__(kBlock) void k_relay_index(
     if (err) atomicOr(relay_flags, err);
 }
 
-// blockIdx.x walks input rows, blockIdx.y the segments of blockDim.x chunks of a row.
-__global__ __launch_bounds__(1024) void k_relay_copy(
+// blockIdx.x selects a segment of 64 chunks of a row, blockIdx.y walks input rows.
+__global__ __launch_bounds__(kRowBlock) void k_relay_copy(
     const mw_recv_peer *__restrict__ in, const mw_relay_child *__restrict__ children, int n_hops, int K, int n_chunks,
     uint32_t max_tokens, uint64_t row_bytes, const int32_t *__restrict__ group_of_row,
     const uint32_t *__restrict__ child_pos, uint32_t *relay_flags, mw_relay_stats *__restrict__ stats)
 {
     const mw_recv_peer src = in[0];
     const uint32_t n_rows = min(src.n_rows, max_tokens);
-    const int c = blockIdx.y * blockDim.x + threadIdx.x;
-    const int lane = threadIdx.x & 63;
-    for (uint32_t i = blockIdx.x; i < n_rows; i += gridDim.x) {
+    const int c = blockIdx.x * kRowBlock + threadIdx.x;
+    const int lane = threadIdx.x;
+    for (uint32_t i = blockIdx.y; i < n_rows; i += gridDim.y) {
         const int32_t g = group_of_row[i];
         if (g < 0) continue;
         const uint32_t off = i - src.desc[g].row_offset;
@@ -192,7 +191,7 @@ __global__ __launch_bounds__(1024) void k_relay_copy(
         const uint32_t p = (lane < n_hops) ? child_pos[(size_t)g * MW_MAX_HOPS + lane] : kNoChild;
         const int32_t st = src.row_src_token[i];
         int32_t tk = 0;
-        if ((int)threadIdx.x < K && blockIdx.y == 0) tk = src.row_topk[(size_t)i * K + threadIdx.x];
+        if ((int)threadIdx.x < K && blockIdx.x == 0) tk = src.row_topk[(size_t)i * K + threadIdx.x];
         uint64_t hops = __ballot(p != kNoChild);              // the same in every wave
         while (hops) {
             const int h = __ffsll((unsigned long long)hops) - 1;
@@ -200,7 +199,7 @@ __global__ __launch_bounds__(1024) void k_relay_copy(
             const uint32_t dst = (uint32_t)__shfl((int)p, h, 64) + off;
             const mw_relay_child ch = children[h];
             if (c < n_chunks) mw_st16((u32x4 *)ch.rows + (size_t)dst * n_chunks + c, v);
-            if (blockIdx.y == 0) {
+            if (blockIdx.x == 0) {
                 if (threadIdx.x == 0) ch.row_src_token[dst] = st;
                 if ((int)threadIdx.x < K) ch.row_topk[(size_t)dst * K + threadIdx.x] = tk;
             }
@@ -229,12 +228,11 @@ int32_t mw_launch_relay(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay_chil
                            ctx->d_hop_bits, ctx->d_group_of_row, ctx->d_child_pos, ctx->d_relay_flags, stats);
     }
     {
-        int bs, nseg;
-        mw_row_block_shape(n_chunks, &bs, &nseg);
-        uint32_t gx = (uint32_t)c.max_tokens < kCopyMaxRowBlocks ? (uint32_t)c.max_tokens : kCopyMaxRowBlocks;
-        if (gx < 1) gx = 1;
+        const int nseg = mw_row_segments(n_chunks);
+        uint32_t gy = (uint32_t)c.max_tokens < kRowGridMax ? (uint32_t)c.max_tokens : kRowGridMax;
+        if (gy < 1) gy = 1;
         mw_timed tm(ctx, MW_KERNEL_RELAY_COPY, s);
-        hipLaunchKernelGGL(k_relay_copy, dim3(gx, nseg), dim3(bs), 0, s, in, children, ctx->n_hops, c.top_k, n_chunks,
+        hipLaunchKernelGGL(k_relay_copy, dim3(nseg, gy), dim3(kRowBlock), 0, s, in, children, ctx->n_hops, c.top_k, n_chunks,
                            (uint32_t)c.max_tokens, (uint64_t)ctx->row_bytes, ctx->d_group_of_row, ctx->d_child_pos,
                            ctx->d_relay_flags, stats);
     }
