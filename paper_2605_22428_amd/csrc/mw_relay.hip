@@ -14,8 +14,7 @@
 //                  if its bitmap intersects the hop's rank set; kept groups are ranked with
 //                  block scans (group index, first row), so the child is in parent order
 //                  whatever the timing.  The (group, hop) -> first child row table feeds the
-//                  copy.  One more workgroup maps rows to groups (group starts marked, then a
-//                  running maximum) and does the byte accounting.
+//                  copy.  One more workgroup maps rows to groups and does the byte accounting.
 //   k_relay_copy   single-wave workgroups, each moving 64 consecutive 16-byte chunks of one
 //                  input row: read once, stored once per next hop that keeps the row's group
 //                  (lane h holds hop h's position; a ballot lists the hops).  Bound by HBM
@@ -26,6 +25,7 @@ namespace {
 
 constexpr int kBlock = 1024;
 constexpr uint32_t kNoChild = 0xffffffffu;
+constexpr uint32_t kLongGroup = 32;          // rows; longer groups are filled cooperatively
 
 struct grp_view { uint64_t m[MW_MASK_WORDS]; uint32_t off, cnt; bool valid; };
 
@@ -57,6 +57,8 @@ __global__ __launch_bounds__(kBlock) void k_relay_index(
     __shared__ uint32_t scratch[17];
     __shared__ uint32_t fit[2];                  // groups, rows of the child that fit its capacity
     __shared__ unsigned long long acc[2];        // rows taken, rows * destinations
+    __shared__ uint32_t n_long;
+    __shared__ uint32_t long_groups[65536 / kLongGroup];
     const uint32_t tid = threadIdx.x;
     const mw_recv_peer src = in[0];
     const uint32_t G = min(src.n_desc, max_tokens), n_rows = min(src.n_rows, max_tokens);
@@ -72,9 +74,11 @@ __global__ __launch_bounds__(kBlock) void k_relay_index(
         if (tid < 2) fit[tid] = 0;
         mw_lds_barrier();
         uint32_t carry_g = 0, carry_r = 0;
+        grp_view nxt = load_group(src.desc, tid, G, n_rows);
         for (uint32_t g0 = 0; g0 < G; g0 += kBlock) {
             const uint32_t g = g0 + tid;
-            const grp_view v = load_group(src.desc, g, G, n_rows);
+            const grp_view v = nxt;
+            nxt = load_group(src.desc, g + kBlock, G, n_rows);     // in flight during the scans
             uint64_t sub[MW_MASK_WORDS];
             uint32_t nd = 0;
 #pragma unroll
@@ -83,6 +87,7 @@ __global__ __launch_bounds__(kBlock) void k_relay_index(
             uint32_t tot_g, tot_r;
             const uint32_t cg = carry_g + mw_block_exscan(keep ? 1u : 0u, scratch, &tot_g);
             const uint32_t cr = carry_r + mw_block_exscan(keep ? v.cnt : 0u, scratch, &tot_r);
+            uint32_t fit_g = 0, fit_r = 0;
             if (g < G) {
                 uint32_t pos = kNoChild;
                 if (keep) {
@@ -93,25 +98,34 @@ __global__ __launch_bounds__(kBlock) void k_relay_index(
                         d.row_offset = cr; d.row_count = v.cnt; d.n_dest = nd; d.reserved0 = 0;
                         cdesc[cg] = d;
                         pos = cr;
-                        // kept groups that fit are a prefix of the kept groups: the largest
-                        // (index + 1, end row) pair describes the child
-                        atomicMax(&fit[0], cg + 1u);
-                        atomicMax(&fit[1], cr + v.cnt);
+                        fit_g = cg + 1u; fit_r = cr + v.cnt;
                     } else {
                         err |= MW_FLAG_OUT_CAPACITY;
                     }
                 }
                 child_pos[(size_t)g * MW_MAX_HOPS + h] = pos;
             }
+            // kept groups that fit are a prefix of the kept groups: the largest (index + 1, end
+            // row) pair describes the child.  Reduced over the wave first: same-address LDS
+            // atomics of a whole workgroup would serialise.
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) {
+                fit_g = max(fit_g, (uint32_t)__shfl_xor((int)fit_g, d, 64));
+                fit_r = max(fit_r, (uint32_t)__shfl_xor((int)fit_r, d, 64));
+            }
+            if ((tid & 63) == 0 && fit_g) { atomicMax(&fit[0], fit_g); atomicMax(&fit[1], fit_r); }
             carry_g += tot_g; carry_r += tot_r;
         }
         mw_lds_barrier();
         if (tid == 0) { stats->groups_per_hop[h] = fit[0]; stats->rows_per_hop[h] = fit[1]; }
     } else {
-        // ---- rows -> groups, accounting
+        // ---- rows -> groups, accounting.  A group's thread writes the group's index over its
+        // rows; groups longer than kLongGroup rows are queued in LDS and filled by the whole
+        // workgroup.  Rows of no valid group keep whatever the array held: the copy kernel
+        // checks every entry against the descriptors.
         if (tid < 2) acc[tid] = 0;
-        for (uint32_t i = tid; i < n_rows; i += kBlock) group_of_row[i] = -1;
-        __syncthreads();                         // (global memory is exchanged inside this workgroup)
+        if (tid == 0) n_long = 0;
+        mw_lds_barrier();
         uint64_t valid_ranks[MW_MASK_WORDS];
 #pragma unroll
         for (int w = 0; w < MW_MASK_WORDS; ++w) {
@@ -129,36 +143,21 @@ __global__ __launch_bounds__(kBlock) void k_relay_index(
                 if (v.m[w] & ~valid_ranks[w]) err |= MW_FLAG_BAD_RANK;
                 nd += (uint32_t)__popcll(v.m[w] & valid_ranks[w]);
             }
-            group_of_row[v.off] = (int32_t)g;
+            if (v.cnt <= kLongGroup) {
+                for (uint32_t r = 0; r < v.cnt; ++r) group_of_row[v.off + r] = (int32_t)g;
+            } else {
+                long_groups[atomicAdd(&n_long, 1u)] = g;      // at most max_tokens / kLongGroup of them
+            }
             rows_in += v.cnt; dest_rows += (unsigned long long)v.cnt * nd; ++groups_in;
         }
         if (rows_in) atomicAdd(&acc[0], rows_in);            // integer sums: order-free
         if (dest_rows) atomicAdd(&acc[1], dest_rows);
         uint32_t tot_groups;
-        mw_block_exscan(groups_in, scratch, &tot_groups);
-        __syncthreads();
-        // running maximum of the marked group starts = group of every row (descriptor row
-        // ranges ascend); rows behind a group's end are filtered by the copy kernel
-        int32_t carry = -1;
-        for (uint32_t i0 = 0; i0 < n_rows; i0 += kBlock) {
-            const uint32_t i = i0 + tid;
-            int32_t v = (i < n_rows) ? group_of_row[i] : -1;
-            const int lane = tid & 63, wave = tid >> 6;
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const int32_t o = __shfl_up(v, d, 64);
-                if (lane >= d) v = max(v, o);
-            }
-            if (lane == 63) scratch[wave] = (uint32_t)v;
-            mw_lds_barrier();
-            int32_t before = carry;
-            for (int w = 0; w < wave; ++w) before = max(before, (int32_t)scratch[w]);
-            int32_t all = carry;
-            for (int w = 0; w < kBlock / 64; ++w) all = max(all, (int32_t)scratch[w]);
-            v = max(v, before);
-            if (i < n_rows) group_of_row[i] = v;
-            carry = all;
-            mw_lds_barrier();
+        mw_block_exscan(groups_in, scratch, &tot_groups);     // (its barriers also publish the queue)
+        for (uint32_t q = 0; q < n_long; ++q) {
+            const uint32_t g = long_groups[q];
+            const uint32_t off = src.desc[g].row_offset, cnt = src.desc[g].row_count;
+            for (uint32_t r = tid; r < cnt; r += kBlock) group_of_row[off + r] = (int32_t)g;
         }
         if (tid == 0) {
             stats->n_groups_in = tot_groups;
@@ -178,12 +177,12 @@ __global__ __launch_bounds__(kRowBlock) void k_relay_copy(
     const uint32_t *__restrict__ child_pos, uint32_t *relay_flags, mw_relay_stats *__restrict__ stats)
 {
     const mw_recv_peer src = in[0];
-    const uint32_t n_rows = min(src.n_rows, max_tokens);
+    const uint32_t n_rows = min(src.n_rows, max_tokens), n_desc = min(src.n_desc, max_tokens);
     const int c = blockIdx.x * kRowBlock + threadIdx.x;
     const int lane = threadIdx.x;
     for (uint32_t i = blockIdx.y; i < n_rows; i += gridDim.y) {
         const int32_t g = group_of_row[i];
-        if (g < 0) continue;
+        if (g < 0 || (uint32_t)g >= n_desc) continue;        // (stale or never written)
         const uint32_t off = i - src.desc[g].row_offset;
         if (off >= src.desc[g].row_count) continue;          // behind its group's end: in no valid group
         u32x4 v = {0u, 0u, 0u, 0u};

@@ -135,7 +135,9 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
     if (tid < 2) scratch[18 + tid] = 0;
     mw_lds_barrier();
     // at most 256 peers of at most 65536 rows, so 32 bits are enough; a sum, so order-free
-    if (part) atomicAdd(&scratch[19], part);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) part += __shfl_xor(part, d, 64);
+    if ((tid & 63) == 0 && part) atomicAdd(&scratch[19], part);
 
     // rank-table entries of the first row's ids (second round trip)
     int32_t q_c[8];
@@ -180,7 +182,9 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
     {
         uint32_t a = 0;
         for (uint32_t w = tid; w < wpl; w += nthr) a += __popc(addr[w]);
-        if (a) atomicAdd(&scratch[18], a);
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) a += __shfl_xor(a, d, 64);     // one LDS atomic per wave
+        if ((tid & 63) == 0 && a) atomicAdd(&scratch[18], a);
     }
 
     // ---- per row: its distinct local experts in top-k order (duplicate ids count once).
