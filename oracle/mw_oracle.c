@@ -576,3 +576,77 @@ int ref_unpack_allgather(const uint8_t *const *peer_shards, int32_t R, int64_t s
         memcpy(out + (size_t)p * (size_t)shard_bytes, peer_shards[p], (size_t)shard_bytes);
     return REF_OK;
 }
+
+/* ------------------------------------------------------------------------ */
+/*
+ * AllGather with a two-segment fragment (Section 5.2, modified workflow
+ * step 1 and 2): every node splits its fragment into a segment sent over the
+ * direct links by plain writes (one copy per destination) and a segment sent
+ * once through the relay path as a MultiWrite; the split ratio is chosen from
+ * the bandwidths of the two paths so that both segments arrive together.
+ *
+ * Section 3.1's model, written out: with the direct fraction f, the direct
+ * path takes f*s/w_direct and the relay path (1-f)*s*copies/w_relay, where
+ * `copies` is how often the relayed segment crosses the link to the relay
+ * (1 with multicast, one per final destination with unicast multi-path).
+ * Both are equal at
+ *     f = copies*w_direct / (w_relay + copies*w_direct).
+ * Equal bandwidths: f = 1/2 and latency s/(2w) with multicast, f = 3/4 and
+ * 3s/(4w) with unicast to three destinations -- the paper's two figures.
+ *
+ * Reading used here: the split point is f*s rounded down to a multiple of 16
+ * bytes.  Descriptors count 16-byte units: desc[0] = units [0, a/16) (direct
+ * segment), desc[1] = units [a/16, s/16) (relayed segment), both naming all R
+ * ranks; an empty segment still gets its (empty) descriptor.  multicast_bytes
+ * is what this node injects with the split, a*R + (s-a), unicast_bytes = s*R
+ * (this rank's own copy counted, as in ref_plan_allgather).
+ */
+int ref_allgather_split_point(int64_t shard_bytes, double w_direct, double w_relay, int32_t copies,
+                              int64_t *direct_bytes)
+{
+    if (shard_bytes < 0 || shard_bytes % 16 != 0 || !(w_direct > 0.0) || !(w_relay > 0.0) || copies < 1)
+        return REF_ERR_ARG;
+    const double f = (double)copies * w_direct / (w_relay + (double)copies * w_direct);
+    int64_t a = (int64_t)(f * (double)shard_bytes);
+    a -= a % 16;
+    if (a < 0) a = 0;
+    if (a > shard_bytes) a = shard_bytes;
+    *direct_bytes = a;
+    return REF_OK;
+}
+
+int ref_plan_allgather_split(int32_t R, int64_t shard_bytes, int64_t direct_bytes,
+                             ref_group_desc *desc /* [2] */, ref_send_stats *stats)
+{
+    if (R < 1 || R > REF_MAX_RANKS || shard_bytes < 0 || shard_bytes % 16 != 0) return REF_ERR_ARG;
+    if (direct_bytes < 0 || direct_bytes > shard_bytes || direct_bytes % 16 != 0) return REF_ERR_ARG;
+    if (shard_bytes / 16 > 0xffffffffLL) return REF_ERR_ARG;
+    memset(desc, 0, 2 * sizeof(*desc));
+    memset(stats, 0, sizeof(*stats));
+    for (int q = 0; q < 2; ++q)
+        for (int32_t r = 0; r < R; ++r) desc[q].mask[r >> 6] |= (uint64_t)1 << (r & 63);
+    desc[0].row_offset = 0;
+    desc[0].row_count = (uint32_t)(direct_bytes / 16);
+    desc[1].row_offset = (uint32_t)(direct_bytes / 16);
+    desc[1].row_count = (uint32_t)((shard_bytes - direct_bytes) / 16);
+    desc[0].n_dest = desc[1].n_dest = (uint32_t)R;
+    for (int32_t r = 0; r < R; ++r) stats->rows_per_dest[r] = (uint32_t)(shard_bytes / 16);
+    stats->n_rows = (uint32_t)(shard_bytes / 16);
+    stats->n_groups = 2;
+    stats->multicast_bytes = (uint64_t)direct_bytes * (uint64_t)R + (uint64_t)(shard_bytes - direct_bytes);
+    stats->unicast_bytes = (uint64_t)shard_bytes * (uint64_t)R;
+    return REF_OK;
+}
+
+/* Result: rank p's fragment = its direct piece followed by its relayed piece, ranks side by side. */
+int ref_unpack_allgather_split(const uint8_t *const *direct, const uint8_t *const *relayed, int32_t R,
+                               int64_t shard_bytes, int64_t direct_bytes, uint8_t *out)
+{
+    if (direct_bytes < 0 || direct_bytes > shard_bytes) return REF_ERR_ARG;
+    for (int32_t p = 0; p < R; ++p) {
+        uint8_t *o = out + (size_t)p * (size_t)shard_bytes;
+        memcpy(o, direct[p], (size_t)direct_bytes);
+        memcpy(o + direct_bytes, relayed[p], (size_t)(shard_bytes - direct_bytes));
+    }
+    return REF_OK;
+}

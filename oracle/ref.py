@@ -51,7 +51,8 @@ def lib():
         for name in ("ref_masks", "ref_plan", "ref_accounting_plain", "ref_pack", "ref_deliver",
                      "ref_unpack", "ref_dispatch_plain", "ref_plan_allgather",
                      "ref_pack_allgather", "ref_unpack_allgather",
-                     "ref_relay_child", "ref_relay_accounting"):
+                     "ref_relay_child", "ref_relay_accounting", "ref_allgather_split_point",
+                     "ref_plan_allgather_split", "ref_unpack_allgather_split"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -270,4 +271,33 @@ def unpack_allgather(shards: Sequence[np.ndarray]) -> np.ndarray:
     out = np.zeros(n * len(bs), dtype=np.uint8)
     _check(lib().ref_unpack_allgather(ptrs, C.c_int32(len(bs)), C.c_int64(n), _p(out)),
            "ref_unpack_allgather")
+    return out
+
+
+def allgather_split_point(shard_bytes: int, w_direct: float, w_relay: float, copies: int) -> int:
+    """Bytes of the direct segment for which both paths finish together (multiple of 16)."""
+    a = C.c_int64(0)
+    _check(lib().ref_allgather_split_point(C.c_int64(shard_bytes), C.c_double(w_direct), C.c_double(w_relay),
+                                           C.c_int32(copies), C.byref(a)), "ref_allgather_split_point")
+    return a.value
+
+
+def plan_allgather_split(n_ranks: int, shard_bytes: int, direct_bytes: int):
+    d = np.zeros(2, dtype=DESC)
+    st = np.zeros(1, dtype=STATS)
+    _check(lib().ref_plan_allgather_split(C.c_int32(n_ranks), C.c_int64(shard_bytes), C.c_int64(direct_bytes),
+                                          _p(d), _p(st)), "ref_plan_allgather_split")
+    return d, st[0]
+
+
+def unpack_allgather_split(direct: Sequence[np.ndarray], relayed: Sequence[np.ndarray], shard_bytes: int,
+                           direct_bytes: int) -> np.ndarray:
+    db = [np.ascontiguousarray(s).view(np.uint8).reshape(-1) for s in direct]
+    rb = [np.ascontiguousarray(s).view(np.uint8).reshape(-1) for s in relayed]
+    assert all(b.size >= direct_bytes for b in db) and all(b.size >= shard_bytes - direct_bytes for b in rb)
+    dp = (C.c_void_p * len(db))(*[b.ctypes.data for b in db])
+    rp = (C.c_void_p * len(rb))(*[b.ctypes.data for b in rb])
+    out = np.zeros(shard_bytes * len(db), dtype=np.uint8)
+    _check(lib().ref_unpack_allgather_split(dp, rp, C.c_int32(len(db)), C.c_int64(shard_bytes),
+                                            C.c_int64(direct_bytes), _p(out)), "ref_unpack_allgather_split")
     return out

@@ -205,3 +205,61 @@ def test_relay_rejects_bad_tables_and_bitmaps():
     short = np.zeros(4, dtype=np.int32)                              # bitmaps name ranks the table lacks
     with pytest.raises(ref.OracleError):
         ref.relay_child(*parent, short, 1, 0)
+
+
+# ---------------------------------------------------------------- AllGather with a two-segment fragment
+def test_allgather_split_point_reproduces_the_papers_model(golden_dir):
+    g = json.load(open(os.path.join(golden_dir, "paper_arithmetic.json")))["allgather_tp4_full_mesh"]
+    s, w = 16 << 20, 1.0
+
+    def latency(a, copies):            # the slower of the two paths, in units of s/w
+        return max(a / w, (s - a) * copies / w) / (s / w)
+
+    a_mc = ref.allgather_split_point(s, w, w, g["copies_multicast"])
+    a_uc = ref.allgather_split_point(s, w, w, g["copies_unicast"])
+    assert a_mc == s // 2 and a_uc == 3 * s // 4
+    assert latency(a_mc, 1) == g["latency_multicast"] and latency(a_uc, 3) == g["latency_unicast_multipath"]
+    assert latency(s, 1) == g["latency_direct_only"]
+    assert 1 - latency(a_mc, 1) / latency(s, 1) == g["reduction_vs_baseline"]
+    assert round(100 * (1 - latency(a_mc, 1) / latency(a_uc, 3))) == g["reduction_vs_unicast_multipath_printed_percent"]
+    # the balanced point is the minimum of the slower path over all splits
+    for copies, wd, wr in [(1, 1.0, 1.0), (3, 1.0, 1.0), (1, 56.0, 25.0), (2, 3.0, 7.0)]:
+        a = ref.allgather_split_point(s, wd, wr, copies)
+        t = lambda x: max(x / wd, (s - x) * copies / wr)
+        assert a % 16 == 0 and 0 <= a <= s
+        assert all(t(a) <= t(x) * (1 + 1e-6) for x in range(0, s + 1, s // 64))
+    for bad in [(s + 8, 1.0, 1.0, 1), (s, 0.0, 1.0, 1), (s, 1.0, -1.0, 1), (s, 1.0, 1.0, 0)]:
+        with pytest.raises(ref.OracleError):
+            ref.allgather_split_point(*bad)
+
+
+@pytest.mark.parametrize("direct", [0, 16, 4096, 8000, 16384])
+def test_allgather_split_is_still_concatenation(direct):
+    w = W.AllGatherWorkload("ags", 43, 8, 8192)          # 16 KiB fragments
+    s = w.shard_bytes
+    shards = [W.allgather_shard(w, 5, r).view(np.uint8) for r in range(w.n_ranks)]
+    d, st = ref.plan_allgather_split(w.n_ranks, s, direct)
+    full = brute.words_to_int(d[0]["mask"])
+    assert full == (1 << w.n_ranks) - 1 == brute.words_to_int(d[1]["mask"])
+    assert (int(d[0]["row_offset"]), int(d[0]["row_count"])) == (0, direct // 16)
+    assert (int(d[1]["row_offset"]), int(d[1]["row_count"])) == (direct // 16, (s - direct) // 16)
+    assert int(st["n_groups"]) == 2 and int(st["n_rows"]) == s // 16
+    assert int(st["multicast_bytes"]) == direct * w.n_ranks + (s - direct)
+    assert int(st["unicast_bytes"]) == s * w.n_ranks
+    # the two pieces travel separately (and land in separate regions)
+    dpieces = [np.ascontiguousarray(x[:direct]) for x in shards]
+    rpieces = [np.ascontiguousarray(x[direct:]) for x in shards]
+    out = ref.unpack_allgather_split(dpieces, rpieces, s, direct)
+    assert out.tobytes() == np.concatenate(shards).tobytes() == ref.unpack_allgather(shards).tobytes()
+    if direct == s:                       # everything direct: the plain AllGather accounting
+        _, st1 = ref.plan_allgather(w.n_ranks, s)
+        assert int(st["multicast_bytes"]) == int(st1["unicast_bytes"])
+    if direct == 0:                       # everything relayed once
+        _, st1 = ref.plan_allgather(w.n_ranks, s)
+        assert int(st["multicast_bytes"]) == int(st1["multicast_bytes"])
+
+
+def test_allgather_split_rejects_bad_split_points():
+    for args in [(8, 1024, 8), (8, 1024, 2048), (8, 1024, -16), (8, 1000, 0), (300, 1024, 0)]:
+        with pytest.raises(ref.OracleError):
+            ref.plan_allgather_split(*args)
