@@ -231,6 +231,39 @@ MW_API int32_t mw_unpack(mw_ctx *ctx, const mw_recv_peer *peers_dev, int32_t n_p
 MW_API int32_t mw_unpack_allgather(mw_ctx *ctx, const void *const *peer_shards_dev, int64_t shard_bytes,
                             void *out_dev, void *stream);
 
+/*
+ * AllGather with a two-segment fragment (Section 5.2, modified workflow): each node splits
+ * its fragment into a segment sent over the direct links by plain writes and a segment sent
+ * once through the relay path as a MultiWrite; the ratio follows from the bandwidths of the
+ * two paths so that both segments arrive together (Section 3.1's model).
+ *
+ * mw_allgather_split_point (HOST only, no context): direct_bytes = f * shard_bytes rounded
+ * down to a multiple of 16 with f = copies * bw_direct / (bw_relay + copies * bw_direct),
+ * where `copies` is how often the relayed segment crosses the link to the relay (1 with
+ * MultiWrite; the number of final destinations with unicast multi-path).
+ */
+MW_API int32_t mw_allgather_split_point(int64_t shard_bytes, double bw_direct, double bw_relay, int32_t copies,
+                                 int64_t *direct_bytes);
+
+/*
+ * Descriptor pair for a split fragment, in units of 16 bytes: desc[0] = units
+ * [0, direct_bytes / 16) (direct segment), desc[1] = the rest (relayed segment), both naming
+ * ranks 0..R-1.  stats: n_rows = units, n_groups = 2, multicast_bytes = direct_bytes * R +
+ * (shard_bytes - direct_bytes) (what this node injects), unicast_bytes = shard_bytes * R.
+ * The send buffer is the one mw_pack_allgather fills; the segments are byte ranges of it.
+ */
+MW_API int32_t mw_plan_allgather_split(mw_ctx *ctx, int64_t shard_bytes, int64_t direct_bytes,
+                                mw_group_desc *desc_dev, mw_send_stats *stats_dev, void *stream);
+
+/*
+ * Assembly of split fragments: out = for p = 0..R-1: direct_dev[p][0, direct_bytes) followed by
+ * relayed_dev[p][0, shard_bytes - direct_bytes).  Two device arrays of n_ranks device pointers
+ * (the pieces of one rank arrive in different receive regions).  A pointer may be NULL when its
+ * piece is empty.
+ */
+MW_API int32_t mw_unpack_allgather_split(mw_ctx *ctx, const void *const *direct_dev, const void *const *relayed_dev,
+                                  int64_t shard_bytes, int64_t direct_bytes, void *out_dev, void *stream);
+
 /* ---- relay (Section 4.3.3, recursive execution model; Section 4.1, local forwarding table,
  *      replication and forwarding, update of in-packet metadata) ------------------------------ */
 

@@ -26,6 +26,7 @@ EXPORTS = ["mw_workspace_bytes", "mw_ctx_create", "mw_ctx_destroy", "mw_plan", "
            "mw_plan_allgather", "mw_pack_allgather", "mw_unpack", "mw_unpack_allgather",
            "mw_sim_deliver", "mw_copy_bytes", "mw_get_send_stats", "mw_get_recv_stats",
            "mw_set_forwarding", "mw_relay", "mw_get_relay_stats",
+           "mw_allgather_split_point", "mw_plan_allgather_split", "mw_unpack_allgather_split",
            "mw_ctx_set_timing_events", "mw_status_string"]
 MW_KERNEL_PLAN_RANK, MW_KERNEL_PLAN_GROUPS, MW_KERNEL_PACK, MW_KERNEL_RECV_INDEX, MW_KERNEL_EXPAND = 0, 1, 2, 3, 4
 MW_KERNEL_AG_PACK, MW_KERNEL_AG_GATHER, MW_KERNEL_RELAY_INDEX, MW_KERNEL_RELAY_COPY = 5, 6, 7, 8
@@ -104,6 +105,13 @@ def mw_copy_bytes(dst: torch.Tensor, src: torch.Tensor, n_bytes: int):
     _check(load().mw_copy_bytes(_ptr(dst), _ptr(src), C.c_int64(n_bytes), _stream()), "mw_copy_bytes")
 
 
+def mw_allgather_split_point(shard_bytes: int, bw_direct: float, bw_relay: float, copies: int) -> int:
+    a = C.c_int64(0)
+    _check(load().mw_allgather_split_point(C.c_int64(shard_bytes), C.c_double(bw_direct), C.c_double(bw_relay),
+                                           C.c_int32(copies), C.byref(a)), "mw_allgather_split_point")
+    return a.value
+
+
 class Context:
     """mw_ctx plus the device workspace it uses (a torch tensor, caller-owned in ABI terms)."""
 
@@ -170,6 +178,16 @@ class Context:
     def mw_pack_allgather(self, shard: torch.Tensor, shard_bytes: int, send_buf: torch.Tensor):
         _check(load().mw_pack_allgather(self._h, _ptr(shard), C.c_int64(shard_bytes), _ptr(send_buf),
                                         _stream()), "mw_pack_allgather")
+
+    def mw_plan_allgather_split(self, shard_bytes: int, direct_bytes: int, desc: torch.Tensor, stats: torch.Tensor):
+        _check(load().mw_plan_allgather_split(self._h, C.c_int64(shard_bytes), C.c_int64(direct_bytes), _ptr(desc),
+                                              _ptr(stats), _stream()), "mw_plan_allgather_split")
+
+    def mw_unpack_allgather_split(self, direct: torch.Tensor, relayed: torch.Tensor, shard_bytes: int,
+                                  direct_bytes: int, out: torch.Tensor):
+        _check(load().mw_unpack_allgather_split(self._h, _ptr(direct), _ptr(relayed), C.c_int64(shard_bytes),
+                                                C.c_int64(direct_bytes), _ptr(out), _stream()),
+               "mw_unpack_allgather_split")
 
     # ---- receive side --------------------------------------------------------------------
     def mw_unpack(self, peers: torch.Tensor, n_peers: int, out_rows: torch.Tensor,

@@ -228,6 +228,41 @@ MW_API int32_t mw_pack_allgather(mw_ctx *ctx, const void *shard_dev, int64_t sha
     return mw_launch_copy(ctx, send_buf_dev, shard_dev, shard_bytes, (hipStream_t)stream);
 }
 
+MW_API int32_t mw_allgather_split_point(int64_t shard_bytes, double bw_direct, double bw_relay, int32_t copies,
+                                 int64_t *direct_bytes)
+{
+    if (!direct_bytes || shard_bytes < 0 || copies < 1 || !(bw_direct > 0.0) || !(bw_relay > 0.0))
+        return MW_ERR_INVALID_ARG;
+    if (shard_bytes % 16 != 0) return MW_ERR_UNSUPPORTED;
+    const double f = (double)copies * bw_direct / (bw_relay + (double)copies * bw_direct);
+    int64_t a = (int64_t)(f * (double)shard_bytes);
+    a -= a % 16;
+    if (a < 0) a = 0;
+    if (a > shard_bytes) a = shard_bytes;
+    *direct_bytes = a;
+    return MW_OK;
+}
+
+MW_API int32_t mw_plan_allgather_split(mw_ctx *ctx, int64_t shard_bytes, int64_t direct_bytes,
+                                mw_group_desc *desc_dev, mw_send_stats *stats_dev, void *stream)
+{
+    if (!ctx || !desc_dev || !stats_dev || shard_bytes < 0 || direct_bytes < 0 || direct_bytes > shard_bytes)
+        return MW_ERR_INVALID_ARG;
+    if (shard_bytes % 16 != 0 || direct_bytes % 16 != 0 || shard_bytes / 16 > 0xffffffffLL) return MW_ERR_UNSUPPORTED;
+    return mw_launch_plan_allgather_split(ctx, shard_bytes, direct_bytes, desc_dev, stats_dev, (hipStream_t)stream);
+}
+
+MW_API int32_t mw_unpack_allgather_split(mw_ctx *ctx, const void *const *direct_dev, const void *const *relayed_dev,
+                                  int64_t shard_bytes, int64_t direct_bytes, void *out_dev, void *stream)
+{
+    if (!ctx || shard_bytes < 0 || direct_bytes < 0 || direct_bytes > shard_bytes) return MW_ERR_INVALID_ARG;
+    if (shard_bytes % 16 != 0 || direct_bytes % 16 != 0) return MW_ERR_UNSUPPORTED;
+    if (shard_bytes == 0) return MW_OK;
+    if (!direct_dev || !relayed_dev || !out_dev || ((uintptr_t)out_dev & 15u)) return MW_ERR_INVALID_ARG;
+    return mw_launch_gather_split(ctx, direct_dev, relayed_dev, shard_bytes, direct_bytes, out_dev,
+                                  (hipStream_t)stream);
+}
+
 MW_API int32_t mw_unpack(mw_ctx *ctx, const mw_recv_peer *peers_dev, int32_t n_peers, void *out_rows_dev,
                   float *out_scales_dev, int64_t out_capacity_rows, int32_t *out_src_peer_dev,
                   int32_t *out_src_token_dev, int64_t *expert_offsets_dev, mw_recv_stats *recv_stats_dev,

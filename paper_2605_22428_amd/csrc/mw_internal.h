@@ -166,6 +166,10 @@ int32_t mw_launch_unpack(mw_ctx *ctx, const mw_recv_peer *peers, int32_t P, void
                          int64_t *expert_offsets, mw_recv_stats *stats, hipStream_t s);
 int32_t mw_launch_plan_allgather(mw_ctx *ctx, int64_t shard_bytes, mw_group_desc *desc,
                                  mw_send_stats *stats, hipStream_t s);
+int32_t mw_launch_plan_allgather_split(mw_ctx *ctx, int64_t shard_bytes, int64_t direct_bytes, mw_group_desc *desc,
+                                       mw_send_stats *stats, hipStream_t s);
+int32_t mw_launch_gather_split(mw_ctx *ctx, const void *const *direct, const void *const *relayed,
+                               int64_t shard_bytes, int64_t direct_bytes, void *out, hipStream_t s);
 int32_t mw_launch_copy(mw_ctx *ctx, void *dst, const void *src, int64_t n_bytes, hipStream_t s);
 int32_t mw_launch_gather_shards(mw_ctx *ctx, const void *const *shards, int64_t shard_bytes, void *out,
                                 hipStream_t s);

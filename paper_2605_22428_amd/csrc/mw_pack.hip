@@ -67,7 +67,37 @@ __global__ __launch_bounds__(256) void k_gather_shards(const u32x4 *const *__res
     if (c < shard_chunks) mw_st16(dst + c, mw_ld16(src + c));
 }
 
+// AllGather assembly of split fragments (Section 5.2): chunk c of shard p comes from the
+// direct piece while c < direct_chunks, else from the relayed piece.  blockIdx.y = p.
+__global__ __launch_bounds__(256) void k_gather_split(const u32x4 *const *__restrict__ direct,
+                                                      const u32x4 *const *__restrict__ relayed,
+                                                      int64_t shard_chunks, int64_t direct_chunks,
+                                                      u32x4 *__restrict__ out)
+{
+    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (c >= shard_chunks) return;
+    const u32x4 *src = (c < direct_chunks) ? direct[blockIdx.y] + c : relayed[blockIdx.y] + (c - direct_chunks);
+    mw_st16(out + (int64_t)blockIdx.y * shard_chunks + c, mw_ld16(src));
+}
+
 }  // namespace
+
+int32_t mw_launch_gather_split(mw_ctx *ctx, const void *const *direct, const void *const *relayed,
+                               int64_t shard_bytes, int64_t direct_bytes, void *out, hipStream_t s)
+{
+    const int64_t shard_chunks = shard_bytes / 16;
+    if (shard_chunks == 0) return MW_OK;
+    const int64_t gx = (shard_chunks + 255) / 256;
+    if (gx > 0x7fffffffLL) return MW_ERR_UNSUPPORTED;
+    {
+        mw_timed tm(ctx, MW_KERNEL_AG_GATHER, s);
+        hipLaunchKernelGGL(k_gather_split, dim3((uint32_t)gx, ctx->cfg.n_ranks), dim3(256), 0, s,
+                           (const u32x4 *const *)direct, (const u32x4 *const *)relayed, shard_chunks, direct_bytes / 16,
+                           (u32x4 *)out);
+    }
+    MW_HIP_CHECK(hipGetLastError());
+    return MW_OK;
+}
 
 int32_t mw_launch_pack(mw_ctx *ctx, const void *x, const float *scales, const int32_t *topk,
                        const int32_t *perm, const mw_send_stats *stats, int32_t T, void *packed,

@@ -236,7 +236,44 @@ __global__ __launch_bounds__(256) void k_plan_allgather(int R, uint64_t shard_by
     }
 }
 
+// Descriptor pair of a fragment split into a direct and a relayed segment (Section 5.2),
+// in units of 16 bytes.
+__global__ __launch_bounds__(256) void k_plan_allgather_split(int R, uint64_t shard_bytes, uint64_t direct_bytes,
+                                                              mw_group_desc *desc, mw_send_stats *stats)
+{
+    const int tid = threadIdx.x;
+    const uint32_t units = (uint32_t)(shard_bytes / 16), d_units = (uint32_t)(direct_bytes / 16);
+    if (tid < MW_MAX_RANKS) stats->rows_per_dest[tid] = (tid < R) ? units : 0u;
+    if (tid < 2) {
+        mw_group_desc d;
+#pragma unroll
+        for (int w = 0; w < MW_MASK_WORDS; ++w) {
+            const int lo = w * 64;
+            d.mask[w] = (R >= lo + 64) ? ~0ull : (R > lo ? ((1ull << (R - lo)) - 1ull) : 0ull);
+        }
+        d.row_offset = tid == 0 ? 0u : d_units;
+        d.row_count = tid == 0 ? d_units : units - d_units;
+        d.n_dest = (uint32_t)R; d.reserved0 = 0;
+        desc[tid] = d;
+    }
+    if (tid == 0) {
+        stats->n_rows = units; stats->n_groups = 2;
+        stats->multicast_bytes = direct_bytes * (uint64_t)R + (shard_bytes - direct_bytes);
+        stats->unicast_bytes = shard_bytes * (uint64_t)R;
+        stats->error_flags = 0; stats->reserved0 = 0;
+    }
+}
+
 }  // namespace
+
+int32_t mw_launch_plan_allgather_split(mw_ctx *ctx, int64_t shard_bytes, int64_t direct_bytes, mw_group_desc *desc,
+                                       mw_send_stats *stats, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_plan_allgather_split, dim3(1), dim3(256), 0, s, ctx->cfg.n_ranks, (uint64_t)shard_bytes,
+                       (uint64_t)direct_bytes, desc, stats);
+    MW_HIP_CHECK(hipGetLastError());
+    return MW_OK;
+}
 
 int32_t mw_launch_plan(mw_ctx *ctx, const int32_t *topk, int32_t T, uint64_t *mask, int32_t *perm,
                        mw_group_desc *desc, mw_send_stats *stats, hipStream_t s)

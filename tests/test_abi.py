@@ -111,3 +111,20 @@ def test_status_strings(lib):
     for s in (-1, -2, -3, -4, -5):
         assert B.status_string(s) not in ("ok", "unknown status")
     assert B.status_string(-99) == "unknown status"
+
+
+def test_allgather_split_point_is_host_arithmetic(lib):
+    """No device involved: the split point follows Section 3.1's two-path model; compared with
+    the oracle's own formula and with the two cases the paper works out."""
+    from oracle import ref
+    s = 16 << 20
+    assert B.mw_allgather_split_point(s, 1.0, 1.0, 1) == s // 2        # multicast: half and half
+    assert B.mw_allgather_split_point(s, 1.0, 1.0, 3) == 3 * s // 4    # unicast multi-path to 3 peers
+    for args in [(s, 56.0, 25.0, 1), (2 << 20, 3.0, 7.0, 2), (4096, 1.0, 1000.0, 1), (0, 1.0, 1.0, 1),
+                 (48, 1.0, 1.0, 1)]:
+        assert B.mw_allgather_split_point(*args) == ref.allgather_split_point(*args)
+    for args, want in [((s + 8, 1.0, 1.0, 1), B.MW_ERR_UNSUPPORTED), ((s, 0.0, 1.0, 1), B.MW_ERR_INVALID_ARG),
+                       ((s, 1.0, 1.0, 0), B.MW_ERR_INVALID_ARG), ((-16, 1.0, 1.0, 1), B.MW_ERR_INVALID_ARG)]:
+        with pytest.raises(B.MwError) as e:
+            B.mw_allgather_split_point(*args)
+        assert e.value.status == want

@@ -184,6 +184,40 @@ def test_allgather(w):
     ctx.close()
 
 
+@pytest.mark.parametrize("direct_frac", [0.0, 0.5, 0.75, 1.0])
+@pytest.mark.parametrize("w", [W.AllGatherWorkload("ag_small", 41, 8, 1000 * 8), W.C4], ids=["small", "C4_full"])
+def test_allgather_split_fragment(w, direct_frac):
+    """Section 5.2: fragment split into a direct and a relayed segment; the assembly of the two
+    pieces of every rank equals the plain AllGather result."""
+    _say("allgather split", w.name, direct_frac)
+    s = w.shard_bytes
+    if 0.0 < direct_frac < 1.0:      # bandwidth ratio that puts this fraction on the direct path
+        direct = B.mw_allgather_split_point(s, direct_frac, 1.0 - direct_frac, 1)
+        assert direct == ref.allgather_split_point(s, direct_frac, 1.0 - direct_frac, 1)
+    else:
+        direct = int(direct_frac) * s
+    ctx = B.Context(w.n_ranks, 0, 1, w.my_rank, 0, B.MW_ROW_BYTES, 1, 0, None, row_bytes=s, device=H.DEV)
+    desc = torch.zeros(2 * B.DESC_BYTES, dtype=torch.uint8, device=H.DEV)
+    stats = torch.zeros(B.SEND_STATS_BYTES, dtype=torch.uint8, device=H.DEV)
+    ctx.mw_plan_allgather_split(s, direct, desc, stats)
+    od, ost = ref.plan_allgather_split(w.n_ranks, s, direct)
+    H.assert_same_bytes(H.host(desc), od.view(np.uint8).reshape(-1), "split desc pair")
+    st = ctx.mw_get_send_stats(stats)
+    H.assert_same_bytes(np.array([st]).view(np.uint8), np.array([ost]).view(np.uint8), "split stats")
+    shards = [W.allgather_shard(w, W.BASE_SEED, r).view(np.uint8) for r in range(w.n_ranks)]
+    dp = [H.dev(np.ascontiguousarray(x[:direct])) if direct else None for x in shards]
+    rp = [H.dev(np.ascontiguousarray(x[direct:])) if direct < s else None for x in shards]
+    dt = torch.tensor([0 if t is None else t.data_ptr() for t in dp], dtype=torch.int64, device=H.DEV)
+    rt = torch.tensor([0 if t is None else t.data_ptr() for t in rp], dtype=torch.int64, device=H.DEV)
+    out = torch.zeros(w.n_ranks * s, dtype=torch.uint8, device=H.DEV)
+    ctx.mw_unpack_allgather_split(dt, rt, s, direct, out)
+    torch.cuda.synchronize()
+    want = ref.unpack_allgather_split([x[:direct] for x in shards], [x[direct:] for x in shards], s, direct)
+    H.assert_same_bytes(H.host(out), want, "split assembly")
+    H.assert_same_bytes(H.host(out), ref.unpack_allgather(shards), "split assembly vs plain AllGather")
+    ctx.close()
+
+
 def test_allgather_equals_dispatch_with_all_ranks_set():
     # Section 2.3.3 / 5.2: AllGather is the static destination set "everyone"
     R, elems = 8, 2048
