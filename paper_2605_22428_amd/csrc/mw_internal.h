@@ -28,15 +28,24 @@ struct mw_row_rec {
     int32_t reserved0;
 };
 
-// Launch shape of the row movers: single-wave workgroups, one 16-byte chunk per lane.  A row
-// of `chunks` chunks is covered by `nseg` consecutive workgroups (grid x = segment, grid y =
-// row, so workgroups are dispatched in address order along a row and then row by row).
-// Measured on MI355X this is the shape that follows the plain-copy ceiling most closely:
-// whole-row workgroups of 14 waves leave an eighth of a CU's wave slots empty, several
-// chunks per lane and row-major segment order (all rows' first segments first) are slower.
-constexpr int kRowBlock = 64;
+// Launch shape of the row movers: one 16-byte chunk per lane, grid x = segment of `bs` chunks
+// of a row, grid y = row, so workgroups are dispatched in address order along a row and then
+// row by row.  Rows that are whole 128-byte cache lines (bf16 rows of 14336 bytes) are moved by
+// single-wave workgroups: measured on MI355X this follows the plain-copy ceiling most closely
+// (whole-row workgroups of 14 waves leave an eighth of a CU's wave slots empty; several chunks
+// per lane, or all rows' first segments first, are slower).  Rows that are not (fp8 rows of 7392
+// bytes start and end inside cache lines) keep one workgroup per row, so the lines two pieces
+// share are touched from one CU: with single-wave workgroups such rows were 40 % slower.
 constexpr uint32_t kRowGridMax = 32768;       // grid y; further rows by striding
-static inline int mw_row_segments(int chunks) { return chunks > 0 ? (chunks + kRowBlock - 1) / kRowBlock : 1; }
+struct mw_row_shape { int bs; int nseg; };
+static inline mw_row_shape mw_row_shape_of(int chunks)
+{
+    if (chunks < 1) return mw_row_shape{64, 1};
+    if (chunks % 8 == 0) return mw_row_shape{64, (chunks + 63) / 64};
+    int b = (chunks + 63) / 64 * 64;
+    if (b > 1024) b = 1024;
+    return mw_row_shape{b, (chunks + b - 1) / b};
+}
 
 // Host-side context.  Every d_* pointer is a slice of the caller's workspace.
 struct mw_ctx {

@@ -6,27 +6,27 @@
 // source token index and top-k ids travel with it.
 //
 // The packer is a row gather bound by HBM bandwidth: packed[i] = x[perm[i]].  Rows are
-// multiples of 16 bytes.  Single-wave workgroups, each moving 64 consecutive 16-byte chunks
-// of one row with a single streaming load and store per lane: on MI355X many light waves
+// multiples of 16 bytes.  Small workgroups, each moving consecutive 16-byte chunks of one
+// row with a single streaming load and store per lane: on MI355X many light waves
 // follow the plain-copy ceiling more closely than fewer waves with several loads in flight.
 // Nothing is reused, so accesses are non-temporal.
 #include "mw_internal.h"
 
 namespace {
 
-// blockIdx.x = segment of 64 chunks, blockIdx.y walks packed rows.  Chunks [0, xc) come
+// blockIdx.x = segment of blockDim.x chunks, blockIdx.y walks packed rows.  Chunks [0, xc) come
 // from x, chunks [xc, xc + sc) from the fp8 scale rows (sc == 0 otherwise).  The row count
 // and the row's token are wave-uniform and fetched together (perm has room for every row
 // the grid can reach, so the read is in bounds even past the last kept row).
-__global__ __launch_bounds__(kRowBlock) void k_pack(const u32x4 *__restrict__ x, const u32x4 *__restrict__ scales,
+__global__ __launch_bounds__(1024) void k_pack(const u32x4 *__restrict__ x, const u32x4 *__restrict__ scales,
                                                     int xc, int sc, const int32_t *__restrict__ topk, int K,
                                                     const int32_t *__restrict__ perm,
                                                     const mw_send_stats *__restrict__ stats,
                                                     u32x4 *__restrict__ packed, int32_t *__restrict__ row_src_token,
                                                     int32_t *__restrict__ row_topk)
 {
-    uint32_t gdim = gridDim.y;
-    MW_PIN_S(gdim); MW_PIN_S(xc); MW_PIN_S(sc); MW_PIN_S(K);
+    uint32_t gdim = gridDim.y, bdim = blockDim.x;
+    MW_PIN_S(gdim); MW_PIN_S(bdim); MW_PIN_S(xc); MW_PIN_S(sc); MW_PIN_S(K);
     MW_PIN_PTR(x); MW_PIN_PTR(scales); MW_PIN_PTR(topk); MW_PIN_PTR(packed); MW_PIN_PTR(row_src_token);
     MW_PIN_PTR(row_topk);
     uint32_t i = blockIdx.y;
@@ -34,7 +34,7 @@ __global__ __launch_bounds__(kRowBlock) void k_pack(const u32x4 *__restrict__ x,
     uint32_t n_rows = stats->n_rows;
     MW_PIN_S(t); MW_PIN_S(n_rows);
     const int n = xc + sc;
-    const int c = blockIdx.x * kRowBlock + threadIdx.x;
+    const int c = blockIdx.x * bdim + threadIdx.x;
     while (i < n_rows) {
         if (c < n) {
             const u32x4 v = (c < xc) ? mw_ld16(x + (size_t)t * xc + c) : mw_ld16(scales + (size_t)t * sc + (c - xc));
@@ -42,7 +42,7 @@ __global__ __launch_bounds__(kRowBlock) void k_pack(const u32x4 *__restrict__ x,
         }
         if (blockIdx.x == 0) {
             if (threadIdx.x == 0) row_src_token[i] = t;
-            for (int j = threadIdx.x; j < K; j += kRowBlock) row_topk[(size_t)i * K + j] = topk[(size_t)t * K + j];
+            for (int j = threadIdx.x; j < K; j += bdim) row_topk[(size_t)i * K + j] = topk[(size_t)t * K + j];
         }
         i += gdim;
         if (i < n_rows) t = perm[i];
@@ -105,11 +105,11 @@ int32_t mw_launch_pack(mw_ctx *ctx, const void *x, const float *scales, const in
 {
     if (T == 0) return MW_OK;
     const int xc = (int)(ctx->x_row_bytes / 16), sc = (int)(ctx->s_row_bytes / 16);
-    const int nseg = mw_row_segments(xc + sc);
+    const mw_row_shape shape = mw_row_shape_of(xc + sc);
     const uint32_t gy = (uint32_t)T < kRowGridMax ? (uint32_t)T : kRowGridMax;
     {
         mw_timed tm(ctx, MW_KERNEL_PACK, s);
-        hipLaunchKernelGGL(k_pack, dim3(nseg, gy), dim3(kRowBlock), 0, s, (const u32x4 *)x, (const u32x4 *)scales, xc, sc,
+        hipLaunchKernelGGL(k_pack, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, (const u32x4 *)x, (const u32x4 *)scales, xc, sc,
                            topk, ctx->cfg.top_k, perm, stats, (u32x4 *)packed, row_src_token, row_topk);
     }
     MW_HIP_CHECK(hipGetLastError());

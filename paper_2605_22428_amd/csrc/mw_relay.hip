@@ -15,9 +15,9 @@
 //                  block scans (group index, first row), so the child is in parent order
 //                  whatever the timing.  The (group, hop) -> first child row table feeds the
 //                  copy.  One more workgroup maps rows to groups and does the byte accounting.
-//   k_relay_copy   single-wave workgroups, each moving 64 consecutive 16-byte chunks of one
-//                  input row: read once, stored once per next hop that keeps the row's group
-//                  (lane h holds hop h's position; a ballot lists the hops).  Bound by HBM
+//   k_relay_copy   small workgroups (a single wave for cache-line-sized rows), each moving
+//                  consecutive 16-byte chunks of one input row: read once, stored once per next hop that keeps the row's group
+//                  (lane h of every wave holds hop h's position; a ballot lists the hops).  Bound by HBM
 //                  bandwidth: rows * row_bytes read, rows * copies * row_bytes written.
 #include "mw_internal.h"
 
@@ -170,16 +170,16 @@ __global__ __launch_bounds__(kBlock) void k_relay_index(
     if (err) atomicOr(relay_flags, err);
 }
 
-// blockIdx.x selects a segment of 64 chunks of a row, blockIdx.y walks input rows.
-__global__ __launch_bounds__(kRowBlock) void k_relay_copy(
+// blockIdx.x selects a segment of blockDim.x chunks of a row, blockIdx.y walks input rows.
+__global__ __launch_bounds__(1024) void k_relay_copy(
     const mw_recv_peer *__restrict__ in, const mw_relay_child *__restrict__ children, int n_hops, int K, int n_chunks,
     uint32_t max_tokens, uint64_t row_bytes, const int32_t *__restrict__ group_of_row,
     const uint32_t *__restrict__ child_pos, uint32_t *relay_flags, mw_relay_stats *__restrict__ stats)
 {
     const mw_recv_peer src = in[0];
     const uint32_t n_rows = min(src.n_rows, max_tokens), n_desc = min(src.n_desc, max_tokens);
-    const int c = blockIdx.x * kRowBlock + threadIdx.x;
-    const int lane = threadIdx.x;
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    const int lane = threadIdx.x & 63;
     for (uint32_t i = blockIdx.y; i < n_rows; i += gridDim.y) {
         const int32_t g = group_of_row[i];
         if (g < 0 || (uint32_t)g >= n_desc) continue;        // (stale or never written)
@@ -227,11 +227,11 @@ int32_t mw_launch_relay(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay_chil
                            ctx->d_hop_bits, ctx->d_group_of_row, ctx->d_child_pos, ctx->d_relay_flags, stats);
     }
     {
-        const int nseg = mw_row_segments(n_chunks);
+        const mw_row_shape shape = mw_row_shape_of(n_chunks);
         uint32_t gy = (uint32_t)c.max_tokens < kRowGridMax ? (uint32_t)c.max_tokens : kRowGridMax;
         if (gy < 1) gy = 1;
         mw_timed tm(ctx, MW_KERNEL_RELAY_COPY, s);
-        hipLaunchKernelGGL(k_relay_copy, dim3(nseg, gy), dim3(kRowBlock), 0, s, in, children, ctx->n_hops, c.top_k, n_chunks,
+        hipLaunchKernelGGL(k_relay_copy, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, in, children, ctx->n_hops, c.top_k, n_chunks,
                            (uint32_t)c.max_tokens, (uint64_t)ctx->row_bytes, ctx->d_group_of_row, ctx->d_child_pos,
                            ctx->d_relay_flags, stats);
     }

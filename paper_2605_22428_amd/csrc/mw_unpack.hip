@@ -18,8 +18,8 @@
 //                 peer and (expert slot, rank) pairs.  The workgroup that finishes last
 //                 (device-scope counter) scans the counts into output bases, so no
 //                 third launch and no grid-wide barrier is needed.
-//   k_expand      single-wave workgroups, each moving 64 consecutive 16-byte chunks of one
-//                 received row (rows beyond 32768 by striding): the chunk is read once
+//   k_expand      small workgroups (a single wave for cache-line-sized rows), each moving
+//                 consecutive 16-byte chunks of one received row (rows beyond 32768 by striding): the chunk is read once
 //                 with a streaming load and stored to each of the row's experts' slots.
 //                 Measured on MI355X, many small waves with a single load in flight each
 //                 track the plain-copy ceiling, while fewer waves with deep per-lane
@@ -358,13 +358,13 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
     mw_finish_counts(cnt, addr_cnt, flags, (uint32_t)L, (uint32_t)P, out_cap, base, expert_offsets, stats, scratch);
 }
 
-// blockIdx.x selects a segment of 64 chunks of the row; blockIdx.y walks rows.  All
+// blockIdx.x selects a segment of blockDim.x chunks of the row; blockIdx.y walks rows.  All
 // index reads are wave-uniform (scalar loads).  The dependent chain in front of a row's
 // payload is what a one-shot workgroup cannot hide, so it is kept to two steps: the row
 // record and the row count are fetched together, then the payload load and the lookup of
 // the first output position are issued together; the position is there long before the
 // payload is.
-__global__ __launch_bounds__(kRowBlock) void k_expand(
+__global__ __launch_bounds__(1024) void k_expand(
     const mw_row_rec *__restrict__ recs, const mw_hit *__restrict__ hits, const uint32_t *__restrict__ base,
     const uint32_t *__restrict__ row_base, int P, int Kd, int xc, int sc,
     u32x4 *__restrict__ out_rows, u32x4 *__restrict__ out_scales, uint32_t cap,
@@ -373,12 +373,12 @@ __global__ __launch_bounds__(kRowBlock) void k_expand(
     // Every kernel argument is fetched in the first batch, not after the first branch.
     // Pointers are pinned through a copy of their low half, so the originals keep their
     // address space.
-    uint32_t gdim = gridDim.y;
-    MW_PIN_S(gdim); MW_PIN_S(Kd); MW_PIN_S(xc); MW_PIN_S(sc); MW_PIN_S(cap);
+    uint32_t gdim = gridDim.y, bdim = blockDim.x;
+    MW_PIN_S(gdim); MW_PIN_S(bdim); MW_PIN_S(Kd); MW_PIN_S(xc); MW_PIN_S(sc); MW_PIN_S(cap);
     MW_PIN_PTR(hits); MW_PIN_PTR(out_rows); MW_PIN_PTR(out_scales); MW_PIN_PTR(out_src_peer);
     MW_PIN_PTR(out_src_token);
     const int n = xc + sc;
-    const int c = blockIdx.x * kRowBlock + threadIdx.x;
+    const int c = blockIdx.x * bdim + threadIdx.x;
     uint32_t g = blockIdx.y;
     // gridDim.y <= max_recv_rows, so the first record read is always inside the workspace
     const u32x4 *rp = (const u32x4 *)(recs + g);
@@ -436,10 +436,10 @@ int32_t mw_launch_unpack(mw_ctx *ctx, const mw_recv_peer *peers, int32_t P, void
     }
     if (c.max_recv_rows > 0) {
         const int xc = (int)(ctx->x_row_bytes / 16), sc = (int)(ctx->s_row_bytes / 16);
-        const int nseg = mw_row_segments(xc + sc);
+        const mw_row_shape shape = mw_row_shape_of(xc + sc);
         const uint32_t gy = (uint32_t)(c.max_recv_rows < kRowGridMax ? c.max_recv_rows : kRowGridMax);
         mw_timed tm(ctx, MW_KERNEL_EXPAND, s);
-        hipLaunchKernelGGL(k_expand, dim3(nseg, gy), dim3(kRowBlock), 0, s, ctx->d_recs, ctx->d_hits, ctx->d_base,
+        hipLaunchKernelGGL(k_expand, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, ctx->d_recs, ctx->d_hits, ctx->d_base,
                            ctx->d_row_base, P, Kd, xc, sc, (u32x4 *)out_rows, (u32x4 *)out_scales,
                            (uint32_t)(cap < 0x7fffffffLL ? cap : 0x7fffffffLL), out_src_peer, out_src_token);
     }
