@@ -19,20 +19,18 @@
 //                 (device-scope counter) scans the counts into output bases, so no
 //                 third launch and no grid-wide barrier is needed.
 //   k_expand      small workgroups (a single wave for cache-line-sized rows), each moving
-//                 consecutive 16-byte chunks of one received row (rows beyond 32768 by striding): the chunk is read once
-//                 with a streaming load and stored to each of the row's experts' slots.
-//                 Measured on MI355X, many small waves with a single load in flight each
-//                 track the plain-copy ceiling, while fewer waves with deep per-lane
-//                 unrolling fall 10-30 % short, and a persistent grid loses ~5 % to the
-//                 hardware dispatcher.  This kernel moves ~all receive-side bytes and is
-//                 bound by HBM bandwidth.
+//                 consecutive 16-byte chunks of one received row (rows beyond 32768 by
+//                 striding): a chunk is read once with a streaming load and stored to each
+//                 of the row's experts' slots.  Measured on MI355X, many small waves with
+//                 a single load in flight each track the plain-copy ceiling, while fewer
+//                 waves with deep per-lane unrolling fall 10-30 % short, and a persistent
+//                 grid loses ~5 % to the hardware dispatcher.  This kernel moves ~all
+//                 receive-side bytes and is bound by HBM bandwidth.
 #include "mw_internal.h"
 
 namespace {
 
 constexpr int kIndexBlock = 1024;
-
-__device__ __forceinline__ bool mask_has(const uint64_t *m, int r) { return (m[r >> 6] >> (r & 63)) & 1ull; }
 
 __device__ __forceinline__ uint32_t ld_agent(const uint32_t *p)
 {
