@@ -167,11 +167,13 @@ def bench_dispatch(args, name: str) -> dict:
         ctx.mw_unpack(s["table"], R, rv.out_rows, rv.out_scales, cap, rv.out_src_peer, rv.out_src_token,
                       rv.expert_offsets, rv.stats)
 
-    # Default schedule ("aligned"): two streams and one cross-stream wait per step.  The packer
-    # (bandwidth-bound, short) is held back until the previous batch's expander has finished, so it
-    # runs beside the receive index (latency-bound, moves almost nothing) instead of competing
-    # with the expander for HBM; the plan of the next batch (latency-bound) runs beside the
-    # expander.  "free" lets the two streams drift, "single" issues everything on one stream.
+    # Schedules of a step (all move the same bytes through the same kernels):
+    #  "aligned" (default)  two streams and one cross-stream wait per step.  The packer
+    #            (bandwidth-bound, short) is held back until the previous batch's expander has
+    #            finished, so the two bandwidth-bound kernels do not share HBM and the expander's
+    #            launches show its own rate; the plan of the next batch (latency-bound) runs
+    #            beside the expander.
+    #  "free"    the two streams drift.     "single"   everything on one stream.
     ev_unpack_done = [torch.cuda.Event() for _ in range(2)]
     state = {"n": 0}
 
@@ -198,6 +200,9 @@ def bench_dispatch(args, name: str) -> dict:
                 recv_side(s)
                 ev_unpack_done[n % 2].record(s_recv)
 
+    def set_expand_events(a, b):
+        ctx.mw_ctx_set_timing_events(B.MW_KERNEL_EXPAND, a, b)
+
     # ---------------------------------------------------------------- warm-up, then the timed region
     for i in range(args.warmup):
         step(i)
@@ -215,13 +220,13 @@ def bench_dispatch(args, name: str) -> dict:
     t0 = time.perf_counter()
     for i in range(args.steps):
         if i % EV_STRIDE == 0:
-            ctx.mw_ctx_set_timing_events(B.MW_KERNEL_EXPAND, *ev_expand[i // EV_STRIDE])
+            set_expand_events(*ev_expand[i // EV_STRIDE])
         elif i % EV_STRIDE == 1:
-            ctx.mw_ctx_set_timing_events(B.MW_KERNEL_EXPAND, None, None)
+            set_expand_events(None, None)
         step(i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ctx.mw_ctx_set_timing_events(B.MW_KERNEL_EXPAND, None, None)
+    set_expand_events(None, None)
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     expand_ms = sorted(a.elapsed_time(b) for a, b in ev_expand)
     expand_avg_ms = sum(expand_ms) / len(expand_ms)

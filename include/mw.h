@@ -225,6 +225,22 @@ MW_API int32_t mw_unpack(mw_ctx *ctx, const mw_recv_peer *peers_dev, int32_t n_p
                   int64_t *expert_offsets_dev, mw_recv_stats *recv_stats_dev, void *stream);
 
 /*
+ * The two halves of mw_unpack as separate calls, so that a caller with several batches in
+ * flight can run the latency-bound half of the next batch beside the bandwidth-bound half of
+ * the current one.  mw_unpack_index reads the peers' metadata, writes expert_offsets and the
+ * statistics and leaves one record per received row in the context's workspace;
+ * mw_unpack_expand moves the payload as those records say.  mw_unpack(...) is exactly
+ * mw_unpack_index(...) followed by mw_unpack_expand(...) with the same arguments on the same
+ * stream.  The expand must be ordered after its index (same stream, or an event), the peers'
+ * buffers must stay unchanged in between, and a context's workspace holds one index at a
+ * time: batches in flight at once need one context each.
+ */
+MW_API int32_t mw_unpack_index(mw_ctx *ctx, const mw_recv_peer *peers_dev, int32_t n_peers, int64_t out_capacity_rows,
+                        int64_t *expert_offsets_dev, mw_recv_stats *recv_stats_dev, void *stream);
+MW_API int32_t mw_unpack_expand(mw_ctx *ctx, int32_t n_peers, void *out_rows_dev, float *out_scales_dev,
+                         int64_t out_capacity_rows, int32_t *out_src_peer_dev, int32_t *out_src_token_dev, void *stream);
+
+/*
  * AllGather result (Section 5.2): out = shard of rank 0, rank 1, ... rank R-1
  * side by side.  peer_shards_dev: device array of n_ranks device pointers.
  */

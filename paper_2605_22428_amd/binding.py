@@ -23,7 +23,8 @@ MW_FLAG_BAD_EXPERT, MW_FLAG_OUT_CAPACITY, MW_FLAG_NO_LOCAL_EXPERT = 0x01, 0x02, 
 MW_FLAG_BAD_SRC_TOKEN, MW_FLAG_BAD_DESC, MW_FLAG_RECV_CAPACITY, MW_FLAG_DUP_SRC_TOKEN = 0x08, 0x10, 0x20, 0x40
 
 EXPORTS = ["mw_workspace_bytes", "mw_ctx_create", "mw_ctx_destroy", "mw_plan", "mw_pack",
-           "mw_plan_allgather", "mw_pack_allgather", "mw_unpack", "mw_unpack_allgather",
+           "mw_plan_allgather", "mw_pack_allgather", "mw_unpack", "mw_unpack_index", "mw_unpack_expand",
+           "mw_unpack_allgather",
            "mw_sim_deliver", "mw_copy_bytes", "mw_get_send_stats", "mw_get_recv_stats",
            "mw_set_forwarding", "mw_relay", "mw_get_relay_stats",
            "mw_allgather_split_point", "mw_plan_allgather_split", "mw_unpack_allgather_split",
@@ -196,6 +197,17 @@ class Context:
         _check(load().mw_unpack(self._h, _ptr(peers), C.c_int32(n_peers), _ptr(out_rows), _ptr(out_scales),
                                 C.c_int64(out_capacity_rows), _ptr(out_src_peer), _ptr(out_src_token),
                                 _ptr(expert_offsets), _ptr(recv_stats), _stream()), "mw_unpack")
+
+    def mw_unpack_index(self, peers: torch.Tensor, n_peers: int, out_capacity_rows: int,
+                        expert_offsets: torch.Tensor, recv_stats: torch.Tensor):
+        _check(load().mw_unpack_index(self._h, _ptr(peers), C.c_int32(n_peers), C.c_int64(out_capacity_rows),
+                                      _ptr(expert_offsets), _ptr(recv_stats), _stream()), "mw_unpack_index")
+
+    def mw_unpack_expand(self, n_peers: int, out_rows: torch.Tensor, out_scales: Optional[torch.Tensor],
+                         out_capacity_rows: int, out_src_peer: torch.Tensor, out_src_token: torch.Tensor):
+        _check(load().mw_unpack_expand(self._h, C.c_int32(n_peers), _ptr(out_rows), _ptr(out_scales),
+                                       C.c_int64(out_capacity_rows), _ptr(out_src_peer), _ptr(out_src_token),
+                                       _stream()), "mw_unpack_expand")
 
     def mw_unpack_allgather(self, peer_shards: torch.Tensor, shard_bytes: int, out: torch.Tensor):
         _check(load().mw_unpack_allgather(self._h, _ptr(peer_shards), C.c_int64(shard_bytes), _ptr(out),

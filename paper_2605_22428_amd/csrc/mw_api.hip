@@ -263,13 +263,21 @@ MW_API int32_t mw_unpack_allgather_split(mw_ctx *ctx, const void *const *direct_
                                   (hipStream_t)stream);
 }
 
-MW_API int32_t mw_unpack(mw_ctx *ctx, const mw_recv_peer *peers_dev, int32_t n_peers, void *out_rows_dev,
-                  float *out_scales_dev, int64_t out_capacity_rows, int32_t *out_src_peer_dev,
-                  int32_t *out_src_token_dev, int64_t *expert_offsets_dev, mw_recv_stats *recv_stats_dev,
-                  void *stream)
+static int32_t check_unpack_index(mw_ctx *ctx, const mw_recv_peer *peers_dev, int32_t n_peers,
+                                  int64_t out_capacity_rows, int64_t *expert_offsets_dev, mw_recv_stats *recv_stats_dev)
 {
     if (!ctx || !peers_dev || !expert_offsets_dev || !recv_stats_dev || out_capacity_rows < 0)
         return MW_ERR_INVALID_ARG;
+    if (n_peers < 1 || n_peers > ctx->cfg.n_ranks) return MW_ERR_INVALID_ARG;
+    if (ctx->cfg.n_experts == 0) return MW_ERR_INVALID_ARG;
+    if (out_capacity_rows > 0xffffffffLL) return MW_ERR_UNSUPPORTED;
+    return MW_OK;
+}
+
+static int32_t check_unpack_expand(mw_ctx *ctx, int32_t n_peers, void *out_rows_dev, float *out_scales_dev,
+                                   int64_t out_capacity_rows, int32_t *out_src_peer_dev, int32_t *out_src_token_dev)
+{
+    if (!ctx || out_capacity_rows < 0) return MW_ERR_INVALID_ARG;
     if (n_peers < 1 || n_peers > ctx->cfg.n_ranks) return MW_ERR_INVALID_ARG;
     if (ctx->cfg.n_experts == 0) return MW_ERR_INVALID_ARG;
     if (out_capacity_rows > 0 && (!out_rows_dev || !out_src_peer_dev || !out_src_token_dev))
@@ -277,9 +285,43 @@ MW_API int32_t mw_unpack(mw_ctx *ctx, const mw_recv_peer *peers_dev, int32_t n_p
     if (out_capacity_rows > 0 && (ctx->s_row_bytes > 0) != (out_scales_dev != nullptr)) return MW_ERR_INVALID_ARG;
     if (out_capacity_rows > 0xffffffffLL) return MW_ERR_UNSUPPORTED;
     if (((uintptr_t)out_rows_dev | (uintptr_t)out_scales_dev) & 15u) return MW_ERR_INVALID_ARG;
-    return mw_launch_unpack(ctx, peers_dev, n_peers, out_rows_dev, out_scales_dev, out_capacity_rows,
-                            out_src_peer_dev, out_src_token_dev, expert_offsets_dev, recv_stats_dev,
-                            (hipStream_t)stream);
+    return MW_OK;
+}
+
+MW_API int32_t mw_unpack(mw_ctx *ctx, const mw_recv_peer *peers_dev, int32_t n_peers, void *out_rows_dev,
+                  float *out_scales_dev, int64_t out_capacity_rows, int32_t *out_src_peer_dev,
+                  int32_t *out_src_token_dev, int64_t *expert_offsets_dev, mw_recv_stats *recv_stats_dev,
+                  void *stream)
+{
+    int32_t rc = check_unpack_index(ctx, peers_dev, n_peers, out_capacity_rows, expert_offsets_dev, recv_stats_dev);
+    if (rc == MW_OK)
+        rc = check_unpack_expand(ctx, n_peers, out_rows_dev, out_scales_dev, out_capacity_rows, out_src_peer_dev,
+                                 out_src_token_dev);
+    if (rc != MW_OK) return rc;
+    rc = mw_launch_unpack_index(ctx, peers_dev, n_peers, out_capacity_rows, expert_offsets_dev, recv_stats_dev,
+                                (hipStream_t)stream);
+    if (rc != MW_OK) return rc;
+    return mw_launch_unpack_expand(ctx, n_peers, out_rows_dev, out_scales_dev, out_capacity_rows, out_src_peer_dev,
+                                   out_src_token_dev, (hipStream_t)stream);
+}
+
+MW_API int32_t mw_unpack_index(mw_ctx *ctx, const mw_recv_peer *peers_dev, int32_t n_peers, int64_t out_capacity_rows,
+                        int64_t *expert_offsets_dev, mw_recv_stats *recv_stats_dev, void *stream)
+{
+    const int32_t rc = check_unpack_index(ctx, peers_dev, n_peers, out_capacity_rows, expert_offsets_dev, recv_stats_dev);
+    if (rc != MW_OK) return rc;
+    return mw_launch_unpack_index(ctx, peers_dev, n_peers, out_capacity_rows, expert_offsets_dev, recv_stats_dev,
+                                  (hipStream_t)stream);
+}
+
+MW_API int32_t mw_unpack_expand(mw_ctx *ctx, int32_t n_peers, void *out_rows_dev, float *out_scales_dev,
+                         int64_t out_capacity_rows, int32_t *out_src_peer_dev, int32_t *out_src_token_dev, void *stream)
+{
+    const int32_t rc = check_unpack_expand(ctx, n_peers, out_rows_dev, out_scales_dev, out_capacity_rows,
+                                           out_src_peer_dev, out_src_token_dev);
+    if (rc != MW_OK) return rc;
+    return mw_launch_unpack_expand(ctx, n_peers, out_rows_dev, out_scales_dev, out_capacity_rows, out_src_peer_dev,
+                                   out_src_token_dev, (hipStream_t)stream);
 }
 
 MW_API int32_t mw_unpack_allgather(mw_ctx *ctx, const void *const *peer_shards_dev, int64_t shard_bytes, void *out_dev,

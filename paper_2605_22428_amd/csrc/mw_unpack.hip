@@ -411,9 +411,8 @@ __global__ __launch_bounds__(1024) void k_expand(
 
 }  // namespace
 
-int32_t mw_launch_unpack(mw_ctx *ctx, const mw_recv_peer *peers, int32_t P, void *out_rows,
-                         float *out_scales, int64_t cap, int32_t *out_src_peer, int32_t *out_src_token,
-                         int64_t *expert_offsets, mw_recv_stats *stats, hipStream_t s)
+int32_t mw_launch_unpack_index(mw_ctx *ctx, const mw_recv_peer *peers, int32_t P, int64_t cap,
+                               int64_t *expert_offsets, mw_recv_stats *stats, hipStream_t s)
 {
     const mw_config &c = ctx->cfg;
     const int L = ctx->n_local, Kd = ctx->hit_slots;
@@ -432,13 +431,21 @@ int32_t mw_launch_unpack(mw_ctx *ctx, const mw_recv_peer *peers, int32_t P, void
                            ctx->d_row_base, ctx->d_addr_cnt, ctx->d_recs, ctx->d_hits, ctx->d_base,
                            expert_offsets, stats, ctx->d_flags);
     }
+    MW_HIP_CHECK(hipGetLastError());
+    return MW_OK;
+}
+
+int32_t mw_launch_unpack_expand(mw_ctx *ctx, int32_t P, void *out_rows, float *out_scales, int64_t cap,
+                                int32_t *out_src_peer, int32_t *out_src_token, hipStream_t s)
+{
+    const mw_config &c = ctx->cfg;
     if (c.max_recv_rows > 0) {
         const int xc = (int)(ctx->x_row_bytes / 16), sc = (int)(ctx->s_row_bytes / 16);
         const mw_row_shape shape = mw_row_shape_of(xc + sc);
         const uint32_t gy = (uint32_t)(c.max_recv_rows < kRowGridMax ? c.max_recv_rows : kRowGridMax);
         mw_timed tm(ctx, MW_KERNEL_EXPAND, s);
         hipLaunchKernelGGL(k_expand, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, ctx->d_recs, ctx->d_hits, ctx->d_base,
-                           ctx->d_row_base, P, Kd, xc, sc, (u32x4 *)out_rows, (u32x4 *)out_scales,
+                           ctx->d_row_base, P, ctx->hit_slots, xc, sc, (u32x4 *)out_rows, (u32x4 *)out_scales,
                            (uint32_t)(cap < 0x7fffffffLL ? cap : 0x7fffffffLL), out_src_peer, out_src_token);
     }
     MW_HIP_CHECK(hipGetLastError());

@@ -156,6 +156,51 @@ def test_c3_full_size_receive_median_rank():
                  sample_peers=(0, 255))
 
 
+def test_unpack_in_two_calls_with_two_contexts_in_flight():
+    """mw_unpack_index + mw_unpack_expand == mw_unpack; two batches indexed before either is
+    expanded (one context each), on two streams with an event between the halves."""
+    w = W.scaled(W.C1, n_tokens=150, hidden=512)
+    e2r = W.expert_to_rank(w)
+    batches = []
+    for seed, my_rank in ((1, 3), (2, 40)):
+        ctx = H.make_ctx(w, my_rank)
+        recs, toks = [], []
+        for p in range(w.n_ranks):
+            tk = W.topk_ids(w, seed, p)
+            x, sc = W.payload_rows(w, seed, p)
+            g = H.GpuSend(ctx, tk, x, sc)
+            recs.append(H.shrink(g.deliver(my_rank)))
+            toks.append((tk, x, sc))
+        cap = sum(r["n_rows"] for r in recs) * 4
+        batches.append(dict(ctx=ctx, recs=recs, toks=toks, cap=cap, table=B.peers_table(recs, H.DEV),
+                            buf=B.RecvBuffers(ctx, cap), my_rank=my_rank))
+    s_idx, s_exp = torch.cuda.Stream(), torch.cuda.Stream()
+    done = [torch.cuda.Event() for _ in batches]
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s_idx):
+        for b, ev in zip(batches, done):
+            b["ctx"].mw_unpack_index(b["table"], w.n_ranks, b["cap"], b["buf"].expert_offsets, b["buf"].stats)
+            ev.record(s_idx)
+    with torch.cuda.stream(s_exp):
+        for b, ev in zip(batches, done):
+            s_exp.wait_event(ev)
+            b["ctx"].mw_unpack_expand(w.n_ranks, b["buf"].out_rows, None, b["cap"], b["buf"].out_src_peer,
+                                      b["buf"].out_src_token)
+    torch.cuda.synchronize()
+    for b in batches:
+        want = ref.dispatch_plain(b["toks"], e2r, b["my_rank"], b["cap"])
+        st = b["ctx"].mw_get_recv_stats(b["buf"].stats)
+        q = int(st["n_out_rows"])
+        assert int(st["error_flags"]) == 0
+        H.assert_same_bytes(H.host(b["buf"].expert_offsets), want[4], "two-call expert_offsets")
+        H.assert_same_bytes(H.host(b["buf"].out_rows)[:q], want[0], "two-call out_rows")
+        H.assert_same_bytes(H.host(b["buf"].out_src_peer)[:q], want[2], "two-call out_src_peer")
+        H.assert_same_bytes(H.host(b["buf"].out_src_token)[:q], want[3], "two-call out_src_token")
+        one = H.GpuUnpack(b["ctx"], b["recs"], b["cap"])          # the single call, same context
+        H.check_unpack(one, want, "single call")
+        b["ctx"].close()
+
+
 # ------------------------------------------------------------------ AllGather
 @pytest.mark.parametrize("w", [W.AllGatherWorkload("ag_small", 41, 8, 1000 * 8), W.C4],
                          ids=["small", "C4_full"])
