@@ -109,7 +109,13 @@ static inline int64_t mw_align_up(int64_t v, int64_t a) { return (v + a - 1) / a
 // Streaming 16-byte accesses: payload rows are touched once, keep them out of the way of
 // the small, reused index arrays.
 __device__ __forceinline__ u32x4 mw_ld16(const u32x4 *p) { return __builtin_nontemporal_load(p); }
-__device__ __forceinline__ void mw_st16(u32x4 *p, u32x4 v) { __builtin_nontemporal_store(v, p); }
+// The store is streaming and written through (sc0 sc1 nt): the lines leave the L2 as they are
+// written, so the end of the kernel has nothing left to write back and the next launch on the
+// stream starts about two microseconds sooner than with a plain non-temporal store.
+__device__ __forceinline__ void mw_st16(u32x4 *p, u32x4 v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt" ::"v"(p), "v"(v) : "memory");
+}
 // The same load through a pointer that was read from memory: saying that it is a global
 // address keeps it off the flat path, whose loads also count as LDS traffic and would make
 // every later wait for a scalar load wait for the payload too.
