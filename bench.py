@@ -168,12 +168,15 @@ def bench_dispatch(args, name: str) -> dict:
                       rv.expert_offsets, rv.stats)
 
     # Schedules of a step (all move the same bytes through the same kernels):
-    #  "aligned" (default)  two streams and one cross-stream wait per step.  The packer
-    #            (bandwidth-bound, short) is held back until the previous batch's expander has
-    #            finished, so the two bandwidth-bound kernels do not share HBM and the expander's
-    #            launches show its own rate; the plan of the next batch (latency-bound) runs
-    #            beside the expander.
-    #  "free"    the two streams drift.     "single"   everything on one stream.
+    #  "free" (default)  the send side and the receive side are independent operations; each is
+    #            issued on its own stream and the two drift.  The latency-bound kernels of one side
+    #            run beside the bandwidth-bound kernels of the other; when packer and expander
+    #            overlap they share HBM (an expander launch then takes longer by about the packer's
+    #            bytes).
+    #  "aligned" one cross-stream wait per step holds the packer back until the previous batch's
+    #            expander has finished, so the two bandwidth-bound kernels never share HBM and the
+    #            expander's launches show its own rate (the wait itself costs about 10 us).
+    #  "single"  everything on one stream.
     ev_unpack_done = [torch.cuda.Event() for _ in range(2)]
     state = {"n": 0}
 
@@ -214,7 +217,7 @@ def bench_dispatch(args, name: str) -> dict:
 
     # An event pair costs a few microseconds of bubble on this platform, so the expander is
     # bracketed on every EV_STRIDE-th step of the timed region only.
-    EV_STRIDE = 4
+    EV_STRIDE = 8
     ev_expand = new_events(torch, (args.steps + EV_STRIDE - 1) // EV_STRIDE)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -466,7 +469,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", choices=["c0", "c1", "c2", "c3", "c4"], default="c1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--schedule", choices=["aligned", "free", "single"], default="aligned",
+    ap.add_argument("--schedule", choices=["aligned", "free", "single"], default="free",
                     help="how the send side and the receive side of a step are issued (see step())")
     ap.add_argument("--seed", type=int, default=None)
     args = ap.parse_args()

@@ -338,17 +338,20 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
         // no expert lives here: any addressed row is inconsistent
         for (uint32_t w = tid; w < wpl; w += nthr) if (addr[w]) err |= MW_FLAG_NO_LOCAL_EXPERT;
     }
-    if (err) atomicOr(&flags[1], err);
+    if (err) __hip_atomic_fetch_or(&flags[1], err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (tid == 0) st_agent(&addr_cnt[p], scratch[18]);
 
     // ---- the workgroup that finishes last turns the counts into output bases ----------
-    // Counts, addressed-row counts and flags are published with device-scope atomics; the
-    // barrier orders them before thread 0's release fence and counter increment.
+    // Everything the last workgroup reads (counts, addressed-row counts, flags) is written and
+    // read with device-scope atomics, which are performed at the device's coherence point and
+    // bypass the per-XCD L2.  __syncthreads() makes every wave wait until its stores have been
+    // acknowledged there, so thread 0's counter increment is performed after them; no
+    // device-scope fence (a write-back of the whole L2) is needed.  The row records and hit
+    // slots, written with ordinary stores, are read by the next kernel only.
     __syncthreads();
     if (tid == 0) {
-        __threadfence();
-        const bool last = atomicAdd(&flags[2], 1u) == (uint32_t)P - 1u;
-        __threadfence();
+        const bool last = __hip_atomic_fetch_add(&flags[2], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                          (uint32_t)P - 1u;
         scratch[17] = last ? 1u : 0u;
     }
     __syncthreads();
