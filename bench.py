@@ -168,14 +168,14 @@ def bench_dispatch(args, name: str) -> dict:
                       rv.expert_offsets, rv.stats)
 
     # Schedules of a step (all move the same bytes through the same kernels):
-    #  "free" (default)  the send side and the receive side are independent operations; each is
-    #            issued on its own stream and the two drift.  The latency-bound kernels of one side
-    #            run beside the bandwidth-bound kernels of the other; when packer and expander
-    #            overlap they share HBM (an expander launch then takes longer by about the packer's
-    #            bytes).
-    #  "aligned" one cross-stream wait per step holds the packer back until the previous batch's
-    #            expander has finished, so the two bandwidth-bound kernels never share HBM and the
-    #            expander's launches show its own rate (the wait itself costs about 10 us).
+    #  "aligned" (default)  the send side and the receive side are independent operations, each
+    #            issued on its own stream; one cross-stream wait per step holds the packer back
+    #            until the previous batch's expander has finished.  The packer (bandwidth-bound,
+    #            short) then runs beside the receive index (latency-bound, moves almost nothing),
+    #            the plan of the next batch (latency-bound) beside the expander, and the two
+    #            bandwidth-bound kernels never share HBM: the expander's launches show its own rate.
+    #  "free"    no wait: the two streams drift; when packer and expander overlap, an expander
+    #            launch takes longer by about the packer's bytes.
     #  "single"  everything on one stream.
     ev_unpack_done = [torch.cuda.Event() for _ in range(2)]
     state = {"n": 0}
@@ -469,7 +469,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", choices=["c0", "c1", "c2", "c3", "c4"], default="c1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--schedule", choices=["aligned", "free", "single"], default="free",
+    ap.add_argument("--schedule", choices=["aligned", "free", "single"], default="aligned",
                     help="how the send side and the receive side of a step are issued (see step())")
     ap.add_argument("--seed", type=int, default=None)
     args = ap.parse_args()
