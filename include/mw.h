@@ -99,7 +99,7 @@ typedef struct mw_recv_stats {
     uint64_t n_recv_rows;       /* M: received rows whose group bitmap names this rank */
     uint64_t n_out_rows;        /* Q: (row, local expert) pairs = rows of the expert-major output */
     uint32_t error_flags;       /* MW_FLAG_* */
-    uint32_t reserved0;
+    uint32_t n_rows_seen;       /* rows in the peers' buffers, addressed to this rank or not */
 } mw_recv_stats;                /* 24 bytes */
 
 /*
@@ -352,7 +352,10 @@ MW_API int32_t mw_sim_deliver(mw_ctx *ctx, const mw_group_desc *desc_dev, const 
  * row movers are compared with, and the reference kernel for counter scaling. */
 MW_API int32_t mw_copy_bytes(void *dst_dev, const void *src_dev, int64_t n_bytes, void *stream);
 
-/* Copy a statistics block to the host.  SYNCHRONISES `stream`. */
+/* Copy a statistics block to the host.  SYNCHRONISES `stream`.  mw_get_recv_stats also lets
+ * the context remember how many rows the peers' buffers held, and the next mw_unpack sizes its
+ * launch for about that many rows instead of max_recv_rows (a hint only: any number of rows
+ * up to max_recv_rows is still handled). */
 MW_API int32_t mw_get_send_stats(mw_ctx *ctx, const mw_send_stats *stats_dev, mw_send_stats *host_out, void *stream);
 MW_API int32_t mw_get_recv_stats(mw_ctx *ctx, const mw_recv_stats *stats_dev, mw_recv_stats *host_out, void *stream);
 MW_API int32_t mw_get_relay_stats(mw_ctx *ctx, const mw_relay_stats *stats_dev, mw_relay_stats *host_out, void *stream);

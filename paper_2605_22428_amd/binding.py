@@ -41,7 +41,7 @@ SEND_STATS_DTYPE = np.dtype([("n_rows", "<u4"), ("n_groups", "<u4"), ("multicast
                              ("unicast_bytes", "<u8"), ("rows_per_dest", "<u4", (256,)),
                              ("error_flags", "<u4"), ("reserved0", "<u4")])
 RECV_STATS_DTYPE = np.dtype([("n_recv_rows", "<u8"), ("n_out_rows", "<u8"), ("error_flags", "<u4"),
-                             ("reserved0", "<u4")])
+                             ("n_rows_seen", "<u4")])
 RECV_PEER_DTYPE = np.dtype([("desc", "<u8"), ("n_desc", "<u4"), ("n_rows", "<u4"), ("rows", "<u8"),
                             ("row_src_token", "<u8"), ("row_topk", "<u8")])
 RELAY_CHILD_DTYPE = np.dtype([("desc", "<u8"), ("rows", "<u8"), ("row_src_token", "<u8"), ("row_topk", "<u8")])

@@ -145,6 +145,7 @@ MW_API int32_t mw_ctx_create(const mw_config *cfg, void *workspace_dev, int64_t 
     ctx->d_hits = (mw_hit *)(b + w.hits);
     ctx->d_row_map = (int32_t *)(b + w.row_map);
     ctx->n_hops = 0;
+    ctx->recv_rows_hint = 0;
     ctx->d_hop_bits = (uint64_t *)(b + w.hop_bits);
     ctx->d_relay_flags = (uint32_t *)(b + w.hop_bits + 8LL * MW_MASK_WORDS * MW_MAX_HOPS);
     ctx->d_group_of_row = (int32_t *)(b + w.group_of_row);
@@ -374,6 +375,7 @@ MW_API int32_t mw_get_recv_stats(mw_ctx *ctx, const mw_recv_stats *stats_dev, mw
     if (!ctx || !stats_dev || !host_out) return MW_ERR_INVALID_ARG;
     MW_HIP_CHECK(hipMemcpyAsync(host_out, stats_dev, sizeof(mw_recv_stats), hipMemcpyDeviceToHost, (hipStream_t)stream));
     MW_HIP_CHECK(hipStreamSynchronize((hipStream_t)stream));
+    ctx->recv_rows_hint = host_out->n_rows_seen;       // sizes the next mw_unpack's launch
     return MW_OK;
 }
 

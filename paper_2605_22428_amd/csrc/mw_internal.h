@@ -72,6 +72,7 @@ struct mw_ctx {
     uint32_t *d_addr_cnt;   // [R] rows of peer p whose group names this rank
     mw_hit *d_hits;         // [max_recv_rows][Kd]
     int32_t *d_row_map;     // [max_tokens] mw_sim_deliver: kept row -> sender row
+    int64_t recv_rows_hint; // rows the peers' buffers held at the last mw_get_recv_stats (0: unknown)
     // relay (only with cfg.max_hops > 0)
     int32_t n_hops;         // 0 until mw_set_forwarding
     uint64_t *d_hop_bits;   // [MW_MAX_HOPS][4] ranks served through each next hop

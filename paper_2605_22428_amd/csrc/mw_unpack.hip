@@ -45,14 +45,16 @@ __device__ __forceinline__ void st_agent(uint32_t *p, uint32_t v)
 // offsets, totals and flags.  `scratch` is LDS scan scratch of 17 words.  Every device-scope
 // read that does not depend on another is issued before the first scan.
 __device__ __forceinline__ void mw_finish_counts(const uint32_t *cnt, const uint32_t *addr_cnt, uint32_t *flags,
-                                                 uint32_t L, uint32_t P, int64_t out_cap, uint32_t *base,
-                                                 int64_t *expert_offsets, mw_recv_stats *stats, uint32_t *scratch)
+                                                 const uint32_t *row_base, uint32_t L, uint32_t P, int64_t out_cap,
+                                                 uint32_t *base, int64_t *expert_offsets, mw_recv_stats *stats,
+                                                 uint32_t *scratch)
 {
     const uint32_t tid = threadIdx.x, nthr = blockDim.x;
     const uint32_t n_lp = L * P;
     uint32_t m = 0;
     for (uint32_t q = tid; q < P; q += nthr) m += ld_agent(&addr_cnt[q]);
     const uint32_t err = (tid == 0) ? ld_agent(&flags[1]) : 0u;
+    const uint32_t row_base_total = (tid == 0) ? ld_agent(&row_base[P]) : 0u;
     uint32_t v_next = (tid < n_lp) ? ld_agent(&cnt[tid]) : 0u;
     uint32_t carry = 0;
     for (uint32_t f0 = 0; f0 < n_lp; f0 += nthr) {          // (expert, peer) order = output order
@@ -74,7 +76,7 @@ __device__ __forceinline__ void mw_finish_counts(const uint32_t *cnt, const uint
         stats->n_recv_rows = m_tot;
         stats->n_out_rows = Q;
         stats->error_flags = err | (((int64_t)Q > out_cap) ? MW_FLAG_OUT_CAPACITY : 0u);
-        stats->reserved0 = 0;
+        stats->n_rows_seen = row_base_total;
         st_agent(&flags[1], 0u);           // ready for the next unpack
         st_agent(&flags[2], 0u);
     }
@@ -84,7 +86,7 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
     const mw_recv_peer *__restrict__ peers, int P, const int32_t *__restrict__ eslot,
     int E, int K, int Kd, int my_rank, int L, int Lc,
     uint32_t max_tokens, uint32_t wpl, uint32_t cap_rows, uint64_t row_bytes, int64_t out_cap,
-    uint32_t *cnt, uint32_t *__restrict__ row_base, uint32_t *addr_cnt, mw_row_rec *__restrict__ recs,
+    uint32_t *cnt, uint32_t *row_base, uint32_t *addr_cnt, mw_row_rec *__restrict__ recs,
     mw_hit *__restrict__ hits, uint32_t *__restrict__ base, int64_t *__restrict__ expert_offsets,
     mw_recv_stats *__restrict__ stats, uint32_t *flags)
 {
@@ -153,7 +155,7 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
     const uint32_t n_rows = min(before + mine, cap_rows) - rb;
     if (tid == 0) {
         row_base[p] = rb;
-        if (p == P - 1) row_base[P] = rb + n_rows;
+        if (p == P - 1) st_agent(&row_base[P], rb + n_rows);    // (also read by the last workgroup)
     }
 
     // ---- addressed rows: groups whose bitmap has this rank's bit
@@ -356,7 +358,8 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
     }
     __syncthreads();
     if (!scratch[17]) return;
-    mw_finish_counts(cnt, addr_cnt, flags, (uint32_t)L, (uint32_t)P, out_cap, base, expert_offsets, stats, scratch);
+    mw_finish_counts(cnt, addr_cnt, flags, row_base, (uint32_t)L, (uint32_t)P, out_cap, base, expert_offsets, stats,
+                     scratch);
 }
 
 // blockIdx.x selects a segment of blockDim.x chunks of the row; blockIdx.y walks rows.  All
@@ -445,7 +448,15 @@ int32_t mw_launch_unpack_expand(mw_ctx *ctx, int32_t P, void *out_rows, float *o
     if (c.max_recv_rows > 0) {
         const int xc = (int)(ctx->x_row_bytes / 16), sc = (int)(ctx->s_row_bytes / 16);
         const mw_row_shape shape = mw_row_shape_of(xc + sc);
-        const uint32_t gy = (uint32_t)(c.max_recv_rows < kRowGridMax ? c.max_recv_rows : kRowGridMax);
+        // Workgroups are dispatched at a finite rate, empty ones included: the grid is sized for
+        // about as many rows as the peers held last time (if the caller has asked for the
+        // statistics), not for the capacity.  More rows than that are reached by striding.
+        int64_t rows = c.max_recv_rows;
+        if (ctx->recv_rows_hint > 0) {
+            const int64_t want = ctx->recv_rows_hint + ctx->recv_rows_hint / 64 + 64;
+            if (want < rows) rows = want;
+        }
+        const uint32_t gy = (uint32_t)(rows < kRowGridMax ? rows : kRowGridMax);
         mw_timed tm(ctx, MW_KERNEL_EXPAND, s);
         hipLaunchKernelGGL(k_expand, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, ctx->d_recs, ctx->d_hits, ctx->d_base,
                            ctx->d_row_base, P, ctx->hit_slots, xc, sc, (u32x4 *)out_rows, (u32x4 *)out_scales,
