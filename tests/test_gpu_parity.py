@@ -201,6 +201,35 @@ def test_unpack_in_two_calls_with_two_contexts_in_flight():
         b["ctx"].close()
 
 
+def test_unpack_after_a_smaller_batch_strides_over_the_rows():
+    """The expander's launch is sized from the row count seen at the last mw_get_recv_stats; a later,
+    larger batch on the same context must still be expanded completely (and a smaller one too)."""
+    w = W.scaled(W.C1, n_tokens=300, hidden=256)
+    e2r = W.expert_to_rank(w)
+    my_rank = 9
+    ctx = H.make_ctx(w, my_rank)
+    recs, toks = [], []
+    for p in range(w.n_ranks):
+        tk = W.topk_ids(w, 7, p)
+        x, sc = W.payload_rows(w, 7, p)
+        g = H.GpuSend(ctx, tk, x, sc)
+        recs.append(H.shrink(g.deliver(my_rank)))
+        toks.append((tk, x, sc))
+    empty = [(np.full_like(t[0], -1), t[1], t[2]) for t in toks]
+    few = [dict(r, n_desc=0, n_rows=0) for r in recs]
+    few[5] = recs[5]
+    cap = sum(r["n_rows"] for r in recs) * 4
+    small = H.GpuUnpack(ctx, few, cap)                     # reads the statistics: the hint is now tiny
+    H.check_unpack(small, ref.dispatch_plain(empty[:5] + [toks[5]] + empty[6:], e2r, my_rank, cap), "one peer")
+    assert int(small.stats["n_rows_seen"]) == recs[5]["n_rows"]
+    big = H.GpuUnpack(ctx, recs, cap)                      # ~60 times as many rows as the hint
+    H.check_unpack(big, ref.dispatch_plain(toks, e2r, my_rank, cap), "all peers after one peer")
+    assert int(big.stats["n_rows_seen"]) == sum(r["n_rows"] for r in recs)
+    again = H.GpuUnpack(ctx, few, cap)                     # and back
+    H.check_unpack(again, ref.dispatch_plain(empty[:5] + [toks[5]] + empty[6:], e2r, my_rank, cap), "one peer again")
+    ctx.close()
+
+
 # ------------------------------------------------------------------ AllGather
 @pytest.mark.parametrize("w", [W.AllGatherWorkload("ag_small", 41, 8, 1000 * 8), W.C4],
                          ids=["small", "C4_full"])
