@@ -302,6 +302,39 @@ def bench_dispatch(args, name: str) -> dict:
                  "copy_pct_of_hbm_peak": round(100.0 * relay_bytes / relay_us["relay_copy"] / 1e3 / HBM_PEAK_GBPS, 2)}
         del children
 
+    # ---------------------------------------------------------------- decode-sized send side (extra, untimed region)
+    # The first 64 / 128 tokens of this rank's batch (the small batch sizes of the paper's
+    # dispatch experiment, Section 6.3): mw_plan + mw_pack against the single launch of
+    # mw_plan_pack, back to back on one stream.
+    decode = {}
+    sd0 = sets[0]["send"]
+    for Td in (64, 128):
+        if Td > T:
+            continue
+        tk_s, x_s = topk_d[:Td], sets[0]["x"][:Td]
+        sc_s = sets[0]["sc"][:Td] if fp8 else None
+
+        def two_calls():
+            ctx.mw_plan(tk_s, sd0.mask, sd0.perm, sd0.desc, sd0.stats)
+            ctx.mw_pack(x_s, sc_s, tk_s, sd0.perm, sd0.stats, sd0.packed, sd0.row_src_token, sd0.row_topk)
+
+        def one_launch():
+            ctx.mw_plan_pack(tk_s, x_s, sc_s, sd0.mask, sd0.perm, sd0.desc, sd0.stats, sd0.packed,
+                             sd0.row_src_token, sd0.row_topk)
+
+        us = {}
+        for label, fn in (("plan_then_pack_us", two_calls), ("plan_pack_us", one_launch)):
+            for _ in range(10):
+                fn()
+            (a, b), = new_events(torch, 1)
+            a.record()
+            for _ in range(100):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            us[label] = round(10.0 * a.elapsed_time(b), 2)
+        decode["%d_tokens" % Td] = us
+
     # ---------------------------------------------------------------- algorithmic bytes
     pack_bytes = 2 * N * rb + N * (4 + 4 * K) + N * 4 + N * 4 * K
     unpack_bytes = M * rb + Q * rb + M * (4 + 4 * K) + n_desc_total * 48 + Q * 8 + (L + 1) * 8
@@ -337,6 +370,8 @@ def bench_dispatch(args, name: str) -> dict:
     }
     if relay is not None:
         result["relay"] = relay
+    if decode:
+        result["decode_send_side"] = decode
 
     # ---------------------------------------------------------------- oracle on the host cores
     if not args.no_cpu_baseline and name == "c1":

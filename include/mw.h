@@ -45,6 +45,7 @@ extern "C" {
 #define MW_MAX_RANKS  256        /* Section 6.4: bitmaps wider than 64 bit; 256 ranks here */
 #define MW_MAX_TOPK   64
 #define MW_MAX_HOPS   64         /* next hops (egress ports) a relay's forwarding table may name */
+#define MW_FUSED_MAX_TOKENS 256  /* largest batch mw_plan_pack takes */
 
 /* status codes */
 #define MW_OK                 0
@@ -190,6 +191,20 @@ MW_API int32_t mw_pack(mw_ctx *ctx, const void *x_dev, const float *scales_dev,
                 const mw_send_stats *stats_dev, int32_t n_tokens,
                 void *packed_rows_dev, int32_t *row_src_token_dev, int32_t *row_topk_dev,
                 void *stream);
+
+/*
+ * mw_plan_pack: mw_plan followed by mw_pack for a decode-sized batch, as one kernel launch.
+ * Section 6.3 (AlltoAll dispatch over batch sizes): at 64 and 128 tokens per rank the fixed
+ * cost of a MultiWrite, not the bytes, decides; here that cost is launches and their
+ * dependencies.  Every output is byte for byte what the two calls write (same argument
+ * meaning, layout and error flags).  0 <= n_tokens <= min(max_tokens, MW_FUSED_MAX_TOKENS);
+ * more returns MW_ERR_CAPACITY and nothing is enqueued.  Uses no workspace, so it may overlap
+ * other calls on the same context.
+ */
+MW_API int32_t mw_plan_pack(mw_ctx *ctx, const int32_t *topk_ids_dev, const void *x_dev, const float *scales_dev,
+                     int32_t n_tokens, uint64_t *mask_dev, int32_t *perm_dev, mw_group_desc *desc_dev,
+                     mw_send_stats *stats_dev, void *packed_rows_dev, int32_t *row_src_token_dev,
+                     int32_t *row_topk_dev, void *stream);
 
 /*
  * AllGather as a MultiWrite with a static destination set (Section 2.3.3,
@@ -376,7 +391,8 @@ MW_API int32_t mw_get_relay_stats(mw_ctx *ctx, const mw_relay_stats *stats_dev, 
 #define MW_KERNEL_AG_GATHER    6   /* mw_unpack_allgather's shard assembly */
 #define MW_KERNEL_RELAY_INDEX  7
 #define MW_KERNEL_RELAY_COPY   8
-#define MW_KERNEL_COUNT        9
+#define MW_KERNEL_PLAN_PACK    9   /* mw_plan_pack's single kernel */
+#define MW_KERNEL_COUNT        10
 MW_API int32_t mw_ctx_set_timing_events(mw_ctx *ctx, int32_t kernel, void *ev_start, void *ev_stop);
 
 MW_API const char *mw_status_string(int32_t status);

@@ -211,6 +211,25 @@ MW_API int32_t mw_pack(mw_ctx *ctx, const void *x_dev, const float *scales_dev, 
                           row_src_token_dev, row_topk_dev, (hipStream_t)stream);
 }
 
+MW_API int32_t mw_plan_pack(mw_ctx *ctx, const int32_t *topk_ids_dev, const void *x_dev, const float *scales_dev,
+                     int32_t n_tokens, uint64_t *mask_dev, int32_t *perm_dev, mw_group_desc *desc_dev,
+                     mw_send_stats *stats_dev, void *packed_rows_dev, int32_t *row_src_token_dev,
+                     int32_t *row_topk_dev, void *stream)
+{
+    if (!ctx || !stats_dev || n_tokens < 0) return MW_ERR_INVALID_ARG;
+    if (n_tokens > ctx->cfg.max_tokens || n_tokens > MW_FUSED_MAX_TOKENS) return MW_ERR_CAPACITY;
+    if (ctx->cfg.n_experts == 0) return MW_ERR_INVALID_ARG;
+    if (n_tokens > 0) {
+        if (!topk_ids_dev || !mask_dev || !perm_dev || !desc_dev || !x_dev || !packed_rows_dev || !row_src_token_dev ||
+            !row_topk_dev)
+            return MW_ERR_INVALID_ARG;
+        if ((ctx->s_row_bytes > 0) != (scales_dev != nullptr)) return MW_ERR_INVALID_ARG;
+        if (((uintptr_t)x_dev | (uintptr_t)packed_rows_dev | (uintptr_t)scales_dev) & 15u) return MW_ERR_INVALID_ARG;
+    }
+    return mw_launch_plan_pack(ctx, topk_ids_dev, n_tokens, x_dev, scales_dev, mask_dev, perm_dev, desc_dev, stats_dev,
+                               packed_rows_dev, row_src_token_dev, row_topk_dev, (hipStream_t)stream);
+}
+
 MW_API int32_t mw_plan_allgather(mw_ctx *ctx, int64_t shard_bytes, mw_group_desc *desc_dev, mw_send_stats *stats_dev,
                           void *stream)
 {

@@ -177,6 +177,9 @@ int32_t mw_launch_plan(mw_ctx *ctx, const int32_t *topk, int32_t T, uint64_t *ma
 int32_t mw_launch_pack(mw_ctx *ctx, const void *x, const float *scales, const int32_t *topk,
                        const int32_t *perm, const mw_send_stats *stats, int32_t T, void *packed,
                        int32_t *row_src_token, int32_t *row_topk, hipStream_t s);
+int32_t mw_launch_plan_pack(mw_ctx *ctx, const int32_t *topk, int32_t T, const void *x, const float *scales,
+                            uint64_t *mask, int32_t *perm, mw_group_desc *desc, mw_send_stats *stats, void *packed,
+                            int32_t *row_src_token, int32_t *row_topk, hipStream_t s);
 int32_t mw_launch_unpack_index(mw_ctx *ctx, const mw_recv_peer *peers, int32_t P, int64_t cap,
                                int64_t *expert_offsets, mw_recv_stats *stats, hipStream_t s);
 int32_t mw_launch_unpack_expand(mw_ctx *ctx, int32_t P, void *out_rows, float *out_scales, int64_t cap,

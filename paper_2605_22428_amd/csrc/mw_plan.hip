@@ -264,6 +264,157 @@ __global__ __launch_bounds__(256) void k_plan_allgather_split(int R, uint64_t sh
     }
 }
 
+// Plan and pack of a decode-sized batch (at most kFusedMax tokens) in one launch.  The results
+// are those of k_rank + k_groups + the packer; what changes is the latency: three dependent
+// launches and two rounds of global atomics become one launch without any global scratch.
+// Workgroup b moves packed row b.  To find that row's token every workgroup builds all
+// bitmaps in LDS and ranks all tokens itself (one token per lane): for so few tokens that is
+// cheaper than waiting for another workgroup's result.  The first workgroup also writes the
+// bitmaps, perm and the descriptors, the last one the statistics.
+constexpr int kFusedMax = MW_FUSED_MAX_TOKENS;
+static_assert(kFusedMax == kBlock, "one token per lane");
+
+// a < b for bitmaps of W words, word W - 1 most significant
+template <int W>
+__device__ __forceinline__ bool mask_less(const uint64_t *a, const uint64_t *b)
+{
+    bool lt = false, eq = true;
+#pragma unroll
+    for (int w = W - 1; w >= 0; --w) {
+        lt = lt || (eq && a[w] < b[w]);
+        eq = eq && (a[w] == b[w]);
+    }
+    return lt;
+}
+
+template <int W>
+__global__ __launch_bounds__(kBlock) void k_plan_pack(const int32_t *__restrict__ topk, int T, int K,
+                                                      const int32_t *__restrict__ eslot, int E,
+                                                      const u32x4 *__restrict__ x, const u32x4 *__restrict__ scales,
+                                                      int xc, int sc, uint64_t row_bytes,
+                                                      uint64_t *__restrict__ mask_out, int32_t *__restrict__ perm,
+                                                      mw_group_desc *__restrict__ desc, mw_send_stats *__restrict__ stats,
+                                                      u32x4 *__restrict__ packed, int32_t *__restrict__ row_src_token,
+                                                      int32_t *__restrict__ row_topk)
+{
+    __shared__ uint64_t smask[kFusedMax * W];
+    __shared__ int32_t tok[kFusedMax];            // token of packed row i
+    __shared__ uint32_t gstart[kFusedMax + 1];    // first packed row of group g
+    __shared__ uint32_t hist[MW_MAX_RANKS];
+    __shared__ uint32_t scratch[17];
+    __shared__ uint32_t any_bad;
+    const int t = threadIdx.x, lane = t & 63;
+    bool bad = false;
+    uint64_t m[MW_MASK_WORDS] = {0, 0, 0, 0};
+    if (t < T) token_mask(topk + (size_t)t * K, K, eslot, E, m, bad);
+#pragma unroll
+    for (int w = 0; w < W; ++w) smask[t * W + w] = m[w];
+    hist[t] = 0;
+    if (t == 0) any_bad = 0;
+    const bool any = (m[0] | m[1] | m[2] | m[3]) != 0;
+    uint32_t N;
+    mw_block_exscan(any ? 1u : 0u, scratch, &N);          // its barriers also publish smask
+    if (bad) atomicOr(&any_bad, 1u);
+
+    // Packed row of token t = number of kept tokens u with (bitmap, u) < (bitmap, t).  Whether
+    // u < t is the same for the whole wavefront except among its own 64 tokens, so the walk
+    // splits into "bitmap <= mine" before them, the full test among them, "bitmap < mine" after
+    // them.  An empty bitmap is below every kept one: all T - N of them are counted and taken
+    // off again.
+    const int w0 = min(t & ~63, T), w1 = min(w0 + 64, T);
+    uint32_t c = 0;
+#pragma unroll 4
+    for (int u = 0; u < w0; ++u) c += mask_less<W>(m, smask + u * W) ? 0u : 1u;
+#pragma unroll 4
+    for (int u = w0; u < w1; ++u) {
+        const uint64_t *q = smask + u * W;
+        c += (mask_less<W>(q, m) || (u < t && !mask_less<W>(m, q))) ? 1u : 0u;
+    }
+#pragma unroll 4
+    for (int u = w1; u < T; ++u) c += mask_less<W>(smask + u * W, m) ? 1u : 0u;
+    const uint32_t p = c - ((uint32_t)T - N);
+    if (any) tok[p] = t;
+    mw_lds_barrier();
+
+    const uint32_t i = blockIdx.x;
+    if (i < N) {
+        const int32_t tt = tok[i];
+        const int n = xc + sc;
+        for (int ch = t; ch < n; ch += kBlock) {
+            const u32x4 v = (ch < xc) ? mw_ld16(x + (size_t)tt * xc + ch)
+                                      : mw_ld16(scales + (size_t)tt * sc + (ch - xc));
+            mw_st16(packed + (size_t)i * n + ch, v);
+        }
+        if (t == 0) row_src_token[i] = tt;
+        for (int j = t; j < K; j += kBlock) row_topk[(size_t)i * K + j] = topk[(size_t)tt * K + j];
+    }
+    const bool writes_plan = blockIdx.x == 0, writes_stats = blockIdx.x == gridDim.x - 1;
+    if (!writes_plan && !writes_stats) return;
+
+    // groups: lane i looks at packed row i; a group starts where the bitmap differs from the
+    // row before
+    bool start = false;
+    if ((uint32_t)t < N) {
+        const uint64_t *q = smask + tok[t] * W;
+        start = t == 0 || mask_less<W>(smask + tok[t - 1] * W, q);
+    }
+    uint32_t G;
+    const uint32_t g = mw_block_exscan(start ? 1u : 0u, scratch, &G);
+    if (writes_plan) {
+        if (start) gstart[g] = (uint32_t)t;
+        if (t == 0) gstart[G] = N;
+        if (t < T) {
+            uint64_t *o = mask_out + (size_t)t * MW_MASK_WORDS;
+#pragma unroll
+            for (int q = 0; q < MW_MASK_WORDS; ++q) o[q] = m[q];
+        }
+        if (any) perm[p] = t;
+        mw_lds_barrier();
+        if (start) {
+            const uint64_t *q = smask + tok[t] * W;
+            mw_group_desc d;
+            uint32_t nd = 0;
+#pragma unroll
+            for (int w = 0; w < MW_MASK_WORDS; ++w) {
+                d.mask[w] = (w < W) ? q[w < W ? w : 0] : 0ull;
+                nd += (uint32_t)__popcll(d.mask[w]);
+            }
+            d.row_offset = (uint32_t)t;
+            d.row_count = gstart[g + 1] - (uint32_t)t;
+            d.n_dest = nd;
+            d.reserved0 = 0;
+            desc[g] = d;
+        }
+    }
+    if (writes_stats) {
+        // rows per destination: a wavefront ballot of bit b over 64 tokens, popcounted, is the
+        // number of those tokens that name rank 64 q + b; lane b keeps it
+#pragma unroll
+        for (int q = 0; q < W; ++q) {
+            if (__ballot(m[q] != 0) == 0) continue;      // wave-uniform
+            uint32_t mine = 0;
+            for (int b = 0; b < 64; ++b) {
+                const uint32_t n_b = (uint32_t)__popcll(__ballot((m[q] >> b) & 1ull));
+                if (lane == b) mine = n_b;
+            }
+            if (mine) atomicAdd(&hist[q * 64 + lane], mine);
+        }
+        mw_lds_barrier();
+        const uint32_t h = hist[t];
+        stats->rows_per_dest[t] = h;
+        uint32_t D;
+        mw_block_exscan(h, scratch, &D);
+        if (t == 0) {
+            stats->n_rows = N;
+            stats->n_groups = G;
+            stats->multicast_bytes = (uint64_t)N * row_bytes;
+            stats->unicast_bytes = (uint64_t)D * row_bytes;
+            stats->error_flags = any_bad ? MW_FLAG_BAD_EXPERT : 0u;
+            stats->reserved0 = 0;
+        }
+    }
+}
+
 }  // namespace
 
 int32_t mw_launch_plan_allgather_split(mw_ctx *ctx, int64_t shard_bytes, int64_t direct_bytes, mw_group_desc *desc,
@@ -311,6 +462,32 @@ int32_t mw_launch_plan(mw_ctx *ctx, const int32_t *topk, int32_t T, uint64_t *ma
     ctx->plan_T[oth] = 0;        // cleared by this plan
     ctx->plan_T[cur] = T;        // to be cleared by the next one
     ctx->plan_parity = oth;
+    MW_HIP_CHECK(hipGetLastError());
+    return MW_OK;
+}
+
+
+int32_t mw_launch_plan_pack(mw_ctx *ctx, const int32_t *topk, int32_t T, const void *x, const float *scales,
+                            uint64_t *mask, int32_t *perm, mw_group_desc *desc, mw_send_stats *stats, void *packed,
+                            int32_t *row_src_token, int32_t *row_topk, hipStream_t s)
+{
+    static_assert(MW_MAX_RANKS == kBlock, "one lane per rank in the statistics");
+    const int xc = (int)(ctx->x_row_bytes / 16), sc = (int)(ctx->s_row_bytes / 16);
+    const dim3 grid(T > 0 ? T : 1), block(kBlock);
+    const int K = ctx->cfg.top_k, E = ctx->cfg.n_experts;
+    const uint64_t rb = (uint64_t)ctx->row_bytes;
+    mw_timed tm(ctx, MW_KERNEL_PLAN_PACK, s);
+#define MW_FUSED(W)                                                                                              \
+    hipLaunchKernelGGL(k_plan_pack<W>, grid, block, 0, s, topk, T, K, ctx->d_eslot, E, (const u32x4 *)x,         \
+                       (const u32x4 *)scales, xc, sc, rb, mask, perm, desc, stats, (u32x4 *)packed, row_src_token, \
+                       row_topk)
+    switch (ctx->mask_words) {
+    case 1: MW_FUSED(1); break;
+    case 2: MW_FUSED(2); break;
+    case 3: MW_FUSED(3); break;
+    default: MW_FUSED(4); break;
+    }
+#undef MW_FUSED
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;
 }

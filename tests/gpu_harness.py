@@ -47,18 +47,24 @@ def host(t: torch.Tensor, dtype=None) -> np.ndarray:
 
 
 class GpuSend:
-    """mw_plan + mw_pack of one rank's tokens; host copies of everything written."""
+    """mw_plan + mw_pack (or the single-launch mw_plan_pack) of one rank's tokens; host copies
+    of everything written."""
 
     def __init__(self, ctx: B.Context, topk: np.ndarray, x: np.ndarray, scales: Optional[np.ndarray],
-                 x_dev: Optional[torch.Tensor] = None, scales_dev: Optional[torch.Tensor] = None):
+                 x_dev: Optional[torch.Tensor] = None, scales_dev: Optional[torch.Tensor] = None,
+                 fused: bool = False):
         self.ctx, self.T = ctx, topk.shape[0]
         self.topk_d = dev(topk.astype(np.int32))
         self.x_d = x_dev if x_dev is not None else dev(x)
         self.s_d = scales_dev if scales_dev is not None else dev(scales)
         self.buf = B.SendBuffers(ctx, self.T)
-        ctx.mw_plan(self.topk_d, self.buf.mask, self.buf.perm, self.buf.desc, self.buf.stats)
-        ctx.mw_pack(self.x_d, self.s_d, self.topk_d, self.buf.perm, self.buf.stats, self.buf.packed,
-                    self.buf.row_src_token, self.buf.row_topk)
+        if fused:
+            ctx.mw_plan_pack(self.topk_d, self.x_d, self.s_d, self.buf.mask, self.buf.perm, self.buf.desc,
+                             self.buf.stats, self.buf.packed, self.buf.row_src_token, self.buf.row_topk)
+        else:
+            ctx.mw_plan(self.topk_d, self.buf.mask, self.buf.perm, self.buf.desc, self.buf.stats)
+            ctx.mw_pack(self.x_d, self.s_d, self.topk_d, self.buf.perm, self.buf.stats, self.buf.packed,
+                        self.buf.row_src_token, self.buf.row_topk)
         self.stats = ctx.mw_get_send_stats(self.buf.stats)
         self.N, self.G = int(self.stats["n_rows"]), int(self.stats["n_groups"])
 
