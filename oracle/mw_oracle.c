@@ -650,3 +650,157 @@ int ref_unpack_allgather_split(const uint8_t *const *direct, const uint8_t *cons
     }
     return REF_OK;
 }
+
+/* ------------------------------------------------------------------------ */
+/*
+ * Packets: the bitmap embedded in the payload (Section 6.4, "Metadata
+ * overhead", second option: for more ranks than a protocol field holds, the
+ * metadata travels in front of the data) together with the rest of what a
+ * receiver needs (Section 4.3.4, statelessness: all mapping information is in
+ * the packet).  The paper fixes no layout; this reading:
+ *   packet = header | row,   header_bytes = 40 + 4K rounded up to 128
+ *   header: bytes  0..31  destination bitmap, 4 little-endian 64-bit words
+ *           bytes 32..35  index of the token at its source (int32)
+ *           bytes 36..39  K (uint32)
+ *           bytes 40..    the token's K expert ids (int32 each), as the gate
+ *                         emitted them; the rest of the header is zero.
+ * 128 bytes in front of a 4096-byte payload is the paper's own example of the
+ * cost (1024 bit per 4096 byte = 3.13 %).
+ */
+int64_t ref_packet_header_bytes(int32_t K)
+{
+    if (K < 0) return REF_ERR_ARG;
+    return ((int64_t)40 + 4 * (int64_t)K + 127) / 128 * 128;
+}
+
+static void put_le(uint8_t *dst, uint64_t v, int n_bytes)
+{
+    for (int b = 0; b < n_bytes; ++b) dst[b] = (uint8_t)(v >> (8 * b));
+}
+
+static uint64_t get_le(const uint8_t *src, int n_bytes)
+{
+    uint64_t v = 0;
+    for (int b = 0; b < n_bytes; ++b) v |= (uint64_t)src[b] << (8 * b);
+    return v;
+}
+
+/* packet i = header of token perm[i] followed by its row (x part, then scales) */
+int ref_pack_packets(const uint8_t *x, int64_t x_row_bytes, const uint8_t *scales, int64_t s_row_bytes,
+                     const int32_t *topk, int32_t K, const uint64_t *mask /* [T][4] */,
+                     const int32_t *perm, int32_t N, uint8_t *packets /* [N][header + row bytes] */)
+{
+    if (x_row_bytes < 0 || s_row_bytes < 0 || (s_row_bytes > 0 && !scales) || K < 0) return REF_ERR_ARG;
+    const int64_t hb = ref_packet_header_bytes(K), pb = hb + x_row_bytes + s_row_bytes;
+    for (int32_t i = 0; i < N; ++i) {
+        const int32_t t = perm[i];
+        uint8_t *h = packets + (size_t)i * (size_t)pb;
+        memset(h, 0, (size_t)hb);
+        for (int w = 0; w < REF_MASK_WORDS; ++w) put_le(h + 8 * w, mask[(size_t)t * REF_MASK_WORDS + w], 8);
+        put_le(h + 32, (uint32_t)t, 4);
+        put_le(h + 36, (uint32_t)K, 4);
+        for (int32_t j = 0; j < K; ++j) put_le(h + 40 + 4 * j, (uint32_t)topk[(size_t)t * K + j], 4);
+        memcpy(h + hb, x + (size_t)t * (size_t)x_row_bytes, (size_t)x_row_bytes);
+        if (s_row_bytes > 0)
+            memcpy(h + hb + x_row_bytes, scales + (size_t)t * (size_t)s_row_bytes, (size_t)s_row_bytes);
+    }
+    return REF_OK;
+}
+
+/* Simulated network for packets (Section 4.1 step 4): the packets whose bitmap names dst_rank,
+ * in order, unchanged.  Returns how many were kept through *n_kept. */
+int ref_deliver_packets(const uint8_t *packets, int64_t n_packets, int64_t packet_bytes, int32_t dst_rank,
+                        uint8_t *out, int64_t *n_kept)
+{
+    if (dst_rank < 0 || dst_rank >= REF_MAX_RANKS || packet_bytes < 128) return REF_ERR_ARG;
+    int64_t n = 0;
+    for (int64_t i = 0; i < n_packets; ++i) {
+        const uint8_t *h = packets + (size_t)i * (size_t)packet_bytes;
+        const uint64_t word = get_le(h + 8 * (dst_rank >> 6), 8);
+        if (!((word >> (dst_rank & 63)) & 1u)) continue;
+        memcpy(out + (size_t)n * (size_t)packet_bytes, h, (size_t)packet_bytes);
+        ++n;
+    }
+    *n_kept = n;
+    return REF_OK;
+}
+
+typedef struct {
+    const uint8_t *packets;   /* [n_rows][packet_bytes] */
+    uint32_t n_rows;
+    uint32_t reserved0;
+} ref_recv_packets;
+
+typedef struct { int32_t token; int64_t packet; } token_at;
+
+static int token_at_cmp(const void *pa, const void *pb)
+{
+    const token_at *a = (const token_at *)pa, *b = (const token_at *)pb;
+    return (a->token > b->token) - (a->token < b->token);
+}
+
+/*
+ * Receive side for packets (Section 4.1 steps 3-4): every packet is parsed on
+ * its own.  If its bitmap names this rank, its row is delivered to each local
+ * expert among its ids.  Same output as ref_unpack: expert-major, inside an
+ * expert ordered by (source peer, source token index), whatever order the
+ * packets arrived in.
+ */
+int ref_unpack_packets(const ref_recv_packets *peers, int32_t P, int32_t K,
+                       const int32_t *expert_to_rank, int32_t E, int32_t my_rank,
+                       int64_t x_row_bytes, int64_t s_row_bytes, int64_t out_capacity_rows,
+                       uint8_t *out_rows, uint8_t *out_scales, int32_t *out_src_peer, int32_t *out_src_token,
+                       int64_t *expert_offsets /* [L+1] */, int64_t *n_recv_rows)
+{
+    if (my_rank < 0 || my_rank >= REF_MAX_RANKS || P < 0 || K < 0) return REF_ERR_ARG;
+    const int32_t L = local_count(expert_to_rank, E, my_rank);
+    const int64_t hb = ref_packet_header_bytes(K), pb = hb + x_row_bytes + s_row_bytes;
+    int bad = 0;
+    int64_t pos = 0, M = 0, most = 1;
+    for (int32_t p = 0; p < P; ++p) if ((int64_t)peers[p].n_rows > most) most = peers[p].n_rows;
+    token_at *list = (token_at *)malloc((size_t)most * sizeof(token_at));
+    int32_t *ids = (int32_t *)malloc((size_t)(K > 0 ? K : 1) * sizeof(int32_t));
+    if (!list || !ids) { free(list); free(ids); return REF_ERR_CAPACITY; }
+    int rc = REF_OK;
+
+    for (int32_t p = 0; p < P; ++p)
+        for (uint32_t i = 0; i < peers[p].n_rows; ++i) {
+            const uint8_t *h = peers[p].packets + (size_t)i * (size_t)pb;
+            if ((int64_t)get_le(h + 36, 4) != K) { rc = REF_ERR_INPUT; goto done; }
+            if ((get_le(h + 8 * (my_rank >> 6), 8) >> (my_rank & 63)) & 1u) ++M;
+        }
+    *n_recv_rows = M;
+
+    for (int32_t le = 0; le < L; ++le) {
+        expert_offsets[le] = pos;
+        for (int32_t p = 0; p < P; ++p) {
+            int64_t n = 0;
+            for (uint32_t i = 0; i < peers[p].n_rows; ++i) {
+                const uint8_t *h = peers[p].packets + (size_t)i * (size_t)pb;
+                if (!((get_le(h + 8 * (my_rank >> 6), 8) >> (my_rank & 63)) & 1u)) continue;
+                for (int32_t j = 0; j < K; ++j) ids[j] = (int32_t)(uint32_t)get_le(h + 40 + 4 * j, 4);
+                if (!row_hits(ids, K, expert_to_rank, E, my_rank, le, &bad)) continue;
+                list[n].token = (int32_t)(uint32_t)get_le(h + 32, 4);
+                list[n].packet = i;
+                ++n;
+            }
+            qsort(list, (size_t)n, sizeof(token_at), token_at_cmp);
+            for (int64_t k = 0; k < n; ++k) {
+                if (k > 0 && list[k].token == list[k - 1].token) { rc = REF_ERR_INPUT; goto done; }
+                if (pos >= out_capacity_rows) { rc = REF_ERR_CAPACITY; goto done; }
+                const uint8_t *row = peers[p].packets + (size_t)list[k].packet * (size_t)pb + hb;
+                memcpy(out_rows + (size_t)pos * (size_t)x_row_bytes, row, (size_t)x_row_bytes);
+                if (s_row_bytes > 0)
+                    memcpy(out_scales + (size_t)pos * (size_t)s_row_bytes, row + x_row_bytes, (size_t)s_row_bytes);
+                out_src_peer[pos] = p;
+                out_src_token[pos] = list[k].token;
+                ++pos;
+            }
+        }
+    }
+    expert_offsets[L] = pos;
+    if (bad) rc = REF_ERR_EXPERT;
+done:
+    free(list); free(ids);
+    return rc;
+}

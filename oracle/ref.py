@@ -36,6 +36,10 @@ class _RecvPeer(C.Structure):
                 ("rows", C.c_void_p), ("row_src_token", C.c_void_p), ("row_topk", C.c_void_p)]
 
 
+class _RecvPackets(C.Structure):
+    _fields_ = [("packets", C.c_void_p), ("n_rows", C.c_uint32), ("reserved0", C.c_uint32)]
+
+
 class _PeerTokens(C.Structure):
     _fields_ = [("topk", C.c_void_p), ("n_tokens", C.c_int32),
                 ("x", C.c_void_p), ("scales", C.c_void_p)]
@@ -52,8 +56,10 @@ def lib():
                      "ref_unpack", "ref_dispatch_plain", "ref_plan_allgather",
                      "ref_pack_allgather", "ref_unpack_allgather",
                      "ref_relay_child", "ref_relay_accounting", "ref_allgather_split_point",
-                     "ref_plan_allgather_split", "ref_unpack_allgather_split"):
+                     "ref_plan_allgather_split", "ref_unpack_allgather_split",
+                     "ref_pack_packets", "ref_deliver_packets", "ref_unpack_packets"):
             getattr(_lib, name).restype = C.c_int
+        _lib.ref_packet_header_bytes.restype = C.c_int64
     return _lib
 
 
@@ -301,3 +307,59 @@ def unpack_allgather_split(direct: Sequence[np.ndarray], relayed: Sequence[np.nd
     _check(lib().ref_unpack_allgather_split(dp, rp, C.c_int32(len(db)), C.c_int64(shard_bytes),
                                             C.c_int64(direct_bytes), _p(out)), "ref_unpack_allgather_split")
     return out
+
+
+# ---------------------------------------------------------------------------
+# packets: bitmap and row metadata embedded in front of every row (Section 6.4)
+def packet_header_bytes(top_k: int) -> int:
+    return int(lib().ref_packet_header_bytes(C.c_int32(top_k)))
+
+
+def pack_packets(x: np.ndarray, scales: Optional[np.ndarray], topk, mask: np.ndarray, perm) -> np.ndarray:
+    """-> uint8 [N][header_bytes + row_bytes]"""
+    topk, perm = _i32(topk), _i32(perm)
+    xb = _bytes2d(x)
+    sb = _bytes2d(scales) if scales is not None else None
+    mask = np.ascontiguousarray(mask, dtype=np.uint64)
+    K = topk.shape[1]
+    pb = packet_header_bytes(K) + xb.shape[1] + (sb.shape[1] if sb is not None else 0)
+    out = np.zeros((len(perm), pb), dtype=np.uint8)
+    _check(lib().ref_pack_packets(_p(xb), C.c_int64(xb.shape[1]), _p(sb),
+                                  C.c_int64(0 if sb is None else sb.shape[1]), _p(topk), C.c_int32(K), _p(mask),
+                                  _p(perm), C.c_int32(len(perm)), _p(out)), "ref_pack_packets")
+    return out
+
+
+def deliver_packets(packets: np.ndarray, dst_rank: int) -> np.ndarray:
+    packets = np.ascontiguousarray(packets, dtype=np.uint8)
+    out = np.zeros_like(packets)
+    n = C.c_int64(0)
+    _check(lib().ref_deliver_packets(_p(packets), C.c_int64(packets.shape[0]), C.c_int64(packets.shape[1]),
+                                     C.c_int32(dst_rank), _p(out), C.byref(n)), "ref_deliver_packets")
+    return out[: n.value]
+
+
+def unpack_packets(peers: Sequence[np.ndarray], top_k: int, e2r, my_rank: int, x_row_bytes: int,
+                   s_row_bytes: int, out_capacity_rows: int):
+    """peers[p] = uint8 [n_p][packet_bytes].  Same return value as unpack()."""
+    e2r = _i32(e2r)
+    L = int((e2r == my_rank).sum())
+    keep = []
+    arr = (_RecvPackets * max(len(peers), 1))()
+    for i, pk in enumerate(peers):
+        pk = np.ascontiguousarray(pk, dtype=np.uint8)
+        keep.append(pk)
+        arr[i] = _RecvPackets(pk.ctypes.data, pk.shape[0], 0)
+    cap = max(int(out_capacity_rows), 1)
+    out = np.zeros((cap, x_row_bytes), dtype=np.uint8)
+    osc = np.zeros((cap, s_row_bytes), dtype=np.uint8) if s_row_bytes else None
+    sp = np.full(cap, -1, dtype=np.int32)
+    stok = np.full(cap, -1, dtype=np.int32)
+    offs = np.zeros(L + 1, dtype=np.int64)
+    m = C.c_int64(0)
+    _check(lib().ref_unpack_packets(arr, C.c_int32(len(peers)), C.c_int32(top_k), _p(e2r), C.c_int32(len(e2r)),
+                                    C.c_int32(my_rank), C.c_int64(x_row_bytes), C.c_int64(s_row_bytes),
+                                    C.c_int64(out_capacity_rows), _p(out), _p(osc), _p(sp), _p(stok), _p(offs),
+                                    C.byref(m)), "ref_unpack_packets")
+    Q = int(offs[L])
+    return out[:Q], (osc[:Q] if osc is not None else None), sp[:Q], stok[:Q], offs, int(m.value)
