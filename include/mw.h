@@ -295,6 +295,51 @@ MW_API int32_t mw_plan_allgather_split(mw_ctx *ctx, int64_t shard_bytes, int64_t
 MW_API int32_t mw_unpack_allgather_split(mw_ctx *ctx, const void *const *direct_dev, const void *const *relayed_dev,
                                   int64_t shard_bytes, int64_t direct_bytes, void *out_dev, void *stream);
 
+/* ---- packets: bitmap and row metadata in front of every row ------------------------------
+ *
+ * Section 6.4, "Metadata overhead": when the bitmap does not fit a protocol field it is
+ * embedded in the payload (the paper's example: 1024 bit in front of 4096 byte, 3.13 %).
+ * Together with the source token and the expert ids this makes every row self-describing
+ * (Section 4.3.4, statelessness), so no descriptor table and no side arrays travel with it and
+ * a receiver can take packets in any order.  Layout of this build (the paper fixes none):
+ *   packet = header | row;  header_bytes = 40 + 4 * top_k rounded up to 128 (128 for top_k <= 22)
+ *   header: bytes  0..31  destination bitmap, mask[0..3] little endian
+ *           bytes 32..35  row_src_token (int32)
+ *           bytes 36..39  top_k (uint32)
+ *           bytes 40..    the token's top_k expert ids (int32), then zeros
+ * Packets are 16-byte aligned; a whole number of 128-byte lines in front of the row keeps
+ * the row's alignment.
+ */
+MW_API int32_t mw_packet_header_bytes(int32_t top_k, int64_t *header_bytes);   /* HOST only */
+
+/*
+ * mw_pack_packets: mw_pack with that layout.  packets[i] = header(perm[i]) | row(perm[i]) for
+ * i < stats->n_rows, with mask_dev, perm_dev and stats_dev as mw_plan wrote them.
+ * packets_dev has room for n_tokens packets of header_bytes + row_bytes.  Other arguments as
+ * mw_pack.
+ */
+MW_API int32_t mw_pack_packets(mw_ctx *ctx, const void *x_dev, const float *scales_dev,
+                        const int32_t *topk_ids_dev, const uint64_t *mask_dev, const int32_t *perm_dev,
+                        const mw_send_stats *stats_dev, int32_t n_tokens, void *packets_dev, void *stream);
+
+/* What one peer wrote into this rank's receive region, as packets. */
+typedef struct mw_recv_packets {
+    const void *packets;    /* [n_rows][header_bytes + row_bytes], 16-byte aligned */
+    uint32_t n_rows;        /* <= max_tokens */
+    uint32_t reserved0;
+} mw_recv_packets;          /* 16 bytes */
+
+/*
+ * mw_unpack_packets: mw_unpack for regions of packets; same outputs, same order (by source
+ * peer and source token, whatever order the packets lie in), same flags.  A packet is taken
+ * iff its bitmap names this rank; a header whose id count is not top_k sets MW_FLAG_BAD_DESC
+ * and the packet is left out.  mw_unpack_expand is not used with it: this call does both halves.
+ */
+MW_API int32_t mw_unpack_packets(mw_ctx *ctx, const mw_recv_packets *peers_dev, int32_t n_peers,
+                          void *out_rows_dev, float *out_scales_dev, int64_t out_capacity_rows,
+                          int32_t *out_src_peer_dev, int32_t *out_src_token_dev,
+                          int64_t *expert_offsets_dev, mw_recv_stats *recv_stats_dev, void *stream);
+
 /* ---- relay (Section 4.3.3, recursive execution model; Section 4.1, local forwarding table,
  *      replication and forwarding, update of in-packet metadata) ------------------------------ */
 

@@ -23,6 +23,7 @@ MW_FLAG_BAD_EXPERT, MW_FLAG_OUT_CAPACITY, MW_FLAG_NO_LOCAL_EXPERT = 0x01, 0x02, 
 MW_FLAG_BAD_SRC_TOKEN, MW_FLAG_BAD_DESC, MW_FLAG_RECV_CAPACITY, MW_FLAG_DUP_SRC_TOKEN = 0x08, 0x10, 0x20, 0x40
 
 EXPORTS = ["mw_workspace_bytes", "mw_ctx_create", "mw_ctx_destroy", "mw_plan", "mw_pack", "mw_plan_pack",
+           "mw_packet_header_bytes", "mw_pack_packets", "mw_unpack_packets",
            "mw_plan_allgather", "mw_pack_allgather", "mw_unpack", "mw_unpack_index", "mw_unpack_expand",
            "mw_unpack_allgather",
            "mw_sim_deliver", "mw_copy_bytes", "mw_get_send_stats", "mw_get_recv_stats",
@@ -46,6 +47,7 @@ RECV_STATS_DTYPE = np.dtype([("n_recv_rows", "<u8"), ("n_out_rows", "<u8"), ("er
                              ("n_rows_seen", "<u4")])
 RECV_PEER_DTYPE = np.dtype([("desc", "<u8"), ("n_desc", "<u4"), ("n_rows", "<u4"), ("rows", "<u8"),
                             ("row_src_token", "<u8"), ("row_topk", "<u8")])
+RECV_PACKETS_DTYPE = np.dtype([("packets", "<u8"), ("n_rows", "<u4"), ("reserved0", "<u4")])
 RELAY_CHILD_DTYPE = np.dtype([("desc", "<u8"), ("rows", "<u8"), ("row_src_token", "<u8"), ("row_topk", "<u8")])
 RELAY_STATS_DTYPE = np.dtype([("n_groups_in", "<u4"), ("n_rows_in", "<u4"), ("forward_bytes", "<u8"),
                               ("unicast_bytes", "<u8"), ("groups_per_hop", "<u4", (64,)),
@@ -106,6 +108,12 @@ def _stream() -> C.c_void_p:
 
 def mw_copy_bytes(dst: torch.Tensor, src: torch.Tensor, n_bytes: int):
     _check(load().mw_copy_bytes(_ptr(dst), _ptr(src), C.c_int64(n_bytes), _stream()), "mw_copy_bytes")
+
+
+def mw_packet_header_bytes(top_k: int) -> int:
+    a = C.c_int64(0)
+    _check(load().mw_packet_header_bytes(C.c_int32(top_k), C.byref(a)), "mw_packet_header_bytes")
+    return a.value
 
 
 def mw_allgather_split_point(shard_bytes: int, bw_direct: float, bw_relay: float, copies: int) -> int:
@@ -181,6 +189,19 @@ class Context:
         _check(load().mw_plan_pack(self._h, _ptr(topk_ids), _ptr(x), _ptr(scales), C.c_int32(n_tokens), _ptr(mask),
                                    _ptr(perm), _ptr(desc), _ptr(stats), _ptr(packed), _ptr(row_src_token),
                                    _ptr(row_topk), _stream()), "mw_plan_pack")
+
+    def mw_pack_packets(self, x: torch.Tensor, scales: Optional[torch.Tensor], topk_ids: torch.Tensor,
+                        mask: torch.Tensor, perm: torch.Tensor, stats: torch.Tensor, packets: torch.Tensor):
+        n_tokens = topk_ids.shape[0]
+        _check(load().mw_pack_packets(self._h, _ptr(x), _ptr(scales), _ptr(topk_ids), _ptr(mask), _ptr(perm),
+                                      _ptr(stats), C.c_int32(n_tokens), _ptr(packets), _stream()), "mw_pack_packets")
+
+    def mw_unpack_packets(self, peers: torch.Tensor, n_peers: int, out_rows: torch.Tensor,
+                          out_scales: Optional[torch.Tensor], out_capacity_rows: int, out_src_peer: torch.Tensor,
+                          out_src_token: torch.Tensor, expert_offsets: torch.Tensor, recv_stats: torch.Tensor):
+        _check(load().mw_unpack_packets(self._h, _ptr(peers), C.c_int32(n_peers), _ptr(out_rows), _ptr(out_scales),
+                                        C.c_int64(out_capacity_rows), _ptr(out_src_peer), _ptr(out_src_token),
+                                        _ptr(expert_offsets), _ptr(recv_stats), _stream()), "mw_unpack_packets")
 
     def mw_plan_allgather(self, shard_bytes: int, desc: torch.Tensor, stats: torch.Tensor):
         _check(load().mw_plan_allgather(self._h, C.c_int64(shard_bytes), _ptr(desc), _ptr(stats),
@@ -275,6 +296,14 @@ def peers_table(records: Sequence[dict], device) -> torch.Tensor:
     for i, r in enumerate(records):
         host[i] = (r["desc"].data_ptr(), r["n_desc"], r["n_rows"], r["rows"].data_ptr(),
                    r["row_src_token"].data_ptr(), r["row_topk"].data_ptr())
+    return torch.from_numpy(host.view(np.uint8).reshape(-1)).to(device)
+
+
+def packets_table(regions: Sequence[torch.Tensor], n_rows: Sequence[int], device) -> torch.Tensor:
+    """Device array of mw_recv_packets records from device tensors of packets."""
+    host = np.zeros(max(len(regions), 1), dtype=RECV_PACKETS_DTYPE)
+    for i, (r, n) in enumerate(zip(regions, n_rows)):
+        host[i] = (r.data_ptr(), n, 0)
     return torch.from_numpy(host.view(np.uint8).reshape(-1)).to(device)
 
 

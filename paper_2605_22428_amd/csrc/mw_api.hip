@@ -283,7 +283,7 @@ MW_API int32_t mw_unpack_allgather_split(mw_ctx *ctx, const void *const *direct_
                                   (hipStream_t)stream);
 }
 
-static int32_t check_unpack_index(mw_ctx *ctx, const mw_recv_peer *peers_dev, int32_t n_peers,
+static int32_t check_unpack_index(mw_ctx *ctx, const void *peers_dev, int32_t n_peers,
                                   int64_t out_capacity_rows, int64_t *expert_offsets_dev, mw_recv_stats *recv_stats_dev)
 {
     if (!ctx || !peers_dev || !expert_offsets_dev || !recv_stats_dev || out_capacity_rows < 0)
@@ -318,7 +318,46 @@ MW_API int32_t mw_unpack(mw_ctx *ctx, const mw_recv_peer *peers_dev, int32_t n_p
         rc = check_unpack_expand(ctx, n_peers, out_rows_dev, out_scales_dev, out_capacity_rows, out_src_peer_dev,
                                  out_src_token_dev);
     if (rc != MW_OK) return rc;
-    rc = mw_launch_unpack_index(ctx, peers_dev, n_peers, out_capacity_rows, expert_offsets_dev, recv_stats_dev,
+    rc = mw_launch_unpack_index(ctx, peers_dev, false, n_peers, out_capacity_rows, expert_offsets_dev, recv_stats_dev,
+                                (hipStream_t)stream);
+    if (rc != MW_OK) return rc;
+    return mw_launch_unpack_expand(ctx, n_peers, out_rows_dev, out_scales_dev, out_capacity_rows, out_src_peer_dev,
+                                   out_src_token_dev, (hipStream_t)stream);
+}
+
+MW_API int32_t mw_packet_header_bytes(int32_t top_k, int64_t *header_bytes)
+{
+    if (!header_bytes || top_k < 1 || top_k > MW_MAX_TOPK) return MW_ERR_INVALID_ARG;
+    *header_bytes = mw_packet_header_bytes_of(top_k);
+    return MW_OK;
+}
+
+MW_API int32_t mw_pack_packets(mw_ctx *ctx, const void *x_dev, const float *scales_dev, const int32_t *topk_ids_dev,
+                        const uint64_t *mask_dev, const int32_t *perm_dev, const mw_send_stats *stats_dev,
+                        int32_t n_tokens, void *packets_dev, void *stream)
+{
+    if (!ctx || !stats_dev || n_tokens < 0) return MW_ERR_INVALID_ARG;
+    if (n_tokens > ctx->cfg.max_tokens) return MW_ERR_CAPACITY;
+    if (ctx->cfg.n_experts == 0) return MW_ERR_INVALID_ARG;
+    if (n_tokens == 0) return MW_OK;
+    if (!x_dev || !topk_ids_dev || !mask_dev || !perm_dev || !packets_dev) return MW_ERR_INVALID_ARG;
+    if ((ctx->s_row_bytes > 0) != (scales_dev != nullptr)) return MW_ERR_INVALID_ARG;
+    if (((uintptr_t)x_dev | (uintptr_t)packets_dev | (uintptr_t)scales_dev) & 15u) return MW_ERR_INVALID_ARG;
+    return mw_launch_pack_packets(ctx, x_dev, scales_dev, topk_ids_dev, mask_dev, perm_dev, stats_dev, n_tokens,
+                                  packets_dev, (hipStream_t)stream);
+}
+
+MW_API int32_t mw_unpack_packets(mw_ctx *ctx, const mw_recv_packets *peers_dev, int32_t n_peers, void *out_rows_dev,
+                          float *out_scales_dev, int64_t out_capacity_rows, int32_t *out_src_peer_dev,
+                          int32_t *out_src_token_dev, int64_t *expert_offsets_dev, mw_recv_stats *recv_stats_dev,
+                          void *stream)
+{
+    int32_t rc = check_unpack_index(ctx, peers_dev, n_peers, out_capacity_rows, expert_offsets_dev, recv_stats_dev);
+    if (rc == MW_OK)
+        rc = check_unpack_expand(ctx, n_peers, out_rows_dev, out_scales_dev, out_capacity_rows, out_src_peer_dev,
+                                 out_src_token_dev);
+    if (rc != MW_OK) return rc;
+    rc = mw_launch_unpack_index(ctx, peers_dev, true, n_peers, out_capacity_rows, expert_offsets_dev, recv_stats_dev,
                                 (hipStream_t)stream);
     if (rc != MW_OK) return rc;
     return mw_launch_unpack_expand(ctx, n_peers, out_rows_dev, out_scales_dev, out_capacity_rows, out_src_peer_dev,
@@ -330,7 +369,7 @@ MW_API int32_t mw_unpack_index(mw_ctx *ctx, const mw_recv_peer *peers_dev, int32
 {
     const int32_t rc = check_unpack_index(ctx, peers_dev, n_peers, out_capacity_rows, expert_offsets_dev, recv_stats_dev);
     if (rc != MW_OK) return rc;
-    return mw_launch_unpack_index(ctx, peers_dev, n_peers, out_capacity_rows, expert_offsets_dev, recv_stats_dev,
+    return mw_launch_unpack_index(ctx, peers_dev, false, n_peers, out_capacity_rows, expert_offsets_dev, recv_stats_dev,
                                   (hipStream_t)stream);
 }
 

@@ -105,6 +105,10 @@ struct mw_timed {
 
 static inline int64_t mw_align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 
+// Header in front of a packet's row: 4 bitmap words, source token, id count, the ids; whole
+// 128-byte lines so that the row behind it starts on a cache line.
+static inline int64_t mw_packet_header_bytes_of(int32_t top_k) { return mw_align_up(40 + 4 * (int64_t)top_k, 128); }
+
 // ---- device helpers ---------------------------------------------------------------------
 #ifdef __HIPCC__
 // Streaming 16-byte accesses: payload rows are touched once, keep them out of the way of
@@ -180,8 +184,11 @@ int32_t mw_launch_pack(mw_ctx *ctx, const void *x, const float *scales, const in
 int32_t mw_launch_plan_pack(mw_ctx *ctx, const int32_t *topk, int32_t T, const void *x, const float *scales,
                             uint64_t *mask, int32_t *perm, mw_group_desc *desc, mw_send_stats *stats, void *packed,
                             int32_t *row_src_token, int32_t *row_topk, hipStream_t s);
-int32_t mw_launch_unpack_index(mw_ctx *ctx, const mw_recv_peer *peers, int32_t P, int64_t cap,
+int32_t mw_launch_unpack_index(mw_ctx *ctx, const void *peers, bool packets, int32_t P, int64_t cap,
                                int64_t *expert_offsets, mw_recv_stats *stats, hipStream_t s);
+int32_t mw_launch_pack_packets(mw_ctx *ctx, const void *x, const float *scales, const int32_t *topk,
+                               const uint64_t *mask, const int32_t *perm, const mw_send_stats *stats, int32_t T,
+                               void *packets, hipStream_t s);
 int32_t mw_launch_unpack_expand(mw_ctx *ctx, int32_t P, void *out_rows, float *out_scales, int64_t cap,
                                 int32_t *out_src_peer, int32_t *out_src_token, hipStream_t s);
 int32_t mw_launch_plan_allgather(mw_ctx *ctx, int64_t shard_bytes, mw_group_desc *desc,

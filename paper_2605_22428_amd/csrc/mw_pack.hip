@@ -49,6 +49,49 @@ __global__ __launch_bounds__(1024) void k_pack(const u32x4 *__restrict__ x, cons
     }
 }
 
+// The packer for packets (Section 6.4: the bitmap embedded in front of the payload): packet i =
+// header | row of token perm[i], `hc` header chunks then the row's chunks.  Same launch shape
+// as k_pack; the workgroup of the row's first segment also writes the header, one 32-bit word
+// per lane: words 0..7 the bitmap, 8 the token index, 9 the id count, then the ids, then zeros.
+__global__ __launch_bounds__(1024) void k_pack_packets(const u32x4 *__restrict__ x, const u32x4 *__restrict__ scales,
+                                                       int xc, int sc, int hc, const int32_t *__restrict__ topk, int K,
+                                                       const uint64_t *__restrict__ mask,
+                                                       const int32_t *__restrict__ perm,
+                                                       const mw_send_stats *__restrict__ stats,
+                                                       u32x4 *__restrict__ packets)
+{
+    uint32_t gdim = gridDim.y, bdim = blockDim.x;
+    MW_PIN_S(gdim); MW_PIN_S(bdim); MW_PIN_S(xc); MW_PIN_S(sc); MW_PIN_S(hc); MW_PIN_S(K);
+    MW_PIN_PTR(x); MW_PIN_PTR(scales); MW_PIN_PTR(topk); MW_PIN_PTR(mask); MW_PIN_PTR(packets);
+    uint32_t i = blockIdx.y;
+    int32_t t = perm[i];
+    uint32_t n_rows = stats->n_rows;
+    MW_PIN_S(t); MW_PIN_S(n_rows);
+    const int n = xc + sc;
+    const int c = blockIdx.x * bdim + threadIdx.x;
+    while (i < n_rows) {
+        u32x4 *pk = packets + (size_t)i * (hc + n);
+        if (c < n) {
+            const u32x4 v = (c < xc) ? mw_ld16(x + (size_t)t * xc + c) : mw_ld16(scales + (size_t)t * sc + (c - xc));
+            mw_st16(pk + hc + c, v);
+        }
+        if (blockIdx.x == 0) {
+            uint32_t *hw = (uint32_t *)pk;
+            const uint32_t *mw = (const uint32_t *)(mask + (size_t)t * MW_MASK_WORDS);
+            for (int j = threadIdx.x; j < hc * 4; j += bdim) {
+                uint32_t v = 0;
+                if (j < 2 * MW_MASK_WORDS) v = mw[j];
+                else if (j == 8) v = (uint32_t)t;
+                else if (j == 9) v = (uint32_t)K;
+                else if (j < 10 + K) v = (uint32_t)topk[(size_t)t * K + (j - 10)];
+                hw[j] = v;
+            }
+        }
+        i += gdim;
+        if (i < n_rows) t = perm[i];
+    }
+}
+
 // Flat streaming copy, one chunk per lane.
 __global__ __launch_bounds__(256) void k_copy(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
                                               int64_t n_chunks)
@@ -111,6 +154,24 @@ int32_t mw_launch_pack(mw_ctx *ctx, const void *x, const float *scales, const in
         mw_timed tm(ctx, MW_KERNEL_PACK, s);
         hipLaunchKernelGGL(k_pack, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, (const u32x4 *)x, (const u32x4 *)scales, xc, sc,
                            topk, ctx->cfg.top_k, perm, stats, (u32x4 *)packed, row_src_token, row_topk);
+    }
+    MW_HIP_CHECK(hipGetLastError());
+    return MW_OK;
+}
+
+int32_t mw_launch_pack_packets(mw_ctx *ctx, const void *x, const float *scales, const int32_t *topk,
+                               const uint64_t *mask, const int32_t *perm, const mw_send_stats *stats, int32_t T,
+                               void *packets, hipStream_t s)
+{
+    if (T == 0) return MW_OK;
+    const int xc = (int)(ctx->x_row_bytes / 16), sc = (int)(ctx->s_row_bytes / 16);
+    const int hc = (int)(mw_packet_header_bytes_of(ctx->cfg.top_k) / 16);
+    const mw_row_shape shape = mw_row_shape_of(xc + sc);      // the header is whole cache lines
+    const uint32_t gy = (uint32_t)T < kRowGridMax ? (uint32_t)T : kRowGridMax;
+    {
+        mw_timed tm(ctx, MW_KERNEL_PACK, s);
+        hipLaunchKernelGGL(k_pack_packets, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, (const u32x4 *)x,
+                           (const u32x4 *)scales, xc, sc, hc, topk, ctx->cfg.top_k, mask, perm, stats, (u32x4 *)packets);
     }
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;

@@ -82,10 +82,14 @@ __device__ __forceinline__ void mw_finish_counts(const uint32_t *cnt, const uint
     }
 }
 
+// kPackets: the peers' regions hold packets (mw_recv_packets): every row is its own group and
+// carries its bitmap, source token and expert ids in a header in front of it; `row_bytes` is
+// then the distance between packets and `header_bytes` the payload's offset inside one.
+template <bool kPackets>
 __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
-    const mw_recv_peer *__restrict__ peers, int P, const int32_t *__restrict__ eslot,
+    const void *__restrict__ peers_v, int P, const int32_t *__restrict__ eslot,
     int E, int K, int Kd, int my_rank, int L, int Lc,
-    uint32_t max_tokens, uint32_t wpl, uint32_t cap_rows, uint64_t row_bytes, int64_t out_cap,
+    uint32_t max_tokens, uint32_t wpl, uint32_t cap_rows, uint64_t row_bytes, uint32_t header_bytes, int64_t out_cap,
     uint32_t *cnt, uint32_t *row_base, uint32_t *addr_cnt, mw_row_rec *__restrict__ recs,
     mw_hit *__restrict__ hits, uint32_t *__restrict__ base, int64_t *__restrict__ expert_offsets,
     mw_recv_stats *__restrict__ stats, uint32_t *flags)
@@ -98,7 +102,29 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
                                                 // [19] rows of the peers before this one
 
     const int tid = threadIdx.x, nthr = blockDim.x, p = blockIdx.x;
-    const mw_recv_peer pr = peers[p];
+    mw_recv_peer pr;
+    if constexpr (kPackets) {
+        const mw_recv_packets q = ((const mw_recv_packets *)peers_v)[p];
+        const char *first_packet = (const char *)q.packets;
+        pr.desc = nullptr; pr.n_desc = q.n_rows; pr.n_rows = q.n_rows;
+        pr.rows = first_packet + header_bytes;
+        pr.row_src_token = (const int32_t *)(first_packet + 32);
+        pr.row_topk = (const int32_t *)(first_packet + 40);
+    } else {
+        pr = ((const mw_recv_peer *)peers_v)[p];
+    }
+    auto ids_of = [&](uint32_t i) -> const int32_t * {
+        if constexpr (kPackets) return (const int32_t *)((const char *)pr.row_topk + (size_t)i * row_bytes);
+        else return pr.row_topk + (size_t)i * K;
+    };
+    auto token_of = [&](uint32_t i) -> uint32_t {
+        if constexpr (kPackets) return (uint32_t)*(const int32_t *)((const char *)pr.row_src_token + (size_t)i * row_bytes);
+        else return (uint32_t)pr.row_src_token[i];
+    };
+    auto rows_of_peer = [&](int q) -> uint32_t {
+        if constexpr (kPackets) return ((const mw_recv_packets *)peers_v)[q].n_rows;
+        else return ((const mw_recv_peer *)peers_v)[q].n_rows;
+    };
     const uint32_t mine = min(pr.n_rows, max_tokens);
     // All experts' bitmaps fit in LDS at once (the usual case): marking is fused into the row
     // parse and the thread's first row never leaves its registers.
@@ -109,26 +135,32 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
     // the thread's first row (source token, first eight expert ids), its first descriptor and
     // the row counts of the peers before this one.  The kernel is a chain of memory round
     // trips; beside a bandwidth-bound kernel each of them takes several times longer.
-    const int32_t *tk_c = pr.row_topk + (size_t)tid * K;
+    const int32_t *tk_c = ids_of((uint32_t)tid);
     uint32_t s_c = 0;
     int32_t e_c[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) e_c[u] = -1;
     if ((uint32_t)tid < mine) {
-        s_c = (uint32_t)pr.row_src_token[tid];
+        s_c = token_of((uint32_t)tid);
 #pragma unroll
         for (int u = 0; u < 8; ++u) if (u < K) e_c[u] = tk_c[u];
     }
     uint64_t dmask_c = 0;
-    uint32_t doff_c = 0, dcnt_c = 0;
+    uint32_t doff_c = 0, dcnt_c = 0;       // packets: dcnt_c holds the header's id count
     if ((uint32_t)tid < pr.n_desc) {
-        const mw_group_desc *d = pr.desc + tid;
-        dmask_c = d->mask[my_rank >> 6];
-        doff_c = d->row_offset;
-        dcnt_c = d->row_count;
+        if constexpr (kPackets) {
+            const char *hd = (const char *)pr.rows - header_bytes + (size_t)tid * row_bytes;
+            dmask_c = ((const uint64_t *)hd)[my_rank >> 6];
+            dcnt_c = *(const uint32_t *)(hd + 36);
+        } else {
+            const mw_group_desc *d = pr.desc + tid;
+            dmask_c = d->mask[my_rank >> 6];
+            doff_c = d->row_offset;
+            dcnt_c = d->row_count;
+        }
     }
     uint32_t part = 0;
-    for (int q = tid; q < p; q += nthr) part += min(peers[q].n_rows, max_tokens);
+    for (int q = tid; q < p; q += nthr) part += min(rows_of_peer(q), max_tokens);
 
     for (uint32_t w = tid; w < wpl; w += nthr) addr[w] = 0;
     if (one_chunk) for (uint32_t w = tid; w < (uint32_t)L * wpl; w += nthr) bits[w] = 0;
@@ -159,6 +191,27 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
     }
 
     // ---- addressed rows: groups whose bitmap has this rank's bit
+    if constexpr (kPackets) {
+        // one bitmap per row: 32 consecutive rows are 32 consecutive lanes, so a ballot is the
+        // word of the addressed-rows bitmap and its first lane stores it (no atomics)
+        for (uint32_t g0 = 0; g0 < pr.n_desc; g0 += nthr) {
+            const uint32_t g = g0 + tid;
+            bool a = false;
+            if (g < pr.n_desc) {
+                uint64_t dm = dmask_c;
+                uint32_t hk = dcnt_c;
+                if (g != (uint32_t)tid) {
+                    const char *hd = (const char *)pr.rows - header_bytes + (size_t)g * row_bytes;
+                    dm = ((const uint64_t *)hd)[my_rank >> 6];
+                    hk = *(const uint32_t *)(hd + 36);
+                }
+                a = (dm >> (my_rank & 63)) & 1ull;
+                if (a && (hk != (uint32_t)K || g >= n_rows)) { err |= MW_FLAG_BAD_DESC; a = false; }
+            }
+            const uint64_t bal = __ballot(a);
+            if ((tid & 31) == 0 && (g >> 5) < wpl) addr[g >> 5] = (uint32_t)(bal >> (tid & 32));
+        }
+    } else
     for (uint32_t g = tid; g < pr.n_desc; g += nthr) {
         uint64_t dm = dmask_c;
         uint64_t b = doff_c, e = (uint64_t)doff_c + dcnt_c;
@@ -193,7 +246,7 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
     // row it may read back later without a barrier.
     auto parse = [&](uint32_t i, bool first, int (&f)[8]) -> int {
         mw_hit *h = hits + (size_t)(rb + i) * Kd;
-        const int32_t *tk = pr.row_topk + (size_t)i * K;
+        const int32_t *tk = ids_of(i);
         int nk = 0;
         for (int j0 = 0; j0 < K; j0 += 8) {
             int32_t q[8];
@@ -258,7 +311,7 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
         const bool first = i == (uint32_t)tid;
         mw_row_rec rec = {nullptr, 0, p, 0, 0, 0, 0};
         if ((addr[i >> 5] >> (i & 31)) & 1u) {
-            const uint32_t s = first ? s_c : (uint32_t)pr.row_src_token[i];
+            const uint32_t s = first ? s_c : token_of(i);
             if (s >= max_tokens) {
                 err |= MW_FLAG_BAD_SRC_TOKEN;
             } else {
@@ -417,7 +470,7 @@ __global__ __launch_bounds__(1024) void k_expand(
 
 }  // namespace
 
-int32_t mw_launch_unpack_index(mw_ctx *ctx, const mw_recv_peer *peers, int32_t P, int64_t cap,
+int32_t mw_launch_unpack_index(mw_ctx *ctx, const void *peers, bool packets, int32_t P, int64_t cap,
                                int64_t *expert_offsets, mw_recv_stats *stats, hipStream_t s)
 {
     const mw_config &c = ctx->cfg;
@@ -431,11 +484,19 @@ int32_t mw_launch_unpack_index(mw_ctx *ctx, const mw_recv_peer *peers, int32_t P
     const size_t lds_index = ((size_t)wpl + 2 * (size_t)Lc * wpl + 64) * sizeof(uint32_t);
     {
         mw_timed tm(ctx, MW_KERNEL_RECV_INDEX, s);
-        hipLaunchKernelGGL(k_recv_index, dim3(P), dim3(kIndexBlock), lds_index, s, peers, P, ctx->d_eslot,
-                           c.n_experts, c.top_k, Kd, c.my_rank, L, Lc, (uint32_t)c.max_tokens,
-                           wpl, (uint32_t)c.max_recv_rows, (uint64_t)ctx->row_bytes, cap, ctx->d_cnt,
-                           ctx->d_row_base, ctx->d_addr_cnt, ctx->d_recs, ctx->d_hits, ctx->d_base,
-                           expert_offsets, stats, ctx->d_flags);
+        const uint32_t hb = (uint32_t)mw_packet_header_bytes_of(c.top_k);
+        if (packets)
+            hipLaunchKernelGGL(k_recv_index<true>, dim3(P), dim3(kIndexBlock), lds_index, s, peers, P, ctx->d_eslot,
+                               c.n_experts, c.top_k, Kd, c.my_rank, L, Lc, (uint32_t)c.max_tokens,
+                               wpl, (uint32_t)c.max_recv_rows, (uint64_t)(hb + ctx->row_bytes), hb, cap, ctx->d_cnt,
+                               ctx->d_row_base, ctx->d_addr_cnt, ctx->d_recs, ctx->d_hits, ctx->d_base,
+                               expert_offsets, stats, ctx->d_flags);
+        else
+            hipLaunchKernelGGL(k_recv_index<false>, dim3(P), dim3(kIndexBlock), lds_index, s, peers, P, ctx->d_eslot,
+                               c.n_experts, c.top_k, Kd, c.my_rank, L, Lc, (uint32_t)c.max_tokens,
+                               wpl, (uint32_t)c.max_recv_rows, (uint64_t)ctx->row_bytes, 0u, cap, ctx->d_cnt,
+                               ctx->d_row_base, ctx->d_addr_cnt, ctx->d_recs, ctx->d_hits, ctx->d_base,
+                               expert_offsets, stats, ctx->d_flags);
     }
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;

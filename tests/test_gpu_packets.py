@@ -1,0 +1,206 @@
+"""GPU parity of the packet path (bitmap and row metadata in front of every row, Section 6.4):
+mw_pack_packets and mw_unpack_packets, called through the C ABI, against the CPU oracle on the
+same seeded inputs.  Bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2605_22428_amd import binding as B
+from paper_2605_22428_amd import workloads as W
+
+import gpu_harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+class GpuPackets:
+    """mw_plan + mw_pack_packets of one rank's tokens."""
+
+    def __init__(self, ctx, topk, x, scales, x_dev=None, scales_dev=None):
+        self.ctx, self.T = ctx, topk.shape[0]
+        self.topk_d = H.dev(topk.astype(np.int32))
+        self.x_d = x_dev if x_dev is not None else H.dev(x)
+        self.s_d = scales_dev if scales_dev is not None else H.dev(scales)
+        self.buf = B.SendBuffers(ctx, self.T)
+        self.hb = B.mw_packet_header_bytes(ctx.top_k)
+        self.packets = torch.zeros((max(self.T, 1), self.hb + ctx.row_bytes), dtype=torch.uint8, device=H.DEV)
+        ctx.mw_plan(self.topk_d, self.buf.mask, self.buf.perm, self.buf.desc, self.buf.stats)
+        ctx.mw_pack_packets(self.x_d, self.s_d, self.topk_d, self.buf.mask, self.buf.perm, self.buf.stats,
+                            self.packets)
+        self.stats = ctx.mw_get_send_stats(self.buf.stats)
+        self.N = int(self.stats["n_rows"])
+
+    def names(self, rank: int) -> torch.Tensor:
+        """Which of the N packets name `rank` (read from the packets' own headers; test plumbing
+        standing in for the network)."""
+        word = self.packets[: self.N, 8 * (rank >> 6): 8 * (rank >> 6) + 8].contiguous().view(torch.int64)[:, 0]
+        return ((word >> (rank & 63)) & 1).bool()
+
+
+def unpack_packets(ctx, regions, capacity):
+    table = B.packets_table(regions, [r.shape[0] if r.numel() else 0 for r in regions], H.DEV)
+    buf = B.RecvBuffers(ctx, capacity)
+    ctx.mw_unpack_packets(table, len(regions), buf.out_rows, buf.out_scales, capacity, buf.out_src_peer,
+                          buf.out_src_token, buf.expert_offsets, buf.stats)
+    st = ctx.mw_get_recv_stats(buf.stats)
+    q = min(int(st["n_out_rows"]), capacity)
+    out = (H.host(buf.out_rows)[:q], None if buf.out_scales is None else H.host(buf.out_scales)[:q],
+           H.host(buf.out_src_peer)[:q], H.host(buf.out_src_token)[:q], H.host(buf.expert_offsets))
+    return out, st
+
+
+def same(got, want, what):
+    H.assert_same_bytes(got[4], want[4], what + " expert_offsets")
+    H.assert_same_bytes(got[2], want[2], what + " out_src_peer")
+    H.assert_same_bytes(got[3], want[3], what + " out_src_token")
+    H.assert_same_bytes(got[0], want[0], what + " out_rows")
+    if want[1] is not None:
+        H.assert_same_bytes(got[1], want[1], what + " out_scales")
+
+
+def run_packets(w, seed, my_rank, lazy=False, check_senders=None, complete_too=False, edit=None):
+    _say("packets", w.name, "seed", seed, "my_rank", my_rank, "T", w.n_tokens, "H", w.hidden, w.row_format)
+    e2r = W.expert_to_rank(w)
+    ctx = H.make_ctx(w, my_rank)
+    topks = W.topk_ids_many(w, seed, range(w.n_ranks))
+    x_dev = s_dev = None
+    if lazy:
+        xdt = torch.uint8 if w.row_format == "fp8" else torch.int16
+        x_dev = torch.zeros((w.n_tokens, w.hidden), dtype=xdt, device=H.DEV)
+        if w.row_format == "fp8":
+            s_dev = torch.zeros((w.n_tokens, w.hidden // 128), dtype=torch.float32, device=H.DEV)
+    gen = torch.Generator(device="cpu"); gen.manual_seed(seed)
+    toks, kept, complete, shuffled = [], [], [], []
+    for p in range(w.n_ranks):
+        tk = topks[p]
+        if edit is not None:
+            edit(p, tk)
+        if lazy:
+            tokens = W.tokens_for_rank(w, tk, my_rank)
+            rows, sc_rows = W.payload_rows(w, seed, p, tokens)
+            x = np.zeros((w.n_tokens, w.hidden), dtype=rows.dtype)
+            x[tokens] = rows
+            sc = None
+            idx = torch.from_numpy(tokens).to(H.DEV)
+            x_dev.zero_()
+            x_dev[idx] = H.dev(rows).view(x_dev.dtype)
+            if sc_rows is not None:
+                sc = np.zeros((w.n_tokens, w.hidden // 128), dtype=np.float32)
+                sc[tokens] = sc_rows
+                s_dev.zero_()
+                s_dev[idx] = H.dev(sc_rows)
+            g = GpuPackets(ctx, tk, x, sc, x_dev=x_dev, scales_dev=s_dev)
+        else:
+            x, sc = W.payload_rows(w, seed, p)
+            g = GpuPackets(ctx, tk, x, sc)
+        toks.append((tk, x, sc))
+        if check_senders is None or p in check_senders:
+            mask, perm, _, st = ref.plan(tk, e2r, w.n_ranks, w.row_bytes)
+            want = ref.pack_packets(x, sc, tk, mask, perm)
+            assert g.N == len(perm)
+            H.assert_same_bytes(H.host(g.packets)[: g.N], want, "packets of peer %d" % p)
+        mine = g.packets[: g.N][g.names(my_rank)].clone()
+        kept.append(mine)
+        if complete_too:
+            complete.append(g.packets[: g.N].clone())
+            shuffled.append(mine[torch.randperm(mine.shape[0], generator=gen).to(H.DEV)].clone())
+        del g
+    m_rows = sum(int(k.shape[0]) for k in kept)
+    cap = max(1, m_rows * min(w.top_k, w.experts_per_rank))
+    want = ref.dispatch_plain(toks, e2r, my_rank, cap)
+    got, st = unpack_packets(ctx, kept, cap)
+    assert int(st["error_flags"]) == 0, hex(int(st["error_flags"]))
+    same(got, want, "packets vs plain definition")
+    assert int(st["n_recv_rows"]) == m_rows == int(st["n_rows_seen"])
+    if complete_too:
+        got, st = unpack_packets(ctx, complete, cap)
+        assert int(st["error_flags"]) == 0 and int(st["n_recv_rows"]) == m_rows
+        same(got, want, "complete sender buffers")
+        got, st = unpack_packets(ctx, shuffled, cap)
+        assert int(st["error_flags"]) == 0
+        same(got, want, "packets in any order")
+        xrb = 2 * w.hidden if w.row_format == "bf16" else w.hidden
+        o2 = ref.unpack_packets([H.host(k) for k in shuffled], w.top_k, e2r, my_rank, xrb, w.row_bytes - xrb, cap)
+        same(got, o2, "vs the oracle's packet parser")
+    _say("  packets received", m_rows, "output rows", int(st["n_out_rows"]))
+    ctx.close()
+
+
+@pytest.mark.parametrize("seed", [W.BASE_SEED, 1])
+@pytest.mark.parametrize("my_rank", [0, 5])
+def test_c0_tiny(seed, my_rank):
+    run_packets(W.C0, seed, my_rank, complete_too=True)
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_c1_shape_reduced(seed):
+    run_packets(W.scaled(W.C1, n_tokens=333, hidden=1024), seed, 37, complete_too=(seed == 1))
+
+
+def test_c2_shape_reduced_fp8():
+    run_packets(W.scaled(W.C2, n_tokens=333, hidden=1024), 1, 0, complete_too=True)
+
+
+def test_c3_shape_reduced_wide_bitmaps():
+    w = W.scaled(W.C3, n_tokens=200, hidden=512)
+    run_packets(w, 1, W.zipf_hottest_rank(w, 1), check_senders=(0, 100, 255), complete_too=True)
+    run_packets(w, 1, 200, check_senders=(3,))
+
+
+def test_full_width_rows_duplicates_and_padding():
+    def edit(p, tk):
+        tk[p % 3::3, 1] = tk[p % 3::3, 0]
+        tk[1::5, 0] = -1
+        tk[7] = -1
+    run_packets(W.DispatchWorkload("wide_bf16", 11, 8, 16, 2, 257, 7168, "bf16", "uniform"), 1, 3,
+                complete_too=True, edit=edit)
+    run_packets(W.DispatchWorkload("wide_fp8", 12, 8, 16, 2, 129, 7168, "fp8", "uniform"), 1, 6, edit=edit)
+    # more ids than one 128-byte header holds: two header lines
+    run_packets(W.DispatchWorkload("k24", 13, 16, 64, 24, 70, 256, "bf16", "uniform"), 2, 9, complete_too=True)
+
+
+def test_c1_full_size():
+    run_packets(W.C1, W.BASE_SEED, 0, lazy=True, check_senders=(7, 63))
+
+
+def test_empty_regions_and_bad_headers():
+    w = W.DispatchWorkload("small", 31, 8, 16, 2, 128, 256, "bf16", "uniform")
+    e2r = W.expert_to_rank(w)
+    ctx = H.make_ctx(w, 0)
+    hb = B.mw_packet_header_bytes(w.top_k)
+    assert hb == 128 == ref.packet_header_bytes(w.top_k)
+    empty = torch.zeros((0, hb + w.row_bytes), dtype=torch.uint8, device=H.DEV)
+    got, st = unpack_packets(ctx, [empty, empty], 4)
+    assert int(st["n_out_rows"]) == 0 and int(st["error_flags"]) == 0 and got[4].tolist() == [0, 0, 0]
+    tk = W.topk_ids(w, 1, 0)
+    x, _ = W.payload_rows(w, 1, 0)
+    g = GpuPackets(ctx, tk, x, None)
+    mine = g.packets[: g.N][g.names(0)].clone()
+    want = ref.dispatch_plain([(tk, x, None)], e2r, 0, 1000)
+    got, st = unpack_packets(ctx, [mine], 1000)
+    same(got, want, "one peer")
+    # a header that says K = 3: that packet is left out and flagged; the others are delivered
+    bad = mine.clone()
+    victim = 4
+    bad[victim, 36] = 3
+    tok = int(H.host(bad)[victim, 32:36].view(np.int32)[0])
+    tk2 = tk.copy(); tk2[tok] = -1
+    want2 = ref.dispatch_plain([(tk2, x, None)], e2r, 0, 1000)
+    got, st = unpack_packets(ctx, [bad], 1000)
+    assert int(st["error_flags"]) == B.MW_FLAG_BAD_DESC
+    same(got, want2, "bad header left out")
+    with pytest.raises(ref.OracleError):
+        ref.unpack_packets([H.host(bad)], w.top_k, e2r, 0, w.row_bytes, 0, 1000)
+    # the flag does not stick
+    got, st = unpack_packets(ctx, [mine], 1000)
+    assert int(st["error_flags"]) == 0
+    # the descriptor path on the same context still works after the packet path
+    gs = H.GpuSend(ctx, tk, x, None)
+    gu = H.GpuUnpack(ctx, [H.shrink(gs.deliver(0))], 1000)
+    H.check_unpack(gu, want, "descriptor path after packets")
+    ctx.close()
