@@ -120,6 +120,11 @@ def bench_dispatch(args, name: str) -> dict:
                row_topk=torch.zeros((T, K), dtype=torch.int32, device=dev))
     counts = torch.zeros(2, dtype=torch.int32, device=dev)
     recs = []
+    # the same peers' traffic as packets (header in front of every row), for the packet path
+    with_packets = name in ("c1", "c2")
+    hb = B.mw_packet_header_bytes(K)
+    pk_all = torch.zeros((T, hb + rb), dtype=torch.uint8, device=dev) if with_packets else None
+    pk_regions = []
     for p in range(R):
         tokens = W.tokens_for_rank(w, topks[p], my_rank)
         rows, sc = W.payload_rows(w, seed, p, tokens)
@@ -135,10 +140,15 @@ def bench_dispatch(args, name: str) -> dict:
         ctx.mw_sim_deliver(sb.desc, sb.stats, T, sb.packed, sb.row_src_token, sb.row_topk, my_rank,
                            out["desc"], out["rows"], out["row_src_token"], out["row_topk"], counts)
         g, n = (int(v) for v in counts.cpu().numpy())
+        if with_packets:
+            ctx.mw_pack_packets(x_peer, s_peer, tk_d, sb.mask, sb.perm, sb.stats, pk_all)
+            n_p = int(ctx.mw_get_send_stats(sb.stats)["n_rows"])
+            word = pk_all[:n_p, 8 * (my_rank >> 6): 8 * (my_rank >> 6) + 8].contiguous().view(torch.int64)[:, 0]
+            pk_regions.append(pk_all[:n_p][((word >> (my_rank & 63)) & 1).bool()].clone())
         recs.append(dict(desc=out["desc"][:max(g, 1)].clone(), rows=out["rows"][:max(n, 1)].clone(),
                          row_src_token=out["row_src_token"][:max(n, 1)].clone(),
                          row_topk=out["row_topk"][:max(n, 1)].clone(), n_desc=g, n_rows=n))
-    del x_peer, s_peer, out
+    del x_peer, s_peer, out, pk_all
     M = sum(r["n_rows"] for r in recs)
     n_desc_total = sum(r["n_desc"] for r in recs)
     cap = max(1, M * min(K, L))
@@ -302,6 +312,42 @@ def bench_dispatch(args, name: str) -> dict:
                  "copy_pct_of_hbm_peak": round(100.0 * relay_bytes / relay_us["relay_copy"] / 1e3 / HBM_PEAK_GBPS, 2)}
         del children
 
+    # ---------------------------------------------------------------- packet path (extra, untimed region)
+    # The same step with the bitmap and the row metadata in a header in front of every row
+    # (Section 6.4) instead of descriptor tables and side arrays.
+    packets = None
+    if with_packets:
+        assert sum(int(r.shape[0]) for r in pk_regions) == M
+        pk_table = B.packets_table(pk_regions, [int(r.shape[0]) for r in pk_regions], dev)
+        pk_send = torch.zeros((T, hb + rb), dtype=torch.uint8, device=dev)
+        s0 = sets[0]
+        sd, rv = s0["send"], s0["recv"]
+        pk_names = {"pack": B.MW_KERNEL_PACK, "recv_index": B.MW_KERNEL_RECV_INDEX, "expand": B.MW_KERNEL_EXPAND}
+        n_r = 20
+        evp = {k: new_events(torch, n_r) for k in pk_names}
+        for i in range(n_r + 3):
+            if i >= 3:
+                for k, code in pk_names.items():
+                    ctx.mw_ctx_set_timing_events(code, *evp[k][i - 3])
+            ctx.mw_pack_packets(s0["x"], s0["sc"], topk_d, sd.mask, sd.perm, sd.stats, pk_send)
+            ctx.mw_unpack_packets(pk_table, R, rv.out_rows, rv.out_scales, cap, rv.out_src_peer, rv.out_src_token,
+                                  rv.expert_offsets, rv.stats)
+        torch.cuda.synchronize()
+        for code in pk_names.values():
+            ctx.mw_ctx_set_timing_events(code, None, None)
+        rsp = ctx.mw_get_recv_stats(rv.stats)
+        assert int(rsp["error_flags"]) == 0 and int(rsp["n_recv_rows"]) == M and int(rsp["n_out_rows"]) == Q
+        pk_us = {k: 1e3 * sum(a.elapsed_time(b) for a, b in evp[k]) / n_r for k in pk_names}
+        pk_pack_bytes = N * rb + N * (hb + rb) + N * (4 * K + 32 + 4)
+        pk_expand_bytes = M * rb + Q * rb + Q * 8 + M * 4
+        packets = {"header_bytes": hb, "overhead_pct_of_row": round(100.0 * hb / rb, 3),
+                   "us": {k: round(v, 2) for k, v in pk_us.items()},
+                   "pack_GBps": round(pk_pack_bytes / pk_us["pack"] / 1e3, 1),
+                   "expand_GBps": round(pk_expand_bytes / pk_us["expand"] / 1e3, 1),
+                   "expand_pct_of_hbm_peak": round(100.0 * pk_expand_bytes / pk_us["expand"] / 1e3 / HBM_PEAK_GBPS, 2)}
+        del pk_send, pk_table
+    del pk_regions
+
     # ---------------------------------------------------------------- decode-sized send side (extra, untimed region)
     # The first 64 / 128 tokens of this rank's batch (the small batch sizes of the paper's
     # dispatch experiment, Section 6.3): mw_plan + mw_pack against the single launch of
@@ -372,6 +418,8 @@ def bench_dispatch(args, name: str) -> dict:
         result["relay"] = relay
     if decode:
         result["decode_send_side"] = decode
+    if packets is not None:
+        result["packets"] = packets
 
     # ---------------------------------------------------------------- oracle on the host cores
     if not args.no_cpu_baseline and name == "c1":
