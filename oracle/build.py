@@ -19,7 +19,7 @@ def build(force: bool = False) -> str:
         return LIB
     tmp = LIB + ".tmp%d" % os.getpid()
     subprocess.check_call(["gcc", "-std=c99", "-O2", "-Wall", "-Wextra", "-fPIC", "-shared",
-                           SRC, "-o", tmp])
+                           "-ffp-contract=off", SRC, "-o", tmp, "-lm"])
     os.replace(tmp, LIB)
     return LIB
 

@@ -44,6 +44,7 @@
  * a one-hop table returns the parent, delivery through relays equals direct
  * delivery bytewise, and the copy count against a closed form.
  */
+#include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -803,4 +804,83 @@ int ref_unpack_packets(const ref_recv_packets *peers, int32_t P, int32_t K,
 done:
     free(list); free(ids);
     return rc;
+}
+
+/* ------------------------------------------------------------------------ */
+/*
+ * Quantise-in-pack: the packer takes bf16 rows and writes fp8 rows
+ * (H e4m3 codes, then H/128 fp32 scales), so the quantised copy is never
+ * written to memory on its own.  Not in the paper (its payload is opaque
+ * bytes); the arithmetic is the usual block-wise fp8 recipe, and this is the
+ * contract both sides follow, in IEEE single precision with round to nearest
+ * even and no fused or reordered operations:
+ *   per block of 128 consecutive elements of a row
+ *     a   = max |x_j|                       (bf16 widened to fp32, exact)
+ *     a_c = max(a, 2^-20)                   (never zero, never subnormal)
+ *     s   = a_c / 448                       -> the block's stored scale
+ *     inv = 448 / a_c
+ *     y_j = x_j * inv, limited to [-448, 448]
+ *     code_j = the OCP e4m3 ("fn": no infinities, largest finite 448) value
+ *              nearest to y_j; a tie goes to the code with an even mantissa;
+ *              the sign is kept (a negative y_j that rounds to zero is -0).
+ * Inputs must be finite.
+ * The nearest code is found by definition: the 127 non-negative finite codes
+ * are decoded from the format (exponent bias 7, three mantissa bits,
+ * subnormals at exponent field 0) and searched.
+ */
+static double e4m3_value(int code /* 0..126 */)
+{
+    const int e = code >> 3, m = code & 7;
+    return e == 0 ? ldexp((double)m, -9) : ldexp((double)(8 + m), e - 10);
+}
+
+static uint8_t e4m3_nearest(float y /* finite, |y| <= 448 */)
+{
+    uint32_t bits;
+    memcpy(&bits, &y, 4);
+    const uint8_t sign = (uint8_t)((bits >> 24) & 0x80u);
+    const double a = fabs((double)y);
+    int lo = 0;                                  /* largest code whose value is <= a */
+    while (lo < 126 && e4m3_value(lo + 1) <= a) ++lo;
+    if (lo == 126) return (uint8_t)(sign | 126);
+    const double d_lo = a - e4m3_value(lo), d_hi = e4m3_value(lo + 1) - a;   /* exact in double */
+    int code = lo;
+    if (d_hi < d_lo || (d_hi == d_lo && (lo & 1))) code = lo + 1;
+    return (uint8_t)(sign | code);
+}
+
+static float bf16_value(uint16_t b)
+{
+    const uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+int ref_quantize_e4m3_block128(const uint16_t *x /* [n_rows][H] bf16 bit patterns */, int64_t n_rows, int32_t H,
+                               uint8_t *codes /* [n_rows][H] */, float *scales /* [n_rows][H/128] */)
+{
+    if (n_rows < 0 || H < 0 || H % 128 != 0) return REF_ERR_ARG;
+    const int32_t nb = H / 128;
+    for (int64_t r = 0; r < n_rows; ++r)
+        for (int32_t b = 0; b < nb; ++b) {
+            const uint16_t *xb = x + (size_t)r * (size_t)H + (size_t)b * 128;
+            volatile float a = 0.0f;             /* volatile: every step is rounded to single precision */
+            for (int j = 0; j < 128; ++j) {
+                const float v = fabsf(bf16_value(xb[j]));
+                if (!(v <= 3.4028234663852886e38f)) return REF_ERR_INPUT;      /* not finite */
+                if (v > a) a = v;
+            }
+            volatile float a_c = a > 0x1p-20f ? a : 0x1p-20f;
+            volatile float s = a_c / 448.0f;
+            volatile float inv = 448.0f / a_c;
+            scales[(size_t)r * (size_t)nb + b] = s;
+            for (int j = 0; j < 128; ++j) {
+                volatile float y = bf16_value(xb[j]) * inv;
+                if (y > 448.0f) y = 448.0f;
+                if (y < -448.0f) y = -448.0f;
+                codes[(size_t)r * (size_t)H + (size_t)b * 128 + j] = e4m3_nearest(y);
+            }
+        }
+    return REF_OK;
 }

@@ -57,7 +57,8 @@ def lib():
                      "ref_pack_allgather", "ref_unpack_allgather",
                      "ref_relay_child", "ref_relay_accounting", "ref_allgather_split_point",
                      "ref_plan_allgather_split", "ref_unpack_allgather_split",
-                     "ref_pack_packets", "ref_deliver_packets", "ref_unpack_packets"):
+                     "ref_pack_packets", "ref_deliver_packets", "ref_unpack_packets",
+                     "ref_quantize_e4m3_block128"):
             getattr(_lib, name).restype = C.c_int
         _lib.ref_packet_header_bytes.restype = C.c_int64
     return _lib
@@ -363,3 +364,16 @@ def unpack_packets(peers: Sequence[np.ndarray], top_k: int, e2r, my_rank: int, x
                                     C.byref(m)), "ref_unpack_packets")
     Q = int(offs[L])
     return out[:Q], (osc[:Q] if osc is not None else None), sp[:Q], stok[:Q], offs, int(m.value)
+
+
+# ---------------------------------------------------------------------------
+# quantise-in-pack: bf16 rows -> e4m3 codes + one fp32 scale per 128 elements
+def quantize_rows(x_bf16: np.ndarray):
+    """x_bf16: uint16 [n][H] bit patterns -> (codes uint8 [n][H], scales float32 [n][H/128])."""
+    x = np.ascontiguousarray(x_bf16, dtype=np.uint16)
+    n, H = x.shape
+    codes = np.zeros((n, H), dtype=np.uint8)
+    scales = np.zeros((n, H // 128), dtype=np.float32)
+    _check(lib().ref_quantize_e4m3_block128(_p(x), C.c_int64(n), C.c_int32(H), _p(codes), _p(scales)),
+           "ref_quantize_e4m3_block128")
+    return codes, scales
