@@ -348,6 +348,29 @@ def bench_dispatch(args, name: str) -> dict:
         del pk_send, pk_table
     del pk_regions
 
+    # ---------------------------------------------------------------- quantise-in-pack (extra, untimed region)
+    # fp8 workload only: the packer fed with this rank's bf16 rows, quantising on the way.
+    quant = None
+    if fp8:
+        import dataclasses
+        xb, _ = W.payload_rows(dataclasses.replace(w, row_format="bf16"), seed, my_rank)
+        xb_d = up(xb)
+        sd = sets[0]["send"]
+        n_r = 20
+        evq = new_events(torch, n_r)
+        for i in range(n_r + 3):
+            if i >= 3:
+                ctx.mw_ctx_set_timing_events(B.MW_KERNEL_PACK_QUANT, *evq[i - 3])
+            ctx.mw_pack_quantize(xb_d, topk_d, sd.perm, sd.stats, sd.packed, sd.row_src_token, sd.row_topk)
+        torch.cuda.synchronize()
+        ctx.mw_ctx_set_timing_events(B.MW_KERNEL_PACK_QUANT, None, None)
+        q_us = 1e3 * sum(a.elapsed_time(b) for a, b in evq) / n_r
+        q_bytes = N * 2 * w.hidden + N * rb + N * (4 + 4 * K) + N * 4 + N * 4 * K
+        quant = {"us": round(q_us, 2), "bytes": q_bytes, "GBps": round(q_bytes / q_us / 1e3, 1),
+                 "pct_of_hbm_peak": round(100.0 * q_bytes / q_us / 1e3 / HBM_PEAK_GBPS, 2),
+                 "bytes_of_quantise_then_pack": q_bytes + 2 * N * rb}
+        del xb_d
+
     # ---------------------------------------------------------------- decode-sized send side (extra, untimed region)
     # The first 64 / 128 tokens of this rank's batch (the small batch sizes of the paper's
     # dispatch experiment, Section 6.3): mw_plan + mw_pack against the single launch of
@@ -420,6 +443,8 @@ def bench_dispatch(args, name: str) -> dict:
         result["decode_send_side"] = decode
     if packets is not None:
         result["packets"] = packets
+    if quant is not None:
+        result["quantize_in_pack"] = quant
 
     # ---------------------------------------------------------------- oracle on the host cores
     if not args.no_cpu_baseline and name == "c1":

@@ -193,6 +193,24 @@ MW_API int32_t mw_pack(mw_ctx *ctx, const void *x_dev, const float *scales_dev,
                 void *stream);
 
 /*
+ * mw_pack_quantize: mw_pack for a context of MW_ROW_FP8_E4M3_BLOCK128 rows whose input is
+ * still bf16: x_bf16_dev [n_tokens][H] bf16, packed rows = H e4m3 codes then H/128 fp32 scales,
+ * quantised on the way (the paper's payload is opaque bytes, Section 4.3.1; this only changes
+ * what the send module loads into the send buffer, Section 5.2 step 1).  Contract, in IEEE
+ * single precision with round to nearest even, one rounding per operation, per block of 128
+ * consecutive elements of a row:
+ *   a = max |x_j|;  a_c = max(a, 2^-20);  scale = a_c / 448 (stored);
+ *   code_j = the OCP e4m3 value (no infinities, largest finite 448) nearest to
+ *            x_j * (448 / a_c) limited to [-448, 448]; ties to the even mantissa; sign kept.
+ * Inputs must be finite: a block holding an infinity or a NaN gets unspecified codes and
+ * scale (nothing faults, no flag).  Other arguments, metadata outputs and errors as mw_pack;
+ * MW_ERR_UNSUPPORTED for a context of another row format.
+ */
+MW_API int32_t mw_pack_quantize(mw_ctx *ctx, const void *x_bf16_dev, const int32_t *topk_ids_dev,
+                         const int32_t *perm_dev, const mw_send_stats *stats_dev, int32_t n_tokens,
+                         void *packed_rows_dev, int32_t *row_src_token_dev, int32_t *row_topk_dev, void *stream);
+
+/*
  * mw_plan_pack: mw_plan followed by mw_pack for a decode-sized batch, as one kernel launch.
  * Section 6.3 (AlltoAll dispatch over batch sizes): at 64 and 128 tokens per rank the fixed
  * cost of a MultiWrite, not the bytes, decides; here that cost is launches and their
@@ -437,7 +455,8 @@ MW_API int32_t mw_get_relay_stats(mw_ctx *ctx, const mw_relay_stats *stats_dev, 
 #define MW_KERNEL_RELAY_INDEX  7
 #define MW_KERNEL_RELAY_COPY   8
 #define MW_KERNEL_PLAN_PACK    9   /* mw_plan_pack's single kernel */
-#define MW_KERNEL_COUNT        10
+#define MW_KERNEL_PACK_QUANT   10  /* mw_pack_quantize's kernel */
+#define MW_KERNEL_COUNT        11
 MW_API int32_t mw_ctx_set_timing_events(mw_ctx *ctx, int32_t kernel, void *ev_start, void *ev_stop);
 
 MW_API const char *mw_status_string(int32_t status);

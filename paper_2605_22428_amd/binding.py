@@ -22,7 +22,7 @@ MW_ROW_BF16, MW_ROW_FP8_E4M3_BLOCK128, MW_ROW_BYTES = 0, 1, 2
 MW_FLAG_BAD_EXPERT, MW_FLAG_OUT_CAPACITY, MW_FLAG_NO_LOCAL_EXPERT = 0x01, 0x02, 0x04
 MW_FLAG_BAD_SRC_TOKEN, MW_FLAG_BAD_DESC, MW_FLAG_RECV_CAPACITY, MW_FLAG_DUP_SRC_TOKEN = 0x08, 0x10, 0x20, 0x40
 
-EXPORTS = ["mw_workspace_bytes", "mw_ctx_create", "mw_ctx_destroy", "mw_plan", "mw_pack", "mw_plan_pack",
+EXPORTS = ["mw_workspace_bytes", "mw_ctx_create", "mw_ctx_destroy", "mw_plan", "mw_pack", "mw_plan_pack", "mw_pack_quantize",
            "mw_packet_header_bytes", "mw_pack_packets", "mw_unpack_packets",
            "mw_plan_allgather", "mw_pack_allgather", "mw_unpack", "mw_unpack_index", "mw_unpack_expand",
            "mw_unpack_allgather",
@@ -32,7 +32,7 @@ EXPORTS = ["mw_workspace_bytes", "mw_ctx_create", "mw_ctx_destroy", "mw_plan", "
            "mw_ctx_set_timing_events", "mw_status_string"]
 MW_KERNEL_PLAN_RANK, MW_KERNEL_PLAN_GROUPS, MW_KERNEL_PACK, MW_KERNEL_RECV_INDEX, MW_KERNEL_EXPAND = 0, 1, 2, 3, 4
 MW_KERNEL_AG_PACK, MW_KERNEL_AG_GATHER, MW_KERNEL_RELAY_INDEX, MW_KERNEL_RELAY_COPY = 5, 6, 7, 8
-MW_KERNEL_PLAN_PACK = 9
+MW_KERNEL_PLAN_PACK, MW_KERNEL_PACK_QUANT = 9, 10
 MW_MAX_HOPS = 64
 MW_FUSED_MAX_TOKENS = 256
 MW_FLAG_BAD_RANK = 0x80
@@ -181,6 +181,14 @@ class Context:
         _check(load().mw_pack(self._h, _ptr(x), _ptr(scales), _ptr(topk_ids), _ptr(perm), _ptr(stats),
                               C.c_int32(n_tokens), _ptr(packed), _ptr(row_src_token), _ptr(row_topk),
                               _stream()), "mw_pack")
+
+    def mw_pack_quantize(self, x_bf16: torch.Tensor, topk_ids: torch.Tensor, perm: torch.Tensor,
+                         stats: torch.Tensor, packed: torch.Tensor, row_src_token: torch.Tensor,
+                         row_topk: torch.Tensor):
+        n_tokens = topk_ids.shape[0]
+        _check(load().mw_pack_quantize(self._h, _ptr(x_bf16), _ptr(topk_ids), _ptr(perm), _ptr(stats),
+                                       C.c_int32(n_tokens), _ptr(packed), _ptr(row_src_token), _ptr(row_topk),
+                                       _stream()), "mw_pack_quantize")
 
     def mw_plan_pack(self, topk_ids: torch.Tensor, x: torch.Tensor, scales: Optional[torch.Tensor],
                      mask: torch.Tensor, perm: torch.Tensor, desc: torch.Tensor, stats: torch.Tensor,

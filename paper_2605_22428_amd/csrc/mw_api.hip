@@ -211,6 +211,21 @@ MW_API int32_t mw_pack(mw_ctx *ctx, const void *x_dev, const float *scales_dev, 
                           row_src_token_dev, row_topk_dev, (hipStream_t)stream);
 }
 
+MW_API int32_t mw_pack_quantize(mw_ctx *ctx, const void *x_bf16_dev, const int32_t *topk_ids_dev,
+                         const int32_t *perm_dev, const mw_send_stats *stats_dev, int32_t n_tokens,
+                         void *packed_rows_dev, int32_t *row_src_token_dev, int32_t *row_topk_dev, void *stream)
+{
+    if (!ctx || !stats_dev || n_tokens < 0) return MW_ERR_INVALID_ARG;
+    if (ctx->cfg.row_format != MW_ROW_FP8_E4M3_BLOCK128) return MW_ERR_UNSUPPORTED;
+    if (n_tokens > ctx->cfg.max_tokens) return MW_ERR_CAPACITY;
+    if (n_tokens == 0) return MW_OK;
+    if (!x_bf16_dev || !topk_ids_dev || !perm_dev || !packed_rows_dev || !row_src_token_dev || !row_topk_dev)
+        return MW_ERR_INVALID_ARG;
+    if (((uintptr_t)x_bf16_dev | (uintptr_t)packed_rows_dev) & 15u) return MW_ERR_INVALID_ARG;
+    return mw_launch_pack_quantize(ctx, x_bf16_dev, topk_ids_dev, perm_dev, stats_dev, n_tokens, packed_rows_dev,
+                                   row_src_token_dev, row_topk_dev, (hipStream_t)stream);
+}
+
 MW_API int32_t mw_plan_pack(mw_ctx *ctx, const int32_t *topk_ids_dev, const void *x_dev, const float *scales_dev,
                      int32_t n_tokens, uint64_t *mask_dev, int32_t *perm_dev, mw_group_desc *desc_dev,
                      mw_send_stats *stats_dev, void *packed_rows_dev, int32_t *row_src_token_dev,

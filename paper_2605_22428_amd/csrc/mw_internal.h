@@ -186,6 +186,9 @@ int32_t mw_launch_plan_pack(mw_ctx *ctx, const int32_t *topk, int32_t T, const v
                             int32_t *row_src_token, int32_t *row_topk, hipStream_t s);
 int32_t mw_launch_unpack_index(mw_ctx *ctx, const void *peers, bool packets, int32_t P, int64_t cap,
                                int64_t *expert_offsets, mw_recv_stats *stats, hipStream_t s);
+int32_t mw_launch_pack_quantize(mw_ctx *ctx, const void *x_bf16, const int32_t *topk, const int32_t *perm,
+                                const mw_send_stats *stats, int32_t T, void *packed, int32_t *row_src_token,
+                                int32_t *row_topk, hipStream_t s);
 int32_t mw_launch_pack_packets(mw_ctx *ctx, const void *x, const float *scales, const int32_t *topk,
                                const uint64_t *mask, const int32_t *perm, const mw_send_stats *stats, int32_t T,
                                void *packets, hipStream_t s);

@@ -92,6 +92,75 @@ __global__ __launch_bounds__(1024) void k_pack_packets(const u32x4 *__restrict__
     }
 }
 
+// Quantise-in-pack: the packer for fp8 rows fed with bf16 rows, so the quantised copy of the
+// batch is never written and read back on its own (a separate quantiser would add
+// 2 * N * (H + H / 32) bytes of traffic to the 2 H + H + H / 32 per row moved here).
+// Contract, in IEEE single precision, one rounding per operation:
+//   per 128 consecutive elements: a = max |x|, a_c = max(a, 2^-20), scale = a_c / 448 (stored),
+//   code = e4m3 (OCP "fn", largest finite 448) nearest to x * (448 / a_c) limited to +-448,
+//   ties to the even mantissa, sign kept.  Inputs must be finite.
+// One workgroup per packed row, one 16-byte chunk (8 elements) per lane: a block of 128 elements
+// is 16 neighbouring lanes, whose maxima meet by four exchanges inside the wave.  The
+// conversion is the hardware's (round to nearest even); the limit to +-448 in front of it means
+// it never sees a value it would have to saturate.
+__device__ __forceinline__ float mw_bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float mw_bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+template <int U>
+__global__ __launch_bounds__(1024) void k_pack_quant(const u32x4 *__restrict__ x, int ic, int H,
+                                                     const int32_t *__restrict__ topk, int K,
+                                                     const int32_t *__restrict__ perm,
+                                                     const mw_send_stats *__restrict__ stats,
+                                                     unsigned char *__restrict__ packed, uint64_t row_bytes,
+                                                     int32_t *__restrict__ row_src_token, int32_t *__restrict__ row_topk)
+{
+    const uint32_t gdim = gridDim.x, bdim = blockDim.x;
+    uint32_t i = blockIdx.x;
+    int32_t t = perm[i];
+    const uint32_t n_rows = stats->n_rows;
+    while (i < n_rows) {
+        unsigned char *row = packed + (size_t)i * row_bytes;
+        // ic is a multiple of 64: whole waves.  A lane's U chunks are requested together.
+        for (int c0 = threadIdx.x; c0 < ic; c0 += U * bdim) {
+            u32x4 vv[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int c = c0 + u * bdim;
+                if (c < ic) vv[u] = mw_ld16(x + (size_t)t * ic + c);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int c = c0 + u * bdim;
+                if (c >= ic) break;
+                const u32x4 v = vv[u];
+                float f[8] = {mw_bf16_lo(v.x), mw_bf16_hi(v.x), mw_bf16_lo(v.y), mw_bf16_hi(v.y),
+                              mw_bf16_lo(v.z), mw_bf16_hi(v.z), mw_bf16_lo(v.w), mw_bf16_hi(v.w)};
+                float a = 0.0f;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) a = fmaxf(a, fabsf(f[j]));
+#pragma unroll
+                for (int d = 1; d < 16; d <<= 1) a = fmaxf(a, __shfl_xor(a, d, 64));
+                const float a_c = fmaxf(a, 0x1p-20f);
+                const float scale = a_c / 448.0f, inv = 448.0f / a_c;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) f[j] = fminf(fmaxf(f[j] * inv, -448.0f), 448.0f);
+                uint32_t lo = 0, hi = 0;
+                lo = __builtin_amdgcn_cvt_pk_fp8_f32(f[0], f[1], lo, false);
+                lo = __builtin_amdgcn_cvt_pk_fp8_f32(f[2], f[3], lo, true);
+                hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[4], f[5], hi, false);
+                hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[6], f[7], hi, true);
+                __builtin_nontemporal_store(((unsigned long long)hi << 32) | lo,
+                                            (unsigned long long *)(row + 8 * (size_t)c));
+                if ((c & 15) == 0) *(float *)(row + H + 4 * (c >> 4)) = scale;
+            }
+        }
+        if (threadIdx.x == 0) row_src_token[i] = t;
+        for (int j = threadIdx.x; j < K; j += bdim) row_topk[(size_t)i * K + j] = topk[(size_t)t * K + j];
+        i += gdim;
+        if (i < n_rows) t = perm[i];
+    }
+}
+
 // Flat streaming copy, one chunk per lane.
 __global__ __launch_bounds__(256) void k_copy(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
                                               int64_t n_chunks)
@@ -172,6 +241,29 @@ int32_t mw_launch_pack_packets(mw_ctx *ctx, const void *x, const float *scales, 
         mw_timed tm(ctx, MW_KERNEL_PACK, s);
         hipLaunchKernelGGL(k_pack_packets, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, (const u32x4 *)x,
                            (const u32x4 *)scales, xc, sc, hc, topk, ctx->cfg.top_k, mask, perm, stats, (u32x4 *)packets);
+    }
+    MW_HIP_CHECK(hipGetLastError());
+    return MW_OK;
+}
+
+int32_t mw_launch_pack_quantize(mw_ctx *ctx, const void *x_bf16, const int32_t *topk, const int32_t *perm,
+                                const mw_send_stats *stats, int32_t T, void *packed, int32_t *row_src_token,
+                                int32_t *row_topk, hipStream_t s)
+{
+    if (T == 0) return MW_OK;
+    const int H = ctx->cfg.hidden, ic = H / 8;                  // H % 512 == 0 for fp8 rows
+    // Two chunks per lane, both requested before either is processed: unlike the plain row
+    // movers this kernel has a long chain behind every load (exchanges, two divisions, the
+    // conversions), and a second load in flight hides it (23 -> 17 us at 4096 x 7168; four are
+    // no better).
+    constexpr int U = 2;
+    int bs = (ic / U + 63) / 64 * 64;
+    if (bs > 1024) bs = 1024;
+    const uint32_t gx = (uint32_t)T < kRowGridMax ? (uint32_t)T : kRowGridMax;
+    {
+        mw_timed tm(ctx, MW_KERNEL_PACK_QUANT, s);
+        hipLaunchKernelGGL(k_pack_quant<U>, dim3(gx), dim3(bs), 0, s, (const u32x4 *)x_bf16, ic, H, topk, ctx->cfg.top_k,
+                           perm, stats, (unsigned char *)packed, (uint64_t)ctx->row_bytes, row_src_token, row_topk);
     }
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;
