@@ -884,3 +884,94 @@ int ref_quantize_e4m3_block128(const uint16_t *x /* [n_rows][H] bf16 bit pattern
         }
     return REF_OK;
 }
+
+/* ------------------------------------------------------------------------ */
+/*
+ * The way back (Section 2.1, combine-style AlltoAll; Section 2.3.2 notes that
+ * the combine phase reduces and cannot use multicast).  What this rank can do
+ * locally is the mirror image of MultiWrite's "one copy per destination
+ * set": a token that reached h of this rank's experts gets ONE row back, the
+ * sum of those h expert outputs, instead of h rows.
+ *
+ * Reading (the paper does not define the step):
+ *   y [Q][H] bf16 is laid out exactly like the dispatch output (expert-major,
+ *   then source peer, then source token).  For source peer p and token t with
+ *   at least one local expert in its id list,
+ *     ret(p, t) = bf16( ((y[q_1] + y[q_2]) + ...) + y[q_h] )
+ *   summed in single precision in the order the distinct local experts appear
+ *   in the token's id list (first occurrences), one rounding to bf16 (nearest,
+ *   ties to even) at the end; h = 1 is a plain copy of the 16-bit patterns.
+ *   A NaN sum becomes the quiet NaN 0x7FC0 with the sum's sign bit.
+ * Row (p, t) is written to return row i of peer p's return region, where i is
+ * the row's position in what the peer sent (row_src_token[i] == t): the peer
+ * gets its rows back in the order it packed them.  Rows that were not
+ * addressed to this rank are left untouched.
+ */
+static uint16_t bf16_round(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)(((u >> 16) & 0x8000u) | 0x7fc0u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+int ref_combine_gather(const ref_recv_peer *peers, int32_t P, int32_t K,
+                       const int32_t *expert_to_rank, int32_t E, int32_t my_rank, int32_t H,
+                       const uint16_t *y /* [Q][H] */, const int32_t *out_src_peer, const int32_t *out_src_token,
+                       const int64_t *expert_offsets /* [L+1] */,
+                       uint16_t *const *ret /* [P] -> [n_rows of that peer][H] */)
+{
+    if (my_rank < 0 || my_rank >= REF_MAX_RANKS || P < 0 || H < 0) return REF_ERR_ARG;
+    int bad = 0;
+    float *acc = (float *)malloc((size_t)(H > 0 ? H : 1) * sizeof(float));
+    if (!acc) return REF_ERR_CAPACITY;
+    int rc = REF_OK;
+    for (int32_t p = 0; p < P && rc == REF_OK; ++p) {
+        const ref_recv_peer *pr = &peers[p];
+        uint8_t *addr = (uint8_t *)calloc((size_t)pr->n_rows + 1, 1);
+        for (uint32_t g = 0; g < pr->n_desc; ++g) {
+            const ref_group_desc *d = &pr->desc[g];
+            if ((uint64_t)d->row_offset + d->row_count > pr->n_rows) { rc = REF_ERR_INPUT; break; }
+            if (!mask_bit(d->mask, my_rank)) continue;
+            for (uint32_t i = 0; i < d->row_count; ++i) addr[d->row_offset + i] = 1;
+        }
+        for (uint32_t i = 0; i < pr->n_rows && rc == REF_OK; ++i) {
+            if (!addr[i]) continue;
+            const int32_t *ids = pr->row_topk + (size_t)i * K;
+            const int32_t t = pr->row_src_token[i];
+            int h = 0;
+            const uint16_t *only = NULL;
+            for (int32_t j = 0; j < K; ++j) {
+                const int32_t e = ids[j];
+                if (e == -1) continue;
+                if (e < 0 || e >= E) { bad = 1; continue; }
+                if (expert_to_rank[e] != my_rank) continue;
+                int seen = 0;
+                for (int32_t j2 = 0; j2 < j; ++j2) seen |= (ids[j2] == e);
+                if (seen) continue;
+                const int32_t le = local_slot_of(expert_to_rank, e, my_rank);
+                int64_t q = -1;
+                for (int64_t c = expert_offsets[le]; c < expert_offsets[le + 1]; ++c)
+                    if (out_src_peer[c] == p && out_src_token[c] == t) { q = c; break; }
+                if (q < 0) { rc = REF_ERR_INPUT; break; }
+                const uint16_t *row = y + (size_t)q * (size_t)H;
+                for (int32_t c = 0; c < H; ++c) {
+                    volatile float sum = (h == 0) ? bf16_value(row[c]) : acc[c] + bf16_value(row[c]);
+                    acc[c] = sum;
+                }
+                only = row;
+                ++h;
+            }
+            if (rc != REF_OK) break;
+            if (h == 0) { rc = REF_ERR_INPUT; break; }
+            uint16_t *dst = ret[p] + (size_t)i * (size_t)H;
+            if (h == 1) memcpy(dst, only, (size_t)H * 2);
+            else for (int32_t c = 0; c < H; ++c) dst[c] = bf16_round(acc[c]);
+        }
+        free(addr);
+    }
+    free(acc);
+    if (rc == REF_OK && bad) rc = REF_ERR_EXPERT;
+    return rc;
+}

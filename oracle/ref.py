@@ -58,7 +58,7 @@ def lib():
                      "ref_relay_child", "ref_relay_accounting", "ref_allgather_split_point",
                      "ref_plan_allgather_split", "ref_unpack_allgather_split",
                      "ref_pack_packets", "ref_deliver_packets", "ref_unpack_packets",
-                     "ref_quantize_e4m3_block128"):
+                     "ref_quantize_e4m3_block128", "ref_combine_gather"):
             getattr(_lib, name).restype = C.c_int
         _lib.ref_packet_header_bytes.restype = C.c_int64
     return _lib
@@ -377,3 +377,30 @@ def quantize_rows(x_bf16: np.ndarray):
     _check(lib().ref_quantize_e4m3_block128(_p(x), C.c_int64(n), C.c_int32(H), _p(codes), _p(scales)),
            "ref_quantize_e4m3_block128")
     return codes, scales
+
+
+# ---------------------------------------------------------------------------
+# the way back: one row per received row, the sum of its local experts' outputs
+def combine_gather(peers: Sequence[PeerBuf], top_k: int, e2r, my_rank: int, y_bf16: np.ndarray,
+                   out_src_peer, out_src_token, expert_offsets) -> List[np.ndarray]:
+    """peers as for unpack(); y_bf16 uint16 [Q][H] laid out like unpack()'s out_rows.
+    -> per peer uint16 [n_rows_p][H]; rows not addressed to my_rank stay zero."""
+    e2r = _i32(e2r)
+    y = np.ascontiguousarray(y_bf16, dtype=np.uint16)
+    H = y.shape[1]
+    sp, stok = _i32(out_src_peer), _i32(out_src_token)
+    offs = np.ascontiguousarray(expert_offsets, dtype=np.int64)
+    keep: List[np.ndarray] = []
+    arr = (_RecvPeer * max(len(peers), 1))()
+    outs = []
+    for i, (d, r, s, t) in enumerate(peers):
+        d = np.ascontiguousarray(d, dtype=DESC)
+        s, t = _i32(s), _i32(t)
+        keep += [d, s, t]
+        arr[i] = _RecvPeer(d.ctypes.data, len(d), len(s), 0, s.ctypes.data, t.ctypes.data)
+        outs.append(np.zeros((len(s), H), dtype=np.uint16))
+    ptrs = (C.c_void_p * max(len(peers), 1))(*[o.ctypes.data for o in outs])
+    _check(lib().ref_combine_gather(arr, C.c_int32(len(peers)), C.c_int32(top_k), _p(e2r), C.c_int32(len(e2r)),
+                                    C.c_int32(my_rank), C.c_int32(H), _p(y), _p(sp), _p(stok), _p(offs), ptrs),
+           "ref_combine_gather")
+    return outs
