@@ -274,6 +274,29 @@ MW_API int32_t mw_unpack_expand(mw_ctx *ctx, int32_t n_peers, void *out_rows_dev
                          int64_t out_capacity_rows, int32_t *out_src_peer_dev, int32_t *out_src_token_dev, void *stream);
 
 /*
+ * mw_combine_gather: the way back (Section 2.1, combine-style AlltoAll).  The paper notes that
+ * the combine phase reduces and cannot use multicast (Section 2.3.2); what a rank can do
+ * locally is the mirror image of "one copy per destination set": a token that reached h of
+ * this rank's experts gets ONE row back, the sum of those h expert outputs.
+ *   y_dev [out_capacity_rows][H] bf16: the experts' outputs, laid out exactly like the
+ *   out_rows of the last mw_unpack / mw_unpack_index / mw_unpack_packets on this context
+ *   (same n_peers, same out_capacity_rows); the peers' receive regions are not read again.
+ *   ret_rows_dev [ret_capacity_rows][H] bf16: return row b_p + i belongs to row i of peer p's
+ *   region, b_p = sum of the n_rows of the peers before p; peer p's return region is
+ *   rows [b_p, b_p + n_rows_p): the peer gets its rows back in the order it packed them.
+ *     ret = bf16(((y[q_1] + y[q_2]) + ...) + y[q_h]), single precision, summed in the order the
+ *     distinct local experts appear in the row's id list, one rounding to bf16 (nearest, ties
+ *     to even) at the end; a NaN sum gives 0x7FC0 with the sum's sign; h = 1 copies the row
+ *     unchanged.  Outputs of rows dropped for capacity contribute nothing.
+ *   Rows of a region that were not addressed to this rank, and rows at or beyond
+ *   ret_capacity_rows, are not written.
+ * bf16 contexts only (MW_ERR_UNSUPPORTED otherwise).  Races with a later unpack on the same
+ * context, whose index it reads.
+ */
+MW_API int32_t mw_combine_gather(mw_ctx *ctx, int32_t n_peers, const void *y_dev, int64_t out_capacity_rows,
+                          void *ret_rows_dev, int64_t ret_capacity_rows, void *stream);
+
+/*
  * AllGather result (Section 5.2): out = shard of rank 0, rank 1, ... rank R-1
  * side by side.  peer_shards_dev: device array of n_ranks device pointers.
  */
@@ -456,7 +479,8 @@ MW_API int32_t mw_get_relay_stats(mw_ctx *ctx, const mw_relay_stats *stats_dev, 
 #define MW_KERNEL_RELAY_COPY   8
 #define MW_KERNEL_PLAN_PACK    9   /* mw_plan_pack's single kernel */
 #define MW_KERNEL_PACK_QUANT   10  /* mw_pack_quantize's kernel */
-#define MW_KERNEL_COUNT        11
+#define MW_KERNEL_COMBINE      11  /* mw_combine_gather's kernel */
+#define MW_KERNEL_COUNT        12
 MW_API int32_t mw_ctx_set_timing_events(mw_ctx *ctx, int32_t kernel, void *ev_start, void *ev_stop);
 
 MW_API const char *mw_status_string(int32_t status);

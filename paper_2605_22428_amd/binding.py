@@ -25,14 +25,14 @@ MW_FLAG_BAD_SRC_TOKEN, MW_FLAG_BAD_DESC, MW_FLAG_RECV_CAPACITY, MW_FLAG_DUP_SRC_
 EXPORTS = ["mw_workspace_bytes", "mw_ctx_create", "mw_ctx_destroy", "mw_plan", "mw_pack", "mw_plan_pack", "mw_pack_quantize",
            "mw_packet_header_bytes", "mw_pack_packets", "mw_unpack_packets",
            "mw_plan_allgather", "mw_pack_allgather", "mw_unpack", "mw_unpack_index", "mw_unpack_expand",
-           "mw_unpack_allgather",
+           "mw_unpack_allgather", "mw_combine_gather",
            "mw_sim_deliver", "mw_copy_bytes", "mw_get_send_stats", "mw_get_recv_stats",
            "mw_set_forwarding", "mw_relay", "mw_get_relay_stats",
            "mw_allgather_split_point", "mw_plan_allgather_split", "mw_unpack_allgather_split",
            "mw_ctx_set_timing_events", "mw_status_string"]
 MW_KERNEL_PLAN_RANK, MW_KERNEL_PLAN_GROUPS, MW_KERNEL_PACK, MW_KERNEL_RECV_INDEX, MW_KERNEL_EXPAND = 0, 1, 2, 3, 4
 MW_KERNEL_AG_PACK, MW_KERNEL_AG_GATHER, MW_KERNEL_RELAY_INDEX, MW_KERNEL_RELAY_COPY = 5, 6, 7, 8
-MW_KERNEL_PLAN_PACK, MW_KERNEL_PACK_QUANT = 9, 10
+MW_KERNEL_PLAN_PACK, MW_KERNEL_PACK_QUANT, MW_KERNEL_COMBINE = 9, 10, 11
 MW_MAX_HOPS = 64
 MW_FUSED_MAX_TOKENS = 256
 MW_FLAG_BAD_RANK = 0x80
@@ -247,6 +247,11 @@ class Context:
         _check(load().mw_unpack_expand(self._h, C.c_int32(n_peers), _ptr(out_rows), _ptr(out_scales),
                                        C.c_int64(out_capacity_rows), _ptr(out_src_peer), _ptr(out_src_token),
                                        _stream()), "mw_unpack_expand")
+
+    def mw_combine_gather(self, n_peers: int, y: torch.Tensor, out_capacity_rows: int, ret_rows: torch.Tensor,
+                          ret_capacity_rows: int):
+        _check(load().mw_combine_gather(self._h, C.c_int32(n_peers), _ptr(y), C.c_int64(out_capacity_rows),
+                                        _ptr(ret_rows), C.c_int64(ret_capacity_rows), _stream()), "mw_combine_gather")
 
     def mw_unpack_allgather(self, peer_shards: torch.Tensor, shard_bytes: int, out: torch.Tensor):
         _check(load().mw_unpack_allgather(self._h, _ptr(peer_shards), C.c_int64(shard_bytes), _ptr(out),

@@ -379,6 +379,19 @@ MW_API int32_t mw_unpack_packets(mw_ctx *ctx, const mw_recv_packets *peers_dev, 
                                    out_src_token_dev, (hipStream_t)stream);
 }
 
+MW_API int32_t mw_combine_gather(mw_ctx *ctx, int32_t n_peers, const void *y_dev, int64_t out_capacity_rows,
+                          void *ret_rows_dev, int64_t ret_capacity_rows, void *stream)
+{
+    if (!ctx || out_capacity_rows < 0 || ret_capacity_rows < 0) return MW_ERR_INVALID_ARG;
+    if (ctx->cfg.row_format != MW_ROW_BF16) return MW_ERR_UNSUPPORTED;
+    if (n_peers < 1 || n_peers > ctx->cfg.n_ranks || ctx->cfg.n_experts == 0) return MW_ERR_INVALID_ARG;
+    if (out_capacity_rows > 0xffffffffLL || ret_capacity_rows > 0xffffffffLL) return MW_ERR_UNSUPPORTED;
+    if (ret_capacity_rows == 0 || out_capacity_rows == 0) return MW_OK;
+    if (!y_dev || !ret_rows_dev || (((uintptr_t)y_dev | (uintptr_t)ret_rows_dev) & 15u)) return MW_ERR_INVALID_ARG;
+    return mw_launch_combine(ctx, n_peers, y_dev, out_capacity_rows, ret_rows_dev, ret_capacity_rows,
+                             (hipStream_t)stream);
+}
+
 MW_API int32_t mw_unpack_index(mw_ctx *ctx, const mw_recv_peer *peers_dev, int32_t n_peers, int64_t out_capacity_rows,
                         int64_t *expert_offsets_dev, mw_recv_stats *recv_stats_dev, void *stream)
 {

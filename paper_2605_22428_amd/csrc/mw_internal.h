@@ -194,6 +194,7 @@ int32_t mw_launch_pack_packets(mw_ctx *ctx, const void *x, const float *scales, 
                                void *packets, hipStream_t s);
 int32_t mw_launch_unpack_expand(mw_ctx *ctx, int32_t P, void *out_rows, float *out_scales, int64_t cap,
                                 int32_t *out_src_peer, int32_t *out_src_token, hipStream_t s);
+int32_t mw_launch_combine(mw_ctx *ctx, int32_t P, const void *y, int64_t cap, void *ret, int64_t ret_cap, hipStream_t s);
 int32_t mw_launch_plan_allgather(mw_ctx *ctx, int64_t shard_bytes, mw_group_desc *desc,
                                  mw_send_stats *stats, hipStream_t s);
 int32_t mw_launch_plan_allgather_split(mw_ctx *ctx, int64_t shard_bytes, int64_t direct_bytes, mw_group_desc *desc,

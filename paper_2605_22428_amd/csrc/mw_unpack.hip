@@ -468,6 +468,77 @@ __global__ __launch_bounds__(1024) void k_expand(
     }
 }
 
+// The way back (Section 2.1, combine-style AlltoAll; Section 2.3.2: the combine phase reduces
+// and cannot be multicast).  The mirror image of the expander: a received row that went to h
+// local experts gets ONE row back, the sum of those h expert outputs, so the return traffic is
+// one copy per (token, rank) like the dispatch's.  Reads the index the last unpack left in the
+// workspace.  Per 16-byte chunk (8 bf16): widen to single precision, add in the order of the
+// row's hit slots (the order of its id list), round once to bf16 (nearest even; a NaN sum
+// becomes 0x7FC0 with the sum's sign); h == 1 is a copy.  Hits whose output row was dropped for
+// capacity contribute nothing.  Same launch shape and the same bytes as the expander, in the
+// other direction: bound by HBM bandwidth.
+__device__ __forceinline__ uint32_t mw_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return ((u >> 16) & 0x8000u) | 0x7fc0u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+__global__ __launch_bounds__(1024) void k_combine(
+    const mw_row_rec *__restrict__ recs, const mw_hit *__restrict__ hits, const uint32_t *__restrict__ base,
+    const uint32_t *__restrict__ row_base, int P, int Kd, int n, const u32x4 *__restrict__ y, uint32_t cap,
+    u32x4 *__restrict__ ret, uint32_t ret_cap)
+{
+    uint32_t gdim = gridDim.y, bdim = blockDim.x;
+    MW_PIN_S(gdim); MW_PIN_S(bdim); MW_PIN_S(Kd); MW_PIN_S(n); MW_PIN_S(cap); MW_PIN_S(ret_cap);
+    MW_PIN_PTR(hits); MW_PIN_PTR(y); MW_PIN_PTR(ret);
+    const int c = blockIdx.x * bdim + threadIdx.x;
+    uint32_t g = blockIdx.y;
+    const u32x4 *rp = (const u32x4 *)(recs + g);
+    u32x4 r0 = rp[0], r1 = rp[1];
+    uint32_t m_total = row_base[P];
+    MW_PIN_S4(r0); MW_PIN_S4(r1); MW_PIN_S(m_total);
+    while (g < m_total) {
+        const int n_hits = (int)r1.x;
+        if (n_hits > 0 && g < ret_cap) {
+            const uint32_t peer = r0.w;
+            uint32_t pos = base[r1.y * (uint32_t)P + peer] + r1.z;
+            if (n_hits == 1) {
+                if (pos < cap && c < n) mw_st16(ret + (size_t)g * n + c, mw_ld16(y + (size_t)pos * n + c));
+            } else {
+                float acc[8];
+                bool any = false;
+                for (int k = 0;; ++k) {
+                    if (pos < cap && c < n) {
+                        const u32x4 v = mw_ld16(y + (size_t)pos * n + c);
+                        const float f[8] = {__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u),
+                                            __uint_as_float(v.y << 16), __uint_as_float(v.y & 0xffff0000u),
+                                            __uint_as_float(v.z << 16), __uint_as_float(v.z & 0xffff0000u),
+                                            __uint_as_float(v.w << 16), __uint_as_float(v.w & 0xffff0000u)};
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) acc[j] = any ? acc[j] + f[j] : f[j];
+                    }
+                    any = any || pos < cap;
+                    if (k + 1 >= n_hits) break;
+                    const mw_hit hk = hits[(size_t)g * Kd + k + 1];
+                    pos = base[(uint32_t)hk.le * P + peer] + (uint32_t)hk.rank;
+                }
+                if (any && c < n) {
+                    u32x4 o;
+                    o.x = mw_bf16_rne(acc[0]) | (mw_bf16_rne(acc[1]) << 16);
+                    o.y = mw_bf16_rne(acc[2]) | (mw_bf16_rne(acc[3]) << 16);
+                    o.z = mw_bf16_rne(acc[4]) | (mw_bf16_rne(acc[5]) << 16);
+                    o.w = mw_bf16_rne(acc[6]) | (mw_bf16_rne(acc[7]) << 16);
+                    mw_st16(ret + (size_t)g * n + c, o);
+                }
+            }
+        }
+        g += gdim;
+        if (g < m_total) { rp = (const u32x4 *)(recs + g); r0 = rp[0]; r1 = rp[1]; }
+    }
+}
+
 }  // namespace
 
 int32_t mw_launch_unpack_index(mw_ctx *ctx, const void *peers, bool packets, int32_t P, int64_t cap,
@@ -522,6 +593,28 @@ int32_t mw_launch_unpack_expand(mw_ctx *ctx, int32_t P, void *out_rows, float *o
         hipLaunchKernelGGL(k_expand, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, ctx->d_recs, ctx->d_hits, ctx->d_base,
                            ctx->d_row_base, P, ctx->hit_slots, xc, sc, (u32x4 *)out_rows, (u32x4 *)out_scales,
                            (uint32_t)(cap < 0x7fffffffLL ? cap : 0x7fffffffLL), out_src_peer, out_src_token);
+    }
+    MW_HIP_CHECK(hipGetLastError());
+    return MW_OK;
+}
+
+int32_t mw_launch_combine(mw_ctx *ctx, int32_t P, const void *y, int64_t cap, void *ret, int64_t ret_cap, hipStream_t s)
+{
+    const mw_config &c = ctx->cfg;
+    if (c.max_recv_rows > 0 && ret_cap > 0) {
+        const int n = (int)(ctx->x_row_bytes / 16);
+        const mw_row_shape shape = mw_row_shape_of(n);
+        int64_t rows = c.max_recv_rows;                     // grid sized like the expander's
+        if (ctx->recv_rows_hint > 0) {
+            const int64_t want = ctx->recv_rows_hint + ctx->recv_rows_hint / 64 + 64;
+            if (want < rows) rows = want;
+        }
+        const uint32_t gy = (uint32_t)(rows < kRowGridMax ? rows : kRowGridMax);
+        mw_timed tm(ctx, MW_KERNEL_COMBINE, s);
+        hipLaunchKernelGGL(k_combine, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, ctx->d_recs, ctx->d_hits, ctx->d_base,
+                           ctx->d_row_base, P, ctx->hit_slots, n, (const u32x4 *)y,
+                           (uint32_t)(cap < 0x7fffffffLL ? cap : 0x7fffffffLL), (u32x4 *)ret,
+                           (uint32_t)(ret_cap < 0x7fffffffLL ? ret_cap : 0x7fffffffLL));
     }
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;
