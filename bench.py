@@ -371,6 +371,30 @@ def bench_dispatch(args, name: str) -> dict:
                  "bytes_of_quantise_then_pack": q_bytes + 2 * N * rb}
         del xb_d
 
+    # ---------------------------------------------------------------- the way back (extra, untimed region)
+    # bf16 workloads: one returned row per received row, the sum of its local experts' outputs
+    # (here: the expanded rows themselves stand in for the experts' outputs).
+    combine = None
+    if not fp8:
+        rv = sets[0]["recv"]
+        ctx.mw_unpack(sets[0]["table"], R, rv.out_rows, rv.out_scales, cap, rv.out_src_peer, rv.out_src_token,
+                      rv.expert_offsets, rv.stats)
+        ret = torch.zeros((M, w.hidden), dtype=torch.int16, device=dev)
+        n_r = 20
+        evc = new_events(torch, n_r)
+        for i in range(n_r + 3):
+            if i >= 3:
+                ctx.mw_ctx_set_timing_events(B.MW_KERNEL_COMBINE, *evc[i - 3])
+            ctx.mw_combine_gather(R, rv.out_rows, cap, ret, M)
+        torch.cuda.synchronize()
+        ctx.mw_ctx_set_timing_events(B.MW_KERNEL_COMBINE, None, None)
+        c_us = 1e3 * sum(a.elapsed_time(b) for a, b in evc) / n_r
+        c_bytes = Q * rb + M * rb + M * 32
+        combine = {"us": round(c_us, 2), "bytes": c_bytes, "GBps": round(c_bytes / c_us / 1e3, 1),
+                   "pct_of_hbm_peak": round(100.0 * c_bytes / c_us / 1e3 / HBM_PEAK_GBPS, 2),
+                   "rows_back": M, "rows_without_local_sum": Q}
+        del ret
+
     # ---------------------------------------------------------------- decode-sized send side (extra, untimed region)
     # The first 64 / 128 tokens of this rank's batch (the small batch sizes of the paper's
     # dispatch experiment, Section 6.3): mw_plan + mw_pack against the single launch of
@@ -445,6 +469,8 @@ def bench_dispatch(args, name: str) -> dict:
         result["packets"] = packets
     if quant is not None:
         result["quantize_in_pack"] = quant
+    if combine is not None:
+        result["combine_gather"] = combine
 
     # ---------------------------------------------------------------- oracle on the host cores
     if not args.no_cpu_baseline and name == "c1":
