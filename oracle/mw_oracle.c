@@ -975,3 +975,61 @@ int ref_combine_gather(const ref_recv_peer *peers, int32_t P, int32_t K,
     if (rc == REF_OK && bad) rc = REF_ERR_EXPERT;
     return rc;
 }
+
+/* ------------------------------------------------------------------------ */
+/*
+ * Relay of packets: the paper's own form of the step (Section 4.1,
+ * "Replication and forwarding": the relay buffers the payload, parses the
+ * bitmap, makes one copy per distinct egress port and updates the in-packet
+ * metadata of each copy so that downstream nodes do not replicate again;
+ * Section 4.3.3, the recursive model).  Reading, as for ref_relay_child with
+ * every packet its own group: the child for hop h keeps, in order, the
+ * packets whose bitmap names at least one rank with next_hop == h; the
+ * header's bitmap becomes the parent's restricted to those ranks; everything
+ * else in the packet is copied unchanged.
+ * Also returns the accounting of the whole relay step through `copies`
+ * (packets written over all hops: one per distinct next hop, Section 4.1)
+ * and `dests` (one per destination: what unicast would send); both may be
+ * NULL.
+ */
+int ref_relay_packets_child(const uint8_t *packets, int64_t n_packets, int64_t packet_bytes,
+                            const int32_t *next_hop, int32_t R, int32_t n_hops, int32_t hop,
+                            uint8_t *out, int64_t *n_out, uint64_t *copies, uint64_t *dests)
+{
+    if (R < 1 || R > REF_MAX_RANKS || n_hops < 1 || hop < 0 || hop >= n_hops || packet_bytes < 128) return REF_ERR_ARG;
+    for (int32_t r = 0; r < R; ++r)
+        if (next_hop[r] < 0 || next_hop[r] >= n_hops) return REF_ERR_ARG;
+    int64_t n = 0;
+    uint64_t n_copies = 0, n_dests = 0;
+    for (int64_t i = 0; i < n_packets; ++i) {
+        const uint8_t *pk = packets + (size_t)i * (size_t)packet_bytes;
+        uint64_t mask[REF_MASK_WORDS], sub[REF_MASK_WORDS] = {0, 0, 0, 0};
+        for (int w = 0; w < REF_MASK_WORDS; ++w) mask[w] = get_le(pk + 8 * w, 8);
+        int n_sub = 0;
+        for (int32_t h = 0; h < n_hops; ++h) {
+            int used = 0;
+            for (int r = 0; r < REF_MAX_RANKS; ++r) {
+                if (!mask_bit(mask, r)) continue;
+                if (r >= R) return REF_ERR_INPUT;
+                if (next_hop[r] == h) used = 1;
+            }
+            n_copies += (uint64_t)used;
+        }
+        for (int r = 0; r < R; ++r) {
+            if (!mask_bit(mask, r)) continue;
+            ++n_dests;
+            if (next_hop[r] != hop) continue;
+            sub[r >> 6] |= (uint64_t)1 << (r & 63);
+            ++n_sub;
+        }
+        if (n_sub == 0) continue;
+        uint8_t *dst = out + (size_t)n * (size_t)packet_bytes;
+        memcpy(dst, pk, (size_t)packet_bytes);
+        for (int w = 0; w < REF_MASK_WORDS; ++w) put_le(dst + 8 * w, sub[w], 8);
+        ++n;
+    }
+    *n_out = n;
+    if (copies) *copies = n_copies;
+    if (dests) *dests = n_dests;
+    return REF_OK;
+}

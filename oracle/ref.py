@@ -58,7 +58,7 @@ def lib():
                      "ref_relay_child", "ref_relay_accounting", "ref_allgather_split_point",
                      "ref_plan_allgather_split", "ref_unpack_allgather_split",
                      "ref_pack_packets", "ref_deliver_packets", "ref_unpack_packets",
-                     "ref_quantize_e4m3_block128", "ref_combine_gather"):
+                     "ref_quantize_e4m3_block128", "ref_combine_gather", "ref_relay_packets_child"):
             getattr(_lib, name).restype = C.c_int
         _lib.ref_packet_header_bytes.restype = C.c_int64
     return _lib
@@ -404,3 +404,16 @@ def combine_gather(peers: Sequence[PeerBuf], top_k: int, e2r, my_rank: int, y_bf
                                     C.c_int32(my_rank), C.c_int32(H), _p(y), _p(sp), _p(stok), _p(offs), ptrs),
            "ref_combine_gather")
     return outs
+
+
+def relay_packets_child(packets: np.ndarray, next_hop, n_hops: int, hop: int):
+    """-> (child packets of next hop `hop`, packets written by the whole relay step, destinations named)"""
+    packets = np.ascontiguousarray(packets, dtype=np.uint8)
+    next_hop = _i32(next_hop)
+    out = np.zeros_like(packets)
+    n, copies, dests = C.c_int64(0), C.c_uint64(0), C.c_uint64(0)
+    _check(lib().ref_relay_packets_child(_p(packets), C.c_int64(packets.shape[0]), C.c_int64(packets.shape[1]),
+                                         _p(next_hop), C.c_int32(len(next_hop)), C.c_int32(n_hops), C.c_int32(hop),
+                                         _p(out), C.byref(n), C.byref(copies), C.byref(dests)),
+           "ref_relay_packets_child")
+    return out[: n.value].copy(), copies.value, dests.value

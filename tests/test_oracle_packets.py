@@ -146,3 +146,82 @@ def test_inconsistent_packets_are_refused():
         ref.unpack_packets([dup], 2, e2r, 1, 128, 0, 100)
     with pytest.raises(ref.OracleError):
         ref.unpack_packets([pk], 2, e2r, 1, 128, 0, 0)    # no room
+
+
+# ------------------------------------------------------------------ relay of packets
+def _ranks(header: bytes):
+    m, _, _, _ = _parse(header)
+    return {r for r in range(256) if (m >> r) & 1}
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_relayed_copies_partition_every_bitmap_and_match_the_descriptor_path(seed):
+    """Section 4.1, update of in-packet metadata: the copies of one packet name disjoint sets
+    that together are the parent's; the number of copies is the number of distinct next hops."""
+    rng = np.random.default_rng(seed)
+    w = W.DispatchWorkload("t", 34, 12, 24, 3, 50, 64, "bf16", "uniform")
+    tk, x, sc, mask, perm, desc = _sender(w, seed, 0)
+    pk = ref.pack_packets(x, sc, tk, mask, perm)
+    packed, src, rtk = ref.pack(x, sc, tk, perm)
+    n_hops = 5
+    next_hop = rng.integers(0, n_hops, size=w.n_ranks).astype(np.int32)
+    seen = [set() for _ in range(len(pk))]
+    copies_total = 0
+    for h in range(n_hops):
+        child, copies, dests = ref.relay_packets_child(pk, next_hop, n_hops, h)
+        keep = [i for i in range(len(pk)) if any(next_hop[r] == h for r in _ranks(pk[i, :128].tobytes()))]
+        assert len(child) == len(keep)
+        copies_total += len(child)
+        for c, i in zip(child, keep):
+            sub = _ranks(c[:128].tobytes())
+            assert sub == {r for r in _ranks(pk[i, :128].tobytes()) if next_hop[r] == h}
+            assert not (sub & seen[i])
+            seen[i] |= sub
+            assert c[32:].tobytes() == pk[i, 32:].tobytes()        # everything but the bitmap is unchanged
+        # the descriptor-table relay keeps the same rows with the same restricted bitmaps
+        d2, r2, s2, t2 = ref.relay_child(desc, packed, src, rtk, next_hop, n_hops, h)
+        rows_desc = [(brute.words_to_int(d2["mask"][g]), int(s2[int(d2["row_offset"][g]) + k]))
+                     for g in range(len(d2)) for k in range(int(d2["row_count"][g]))]
+        rows_pk = [(_parse(c[:128].tobytes())[0], _parse(c[:128].tobytes())[1]) for c in child]
+        assert rows_pk == rows_desc
+        assert child[:, 128:].tobytes() == r2.tobytes()
+    assert all(seen[i] == _ranks(pk[i, :128].tobytes()) for i in range(len(pk)))
+    assert copies == copies_total == sum(len({int(next_hop[r]) for r in _ranks(p[:128].tobytes())}) for p in pk)
+    assert dests == sum(len(_ranks(p[:128].tobytes())) for p in pk)
+
+
+def test_delivery_through_two_levels_of_relays_equals_direct_delivery():
+    """Section 4.3.3: the recursion ends in plain writes and delivers what a direct MultiWrite
+    delivers.  Two servers of four devices: first hop per server, second hop per device."""
+    w = W.DispatchWorkload("t", 35, 8, 24, 4, 40, 128, "bf16", "uniform")
+    e2r = W.expert_to_rank(w)
+    my_rank = 6
+    toks, direct, relayed = [], [], []
+    for p in range(w.n_ranks):
+        tk, x, sc, mask, perm, desc = _sender(w, 4, p)
+        toks.append((tk, x, sc))
+        pk = ref.pack_packets(x, sc, tk, mask, perm)
+        direct.append(ref.deliver_packets(pk, my_rank))
+        to_server = np.array([r // 4 for r in range(8)], dtype=np.int32)
+        at_server, _, _ = ref.relay_packets_child(pk, to_server, 2, my_rank // 4)
+        to_device = np.array([r % 4 for r in range(8)], dtype=np.int32)      # only this server's ranks remain
+        mine, _, _ = ref.relay_packets_child(at_server, to_device, 4, my_rank % 4)
+        for c in mine:
+            assert _ranks(c[:128].tobytes()) == {my_rank}                    # down to a plain write
+        relayed.append(mine)
+    cap = 10 ** 4
+    a = ref.unpack_packets(direct, w.top_k, e2r, my_rank, w.row_bytes, 0, cap)
+    b = ref.unpack_packets(relayed, w.top_k, e2r, my_rank, w.row_bytes, 0, cap)
+    plain = ref.dispatch_plain(toks, e2r, my_rank, cap)
+    for u, v, z in zip(a[:5], b[:5], plain):
+        assert (u is None and v is None) or u.tobytes() == v.tobytes() == z.tobytes()
+
+
+def test_relay_tables_that_cannot_be_followed_are_refused():
+    w = W.DispatchWorkload("t", 36, 4, 8, 2, 12, 64, "bf16", "uniform")
+    tk, x, sc, mask, perm, desc = _sender(w, 1, 0)
+    pk = ref.pack_packets(x, sc, tk, mask, perm)
+    with pytest.raises(ref.OracleError):
+        ref.relay_packets_child(pk, np.array([0, 1, 2, 3], np.int32), 3, 0)      # hop 3 does not exist
+    with pytest.raises(ref.OracleError):
+        ref.relay_packets_child(pk, np.array([0, 1], np.int32), 2, 0)            # bitmaps name ranks 2, 3
