@@ -345,7 +345,28 @@ def bench_dispatch(args, name: str) -> dict:
                    "pack_GBps": round(pk_pack_bytes / pk_us["pack"] / 1e3, 1),
                    "expand_GBps": round(pk_expand_bytes / pk_us["expand"] / 1e3, 1),
                    "expand_pct_of_hbm_peak": round(100.0 * pk_expand_bytes / pk_us["expand"] / 1e3 / HBM_PEAK_GBPS, 2)}
-        del pk_send, pk_table
+        # the relay step on this rank's own packets, same two-level topology as above
+        kids = [torch.zeros((T, hb + rb), dtype=torch.uint8, device=dev) for _ in range(n_hops)]
+        kid_table = torch.tensor([k.data_ptr() for k in kids], dtype=torch.int64, device=dev)
+        in_pk = B.packets_table([pk_send], [N], dev)
+        rstats = torch.zeros(B.RELAY_STATS_BYTES, dtype=torch.uint8, device=dev)
+        evr = {k: new_events(torch, n_r) for k in relay_names}
+        for i in range(n_r + 3):
+            if i >= 3:
+                for k, code in relay_names.items():
+                    ctx.mw_ctx_set_timing_events(code, *evr[k][i - 3])
+            ctx.mw_relay_packets(in_pk, kid_table, T, rstats)
+        torch.cuda.synchronize()
+        for code in relay_names.values():
+            ctx.mw_ctx_set_timing_events(code, None, None)
+        rst = ctx.mw_get_relay_stats(rstats)
+        assert int(rst["error_flags"]) == 0 and int(rst["n_rows_in"]) == N
+        rp_us = {k: 1e3 * sum(a.elapsed_time(b) for a, b in evr[k]) / n_r for k in relay_names}
+        rp_bytes = N * (hb + rb) + int(rst["forward_bytes"])
+        packets["relay"] = {"us": {k: round(v, 2) for k, v in rp_us.items()},
+                            "copies_per_packet": round(int(rst["forward_bytes"]) / (hb + rb) / N, 4),
+                            "copy_GBps": round(rp_bytes / rp_us["relay_copy"] / 1e3, 1)}
+        del pk_send, pk_table, kids
     del pk_regions
 
     # ---------------------------------------------------------------- quantise-in-pack (extra, untimed region)

@@ -434,6 +434,22 @@ MW_API int32_t mw_set_forwarding(mw_ctx *ctx, const int32_t *next_hop, int32_t n
 MW_API int32_t mw_relay(mw_ctx *ctx, const mw_recv_peer *in_dev, const mw_relay_child *children_dev,
                  int64_t child_capacity_rows, mw_relay_stats *stats_dev, void *stream);
 
+/*
+ * mw_relay_packets: the relay step for packets -- the paper's own form of it (Section 4.1,
+ * "Replication and forwarding": the relay parses the bitmap in front of the payload, makes one
+ * copy per distinct egress port and updates the in-packet metadata of each copy so that
+ * downstream nodes do not replicate again).  in_dev: one device record.  children_dev: device
+ * array of n_hops device pointers, child h a buffer of child_capacity_rows packets.  Child h
+ * keeps, in order, the packets whose bitmap names a rank with next_hop == h; the first 32
+ * bytes of each copy (the bitmap) are the parent's restricted to those ranks, the rest of the
+ * packet is unchanged.  Statistics as mw_relay with every packet its own group; forward_bytes
+ * and unicast_bytes count whole packets (header + row).  A header whose id count is not top_k
+ * drops the packet (MW_FLAG_BAD_DESC); packets beyond a child's capacity are dropped from that
+ * child (MW_FLAG_OUT_CAPACITY); n_rows may not exceed max_tokens.
+ */
+MW_API int32_t mw_relay_packets(mw_ctx *ctx, const mw_recv_packets *in_dev, void *const *children_dev,
+                         int64_t child_capacity_rows, mw_relay_stats *stats_dev, void *stream);
+
 /* ---- simulation and measurement helpers (not part of the dispatch path) ---------------- */
 
 /*

@@ -492,6 +492,16 @@ MW_API int32_t mw_relay(mw_ctx *ctx, const mw_recv_peer *in_dev, const mw_relay_
     return mw_launch_relay(ctx, in_dev, children_dev, child_capacity_rows, stats_dev, (hipStream_t)stream);
 }
 
+MW_API int32_t mw_relay_packets(mw_ctx *ctx, const mw_recv_packets *in_dev, void *const *children_dev,
+                         int64_t child_capacity_rows, mw_relay_stats *stats_dev, void *stream)
+{
+    if (!ctx || !in_dev || !children_dev || !stats_dev || child_capacity_rows < 0) return MW_ERR_INVALID_ARG;
+    if (ctx->cfg.max_hops < 1 || ctx->n_hops < 1) return MW_ERR_INVALID_ARG;      // no forwarding table
+    if (ctx->cfg.n_experts == 0) return MW_ERR_INVALID_ARG;
+    if (child_capacity_rows > 0x7fffffffLL) return MW_ERR_UNSUPPORTED;
+    return mw_launch_relay_packets(ctx, in_dev, children_dev, child_capacity_rows, stats_dev, (hipStream_t)stream);
+}
+
 MW_API int32_t mw_get_relay_stats(mw_ctx *ctx, const mw_relay_stats *stats_dev, mw_relay_stats *host_out, void *stream)
 {
     if (!ctx || !stats_dev || !host_out) return MW_ERR_INVALID_ARG;

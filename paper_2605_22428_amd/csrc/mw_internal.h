@@ -206,6 +206,8 @@ int32_t mw_launch_gather_shards(mw_ctx *ctx, const void *const *shards, int64_t 
                                 hipStream_t s);
 int32_t mw_launch_relay(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay_child *children, int64_t cap,
                         mw_relay_stats *stats, hipStream_t s);
+int32_t mw_launch_relay_packets(mw_ctx *ctx, const mw_recv_packets *in, void *const *children, int64_t cap,
+                                mw_relay_stats *stats, hipStream_t s);
 int32_t mw_launch_sim_deliver(mw_ctx *ctx, const mw_group_desc *desc, const mw_send_stats *stats,
                               int32_t T, const void *rows, const int32_t *src_token, const int32_t *topk,
                               int32_t dst_rank, mw_group_desc *desc_out, void *rows_out,

@@ -213,6 +213,143 @@ __global__ __launch_bounds__(1024) void k_relay_copy(
     }
 }
 
+// ---- the same step for packets (Section 4.1, "Replication and forwarding": the relay parses the
+// bitmap in front of the payload, makes one copy per distinct egress port and updates the
+// in-packet metadata of each copy).  Every packet is its own group, so there is no row -> group
+// map: workgroup h ranks the packets that hop h keeps (child position = exclusive count), the
+// extra workgroup does the accounting, and the copy kernel reads a packet once and stores it
+// once per hop with the first 32 bytes -- the bitmap -- replaced by its restriction to that hop.
+struct pkt_view { uint64_t m[MW_MASK_WORDS]; bool valid; };
+
+__device__ __forceinline__ pkt_view load_packet_header(const char *packets, uint64_t packet_bytes, uint32_t i,
+                                                       uint32_t n_rows, uint32_t K)
+{
+    pkt_view v;
+#pragma unroll
+    for (int w = 0; w < MW_MASK_WORDS; ++w) v.m[w] = 0;
+    v.valid = false;
+    if (i >= n_rows) return v;
+    const char *hd = packets + (size_t)i * packet_bytes;
+    const u32x4 a = *(const u32x4 *)hd, b = *(const u32x4 *)(hd + 16);
+    v.m[0] = ((uint64_t)a.y << 32) | a.x; v.m[1] = ((uint64_t)a.w << 32) | a.z;
+    v.m[2] = ((uint64_t)b.y << 32) | b.x; v.m[3] = ((uint64_t)b.w << 32) | b.z;
+    v.valid = *(const uint32_t *)(hd + 36) == K;
+    return v;
+}
+
+__global__ __launch_bounds__(kBlock) void k_relay_packets_index(
+    const mw_recv_packets *__restrict__ in, int n_hops, int n_ranks, uint32_t K, uint32_t max_tokens, uint32_t cap,
+    uint64_t packet_bytes, const uint64_t *__restrict__ hop_bits, uint32_t *__restrict__ child_pos,
+    uint32_t *relay_flags, mw_relay_stats *__restrict__ stats)
+{
+    __shared__ uint32_t scratch[17];
+    __shared__ unsigned long long acc[2];        // packets taken, destinations named
+    const uint32_t tid = threadIdx.x;
+    const mw_recv_packets src = in[0];
+    const char *packets = (const char *)src.packets;
+    const uint32_t n_rows = min(src.n_rows, max_tokens);
+    uint32_t err = src.n_rows > max_tokens ? MW_FLAG_BAD_DESC : 0u;
+
+    if ((int)blockIdx.x < n_hops) {
+        const int h = blockIdx.x;
+        uint64_t hb[MW_MASK_WORDS];
+#pragma unroll
+        for (int w = 0; w < MW_MASK_WORDS; ++w) hb[w] = hop_bits[(size_t)h * MW_MASK_WORDS + w];
+        uint32_t carry = 0;
+        pkt_view nxt = load_packet_header(packets, packet_bytes, tid, n_rows, K);
+        for (uint32_t i0 = 0; i0 < n_rows; i0 += kBlock) {
+            const uint32_t i = i0 + tid;
+            const pkt_view v = nxt;
+            nxt = load_packet_header(packets, packet_bytes, i + kBlock, n_rows, K);   // in flight during the scan
+            bool keep = false;
+#pragma unroll
+            for (int w = 0; w < MW_MASK_WORDS; ++w) keep |= (v.m[w] & hb[w]) != 0;
+            keep = keep && v.valid;
+            uint32_t tot;
+            const uint32_t pos = carry + mw_block_exscan(keep ? 1u : 0u, scratch, &tot);
+            if (i < n_rows) {
+                const bool fits = keep && pos < cap;
+                if (keep && !fits) err |= MW_FLAG_OUT_CAPACITY;
+                child_pos[(size_t)i * MW_MAX_HOPS + h] = fits ? pos : kNoChild;
+            }
+            carry += tot;
+        }
+        if (tid == 0) {
+            const uint32_t fit = min(carry, cap);      // the packets that fit are a prefix of the kept ones
+            stats->groups_per_hop[h] = fit; stats->rows_per_hop[h] = fit;
+        }
+    } else {
+        if (tid < 2) acc[tid] = 0;
+        mw_lds_barrier();
+        uint64_t valid_ranks[MW_MASK_WORDS];
+#pragma unroll
+        for (int w = 0; w < MW_MASK_WORDS; ++w) {
+            const int lo = w * 64;
+            valid_ranks[w] = (n_ranks >= lo + 64) ? ~0ull : (n_ranks > lo ? ((1ull << (n_ranks - lo)) - 1ull) : 0ull);
+        }
+        uint32_t taken = 0, dests = 0;
+        for (uint32_t i = tid; i < n_rows; i += kBlock) {
+            const pkt_view v = load_packet_header(packets, packet_bytes, i, n_rows, K);
+            if (!v.valid) { err |= MW_FLAG_BAD_DESC; continue; }
+#pragma unroll
+            for (int w = 0; w < MW_MASK_WORDS; ++w) {
+                if (v.m[w] & ~valid_ranks[w]) err |= MW_FLAG_BAD_RANK;
+                dests += (uint32_t)__popcll(v.m[w] & valid_ranks[w]);
+            }
+            ++taken;
+        }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) { taken += __shfl_xor(taken, d, 64); dests += __shfl_xor(dests, d, 64); }
+        if ((tid & 63) == 0) { atomicAdd(&acc[0], (unsigned long long)taken); atomicAdd(&acc[1], (unsigned long long)dests); }
+        mw_lds_barrier();
+        if (tid == 0) {
+            stats->n_groups_in = (uint32_t)acc[0];
+            stats->n_rows_in = (uint32_t)acc[0];
+            stats->unicast_bytes = (uint64_t)acc[1] * packet_bytes;
+            stats->reserved0 = 0;
+        }
+        for (int h = n_hops + tid; h < MW_MAX_HOPS; h += kBlock) { stats->groups_per_hop[h] = 0; stats->rows_per_hop[h] = 0; }
+    }
+    if (err) atomicOr(relay_flags, err);
+}
+
+// blockIdx.x selects a segment of blockDim.x chunks of a packet, blockIdx.y walks packets.
+__global__ __launch_bounds__(1024) void k_relay_packets_copy(
+    const mw_recv_packets *__restrict__ in, void *const *__restrict__ children, int n_hops, int n_chunks,
+    uint32_t max_tokens, uint64_t packet_bytes, const uint64_t *__restrict__ hop_bits,
+    const uint32_t *__restrict__ child_pos, uint32_t *relay_flags, mw_relay_stats *__restrict__ stats)
+{
+    const mw_recv_packets src = in[0];
+    const uint32_t n_rows = min(src.n_rows, max_tokens);
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    for (uint32_t i = blockIdx.y; i < n_rows; i += gridDim.y) {
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (c < n_chunks) v = mw_ld16((const u32x4 *)src.packets + (size_t)i * n_chunks + c);
+        const uint32_t p = (lane < n_hops) ? child_pos[(size_t)i * MW_MAX_HOPS + lane] : kNoChild;
+        uint64_t hops = __ballot(p != kNoChild);              // the same in every wave
+        while (hops) {
+            const int h = __ffsll((unsigned long long)hops) - 1;
+            hops &= hops - 1;
+            const uint32_t dst = (uint32_t)__shfl((int)p, h, 64);
+            u32x4 o = v;
+            if (c < 2) {                                      // chunks 0 and 1 are the bitmap
+                const uint64_t b0 = hop_bits[(size_t)h * MW_MASK_WORDS + 2 * c];
+                const uint64_t b1 = hop_bits[(size_t)h * MW_MASK_WORDS + 2 * c + 1];
+                o.x &= (uint32_t)b0; o.y &= (uint32_t)(b0 >> 32); o.z &= (uint32_t)b1; o.w &= (uint32_t)(b1 >> 32);
+            }
+            if (c < n_chunks) mw_st16((u32x4 *)children[h] + (size_t)dst * n_chunks + c, o);
+        }
+    }
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+        unsigned long long rows_out = 0;
+        for (int h = 0; h < n_hops; ++h) rows_out += stats->rows_per_hop[h];
+        stats->forward_bytes = rows_out * packet_bytes;
+        stats->error_flags = __hip_atomic_load(relay_flags, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(relay_flags, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next relay
+    }
+}
+
 }  // namespace
 
 int32_t mw_launch_relay(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay_child *children, int64_t cap,
@@ -234,6 +371,31 @@ int32_t mw_launch_relay(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay_chil
         hipLaunchKernelGGL(k_relay_copy, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, in, children, ctx->n_hops, c.top_k, n_chunks,
                            (uint32_t)c.max_tokens, (uint64_t)ctx->row_bytes, ctx->d_group_of_row, ctx->d_child_pos,
                            ctx->d_relay_flags, stats);
+    }
+    MW_HIP_CHECK(hipGetLastError());
+    return MW_OK;
+}
+
+int32_t mw_launch_relay_packets(mw_ctx *ctx, const mw_recv_packets *in, void *const *children, int64_t cap,
+                                mw_relay_stats *stats, hipStream_t s)
+{
+    const mw_config &c = ctx->cfg;
+    const uint64_t pb = (uint64_t)(mw_packet_header_bytes_of(c.top_k) + ctx->row_bytes);
+    const int n_chunks = (int)(pb / 16);
+    {
+        mw_timed tm(ctx, MW_KERNEL_RELAY_INDEX, s);
+        hipLaunchKernelGGL(k_relay_packets_index, dim3(ctx->n_hops + 1), dim3(kBlock), 0, s, in, ctx->n_hops, c.n_ranks,
+                           (uint32_t)c.top_k, (uint32_t)c.max_tokens, (uint32_t)cap, pb, ctx->d_hop_bits,
+                           ctx->d_child_pos, ctx->d_relay_flags, stats);
+    }
+    {
+        const mw_row_shape shape = mw_row_shape_of(n_chunks);
+        uint32_t gy = (uint32_t)c.max_tokens < kRowGridMax ? (uint32_t)c.max_tokens : kRowGridMax;
+        if (gy < 1) gy = 1;
+        mw_timed tm(ctx, MW_KERNEL_RELAY_COPY, s);
+        hipLaunchKernelGGL(k_relay_packets_copy, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, in, children, ctx->n_hops,
+                           n_chunks, (uint32_t)c.max_tokens, pb, ctx->d_hop_bits, ctx->d_child_pos, ctx->d_relay_flags,
+                           stats);
     }
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;

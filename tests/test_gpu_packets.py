@@ -204,3 +204,117 @@ def test_empty_regions_and_bad_headers():
     gu = H.GpuUnpack(ctx, [H.shrink(gs.deliver(0))], 1000)
     H.check_unpack(gu, want, "descriptor path after packets")
     ctx.close()
+
+
+# ------------------------------------------------------------------ relay of packets
+def _relay_ctx(w, my_rank, max_hops):
+    return B.Context(w.n_ranks, w.n_experts, w.top_k, my_rank, w.hidden, H.fmt_code(w), max(w.n_tokens, 1),
+                     w.n_ranks * w.n_tokens, W.expert_to_rank(w), device=H.DEV, max_hops=max_hops)
+
+
+def gpu_relay_packets(ctx, packets, n_rows, next_hop, n_hops, capacity):
+    ctx.mw_set_forwarding(next_hop, n_hops)
+    pb = packets.shape[1]
+    kids = [torch.zeros((max(capacity, 1), pb), dtype=torch.uint8, device=H.DEV) for _ in range(n_hops)]
+    table = torch.tensor([k.data_ptr() for k in kids], dtype=torch.int64, device=H.DEV)
+    rec = B.packets_table([packets], [n_rows], H.DEV)
+    stats = torch.zeros(B.RELAY_STATS_BYTES, dtype=torch.uint8, device=H.DEV)
+    ctx.mw_relay_packets(rec, table, capacity, stats)
+    st = ctx.mw_get_relay_stats(stats)
+    return kids, st
+
+
+@pytest.mark.parametrize("which", ["c0", "c1_reduced", "c3_reduced", "fp8"])
+def test_relay_packets_children_and_accounting(which):
+    w = {"c0": W.C0, "c1_reduced": W.scaled(W.C1, n_tokens=333, hidden=1024),
+         "c3_reduced": W.scaled(W.C3, n_tokens=200, hidden=512),
+         "fp8": W.scaled(W.C2, n_tokens=150, hidden=1024)}[which]
+    _say("relay packets", w.name)
+    n_per = 8
+    me = 9 % w.n_ranks
+    next_hop = np.array([(r % n_per) if r // n_per == me // n_per else n_per + (r // n_per) -
+                         (1 if r // n_per > me // n_per else 0) for r in range(w.n_ranks)], dtype=np.int32)
+    n_hops = int(next_hop.max()) + 1
+    ctx = _relay_ctx(w, me, n_hops)
+    tk = W.topk_ids(w, 3, me)
+    x, sc = W.payload_rows(w, 3, me)
+    g = GpuPackets(ctx, tk, x, sc)
+    kids, st = gpu_relay_packets(ctx, g.packets, g.N, next_hop, n_hops, w.n_tokens)
+    parent = H.host(g.packets)[: g.N]
+    pb = parent.shape[1]
+    total = 0
+    for h in range(n_hops):
+        want, copies, dests = ref.relay_packets_child(parent, next_hop, n_hops, h)
+        n = int(st["rows_per_hop"][h])
+        assert n == len(want) == int(st["groups_per_hop"][h])
+        H.assert_same_bytes(H.host(kids[h])[:n], want, "child %d packets" % h)
+        total += n
+    assert int(st["error_flags"]) == 0
+    assert (int(st["n_rows_in"]), int(st["n_groups_in"])) == (g.N, g.N)
+    assert int(st["forward_bytes"]) == copies * pb == total * pb
+    assert int(st["unicast_bytes"]) == dests * pb
+    ctx.close()
+
+
+def test_delivery_through_relayed_packets_equals_direct_delivery():
+    """Two servers of four devices: every sender's packets go through a server-level relay and a
+    device-level relay on the GPU; what reaches my_rank is unpacked and compared with the plain
+    definition of the dispatch."""
+    w = W.DispatchWorkload("two_level", 81, 8, 24, 4, 90, 256, "bf16", "uniform")
+    e2r = W.expert_to_rank(w)
+    my_rank = 6
+    ctx = _relay_ctx(w, my_rank, 4)
+    to_server = np.array([r // 4 for r in range(8)], dtype=np.int32)
+    to_device = np.array([r % 4 for r in range(8)], dtype=np.int32)
+    toks, regions = [], []
+    for p in range(w.n_ranks):
+        tk = W.topk_ids(w, 5, p)
+        x, _ = W.payload_rows(w, 5, p)
+        toks.append((tk, x, None))
+        g = GpuPackets(ctx, tk, x, None)
+        kids, st = gpu_relay_packets(ctx, g.packets, g.N, to_server, 2, w.n_tokens)
+        n1 = int(st["rows_per_hop"][my_rank // 4])
+        at_server = kids[my_rank // 4][:max(n1, 1)].clone()
+        kids2, st2 = gpu_relay_packets(ctx, at_server, n1, to_device, 4, w.n_tokens)
+        n2 = int(st2["rows_per_hop"][my_rank % 4])
+        assert int(st["error_flags"]) == 0 and int(st2["error_flags"]) == 0
+        mine = kids2[my_rank % 4][:n2].clone()
+        # down to a plain write: only my_rank is left in every bitmap
+        words = H.host(mine)[:, :32].copy().view(np.uint64)
+        assert np.all(words[:, 0] == np.uint64(1 << my_rank)) and not words[:, 1:].any()
+        regions.append(mine)
+    cap = 10 ** 4
+    want = ref.dispatch_plain(toks, e2r, my_rank, cap)
+    got, st = unpack_packets(ctx, regions, cap)
+    assert int(st["error_flags"]) == 0
+    same(got, want, "through two relay levels")
+    ctx.close()
+
+
+def test_relay_packets_capacity_and_bad_headers():
+    w = W.DispatchWorkload("small", 31, 8, 16, 2, 128, 256, "bf16", "uniform")
+    ctx = _relay_ctx(w, 0, 2)
+    tk = W.topk_ids(w, 1, 0)
+    x, _ = W.payload_rows(w, 1, 0)
+    g = GpuPackets(ctx, tk, x, None)
+    next_hop = np.array([0, 0, 0, 0, 1, 1, 1, 1], dtype=np.int32)
+    parent = H.host(g.packets)[: g.N]
+    want0, _, _ = ref.relay_packets_child(parent, next_hop, 2, 0)
+    cap = len(want0) // 2
+    kids, st = gpu_relay_packets(ctx, g.packets, g.N, next_hop, 2, cap)
+    assert int(st["error_flags"]) == B.MW_FLAG_OUT_CAPACITY
+    assert int(st["rows_per_hop"][0]) == cap
+    H.assert_same_bytes(H.host(kids[0])[:cap], want0[:cap], "packets below the capacity are still exact")
+    # a header with another id count: the packet is forwarded nowhere
+    bad = g.packets.clone()
+    bad[3, 36] = 7
+    kids, st = gpu_relay_packets(ctx, bad, g.N, next_hop, 2, w.n_tokens)
+    assert int(st["error_flags"]) == B.MW_FLAG_BAD_DESC and int(st["n_rows_in"]) == g.N - 1
+    rest = np.delete(parent, 3, axis=0)
+    for h in range(2):
+        want, _, _ = ref.relay_packets_child(rest, next_hop, 2, h)
+        n = int(st["rows_per_hop"][h])
+        H.assert_same_bytes(H.host(kids[h])[:n], want, "child %d without the bad packet" % h)
+    kids, st = gpu_relay_packets(ctx, g.packets, g.N, next_hop, 2, w.n_tokens)
+    assert int(st["error_flags"]) == 0                    # flags do not stick
+    ctx.close()
