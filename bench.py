@@ -507,7 +507,7 @@ def bench_dispatch(args, name: str) -> dict:
             del xp, packed
         reps, spent = 0, 0.0
         t_plan = t_pack = t_unpack = 0.0
-        while reps < 3 or (spent < 10.0 and reps < 40):
+        while reps < 3 or (spent < 12.0 and reps < 400):
             a = time.perf_counter()
             _, perm, desc, ost = ref.plan(topks[my_rank], e2r, R, rb)
             b = time.perf_counter()
