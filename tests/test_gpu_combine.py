@@ -105,6 +105,11 @@ def test_many_local_experts_per_token():
     run_combine(w, 4, 0, y_kind="ints", edit=edit)
 
 
+def test_more_than_eight_local_experts_per_row():
+    run_combine(W.DispatchWorkload("dense20", 91, 2, 40, 24, 100, 256, "bf16", "uniform"), 1, 1)
+    run_combine(W.DispatchWorkload("k64", 92, 4, 128, 64, 60, 128, "bf16", "uniform"), 2, 3, y_kind="ints")
+
+
 def test_full_width_rows():
     run_combine(W.DispatchWorkload("wide_bf16", 11, 8, 16, 2, 257, 7168, "bf16", "uniform"), 1, 3)
 

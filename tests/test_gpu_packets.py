@@ -164,6 +164,11 @@ def test_full_width_rows_duplicates_and_padding():
     run_packets(W.DispatchWorkload("k24", 13, 16, 64, 24, 70, 256, "bf16", "uniform"), 2, 9, complete_too=True)
 
 
+def test_more_than_eight_local_experts_per_row():
+    run_packets(W.DispatchWorkload("dense20", 91, 2, 40, 24, 100, 256, "bf16", "uniform"), 1, 1, complete_too=True)
+    run_packets(W.DispatchWorkload("k64", 92, 4, 128, 64, 60, 128, "bf16", "uniform"), 2, 3)
+
+
 def test_c1_full_size():
     run_packets(W.C1, W.BASE_SEED, 0, lazy=True, check_senders=(7, 63))
 

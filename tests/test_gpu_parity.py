@@ -380,6 +380,22 @@ def test_duplicate_ids_and_padding_inside_tokens():
         ctx.close()
 
 
+def test_more_than_eight_local_experts_per_row():
+    # 2 ranks x 20 experts, 24 ids per token: a row goes to up to 20 experts of one rank, so the
+    # hit slots beyond the eight kept in registers are used; 64 ids per token is the maximum
+    run_dispatch(W.DispatchWorkload("dense20", 91, 2, 40, 24, 100, 256, "bf16", "uniform"), 1, 1, also_full=True)
+    run_dispatch(W.DispatchWorkload("k64", 92, 4, 128, 64, 60, 128, "bf16", "uniform"), 2, 3)
+    run_dispatch(W.DispatchWorkload("k64_fp8", 93, 4, 128, 64, 40, 512, "fp8", "uniform"), 3, 0)
+
+
+def test_more_rows_than_one_launch_has_workgroup_rows():
+    # 20000 tokens per rank, narrow rows: more than 32768 received rows (the row movers' grids
+    # stop there and stride) and 79 token blocks in the plan
+    w = W.DispatchWorkload("long", 94, 4, 8, 2, 20000, 64, "bf16", "uniform")
+    gu = run_dispatch(w, 1, 2, tier2=False)
+    assert int(gu.stats["n_recv_rows"]) > 32768
+
+
 def test_invalid_expert_ids_set_the_error_flag():
     w = _small()
     tk = W.topk_ids(w, 1, 0)
