@@ -181,14 +181,16 @@ __global__ __launch_bounds__(1024) void k_relay_copy(
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
     const int lane = threadIdx.x & 63;
     for (uint32_t i = blockIdx.y; i < n_rows; i += gridDim.y) {
+        // the payload's address depends on the row alone: requested first, the group lookups
+        // (two dependent round trips) are in flight beside it
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (c < n_chunks) v = mw_ld16((const u32x4 *)src.rows + (size_t)i * n_chunks + c);
+        const int32_t st = src.row_src_token[i];
         const int32_t g = group_of_row[i];
         if (g < 0 || (uint32_t)g >= n_desc) continue;        // (stale or never written)
         const uint32_t off = i - src.desc[g].row_offset;
         if (off >= src.desc[g].row_count) continue;          // behind its group's end: in no valid group
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (c < n_chunks) v = mw_ld16((const u32x4 *)src.rows + (size_t)i * n_chunks + c);
         const uint32_t p = (lane < n_hops) ? child_pos[(size_t)g * MW_MAX_HOPS + lane] : kNoChild;
-        const int32_t st = src.row_src_token[i];
         int32_t tk = 0;
         if ((int)threadIdx.x < K && blockIdx.x == 0) tk = src.row_topk[(size_t)i * K + threadIdx.x];
         uint64_t hops = __ballot(p != kNoChild);              // the same in every wave
