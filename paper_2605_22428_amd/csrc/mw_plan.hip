@@ -201,23 +201,33 @@ __global__ __launch_bounds__(kBlock) void k_groups(const uint64_t *__restrict__ 
                                                    mw_send_stats *__restrict__ stats)
 {
     __shared__ int32_t tok[kBlock];
+    __shared__ unsigned long long tokc[kBlock];     // the token's counters, so they are not fetched again
     __shared__ uint32_t scratch[17];
     const int tid = threadIdx.x;
     const uint32_t N = min(pstate[kPsKept], (uint32_t)T), n_empty = (uint32_t)T - N;
     const uint32_t i0 = blockIdx.x * kBlock;
 
     // every workgroup walks all tokens' counters (coalesced): which of them land in its rows,
-    // how many groups start before its first row, how many groups there are
+    // how many groups start before its first row, how many groups there are.  Sixteen counters
+    // per lane are requested before the first is looked at: one memory round trip per 4096 tokens.
     uint32_t starts_before = 0, starts_total = 0;
-#pragma unroll 4
-    for (int t = tid; t < T; t += kBlock) {
-        const unsigned long long c = cnt[t];
-        if ((c >> 42) == 0) continue;                         // empty bitmap
-        const uint32_t p = (uint32_t)(c & kField) - n_empty;  // packed row of token t
-        const uint32_t st = ((c >> 21) & kField) == 0 ? 1u : 0u;
-        starts_total += st;
-        starts_before += (st && p < i0) ? 1u : 0u;
-        if (p - i0 < (uint32_t)kBlock && p < N) tok[p - i0] = t;
+    for (int t0 = 0; t0 < T; t0 += 16 * kBlock) {
+        unsigned long long cc[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int t = t0 + u * kBlock + tid;
+            cc[u] = t < T ? cnt[t] : 0ull;
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const unsigned long long c = cc[u];
+            if ((c >> 42) == 0) continue;                         // empty bitmap (or past the end)
+            const uint32_t p = (uint32_t)(c & kField) - n_empty;  // packed row of the token
+            const uint32_t st = ((c >> 21) & kField) == 0 ? 1u : 0u;
+            starts_total += st;
+            starts_before += (st && p < i0) ? 1u : 0u;
+            if (p - i0 < (uint32_t)kBlock && p < N) { tok[p - i0] = t0 + u * kBlock + tid; tokc[p - i0] = c; }
+        }
     }
     uint32_t g_base, G;
     mw_block_exscan(starts_before, scratch, &g_base);
@@ -233,7 +243,7 @@ __global__ __launch_bounds__(kBlock) void k_groups(const uint64_t *__restrict__ 
     if (i < N) {
         t = tok[tid];
         perm[i] = t;
-        c = cnt[t];
+        c = tokc[tid];
         st = ((c >> 21) & kField) == 0 ? 1u : 0u;
     }
     uint32_t local_total;
