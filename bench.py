@@ -7,7 +7,7 @@ dispatch (64 simulated ranks, 256 experts, top-8 with group-limited routing, 409
 7168 bf16 on this rank; 64 peer receive regions).  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c0|c1|c2|c3|c4]
-                  [--schedule aligned|free|single] [--no-cpu-baseline]
+                  [--schedule aligned|pipelined|free|single] [--no-cpu-baseline]
 
 The other workloads (tiny, fp8, 256-rank Zipf, AllGather) are parity-test configurations;
 they can be timed with the same harness for the per-configuration table in the design doc.
@@ -61,7 +61,7 @@ def copy_ceiling(torch, B, n_bytes, dev):
 def traffic_from_profile(kernel: str, workload: str):
     """HBM bytes per launch from the committed rocprofv3 counter summary (FETCH_SIZE and
     WRITE_SIZE runs of this same command, scaled by what the plain copy kernel reads)."""
-    path = os.path.join(ROOT, "profiles", "%s_%s_hbm_traffic.md" % (kernel, workload))
+    path = os.path.join(ROOT, "profiles", "bench_%s_hbm_traffic.md" % workload)
     if os.path.exists(path):
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch %s:" % kernel):
@@ -105,6 +105,7 @@ def bench_dispatch(args, name: str) -> dict:
     # ---------------------------------------------------------------- set-up (untimed)
     t_setup = time.time()
     ctx = B.Context(R, w.n_experts, K, my_rank, w.hidden, fmt, T, R * T, e2r, device=dev, max_hops=16)
+    ctx_b = B.Context(R, w.n_experts, K, my_rank, w.hidden, fmt, T, R * T, e2r, device=dev)   # second receive index
     topks = W.topk_ids_many(w, seed, range(R))
     x_me, s_me = W.payload_rows(w, seed, my_rank)
     topk_d = up(topks[my_rank])
@@ -187,8 +188,25 @@ def bench_dispatch(args, name: str) -> dict:
     #  "free"    no wait: the two streams drift; when packer and expander overlap, an expander
     #            launch takes longer by about the packer's bytes.
     #  "single"  everything on one stream.
+    #  "pipelined"  as "aligned", but the receive side is one launch per step
+    #            (mw_unpack_expand_index_next): the expander of this batch with the index of the
+    #            next batch riding along, on two contexts used alternately.  The latency-bound index
+    #            no longer stands in front of its expander.  Every step still does one plan, one
+    #            pack, one index and one expand; the first batch's index is built before the timed
+    #            region (in steady state the step before builds it), the last step builds one that
+    #            is not used.  The index is then hidden behind the expander, but the packer no longer
+    #            has the index to hide behind: the step takes as long as in "aligned".
     ev_unpack_done = [torch.cuda.Event() for _ in range(2)]
     state = {"n": 0}
+    rctx = [ctx, ctx_b]
+    pipe = {"n": 0}
+
+    def prime_pipeline():
+        """Index of the batch the next pipelined step expands (the other schedules use the same workspace)."""
+        n = pipe["n"]
+        s = sets[n % N_SETS]
+        with torch.cuda.stream(s_recv):
+            rctx[n % 2].mw_unpack_index(s["table"], R, cap, s["recv"].expert_offsets, s["recv"].stats)
 
     def step(i: int, schedule: str = args.schedule):
         s = sets[i % N_SETS]
@@ -200,6 +218,21 @@ def bench_dispatch(args, name: str) -> dict:
                 send_side(s)
             with torch.cuda.stream(s_recv):
                 recv_side(s)
+        elif schedule == "pipelined":
+            n = pipe["n"]
+            pipe["n"] = n + 1
+            s, s_next = sets[n % N_SETS], sets[(n + 1) % N_SETS]
+            sd, rv, rn = s["send"], s["recv"], s_next["recv"]
+            with torch.cuda.stream(s_send):
+                ctx.mw_plan(topk_d, sd.mask, sd.perm, sd.desc, sd.stats)
+                if n > 0:
+                    s_send.wait_event(ev_unpack_done[(n - 1) % 2])
+                ctx.mw_pack(s["x"], s["sc"], topk_d, sd.perm, sd.stats, sd.packed, sd.row_src_token, sd.row_topk)
+            with torch.cuda.stream(s_recv):
+                rctx[n % 2].mw_unpack_expand_index_next(R, rv.out_rows, rv.out_scales, cap, rv.out_src_peer,
+                                                        rv.out_src_token, rctx[(n + 1) % 2], s_next["table"], R, cap,
+                                                        rn.expert_offsets, rn.stats)
+                ev_unpack_done[n % 2].record(s_recv)
         else:
             n = state["n"]
             state["n"] = n + 1
@@ -214,14 +247,18 @@ def bench_dispatch(args, name: str) -> dict:
                 ev_unpack_done[n % 2].record(s_recv)
 
     def set_expand_events(a, b):
-        ctx.mw_ctx_set_timing_events(B.MW_KERNEL_EXPAND, a, b)
+        for c in rctx:
+            c.mw_ctx_set_timing_events(B.MW_KERNEL_EXPAND, a, b)
 
     # ---------------------------------------------------------------- warm-up, then the timed region
+    if args.schedule == "pipelined":
+        prime_pipeline()
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
     st = ctx.mw_get_send_stats(sets[0]["send"].stats)
     rs0 = ctx.mw_get_recv_stats(sets[0]["recv"].stats)
+    ctx_b.mw_get_recv_stats(sets[0]["recv"].stats)      # (both contexts size their launches from the rows seen)
     N, Q = int(st["n_rows"]), int(rs0["n_out_rows"])
     assert int(st["error_flags"]) == 0 and int(rs0["error_flags"]) == 0 and int(rs0["n_recv_rows"]) == M
 
@@ -245,9 +282,11 @@ def bench_dispatch(args, name: str) -> dict:
     expand_avg_ms = sum(expand_ms) / len(expand_ms)
 
     other = {}
-    for sched in ("single", "free", "aligned"):      # the other schedules, for reference
+    for sched in ("single", "free", "aligned", "pipelined"):      # the other schedules, for reference
         if sched == args.schedule:
             continue
+        if sched == "pipelined":
+            prime_pipeline()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(args.steps):
@@ -458,6 +497,9 @@ def bench_dispatch(args, name: str) -> dict:
     pu_us = kern_us["pack"] + kern_us["recv_index"] + kern_us["expand"]
     saved = 1.0 - int(st["multicast_bytes"]) / int(st["unicast_bytes"])
 
+    # the launch that moves the receive side's bytes: the expander, in the pipelined schedule with
+    # the next batch's index riding along (same bytes; the index's few MB are not counted)
+    dominant = "k_expand_index_next" if args.schedule == "pipelined" else "k_expand"
     result = {
         "metric": METRIC,
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -476,9 +518,9 @@ def bench_dispatch(args, name: str) -> dict:
                              "GBps": round((pack_bytes + unpack_bytes) / pu_us / 1e3, 1),
                              "pct_of_hbm_peak": round(100.0 * (pack_bytes + unpack_bytes) / pu_us / 1e3 / HBM_PEAK_GBPS, 2)},
         "copy_ceiling": ceiling,
-        "roofline": {"kernel": "k_expand", "bound": "hbm", "achieved": round(achieved, 1),
+        "roofline": {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": traffic_from_profile("k_expand", name.upper()), "bytes_per_launch": expand_bytes,
+                     "traffic": traffic_from_profile(dominant, name.upper()), "bytes_per_launch": expand_bytes,
                      "avg_launch_ms": round(expand_avg_ms, 4), "min_launch_ms": round(expand_ms[0], 4),
                      "launches_timed": len(expand_ms)},
     }
@@ -624,7 +666,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", choices=["c0", "c1", "c2", "c3", "c4"], default="c1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--schedule", choices=["aligned", "free", "single"], default="aligned",
+    ap.add_argument("--schedule", choices=["aligned", "pipelined", "free", "single"], default="aligned",
                     help="how the send side and the receive side of a step are issued (see step())")
     ap.add_argument("--seed", type=int, default=None)
     args = ap.parse_args()

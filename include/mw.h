@@ -274,6 +274,26 @@ MW_API int32_t mw_unpack_expand(mw_ctx *ctx, int32_t n_peers, void *out_rows_dev
                          int64_t out_capacity_rows, int32_t *out_src_peer_dev, int32_t *out_src_token_dev, void *stream);
 
 /*
+ * mw_unpack_expand_index_next: for a steady stream of batches.  One launch does what
+ * mw_unpack_expand(ctx, ...) does for the batch whose index `ctx` holds, and what
+ * mw_unpack_index(next_ctx, next_peers_dev, ...) does for the NEXT batch: the index, a
+ * latency-bound kernel that moves almost nothing, rides along with the bandwidth-bound
+ * expander of the batch before it instead of standing in front of its own.  The call after
+ * this one on the same stream (with the roles of the two contexts exchanged) finds the next
+ * batch's index complete: launches on a stream are ordered.  Outputs of both halves are
+ * exactly those of the separate calls.  `ctx` and `next_ctx` must be different contexts on
+ * the same device (each holds one index in its workspace); arguments as for the two calls.
+ * MW_ERR_UNSUPPORTED if the next context's index needs more than 5 KiB of LDS per workgroup
+ * (max_tokens above about 8000 with several local experts): use the separate calls then.
+ */
+MW_API int32_t mw_unpack_expand_index_next(mw_ctx *ctx, int32_t n_peers, void *out_rows_dev, float *out_scales_dev,
+                                    int64_t out_capacity_rows, int32_t *out_src_peer_dev,
+                                    int32_t *out_src_token_dev, mw_ctx *next_ctx,
+                                    const mw_recv_peer *next_peers_dev, int32_t next_n_peers,
+                                    int64_t next_out_capacity_rows, int64_t *next_expert_offsets_dev,
+                                    mw_recv_stats *next_recv_stats_dev, void *stream);
+
+/*
  * mw_combine_gather: the way back (Section 2.1, combine-style AlltoAll).  The paper notes that
  * the combine phase reduces and cannot use multicast (Section 2.3.2); what a rank can do
  * locally is the mirror image of "one copy per destination set": a token that reached h of

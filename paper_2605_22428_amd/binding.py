@@ -25,7 +25,7 @@ MW_FLAG_BAD_SRC_TOKEN, MW_FLAG_BAD_DESC, MW_FLAG_RECV_CAPACITY, MW_FLAG_DUP_SRC_
 EXPORTS = ["mw_workspace_bytes", "mw_ctx_create", "mw_ctx_destroy", "mw_plan", "mw_pack", "mw_plan_pack", "mw_pack_quantize",
            "mw_packet_header_bytes", "mw_pack_packets", "mw_unpack_packets",
            "mw_plan_allgather", "mw_pack_allgather", "mw_unpack", "mw_unpack_index", "mw_unpack_expand",
-           "mw_unpack_allgather", "mw_combine_gather",
+           "mw_unpack_allgather", "mw_combine_gather", "mw_unpack_expand_index_next",
            "mw_sim_deliver", "mw_copy_bytes", "mw_get_send_stats", "mw_get_recv_stats",
            "mw_set_forwarding", "mw_relay", "mw_relay_packets", "mw_get_relay_stats",
            "mw_allgather_split_point", "mw_plan_allgather_split", "mw_unpack_allgather_split",
@@ -247,6 +247,17 @@ class Context:
         _check(load().mw_unpack_expand(self._h, C.c_int32(n_peers), _ptr(out_rows), _ptr(out_scales),
                                        C.c_int64(out_capacity_rows), _ptr(out_src_peer), _ptr(out_src_token),
                                        _stream()), "mw_unpack_expand")
+
+    def mw_unpack_expand_index_next(self, n_peers: int, out_rows: torch.Tensor, out_scales: Optional[torch.Tensor],
+                                    out_capacity_rows: int, out_src_peer: torch.Tensor, out_src_token: torch.Tensor,
+                                    next_ctx: "Context", next_peers: torch.Tensor, next_n_peers: int,
+                                    next_out_capacity_rows: int, next_expert_offsets: torch.Tensor,
+                                    next_recv_stats: torch.Tensor):
+        _check(load().mw_unpack_expand_index_next(
+            self._h, C.c_int32(n_peers), _ptr(out_rows), _ptr(out_scales), C.c_int64(out_capacity_rows),
+            _ptr(out_src_peer), _ptr(out_src_token), next_ctx._h, _ptr(next_peers), C.c_int32(next_n_peers),
+            C.c_int64(next_out_capacity_rows), _ptr(next_expert_offsets), _ptr(next_recv_stats), _stream()),
+            "mw_unpack_expand_index_next")
 
     def mw_combine_gather(self, n_peers: int, y: torch.Tensor, out_capacity_rows: int, ret_rows: torch.Tensor,
                           ret_capacity_rows: int):

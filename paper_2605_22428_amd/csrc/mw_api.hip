@@ -379,6 +379,26 @@ MW_API int32_t mw_unpack_packets(mw_ctx *ctx, const mw_recv_packets *peers_dev, 
                                    out_src_token_dev, (hipStream_t)stream);
 }
 
+MW_API int32_t mw_unpack_expand_index_next(mw_ctx *ctx, int32_t n_peers, void *out_rows_dev, float *out_scales_dev,
+                                    int64_t out_capacity_rows, int32_t *out_src_peer_dev,
+                                    int32_t *out_src_token_dev, mw_ctx *next_ctx,
+                                    const mw_recv_peer *next_peers_dev, int32_t next_n_peers,
+                                    int64_t next_out_capacity_rows, int64_t *next_expert_offsets_dev,
+                                    mw_recv_stats *next_recv_stats_dev, void *stream)
+{
+    if (!ctx || !next_ctx || ctx == next_ctx || ctx->device != next_ctx->device) return MW_ERR_INVALID_ARG;
+    int32_t rc = check_unpack_expand(ctx, n_peers, out_rows_dev, out_scales_dev, out_capacity_rows, out_src_peer_dev,
+                                     out_src_token_dev);
+    if (rc == MW_OK)
+        rc = check_unpack_index(next_ctx, next_peers_dev, next_n_peers, next_out_capacity_rows, next_expert_offsets_dev,
+                                next_recv_stats_dev);
+    if (rc != MW_OK) return rc;
+    return mw_launch_unpack_expand_index_next(ctx, n_peers, out_rows_dev, out_scales_dev, out_capacity_rows,
+                                              out_src_peer_dev, out_src_token_dev, next_ctx, next_peers_dev, next_n_peers,
+                                              next_out_capacity_rows, next_expert_offsets_dev, next_recv_stats_dev,
+                                              (hipStream_t)stream);
+}
+
 MW_API int32_t mw_combine_gather(mw_ctx *ctx, int32_t n_peers, const void *y_dev, int64_t out_capacity_rows,
                           void *ret_rows_dev, int64_t ret_capacity_rows, void *stream)
 {

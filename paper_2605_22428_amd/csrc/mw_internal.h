@@ -194,6 +194,10 @@ int32_t mw_launch_pack_packets(mw_ctx *ctx, const void *x, const float *scales, 
                                void *packets, hipStream_t s);
 int32_t mw_launch_unpack_expand(mw_ctx *ctx, int32_t P, void *out_rows, float *out_scales, int64_t cap,
                                 int32_t *out_src_peer, int32_t *out_src_token, hipStream_t s);
+int32_t mw_launch_unpack_expand_index_next(mw_ctx *ctx, int32_t P, void *out_rows, float *out_scales, int64_t cap,
+                                           int32_t *out_src_peer, int32_t *out_src_token, mw_ctx *next,
+                                           const mw_recv_peer *next_peers, int32_t next_P, int64_t next_cap,
+                                           int64_t *next_expert_offsets, mw_recv_stats *next_stats, hipStream_t s);
 int32_t mw_launch_combine(mw_ctx *ctx, int32_t P, const void *y, int64_t cap, void *ret, int64_t ret_cap, hipStream_t s);
 int32_t mw_launch_plan_allgather(mw_ctx *ctx, int64_t shard_bytes, mw_group_desc *desc,
                                  mw_send_stats *stats, hipStream_t s);

@@ -85,14 +85,25 @@ __device__ __forceinline__ void mw_finish_counts(const uint32_t *cnt, const uint
 // kPackets: the peers' regions hold packets (mw_recv_packets): every row is its own group and
 // carries its bitmap, source token and expert ids in a header in front of it; `row_bytes` is
 // then the distance between packets and `header_bytes` the payload's offset inside one.
+// Everything the index of one batch needs (one kernel argument; the fused launch below carries
+// it beside the expander's arguments).
+struct mw_index_args {
+    const void *peers; int P; const int32_t *eslot;
+    int E, K, Kd, my_rank, L, Lc;
+    uint32_t max_tokens, wpl, cap_rows; uint64_t row_bytes; uint32_t header_bytes; int64_t out_cap;
+    uint32_t *cnt, *row_base, *addr_cnt; mw_row_rec *recs; mw_hit *hits; uint32_t *base;
+    int64_t *expert_offsets; mw_recv_stats *stats; uint32_t *flags;
+};
+
+// The work of workgroup `p` (peer p) of the index; any workgroup size that is a multiple of 64.
 template <bool kPackets>
-__global__ __launch_bounds__(kIndexBlock) void k_recv_index(
+__device__ __forceinline__ void recv_index_body(
     const void *__restrict__ peers_v, int P, const int32_t *__restrict__ eslot,
     int E, int K, int Kd, int my_rank, int L, int Lc,
     uint32_t max_tokens, uint32_t wpl, uint32_t cap_rows, uint64_t row_bytes, uint32_t header_bytes, int64_t out_cap,
     uint32_t *cnt, uint32_t *row_base, uint32_t *addr_cnt, mw_row_rec *__restrict__ recs,
     mw_hit *__restrict__ hits, uint32_t *__restrict__ base, int64_t *__restrict__ expert_offsets,
-    mw_recv_stats *__restrict__ stats, uint32_t *flags)
+    mw_recv_stats *__restrict__ stats, uint32_t *flags, const int p)
 {
     extern __shared__ uint32_t lds[];
     uint32_t *addr = lds;                       // [wpl]      bit i: row i's group names this rank
@@ -101,7 +112,7 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
     uint32_t *scratch = pre + (size_t)Lc * wpl; // [17] scan scratch, [17] "I am last", [18] addressed rows,
                                                 // [19] rows of the peers before this one
 
-    const int tid = threadIdx.x, nthr = blockDim.x, p = blockIdx.x;
+    const int tid = threadIdx.x, nthr = blockDim.x;
     mw_recv_peer pr;
     if constexpr (kPackets) {
         const mw_recv_packets q = ((const mw_recv_packets *)peers_v)[p];
@@ -415,29 +426,44 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(
                      scratch);
 }
 
+template <bool kPackets>
+__device__ __forceinline__ void recv_index_of(const mw_index_args &a, int p)
+{
+    recv_index_body<kPackets>(a.peers, a.P, a.eslot, a.E, a.K, a.Kd, a.my_rank, a.L, a.Lc, a.max_tokens, a.wpl,
+                              a.cap_rows, a.row_bytes, a.header_bytes, a.out_cap, a.cnt, a.row_base, a.addr_cnt, a.recs,
+                              a.hits, a.base, a.expert_offsets, a.stats, a.flags, p);
+}
+
+template <bool kPackets>
+__global__ __launch_bounds__(kIndexBlock) void k_recv_index(const mw_index_args a)
+{
+    recv_index_of<kPackets>(a, blockIdx.x);
+}
+
 // blockIdx.x selects a segment of blockDim.x chunks of the row; blockIdx.y walks rows.  All
 // index reads are wave-uniform (scalar loads).  The dependent chain in front of a row's
 // payload is what a one-shot workgroup cannot hide, so it is kept to two steps: the row
 // record and the row count are fetched together, then the payload load and the lookup of
 // the first output position are issued together; the position is there long before the
 // payload is.
-__global__ __launch_bounds__(1024) void k_expand(
+// g_first / g_stride: the first row of this workgroup and the distance to its next one.
+__device__ __forceinline__ void expand_body(
     const mw_row_rec *__restrict__ recs, const mw_hit *__restrict__ hits, const uint32_t *__restrict__ base,
     const uint32_t *__restrict__ row_base, int P, int Kd, int xc, int sc,
     u32x4 *__restrict__ out_rows, u32x4 *__restrict__ out_scales, uint32_t cap,
-    int32_t *__restrict__ out_src_peer, int32_t *__restrict__ out_src_token)
+    int32_t *__restrict__ out_src_peer, int32_t *__restrict__ out_src_token, uint32_t g_first, uint32_t g_stride)
 {
     // Every kernel argument is fetched in the first batch, not after the first branch.
     // Pointers are pinned through a copy of their low half, so the originals keep their
     // address space.
-    uint32_t gdim = gridDim.y, bdim = blockDim.x;
+    uint32_t gdim = g_stride, bdim = blockDim.x;
     MW_PIN_S(gdim); MW_PIN_S(bdim); MW_PIN_S(Kd); MW_PIN_S(xc); MW_PIN_S(sc); MW_PIN_S(cap);
     MW_PIN_PTR(hits); MW_PIN_PTR(out_rows); MW_PIN_PTR(out_scales); MW_PIN_PTR(out_src_peer);
     MW_PIN_PTR(out_src_token);
     const int n = xc + sc;
     const int c = blockIdx.x * bdim + threadIdx.x;
-    uint32_t g = blockIdx.y;
-    // gridDim.y <= max_recv_rows, so the first record read is always inside the workspace
+    uint32_t g = g_first;
+    // g_first < max_recv_rows, so the first record read is always inside the workspace
     const u32x4 *rp = (const u32x4 *)(recs + g);
     u32x4 r0 = rp[0], r1 = rp[1];
     uint32_t m_total = row_base[P];
@@ -466,6 +492,39 @@ __global__ __launch_bounds__(1024) void k_expand(
         g += gdim;
         if (g < m_total) { rp = (const u32x4 *)(recs + g); r0 = rp[0]; r1 = rp[1]; }
     }
+}
+
+__global__ __launch_bounds__(1024) void k_expand(
+    const mw_row_rec *__restrict__ recs, const mw_hit *__restrict__ hits, const uint32_t *__restrict__ base,
+    const uint32_t *__restrict__ row_base, int P, int Kd, int xc, int sc,
+    u32x4 *__restrict__ out_rows, u32x4 *__restrict__ out_scales, uint32_t cap,
+    int32_t *__restrict__ out_src_peer, int32_t *__restrict__ out_src_token)
+{
+    expand_body(recs, hits, base, row_base, P, Kd, xc, sc, out_rows, out_scales, cap, out_src_peer, out_src_token,
+                blockIdx.y, gridDim.y);
+}
+
+// One launch for a steady stream of batches: the expander of the current batch and, in the
+// first `next.P` workgroup rows of the grid, the index of the NEXT batch, written to another
+// context's workspace.  The index is a chain of memory round trips that moves almost nothing;
+// run as its own launch in front of its expander it costs 14-16 us of an otherwise
+// bandwidth-bound stream, and run on a second stream it costs a cross-stream wait of 7-10 us.
+// Here it rides along: its workgroups are dispatched first and finish long before the
+// expander's do, and the launch that expands the next batch is ordered after this one by the
+// stream, so no wait, flag or fence is needed.
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_expand_index_next(
+    const mw_row_rec *__restrict__ recs, const mw_hit *__restrict__ hits, const uint32_t *__restrict__ base,
+    const uint32_t *__restrict__ row_base, int P, int Kd, int xc, int sc,
+    u32x4 *__restrict__ out_rows, u32x4 *__restrict__ out_scales, uint32_t cap,
+    int32_t *__restrict__ out_src_peer, int32_t *__restrict__ out_src_token, const mw_index_args next)
+{
+    const uint32_t n_index = (uint32_t)next.P;
+    if (blockIdx.y < n_index) {
+        if (blockIdx.x == 0) recv_index_of<false>(next, (int)blockIdx.y);
+        return;
+    }
+    expand_body(recs, hits, base, row_base, P, Kd, xc, sc, out_rows, out_scales, cap, out_src_peer, out_src_token,
+                blockIdx.y - n_index, gridDim.y - n_index);
 }
 
 // The way back (Section 2.1, combine-style AlltoAll; Section 2.3.2: the combine phase reduces
@@ -541,36 +600,56 @@ __global__ __launch_bounds__(1024) void k_combine(
 
 }  // namespace
 
+// Index arguments of `ctx` for a launch whose workgroups may use `lds_budget_words` words of LDS
+// each: the addressed-rows bitmap plus two arrays per expert of a chunk (experts beyond the
+// budget are handled in further passes).  Returns false if not even one expert fits.
+static bool make_index_args(mw_ctx *ctx, const void *peers, bool packets, int32_t P, int64_t cap,
+                            int64_t *expert_offsets, mw_recv_stats *stats, uint32_t lds_budget_words,
+                            mw_index_args *a, size_t *lds_bytes)
+{
+    const mw_config &c = ctx->cfg;
+    const int L = ctx->n_local;
+    const uint32_t wpl = ((uint32_t)c.max_tokens + 31u) / 32u;
+    if (lds_budget_words < 3 * wpl + 64) return false;
+    int Lc = (int)((lds_budget_words - 64 - wpl) / (2 * wpl));
+    if (Lc < 1) return false;
+    if (Lc > L) Lc = L > 0 ? L : 1;
+    *lds_bytes = ((size_t)wpl + 2 * (size_t)Lc * wpl + 64) * sizeof(uint32_t);
+    const uint32_t hb = packets ? (uint32_t)mw_packet_header_bytes_of(c.top_k) : 0u;
+    *a = mw_index_args{peers, P, ctx->d_eslot, c.n_experts, c.top_k, ctx->hit_slots, c.my_rank, L, Lc,
+                       (uint32_t)c.max_tokens, wpl, (uint32_t)c.max_recv_rows, (uint64_t)(hb + ctx->row_bytes), hb, cap,
+                       ctx->d_cnt, ctx->d_row_base, ctx->d_addr_cnt, ctx->d_recs, ctx->d_hits, ctx->d_base,
+                       expert_offsets, stats, ctx->d_flags};
+    return true;
+}
+
 int32_t mw_launch_unpack_index(mw_ctx *ctx, const void *peers, bool packets, int32_t P, int64_t cap,
                                int64_t *expert_offsets, mw_recv_stats *stats, hipStream_t s)
 {
-    const mw_config &c = ctx->cfg;
-    const int L = ctx->n_local, Kd = ctx->hit_slots;
-    const uint32_t wpl = ((uint32_t)c.max_tokens + 31u) / 32u;
-    // LDS budget of the index kernel: addressed bitmap + 2 arrays per expert of the chunk
-    const uint32_t budget_words = 12288 - 64;
-    int Lc = (int)((budget_words - wpl) / (2 * wpl));
-    if (Lc < 1) return MW_ERR_UNSUPPORTED;
-    if (Lc > L) Lc = L > 0 ? L : 1;
-    const size_t lds_index = ((size_t)wpl + 2 * (size_t)Lc * wpl + 64) * sizeof(uint32_t);
+    mw_index_args a;
+    size_t lds_index;
+    if (!make_index_args(ctx, peers, packets, P, cap, expert_offsets, stats, 12288, &a, &lds_index))
+        return MW_ERR_UNSUPPORTED;
     {
         mw_timed tm(ctx, MW_KERNEL_RECV_INDEX, s);
-        const uint32_t hb = (uint32_t)mw_packet_header_bytes_of(c.top_k);
-        if (packets)
-            hipLaunchKernelGGL(k_recv_index<true>, dim3(P), dim3(kIndexBlock), lds_index, s, peers, P, ctx->d_eslot,
-                               c.n_experts, c.top_k, Kd, c.my_rank, L, Lc, (uint32_t)c.max_tokens,
-                               wpl, (uint32_t)c.max_recv_rows, (uint64_t)(hb + ctx->row_bytes), hb, cap, ctx->d_cnt,
-                               ctx->d_row_base, ctx->d_addr_cnt, ctx->d_recs, ctx->d_hits, ctx->d_base,
-                               expert_offsets, stats, ctx->d_flags);
-        else
-            hipLaunchKernelGGL(k_recv_index<false>, dim3(P), dim3(kIndexBlock), lds_index, s, peers, P, ctx->d_eslot,
-                               c.n_experts, c.top_k, Kd, c.my_rank, L, Lc, (uint32_t)c.max_tokens,
-                               wpl, (uint32_t)c.max_recv_rows, (uint64_t)ctx->row_bytes, 0u, cap, ctx->d_cnt,
-                               ctx->d_row_base, ctx->d_addr_cnt, ctx->d_recs, ctx->d_hits, ctx->d_base,
-                               expert_offsets, stats, ctx->d_flags);
+        if (packets) hipLaunchKernelGGL(k_recv_index<true>, dim3(P), dim3(kIndexBlock), lds_index, s, a);
+        else hipLaunchKernelGGL(k_recv_index<false>, dim3(P), dim3(kIndexBlock), lds_index, s, a);
     }
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;
+}
+
+// Grid rows of the expander: about as many as the peers held last time (if the caller has
+// asked for the statistics), not the capacity -- workgroups are dispatched at a finite rate,
+// empty ones included.  More rows than that are reached by striding.
+static uint32_t expand_grid_rows(const mw_ctx *ctx)
+{
+    int64_t rows = ctx->cfg.max_recv_rows;
+    if (ctx->recv_rows_hint > 0) {
+        const int64_t want = ctx->recv_rows_hint + ctx->recv_rows_hint / 64 + 64;
+        if (want < rows) rows = want;
+    }
+    return (uint32_t)(rows < kRowGridMax ? rows : kRowGridMax);
 }
 
 int32_t mw_launch_unpack_expand(mw_ctx *ctx, int32_t P, void *out_rows, float *out_scales, int64_t cap,
@@ -580,19 +659,43 @@ int32_t mw_launch_unpack_expand(mw_ctx *ctx, int32_t P, void *out_rows, float *o
     if (c.max_recv_rows > 0) {
         const int xc = (int)(ctx->x_row_bytes / 16), sc = (int)(ctx->s_row_bytes / 16);
         const mw_row_shape shape = mw_row_shape_of(xc + sc);
-        // Workgroups are dispatched at a finite rate, empty ones included: the grid is sized for
-        // about as many rows as the peers held last time (if the caller has asked for the
-        // statistics), not for the capacity.  More rows than that are reached by striding.
-        int64_t rows = c.max_recv_rows;
-        if (ctx->recv_rows_hint > 0) {
-            const int64_t want = ctx->recv_rows_hint + ctx->recv_rows_hint / 64 + 64;
-            if (want < rows) rows = want;
-        }
-        const uint32_t gy = (uint32_t)(rows < kRowGridMax ? rows : kRowGridMax);
+        const uint32_t gy = expand_grid_rows(ctx);
         mw_timed tm(ctx, MW_KERNEL_EXPAND, s);
         hipLaunchKernelGGL(k_expand, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, ctx->d_recs, ctx->d_hits, ctx->d_base,
                            ctx->d_row_base, P, ctx->hit_slots, xc, sc, (u32x4 *)out_rows, (u32x4 *)out_scales,
                            (uint32_t)(cap < 0x7fffffffLL ? cap : 0x7fffffffLL), out_src_peer, out_src_token);
+    }
+    MW_HIP_CHECK(hipGetLastError());
+    return MW_OK;
+}
+
+int32_t mw_launch_unpack_expand_index_next(mw_ctx *ctx, int32_t P, void *out_rows, float *out_scales, int64_t cap,
+                                           int32_t *out_src_peer, int32_t *out_src_token, mw_ctx *next,
+                                           const mw_recv_peer *next_peers, int32_t next_P, int64_t next_cap,
+                                           int64_t *next_expert_offsets, mw_recv_stats *next_stats, hipStream_t s)
+{
+    const mw_config &c = ctx->cfg;
+    if (c.max_recv_rows < 1) return MW_ERR_UNSUPPORTED;       // nothing to ride on
+    // Every workgroup of the launch reserves the index's LDS, the expander's included: at most
+    // 5 KiB, so that a CU's 160 KiB still hold a full set of 32 single-wave expander workgroups.
+    mw_index_args a;
+    size_t lds_index;
+    if (!make_index_args(next, next_peers, false, next_P, next_cap, next_expert_offsets, next_stats, 1280, &a,
+                         &lds_index))
+        return MW_ERR_UNSUPPORTED;
+    const int xc = (int)(ctx->x_row_bytes / 16), sc = (int)(ctx->s_row_bytes / 16);
+    mw_row_shape shape = mw_row_shape_of(xc + sc);
+    // Rows of whole cache lines: two-wave workgroups here.  The expander runs as fast with them
+    // as with single waves (138.8 against 139.4 us at 30590 rows of 14336 bytes), and the riding
+    // index gets two waves per peer: with one it outlasts the expander (142 against 139 us).
+    if (shape.bs == 64 && (xc + sc) % 16 == 0) { shape.bs = 128; shape.nseg = (xc + sc) / 128 + ((xc + sc) % 128 ? 1 : 0); }
+    const uint32_t gy = expand_grid_rows(ctx);
+    {
+        mw_timed tm(ctx, MW_KERNEL_EXPAND, s);
+        hipLaunchKernelGGL(k_expand_index_next, dim3(shape.nseg, gy + (uint32_t)next_P), dim3(shape.bs), lds_index, s,
+                           ctx->d_recs, ctx->d_hits, ctx->d_base, ctx->d_row_base, P, ctx->hit_slots, xc, sc,
+                           (u32x4 *)out_rows, (u32x4 *)out_scales, (uint32_t)(cap < 0x7fffffffLL ? cap : 0x7fffffffLL),
+                           out_src_peer, out_src_token, a);
     }
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;

@@ -201,6 +201,64 @@ def test_unpack_in_two_calls_with_two_contexts_in_flight():
         b["ctx"].close()
 
 
+def test_index_of_the_next_batch_rides_with_the_expander():
+    """A stream of batches through mw_unpack_expand_index_next on two contexts: every batch's
+    output must be what mw_unpack gives (bit-exact against the plain definition), whatever ran
+    beside its index."""
+    for w, my_rank in ((W.scaled(W.C1, n_tokens=150, hidden=512), 3),
+                       (W.scaled(W.C2, n_tokens=90, hidden=1024), 40),
+                       (W.scaled(W.C3, n_tokens=64, hidden=256), 200)):
+        _say("pipelined unpack", w.name)
+        e2r = W.expert_to_rank(w)
+        ctxs = [H.make_ctx(w, my_rank), H.make_ctx(w, my_rank)]
+        batches = []
+        for seed in (1, 2, 3, 4):
+            recs, toks = [], []
+            for p in range(w.n_ranks):
+                tk = W.topk_ids(w, seed, p)
+                if seed == 3:
+                    tk = tk.copy(); tk[::2] = -1                  # a much smaller batch in the middle
+                x, sc = W.payload_rows(w, seed, p)
+                g = H.GpuSend(ctxs[0], tk, x, sc)
+                recs.append(H.shrink(g.deliver(my_rank)))
+                toks.append((tk, x, sc))
+            cap = max(1, sum(r["n_rows"] for r in recs) * min(w.top_k, w.experts_per_rank))
+            batches.append(dict(recs=recs, toks=toks, cap=cap, table=B.peers_table(recs, H.DEV)))
+        bufs = [B.RecvBuffers(ctxs[i % 2], b["cap"]) for i, b in enumerate(batches)]
+        R = w.n_ranks
+        b0 = batches[0]
+        ctxs[0].mw_unpack_index(b0["table"], R, b0["cap"], bufs[0].expert_offsets, bufs[0].stats)
+        for i, b in enumerate(batches):
+            cur, buf = ctxs[i % 2], bufs[i]
+            if i + 1 < len(batches):
+                nb, nbuf = batches[i + 1], bufs[i + 1]
+                cur.mw_unpack_expand_index_next(R, buf.out_rows, buf.out_scales, b["cap"], buf.out_src_peer,
+                                                buf.out_src_token, ctxs[(i + 1) % 2], nb["table"], R, nb["cap"],
+                                                nbuf.expert_offsets, nbuf.stats)
+            else:
+                cur.mw_unpack_expand(R, buf.out_rows, buf.out_scales, b["cap"], buf.out_src_peer, buf.out_src_token)
+        torch.cuda.synchronize()
+        for i, b in enumerate(batches):
+            want = ref.dispatch_plain(b["toks"], e2r, my_rank, b["cap"])
+            st = ctxs[i % 2].mw_get_recv_stats(bufs[i].stats)
+            q = int(st["n_out_rows"])
+            assert int(st["error_flags"]) == 0 and q == len(want[2])
+            H.assert_same_bytes(H.host(bufs[i].expert_offsets), want[4], "batch %d expert_offsets" % i)
+            H.assert_same_bytes(H.host(bufs[i].out_src_peer)[:q], want[2], "batch %d out_src_peer" % i)
+            H.assert_same_bytes(H.host(bufs[i].out_src_token)[:q], want[3], "batch %d out_src_token" % i)
+            H.assert_same_bytes(H.host(bufs[i].out_rows)[:q], want[0], "batch %d out_rows" % i)
+            if want[1] is not None:
+                H.assert_same_bytes(H.host(bufs[i].out_scales)[:q], want[1], "batch %d out_scales" % i)
+        with pytest.raises(B.MwError) as ei:                      # one context cannot hold both indexes
+            ctxs[0].mw_unpack_expand_index_next(R, bufs[0].out_rows, bufs[0].out_scales, batches[0]["cap"],
+                                                bufs[0].out_src_peer, bufs[0].out_src_token, ctxs[0],
+                                                batches[1]["table"], R, batches[1]["cap"], bufs[1].expert_offsets,
+                                                bufs[1].stats)
+        assert ei.value.status == B.MW_ERR_INVALID_ARG
+        for c in ctxs:
+            c.close()
+
+
 def test_unpack_after_a_smaller_batch_strides_over_the_rows():
     """The expander's launch is sized from the row count seen at the last mw_get_recv_stats; a later,
     larger batch on the same context must still be expanded completely (and a smaller one too)."""
