@@ -502,9 +502,13 @@ int32_t mw_launch_plan(mw_ctx *ctx, const int32_t *topk, int32_t T, uint64_t *ma
     unsigned long long *cnt_o = (unsigned long long *)ctx->d_plan_cnt[oth];
     const int tb = (T + kBlock - 1) / kBlock;
     if (T > 0) {
-        // split the predecessor walk into slices so that about 4 workgroups land on every CU;
-        // a slice's bitmaps must fit in LDS
-        int ns = (4 * ctx->n_cu + tb - 1) / tb;
+        // split the predecessor walk into slices so that about 2 workgroups land on every CU when
+        // a compare is one word (4 when it is a key and a flag: more compare work per pair); a
+        // slice's bitmaps must fit in LDS.  Fewer, longer workgroups mean fewer atomics and less
+        // disturbance of a bandwidth-bound kernel running beside the plan (the expander of the
+        // batch before: 88 -> 85 us per launch with fp8 rows), at the same latency.
+        const int per_cu = ctx->mask_words == 1 ? 2 : 4;
+        int ns = (per_cu * ctx->n_cu + tb - 1) / tb;
         if (ns < 1) ns = 1;
         int slice = (T + ns - 1) / ns;
         if (slice < 64) slice = 64;
