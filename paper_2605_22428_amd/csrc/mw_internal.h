@@ -30,18 +30,24 @@ struct mw_row_rec {
 
 // Launch shape of the row movers: one 16-byte chunk per lane, grid x = segment of `bs` chunks
 // of a row, grid y = row, so workgroups are dispatched in address order along a row and then
-// row by row.  Rows that are whole 128-byte cache lines (bf16 rows of 14336 bytes) are moved by
-// single-wave workgroups: measured on MI355X this follows the plain-copy ceiling most closely
-// (whole-row workgroups of 14 waves leave an eighth of a CU's wave slots empty; several chunks
-// per lane, or all rows' first segments first, are slower).  Rows that are not (fp8 rows of 7392
-// bytes start and end inside cache lines) keep one workgroup per row, so the lines two pieces
-// share are touched from one CU: with single-wave workgroups such rows were 40 % slower.
+// row by row.  Measured on MI355X (expander, 30590 received rows, GB/s of HBM traffic):
+//
+//   row bytes              2048  4096  7168  8192  10240  12288  14336  16384  24576
+//   single-wave segments   4413  4753  4848  4872   5879   6470   6485   6350   6427
+//   one workgroup per row  5824  6194  6158  6332   5976   6225   6073   6225   6448
+//
+// Rows of up to 10 KiB are moved by one workgroup each (a wave per KiB).  Longer rows that are
+// whole 128-byte cache lines (bf16 rows of 14336 bytes) are cut into single-wave workgroups:
+// whole-row workgroups of 14 waves leave an eighth of a CU's wave slots empty, and several
+// chunks per lane, or all rows' first segments first, are slower still.  Rows that are not whole
+// cache lines (fp8 rows of 7392 bytes start and end inside lines) are never cut into single
+// waves, so the lines two pieces share are touched from one CU: cut, such rows were 40 % slower.
 constexpr uint32_t kRowGridMax = 32768;       // grid y; further rows by striding
 struct mw_row_shape { int bs; int nseg; };
 static inline mw_row_shape mw_row_shape_of(int chunks)
 {
     if (chunks < 1) return mw_row_shape{64, 1};
-    if (chunks % 8 == 0) return mw_row_shape{64, (chunks + 63) / 64};
+    if (chunks % 8 == 0 && chunks > 640) return mw_row_shape{64, (chunks + 63) / 64};
     int b = (chunks + 63) / 64 * 64;
     if (b > 1024) b = 1024;
     return mw_row_shape{b, (chunks + b - 1) / b};
