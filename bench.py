@@ -10,7 +10,7 @@ dispatch (64 simulated ranks, 256 experts, top-8 with group-limited routing, 409
                   [--schedule aligned|pipelined|free|single] [--no-cpu-baseline]
 
 The other workloads (tiny, fp8, 256-rank Zipf, AllGather) are parity-test configurations;
-they can be timed with the same harness for the per-configuration table in the design doc.
+they can be timed with the same harness.
 """
 from __future__ import annotations
 
