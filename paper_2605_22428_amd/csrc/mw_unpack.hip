@@ -630,10 +630,13 @@ int32_t mw_launch_unpack_index(mw_ctx *ctx, const void *peers, bool packets, int
     size_t lds_index;
     if (!make_index_args(ctx, peers, packets, P, cap, expert_offsets, stats, 12288, &a, &lds_index))
         return MW_ERR_UNSUPPORTED;
+    // A peer seldom sends more than a fraction of its tokens to one rank: for small batches a
+    // quarter of the lanes do, with shorter barriers and scans (about a microsecond of 11).
+    const int ib = ctx->cfg.max_tokens <= 2048 ? 256 : kIndexBlock;
     {
         mw_timed tm(ctx, MW_KERNEL_RECV_INDEX, s);
-        if (packets) hipLaunchKernelGGL(k_recv_index<true>, dim3(P), dim3(kIndexBlock), lds_index, s, a);
-        else hipLaunchKernelGGL(k_recv_index<false>, dim3(P), dim3(kIndexBlock), lds_index, s, a);
+        if (packets) hipLaunchKernelGGL(k_recv_index<true>, dim3(P), dim3(ib), lds_index, s, a);
+        else hipLaunchKernelGGL(k_recv_index<false>, dim3(P), dim3(ib), lds_index, s, a);
     }
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;
