@@ -495,7 +495,8 @@ def bench_dispatch(args, name: str) -> dict:
     # ---------------------------------------------------------------- decode-sized send side (extra, untimed region)
     # The first 64 / 128 tokens of this rank's batch (the small batch sizes of the paper's
     # dispatch experiment, Section 6.3): mw_plan + mw_pack against the single launch of
-    # mw_plan_pack, back to back on one stream.
+    # mw_plan_pack, back to back on one stream; and mw_unpack of what the peers send for batches
+    # of that size.
     decode = {}
     sd0 = sets[0]["send"]
     for Td in (64, 128):
@@ -523,7 +524,48 @@ def bench_dispatch(args, name: str) -> dict:
             b.record()
             torch.cuda.synchronize()
             us[label] = round(10.0 * a.elapsed_time(b), 2)
+        # the receive side of the same batch size: every peer sends its first Td tokens
+        ctx_d = B.Context(R, w.n_experts, K, my_rank, w.hidden, fmt, Td, R * Td, e2r, device=dev)
+        sb_d = B.SendBuffers(ctx_d, Td)
+        x_d = torch.zeros((Td, w.hidden), dtype=xdt, device=dev)
+        s_d = torch.zeros((Td, w.hidden // 128), dtype=torch.float32, device=dev) if fp8 else None
+        o_d = dict(desc=torch.zeros((Td, B.DESC_BYTES), dtype=torch.uint8, device=dev),
+                   rows=torch.zeros((Td, rb), dtype=torch.uint8, device=dev),
+                   row_src_token=torch.zeros(Td, dtype=torch.int32, device=dev),
+                   row_topk=torch.zeros((Td, K), dtype=torch.int32, device=dev))
+        recs_d = []
+        for p in range(R):
+            tk_p = up(topks[p][:Td])
+            ctx_d.mw_plan_pack(tk_p, x_d, s_d, sb_d.mask, sb_d.perm, sb_d.desc, sb_d.stats, sb_d.packed,
+                               sb_d.row_src_token, sb_d.row_topk)
+            ctx_d.mw_sim_deliver(sb_d.desc, sb_d.stats, Td, sb_d.packed, sb_d.row_src_token, sb_d.row_topk, my_rank,
+                                 o_d["desc"], o_d["rows"], o_d["row_src_token"], o_d["row_topk"], counts)
+            g_d, n_d = (int(v) for v in counts.cpu().numpy())
+            recs_d.append(dict(desc=o_d["desc"][:max(g_d, 1)].clone(), rows=o_d["rows"][:max(n_d, 1)].clone(),
+                               row_src_token=o_d["row_src_token"][:max(n_d, 1)].clone(),
+                               row_topk=o_d["row_topk"][:max(n_d, 1)].clone(), n_desc=g_d, n_rows=n_d))
+        m_d = sum(r["n_rows"] for r in recs_d)
+        cap_d = max(1, m_d * min(K, L))
+        table_d, rv_d = B.peers_table(recs_d, dev), B.RecvBuffers(ctx_d, cap_d)
+
+        def unpack_d():
+            ctx_d.mw_unpack(table_d, R, rv_d.out_rows, rv_d.out_scales, cap_d, rv_d.out_src_peer, rv_d.out_src_token,
+                            rv_d.expert_offsets, rv_d.stats)
+
+        unpack_d()
+        ctx_d.mw_get_recv_stats(rv_d.stats)
+        for _ in range(10):
+            unpack_d()
+        (a, b), = new_events(torch, 1)
+        a.record()
+        for _ in range(100):
+            unpack_d()
+        b.record()
+        torch.cuda.synchronize()
+        us["unpack_us"] = round(10.0 * a.elapsed_time(b), 2)
+        us["rows_received"] = m_d
         decode["%d_tokens" % Td] = us
+        ctx_d.close()
 
     # ---------------------------------------------------------------- algorithmic bytes
     pack_bytes = 2 * N * rb + N * (4 + 4 * K) + N * 4 + N * 4 * K
@@ -564,7 +606,7 @@ def bench_dispatch(args, name: str) -> dict:
     if relay is not None:
         result["relay"] = relay
     if decode:
-        result["decode_send_side"] = decode
+        result["decode_sized_batches"] = decode
     if packets is not None:
         result["packets"] = packets
     if quant is not None:
