@@ -66,7 +66,9 @@ extern "C" {
 #define MW_FLAG_NO_LOCAL_EXPERT  0x04u  /* row's group names this rank but none of its experts is local */
 #define MW_FLAG_BAD_SRC_TOKEN    0x08u  /* row_src_token outside [0, max_tokens): row dropped */
 #define MW_FLAG_BAD_DESC         0x10u  /* descriptor row range outside the peer's rows: group dropped */
-#define MW_FLAG_RECV_CAPACITY    0x20u  /* peers hold more rows than max_recv_rows: surplus peers' rows dropped */
+#define MW_FLAG_RECV_CAPACITY    0x20u  /* peers hold more rows than max_recv_rows (or one more than max_tokens):
+                                           surplus rows dropped; a group cut by the limit is dropped whole and
+                                           sets MW_FLAG_BAD_DESC too */
 #define MW_FLAG_DUP_SRC_TOKEN    0x40u  /* two rows of one peer carry the same source token for one expert */
 #define MW_FLAG_BAD_RANK         0x80u  /* relay: a bitmap names a rank >= n_ranks: that bit is not forwarded */
 
