@@ -202,6 +202,24 @@ def test_relay_capacity_bad_descriptors_and_host_errors():
     good = np.delete(desc, [3, 4, 7])
     fwd, uni, rph = ref.relay_accounting(good, w.row_bytes, next_hop, 3)
     assert st["rows_per_hop"][:3].tolist() == rph.tolist() and int(st["unicast_bytes"]) == uni
+    # a bitmap that names a rank this configuration does not have: that bit is forwarded nowhere
+    # and flagged, everything else is as without it
+    desc = g.host_plan()[2].copy()
+    desc["mask"][5][1] |= np.uint64(1) << np.uint64(3)            # rank 67 of 64
+    desc["mask"][6][2] |= np.uint64(1)                            # rank 128
+    rec = dict(g.full_record(), desc=H.dev(desc.view(np.uint8).reshape(-1, B.DESC_BYTES)))
+    ch, st, _ = gpu_relay(ctx, rec, next_hop, 3, w.n_tokens)
+    assert int(st["error_flags"]) == B.MW_FLAG_BAD_RANK
+    parent = (g.host_plan()[2],) + g.host_pack()
+    for h in range(3):
+        want = ref.relay_child(*parent, next_hop, 3, h)
+        got = child_host(ch, st, h)
+        H.assert_same_bytes(got[0].view(np.uint8), want[0].view(np.uint8), "child %d desc without the bad bits" % h)
+        H.assert_same_bytes(got[1], want[1], "child %d rows" % h)
+    fwd, uni, rph = ref.relay_accounting(parent[0], w.row_bytes, next_hop, 3)
+    assert (int(st["forward_bytes"]), int(st["unicast_bytes"])) == (fwd, uni)
+    with pytest.raises(ref.OracleError):
+        ref.relay_child(desc, *parent[1:], next_hop, 3, 0)
     # the flag word is cleared again: a clean relay afterwards reports no error
     ch, st, _ = gpu_relay(ctx, g.full_record(), next_hop, 3, w.n_tokens)
     assert int(st["error_flags"]) == 0
