@@ -70,6 +70,9 @@ struct mw_ctx {
     uint32_t *d_plan_state[2];  // [MW_PLAN_STATE_WORDS] rows per destination, kept tokens, flags
     int plan_parity;            // which buffer pair the next mw_plan accumulates into
     int plan_T[2];              // tokens whose counters in that buffer still need clearing
+    uint64_t *d_sort_key;       // [max_tokens rounded up to 1024] sorted chunks of the large-batch plan (or null)
+    uint32_t *d_sort_sec;       // same count: second sort word
+    uint32_t *d_chunk_kept;     // [64] kept tokens per chunk
     uint32_t *d_flags;      // [4] 1: receive flags, 2: receive workgroups done
     uint32_t *d_base;       // [L][R] first output row of (local expert, peer)
     mw_row_rec *d_recs;     // [max_recv_rows]

@@ -482,6 +482,155 @@ __global__ __launch_bounds__(kBlock) void k_plan_pack(const int32_t *__restrict_
     }
 }
 
+// ---- ordering of large batches: sorted chunks, then ranks by binary search ------------------
+// The all-pairs walk of k_rank costs T^2 compares: 84 us at 16 k tokens, 220 us at 32 k, 700 us
+// at 64 k (one-word bitmaps; 120 / 335 / 1085 us with short keys).  This path: 52 / 72 / 102 us
+// (64 / 85 / 119 us).  For batches of kChunkFrom tokens or more whose bitmaps have a 64-bit order-preserving key (one word, or
+// short keys) the same counters are produced in T log T work:
+//   k_chunk_sort   one workgroup per chunk of 1024 tokens: bitmaps, keys, a bitonic sort of
+//                  (key, second word) pairs in LDS; the sorted chunk goes to the workspace.
+//   k_merge_rank   workgroup (c, part), one lane per sorted element of chunk c: the chunks of its
+//                  part are staged through LDS in turn and searched for the element's key.  A
+//                  chunk of lower index contributes its keys <= mine (ties there come before me),
+//                  one of higher index its keys < mine, my own chunk my sorted position.  The
+//                  parts' sums meet in one 64-bit atomic add per element, as in k_rank.
+// k_groups then runs unchanged on the counters.
+// Second word of a sort element: (bit-0 flag << 31) | index inside the chunk for kept tokens;
+// tokens without a destination and the padding of the last chunk carry the largest key and a
+// second word above every kept token's, so they sort behind all kept tokens of the chunk.
+constexpr int kChunk = 1024;
+constexpr int kChunkFrom = 8193;      // measured: at 8192 tokens the all-pairs walk is still ahead (35 against 39 us)
+constexpr uint32_t kSecEmpty = 0x40000000u, kSecPad = 0x7fffffffu;
+
+template <int W>
+__global__ __launch_bounds__(kChunk) void k_chunk_sort(const int32_t *__restrict__ topk, int T, int K,
+                                                       const int32_t *__restrict__ eslot, int E,
+                                                       uint64_t *__restrict__ mask_out, uint32_t *__restrict__ pstate,
+                                                       uint64_t *__restrict__ sort_key, uint32_t *__restrict__ sort_sec,
+                                                       uint32_t *__restrict__ chunk_kept)
+{
+    __shared__ uint64_t sk[kChunk];
+    __shared__ uint32_t ss[kChunk];
+    __shared__ uint32_t scratch[17];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int t = blockIdx.x * kChunk + tid;
+    bool bad = false;
+    uint64_t m[MW_MASK_WORDS] = {0, 0, 0, 0};
+    if (t < T) {
+        token_mask(topk + (size_t)t * K, K, eslot, E, m, bad);
+        uint64_t *o = mask_out + (size_t)t * MW_MASK_WORDS;
+#pragma unroll
+        for (int q = 0; q < MW_MASK_WORDS; ++q) o[q] = m[q];
+        if (bad) atomicOr(&pstate[kPsFlags], MW_FLAG_BAD_EXPERT);
+    }
+    const bool any = (m[0] | m[1] | m[2] | m[3]) != 0;
+    uint64_t key = ~0ull;
+    uint32_t sec = t < T ? (kSecEmpty | (uint32_t)tid) : kSecPad;
+    if (any) {
+        if constexpr (W == 1) { key = m[0]; sec = (uint32_t)tid; }
+        else { const mw_short_key k = short_key(m); key = k.key; sec = (k.flag << 31) | (uint32_t)tid; }
+    }
+    sk[tid] = key; ss[tid] = sec;
+    // rows per destination, as in k_rank
+#pragma unroll
+    for (int q = 0; q < MW_MASK_WORDS; ++q) {
+        if (__ballot(m[q] != 0) == 0) continue;          // wave-uniform
+        uint32_t mine = 0;
+        for (int b = 0; b < 64; ++b) {
+            const uint32_t n_b = (uint32_t)__popcll(__ballot((m[q] >> b) & 1ull));
+            if (lane == b) mine = n_b;
+        }
+        if (mine) atomicAdd(&pstate[q * 64 + lane], mine);
+    }
+    uint32_t kept;
+    mw_block_exscan(any ? 1u : 0u, scratch, &kept);        // its barriers also publish the keys
+    if (tid == 0) {
+        chunk_kept[blockIdx.x] = kept;
+        if (kept) atomicAdd(&pstate[kPsKept], kept);
+    }
+    // Bitonic network, one compare-exchange per lane of the first eight waves.  A step whose
+    // partner distance j is at most 32 stays inside the 128 elements one wavefront owns, so it
+    // needs no workgroup barrier: the wavefront's own LDS accesses are ordered by a fence.  Only
+    // the ten steps with j >= 64 (and the step after each of them) synchronise the workgroup.
+    for (int k = 2; k <= kChunk; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            if (tid < kChunk / 2) {
+                const int a = ((tid & ~(j - 1)) << 1) | (tid & (j - 1)), b = a | j;
+                const uint64_t ka = sk[a], kb = sk[b];
+                const uint32_t sa = ss[a], sb = ss[b];
+                const bool a_after_b = ka > kb || (ka == kb && sa > sb);
+                if (a_after_b == ((a & k) == 0)) { sk[a] = kb; sk[b] = ka; ss[a] = sb; ss[b] = sa; }
+            }
+            if (j >= 64 || (j == 1 && k >= 64)) mw_lds_barrier();   // the next step (j = k at the next k) crosses wavefronts
+            else __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront", "local");
+        }
+    }
+    mw_lds_barrier();
+    sort_key[(size_t)blockIdx.x * kChunk + tid] = sk[tid];
+    sort_sec[(size_t)blockIdx.x * kChunk + tid] = ss[tid];
+}
+
+template <int W>
+__global__ __launch_bounds__(kChunk) void k_merge_rank(int T, int n_chunks, const uint32_t *__restrict__ pstate,
+                                                       const uint64_t *__restrict__ sort_key,
+                                                       const uint32_t *__restrict__ sort_sec,
+                                                       const uint32_t *__restrict__ chunk_kept,
+                                                       unsigned long long *__restrict__ cnt)
+{
+    __shared__ uint64_t sk[kChunk];
+    __shared__ uint32_t ss[kChunk];
+    __shared__ uint32_t kept_of[64];                       // 65536 tokens / 1024
+    const int tid = threadIdx.x, c = blockIdx.x;
+    const int per = (n_chunks + (int)gridDim.y - 1) / (int)gridDim.y;
+    const int c_first = blockIdx.y * per, c_end = min(n_chunks, c_first + per);
+    if (c_first >= c_end) return;
+    if (tid < n_chunks) kept_of[tid] = chunk_kept[tid];
+    const uint64_t key = sort_key[(size_t)c * kChunk + tid];
+    const uint32_t sec = sort_sec[(size_t)c * kChunk + tid];
+    const uint32_t flag = sec >> 31;
+    const uint32_t n_empty = blockIdx.y == 0 ? (uint32_t)T - min(pstate[kPsKept], (uint32_t)T) : 0u;
+    uint64_t nk = sort_key[(size_t)c_first * kChunk + tid];  // the part's first chunk, staged below
+    uint32_t ns = sort_sec[(size_t)c_first * kChunk + tid];
+    uint32_t c_lt = 0, c_eqb = 0, c_eqa = 0;
+    // entries of the staged chunk that are below / not above my (key, flag)
+    auto below = [&](uint32_t idx) -> bool {
+        const uint64_t q = sk[idx];
+        if constexpr (W == 1) return q < key;
+        else return q < key || (q == key && (ss[idx] >> 31) < flag);
+    };
+    auto not_above = [&](uint32_t idx) -> bool {
+        const uint64_t q = sk[idx];
+        if constexpr (W == 1) return q <= key;
+        else return q < key || (q == key && (ss[idx] >> 31) <= flag);
+    };
+    for (int c2 = c_first; c2 < c_end; ++c2) {
+        mw_lds_barrier();                                   // the previous chunk has been searched
+        sk[tid] = nk; ss[tid] = ns;
+        mw_lds_barrier();
+        if (c2 + 1 < c_end) {                               // next chunk in flight during the search
+            nk = sort_key[(size_t)(c2 + 1) * kChunk + tid];
+            ns = sort_sec[(size_t)(c2 + 1) * kChunk + tid];
+        }
+        const uint32_t n = kept_of[c2];
+        uint32_t lb = 0, ub = 0;
+#pragma unroll
+        for (uint32_t st = kChunk; st >= 1; st >>= 1) {
+            if (lb + st <= n && below(lb + st - 1)) lb += st;
+            if (ub + st <= n && not_above(ub + st - 1)) ub += st;
+        }
+        c_lt += lb;
+        if (c2 < c) c_eqb += ub - lb;
+        else if (c2 > c) c_eqa += ub - lb;
+        else { c_eqb += (uint32_t)tid - lb; c_eqa += ub - (uint32_t)tid; }
+    }
+    if ((uint32_t)tid < kept_of[c]) {
+        const int t = c * kChunk + (int)(sec & 0x3fffffffu);
+        const unsigned long long add = (unsigned long long)(c_lt + c_eqb + n_empty) |
+                                       ((unsigned long long)c_eqb << 21) | ((unsigned long long)c_eqa << 42);
+        if (add) atomicAdd(&cnt[t], add);
+    }
+}
+
 }  // namespace
 
 int32_t mw_launch_plan_allgather_split(mw_ctx *ctx, int64_t shard_bytes, int64_t direct_bytes, mw_group_desc *desc,
@@ -501,7 +650,26 @@ int32_t mw_launch_plan(mw_ctx *ctx, const int32_t *topk, int32_t T, uint64_t *ma
     unsigned long long *cnt = (unsigned long long *)ctx->d_plan_cnt[cur];
     unsigned long long *cnt_o = (unsigned long long *)ctx->d_plan_cnt[oth];
     const int tb = (T + kBlock - 1) / kBlock;
-    if (T > 0) {
+    const bool has_key = ctx->mask_words == 1 || K <= 8;
+    if (T >= kChunkFrom && has_key && ctx->d_sort_key) {
+        const int nc = (T + kChunk - 1) / kChunk;
+        // split every chunk's walk over the other chunks into parts so that the grid fills the chip
+        int parts = (2 * ctx->n_cu + nc - 1) / nc;
+        if (parts > nc) parts = nc;
+        if (parts < 1) parts = 1;
+        mw_timed tm(ctx, MW_KERNEL_PLAN_RANK, s);
+        if (ctx->mask_words == 1) {
+            hipLaunchKernelGGL(k_chunk_sort<1>, dim3(nc), dim3(kChunk), 0, s, topk, T, K, ctx->d_eslot, E, mask,
+                               ctx->d_plan_state[cur], ctx->d_sort_key, ctx->d_sort_sec, ctx->d_chunk_kept);
+            hipLaunchKernelGGL(k_merge_rank<1>, dim3(nc, parts), dim3(kChunk), 0, s, T, nc, ctx->d_plan_state[cur],
+                               ctx->d_sort_key, ctx->d_sort_sec, ctx->d_chunk_kept, cnt);
+        } else {
+            hipLaunchKernelGGL(k_chunk_sort<4>, dim3(nc), dim3(kChunk), 0, s, topk, T, K, ctx->d_eslot, E, mask,
+                               ctx->d_plan_state[cur], ctx->d_sort_key, ctx->d_sort_sec, ctx->d_chunk_kept);
+            hipLaunchKernelGGL(k_merge_rank<4>, dim3(nc, parts), dim3(kChunk), 0, s, T, nc, ctx->d_plan_state[cur],
+                               ctx->d_sort_key, ctx->d_sort_sec, ctx->d_chunk_kept, cnt);
+        }
+    } else if (T > 0) {
         // split the predecessor walk into slices so that about 2 workgroups land on every CU when
         // a compare is one word (4 when it is a key and a flag: more compare work per pair); a
         // slice's bitmaps must fit in LDS.  Fewer, longer workgroups mean fewer atomics and less

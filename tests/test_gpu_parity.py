@@ -454,6 +454,44 @@ def test_more_rows_than_one_launch_has_workgroup_rows():
     assert int(gu.stats["n_recv_rows"]) > 32768
 
 
+@pytest.mark.parametrize("T,R,E,K", [(8193, 64, 256, 8), (9000, 256, 256, 8), (40000, 64, 128, 4), (65536, 130, 260, 8),
+                                     (65536, 8, 8, 2), (9500, 256, 512, 12)])
+def test_plan_of_large_batches(T, R, E, K):
+    """Batches the plan orders through sorted chunks (and, with 12 ids per token over 256 ranks,
+    one that still takes the all-pairs walk): bitmaps, perm, descriptors and statistics against
+    the oracle; some tokens go nowhere, many share their bitmap."""
+    _say("large plan", T, R, E, K)
+    w = W.DispatchWorkload("large", 95, R, E, K, T, 8, "bf16", "uniform")
+    e2r = W.expert_to_rank(w)
+    tk = W.topk_ids(w, 3, 0)
+    tk[::97] = -1
+    tk[5::11, K - 1] = -1
+    if R == 8:
+        tk[1000:30000] = tk[999]                      # one long run of equal bitmaps across many chunks
+    ctx = H.make_ctx(w, 0, max_recv_rows=1)
+    tk_d = H.dev(tk)
+    sb = B.SendBuffers(ctx, T)
+    for _ in range(2):                                   # twice: the counters' double buffering
+        ctx.mw_plan(tk_d, sb.mask, sb.perm, sb.desc, sb.stats)
+    st = ctx.mw_get_send_stats(sb.stats)
+    m, perm, desc, ost = ref.plan(tk, e2r, R, w.row_bytes)
+    N, G = int(st["n_rows"]), int(st["n_groups"])
+    assert (N, G, int(st["error_flags"])) == (len(perm), len(desc), 0)
+    H.assert_same_bytes(H.host(sb.mask).view(np.uint64), m, "mask")
+    H.assert_same_bytes(H.host(sb.perm)[:N], perm, "perm")
+    H.assert_same_bytes(H.host(sb.desc).reshape(-1).view(B.DESC_DTYPE)[:G].view(np.uint8), desc.view(np.uint8), "desc")
+    H.assert_same_bytes(st["rows_per_dest"], ost["rows_per_dest"], "rows_per_dest")
+    assert int(st["unicast_bytes"]) == int(ost["unicast_bytes"])
+    # and a small batch afterwards on the same context (the other ordering path, same counters)
+    small = tk[:300].copy()
+    ctx.mw_plan(H.dev(small), sb.mask, sb.perm, sb.desc, sb.stats)
+    st = ctx.mw_get_send_stats(sb.stats)
+    m, perm, desc, ost = ref.plan(small, e2r, R, w.row_bytes)
+    assert (int(st["n_rows"]), int(st["n_groups"])) == (len(perm), len(desc))
+    H.assert_same_bytes(H.host(sb.perm)[: len(perm)], perm, "perm after a large batch")
+    ctx.close()
+
+
 def test_invalid_expert_ids_set_the_error_flag():
     w = _small()
     tk = W.topk_ids(w, 1, 0)
