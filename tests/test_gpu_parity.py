@@ -452,6 +452,10 @@ def test_more_rows_than_one_launch_has_workgroup_rows():
     w = W.DispatchWorkload("long", 94, 4, 8, 2, 20000, 64, "bf16", "uniform")
     gu = run_dispatch(w, 1, 2, tier2=False)
     assert int(gu.stats["n_recv_rows"]) > 32768
+    # 30000 tokens and 20 local experts: the experts' source-token bitmaps no longer fit in LDS
+    # together, so the receive index makes several passes over the rows
+    w = W.DispatchWorkload("long_many_experts", 96, 2, 40, 4, 30000, 32, "bf16", "uniform")
+    run_dispatch(w, 2, 1, tier2=False, check_all_senders=False)
 
 
 @pytest.mark.parametrize("T,R,E,K", [(8193, 64, 256, 8), (9000, 256, 256, 8), (40000, 64, 128, 4), (65536, 130, 260, 8),
