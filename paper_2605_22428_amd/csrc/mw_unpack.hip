@@ -18,14 +18,17 @@
 //                 peer and (expert slot, rank) pairs.  The workgroup that finishes last
 //                 (device-scope counter) scans the counts into output bases, so no
 //                 third launch and no grid-wide barrier is needed.
-//   k_expand      small workgroups (a single wave for cache-line-sized rows), each moving
-//                 consecutive 16-byte chunks of one received row (rows beyond 32768 by
-//                 striding): a chunk is read once with a streaming load and stored to each
-//                 of the row's experts' slots.  Measured on MI355X, many small waves with
-//                 a single load in flight each track the plain-copy ceiling, while fewer
-//                 waves with deep per-lane unrolling fall 10-30 % short, and a persistent
-//                 grid loses ~5 % to the hardware dispatcher.  This kernel moves ~all
-//                 receive-side bytes and is bound by HBM bandwidth.
+//   k_expand      small workgroups (a single wave for long cache-line-sized rows, one
+//                 workgroup per row up to 10 KiB), each moving consecutive 16-byte chunks of
+//                 one received row (rows beyond 32768 by striding): a chunk is read once with
+//                 a streaming load and stored to each of the row's experts' slots.  Measured
+//                 on MI355X, many small waves with a single load in flight each track the
+//                 plain-copy ceiling, while fewer waves with deep per-lane unrolling fall
+//                 10-30 % short, and a persistent grid loses ~5 % to the hardware dispatcher.
+//                 This kernel moves ~all receive-side bytes and is bound by HBM bandwidth.
+// Further entry points share these bodies: k_recv_index<true> reads per-row headers (packets),
+// k_expand_index_next runs the expander with the next batch's index in the same launch, and
+// k_combine is the expander's mirror image for the way back.
 #include "mw_internal.h"
 
 namespace {
