@@ -27,6 +27,9 @@
 //             of scattered stores per cycle.
 // The count and histogram buffers are double-buffered between consecutive plans: a plan
 // clears the buffers the previous plan used, so no extra clearing launch is needed.
+// Batches above 8192 tokens replace k_rank by k_chunk_sort + k_merge_rank (sorted chunks,
+// ranks by binary search: T log T instead of T^2); batches of at most 256 tokens can take
+// k_plan_pack, which plans and packs in one launch.
 #include "mw_internal.h"
 
 namespace {
