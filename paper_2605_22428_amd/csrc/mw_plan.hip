@@ -487,8 +487,8 @@ __global__ __launch_bounds__(kBlock) void k_plan_pack(const int32_t *__restrict_
 
 // ---- ordering of large batches: sorted chunks, then ranks by binary search ------------------
 // The all-pairs walk of k_rank costs T^2 compares: 84 us at 16 k tokens, 220 us at 32 k, 700 us
-// at 64 k (one-word bitmaps; 120 / 335 / 1085 us with short keys).  This path: 52 / 72 / 102 us
-// (64 / 85 / 119 us).  For batches of kChunkFrom tokens or more whose bitmaps have a 64-bit order-preserving key (one word, or
+// at 64 k (one-word bitmaps; 120 / 335 / 1085 us with short keys).  This path: 48 / 68 / 97 us
+// (53 / 74 / 107 us).  For batches of kChunkFrom tokens or more whose bitmaps have a 64-bit order-preserving key (one word, or
 // short keys) the same counters are produced in T log T work:
 //   k_chunk_sort   one workgroup per chunk of 1024 tokens: bitmaps, keys, a bitonic sort of
 //                  (key, second word) pairs in LDS; the sorted chunk goes to the workspace.
@@ -514,9 +514,11 @@ __global__ __launch_bounds__(kChunk) void k_chunk_sort(const int32_t *__restrict
 {
     __shared__ uint64_t sk[kChunk];
     __shared__ uint32_t ss[kChunk];
+    __shared__ uint32_t hist[MW_MAX_RANKS];
     __shared__ uint32_t scratch[17];
-    const int tid = threadIdx.x, lane = tid & 63;
+    const int tid = threadIdx.x;
     const int t = blockIdx.x * kChunk + tid;
+    if (tid < MW_MAX_RANKS) hist[tid] = 0;
     bool bad = false;
     uint64_t m[MW_MASK_WORDS] = {0, 0, 0, 0};
     if (t < T) {
@@ -533,44 +535,51 @@ __global__ __launch_bounds__(kChunk) void k_chunk_sort(const int32_t *__restrict
         if constexpr (W == 1) { key = m[0]; sec = (uint32_t)tid; }
         else { const mw_short_key k = short_key(m); key = k.key; sec = (k.flag << 31) | (uint32_t)tid; }
     }
-    sk[tid] = key; ss[tid] = sec;
-    // rows per destination, as in k_rank
-#pragma unroll
-    for (int q = 0; q < MW_MASK_WORDS; ++q) {
-        if (__ballot(m[q] != 0) == 0) continue;          // wave-uniform
-        uint32_t mine = 0;
-        for (int b = 0; b < 64; ++b) {
-            const uint32_t n_b = (uint32_t)__popcll(__ballot((m[q] >> b) & 1ull));
-            if (lane == b) mine = n_b;
-        }
-        if (mine) atomicAdd(&pstate[q * 64 + lane], mine);
-    }
     uint32_t kept;
-    mw_block_exscan(any ? 1u : 0u, scratch, &kept);        // its barriers also publish the keys
+    mw_block_exscan(any ? 1u : 0u, scratch, &kept);        // (its barriers also publish the cleared histogram)
     if (tid == 0) {
         chunk_kept[blockIdx.x] = kept;
         if (kept) atomicAdd(&pstate[kPsKept], kept);
     }
-    // Bitonic network, one compare-exchange per lane of the first eight waves.  A step whose
-    // partner distance j is at most 32 stays inside the 128 elements one wavefront owns, so it
-    // needs no workgroup barrier: the wavefront's own LDS accesses are ordered by a fence.  Only
-    // the ten steps with j >= 64 (and the step after each of them) synchronise the workgroup.
-    for (int k = 2; k <= kChunk; k <<= 1) {
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            if (tid < kChunk / 2) {
-                const int a = ((tid & ~(j - 1)) << 1) | (tid & (j - 1)), b = a | j;
-                const uint64_t ka = sk[a], kb = sk[b];
-                const uint32_t sa = ss[a], sb = ss[b];
-                const bool a_after_b = ka > kb || (ka == kb && sa > sb);
-                if (a_after_b == ((a & k) == 0)) { sk[a] = kb; sk[b] = ka; ss[a] = sb; ss[b] = sa; }
-            }
-            if (j >= 64 || (j == 1 && k >= 64)) mw_lds_barrier();   // the next step (j = k at the next k) crosses wavefronts
-            else __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront", "local");
+    // rows per destination: one LDS atomic per set bit (at most top_k per token), then one
+    // global atomic per rank and chunk
+#pragma unroll
+    for (int q = 0; q < W; ++q) {
+        uint64_t left = m[q];
+        while (left) {
+            const int b = __ffsll((unsigned long long)left) - 1;
+            left &= left - 1;
+            atomicAdd(&hist[q * 64 + b], 1u);
         }
     }
-    mw_lds_barrier();
-    sort_key[(size_t)blockIdx.x * kChunk + tid] = sk[tid];
-    sort_sec[(size_t)blockIdx.x * kChunk + tid] = ss[tid];
+
+    // Bitonic network with one element per lane.  Partners closer than 64 are in the same
+    // wavefront and are exchanged in registers; the ten steps with partners 64 or more apart go
+    // through LDS.  Position e keeps the smaller of the pair iff it is the lower position of an
+    // ascending block or the upper position of a descending one.
+    const int e = tid;
+    for (int k = 2; k <= kChunk; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            uint64_t pk;
+            uint32_t ps;
+            if (j >= 64) {
+                sk[e] = key; ss[e] = sec;
+                mw_lds_barrier();
+                pk = sk[e ^ j]; ps = ss[e ^ j];
+                mw_lds_barrier();
+            } else {
+                pk = __shfl_xor(key, j, 64);
+                ps = __shfl_xor(sec, j, 64);
+            }
+            const bool mine_after = key > pk || (key == pk && sec > ps);
+            const bool keep_smaller = ((e & j) == 0) == ((e & k) == 0);
+            if (mine_after == keep_smaller) { key = pk; sec = ps; }
+        }
+    }
+    sort_key[(size_t)blockIdx.x * kChunk + tid] = key;
+    sort_sec[(size_t)blockIdx.x * kChunk + tid] = sec;
+    mw_lds_barrier();                                       // every lane's histogram atomics are done
+    if (tid < MW_MAX_RANKS && hist[tid]) atomicAdd(&pstate[tid], hist[tid]);
 }
 
 template <int W>
