@@ -488,7 +488,7 @@ __global__ __launch_bounds__(kBlock) void k_plan_pack(const int32_t *__restrict_
 // ---- ordering of large batches: sorted chunks, then ranks by binary search ------------------
 // The all-pairs walk of k_rank costs T^2 compares: 84 us at 16 k tokens, 220 us at 32 k, 700 us
 // at 64 k (one-word bitmaps; 120 / 335 / 1085 us with short keys).  This path: 48 / 68 / 97 us
-// (53 / 74 / 107 us).  For batches of kChunkFrom tokens or more whose bitmaps have a 64-bit order-preserving key (one word, or
+// (53 / 74 / 107 us).  For large batches (switch points below) whose bitmaps have a 64-bit order-preserving key (one word, or
 // short keys) the same counters are produced in T log T work:
 //   k_chunk_sort   one workgroup per chunk of 1024 tokens: bitmaps, keys, a bitonic sort of
 //                  (key, second word) pairs in LDS; the sorted chunk goes to the workspace.
@@ -502,7 +502,9 @@ __global__ __launch_bounds__(kBlock) void k_plan_pack(const int32_t *__restrict_
 // tokens without a destination and the padding of the last chunk carry the largest key and a
 // second word above every kept token's, so they sort behind all kept tokens of the chunk.
 constexpr int kChunk = 1024;
-constexpr int kChunkFrom = 8193;      // measured: at 8192 tokens the all-pairs walk is still ahead (35 against 39 us)
+// Switch points, measured: one-word bitmaps tie at 8192 tokens (35 us either way); with short
+// keys (a costlier compare per pair) sorting is ahead from about 6144 (8192 tokens: 39 against 48 us).
+constexpr int kChunkFromOneWord = 8193, kChunkFromKeyed = 6145;
 constexpr uint32_t kSecEmpty = 0x40000000u, kSecPad = 0x7fffffffu;
 
 template <int W>
@@ -663,7 +665,7 @@ int32_t mw_launch_plan(mw_ctx *ctx, const int32_t *topk, int32_t T, uint64_t *ma
     unsigned long long *cnt_o = (unsigned long long *)ctx->d_plan_cnt[oth];
     const int tb = (T + kBlock - 1) / kBlock;
     const bool has_key = ctx->mask_words == 1 || K <= 8;
-    if (T >= kChunkFrom && has_key && ctx->d_sort_key) {
+    if (T >= (ctx->mask_words == 1 ? kChunkFromOneWord : kChunkFromKeyed) && has_key && ctx->d_sort_key) {
         const int nc = (T + kChunk - 1) / kChunk;
         // split every chunk's walk over the other chunks into parts so that the grid fills the chip
         int parts = (2 * ctx->n_cu + nc - 1) / nc;
