@@ -9,7 +9,7 @@ namespace {
 
 struct ws_layout {
     int64_t eslot, plan_cnt[2], plan_state[2], flags, cnt, base, row_base, addr_cnt, recs, hits, row_map,
-        hop_bits, group_of_row, child_pos, sort_key, sort_sec, chunk_kept, total;
+        hop_bits, group_of_row, child_pos, sort_key, sort_sec, chunk_kept, row_cnt, row_start, total;
 };
 
 // Derived row geometry; returns a status.
@@ -86,12 +86,14 @@ ws_layout layout(const mw_config &c, int32_t L)
         w.child_pos = o;    o += mw_align_up(4LL * MW_MAX_HOPS * ntok, A);
     }
     // sorted chunks for the plan of large batches (only contexts that can see such batches)
-    w.sort_key = w.sort_sec = w.chunk_kept = -1;
+    w.sort_key = w.sort_sec = w.chunk_kept = w.row_cnt = w.row_start = -1;
     if (c.max_tokens > 4096) {
         const int64_t padded = mw_align_up(ntok, 1024);
         w.sort_key = o;   o += mw_align_up(8LL * padded, A);
         w.sort_sec = o;   o += mw_align_up(4LL * padded, A);
         w.chunk_kept = o; o += mw_align_up(4LL * 64, A);
+        w.row_cnt = o;    o += mw_align_up(8LL * padded, A);
+        w.row_start = o;  o += mw_align_up(padded, A);
     }
     w.total = o;
     return w;
@@ -147,6 +149,8 @@ MW_API int32_t mw_ctx_create(const mw_config *cfg, void *workspace_dev, int64_t 
     ctx->d_sort_key = w.sort_key >= 0 ? (uint64_t *)(b + w.sort_key) : nullptr;
     ctx->d_sort_sec = w.sort_sec >= 0 ? (uint32_t *)(b + w.sort_sec) : nullptr;
     ctx->d_chunk_kept = w.chunk_kept >= 0 ? (uint32_t *)(b + w.chunk_kept) : nullptr;
+    ctx->d_row_cnt = w.row_cnt >= 0 ? (uint64_t *)(b + w.row_cnt) : nullptr;
+    ctx->d_row_start = w.row_start >= 0 ? (unsigned char *)(b + w.row_start) : nullptr;
     ctx->d_flags = (uint32_t *)(b + w.flags);
     ctx->d_cnt = (uint32_t *)(b + w.cnt);
     ctx->d_base = (uint32_t *)(b + w.base);

@@ -73,6 +73,8 @@ struct mw_ctx {
     uint64_t *d_sort_key;       // [max_tokens rounded up to 1024] sorted chunks of the large-batch plan (or null)
     uint32_t *d_sort_sec;       // same count: second sort word
     uint32_t *d_chunk_kept;     // [64] kept tokens per chunk
+    uint64_t *d_row_cnt;        // [max_tokens] a packed row's counters (large-batch plan, or null)
+    unsigned char *d_row_start; // [max_tokens] 1: a group starts at this packed row
     uint32_t *d_flags;      // [4] 1: receive flags, 2: receive workgroups done
     uint32_t *d_base;       // [L][R] first output row of (local expert, peer)
     mw_row_rec *d_recs;     // [max_recv_rows]

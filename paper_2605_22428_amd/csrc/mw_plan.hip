@@ -195,13 +195,38 @@ __global__ __launch_bounds__(kBlock) void k_rank(const int32_t *__restrict__ top
     }
 }
 
+// For very large batches the walk below (every workgroup over every token's counters) is
+// itself T^2 / 256 loads.  This kernel turns the counters into arrays indexed by packed row
+// first -- perm, the row's counters and a "group starts here" byte -- so that k_groups<true>
+// only sums the start bytes in front of its rows.
+__global__ __launch_bounds__(kBlock) void k_rows_from_counters(int T, const unsigned long long *__restrict__ cnt,
+                                                               const uint32_t *__restrict__ pstate,
+                                                               int32_t *__restrict__ perm,
+                                                               unsigned long long *__restrict__ row_cnt,
+                                                               unsigned char *__restrict__ row_start)
+{
+    const int t = blockIdx.x * kBlock + threadIdx.x;
+    if (t >= T) return;
+    const uint32_t N = min(pstate[kPsKept], (uint32_t)T), n_empty = (uint32_t)T - N;
+    const unsigned long long c = cnt[t];
+    if ((c >> 42) == 0) return;                               // empty bitmap
+    const uint32_t p = (uint32_t)(c & kField) - n_empty;
+    if (p >= N) return;
+    perm[p] = t;
+    row_cnt[p] = c;
+    row_start[p] = ((c >> 21) & kField) == 0 ? 1 : 0;
+}
+
+template <bool kByRow>
 __global__ __launch_bounds__(kBlock) void k_groups(const uint64_t *__restrict__ mask, int T, uint64_t row_bytes,
                                                    const unsigned long long *__restrict__ cnt,
                                                    uint32_t *__restrict__ pstate,
                                                    unsigned long long *__restrict__ cnt_other, int T_other,
                                                    uint32_t *__restrict__ pstate_other,
                                                    int32_t *__restrict__ perm, mw_group_desc *__restrict__ desc,
-                                                   mw_send_stats *__restrict__ stats)
+                                                   mw_send_stats *__restrict__ stats,
+                                                   const unsigned long long *__restrict__ row_cnt,
+                                                   const unsigned char *__restrict__ row_start)
 {
     __shared__ int32_t tok[kBlock];
     __shared__ unsigned long long tokc[kBlock];     // the token's counters, so they are not fetched again
@@ -214,6 +239,17 @@ __global__ __launch_bounds__(kBlock) void k_groups(const uint64_t *__restrict__ 
     // how many groups start before its first row, how many groups there are.  Sixteen counters
     // per lane are requested before the first is looked at: one memory round trip per 4096 tokens.
     uint32_t starts_before = 0, starts_total = 0;
+    if constexpr (kByRow) {
+        // rows in front of this workgroup's, sixteen start bytes per load (i0 is a multiple of 256);
+        // the first workgroup also counts all groups for the statistics
+        const u32x4 *sb = (const u32x4 *)row_start;
+        auto ones = [](u32x4 v) { return (uint32_t)(__popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w)); };
+        for (uint32_t q = tid; q < i0 / 16; q += kBlock) starts_before += ones(sb[q]);
+        if (blockIdx.x == 0) {
+            for (uint32_t r = tid; r < N; r += kBlock) starts_total += row_start[r];
+        }
+        if (i0 + tid < N) { tok[tid] = perm[i0 + tid]; tokc[tid] = row_cnt[i0 + tid]; }
+    } else
     for (int t0 = 0; t0 < T; t0 += 16 * kBlock) {
         unsigned long long cc[16];
 #pragma unroll
@@ -505,6 +541,7 @@ constexpr int kChunk = 1024;
 // Switch points, measured: one-word bitmaps tie at 8192 tokens (35 us either way); with short
 // keys (a costlier compare per pair) sorting is ahead from about 6144 (8192 tokens: 39 against 48 us).
 constexpr int kChunkFromOneWord = 8193, kChunkFromKeyed = 6145;
+constexpr int kRowsFrom = 24576;       // from here k_groups works on row-indexed arrays
 constexpr uint32_t kSecEmpty = 0x40000000u, kSecPad = 0x7fffffffu;
 
 template <int W>
@@ -713,8 +750,17 @@ int32_t mw_launch_plan(mw_ctx *ctx, const int32_t *topk, int32_t T, uint64_t *ma
     }
     {
         mw_timed tm(ctx, MW_KERNEL_PLAN_GROUPS, s);
-        hipLaunchKernelGGL(k_groups, dim3(tb > 0 ? tb : 1), dim3(kBlock), 0, s, mask, T, (uint64_t)ctx->row_bytes, cnt,
-                           ctx->d_plan_state[cur], cnt_o, ctx->plan_T[oth], ctx->d_plan_state[oth], perm, desc, stats);
+        if (T >= kRowsFrom && ctx->d_row_cnt) {
+            hipLaunchKernelGGL(k_rows_from_counters, dim3(tb), dim3(kBlock), 0, s, T, cnt, ctx->d_plan_state[cur], perm,
+                               (unsigned long long *)ctx->d_row_cnt, ctx->d_row_start);
+            hipLaunchKernelGGL(k_groups<true>, dim3(tb), dim3(kBlock), 0, s, mask, T, (uint64_t)ctx->row_bytes, cnt,
+                               ctx->d_plan_state[cur], cnt_o, ctx->plan_T[oth], ctx->d_plan_state[oth], perm, desc, stats,
+                               (const unsigned long long *)ctx->d_row_cnt, ctx->d_row_start);
+        } else {
+            hipLaunchKernelGGL(k_groups<false>, dim3(tb > 0 ? tb : 1), dim3(kBlock), 0, s, mask, T,
+                               (uint64_t)ctx->row_bytes, cnt, ctx->d_plan_state[cur], cnt_o, ctx->plan_T[oth],
+                               ctx->d_plan_state[oth], perm, desc, stats, nullptr, nullptr);
+        }
     }
     ctx->plan_T[oth] = 0;        // cleared by this plan
     ctx->plan_T[cur] = T;        // to be cleared by the next one
