@@ -28,7 +28,11 @@
  *     received metadata) set MW_FLAG_* bits in the statistics block, the
  *     offending item is left out, and all kernels still terminate normally.
  *   - A context may be used from one stream at a time: calls on the same
- *     context share its workspace and race if they overlap.
+ *     context share its workspace and race if they overlap.  The host-side
+ *     context is not locked either: one host thread at a time per context.
+ *   - A context belongs to the device that was current at mw_ctx_create; an
+ *     entry point called with another device current returns
+ *     MW_ERR_INVALID_ARG and enqueues nothing.
  */
 #ifndef MW_H_
 #define MW_H_

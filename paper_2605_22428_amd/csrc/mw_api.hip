@@ -7,6 +7,15 @@
 
 namespace {
 
+// A context's workspace lives on the device that was current when it was created; work for
+// it enqueued with another device current would run there on foreign pointers.
+#define MW_ON_DEVICE(ctx)                                               \
+    do {                                                                \
+        int mw_dev_now_ = -1;                                           \
+        if (hipGetDevice(&mw_dev_now_) != hipSuccess) return MW_ERR_HIP; \
+        if (mw_dev_now_ != (ctx)->device) return MW_ERR_INVALID_ARG;    \
+    } while (0)
+
 struct ws_layout {
     int64_t eslot, plan_cnt[2], plan_state[2], flags, cnt, base, row_base, addr_cnt, recs, hits, row_map,
         hop_bits, group_of_row, child_pos, sort_key, sort_sec, chunk_kept, row_cnt, row_start, total;
@@ -205,6 +214,7 @@ MW_API int32_t mw_plan(mw_ctx *ctx, const int32_t *topk_ids_dev, int32_t n_token
                 int32_t *perm_dev, mw_group_desc *desc_dev, mw_send_stats *stats_dev, void *stream)
 {
     if (!ctx || !stats_dev || n_tokens < 0) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
     if (n_tokens > ctx->cfg.max_tokens) return MW_ERR_CAPACITY;
     if (n_tokens > 0 && (!topk_ids_dev || !mask_dev || !perm_dev || !desc_dev)) return MW_ERR_INVALID_ARG;
     if (ctx->cfg.n_experts == 0) return MW_ERR_INVALID_ARG;
@@ -216,6 +226,7 @@ MW_API int32_t mw_pack(mw_ctx *ctx, const void *x_dev, const float *scales_dev, 
                 void *packed_rows_dev, int32_t *row_src_token_dev, int32_t *row_topk_dev, void *stream)
 {
     if (!ctx || !stats_dev || n_tokens < 0) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
     if (n_tokens > ctx->cfg.max_tokens) return MW_ERR_CAPACITY;
     if (n_tokens == 0) return MW_OK;
     if (!x_dev || !topk_ids_dev || !perm_dev || !packed_rows_dev || !row_src_token_dev || !row_topk_dev)
@@ -231,6 +242,7 @@ MW_API int32_t mw_pack_quantize(mw_ctx *ctx, const void *x_bf16_dev, const int32
                          void *packed_rows_dev, int32_t *row_src_token_dev, int32_t *row_topk_dev, void *stream)
 {
     if (!ctx || !stats_dev || n_tokens < 0) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
     if (ctx->cfg.row_format != MW_ROW_FP8_E4M3_BLOCK128) return MW_ERR_UNSUPPORTED;
     if (n_tokens > ctx->cfg.max_tokens) return MW_ERR_CAPACITY;
     if (n_tokens == 0) return MW_OK;
@@ -247,6 +259,7 @@ MW_API int32_t mw_plan_pack(mw_ctx *ctx, const int32_t *topk_ids_dev, const void
                      int32_t *row_topk_dev, void *stream)
 {
     if (!ctx || !stats_dev || n_tokens < 0) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
     if (n_tokens > ctx->cfg.max_tokens || n_tokens > MW_FUSED_MAX_TOKENS) return MW_ERR_CAPACITY;
     if (ctx->cfg.n_experts == 0) return MW_ERR_INVALID_ARG;
     if (n_tokens > 0) {
@@ -264,6 +277,7 @@ MW_API int32_t mw_plan_allgather(mw_ctx *ctx, int64_t shard_bytes, mw_group_desc
                           void *stream)
 {
     if (!ctx || !desc_dev || !stats_dev || shard_bytes < 0) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
     return mw_launch_plan_allgather(ctx, shard_bytes, desc_dev, stats_dev, (hipStream_t)stream);
 }
 
@@ -271,6 +285,7 @@ MW_API int32_t mw_pack_allgather(mw_ctx *ctx, const void *shard_dev, int64_t sha
                           void *stream)
 {
     if (!ctx || shard_bytes < 0) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
     if (shard_bytes % 16 != 0) return MW_ERR_UNSUPPORTED;
     if (shard_bytes == 0) return MW_OK;
     if (!shard_dev || !send_buf_dev || (((uintptr_t)shard_dev | (uintptr_t)send_buf_dev) & 15u))
@@ -298,6 +313,7 @@ MW_API int32_t mw_plan_allgather_split(mw_ctx *ctx, int64_t shard_bytes, int64_t
 {
     if (!ctx || !desc_dev || !stats_dev || shard_bytes < 0 || direct_bytes < 0 || direct_bytes > shard_bytes)
         return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
     if (shard_bytes % 16 != 0 || direct_bytes % 16 != 0 || shard_bytes / 16 > 0xffffffffLL) return MW_ERR_UNSUPPORTED;
     return mw_launch_plan_allgather_split(ctx, shard_bytes, direct_bytes, desc_dev, stats_dev, (hipStream_t)stream);
 }
@@ -306,6 +322,7 @@ MW_API int32_t mw_unpack_allgather_split(mw_ctx *ctx, const void *const *direct_
                                   int64_t shard_bytes, int64_t direct_bytes, void *out_dev, void *stream)
 {
     if (!ctx || shard_bytes < 0 || direct_bytes < 0 || direct_bytes > shard_bytes) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
     if (shard_bytes % 16 != 0 || direct_bytes % 16 != 0) return MW_ERR_UNSUPPORTED;
     if (shard_bytes == 0) return MW_OK;
     if (!direct_dev || !relayed_dev || !out_dev || ((uintptr_t)out_dev & 15u)) return MW_ERR_INVALID_ARG;
@@ -318,6 +335,7 @@ static int32_t check_unpack_index(mw_ctx *ctx, const void *peers_dev, int32_t n_
 {
     if (!ctx || !peers_dev || !expert_offsets_dev || !recv_stats_dev || out_capacity_rows < 0)
         return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
     if (n_peers < 1 || n_peers > ctx->cfg.n_ranks) return MW_ERR_INVALID_ARG;
     if (ctx->cfg.n_experts == 0) return MW_ERR_INVALID_ARG;
     if (out_capacity_rows > 0xffffffffLL) return MW_ERR_UNSUPPORTED;
@@ -328,6 +346,7 @@ static int32_t check_unpack_expand(mw_ctx *ctx, int32_t n_peers, void *out_rows_
                                    int64_t out_capacity_rows, int32_t *out_src_peer_dev, int32_t *out_src_token_dev)
 {
     if (!ctx || out_capacity_rows < 0) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
     if (n_peers < 1 || n_peers > ctx->cfg.n_ranks) return MW_ERR_INVALID_ARG;
     if (ctx->cfg.n_experts == 0) return MW_ERR_INVALID_ARG;
     if (out_capacity_rows > 0 && (!out_rows_dev || !out_src_peer_dev || !out_src_token_dev))
@@ -367,6 +386,7 @@ MW_API int32_t mw_pack_packets(mw_ctx *ctx, const void *x_dev, const float *scal
                         int32_t n_tokens, void *packets_dev, void *stream)
 {
     if (!ctx || !stats_dev || n_tokens < 0) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
     if (n_tokens > ctx->cfg.max_tokens) return MW_ERR_CAPACITY;
     if (ctx->cfg.n_experts == 0) return MW_ERR_INVALID_ARG;
     if (n_tokens == 0) return MW_OK;
@@ -402,6 +422,7 @@ MW_API int32_t mw_unpack_expand_index_next(mw_ctx *ctx, int32_t n_peers, void *o
                                     mw_recv_stats *next_recv_stats_dev, void *stream)
 {
     if (!ctx || !next_ctx || ctx == next_ctx || ctx->device != next_ctx->device) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
     int32_t rc = check_unpack_expand(ctx, n_peers, out_rows_dev, out_scales_dev, out_capacity_rows, out_src_peer_dev,
                                      out_src_token_dev);
     if (rc == MW_OK)
@@ -418,6 +439,7 @@ MW_API int32_t mw_combine_gather(mw_ctx *ctx, int32_t n_peers, const void *y_dev
                           void *ret_rows_dev, int64_t ret_capacity_rows, void *stream)
 {
     if (!ctx || out_capacity_rows < 0 || ret_capacity_rows < 0) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
     if (ctx->cfg.row_format != MW_ROW_BF16) return MW_ERR_UNSUPPORTED;
     if (n_peers < 1 || n_peers > ctx->cfg.n_ranks || ctx->cfg.n_experts == 0) return MW_ERR_INVALID_ARG;
     if (out_capacity_rows > 0xffffffffLL || ret_capacity_rows > 0xffffffffLL) return MW_ERR_UNSUPPORTED;
@@ -450,6 +472,7 @@ MW_API int32_t mw_unpack_allgather(mw_ctx *ctx, const void *const *peer_shards_d
                             void *stream)
 {
     if (!ctx || shard_bytes < 0) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
     if (shard_bytes % 16 != 0) return MW_ERR_UNSUPPORTED;
     if (shard_bytes == 0) return MW_OK;
     if (!peer_shards_dev || !out_dev || ((uintptr_t)out_dev & 15u)) return MW_ERR_INVALID_ARG;
@@ -463,6 +486,7 @@ MW_API int32_t mw_sim_deliver(mw_ctx *ctx, const mw_group_desc *desc_dev, const 
                        uint32_t *counts_out_dev, void *stream)
 {
     if (!ctx || !stats_dev || !counts_out_dev || n_tokens < 0) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
     if (n_tokens > ctx->cfg.max_tokens) return MW_ERR_CAPACITY;
     if (dst_rank < 0 || dst_rank >= ctx->cfg.n_ranks) return MW_ERR_INVALID_ARG;
     if (n_tokens > 0 && (!desc_dev || !packed_rows_dev || !row_src_token_dev || !row_topk_dev || !desc_out_dev ||
@@ -486,6 +510,7 @@ MW_API int32_t mw_copy_bytes(void *dst_dev, const void *src_dev, int64_t n_bytes
 MW_API int32_t mw_get_send_stats(mw_ctx *ctx, const mw_send_stats *stats_dev, mw_send_stats *host_out, void *stream)
 {
     if (!ctx || !stats_dev || !host_out) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
     MW_HIP_CHECK(hipMemcpyAsync(host_out, stats_dev, sizeof(mw_send_stats), hipMemcpyDeviceToHost, (hipStream_t)stream));
     MW_HIP_CHECK(hipStreamSynchronize((hipStream_t)stream));
     return MW_OK;
@@ -494,6 +519,7 @@ MW_API int32_t mw_get_send_stats(mw_ctx *ctx, const mw_send_stats *stats_dev, mw
 MW_API int32_t mw_get_recv_stats(mw_ctx *ctx, const mw_recv_stats *stats_dev, mw_recv_stats *host_out, void *stream)
 {
     if (!ctx || !stats_dev || !host_out) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
     MW_HIP_CHECK(hipMemcpyAsync(host_out, stats_dev, sizeof(mw_recv_stats), hipMemcpyDeviceToHost, (hipStream_t)stream));
     MW_HIP_CHECK(hipStreamSynchronize((hipStream_t)stream));
     ctx->recv_rows_hint = host_out->n_rows_seen;       // sizes the next mw_unpack's launch
@@ -503,6 +529,7 @@ MW_API int32_t mw_get_recv_stats(mw_ctx *ctx, const mw_recv_stats *stats_dev, mw
 MW_API int32_t mw_set_forwarding(mw_ctx *ctx, const int32_t *next_hop, int32_t n_hops)
 {
     if (!ctx || !next_hop) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
     if (n_hops < 1) return MW_ERR_INVALID_ARG;
     if (n_hops > ctx->cfg.max_hops) return MW_ERR_CAPACITY;
     std::vector<uint64_t> bits((size_t)MW_MASK_WORDS * MW_MAX_HOPS, 0);
@@ -522,6 +549,7 @@ MW_API int32_t mw_relay(mw_ctx *ctx, const mw_recv_peer *in_dev, const mw_relay_
                  int64_t child_capacity_rows, mw_relay_stats *stats_dev, void *stream)
 {
     if (!ctx || !in_dev || !children_dev || !stats_dev || child_capacity_rows < 0) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
     if (ctx->cfg.max_hops < 1 || ctx->n_hops < 1) return MW_ERR_INVALID_ARG;      // no forwarding table
     if (child_capacity_rows > 0x7fffffffLL) return MW_ERR_UNSUPPORTED;
     return mw_launch_relay(ctx, in_dev, children_dev, child_capacity_rows, stats_dev, (hipStream_t)stream);
@@ -531,6 +559,7 @@ MW_API int32_t mw_relay_packets(mw_ctx *ctx, const mw_recv_packets *in_dev, void
                          int64_t child_capacity_rows, mw_relay_stats *stats_dev, void *stream)
 {
     if (!ctx || !in_dev || !children_dev || !stats_dev || child_capacity_rows < 0) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
     if (ctx->cfg.max_hops < 1 || ctx->n_hops < 1) return MW_ERR_INVALID_ARG;      // no forwarding table
     if (ctx->cfg.n_experts == 0) return MW_ERR_INVALID_ARG;
     if (child_capacity_rows > 0x7fffffffLL) return MW_ERR_UNSUPPORTED;
@@ -540,6 +569,7 @@ MW_API int32_t mw_relay_packets(mw_ctx *ctx, const mw_recv_packets *in_dev, void
 MW_API int32_t mw_get_relay_stats(mw_ctx *ctx, const mw_relay_stats *stats_dev, mw_relay_stats *host_out, void *stream)
 {
     if (!ctx || !stats_dev || !host_out) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
     MW_HIP_CHECK(hipMemcpyAsync(host_out, stats_dev, sizeof(mw_relay_stats), hipMemcpyDeviceToHost, (hipStream_t)stream));
     MW_HIP_CHECK(hipStreamSynchronize((hipStream_t)stream));
     return MW_OK;
