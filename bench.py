@@ -575,6 +575,21 @@ def bench_dispatch(args, name: str) -> dict:
     achieved = expand_bytes / (expand_avg_ms * 1e-3) / 1e9
     pu_us = kern_us["pack"] + kern_us["recv_index"] + kern_us["expand"]
     saved = 1.0 - int(st["multicast_bytes"]) / int(st["unicast_bytes"])
+    # the same figure without this rank's own copy (Section 3.1's AllGather counts the OTHER nodes
+    # only): rows that go nowhere else are not sent at all, and no row counts its local copy
+    G = int(st["n_groups"])
+    desc_h = sets[0]["send"].desc.cpu().numpy().reshape(-1).view(B.DESC_DTYPE)[:G]
+    own = np.zeros(4, dtype=np.uint64)
+    own[my_rank >> 6] = np.uint64(1) << np.uint64(my_rank & 63)
+    self_only_rows = int(desc_h["row_count"][(desc_h["mask"] == own).all(axis=1)].sum())
+    copies = int(st["unicast_bytes"]) // rb
+    to_others = copies - int(st["rows_per_dest"][my_rank])
+    saved_excl_self = (1.0 - (N - self_only_rows) / to_others) if to_others > 0 else 0.0
+    # cross-check straight from the routing table: per token, the distinct ranks other than this one
+    tk_me = np.asarray(topks[my_rank])
+    dest = np.where(tk_me >= 0, np.asarray(e2r)[np.clip(tk_me, 0, None)], -1)
+    n_others = [len(set(int(r) for r in row if r >= 0 and r != my_rank)) for row in dest]
+    assert to_others == sum(n_others) and N - self_only_rows == sum(1 for c in n_others if c > 0)
 
     # the launch that moves the receive side's bytes: the expander, in the pipelined schedule with
     # the next batch's index riding along (same bytes; the index's few MB are not counted)
@@ -591,6 +606,7 @@ def bench_dispatch(args, name: str) -> dict:
         "other_schedules_ms_per_step": other,
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "bytes_saved_vs_unicast": round(saved, 4),
+        "bytes_saved_vs_unicast_excluding_self": round(saved_excl_self, 4),
         "step_bytes": {"pack": pack_bytes, "unpack": unpack_bytes},
         "kernel_us": {k: round(v, 2) for k, v in kern_us.items()},
         "pack_unpack_only": {"us": round(pu_us, 2),

@@ -27,9 +27,16 @@
  *     visible on the device (bad expert id, capacity overflow, inconsistent
  *     received metadata) set MW_FLAG_* bits in the statistics block, the
  *     offending item is left out, and all kernels still terminate normally.
- *   - A context may be used from one stream at a time: calls on the same
- *     context share its workspace and race if they overlap.  The host-side
- *     context is not locked either: one host thread at a time per context.
+ *   - Work enqueued for one context shares its workspace in four parts:
+ *     (1) mw_plan; (2) mw_unpack, mw_unpack_packets, mw_unpack_index,
+ *     mw_unpack_expand, mw_unpack_expand_index_next (the part of `ctx` and,
+ *     for the index, of `next_ctx`) and mw_combine_gather; (3) mw_relay and
+ *     mw_relay_packets; (4) mw_sim_deliver.  Calls of one part race if they
+ *     overlap on the device; calls of different parts, and the packers
+ *     (mw_pack, mw_pack_quantize, mw_pack_packets, mw_plan_pack, the
+ *     AllGather calls), which use no workspace, may run on different streams
+ *     at once.  The host-side context is not locked: one host thread at a
+ *     time per context.
  *   - A context belongs to the device that was current at mw_ctx_create; an
  *     entry point called with another device current returns
  *     MW_ERR_INVALID_ARG and enqueues nothing.
