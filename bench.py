@@ -564,6 +564,33 @@ def bench_dispatch(args, name: str) -> dict:
         torch.cuda.synchronize()
         us["unpack_us"] = round(10.0 * a.elapsed_time(b), 2)
         us["rows_received"] = m_d
+
+        # a whole decode-sized step (send side, then receive side: three launches) issued call by
+        # call, and the same three launches captured once into a HIP graph and replayed
+        def step_d():
+            one_launch()
+            unpack_d()
+
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step_d()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step_d()
+        for label, fn in (("step_us", step_d), ("step_graph_replay_us", graph.replay)):
+            for _ in range(10):
+                fn()
+            (a, b), = new_events(torch, 1)
+            a.record()
+            for _ in range(100):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            us[label] = round(10.0 * a.elapsed_time(b), 2)
+        del graph
         decode["%d_tokens" % Td] = us
         ctx_d.close()
 

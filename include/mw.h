@@ -22,6 +22,11 @@
  *     entry point says so, never allocate or free device memory, and never
  *     take ownership of a caller buffer.  Buffers must stay valid until the
  *     enqueued work has completed.
+ *   - Entry points that take a stream launch kernels only (no memory-set or
+ *     copy nodes, no synchronisation) and keep nothing on the host that a
+ *     later call depends on, so a sequence of them can be captured into a HIP
+ *     graph and replayed; the statistics read-backs (mw_get_*_stats),
+ *     mw_ctx_create and mw_set_forwarding synchronise and stay outside.
  *   - Errors the host can see (null pointers, sizes out of range, misaligned
  *     rows) are returned synchronously and nothing is enqueued.  Errors only
  *     visible on the device (bad expert id, capacity overflow, inconsistent

@@ -17,7 +17,7 @@ namespace {
     } while (0)
 
 struct ws_layout {
-    int64_t eslot, plan_cnt[2], plan_state[2], flags, cnt, base, row_base, addr_cnt, recs, hits, row_map,
+    int64_t eslot, plan_cnt, plan_state, flags, cnt, base, row_base, addr_cnt, recs, hits, row_map,
         hop_bits, group_of_row, child_pos, sort_key, sort_sec, chunk_kept, row_cnt, row_start, total;
 };
 
@@ -78,8 +78,8 @@ ws_layout layout(const mw_config &c, int32_t L)
     int64_t o = 0;
     const int64_t ntok = c.max_tokens > 0 ? c.max_tokens : 1;
     w.eslot = o;      o += mw_align_up(4LL * (c.n_experts > 0 ? c.n_experts : 1), A);
-    for (int q = 0; q < 2; ++q) { w.plan_cnt[q] = o; o += mw_align_up(8LL * ntok, A); }
-    for (int q = 0; q < 2; ++q) { w.plan_state[q] = o; o += mw_align_up(4LL * MW_PLAN_STATE_WORDS, A); }
+    w.plan_cnt = o;   o += mw_align_up(8LL * ntok, A);
+    w.plan_state = o; o += mw_align_up(4LL * MW_PLAN_STATE_WORDS, A);
     w.flags = o;      o += A;
     w.cnt = o;        o += mw_align_up(4LL * ((int64_t)L * c.n_ranks > 0 ? (int64_t)L * c.n_ranks : 1), A);
     w.base = o;       o += mw_align_up(4LL * ((int64_t)L * c.n_ranks > 0 ? (int64_t)L * c.n_ranks : 1), A);
@@ -149,12 +149,8 @@ MW_API int32_t mw_ctx_create(const mw_config *cfg, void *workspace_dev, int64_t 
     ctx->x_row_bytes = xb; ctx->s_row_bytes = sb; ctx->row_bytes = xb + sb;
     char *b = (char *)workspace_dev;
     ctx->d_eslot = (int32_t *)(b + w.eslot);
-    for (int q = 0; q < 2; ++q) {
-        ctx->d_plan_cnt[q] = (uint64_t *)(b + w.plan_cnt[q]);
-        ctx->d_plan_state[q] = (uint32_t *)(b + w.plan_state[q]);
-        ctx->plan_T[q] = 0;
-    }
-    ctx->plan_parity = 0;
+    ctx->d_plan_cnt = (uint64_t *)(b + w.plan_cnt);
+    ctx->d_plan_state = (uint32_t *)(b + w.plan_state);
     ctx->d_sort_key = w.sort_key >= 0 ? (uint64_t *)(b + w.sort_key) : nullptr;
     ctx->d_sort_sec = w.sort_sec >= 0 ? (uint32_t *)(b + w.sort_sec) : nullptr;
     ctx->d_chunk_kept = w.chunk_kept >= 0 ? (uint32_t *)(b + w.chunk_kept) : nullptr;
@@ -192,10 +188,8 @@ MW_API int32_t mw_ctx_create(const mw_config *cfg, void *workspace_dev, int64_t 
     if (cfg->n_experts > 0)
         ok = ok && hipMemcpy(ctx->d_eslot, slot.data(), 4u * (size_t)cfg->n_experts, hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemset(ctx->d_flags, 0, 256) == hipSuccess;
-    for (int q = 0; q < 2; ++q) {
-        ok = ok && hipMemset(ctx->d_plan_cnt[q], 0, 8u * (size_t)(cfg->max_tokens > 0 ? cfg->max_tokens : 1)) == hipSuccess;
-        ok = ok && hipMemset(ctx->d_plan_state[q], 0, 4u * MW_PLAN_STATE_WORDS) == hipSuccess;
-    }
+    ok = ok && hipMemset(ctx->d_plan_cnt, 0, 8u * (size_t)(cfg->max_tokens > 0 ? cfg->max_tokens : 1)) == hipSuccess;
+    ok = ok && hipMemset(ctx->d_plan_state, 0, 4u * MW_PLAN_STATE_WORDS) == hipSuccess;
     if (cfg->max_hops > 0) ok = ok && hipMemset(ctx->d_relay_flags, 0, 256) == hipSuccess;
     ok = ok && hipDeviceSynchronize() == hipSuccess;
     if (!ok) { delete ctx; return MW_ERR_HIP; }

@@ -10,7 +10,7 @@
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-#define MW_PLAN_STATE_WORDS 264   // 256 histogram bins + kept tokens + flags (+ padding)
+#define MW_PLAN_STATE_WORDS 264   // 256 histogram bins + kept tokens + flags + workgroups done (+ padding)
 
 // (local expert slot, rank among the peer's rows for that expert); le < 0 = unused slot
 struct mw_hit { int32_t le; int32_t rank; };
@@ -66,10 +66,8 @@ struct mw_ctx {
     int n_cu;
     // workspace slices
     int32_t *d_eslot;       // [E] (rank << 16) | slot of expert e among the experts of its rank
-    uint64_t *d_plan_cnt[2];    // [max_tokens] packed per-token counters, double-buffered between plans
-    uint32_t *d_plan_state[2];  // [MW_PLAN_STATE_WORDS] rows per destination, kept tokens, flags
-    int plan_parity;            // which buffer pair the next mw_plan accumulates into
-    int plan_T[2];              // tokens whose counters in that buffer still need clearing
+    uint64_t *d_plan_cnt;       // [max_tokens] packed per-token counters; zero between plans
+    uint32_t *d_plan_state;     // [MW_PLAN_STATE_WORDS] rows per destination, kept tokens, flags, workgroups done; zero between plans
     uint64_t *d_sort_key;       // [max_tokens rounded up to 1024] sorted chunks of the large-batch plan (or null)
     uint32_t *d_sort_sec;       // same count: second sort word
     uint32_t *d_chunk_kept;     // [64] kept tokens per chunk

@@ -25,8 +25,9 @@
 //             descriptors; a group's row count is the number of equal bitmaps.  Writing is
 //             spread over many workgroups because one CU retires only about one cache line
 //             of scattered stores per cycle.
-// The count and histogram buffers are double-buffered between consecutive plans: a plan
-// clears the buffers the previous plan used, so no extra clearing launch is needed.
+// The count and histogram buffers are zero between plans: the k_groups workgroup that is the
+// last to have read them clears them, so there is no clearing launch and no host-side state
+// (a captured mw_plan can be replayed).
 // Batches above 8192 tokens replace k_rank by k_chunk_sort + k_merge_rank (sorted chunks,
 // ranks by binary search: T log T instead of T^2); batches of at most 256 tokens can take
 // k_plan_pack, which plans and packs in one launch.
@@ -36,7 +37,7 @@ namespace {
 
 constexpr int kBlock = 256;
 constexpr uint64_t kField = 0x1fffffull;      // 21-bit fields of the packed counter
-constexpr int kPsKept = 256, kPsFlags = 257;  // plan state words after the 256 histogram bins
+constexpr int kPsKept = 256, kPsFlags = 257, kPsDone = 258;  // plan state words after the 256 histogram bins
 
 // Destination bitmap of one token (Section 4.1): ids are fetched in independent batches.
 __device__ __forceinline__ void token_mask(const int32_t *__restrict__ row, int K,
@@ -219,10 +220,8 @@ __global__ __launch_bounds__(kBlock) void k_rows_from_counters(int T, const unsi
 
 template <bool kByRow>
 __global__ __launch_bounds__(kBlock) void k_groups(const uint64_t *__restrict__ mask, int T, uint64_t row_bytes,
-                                                   const unsigned long long *__restrict__ cnt,
+                                                   unsigned long long *__restrict__ cnt,
                                                    uint32_t *__restrict__ pstate,
-                                                   unsigned long long *__restrict__ cnt_other, int T_other,
-                                                   uint32_t *__restrict__ pstate_other,
                                                    int32_t *__restrict__ perm, mw_group_desc *__restrict__ desc,
                                                    mw_send_stats *__restrict__ stats,
                                                    const unsigned long long *__restrict__ row_cnt,
@@ -272,9 +271,6 @@ __global__ __launch_bounds__(kBlock) void k_groups(const uint64_t *__restrict__ 
     mw_block_exscan(starts_before, scratch, &g_base);
     mw_block_exscan(starts_total, scratch, &G);                // ends with a barrier: tok[] is complete
 
-    // clear what the previous plan used, for the plan after this one
-    for (int z = blockIdx.x * kBlock + tid; z < T_other; z += gridDim.x * kBlock) cnt_other[z] = 0;
-
     const uint32_t i = i0 + tid;
     uint32_t st = 0;
     int32_t t = 0;
@@ -317,8 +313,29 @@ __global__ __launch_bounds__(kBlock) void k_groups(const uint64_t *__restrict__ 
             stats->error_flags = pstate[kPsFlags];
             stats->reserved0 = 0;
         }
-        for (int r = tid; r < MW_PLAN_STATE_WORDS; r += kBlock) pstate_other[r] = 0;
     }
+
+    // Leave the counters and the plan state zero for the next plan.  Nobody may clear them
+    // while a workgroup still reads them: every workgroup reports when it has read all it
+    // needs (its loads have returned: their values were used above, and the barrier waits for
+    // the rest), and the one that reports last does the clearing.  The counter of reports is a
+    // device-scope atomic; the zeros are ordinary stores, read by the next plan's kernels only.
+    // With row-indexed arrays this kernel does not read the counters at all, and every
+    // workgroup clears its own slice.
+    __shared__ uint32_t i_am_last;
+    __syncthreads();
+    if (tid == 0)
+        i_am_last = __hip_atomic_fetch_add(&pstate[kPsDone], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                    gridDim.x - 1u ? 1u : 0u;
+    if constexpr (kByRow) {
+        if (i0 + tid < (uint32_t)T) cnt[i0 + tid] = 0;
+    }
+    __syncthreads();
+    if (!i_am_last) return;
+    if constexpr (!kByRow) {
+        for (int z = tid; z < T; z += kBlock) cnt[z] = 0;
+    }
+    for (int r = tid; r < MW_PLAN_STATE_WORDS; r += kBlock) pstate[r] = 0;
 }
 
 __global__ __launch_bounds__(256) void k_plan_allgather(int R, uint64_t shard_bytes, mw_group_desc *desc,
@@ -697,9 +714,9 @@ int32_t mw_launch_plan(mw_ctx *ctx, const int32_t *topk, int32_t T, uint64_t *ma
                        mw_group_desc *desc, mw_send_stats *stats, hipStream_t s)
 {
     const int K = ctx->cfg.top_k, E = ctx->cfg.n_experts;
-    const int cur = ctx->plan_parity, oth = cur ^ 1;
-    unsigned long long *cnt = (unsigned long long *)ctx->d_plan_cnt[cur];
-    unsigned long long *cnt_o = (unsigned long long *)ctx->d_plan_cnt[oth];
+    // both start out zero: mw_ctx_create cleared them, every plan's last kernel clears them again
+    unsigned long long *cnt = (unsigned long long *)ctx->d_plan_cnt;
+    uint32_t *pstate = ctx->d_plan_state;
     const int tb = (T + kBlock - 1) / kBlock;
     const bool has_key = ctx->mask_words == 1 || K <= 8;
     if (T >= (ctx->mask_words == 1 ? kChunkFromOneWord : kChunkFromKeyed) && has_key && ctx->d_sort_key) {
@@ -711,13 +728,13 @@ int32_t mw_launch_plan(mw_ctx *ctx, const int32_t *topk, int32_t T, uint64_t *ma
         mw_timed tm(ctx, MW_KERNEL_PLAN_RANK, s);
         if (ctx->mask_words == 1) {
             hipLaunchKernelGGL(k_chunk_sort<1>, dim3(nc), dim3(kChunk), 0, s, topk, T, K, ctx->d_eslot, E, mask,
-                               ctx->d_plan_state[cur], ctx->d_sort_key, ctx->d_sort_sec, ctx->d_chunk_kept);
-            hipLaunchKernelGGL(k_merge_rank<1>, dim3(nc, parts), dim3(kChunk), 0, s, T, nc, ctx->d_plan_state[cur],
+                               pstate, ctx->d_sort_key, ctx->d_sort_sec, ctx->d_chunk_kept);
+            hipLaunchKernelGGL(k_merge_rank<1>, dim3(nc, parts), dim3(kChunk), 0, s, T, nc, pstate,
                                ctx->d_sort_key, ctx->d_sort_sec, ctx->d_chunk_kept, cnt);
         } else {
             hipLaunchKernelGGL(k_chunk_sort<4>, dim3(nc), dim3(kChunk), 0, s, topk, T, K, ctx->d_eslot, E, mask,
-                               ctx->d_plan_state[cur], ctx->d_sort_key, ctx->d_sort_sec, ctx->d_chunk_kept);
-            hipLaunchKernelGGL(k_merge_rank<4>, dim3(nc, parts), dim3(kChunk), 0, s, T, nc, ctx->d_plan_state[cur],
+                               pstate, ctx->d_sort_key, ctx->d_sort_sec, ctx->d_chunk_kept);
+            hipLaunchKernelGGL(k_merge_rank<4>, dim3(nc, parts), dim3(kChunk), 0, s, T, nc, pstate,
                                ctx->d_sort_key, ctx->d_sort_sec, ctx->d_chunk_kept, cnt);
         }
     } else if (T > 0) {
@@ -740,7 +757,7 @@ int32_t mw_launch_plan(mw_ctx *ctx, const int32_t *topk, int32_t T, uint64_t *ma
         mw_timed tm(ctx, MW_KERNEL_PLAN_RANK, s);
 #define MW_RANK(W_, KEYED_)                                                                                 \
     hipLaunchKernelGGL((k_rank<W_, KEYED_>), grid, block, lds, s, topk, T, K, ctx->d_eslot, E, slice, mask, cnt, \
-                       ctx->d_plan_state[cur])
+                       pstate)
         if (keyed) MW_RANK(4, true);
         else if (W == 1) MW_RANK(1, false);
         else if (W == 2) MW_RANK(2, false);
@@ -751,20 +768,15 @@ int32_t mw_launch_plan(mw_ctx *ctx, const int32_t *topk, int32_t T, uint64_t *ma
     {
         mw_timed tm(ctx, MW_KERNEL_PLAN_GROUPS, s);
         if (T >= kRowsFrom && ctx->d_row_cnt) {
-            hipLaunchKernelGGL(k_rows_from_counters, dim3(tb), dim3(kBlock), 0, s, T, cnt, ctx->d_plan_state[cur], perm,
+            hipLaunchKernelGGL(k_rows_from_counters, dim3(tb), dim3(kBlock), 0, s, T, cnt, pstate, perm,
                                (unsigned long long *)ctx->d_row_cnt, ctx->d_row_start);
             hipLaunchKernelGGL(k_groups<true>, dim3(tb), dim3(kBlock), 0, s, mask, T, (uint64_t)ctx->row_bytes, cnt,
-                               ctx->d_plan_state[cur], cnt_o, ctx->plan_T[oth], ctx->d_plan_state[oth], perm, desc, stats,
-                               (const unsigned long long *)ctx->d_row_cnt, ctx->d_row_start);
+                               pstate, perm, desc, stats, (const unsigned long long *)ctx->d_row_cnt, ctx->d_row_start);
         } else {
             hipLaunchKernelGGL(k_groups<false>, dim3(tb > 0 ? tb : 1), dim3(kBlock), 0, s, mask, T,
-                               (uint64_t)ctx->row_bytes, cnt, ctx->d_plan_state[cur], cnt_o, ctx->plan_T[oth],
-                               ctx->d_plan_state[oth], perm, desc, stats, nullptr, nullptr);
+                               (uint64_t)ctx->row_bytes, cnt, pstate, perm, desc, stats, nullptr, nullptr);
         }
     }
-    ctx->plan_T[oth] = 0;        // cleared by this plan
-    ctx->plan_T[cur] = T;        // to be cleared by the next one
-    ctx->plan_parity = oth;
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;
 }

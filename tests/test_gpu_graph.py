@@ -1,0 +1,130 @@
+"""GPU: the entry points only enqueue kernels and keep no state on the host between calls, so a
+step can be captured into a HIP graph (through torch's capture of the current stream) and
+replayed.  Every replay is checked against the CPU oracle, with the program's own eager work --
+other plans on the same context, cleared outputs, fresh inputs -- and synchronisations between
+the replays."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2605_22428_amd import binding as B
+from paper_2605_22428_amd import workloads as W
+
+import gpu_harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def _clear(*tensors):
+    for t in tensors:
+        if t is not None:
+            t.zero_()
+
+
+def _check_send_buffers(w, sb, ctx, tk, x, sc):
+    e2r = W.expert_to_rank(w)
+    m, perm, desc, ost = ref.plan(tk, e2r, w.n_ranks, w.row_bytes)
+    packed, src, rtk = ref.pack(x, sc, tk, perm)
+    st = ctx.mw_get_send_stats(sb.stats)
+    N, G = int(st["n_rows"]), int(st["n_groups"])
+    assert (N, G, int(st["error_flags"])) == (len(perm), len(desc), 0)
+    H.assert_same_bytes(H.host(sb.mask).view(np.uint64)[: len(tk)], m, "mask")
+    H.assert_same_bytes(H.host(sb.perm)[:N], perm, "perm")
+    H.assert_same_bytes(H.host(sb.desc).reshape(-1).view(B.DESC_DTYPE)[:G].view(np.uint8), desc.view(np.uint8), "desc")
+    H.assert_same_bytes(st["rows_per_dest"], ost["rows_per_dest"], "rows_per_dest")
+    assert int(st["unicast_bytes"]) == int(ost["unicast_bytes"])
+    H.assert_same_bytes(H.host(sb.packed)[:N], packed, "packed rows")
+    H.assert_same_bytes(H.host(sb.row_src_token)[:N], src, "row_src_token")
+    H.assert_same_bytes(H.host(sb.row_topk)[:N], rtk, "row_topk")
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_captured_step_replays(fused):
+    """plan + pack (or the one-launch mw_plan_pack) and unpack of received regions in one graph;
+    four replays, the sender's inputs replaced before each, eager plans of other batch sizes on
+    the same context in between."""
+    T = 200 if fused else 333
+    w = W.DispatchWorkload("graph", 77, 8, 16, 2, T, 256, "bf16", "uniform")
+    my_rank, e2r = 3, W.expert_to_rank(w)
+    _say("graph replay", "fused" if fused else "plan+pack", "T", T)
+    ctx = H.make_ctx(w, my_rank, max_tokens=512)
+
+    # what this rank receives: every peer's delivery, built eagerly once (GPU) / by the oracle
+    recs, bufs = [], []
+    for p in range(w.n_ranks):
+        tk = W.topk_ids(w, 1, p)
+        x, sc = W.payload_rows(w, 1, p)
+        recs.append(H.shrink(H.GpuSend(ctx, tk, x, sc).deliver(my_rank)))
+        _, perm, desc, _ = ref.plan(tk, e2r, w.n_ranks, w.row_bytes)
+        packed, src, rtk = ref.pack(x, sc, tk, perm)
+        bufs.append(ref.deliver(desc, packed, src, rtk, my_rank))
+    cap = max(1, sum(r["n_rows"] for r in recs) * 2)
+    expect_recv = ref.unpack(bufs, w.top_k, e2r, my_rank, 2 * w.hidden, 0, cap)
+    table = B.peers_table(recs, H.DEV)
+
+    # the graph's fixed buffers
+    tk_d = torch.zeros((T, w.top_k), dtype=torch.int32, device=H.DEV)
+    x_d = torch.zeros((T, w.hidden), dtype=torch.int16, device=H.DEV)
+    sb, rv = B.SendBuffers(ctx, T), B.RecvBuffers(ctx, cap)
+    other = B.SendBuffers(ctx, 512)
+
+    def step():
+        if fused:
+            ctx.mw_plan_pack(tk_d, x_d, None, sb.mask, sb.perm, sb.desc, sb.stats, sb.packed, sb.row_src_token,
+                             sb.row_topk)
+        else:
+            ctx.mw_plan(tk_d, sb.mask, sb.perm, sb.desc, sb.stats)
+            ctx.mw_pack(x_d, None, tk_d, sb.perm, sb.stats, sb.packed, sb.row_src_token, sb.row_topk)
+        ctx.mw_unpack(table, w.n_ranks, rv.out_rows, rv.out_scales, cap, rv.out_src_peer, rv.out_src_token,
+                      rv.expert_offsets, rv.stats)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                            # once eagerly on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    torch.cuda.synchronize()
+
+    class _Got:                                           # what check_unpack reads
+        pass
+
+    for rep in range(4):
+        seed = 10 + rep
+        tk = W.topk_ids(w, seed, my_rank)
+        if rep == 2:
+            tk[::7] = -1                                  # fewer rows than the capture saw
+        x, _ = W.payload_rows(w, seed, my_rank)
+        tk_d.copy_(H.dev(tk))
+        x_d.copy_(H.dev(x).view(torch.int16))
+        # eager work on the same context between the replays: plans of other sizes
+        for t_other in (512, 57):
+            ow = W.scaled(w, n_tokens=t_other)
+            ctx.mw_plan(H.dev(W.topk_ids(ow, seed, 0)), other.mask, other.perm, other.desc, other.stats)
+        _clear(sb.mask, sb.desc, sb.stats, sb.packed, sb.row_topk, rv.out_rows, rv.expert_offsets, rv.stats)
+        sb.perm.fill_(-1); sb.row_src_token.fill_(-1); rv.out_src_peer.fill_(-1); rv.out_src_token.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        _say("  replay", rep)
+        _check_send_buffers(w, sb, ctx, tk, x, None)
+        g = _Got()
+        g.ctx, g.buf = ctx, rv
+        g.stats = ctx.mw_get_recv_stats(rv.stats)
+        g.Q = int(g.stats["n_out_rows"])
+        g.host_out = lambda: H.GpuUnpack.host_out(g)
+        H.check_unpack(g, expect_recv, "replay %d" % rep)
+        # and the eager calls still agree after a replay
+        if rep == 1:
+            step()
+            torch.cuda.synchronize()
+            _check_send_buffers(w, sb, ctx, tk, x, None)
+    ctx.close()

@@ -475,7 +475,7 @@ def test_plan_of_large_batches(T, R, E, K):
     ctx = H.make_ctx(w, 0, max_recv_rows=1)
     tk_d = H.dev(tk)
     sb = B.SendBuffers(ctx, T)
-    for _ in range(2):                                   # twice: the counters' double buffering
+    for _ in range(2):                                   # twice: the plan leaves its counters clean
         ctx.mw_plan(tk_d, sb.mask, sb.perm, sb.desc, sb.stats)
     st = ctx.mw_get_send_stats(sb.stats)
     m, perm, desc, ost = ref.plan(tk, e2r, R, w.row_bytes)
