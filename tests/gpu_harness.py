@@ -114,6 +114,20 @@ def shrink(rec: dict) -> dict:
                 row_topk=rec["row_topk"][: max(n, 1)].clone(), n_desc=g, n_rows=n)
 
 
+def oracle_send(w: W.DispatchWorkload, topk: np.ndarray, x: np.ndarray, scales):
+    """The oracle's own send side: (desc, packed rows, row_src_token, row_topk).  What the oracle
+    is given further down the path (delivery, relay, unpack) is always this, never a GPU buffer."""
+    _, perm, desc, _ = ref.plan(topk, W.expert_to_rank(w), w.n_ranks, w.row_bytes)
+    packed, src, rtk = ref.pack(x, scales, topk, perm)
+    return desc, packed, src, rtk
+
+
+def oracle_packets(w: W.DispatchWorkload, topk: np.ndarray, x: np.ndarray, scales) -> np.ndarray:
+    """The oracle's own packets of one sender."""
+    mask, perm, _, _ = ref.plan(topk, W.expert_to_rank(w), w.n_ranks, w.row_bytes)
+    return ref.pack_packets(x, scales, topk, mask, perm)
+
+
 class GpuUnpack:
     def __init__(self, ctx: B.Context, records: Sequence[dict], capacity: int):
         self.ctx = ctx

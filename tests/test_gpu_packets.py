@@ -75,7 +75,7 @@ def run_packets(w, seed, my_rank, lazy=False, check_senders=None, complete_too=F
         if w.row_format == "fp8":
             s_dev = torch.zeros((w.n_tokens, w.hidden // 128), dtype=torch.float32, device=H.DEV)
     gen = torch.Generator(device="cpu"); gen.manual_seed(seed)
-    toks, kept, complete, shuffled = [], [], [], []
+    toks, kept, complete, shuffled, shuffled_oracle = [], [], [], [], []
     for p in range(w.n_ranks):
         tk = topks[p]
         if edit is not None:
@@ -108,7 +108,12 @@ def run_packets(w, seed, my_rank, lazy=False, check_senders=None, complete_too=F
         kept.append(mine)
         if complete_too:
             complete.append(g.packets[: g.N].clone())
-            shuffled.append(mine[torch.randperm(mine.shape[0], generator=gen).to(H.DEV)].clone())
+            order = torch.randperm(mine.shape[0], generator=gen)
+            shuffled.append(mine[order.to(H.DEV)].clone())
+            # the oracle parses its own packets, put into the same order
+            o_mine = ref.deliver_packets(H.oracle_packets(w, tk, x, sc), my_rank)
+            assert len(o_mine) == mine.shape[0]
+            shuffled_oracle.append(o_mine[order.numpy()])
         del g
     m_rows = sum(int(k.shape[0]) for k in kept)
     cap = max(1, m_rows * min(w.top_k, w.experts_per_rank))
@@ -125,7 +130,7 @@ def run_packets(w, seed, my_rank, lazy=False, check_senders=None, complete_too=F
         assert int(st["error_flags"]) == 0
         same(got, want, "packets in any order")
         xrb = 2 * w.hidden if w.row_format == "bf16" else w.hidden
-        o2 = ref.unpack_packets([H.host(k) for k in shuffled], w.top_k, e2r, my_rank, xrb, w.row_bytes - xrb, cap)
+        o2 = ref.unpack_packets(shuffled_oracle, w.top_k, e2r, my_rank, xrb, w.row_bytes - xrb, cap)
         same(got, o2, "vs the oracle's packet parser")
     _say("  packets received", m_rows, "output rows", int(st["n_out_rows"]))
     ctx.close()
@@ -190,17 +195,20 @@ def test_empty_regions_and_bad_headers():
     got, st = unpack_packets(ctx, [mine], 1000)
     same(got, want, "one peer")
     # a header that says K = 3: that packet is left out and flagged; the others are delivered
-    bad = mine.clone()
+    o_mine = ref.deliver_packets(H.oracle_packets(w, tk, x, None), 0)
+    H.assert_same_bytes(H.host(mine), o_mine, "packets naming rank 0")
     victim = 4
-    bad[victim, 36] = 3
-    tok = int(H.host(bad)[victim, 32:36].view(np.int32)[0])
+    bad_o = o_mine.copy()
+    bad_o[victim, 36] = 3
+    bad = H.dev(bad_o)
+    tok = int(bad_o[victim, 32:36].view(np.int32)[0])
     tk2 = tk.copy(); tk2[tok] = -1
     want2 = ref.dispatch_plain([(tk2, x, None)], e2r, 0, 1000)
     got, st = unpack_packets(ctx, [bad], 1000)
     assert int(st["error_flags"]) == B.MW_FLAG_BAD_DESC
     same(got, want2, "bad header left out")
     with pytest.raises(ref.OracleError):
-        ref.unpack_packets([H.host(bad)], w.top_k, e2r, 0, w.row_bytes, 0, 1000)
+        ref.unpack_packets([bad_o], w.top_k, e2r, 0, w.row_bytes, 0, 1000)
     # the flag does not stick
     got, st = unpack_packets(ctx, [mine], 1000)
     assert int(st["error_flags"]) == 0
@@ -245,7 +253,8 @@ def test_relay_packets_children_and_accounting(which):
     x, sc = W.payload_rows(w, 3, me)
     g = GpuPackets(ctx, tk, x, sc)
     kids, st = gpu_relay_packets(ctx, g.packets, g.N, next_hop, n_hops, w.n_tokens)
-    parent = H.host(g.packets)[: g.N]
+    parent = H.oracle_packets(w, tk, x, sc)
+    H.assert_same_bytes(H.host(g.packets)[: g.N], parent, "packets before the relay")
     pb = parent.shape[1]
     total = 0
     for h in range(n_hops):
@@ -303,7 +312,7 @@ def test_relay_packets_capacity_and_bad_headers():
     x, _ = W.payload_rows(w, 1, 0)
     g = GpuPackets(ctx, tk, x, None)
     next_hop = np.array([0, 0, 0, 0, 1, 1, 1, 1], dtype=np.int32)
-    parent = H.host(g.packets)[: g.N]
+    parent = H.oracle_packets(w, tk, x, None)
     want0, _, _ = ref.relay_packets_child(parent, next_hop, 2, 0)
     cap = len(want0) // 2
     kids, st = gpu_relay_packets(ctx, g.packets, g.N, next_hop, 2, cap)

@@ -519,11 +519,12 @@ def test_invalid_expert_ids_set_the_error_flag():
 def test_output_capacity_overflow_is_flagged_and_bounded():
     w = _small(T=128)
     ctx = H.make_ctx(w, 0)
-    recs, toks = [], []
+    recs, toks, bufs = [], [], []
     for p in range(w.n_ranks):
         tk = W.topk_ids(w, 2, p); x, _ = W.payload_rows(w, 2, p)
         recs.append(H.shrink(H.GpuSend(ctx, tk, x, None).deliver(0)))
         toks.append((tk, x, None))
+        bufs.append(ref.deliver(*H.oracle_send(w, tk, x, None), 0))
     o1 = ref.dispatch_plain(toks, W.expert_to_rank(w), 0, 10 ** 6)
     Q = len(o1[2])
     cap = Q // 2
@@ -532,7 +533,7 @@ def test_output_capacity_overflow_is_flagged_and_bounded():
     got = gu.host_out()
     H.assert_same_bytes(got[0], o1[0][:cap], "rows below capacity are still exact")
     with pytest.raises(ref.OracleError):
-        ref.unpack([H.record_host(r) for r in recs], w.top_k, W.expert_to_rank(w), 0, w.row_bytes, 0, cap)
+        ref.unpack(bufs, w.top_k, W.expert_to_rank(w), 0, w.row_bytes, 0, cap)
     ctx.close()
 
 

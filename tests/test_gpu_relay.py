@@ -92,7 +92,7 @@ def test_relay_children_match_oracle_random_tables(fmt, seed):
     tk, x, sc, g = _send(ctx, w, seed, 0)
     H.check_send(w, g, tk, x, sc)
     ch, st, _ = gpu_relay(ctx, g.full_record(), next_hop, n_hops, w.n_tokens)
-    parent = (g.host_plan()[2],) + g.host_pack()
+    parent = H.oracle_send(w, tk, x, sc)
     check_children(ch, st, parent, next_hop, n_hops, w.row_bytes)
     ctx.close()
 
@@ -101,7 +101,7 @@ def test_relay_identity_and_single_hop_tables():
     w = W.scaled(W.C1, n_tokens=130, hidden=512)
     ctx = _ctx(w, 0, 64)
     tk, x, sc, g = _send(ctx, w, 1, 0)
-    parent = (g.host_plan()[2],) + g.host_pack()
+    parent = H.oracle_send(w, tk, x, sc)
     ident = np.arange(w.n_ranks, dtype=np.int32)
     ch, st, _ = gpu_relay(ctx, g.full_record(), ident, w.n_ranks, w.n_tokens)
     check_children(ch, st, parent, ident, w.n_ranks, w.row_bytes)
@@ -126,7 +126,7 @@ def test_relay_all_equal_bitmaps_one_long_group():
     assert g.G == 1 and g.N == T
     next_hop = np.array([0, 0, 1, 1, 2, 2, 3, 3], dtype=np.int32)
     ch, st, _ = gpu_relay(ctx, g.full_record(), next_hop, 4, T)
-    check_children(ch, st, (g.host_plan()[2],) + g.host_pack(), next_hop, 4, w.row_bytes)
+    check_children(ch, st, H.oracle_send(w, tk, x, None), next_hop, 4, w.row_bytes)
     assert st["rows_per_hop"][:4].tolist() == [0, T, T, 0]
     ctx.close()
 
@@ -180,7 +180,7 @@ def test_relay_capacity_bad_descriptors_and_host_errors():
     cap = 50
     ch, st, _ = gpu_relay(ctx, g.full_record(), next_hop, 3, cap)
     assert int(st["error_flags"]) & B.MW_FLAG_OUT_CAPACITY
-    parent = (g.host_plan()[2],) + g.host_pack()
+    parent = H.oracle_send(w, tk, x, sc)
     for h in range(3):
         want = ref.relay_child(*parent, next_hop, 3, h)
         gg, n = int(st["groups_per_hop"][h]), int(st["rows_per_hop"][h])
@@ -191,7 +191,7 @@ def test_relay_capacity_bad_descriptors_and_host_errors():
     assert int(st["forward_bytes"]) == w.row_bytes * int(st["rows_per_hop"][:3].sum())
     # dropped: a descriptor reaching outside the buffer (3), its successor, which now starts
     # inside the range 3 claims (4), and one overlapping its predecessor (7)
-    desc = g.host_plan()[2].copy()
+    desc = parent[0].copy()
     desc["row_count"][3] += 1000
     desc["row_offset"][7] -= 1
     rec = g.full_record()
@@ -204,13 +204,12 @@ def test_relay_capacity_bad_descriptors_and_host_errors():
     assert st["rows_per_hop"][:3].tolist() == rph.tolist() and int(st["unicast_bytes"]) == uni
     # a bitmap that names a rank this configuration does not have: that bit is forwarded nowhere
     # and flagged, everything else is as without it
-    desc = g.host_plan()[2].copy()
+    desc = parent[0].copy()
     desc["mask"][5][1] |= np.uint64(1) << np.uint64(3)            # rank 67 of 64
     desc["mask"][6][2] |= np.uint64(1)                            # rank 128
     rec = dict(g.full_record(), desc=H.dev(desc.view(np.uint8).reshape(-1, B.DESC_BYTES)))
     ch, st, _ = gpu_relay(ctx, rec, next_hop, 3, w.n_tokens)
     assert int(st["error_flags"]) == B.MW_FLAG_BAD_RANK
-    parent = (g.host_plan()[2],) + g.host_pack()
     for h in range(3):
         want = ref.relay_child(*parent, next_hop, 3, h)
         got = child_host(ch, st, h)
@@ -240,7 +239,7 @@ def test_relay_full_size_c1_two_level_topology():
     x, _ = W.payload_full(w, W.BASE_SEED, 0, tokens)
     g = H.GpuSend(ctx, tk, x, None)
     ch, st, _ = gpu_relay(ctx, g.full_record(), next_hop, n_hops, w.n_tokens)
-    parent = (g.host_plan()[2],) + g.host_pack()
+    parent = H.oracle_send(w, tk, x, None)
     check_children(ch, st, parent, next_hop, n_hops, w.row_bytes, hops=(0, 7, 8, 14))
     saved = 1.0 - int(st["forward_bytes"]) / int(st["unicast_bytes"])
     _say("  copies per token", int(st["forward_bytes"]) / w.row_bytes / g.N, "saved vs unicast", round(saved, 4))
