@@ -410,7 +410,8 @@ __device__ __forceinline__ bool mask_less(const uint64_t *a, const uint64_t *b)
     return lt;
 }
 
-template <int W>
+// kKeyed (bitmaps of more than one word, top_k <= 8): the all-pairs walk compares short keys.
+template <int W, bool kKeyed>
 __global__ __launch_bounds__(kBlock) void k_plan_pack(const int32_t *__restrict__ topk, int T, int K,
                                                       const int32_t *__restrict__ eslot, int E,
                                                       const u32x4 *__restrict__ x, const u32x4 *__restrict__ scales,
@@ -432,6 +433,9 @@ __global__ __launch_bounds__(kBlock) void k_plan_pack(const int32_t *__restrict_
     if (t < T) token_mask(topk + (size_t)t * K, K, eslot, E, m, bad);
 #pragma unroll
     for (int w = 0; w < W; ++w) smask[t * W + w] = m[w];
+    __shared__ mw_short_key skey[kKeyed ? kFusedMax : 1];
+    mw_short_key mk = {0ull, 0u, 0u};
+    if constexpr (kKeyed) { mk = short_key(m); skey[t] = mk; }
     hist[t] = 0;
     if (t == 0) any_bad = 0;
     const bool any = (m[0] | m[1] | m[2] | m[3]) != 0;
@@ -439,23 +443,52 @@ __global__ __launch_bounds__(kBlock) void k_plan_pack(const int32_t *__restrict_
     mw_block_exscan(any ? 1u : 0u, scratch, &N);          // its barriers also publish smask
     if (bad) atomicOr(&any_bad, 1u);
 
-    // Packed row of token t = number of kept tokens u with (bitmap, u) < (bitmap, t).  Whether
-    // u < t is the same for the whole wavefront except among its own 64 tokens, so the walk
-    // splits into "bitmap <= mine" before them, the full test among them, "bitmap < mine" after
-    // them.  An empty bitmap is below every kept one: all T - N of them are counted and taken
-    // off again.
-    const int w0 = min(t & ~63, T), w1 = min(w0 + 64, T);
+    // Packed row of token t = number of kept tokens u with (bitmap, u) < (bitmap, t).  The
+    // walk takes eight tokens at a time -- eight LDS reads in flight, then eight compares --
+    // because a compare is a few cycles and an LDS round trip about a hundred.  Whether u < t
+    // is the same for the whole wavefront except among its own 64 tokens: "bitmap <= mine"
+    // before them, the full test among them, "bitmap < mine" after them.  Slots from T up to
+    // the next multiple of eight hold empty bitmaps (their lanes wrote zeros); an empty bitmap is
+    // below every kept one: all of them are counted and taken off again.
+    const int T8 = (T + 7) & ~7;
+    const int w0 = t & ~63, w1 = w0 + 64;
     uint32_t c = 0;
-#pragma unroll 4
-    for (int u = 0; u < w0; ++u) c += mask_less<W>(m, smask + u * W) ? 0u : 1u;
-#pragma unroll 4
-    for (int u = w0; u < w1; ++u) {
-        const uint64_t *q = smask + u * W;
-        c += (mask_less<W>(q, m) || (u < t && !mask_less<W>(m, q))) ? 1u : 0u;
+    for (int u0 = 0; u0 < T8; u0 += 8) {
+        bool lt[8], eq[8];
+        if constexpr (kKeyed) {
+            mw_short_key q[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) q[k] = skey[u0 + k];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const bool keq = q[k].key == mk.key;
+                lt[k] = q[k].key < mk.key || (keq && q[k].flag < mk.flag);
+                eq[k] = keq && q[k].flag == mk.flag;
+            }
+        } else {
+            uint64_t q[8][W];
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+#pragma unroll
+                for (int w = 0; w < W; ++w) q[k][w] = smask[(u0 + k) * W + w];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                lt[k] = mask_less<W>(q[k], m);
+                eq[k] = !lt[k] && !mask_less<W>(m, q[k]);
+            }
+        }
+        if (u0 + 8 <= w0) {                         // wave-uniform: all eight before this wave's tokens
+#pragma unroll
+            for (int k = 0; k < 8; ++k) c += (lt[k] || eq[k]) ? 1u : 0u;
+        } else if (u0 >= w1) {                      // all eight after them
+#pragma unroll
+            for (int k = 0; k < 8; ++k) c += lt[k] ? 1u : 0u;
+        } else {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) c += (lt[k] || (eq[k] && u0 + k < t)) ? 1u : 0u;
+        }
     }
-#pragma unroll 4
-    for (int u = w1; u < T; ++u) c += mask_less<W>(smask + u * W, m) ? 1u : 0u;
-    const uint32_t p = c - ((uint32_t)T - N);
+    const uint32_t p = c - ((uint32_t)T8 - N);
     if (any) tok[p] = t;
     mw_lds_barrier();
 
@@ -792,15 +825,16 @@ int32_t mw_launch_plan_pack(mw_ctx *ctx, const int32_t *topk, int32_t T, const v
     const int K = ctx->cfg.top_k, E = ctx->cfg.n_experts;
     const uint64_t rb = (uint64_t)ctx->row_bytes;
     mw_timed tm(ctx, MW_KERNEL_PLAN_PACK, s);
-#define MW_FUSED(W)                                                                                              \
-    hipLaunchKernelGGL(k_plan_pack<W>, grid, block, 0, s, topk, T, K, ctx->d_eslot, E, (const u32x4 *)x,         \
+#define MW_FUSED(W, KEYED)                                                                                        \
+    hipLaunchKernelGGL((k_plan_pack<W, KEYED>), grid, block, 0, s, topk, T, K, ctx->d_eslot, E, (const u32x4 *)x, \
                        (const u32x4 *)scales, xc, sc, rb, mask, perm, desc, stats, (u32x4 *)packed, row_src_token, \
                        row_topk)
+    const bool keyed = K <= 8;              // at most eight bits per bitmap: short keys
     switch (ctx->mask_words) {
-    case 1: MW_FUSED(1); break;
-    case 2: MW_FUSED(2); break;
-    case 3: MW_FUSED(3); break;
-    default: MW_FUSED(4); break;
+    case 1: MW_FUSED(1, false); break;
+    case 2: if (keyed) MW_FUSED(2, true); else MW_FUSED(2, false); break;
+    case 3: if (keyed) MW_FUSED(3, true); else MW_FUSED(3, false); break;
+    default: if (keyed) MW_FUSED(4, true); else MW_FUSED(4, false); break;
     }
 #undef MW_FUSED
     MW_HIP_CHECK(hipGetLastError());

@@ -49,6 +49,9 @@ def test_wide_bitmaps(T):
     _one(W.scaled(W.C3, n_tokens=T, hidden=512), 1, 100)
     # 128 ranks: two words
     _one(W.DispatchWorkload("r128", 21, 128, 256, 6, T, 256, "bf16", "uniform"), 2, 77)
+    # twelve ids per token: more bits than a short key holds, whole bitmaps are compared
+    _one(W.DispatchWorkload("k12", 22, 256, 512, 12, T, 256, "bf16", "uniform"), 3, 200)
+    _one(W.DispatchWorkload("k9", 23, 192, 192, 9, T, 256, "bf16", "uniform"), 4, 5)
 
 
 def test_full_width_rows_bf16_and_fp8():
