@@ -557,3 +557,35 @@ def test_host_side_argument_errors():
     assert ei.value.status == B.MW_ERR_CAPACITY
     assert lib.mw_plan(None, None, 0, None, None, None, None, None) == B.MW_ERR_INVALID_ARG
     ctx.close()
+
+
+# ------------------------------------------------------------------ row sizes across the launch shapes
+@pytest.mark.parametrize("hidden", [8, 24, 520, 5120, 5128, 5184, 8200, 16392])
+def test_row_sizes_across_launch_shapes(hidden):
+    """Rows of 1, 3, 65, 640, 641, 648, 1025 and 2049 16-byte chunks: a single partial wave, just
+    over one wave, the largest one-workgroup row, the first sizes beyond it (cut into single waves
+    only when the row is whole cache lines), and rows longer than one 1024-lane workgroup."""
+    w = W.DispatchWorkload("rows", 91, 8, 16, 3, 70, hidden, "bf16", "uniform")
+    run_dispatch(w, 4, 2, also_full=True)
+
+
+def test_opaque_byte_rows():
+    """MW_ROW_BYTES with experts: the rows are bytes of any meaning (here 1040 of them)."""
+    R, E, K, T, rb, my_rank = 8, 24, 4, 150, 1040, 5
+    w = W.DispatchWorkload("bytes", 92, R, E, K, T, rb // 2, "bf16", "uniform")     # routing and sizes only
+    e2r = W.expert_to_rank(w)
+    ctx = B.Context(R, E, K, my_rank, 0, B.MW_ROW_BYTES, T, R * T, e2r, row_bytes=rb, device=H.DEV)
+    assert ctx.row_bytes == rb
+    rng = np.random.default_rng(92)
+    toks, recs = [], []
+    for p in range(R):
+        tk = W.topk_ids(w, 6, p)
+        x = rng.integers(0, 256, size=(T, rb), dtype=np.uint8)
+        toks.append((tk, x, None))
+        g = H.GpuSend(ctx, tk, x, None)
+        H.check_send(w, g, tk, x, None)
+        recs.append(H.shrink(g.deliver(my_rank)))
+    cap = sum(r["n_rows"] for r in recs) * min(K, E // R)
+    gu = H.GpuUnpack(ctx, recs, cap)
+    H.check_unpack(gu, ref.dispatch_plain(toks, e2r, my_rank, cap), "opaque rows")
+    ctx.close()
