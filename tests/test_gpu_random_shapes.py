@@ -49,6 +49,19 @@ def draw_tokens(rng, T, K, E, hidden):
 def test_random_configuration(case):
     rng = np.random.default_rng(1000 + case)
     R, E, K, T, hidden, e2r = draw_config(rng)
+    _run_configuration(rng, case, R, E, K, T, hidden, e2r)
+
+
+@pytest.mark.parametrize("hidden", [5120, 5128, 5184, 8200])
+def test_long_rows_through_every_entry_point(hidden):
+    """Rows of 640, 641, 648 and 1025 chunks (the launch shape of the row movers changes between
+    them) through plan, pack, delivery, unpack, packets and the way back."""
+    rng = np.random.default_rng(3000 + hidden)
+    R, E, K, T, _, e2r = draw_config(rng)
+    _run_configuration(rng, hidden, R, E, K, min(T, 100), hidden, e2r)
+
+
+def _run_configuration(rng, case, R, E, K, T, hidden, e2r):
     counts = np.bincount(e2r, minlength=R)
     my_rank = int(rng.choice([int(np.argmax(counts)), int(rng.integers(0, R))]))
     L = int(counts[my_rank])

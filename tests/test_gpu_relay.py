@@ -244,3 +244,15 @@ def test_relay_full_size_c1_two_level_topology():
     saved = 1.0 - int(st["forward_bytes"]) / int(st["unicast_bytes"])
     _say("  copies per token", int(st["forward_bytes"]) / w.row_bytes / g.N, "saved vs unicast", round(saved, 4))
     ctx.close()
+
+
+@pytest.mark.parametrize("hidden", [5128, 5184, 8200])
+def test_relay_long_rows(hidden):
+    """Rows of 641, 648 and 1025 chunks: the relay's row mover in each of its launch shapes."""
+    w = W.DispatchWorkload("relay_rows", 93, 16, 32, 4, 90, hidden, "bf16", "uniform")
+    next_hop = (np.arange(w.n_ranks) % 5).astype(np.int32)
+    ctx = _ctx(w, 3, 8)
+    tk, x, sc, g = _send(ctx, w, 2, 3)
+    ch, st, _ = gpu_relay(ctx, g.full_record(), next_hop, 5, w.n_tokens)
+    check_children(ch, st, H.oracle_send(w, tk, x, sc), next_hop, 5, w.row_bytes)
+    ctx.close()
