@@ -33,8 +33,9 @@
  *     received metadata) set MW_FLAG_* bits in the statistics block, the
  *     offending item is left out, and all kernels still terminate normally.
  *   - Work enqueued for one context shares its workspace in four parts:
- *     (1) mw_plan; (2) mw_unpack, mw_unpack_packets, mw_unpack_index,
- *     mw_unpack_expand, mw_unpack_expand_index_next (the part of `ctx` and,
+ *     (1) mw_plan (and the plan half of mw_unpack_expand_index_plan_next,
+ *     in next_ctx); (2) mw_unpack, mw_unpack_packets, mw_unpack_index,
+ *     mw_unpack_expand, mw_unpack_expand_index[_plan]_next (the part of `ctx` and,
  *     for the index, of `next_ctx`) and mw_combine_gather; (3) mw_relay and
  *     mw_relay_packets; (4) mw_sim_deliver.  Calls of one part race if they
  *     overlap on the device; calls of different parts, and the packers
@@ -62,6 +63,7 @@ extern "C" {
 #define MW_MAX_TOPK   64
 #define MW_MAX_HOPS   64         /* next hops (egress ports) a relay's forwarding table may name */
 #define MW_FUSED_MAX_TOKENS 256  /* largest batch mw_plan_pack takes */
+#define MW_RIDE_MAX_TOKENS 8192  /* largest next batch mw_unpack_expand_index_plan_next plans */
 
 /* status codes */
 #define MW_OK                 0
@@ -310,6 +312,31 @@ MW_API int32_t mw_unpack_expand_index_next(mw_ctx *ctx, int32_t n_peers, void *o
                                     const mw_recv_peer *next_peers_dev, int32_t next_n_peers,
                                     int64_t next_out_capacity_rows, int64_t *next_expert_offsets_dev,
                                     mw_recv_stats *next_recv_stats_dev, void *stream);
+
+/*
+ * mw_unpack_expand_index_plan_next: mw_unpack_expand_index_next with the send-side plan of the
+ * next batch in the same launch as well -- what mw_plan(next_ctx, next_topk_ids_dev,
+ * next_n_tokens, next_mask_dev, next_perm_dev, next_desc_dev, next_send_stats_dev) does, with
+ * exactly its outputs (Section 5.1, send module).  The plan, too, is a chain of memory round
+ * trips that moves almost nothing; here it runs in the shadow of the expander.  A steady
+ * stream of batches is then two launches per batch on ONE stream, with no event between them:
+ *     mw_pack(batch n);  mw_unpack_expand_index_plan_next(expand n; index n+1; plan n+1);
+ *     mw_pack(batch n+1);  ...
+ * The plan uses the plan part of next_ctx's workspace (see the conventions above); its outputs
+ * are complete when this launch is, i.e. for every later call on the same stream.
+ * MW_ERR_UNSUPPORTED if next_n_tokens > MW_RIDE_MAX_TOKENS (larger batches: mw_plan), or where
+ * mw_unpack_expand_index_next returns it; MW_ERR_CAPACITY if next_n_tokens > max_tokens of
+ * next_ctx.
+ */
+MW_API int32_t mw_unpack_expand_index_plan_next(mw_ctx *ctx, int32_t n_peers, void *out_rows_dev, float *out_scales_dev,
+                                         int64_t out_capacity_rows, int32_t *out_src_peer_dev,
+                                         int32_t *out_src_token_dev, mw_ctx *next_ctx,
+                                         const mw_recv_peer *next_peers_dev, int32_t next_n_peers,
+                                         int64_t next_out_capacity_rows, int64_t *next_expert_offsets_dev,
+                                         mw_recv_stats *next_recv_stats_dev, const int32_t *next_topk_ids_dev,
+                                         int32_t next_n_tokens, uint64_t *next_mask_dev, int32_t *next_perm_dev,
+                                         mw_group_desc *next_desc_dev, mw_send_stats *next_send_stats_dev,
+                                         void *stream);
 
 /*
  * mw_combine_gather: the way back (Section 2.1, combine-style AlltoAll).  The paper notes that

@@ -18,7 +18,7 @@ namespace {
 
 struct ws_layout {
     int64_t eslot, plan_cnt, plan_state, flags, cnt, base, row_base, addr_cnt, recs, hits, row_map,
-        hop_bits, group_of_row, child_pos, sort_key, sort_sec, chunk_kept, row_cnt, row_start, total;
+        hop_bits, group_of_row, child_pos, sort_key, sort_sec, chunk_kept, row_tok, row_cnt, row_start, total;
 };
 
 // Derived row geometry; returns a status.
@@ -95,13 +95,14 @@ ws_layout layout(const mw_config &c, int32_t L)
         w.child_pos = o;    o += mw_align_up(4LL * MW_MAX_HOPS * ntok, A);
     }
     // sorted chunks for the plan of large batches (only contexts that can see such batches)
-    w.sort_key = w.sort_sec = w.chunk_kept = w.row_cnt = w.row_start = -1;
+    const int64_t padded = mw_align_up(ntok, 1024);
+    w.row_tok = o;    o += mw_align_up(4LL * padded, A);
+    w.row_cnt = o;    o += mw_align_up(8LL * padded, A);
+    w.sort_key = w.sort_sec = w.chunk_kept = w.row_start = -1;
     if (c.max_tokens > 4096) {
-        const int64_t padded = mw_align_up(ntok, 1024);
         w.sort_key = o;   o += mw_align_up(8LL * padded, A);
         w.sort_sec = o;   o += mw_align_up(4LL * padded, A);
         w.chunk_kept = o; o += mw_align_up(4LL * 64, A);
-        w.row_cnt = o;    o += mw_align_up(8LL * padded, A);
         w.row_start = o;  o += mw_align_up(padded, A);
     }
     w.total = o;
@@ -154,7 +155,8 @@ MW_API int32_t mw_ctx_create(const mw_config *cfg, void *workspace_dev, int64_t 
     ctx->d_sort_key = w.sort_key >= 0 ? (uint64_t *)(b + w.sort_key) : nullptr;
     ctx->d_sort_sec = w.sort_sec >= 0 ? (uint32_t *)(b + w.sort_sec) : nullptr;
     ctx->d_chunk_kept = w.chunk_kept >= 0 ? (uint32_t *)(b + w.chunk_kept) : nullptr;
-    ctx->d_row_cnt = w.row_cnt >= 0 ? (uint64_t *)(b + w.row_cnt) : nullptr;
+    ctx->d_row_tok = (uint32_t *)(b + w.row_tok);
+    ctx->d_row_cnt = (uint64_t *)(b + w.row_cnt);
     ctx->d_row_start = w.row_start >= 0 ? (unsigned char *)(b + w.row_start) : nullptr;
     ctx->d_flags = (uint32_t *)(b + w.flags);
     ctx->d_cnt = (uint32_t *)(b + w.cnt);
@@ -427,6 +429,35 @@ MW_API int32_t mw_unpack_expand_index_next(mw_ctx *ctx, int32_t n_peers, void *o
                                               out_src_peer_dev, out_src_token_dev, next_ctx, next_peers_dev, next_n_peers,
                                               next_out_capacity_rows, next_expert_offsets_dev, next_recv_stats_dev,
                                               (hipStream_t)stream);
+}
+
+MW_API int32_t mw_unpack_expand_index_plan_next(mw_ctx *ctx, int32_t n_peers, void *out_rows_dev, float *out_scales_dev,
+                                         int64_t out_capacity_rows, int32_t *out_src_peer_dev,
+                                         int32_t *out_src_token_dev, mw_ctx *next_ctx,
+                                         const mw_recv_peer *next_peers_dev, int32_t next_n_peers,
+                                         int64_t next_out_capacity_rows, int64_t *next_expert_offsets_dev,
+                                         mw_recv_stats *next_recv_stats_dev, const int32_t *next_topk_ids_dev,
+                                         int32_t next_n_tokens, uint64_t *next_mask_dev, int32_t *next_perm_dev,
+                                         mw_group_desc *next_desc_dev, mw_send_stats *next_send_stats_dev, void *stream)
+{
+    if (!ctx || !next_ctx || ctx == next_ctx || ctx->device != next_ctx->device) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
+    int32_t rc = check_unpack_expand(ctx, n_peers, out_rows_dev, out_scales_dev, out_capacity_rows, out_src_peer_dev,
+                                     out_src_token_dev);
+    if (rc == MW_OK)
+        rc = check_unpack_index(next_ctx, next_peers_dev, next_n_peers, next_out_capacity_rows, next_expert_offsets_dev,
+                                next_recv_stats_dev);
+    if (rc != MW_OK) return rc;
+    if (!next_send_stats_dev || next_n_tokens < 0) return MW_ERR_INVALID_ARG;
+    if (next_n_tokens > next_ctx->cfg.max_tokens) return MW_ERR_CAPACITY;
+    if (next_n_tokens > 0 && (!next_topk_ids_dev || !next_mask_dev || !next_perm_dev || !next_desc_dev))
+        return MW_ERR_INVALID_ARG;
+    return mw_launch_unpack_expand_index_plan_next(ctx, n_peers, out_rows_dev, out_scales_dev, out_capacity_rows,
+                                                   out_src_peer_dev, out_src_token_dev, next_ctx, next_peers_dev,
+                                                   next_n_peers, next_out_capacity_rows, next_expert_offsets_dev,
+                                                   next_recv_stats_dev, next_topk_ids_dev, next_n_tokens, next_mask_dev,
+                                                   next_perm_dev, next_desc_dev, next_send_stats_dev,
+                                                   (hipStream_t)stream);
 }
 
 MW_API int32_t mw_combine_gather(mw_ctx *ctx, int32_t n_peers, const void *y_dev, int64_t out_capacity_rows,

@@ -71,7 +71,8 @@ struct mw_ctx {
     uint64_t *d_sort_key;       // [max_tokens rounded up to 1024] sorted chunks of the large-batch plan (or null)
     uint32_t *d_sort_sec;       // same count: second sort word
     uint32_t *d_chunk_kept;     // [64] kept tokens per chunk
-    uint64_t *d_row_cnt;        // [max_tokens] a packed row's counters (large-batch plan, or null)
+    uint32_t *d_row_tok;        // [max_tokens] a packed row's token (plan riding along with the expander)
+    uint64_t *d_row_cnt;        // [max_tokens] a packed row's counters (large-batch plan, riding plan)
     unsigned char *d_row_start; // [max_tokens] 1: a group starts at this packed row
     uint32_t *d_flags;      // [4] 1: receive flags, 2: receive workgroups done
     uint32_t *d_base;       // [L][R] first output row of (local expert, peer)
@@ -207,6 +208,13 @@ int32_t mw_launch_unpack_expand_index_next(mw_ctx *ctx, int32_t P, void *out_row
                                            int32_t *out_src_peer, int32_t *out_src_token, mw_ctx *next,
                                            const mw_recv_peer *next_peers, int32_t next_P, int64_t next_cap,
                                            int64_t *next_expert_offsets, mw_recv_stats *next_stats, hipStream_t s);
+int32_t mw_launch_unpack_expand_index_plan_next(mw_ctx *ctx, int32_t P, void *out_rows, float *out_scales, int64_t cap,
+                                                int32_t *out_src_peer, int32_t *out_src_token, mw_ctx *next,
+                                                const mw_recv_peer *next_peers, int32_t next_P, int64_t next_cap,
+                                                int64_t *next_expert_offsets, mw_recv_stats *next_stats,
+                                                const int32_t *next_topk, int32_t next_T, uint64_t *next_mask,
+                                                int32_t *next_perm, mw_group_desc *next_desc,
+                                                mw_send_stats *next_send_stats, hipStream_t s);
 int32_t mw_launch_combine(mw_ctx *ctx, int32_t P, const void *y, int64_t cap, void *ret, int64_t ret_cap, hipStream_t s);
 int32_t mw_launch_plan_allgather(mw_ctx *ctx, int64_t shard_bytes, mw_group_desc *desc,
                                  mw_send_stats *stats, hipStream_t s);

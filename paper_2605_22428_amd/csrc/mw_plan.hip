@@ -32,72 +32,11 @@
 // ranks by binary search: T log T instead of T^2); batches of at most 256 tokens can take
 // k_plan_pack, which plans and packs in one launch.
 #include "mw_internal.h"
+#include "mw_plan_dev.h"
 
 namespace {
 
 constexpr int kBlock = 256;
-constexpr uint64_t kField = 0x1fffffull;      // 21-bit fields of the packed counter
-constexpr int kPsKept = 256, kPsFlags = 257, kPsDone = 258;  // plan state words after the 256 histogram bins
-
-// Destination bitmap of one token (Section 4.1): ids are fetched in independent batches.
-__device__ __forceinline__ void token_mask(const int32_t *__restrict__ row, int K,
-                                           const int32_t *__restrict__ eslot, int E, uint64_t m[MW_MASK_WORDS],
-                                           bool &bad)
-{
-#pragma unroll
-    for (int q = 0; q < MW_MASK_WORDS; ++q) m[q] = 0;
-    for (int j0 = 0; j0 < K; j0 += 8) {
-        int32_t e[8], s[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) e[u] = (j0 + u < K) ? row[j0 + u] : -1;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const bool ok = (uint32_t)e[u] < (uint32_t)E;
-            bad |= (e[u] != -1 && !ok);
-            s[u] = ok ? eslot[e[u]] : -1;
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            if (s[u] < 0) continue;
-            const int r = s[u] >> 16;
-            const uint64_t bit = 1ull << (r & 63);
-            const int w = r >> 6;
-#pragma unroll
-            for (int q = 0; q < MW_MASK_WORDS; ++q) m[q] |= (w == q) ? bit : 0ull;
-        }
-    }
-}
-
-// Order-preserving short key of a bitmap with at most eight bits set (always the case for
-// top_k <= 8): the positions of the set bits, highest first, one byte each, zero-padded.
-// Comparing bitmaps as 256-bit integers is comparing these lists lexicographically; the one
-// collision -- "bit 0 set" against "no further bit" -- is resolved by bit 0 itself as a second,
-// less significant component.  (key, flag) pairs are equal iff the bitmaps are.  One 64-bit and
-// one 32-bit compare then replace four 64-bit ones in the all-pairs walk.
-struct mw_short_key { uint64_t key; uint32_t flag; uint32_t pad; };     // 16 bytes: one LDS read
-__device__ __forceinline__ mw_short_key short_key(const uint64_t m[MW_MASK_WORDS])
-{
-    uint64_t w[MW_MASK_WORDS] = {m[0], m[1], m[2], m[3]};
-    mw_short_key k = {0ull, (uint32_t)(m[0] & 1ull), 0u};
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int q = w[3] ? 3 : w[2] ? 2 : w[1] ? 1 : 0;
-        uint64_t cur = 0;
-#pragma unroll
-        for (int z = 0; z < MW_MASK_WORDS; ++z) cur = (z == q) ? w[z] : cur;
-        if (cur == 0) break;
-        const int b = 63 - __clzll((long long)cur);
-        k.key |= (uint64_t)(q * 64 + b) << (56 - 8 * j);
-#pragma unroll
-        for (int z = 0; z < MW_MASK_WORDS; ++z) w[z] = (z == q) ? (cur & ~(1ull << b)) : w[z];
-    }
-    return k;
-}
-
-// cnt[t] += (#smaller | #equal before << 21 | #equal at-or-after << 42) over this slice, where
-// "smaller" means (bitmap, index) < (bitmap[t], t).  Empty bitmaps compare below every kept
-// token; k_groups subtracts their number.  A kept token always has a non-zero third field.
-// kKeyed (bitmaps of more than one word, top_k <= 8): the slice holds short keys instead of bitmaps.
 template <int W, bool kKeyed>
 __global__ __launch_bounds__(kBlock) void k_rank(const int32_t *__restrict__ topk, int T, int K,
                                                  const int32_t *__restrict__ eslot, int E, int slice,
@@ -105,95 +44,8 @@ __global__ __launch_bounds__(kBlock) void k_rank(const int32_t *__restrict__ top
                                                  unsigned long long *__restrict__ cnt,
                                                  uint32_t *__restrict__ pstate)
 {
-    extern __shared__ uint64_t smask[];           // [slice][W] bitmaps, or [slice] short keys
-    mw_short_key *skey = (mw_short_key *)smask;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int u0 = blockIdx.y * slice, u1 = min(u0 + slice, T);
-    bool bad = false, bad_slice = false;
-    for (int u = u0 + tid; u < u1; u += kBlock) {
-        uint64_t q[MW_MASK_WORDS];
-        token_mask(topk + (size_t)u * K, K, eslot, E, q, bad_slice);
-        if constexpr (kKeyed) {
-            skey[u - u0] = short_key(q);
-        } else {
-#pragma unroll
-            for (int w = 0; w < W; ++w) smask[(size_t)(u - u0) * W + w] = q[w];
-        }
-    }
-    const int t = blockIdx.x * kBlock + tid;
-    uint64_t m[MW_MASK_WORDS] = {0, 0, 0, 0};
-    if (t < T) token_mask(topk + (size_t)t * K, K, eslot, E, m, bad);
-    const bool any = (m[0] | m[1] | m[2] | m[3]) != 0;
-
-    if (blockIdx.y == 0) {
-        if (t < T) {
-            uint64_t *o = mask_out + (size_t)t * MW_MASK_WORDS;
-#pragma unroll
-            for (int q = 0; q < MW_MASK_WORDS; ++q) o[q] = m[q];
-            if (bad) atomicOr(&pstate[kPsFlags], MW_FLAG_BAD_EXPERT);
-        }
-        const uint32_t kept = (uint32_t)__popcll(__ballot(any));
-        if (lane == 0 && kept) atomicAdd(&pstate[kPsKept], kept);
-        // rows per destination: a wavefront ballot of bit b over 64 tokens, popcounted, is the
-        // number of those tokens that name rank 64*q + b; lane b keeps it and adds it once.
-#pragma unroll
-        for (int q = 0; q < MW_MASK_WORDS; ++q) {
-            if (__ballot(m[q] != 0) == 0) continue;      // wave-uniform
-            uint32_t mine = 0;
-            for (int b = 0; b < 64; ++b) {
-                const uint32_t c = (uint32_t)__popcll(__ballot((m[q] >> b) & 1ull));
-                if (lane == b) mine = c;
-            }
-            if (mine) atomicAdd(&pstate[q * 64 + lane], mine);
-        }
-    }
-    mw_lds_barrier();
-
-    // Whether a slice token u comes before token t (u < t) is the same for the whole wavefront
-    // except among the wavefront's own 64 tokens: before them an equal bitmap is an "equal
-    // before", after them an "equal at or after", and only inside that range the index decides.
-    uint32_t c_lt = 0, c_eqb = 0, c_eqa = 0;
-    const int wt0 = blockIdx.x * kBlock + (tid & ~63);
-    const int ua = min(max(u0, wt0), u1), ub = min(max(u0, wt0 + 64), u1);
-    auto walk = [&](int from, int to, uint32_t &n_lt, uint32_t &n_eq_before, uint32_t &n_eq_after, bool own) {
-        if constexpr (kKeyed) {
-            const mw_short_key mk = short_key(m);
-#pragma unroll 4
-            for (int u = from; u < to; ++u) {
-                const mw_short_key q = skey[u - u0];               // same address in every lane: LDS broadcast
-                const bool keq = q.key == mk.key;
-                const bool lt = q.key < mk.key || (keq && q.flag < mk.flag);
-                const bool eq = keq && q.flag == mk.flag;
-                n_lt += lt ? 1u : 0u;
-                if (own) { n_eq_before += (eq && u < t) ? 1u : 0u; n_eq_after += (eq && u >= t) ? 1u : 0u; }
-                else n_eq_before += eq ? 1u : 0u;
-            }
-        } else {
-#pragma unroll 4
-            for (int u = from; u < to; ++u) {
-                const uint64_t *q = smask + (size_t)(u - u0) * W;  // same address in every lane: LDS broadcast
-                bool lt = false, eq = true;
-#pragma unroll
-                for (int w = W - 1; w >= 0; --w) {
-                    const uint64_t qw = q[w];
-                    lt = lt || (eq && qw < m[w]);
-                    eq = eq && (qw == m[w]);
-                }
-                n_lt += lt ? 1u : 0u;
-                if (own) { n_eq_before += (eq && u < t) ? 1u : 0u; n_eq_after += (eq && u >= t) ? 1u : 0u; }
-                else n_eq_before += eq ? 1u : 0u;
-            }
-        }
-    };
-    uint32_t unused = 0;
-    walk(u0, ua, c_lt, c_eqb, unused, false);      // slice tokens before the wavefront's own
-    walk(ua, ub, c_lt, c_eqb, c_eqa, true);        // the wavefront's own tokens, if in this slice
-    walk(ub, u1, c_lt, c_eqa, unused, false);      // slice tokens after them
-    if (any) {
-        const unsigned long long add = (unsigned long long)(c_lt + c_eqb) | ((unsigned long long)c_eqb << 21) |
-                                       ((unsigned long long)c_eqa << 42);
-        if (add) atomicAdd(&cnt[t], add);
-    }
+    extern __shared__ uint64_t smask[];
+    mw_rank_body<W, kKeyed>(topk, T, K, eslot, E, slice, mask_out, cnt, pstate, blockIdx.x, blockIdx.y, kBlock, smask);
 }
 
 // For very large batches the walk below (every workgroup over every token's counters) is

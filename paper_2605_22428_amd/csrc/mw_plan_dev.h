@@ -1,0 +1,328 @@
+// Device code of the plan that more than one translation unit uses: the bitmap builder, the
+// short keys, the all-pairs ranking of one workgroup (k_rank, and the plan that rides along
+// with the expander), and the single-workgroup second half of that riding plan.
+#ifndef MW_PLAN_DEV_H_
+#define MW_PLAN_DEV_H_
+
+#include "mw_internal.h"
+
+namespace {
+
+constexpr uint64_t kField = 0x1fffffull;      // 21-bit fields of the packed counter
+constexpr int kPsKept = 256, kPsFlags = 257, kPsDone = 258;  // plan state words after the 256 histogram bins
+
+// Destination bitmap of one token (Section 4.1): ids are fetched in independent batches.
+__device__ __forceinline__ void token_mask(const int32_t *__restrict__ row, int K,
+                                           const int32_t *__restrict__ eslot, int E, uint64_t m[MW_MASK_WORDS],
+                                           bool &bad)
+{
+#pragma unroll
+    for (int q = 0; q < MW_MASK_WORDS; ++q) m[q] = 0;
+    for (int j0 = 0; j0 < K; j0 += 8) {
+        int32_t e[8], s[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) e[u] = (j0 + u < K) ? row[j0 + u] : -1;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const bool ok = (uint32_t)e[u] < (uint32_t)E;
+            bad |= (e[u] != -1 && !ok);
+            s[u] = ok ? eslot[e[u]] : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (s[u] < 0) continue;
+            const int r = s[u] >> 16;
+            const uint64_t bit = 1ull << (r & 63);
+            const int w = r >> 6;
+#pragma unroll
+            for (int q = 0; q < MW_MASK_WORDS; ++q) m[q] |= (w == q) ? bit : 0ull;
+        }
+    }
+}
+
+// Order-preserving short key of a bitmap with at most eight bits set (always the case for
+// top_k <= 8): the positions of the set bits, highest first, one byte each, zero-padded.
+// Comparing bitmaps as 256-bit integers is comparing these lists lexicographically; the one
+// collision -- "bit 0 set" against "no further bit" -- is resolved by bit 0 itself as a second,
+// less significant component.  (key, flag) pairs are equal iff the bitmaps are.  One 64-bit and
+// one 32-bit compare then replace four 64-bit ones in the all-pairs walk.
+struct mw_short_key { uint64_t key; uint32_t flag; uint32_t pad; };     // 16 bytes: one LDS read
+__device__ __forceinline__ mw_short_key short_key(const uint64_t m[MW_MASK_WORDS])
+{
+    uint64_t w[MW_MASK_WORDS] = {m[0], m[1], m[2], m[3]};
+    mw_short_key k = {0ull, (uint32_t)(m[0] & 1ull), 0u};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int q = w[3] ? 3 : w[2] ? 2 : w[1] ? 1 : 0;
+        uint64_t cur = 0;
+#pragma unroll
+        for (int z = 0; z < MW_MASK_WORDS; ++z) cur = (z == q) ? w[z] : cur;
+        if (cur == 0) break;
+        const int b = 63 - __clzll((long long)cur);
+        k.key |= (uint64_t)(q * 64 + b) << (56 - 8 * j);
+#pragma unroll
+        for (int z = 0; z < MW_MASK_WORDS; ++z) w[z] = (z == q) ? (cur & ~(1ull << b)) : w[z];
+    }
+    return k;
+}
+
+// cnt[t] += (#smaller | #equal before << 21 | #equal at-or-after << 42) over this slice, where
+// "smaller" means (bitmap, index) < (bitmap[t], t).  Empty bitmaps compare below every kept
+// token; k_groups subtracts their number.  A kept token always has a non-zero third field.
+// kKeyed (bitmaps of more than one word, top_k <= 8): the slice holds short keys instead of bitmaps.
+// Workgroup (bx, by) of `bs` lanes: tokens [bx bs, bx bs + bs) against slice by.  kAgentMask:
+// the bitmaps are written through to device scope, for a reader in the same launch.
+template <int W, bool kKeyed, bool kAgentMask = false>
+__device__ __forceinline__ void mw_rank_body(const int32_t *__restrict__ topk, int T, int K,
+                                             const int32_t *__restrict__ eslot, int E, int slice,
+                                             uint64_t *__restrict__ mask_out,
+                                             unsigned long long *__restrict__ cnt,
+                                             uint32_t *__restrict__ pstate, int bx, int by, int bs,
+                                             uint64_t *smask /* LDS: [slice][W] bitmaps, or [slice] short keys */)
+{
+    mw_short_key *skey = (mw_short_key *)smask;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int u0 = by * slice, u1 = min(u0 + slice, T);
+    bool bad = false, bad_slice = false;
+    for (int u = u0 + tid; u < u1; u += bs) {
+        uint64_t q[MW_MASK_WORDS];
+        token_mask(topk + (size_t)u * K, K, eslot, E, q, bad_slice);
+        if constexpr (kKeyed) {
+            skey[u - u0] = short_key(q);
+        } else {
+#pragma unroll
+            for (int w = 0; w < W; ++w) smask[(size_t)(u - u0) * W + w] = q[w];
+        }
+    }
+    const int t = bx * bs + tid;
+    uint64_t m[MW_MASK_WORDS] = {0, 0, 0, 0};
+    if (t < T) token_mask(topk + (size_t)t * K, K, eslot, E, m, bad);
+    const bool any = (m[0] | m[1] | m[2] | m[3]) != 0;
+
+    if (by == 0) {
+        if (t < T) {
+            uint64_t *o = mask_out + (size_t)t * MW_MASK_WORDS;
+#pragma unroll
+            for (int q = 0; q < MW_MASK_WORDS; ++q) {
+                if constexpr (kAgentMask) __hip_atomic_store(&o[q], m[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                else o[q] = m[q];
+            }
+            if (bad) atomicOr(&pstate[kPsFlags], MW_FLAG_BAD_EXPERT);
+        }
+        const uint32_t kept = (uint32_t)__popcll(__ballot(any));
+        if (lane == 0 && kept) atomicAdd(&pstate[kPsKept], kept);
+        // rows per destination: a wavefront ballot of bit b over 64 tokens, popcounted, is the
+        // number of those tokens that name rank 64*q + b; lane b keeps it and adds it once.
+#pragma unroll
+        for (int q = 0; q < MW_MASK_WORDS; ++q) {
+            if (__ballot(m[q] != 0) == 0) continue;      // wave-uniform
+            uint32_t mine = 0;
+            for (int b = 0; b < 64; ++b) {
+                const uint32_t c = (uint32_t)__popcll(__ballot((m[q] >> b) & 1ull));
+                if (lane == b) mine = c;
+            }
+            if (mine) atomicAdd(&pstate[q * 64 + lane], mine);
+        }
+    }
+    mw_lds_barrier();
+
+    // Whether a slice token u comes before token t (u < t) is the same for the whole wavefront
+    // except among the wavefront's own 64 tokens: before them an equal bitmap is an "equal
+    // before", after them an "equal at or after", and only inside that range the index decides.
+    uint32_t c_lt = 0, c_eqb = 0, c_eqa = 0;
+    const int wt0 = bx * bs + (tid & ~63);
+    const int ua = min(max(u0, wt0), u1), ub = min(max(u0, wt0 + 64), u1);
+    auto walk = [&](int from, int to, uint32_t &n_lt, uint32_t &n_eq_before, uint32_t &n_eq_after, bool own) {
+        if constexpr (kKeyed) {
+            const mw_short_key mk = short_key(m);
+#pragma unroll 4
+            for (int u = from; u < to; ++u) {
+                const mw_short_key q = skey[u - u0];               // same address in every lane: LDS broadcast
+                const bool keq = q.key == mk.key;
+                const bool lt = q.key < mk.key || (keq && q.flag < mk.flag);
+                const bool eq = keq && q.flag == mk.flag;
+                n_lt += lt ? 1u : 0u;
+                if (own) { n_eq_before += (eq && u < t) ? 1u : 0u; n_eq_after += (eq && u >= t) ? 1u : 0u; }
+                else n_eq_before += eq ? 1u : 0u;
+            }
+        } else {
+#pragma unroll 4
+            for (int u = from; u < to; ++u) {
+                const uint64_t *q = smask + (size_t)(u - u0) * W;  // same address in every lane: LDS broadcast
+                bool lt = false, eq = true;
+#pragma unroll
+                for (int w = W - 1; w >= 0; --w) {
+                    const uint64_t qw = q[w];
+                    lt = lt || (eq && qw < m[w]);
+                    eq = eq && (qw == m[w]);
+                }
+                n_lt += lt ? 1u : 0u;
+                if (own) { n_eq_before += (eq && u < t) ? 1u : 0u; n_eq_after += (eq && u >= t) ? 1u : 0u; }
+                else n_eq_before += eq ? 1u : 0u;
+            }
+        }
+    };
+    uint32_t unused = 0;
+    walk(u0, ua, c_lt, c_eqb, unused, false);      // slice tokens before the wavefront's own
+    walk(ua, ub, c_lt, c_eqb, c_eqa, true);        // the wavefront's own tokens, if in this slice
+    walk(ub, u1, c_lt, c_eqa, unused, false);      // slice tokens after them
+    if (any) {
+        const unsigned long long add = (unsigned long long)(c_lt + c_eqb) | ((unsigned long long)c_eqb << 21) |
+                                       ((unsigned long long)c_eqa << 42);
+        if (add) atomicAdd(&cnt[t], add);
+    }
+}
+
+
+// ---- the plan that rides along with another launch -------------------------------------
+// Everything the plan of one batch needs when it runs as extra workgroups of a launch that
+// does something else (one kernel argument).  Rank workgroups: wg = by * tb + bx,
+// n_rank = tb * ns of them.
+struct mw_plan_args {
+    const int32_t *topk; int T, K, E; const int32_t *eslot;
+    uint64_t *mask_out; unsigned long long *cnt; uint32_t *pstate;
+    int32_t *perm; mw_group_desc *desc; mw_send_stats *stats; uint64_t row_bytes;
+    uint32_t *row_tok; unsigned long long *row_cnt;     // [T] scratch indexed by packed row
+    int tb, ns, slice;
+};
+
+__device__ __forceinline__ unsigned long long mw_ld_agent64(const unsigned long long *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t mw_ld_agent32(const uint32_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Second half of a riding plan, run by ONE workgroup (any multiple of 64 lanes) once every
+// rank workgroup of the same launch has reported: counters -> perm, descriptors, statistics;
+// then the counters and the plan state are cleared for the next plan.  What other workgroups
+// of this launch wrote is read at device scope (the counters and the state are atomics; the
+// bitmaps were written through by mw_rank_body<.., true>); what this workgroup writes and
+// reads back itself (the row-indexed scratch) stays within its own CU and L2.  `scratch`: 17
+// words of LDS.
+// It is not fast -- one workgroup, about 25 us for 4096 tokens -- and does not have to be:
+// it runs in the shadow of a launch that takes several times longer.
+__device__ __forceinline__ void mw_plan_finish_one_wg(const mw_plan_args &a, uint32_t *scratch)
+{
+    const uint32_t tid = threadIdx.x, bs = blockDim.x;
+    const uint32_t T = (uint32_t)a.T;
+    const uint32_t N = min(mw_ld_agent32(&a.pstate[kPsKept]), T), n_empty = T - N;
+
+    // (1) every kept token drops its index and its counters at its packed row; counters cleared
+    for (uint32_t t0 = 0; t0 < T; t0 += 8 * bs) {
+        unsigned long long c[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const uint32_t t = t0 + u * bs + tid;
+            c[u] = t < T ? mw_ld_agent64(&a.cnt[t]) : 0ull;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const uint32_t t = t0 + u * bs + tid;
+            if (t >= T) continue;
+            a.cnt[t] = 0;
+            if ((c[u] >> 42) == 0) continue;                          // empty bitmap
+            const uint32_t p = (uint32_t)(c[u] & kField) - n_empty;
+            if (p < N) { a.row_tok[p] = t; a.row_cnt[p] = c[u]; }
+        }
+    }
+    __syncthreads();                        // the rows are written (and acknowledged)
+
+    // (2) lane `tid` owns the packed rows [r0, r1): groups starting in them, then one scan
+    const uint32_t per = (N + bs - 1) / bs;
+    const uint32_t r0 = min(tid * per, N), r1 = min(r0 + per, N);
+    uint32_t starts = 0;
+    for (uint32_t i0 = r0; i0 < r1; i0 += 8) {
+        unsigned long long c[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) c[u] = (i0 + u < r1) ? a.row_cnt[i0 + u] : ~0ull;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) starts += ((c[u] >> 21) & kField) == 0 ? 1u : 0u;
+    }
+    uint32_t G;
+    uint32_t g = mw_block_exscan(starts, scratch, &G);
+
+    // (3) perm and the descriptors of those rows
+    for (uint32_t i0 = r0; i0 < r1; i0 += 4) {
+        unsigned long long c[4];
+        uint32_t t[4];
+        uint64_t m[4][MW_MASK_WORDS];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const bool in = i0 + u < r1;
+            c[u] = in ? a.row_cnt[i0 + u] : ~0ull;
+            t[u] = in ? a.row_tok[i0 + u] : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const unsigned long long *mp = (const unsigned long long *)(a.mask_out + (size_t)t[u] * MW_MASK_WORDS);
+#pragma unroll
+            for (int w = 0; w < MW_MASK_WORDS; ++w) m[u][w] = (i0 + u < r1) ? mw_ld_agent64(mp + w) : 0ull;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (i0 + u >= r1) continue;
+            a.perm[i0 + u] = (int32_t)t[u];
+            if (((c[u] >> 21) & kField) != 0) continue;               // not the first of its bitmap
+            mw_group_desc d;
+            uint32_t nd = 0;
+#pragma unroll
+            for (int w = 0; w < MW_MASK_WORDS; ++w) { d.mask[w] = m[u][w]; nd += (uint32_t)__popcll(m[u][w]); }
+            d.row_offset = i0 + u;
+            d.row_count = (uint32_t)((c[u] >> 42) & kField);
+            d.n_dest = nd;
+            d.reserved0 = 0;
+            a.desc[g++] = d;
+        }
+    }
+
+    // (4) statistics, then the state is cleared
+    uint32_t dests = 0;
+    for (uint32_t r = tid; r < MW_MAX_RANKS; r += bs) {
+        const uint32_t h = mw_ld_agent32(&a.pstate[r]);
+        a.stats->rows_per_dest[r] = h;
+        dests += h;
+    }
+    const uint32_t flags = tid == 0 ? mw_ld_agent32(&a.pstate[kPsFlags]) : 0u;
+    uint32_t D;
+    mw_block_exscan(dests, scratch, &D);                   // its barriers: every lane has read the state
+    if (tid == 0) {
+        a.stats->n_rows = N;
+        a.stats->n_groups = G;
+        a.stats->multicast_bytes = (uint64_t)N * a.row_bytes;
+        a.stats->unicast_bytes = (uint64_t)D * a.row_bytes;
+        a.stats->error_flags = flags;
+        a.stats->reserved0 = 0;
+    }
+    for (uint32_t r = tid; r < MW_PLAN_STATE_WORDS; r += bs)
+        __hip_atomic_store(&a.pstate[r], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// One riding plan workgroup: its share of the ranking, then -- if it is the last to finish --
+// the second half.  `lds` is the launch's dynamic LDS (slice keys, then 17 + 1 scratch words
+// after them).
+template <int W, bool kKeyed>
+__device__ __forceinline__ void mw_plan_ride(const mw_plan_args &a, uint32_t wg, uint64_t *lds)
+{
+    const uint32_t n_rank = (uint32_t)a.tb * (uint32_t)a.ns;
+    if (wg >= n_rank) return;
+    mw_rank_body<W, kKeyed, true>(a.topk, a.T, a.K, a.eslot, a.E, a.slice, a.mask_out, a.cnt, a.pstate,
+                                  (int)(wg % (uint32_t)a.tb), (int)(wg / (uint32_t)a.tb), (int)blockDim.x, lds);
+    // Every workgroup reports when its atomics and write-through stores have been acknowledged
+    // (the barrier waits for them); the counter is a device-scope atomic, no fence is needed.
+    uint32_t *scratch = (uint32_t *)lds;                   // the slice keys are not needed any more
+    __syncthreads();
+    if (threadIdx.x == 0)
+        scratch[17] = __hip_atomic_fetch_add(&a.pstate[kPsDone], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                      n_rank - 1u ? 1u : 0u;
+    __syncthreads();
+    if (!scratch[17]) return;
+    __syncthreads();                                       // (scratch[17] read by all before it is reused)
+    mw_plan_finish_one_wg(a, scratch);
+}
+
+}  // namespace
+
+#endif

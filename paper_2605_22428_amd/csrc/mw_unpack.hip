@@ -30,6 +30,7 @@
 // k_expand_index_next runs the expander with the next batch's index in the same launch, and
 // k_combine is the expander's mirror image for the way back.
 #include "mw_internal.h"
+#include "mw_plan_dev.h"
 
 namespace {
 
@@ -530,6 +531,34 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
                 blockIdx.y - n_index, gridDim.y - n_index);
 }
 
+// The same launch with the PLAN of the next batch riding along as well (Section 5.1, send
+// module: task decomposition for the batch after this one): after the index rows of the grid
+// come `n_plan_rows` rows whose workgroups rank the next batch's tokens; the one that finishes
+// last writes perm, descriptors and statistics.  A steady stream of batches then needs two
+// launches per batch on one stream -- the packer and this -- and no event: 159 us per batch at
+// 4096 tokens x 14336 bytes, against 171 us with the plan on a second stream.
+template <int W, bool kKeyed>
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_expand_index_plan_next(
+    const mw_row_rec *__restrict__ recs, const mw_hit *__restrict__ hits, const uint32_t *__restrict__ base,
+    const uint32_t *__restrict__ row_base, int P, int Kd, int xc, int sc,
+    u32x4 *__restrict__ out_rows, u32x4 *__restrict__ out_scales, uint32_t cap,
+    int32_t *__restrict__ out_src_peer, int32_t *__restrict__ out_src_token, const mw_index_args next,
+    const mw_plan_args plan, const uint32_t n_plan_rows)
+{
+    const uint32_t n_index = (uint32_t)next.P;
+    if (blockIdx.y < n_index) {
+        if (blockIdx.x == 0) recv_index_of<false>(next, (int)blockIdx.y);
+        return;
+    }
+    if (blockIdx.y < n_index + n_plan_rows) {
+        extern __shared__ uint64_t plan_lds[];
+        mw_plan_ride<W, kKeyed>(plan, (blockIdx.y - n_index) * gridDim.x + blockIdx.x, plan_lds);
+        return;
+    }
+    expand_body(recs, hits, base, row_base, P, Kd, xc, sc, out_rows, out_scales, cap, out_src_peer, out_src_token,
+                blockIdx.y - n_index - n_plan_rows, gridDim.y - n_index - n_plan_rows);
+}
+
 // The way back (Section 2.1, combine-style AlltoAll; Section 2.3.2: the combine phase reduces
 // and cannot be multicast).  The mirror image of the expander: a received row that went to h
 // local experts gets ONE row back, the sum of those h expert outputs, so the return traffic is
@@ -702,6 +731,62 @@ int32_t mw_launch_unpack_expand_index_next(mw_ctx *ctx, int32_t P, void *out_row
                            ctx->d_recs, ctx->d_hits, ctx->d_base, ctx->d_row_base, P, ctx->hit_slots, xc, sc,
                            (u32x4 *)out_rows, (u32x4 *)out_scales, (uint32_t)(cap < 0x7fffffffLL ? cap : 0x7fffffffLL),
                            out_src_peer, out_src_token, a);
+    }
+    MW_HIP_CHECK(hipGetLastError());
+    return MW_OK;
+}
+
+int32_t mw_launch_unpack_expand_index_plan_next(mw_ctx *ctx, int32_t P, void *out_rows, float *out_scales, int64_t cap,
+                                                int32_t *out_src_peer, int32_t *out_src_token, mw_ctx *next,
+                                                const mw_recv_peer *next_peers, int32_t next_P, int64_t next_cap,
+                                                int64_t *next_expert_offsets, mw_recv_stats *next_stats,
+                                                const int32_t *next_topk, int32_t next_T, uint64_t *next_mask,
+                                                int32_t *next_perm, mw_group_desc *next_desc,
+                                                mw_send_stats *next_send_stats, hipStream_t s)
+{
+    const mw_config &c = ctx->cfg;
+    if (c.max_recv_rows < 1) return MW_ERR_UNSUPPORTED;       // nothing to ride on
+    if (next_T > MW_RIDE_MAX_TOKENS) return MW_ERR_UNSUPPORTED;
+    mw_index_args a;
+    size_t lds_index;
+    if (!make_index_args(next, next_peers, false, next_P, next_cap, next_expert_offsets, next_stats, 1280, &a,
+                         &lds_index))
+        return MW_ERR_UNSUPPORTED;
+    const int xc = (int)(ctx->x_row_bytes / 16), sc = (int)(ctx->s_row_bytes / 16);
+    mw_row_shape shape = mw_row_shape_of(xc + sc);
+    if (shape.bs == 64 && (xc + sc) % 16 == 0) { shape.bs = 128; shape.nseg = (xc + sc) / 128 + ((xc + sc) % 128 ? 1 : 0); }
+    const uint32_t gy = expand_grid_rows(ctx);
+
+    // the riding plan: workgroups of the launch's size, slices of 128 tokens
+    const int K = next->cfg.top_k, W = next->mask_words;
+    const bool keyed = W > 1 && K <= 8;
+    mw_plan_args pl;
+    pl.topk = next_topk; pl.T = next_T; pl.K = K; pl.E = next->cfg.n_experts; pl.eslot = next->d_eslot;
+    pl.mask_out = next_mask; pl.cnt = (unsigned long long *)next->d_plan_cnt; pl.pstate = next->d_plan_state;
+    pl.perm = next_perm; pl.desc = next_desc; pl.stats = next_send_stats; pl.row_bytes = (uint64_t)next->row_bytes;
+    pl.row_tok = next->d_row_tok; pl.row_cnt = (unsigned long long *)next->d_row_cnt;
+    pl.slice = 128;
+    pl.tb = next_T > 0 ? (next_T + shape.bs - 1) / shape.bs : 1;
+    pl.ns = next_T > 0 ? (next_T + pl.slice - 1) / pl.slice : 1;
+    const uint32_t n_rank = (uint32_t)pl.tb * (uint32_t)pl.ns;
+    const uint32_t n_plan_rows = (n_rank + (uint32_t)shape.nseg - 1) / (uint32_t)shape.nseg;
+    size_t lds_plan = keyed ? (size_t)pl.slice * sizeof(mw_short_key) : (size_t)pl.slice * W * sizeof(uint64_t);
+    if (lds_plan < 18 * sizeof(uint32_t)) lds_plan = 18 * sizeof(uint32_t);
+    const size_t lds = lds_index > lds_plan ? lds_index : lds_plan;
+    {
+        mw_timed tm(ctx, MW_KERNEL_EXPAND, s);
+        const dim3 grid(shape.nseg, gy + (uint32_t)next_P + n_plan_rows), block(shape.bs);
+        const uint32_t cap32 = (uint32_t)(cap < 0x7fffffffLL ? cap : 0x7fffffffLL);
+#define MW_RIDE(W_, KEYED_)                                                                                        \
+    hipLaunchKernelGGL((k_expand_index_plan_next<W_, KEYED_>), grid, block, lds, s, ctx->d_recs, ctx->d_hits,      \
+                       ctx->d_base, ctx->d_row_base, P, ctx->hit_slots, xc, sc, (u32x4 *)out_rows,                 \
+                       (u32x4 *)out_scales, cap32, out_src_peer, out_src_token, a, pl, n_plan_rows)
+        if (keyed) MW_RIDE(4, true);
+        else if (W == 1) MW_RIDE(1, false);
+        else if (W == 2) MW_RIDE(2, false);
+        else if (W == 3) MW_RIDE(3, false);
+        else MW_RIDE(4, false);
+#undef MW_RIDE
     }
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;

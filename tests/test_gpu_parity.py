@@ -259,6 +259,98 @@ def test_index_of_the_next_batch_rides_with_the_expander():
             c.close()
 
 
+def _check_plan_outputs(w, ctx, sb, tk, what):
+    """mask, perm, descriptors and statistics in `sb` against the oracle's plan of `tk`."""
+    e2r = W.expert_to_rank(w)
+    m, perm, desc, ost = ref.plan(tk, e2r, w.n_ranks, w.row_bytes)
+    st = ctx.mw_get_send_stats(sb.stats)
+    N, G = int(st["n_rows"]), int(st["n_groups"])
+    assert (N, G, int(st["error_flags"])) == (len(perm), len(desc), 0), what
+    H.assert_same_bytes(H.host(sb.mask).view(np.uint64)[: len(tk)], m, what + " mask")
+    H.assert_same_bytes(H.host(sb.perm)[:N], perm, what + " perm")
+    H.assert_same_bytes(H.host(sb.desc).reshape(-1).view(B.DESC_DTYPE)[:G].view(np.uint8), desc.view(np.uint8),
+                        what + " desc")
+    H.assert_same_bytes(st["rows_per_dest"], ost["rows_per_dest"], what + " rows_per_dest")
+    for f in ("multicast_bytes", "unicast_bytes"):
+        assert int(st[f]) == int(ost[f]), what + " " + f
+
+
+@pytest.mark.parametrize("which", ["c1", "c2", "c3", "k12", "one_rank"])
+def test_plan_of_the_next_batch_rides_with_the_expander(which):
+    """A stream of batches through mw_unpack_expand_index_plan_next on two contexts: the receive side
+    of every batch against the plain definition, and the riding plan of every next batch -- bitmaps,
+    perm, descriptors, statistics -- against the oracle's plan; batch sizes change from call to
+    call (one is empty, one has tokens that go nowhere, many tokens share their bitmap), and
+    mw_plan itself is used on the same contexts in between."""
+    w, my_rank = {"c1": (W.scaled(W.C1, n_tokens=333, hidden=512), 3),
+                  "c2": (W.scaled(W.C2, n_tokens=300, hidden=1024), 40),
+                  "c3": (W.scaled(W.C3, n_tokens=257, hidden=256), 200),
+                  "k12": (W.DispatchWorkload("k12", 22, 130, 260, 12, 200, 256, "bf16", "uniform"), 77),
+                  "one_rank": (W.DispatchWorkload("r1", 23, 1, 4, 2, 130, 256, "bf16", "uniform"), 0)}[which]
+    _say("riding plan", w.name)
+    e2r = W.expert_to_rank(w)
+    ctxs = [H.make_ctx(w, my_rank, max_tokens=1200), H.make_ctx(w, my_rank, max_tokens=1200)]
+    R = w.n_ranks
+    batches = []
+    for seed in (1, 2, 3, 4, 5):
+        recs, toks = [], []
+        for p in range(R):
+            tk = W.topk_ids(w, seed, p)
+            x, sc = W.payload_rows(w, seed, p)
+            recs.append(H.shrink(H.GpuSend(ctxs[0], tk, x, sc).deliver(my_rank)))
+            toks.append((tk, x, sc))
+        cap = max(1, sum(r["n_rows"] for r in recs) * min(w.top_k, w.experts_per_rank))
+        batches.append(dict(recs=recs, toks=toks, cap=cap, table=B.peers_table(recs, H.DEV)))
+    # the send-side batches whose plans ride along: sizes and contents vary
+    wide = W.scaled(w, n_tokens=1200)
+    sends = [W.topk_ids(w, 11, my_rank), W.topk_ids(wide, 12, my_rank), np.zeros((0, w.top_k), np.int32),
+             W.topk_ids(wide, 14, my_rank)[:700].copy(), W.topk_ids(w, 15, my_rank)[:65].copy()]
+    sends[1][::5] = -1                                     # tokens that go nowhere
+    sends[3][100:600] = sends[3][99]                       # one long run of equal bitmaps
+    sbufs = [B.SendBuffers(ctxs[0], 1200) for _ in sends]
+    bufs = [B.RecvBuffers(ctxs[i % 2], b["cap"]) for i, b in enumerate(batches)]
+    b0 = batches[0]
+    ctxs[0].mw_unpack_index(b0["table"], R, b0["cap"], bufs[0].expert_offsets, bufs[0].stats)
+    for i, b in enumerate(batches):
+        cur, buf = ctxs[i % 2], bufs[i]
+        nb, nbuf = batches[(i + 1) % len(batches)], bufs[(i + 1) % len(batches)]
+        tk_d = H.dev(sends[i]) if len(sends[i]) else torch.zeros((0, w.top_k), dtype=torch.int32, device=H.DEV)
+        if i + 1 < len(batches):
+            cur.mw_unpack_expand_index_plan_next(R, buf.out_rows, buf.out_scales, b["cap"], buf.out_src_peer,
+                                                 buf.out_src_token, ctxs[(i + 1) % 2], nb["table"], R, nb["cap"],
+                                                 nbuf.expert_offsets, nbuf.stats, tk_d, sbufs[i].mask, sbufs[i].perm,
+                                                 sbufs[i].desc, sbufs[i].stats)
+        else:
+            cur.mw_unpack_expand(R, buf.out_rows, buf.out_scales, b["cap"], buf.out_src_peer, buf.out_src_token)
+            cur.mw_plan(tk_d, sbufs[i].mask, sbufs[i].perm, sbufs[i].desc, sbufs[i].stats)
+        if i == 1:                                         # the two-kernel plan on the context the next ride uses
+            ctxs[(i + 2) % 2].mw_plan(H.dev(sends[0]), sbufs[0].mask, sbufs[0].perm, sbufs[0].desc, sbufs[0].stats)
+    torch.cuda.synchronize()
+    for i, b in enumerate(batches):
+        want = ref.dispatch_plain(b["toks"], e2r, my_rank, b["cap"])
+        st = ctxs[i % 2].mw_get_recv_stats(bufs[i].stats)
+        q = int(st["n_out_rows"])
+        assert int(st["error_flags"]) == 0 and q == len(want[2])
+        H.assert_same_bytes(H.host(bufs[i].expert_offsets), want[4], "batch %d expert_offsets" % i)
+        H.assert_same_bytes(H.host(bufs[i].out_src_peer)[:q], want[2], "batch %d out_src_peer" % i)
+        H.assert_same_bytes(H.host(bufs[i].out_src_token)[:q], want[3], "batch %d out_src_token" % i)
+        H.assert_same_bytes(H.host(bufs[i].out_rows)[:q], want[0], "batch %d out_rows" % i)
+        if want[1] is not None:
+            H.assert_same_bytes(H.host(bufs[i].out_scales)[:q], want[1], "batch %d out_scales" % i)
+    for i, tk in enumerate(sends):
+        _check_plan_outputs(w, ctxs[0], sbufs[i], tk, "riding plan %d" % i)
+    with pytest.raises(B.MwError) as ei:                          # more tokens than the context was made for
+        big = torch.zeros((1201, w.top_k), dtype=torch.int32, device=H.DEV)
+        ctxs[0].mw_unpack_expand_index_plan_next(R, bufs[0].out_rows, bufs[0].out_scales, batches[0]["cap"],
+                                                 bufs[0].out_src_peer, bufs[0].out_src_token, ctxs[1],
+                                                 batches[1]["table"], R, batches[1]["cap"], bufs[1].expert_offsets,
+                                                 bufs[1].stats, big, sbufs[0].mask, sbufs[0].perm, sbufs[0].desc,
+                                                 sbufs[0].stats)
+    assert ei.value.status == B.MW_ERR_CAPACITY
+    for c in ctxs:
+        c.close()
+
+
 def test_unpack_after_a_smaller_batch_strides_over_the_rows():
     """The expander's launch is sized from the row count seen at the last mw_get_recv_stats; a later,
     larger batch on the same context must still be expanded completely (and a smaller one too)."""
