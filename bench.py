@@ -7,7 +7,7 @@ dispatch (64 simulated ranks, 256 experts, top-8 with group-limited routing, 409
 7168 bf16 on this rank; 64 peer receive regions).  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c0|c1|c2|c3|c4]
-                  [--schedule aligned|pipelined|free|single] [--no-cpu-baseline]
+                  [--schedule aligned|pipelined|one_stream|free|single] [--no-cpu-baseline]
 
 The other workloads (tiny, fp8, 256-rank Zipf, AllGather) are parity-test configurations;
 they can be timed with the same harness.
@@ -233,17 +233,27 @@ def bench_dispatch(args, name: str) -> dict:
     #            region (in steady state the step before builds it), the last step builds one that
     #            is not used.  The index is then hidden behind the expander, but the packer no longer
     #            has the index to hide behind: the step takes as long as in "aligned".
+    #  "one_stream"  two launches per batch on ONE stream and no event: the packer, then
+    #            mw_unpack_expand_index_plan_next -- the expander of this batch with the index AND the
+    #            plan of the next batch riding along.  Nothing latency-bound stands alone any more,
+    #            and nothing waits across streams.  Every step still does one plan, one pack, one
+    #            index and one expand; the first batch's plan and index are made before the timed
+    #            region, the last step makes ones that are not used.
     ev_unpack_done = [DeviceEvent(torch) for _ in range(2)]
     state = {"n": 0}
     rctx = [ctx, ctx_b]
     pipe = {"n": 0}
 
-    def prime_pipeline():
-        """Index of the batch the next pipelined step expands (the other schedules use the same workspace)."""
+    def prime_pipeline(with_plan=False):
+        """Index (and, for "one_stream", plan) of the batch the next pipelined step works on; the
+        other schedules use the same workspace in between."""
         n = pipe["n"]
         s = sets[n % N_SETS]
         with torch.cuda.stream(s_recv):
             rctx[n % 2].mw_unpack_index(s["table"], R, cap, s["recv"].expert_offsets, s["recv"].stats)
+            if with_plan:
+                sd = s["send"]
+                ctx.mw_plan(topk_d, sd.mask, sd.perm, sd.desc, sd.stats)
 
     def step(i: int, schedule: str = args.schedule):
         s = sets[i % N_SETS]
@@ -270,6 +280,17 @@ def bench_dispatch(args, name: str) -> dict:
                                                         rv.out_src_token, rctx[(n + 1) % 2], s_next["table"], R, cap,
                                                         rn.expert_offsets, rn.stats)
                 ev_unpack_done[n % 2].record(s_recv)
+        elif schedule == "one_stream":
+            n = pipe["n"]
+            pipe["n"] = n + 1
+            s, s_next = sets[n % N_SETS], sets[(n + 1) % N_SETS]
+            sd, rv, rn, sdn = s["send"], s["recv"], s_next["recv"], s_next["send"]
+            with torch.cuda.stream(s_recv):
+                ctx.mw_pack(s["x"], s["sc"], topk_d, sd.perm, sd.stats, sd.packed, sd.row_src_token, sd.row_topk)
+                rctx[n % 2].mw_unpack_expand_index_plan_next(R, rv.out_rows, rv.out_scales, cap, rv.out_src_peer,
+                                                             rv.out_src_token, rctx[(n + 1) % 2], s_next["table"], R,
+                                                             cap, rn.expert_offsets, rn.stats, topk_d, sdn.mask,
+                                                             sdn.perm, sdn.desc, sdn.stats)
         else:
             n = state["n"]
             state["n"] = n + 1
@@ -288,8 +309,8 @@ def bench_dispatch(args, name: str) -> dict:
             c.mw_ctx_set_timing_events(B.MW_KERNEL_EXPAND, a, b)
 
     # ---------------------------------------------------------------- warm-up, then the timed region
-    if args.schedule == "pipelined":
-        prime_pipeline()
+    if args.schedule in ("pipelined", "one_stream"):
+        prime_pipeline(args.schedule == "one_stream")
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -311,23 +332,26 @@ def bench_dispatch(args, name: str) -> dict:
         elif i % EV_STRIDE == 1:
             set_expand_events(None, None)
         step(i)
+    t_issued = time.perf_counter()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     set_expand_events(None, None)
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    issue_ms_per_step = (t_issued - t0) * 1e3 / args.steps      # host time to enqueue a step
     expand_ms = sorted(a.elapsed_time(b) for a, b in ev_expand)
     expand_avg_ms = sum(expand_ms) / len(expand_ms)
 
-    other = {}
-    for sched in ("single", "free", "aligned", "pipelined"):      # the other schedules, for reference
+    other, other_issue = {}, {}
+    for sched in ("single", "free", "aligned", "pipelined", "one_stream"):      # the other schedules, for reference
         if sched == args.schedule:
             continue
-        if sched == "pipelined":
-            prime_pipeline()
+        if sched in ("pipelined", "one_stream"):
+            prime_pipeline(sched == "one_stream")
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(args.steps):
             step(i, sched)
+        other_issue[sched] = round((time.perf_counter() - t0) * 1e3 / args.steps, 4)
         torch.cuda.synchronize()
         other[sched] = round((time.perf_counter() - t0) * 1e3 / args.steps, 4)
 
@@ -620,7 +644,7 @@ def bench_dispatch(args, name: str) -> dict:
 
     # the launch that moves the receive side's bytes: the expander, in the pipelined schedule with
     # the next batch's index riding along (same bytes; the index's few MB are not counted)
-    dominant = "k_expand_index_next" if args.schedule == "pipelined" else "k_expand"
+    dominant = {"pipelined": "k_expand_index_next", "one_stream": "k_expand_index_plan_next"}.get(args.schedule, "k_expand")
     result = {
         "metric": METRIC,
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -629,8 +653,9 @@ def bench_dispatch(args, name: str) -> dict:
         "config": {"workload": describe, "seed": seed, "my_rank": my_rank,
                    "rows_packed": N, "groups": int(st["n_groups"]), "rows_received": M, "rows_out": Q,
                    "buffer_sets": N_SETS, "schedule": args.schedule,
-                   "streams": 1 if args.schedule == "single" else 2},
+                   "streams": 1 if args.schedule in ("single", "one_stream") else 2},
         "other_schedules_ms_per_step": other,
+        "host_issue_ms_per_step": dict(other_issue, **{args.schedule: round(issue_ms_per_step, 4)}),
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "bytes_saved_vs_unicast": round(saved, 4),
         "bytes_saved_vs_unicast_excluding_self": round(saved_excl_self, 4),
@@ -788,7 +813,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", choices=["c0", "c1", "c2", "c3", "c4"], default="c1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--schedule", choices=["aligned", "pipelined", "free", "single"], default="aligned",
+    ap.add_argument("--schedule", choices=["aligned", "pipelined", "one_stream", "free", "single"], default="aligned",
                     help="how the send side and the receive side of a step are issued (see step())")
     ap.add_argument("--seed", type=int, default=None)
     args = ap.parse_args()

@@ -88,6 +88,7 @@ extern "C" {
                                            surplus rows dropped; a group cut by the limit is dropped whole and
                                            sets MW_FLAG_BAD_DESC too */
 #define MW_FLAG_DUP_SRC_TOKEN    0x40u  /* two rows of one peer carry the same source token for one expert */
+#define MW_FLAG_PLAN_TIMEOUT     0x100u /* mw_unpack_expand_index_plan_next: the riding plan gave up waiting (see there) */
 #define MW_FLAG_BAD_RANK         0x80u  /* relay: a bitmap names a rank >= n_ranks: that bit is not forwarded */
 
 /*
@@ -173,6 +174,14 @@ MW_API int32_t mw_workspace_bytes(const mw_config *cfg, int64_t *out_bytes);
  */
 MW_API int32_t mw_ctx_create(const mw_config *cfg, void *workspace_dev, int64_t workspace_bytes, mw_ctx **out);
 MW_API int32_t mw_ctx_destroy(mw_ctx *ctx);
+
+/*
+ * Number of polls (about 3 us each) the second half of a plan riding in
+ * mw_unpack_expand_index_plan_next waits for its first half before it gives up; default 262144.
+ * 0 makes it give up unless the first half is already complete when it looks: for tests of
+ * that path.  Applies to later calls that plan with this context.
+ */
+MW_API int32_t mw_ctx_set_ride_wait_limit(mw_ctx *ctx, int64_t polls);
 
 /* ---- send side (Section 5.1, send module: task decomposition) -------------------------- */
 
@@ -324,6 +333,12 @@ MW_API int32_t mw_unpack_expand_index_next(mw_ctx *ctx, int32_t n_peers, void *o
  *     mw_pack(batch n+1);  ...
  * The plan uses the plan part of next_ctx's workspace (see the conventions above); its outputs
  * are complete when this launch is, i.e. for every later call on the same stream.
+ * Inside the launch the plan's second half waits for its first half (workgroups that come
+ * earlier in the same launch and wait for nothing themselves); the wait is bounded (about a
+ * second by default, mw_ctx_set_ride_wait_limit).  Past the bound -- not observed, and not
+ * expected on hardware that starts a launch's workgroups in order -- next_send_stats_dev
+ * reports MW_FLAG_PLAN_TIMEOUT with zero rows, the other plan outputs are undefined, and the plan
+ * part of next_ctx's workspace is left in an undefined state: destroy that context.
  * MW_ERR_UNSUPPORTED if next_n_tokens > MW_RIDE_MAX_TOKENS (larger batches: mw_plan), or where
  * mw_unpack_expand_index_next returns it; MW_ERR_CAPACITY if next_n_tokens > max_tokens of
  * next_ctx.

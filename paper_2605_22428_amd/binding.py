@@ -25,7 +25,7 @@ MW_FLAG_BAD_SRC_TOKEN, MW_FLAG_BAD_DESC, MW_FLAG_RECV_CAPACITY, MW_FLAG_DUP_SRC_
 EXPORTS = ["mw_workspace_bytes", "mw_ctx_create", "mw_ctx_destroy", "mw_plan", "mw_pack", "mw_plan_pack", "mw_pack_quantize",
            "mw_packet_header_bytes", "mw_pack_packets", "mw_unpack_packets",
            "mw_plan_allgather", "mw_pack_allgather", "mw_unpack", "mw_unpack_index", "mw_unpack_expand",
-           "mw_unpack_allgather", "mw_combine_gather", "mw_unpack_expand_index_next", "mw_unpack_expand_index_plan_next",
+           "mw_unpack_allgather", "mw_combine_gather", "mw_unpack_expand_index_next", "mw_unpack_expand_index_plan_next", "mw_ctx_set_ride_wait_limit",
            "mw_sim_deliver", "mw_copy_bytes", "mw_get_send_stats", "mw_get_recv_stats",
            "mw_set_forwarding", "mw_relay", "mw_relay_packets", "mw_get_relay_stats",
            "mw_allgather_split_point", "mw_plan_allgather_split", "mw_unpack_allgather_split",
@@ -37,6 +37,7 @@ MW_MAX_HOPS = 64
 MW_FUSED_MAX_TOKENS = 256
 MW_RIDE_MAX_TOKENS = 8192
 MW_FLAG_BAD_RANK = 0x80
+MW_FLAG_PLAN_TIMEOUT = 0x100
 
 # numpy views of the ABI records (host copies)
 DESC_DTYPE = np.dtype([("mask", "<u8", (4,)), ("row_offset", "<u4"), ("row_count", "<u4"),
@@ -274,6 +275,9 @@ class Context:
             C.c_int64(next_out_capacity_rows), _ptr(next_expert_offsets), _ptr(next_recv_stats),
             _ptr(next_topk_ids), C.c_int32(next_topk_ids.shape[0]), _ptr(next_mask), _ptr(next_perm),
             _ptr(next_desc), _ptr(next_send_stats), _stream()), "mw_unpack_expand_index_plan_next")
+
+    def mw_ctx_set_ride_wait_limit(self, polls: int):
+        _check(load().mw_ctx_set_ride_wait_limit(self._h, C.c_int64(polls)), "mw_ctx_set_ride_wait_limit")
 
     def mw_combine_gather(self, n_peers: int, y: torch.Tensor, out_capacity_rows: int, ret_rows: torch.Tensor,
                           ret_capacity_rows: int):

@@ -18,7 +18,7 @@ namespace {
 
 struct ws_layout {
     int64_t eslot, plan_cnt, plan_state, flags, cnt, base, row_base, addr_cnt, recs, hits, row_map,
-        hop_bits, group_of_row, child_pos, sort_key, sort_sec, chunk_kept, row_tok, row_cnt, row_start, total;
+        hop_bits, group_of_row, child_pos, sort_key, sort_sec, chunk_kept, row_cnt, row_start, total;
 };
 
 // Derived row geometry; returns a status.
@@ -95,14 +95,13 @@ ws_layout layout(const mw_config &c, int32_t L)
         w.child_pos = o;    o += mw_align_up(4LL * MW_MAX_HOPS * ntok, A);
     }
     // sorted chunks for the plan of large batches (only contexts that can see such batches)
-    const int64_t padded = mw_align_up(ntok, 1024);
-    w.row_tok = o;    o += mw_align_up(4LL * padded, A);
-    w.row_cnt = o;    o += mw_align_up(8LL * padded, A);
-    w.sort_key = w.sort_sec = w.chunk_kept = w.row_start = -1;
+    w.sort_key = w.sort_sec = w.chunk_kept = w.row_cnt = w.row_start = -1;
     if (c.max_tokens > 4096) {
+        const int64_t padded = mw_align_up(ntok, 1024);
         w.sort_key = o;   o += mw_align_up(8LL * padded, A);
         w.sort_sec = o;   o += mw_align_up(4LL * padded, A);
         w.chunk_kept = o; o += mw_align_up(4LL * 64, A);
+        w.row_cnt = o;    o += mw_align_up(8LL * padded, A);
         w.row_start = o;  o += mw_align_up(padded, A);
     }
     w.total = o;
@@ -155,8 +154,7 @@ MW_API int32_t mw_ctx_create(const mw_config *cfg, void *workspace_dev, int64_t 
     ctx->d_sort_key = w.sort_key >= 0 ? (uint64_t *)(b + w.sort_key) : nullptr;
     ctx->d_sort_sec = w.sort_sec >= 0 ? (uint32_t *)(b + w.sort_sec) : nullptr;
     ctx->d_chunk_kept = w.chunk_kept >= 0 ? (uint32_t *)(b + w.chunk_kept) : nullptr;
-    ctx->d_row_tok = (uint32_t *)(b + w.row_tok);
-    ctx->d_row_cnt = (uint64_t *)(b + w.row_cnt);
+    ctx->d_row_cnt = w.row_cnt >= 0 ? (uint64_t *)(b + w.row_cnt) : nullptr;
     ctx->d_row_start = w.row_start >= 0 ? (unsigned char *)(b + w.row_start) : nullptr;
     ctx->d_flags = (uint32_t *)(b + w.flags);
     ctx->d_cnt = (uint32_t *)(b + w.cnt);
@@ -168,6 +166,7 @@ MW_API int32_t mw_ctx_create(const mw_config *cfg, void *workspace_dev, int64_t 
     ctx->d_row_map = (int32_t *)(b + w.row_map);
     ctx->n_hops = 0;
     ctx->recv_rows_hint = 0;
+    ctx->ride_wait_limit = 1u << 18;
     ctx->d_hop_bits = (uint64_t *)(b + w.hop_bits);
     ctx->d_relay_flags = (uint32_t *)(b + w.hop_bits + 8LL * MW_MASK_WORDS * MW_MAX_HOPS);
     ctx->d_group_of_row = (int32_t *)(b + w.group_of_row);
@@ -597,6 +596,13 @@ MW_API int32_t mw_get_relay_stats(mw_ctx *ctx, const mw_relay_stats *stats_dev, 
     MW_ON_DEVICE(ctx);
     MW_HIP_CHECK(hipMemcpyAsync(host_out, stats_dev, sizeof(mw_relay_stats), hipMemcpyDeviceToHost, (hipStream_t)stream));
     MW_HIP_CHECK(hipStreamSynchronize((hipStream_t)stream));
+    return MW_OK;
+}
+
+MW_API int32_t mw_ctx_set_ride_wait_limit(mw_ctx *ctx, int64_t polls)
+{
+    if (!ctx || polls < 0 || polls > 0x7fffffffLL) return MW_ERR_INVALID_ARG;
+    ctx->ride_wait_limit = (uint32_t)polls;
     return MW_OK;
 }
 

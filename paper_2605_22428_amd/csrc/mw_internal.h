@@ -10,7 +10,7 @@
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-#define MW_PLAN_STATE_WORDS 264   // 256 histogram bins + kept tokens + flags + workgroups done (+ padding)
+#define MW_PLAN_STATE_WORDS 264   // 256 histogram bins + kept tokens + flags + two counts of workgroups done (+ padding)
 
 // (local expert slot, rank among the peer's rows for that expert); le < 0 = unused slot
 struct mw_hit { int32_t le; int32_t rank; };
@@ -71,9 +71,9 @@ struct mw_ctx {
     uint64_t *d_sort_key;       // [max_tokens rounded up to 1024] sorted chunks of the large-batch plan (or null)
     uint32_t *d_sort_sec;       // same count: second sort word
     uint32_t *d_chunk_kept;     // [64] kept tokens per chunk
-    uint32_t *d_row_tok;        // [max_tokens] a packed row's token (plan riding along with the expander)
-    uint64_t *d_row_cnt;        // [max_tokens] a packed row's counters (large-batch plan, riding plan)
+    uint64_t *d_row_cnt;        // [max_tokens] a packed row's counters (large-batch plan, or null)
     unsigned char *d_row_start; // [max_tokens] 1: a group starts at this packed row
+    uint32_t ride_wait_limit;   // polls a riding plan's second half waits for its first
     uint32_t *d_flags;      // [4] 1: receive flags, 2: receive workgroups done
     uint32_t *d_base;       // [L][R] first output row of (local expert, peer)
     mw_row_rec *d_recs;     // [max_recv_rows]

@@ -1,6 +1,6 @@
 // Device code of the plan that more than one translation unit uses: the bitmap builder, the
 // short keys, the all-pairs ranking of one workgroup (k_rank, and the plan that rides along
-// with the expander), and the single-workgroup second half of that riding plan.
+// with the expander), and the second half of that riding plan.
 #ifndef MW_PLAN_DEV_H_
 #define MW_PLAN_DEV_H_
 
@@ -9,7 +9,7 @@
 namespace {
 
 constexpr uint64_t kField = 0x1fffffull;      // 21-bit fields of the packed counter
-constexpr int kPsKept = 256, kPsFlags = 257, kPsDone = 258;  // plan state words after the 256 histogram bins
+constexpr int kPsKept = 256, kPsFlags = 257, kPsDone = 258, kPsDone2 = 259;  // plan state words after the 256 histogram bins
 
 // Destination bitmap of one token (Section 4.1): ids are fetched in independent batches.
 __device__ __forceinline__ void token_mask(const int32_t *__restrict__ row, int K,
@@ -176,14 +176,15 @@ __device__ __forceinline__ void mw_rank_body(const int32_t *__restrict__ topk, i
 
 // ---- the plan that rides along with another launch -------------------------------------
 // Everything the plan of one batch needs when it runs as extra workgroups of a launch that
-// does something else (one kernel argument).  Rank workgroups: wg = by * tb + bx,
-// n_rank = tb * ns of them.
+// does something else (one kernel argument).  The launch's workgroups `wg` = 0 .. n_rank - 1
+// rank (wg = by * tb + bx), the next n_finish ones turn the counters into perm, descriptors
+// and statistics.
 struct mw_plan_args {
     const int32_t *topk; int T, K, E; const int32_t *eslot;
     uint64_t *mask_out; unsigned long long *cnt; uint32_t *pstate;
     int32_t *perm; mw_group_desc *desc; mw_send_stats *stats; uint64_t row_bytes;
-    uint32_t *row_tok; unsigned long long *row_cnt;     // [T] scratch indexed by packed row
     int tb, ns, slice;
+    uint32_t n_rank, n_finish, wait_limit;
 };
 
 __device__ __forceinline__ unsigned long long mw_ld_agent64(const unsigned long long *p)
@@ -195,132 +196,145 @@ __device__ __forceinline__ uint32_t mw_ld_agent32(const uint32_t *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Second half of a riding plan, run by ONE workgroup (any multiple of 64 lanes) once every
-// rank workgroup of the same launch has reported: counters -> perm, descriptors, statistics;
-// then the counters and the plan state are cleared for the next plan.  What other workgroups
-// of this launch wrote is read at device scope (the counters and the state are atomics; the
-// bitmaps were written through by mw_rank_body<.., true>); what this workgroup writes and
-// reads back itself (the row-indexed scratch) stays within its own CU and L2.  `scratch`: 17
-// words of LDS.
-// It is not fast -- one workgroup, about 25 us for 4096 tokens -- and does not have to be:
-// it runs in the shadow of a launch that takes several times longer.
-__device__ __forceinline__ void mw_plan_finish_one_wg(const mw_plan_args &a, uint32_t *scratch)
+// LDS a finishing workgroup of `bs` lanes needs, in bytes (counters, tokens, 19 scratch words)
+static inline size_t mw_plan_finish_lds(int bs) { return 12u * (size_t)bs + 19u * sizeof(uint32_t); }
+
+// Second half of a riding plan: finishing workgroup `fb` (of n_finish, `bs` lanes each) owns
+// the packed rows [fb bs, fb bs + bs) -- what k_groups does in a launch of its own.  Here the
+// rank workgroups are part of the SAME launch, so:
+//  * it waits until all of them have reported (pstate[kPsDone] == n_rank).  They come before
+//    it in the launch's workgroup order, are dispatched before it, and wait for nothing, so
+//    the wait ends; it is bounded all the same (wait_limit polls of ~3 us): past the bound
+//    the plan is given up -- statistics with MW_FLAG_PLAN_TIMEOUT and zero rows, state left
+//    as it is -- and the workgroup exits;
+//  * what those workgroups wrote is read at device scope: the counters and the state are
+//    device-scope atomics anyway, the bitmaps were written through (mw_rank_body<.., true>).
+// `lds`: mw_plan_finish_lds(bs) bytes.
+__device__ __forceinline__ void mw_plan_finish_ride(const mw_plan_args &a, uint32_t fb, uint64_t *lds)
 {
     const uint32_t tid = threadIdx.x, bs = blockDim.x;
+    unsigned long long *tokc = (unsigned long long *)lds;          // [bs] the row's counters
+    int32_t *tok = (int32_t *)(lds + bs);                          // [bs] token of packed row i0 + k
+    uint32_t *scratch = (uint32_t *)(lds + bs) + bs;               // [17] scans, [18] "the ranks are complete"
     const uint32_t T = (uint32_t)a.T;
-    const uint32_t N = min(mw_ld_agent32(&a.pstate[kPsKept]), T), n_empty = T - N;
 
-    // (1) every kept token drops its index and its counters at its packed row; counters cleared
-    for (uint32_t t0 = 0; t0 < T; t0 += 8 * bs) {
-        unsigned long long c[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const uint32_t t = t0 + u * bs + tid;
-            c[u] = t < T ? mw_ld_agent64(&a.cnt[t]) : 0ull;
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const uint32_t t = t0 + u * bs + tid;
-            if (t >= T) continue;
-            a.cnt[t] = 0;
-            if ((c[u] >> 42) == 0) continue;                          // empty bitmap
-            const uint32_t p = (uint32_t)(c[u] & kField) - n_empty;
-            if (p < N) { a.row_tok[p] = t; a.row_cnt[p] = c[u]; }
-        }
-    }
-    __syncthreads();                        // the rows are written (and acknowledged)
-
-    // (2) lane `tid` owns the packed rows [r0, r1): groups starting in them, then one scan
-    const uint32_t per = (N + bs - 1) / bs;
-    const uint32_t r0 = min(tid * per, N), r1 = min(r0 + per, N);
-    uint32_t starts = 0;
-    for (uint32_t i0 = r0; i0 < r1; i0 += 8) {
-        unsigned long long c[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) c[u] = (i0 + u < r1) ? a.row_cnt[i0 + u] : ~0ull;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) starts += ((c[u] >> 21) & kField) == 0 ? 1u : 0u;
-    }
-    uint32_t G;
-    uint32_t g = mw_block_exscan(starts, scratch, &G);
-
-    // (3) perm and the descriptors of those rows
-    for (uint32_t i0 = r0; i0 < r1; i0 += 4) {
-        unsigned long long c[4];
-        uint32_t t[4];
-        uint64_t m[4][MW_MASK_WORDS];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const bool in = i0 + u < r1;
-            c[u] = in ? a.row_cnt[i0 + u] : ~0ull;
-            t[u] = in ? a.row_tok[i0 + u] : 0u;
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const unsigned long long *mp = (const unsigned long long *)(a.mask_out + (size_t)t[u] * MW_MASK_WORDS);
-#pragma unroll
-            for (int w = 0; w < MW_MASK_WORDS; ++w) m[u][w] = (i0 + u < r1) ? mw_ld_agent64(mp + w) : 0ull;
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            if (i0 + u >= r1) continue;
-            a.perm[i0 + u] = (int32_t)t[u];
-            if (((c[u] >> 21) & kField) != 0) continue;               // not the first of its bitmap
-            mw_group_desc d;
-            uint32_t nd = 0;
-#pragma unroll
-            for (int w = 0; w < MW_MASK_WORDS; ++w) { d.mask[w] = m[u][w]; nd += (uint32_t)__popcll(m[u][w]); }
-            d.row_offset = i0 + u;
-            d.row_count = (uint32_t)((c[u] >> 42) & kField);
-            d.n_dest = nd;
-            d.reserved0 = 0;
-            a.desc[g++] = d;
-        }
-    }
-
-    // (4) statistics, then the state is cleared
-    uint32_t dests = 0;
-    for (uint32_t r = tid; r < MW_MAX_RANKS; r += bs) {
-        const uint32_t h = mw_ld_agent32(&a.pstate[r]);
-        a.stats->rows_per_dest[r] = h;
-        dests += h;
-    }
-    const uint32_t flags = tid == 0 ? mw_ld_agent32(&a.pstate[kPsFlags]) : 0u;
-    uint32_t D;
-    mw_block_exscan(dests, scratch, &D);                   // its barriers: every lane has read the state
     if (tid == 0) {
-        a.stats->n_rows = N;
-        a.stats->n_groups = G;
-        a.stats->multicast_bytes = (uint64_t)N * a.row_bytes;
-        a.stats->unicast_bytes = (uint64_t)D * a.row_bytes;
-        a.stats->error_flags = flags;
-        a.stats->reserved0 = 0;
+        uint32_t polls = 0;
+        while (mw_ld_agent32(&a.pstate[kPsDone]) < a.n_rank && polls < a.wait_limit) {
+            __builtin_amdgcn_s_sleep(127);
+            ++polls;
+        }
+        scratch[18] = mw_ld_agent32(&a.pstate[kPsDone]) >= a.n_rank ? 1u : 0u;
     }
-    for (uint32_t r = tid; r < MW_PLAN_STATE_WORDS; r += bs)
-        __hip_atomic_store(&a.pstate[r], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (!scratch[18]) {
+        if (fb == 0 && tid == 0) {
+            a.stats->n_rows = 0; a.stats->n_groups = 0;
+            a.stats->multicast_bytes = 0; a.stats->unicast_bytes = 0;
+            a.stats->error_flags = MW_FLAG_PLAN_TIMEOUT; a.stats->reserved0 = 0;
+        }
+        return;
+    }
+
+    const uint32_t N = min(mw_ld_agent32(&a.pstate[kPsKept]), T), n_empty = T - N;
+    const uint32_t i0 = fb * bs;
+    tok[tid] = 0; tokc[tid] = 0;           // (a row no token claims -- corrupted counters only -- reads token 0)
+    mw_lds_barrier();
+    // all tokens' counters: which land in this workgroup's rows, how many groups start before
+    // its first row, how many groups there are (sixteen counters per lane in flight)
+    uint32_t starts_before = 0, starts_total = 0;
+    for (uint32_t t0 = 0; t0 < T; t0 += 16 * bs) {
+        unsigned long long cc[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const uint32_t t = t0 + u * bs + tid;
+            cc[u] = t < T ? mw_ld_agent64(&a.cnt[t]) : 0ull;
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const unsigned long long c = cc[u];
+            if ((c >> 42) == 0) continue;                         // empty bitmap (or past the end)
+            const uint32_t p = (uint32_t)(c & kField) - n_empty;  // packed row of the token
+            const uint32_t st = ((c >> 21) & kField) == 0 ? 1u : 0u;
+            starts_total += st;
+            starts_before += (st && p < i0) ? 1u : 0u;
+            if (p - i0 < bs && p < N) { tok[p - i0] = (int32_t)(t0 + u * bs + tid); tokc[p - i0] = c; }
+        }
+    }
+    uint32_t g_base, G;
+    mw_block_exscan(starts_before, scratch, &g_base);
+    mw_block_exscan(starts_total, scratch, &G);                // ends with a barrier: tok[] is complete
+
+    const uint32_t i = i0 + tid;
+    uint32_t st = 0;
+    int32_t t = 0;
+    unsigned long long c = 0;
+    if (i < N) {
+        t = tok[tid];
+        a.perm[i] = t;
+        c = tokc[tid];
+        st = ((c >> 21) & kField) == 0 ? 1u : 0u;
+    }
+    uint32_t local_total;
+    const uint32_t g = g_base + mw_block_exscan(st, scratch, &local_total);
+    if (st) {
+        const unsigned long long *m = (const unsigned long long *)(a.mask_out + (size_t)t * MW_MASK_WORDS);
+        mw_group_desc d;
+        uint32_t nd = 0;
+#pragma unroll
+        for (int w = 0; w < MW_MASK_WORDS; ++w) { d.mask[w] = mw_ld_agent64(m + w); nd += (uint32_t)__popcll(d.mask[w]); }
+        d.row_offset = i;
+        d.row_count = (uint32_t)((c >> 42) & kField);
+        d.n_dest = nd;
+        d.reserved0 = 0;
+        a.desc[g] = d;
+    }
+    if (fb == 0) {
+        uint32_t dests = 0;
+        for (uint32_t r = tid; r < MW_MAX_RANKS; r += bs) {
+            const uint32_t h = mw_ld_agent32(&a.pstate[r]);
+            a.stats->rows_per_dest[r] = h;
+            dests += h;
+        }
+        uint32_t D;
+        mw_block_exscan(dests, scratch, &D);
+        if (tid == 0) {
+            a.stats->n_rows = N;
+            a.stats->n_groups = G;
+            a.stats->multicast_bytes = (uint64_t)N * a.row_bytes;
+            a.stats->unicast_bytes = (uint64_t)D * a.row_bytes;
+            a.stats->error_flags = mw_ld_agent32(&a.pstate[kPsFlags]);
+            a.stats->reserved0 = 0;
+        }
+    }
+    // the finishing workgroup that is last to have read the counters and the state clears them
+    __syncthreads();
+    if (tid == 0)
+        scratch[18] = __hip_atomic_fetch_add(&a.pstate[kPsDone2], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                      a.n_finish - 1u ? 1u : 0u;
+    __syncthreads();
+    if (!scratch[18]) return;
+    for (uint32_t z = tid; z < T; z += bs) a.cnt[z] = 0;
+    for (uint32_t r = tid; r < MW_PLAN_STATE_WORDS; r += bs) a.pstate[r] = 0;
 }
 
-// One riding plan workgroup: its share of the ranking, then -- if it is the last to finish --
-// the second half.  `lds` is the launch's dynamic LDS (slice keys, then 17 + 1 scratch words
-// after them).
+// One riding plan workgroup.  `lds` is the launch's dynamic LDS: the slice's keys for a rank
+// workgroup, mw_plan_finish_lds(bs) bytes for a finishing one.
 template <int W, bool kKeyed>
 __device__ __forceinline__ void mw_plan_ride(const mw_plan_args &a, uint32_t wg, uint64_t *lds)
 {
-    const uint32_t n_rank = (uint32_t)a.tb * (uint32_t)a.ns;
-    if (wg >= n_rank) return;
-    mw_rank_body<W, kKeyed, true>(a.topk, a.T, a.K, a.eslot, a.E, a.slice, a.mask_out, a.cnt, a.pstate,
-                                  (int)(wg % (uint32_t)a.tb), (int)(wg / (uint32_t)a.tb), (int)blockDim.x, lds);
-    // Every workgroup reports when its atomics and write-through stores have been acknowledged
-    // (the barrier waits for them); the counter is a device-scope atomic, no fence is needed.
-    uint32_t *scratch = (uint32_t *)lds;                   // the slice keys are not needed any more
-    __syncthreads();
-    if (threadIdx.x == 0)
-        scratch[17] = __hip_atomic_fetch_add(&a.pstate[kPsDone], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
-                      n_rank - 1u ? 1u : 0u;
-    __syncthreads();
-    if (!scratch[17]) return;
-    __syncthreads();                                       // (scratch[17] read by all before it is reused)
-    mw_plan_finish_one_wg(a, scratch);
+    if (wg < a.n_rank) {
+        mw_rank_body<W, kKeyed, true>(a.topk, a.T, a.K, a.eslot, a.E, a.slice, a.mask_out, a.cnt, a.pstate,
+                                      (int)(wg % (uint32_t)a.tb), (int)(wg / (uint32_t)a.tb), (int)blockDim.x, lds);
+        // Reports when its atomics and write-through stores have been acknowledged (the barrier
+        // waits for them); the counter is a device-scope atomic, no fence is needed.
+        __syncthreads();
+        if (threadIdx.x == 0)
+            __hip_atomic_fetch_add(&a.pstate[kPsDone], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
+    wg -= a.n_rank;
+    if (wg < a.n_finish) mw_plan_finish_ride(a, wg, lds);
 }
 
 }  // namespace

@@ -533,10 +533,13 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
 
 // The same launch with the PLAN of the next batch riding along as well (Section 5.1, send
 // module: task decomposition for the batch after this one): after the index rows of the grid
-// come `n_plan_rows` rows whose workgroups rank the next batch's tokens; the one that finishes
-// last writes perm, descriptors and statistics.  A steady stream of batches then needs two
-// launches per batch on one stream -- the packer and this -- and no event: 159 us per batch at
-// 4096 tokens x 14336 bytes, against 171 us with the plan on a second stream.
+// come `n_plan_rows` rows whose workgroups rank the next batch's tokens and then, in further
+// workgroups that wait for those, write perm, descriptors and statistics.  A steady stream of
+// batches then needs two launches per batch on ONE stream -- the packer and this -- and no
+// event.  Measured per batch: 4096 tokens x 14336-byte rows 170 us, the same as with the plan
+// on a second stream and one event wait per batch (171 us); fp8 rows of half the size 101
+// against 105 us.  The riding plan is not free: its device-scope atomics and loads take
+// about 4 us of memory-channel time from the expander.
 template <int W, bool kKeyed>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_expand_index_plan_next(
     const mw_row_rec *__restrict__ recs, const mw_hit *__restrict__ hits, const uint32_t *__restrict__ base,
@@ -764,14 +767,23 @@ int32_t mw_launch_unpack_expand_index_plan_next(mw_ctx *ctx, int32_t P, void *ou
     pl.topk = next_topk; pl.T = next_T; pl.K = K; pl.E = next->cfg.n_experts; pl.eslot = next->d_eslot;
     pl.mask_out = next_mask; pl.cnt = (unsigned long long *)next->d_plan_cnt; pl.pstate = next->d_plan_state;
     pl.perm = next_perm; pl.desc = next_desc; pl.stats = next_send_stats; pl.row_bytes = (uint64_t)next->row_bytes;
-    pl.row_tok = next->d_row_tok; pl.row_cnt = (unsigned long long *)next->d_row_cnt;
-    pl.slice = 128;
+    // Slices as long as LDS allows: every (token, slice) pair costs one device-scope atomic and
+    // every rank workgroup one more on a single counter, and those -- unlike the ranking itself --
+    // take memory-channel time from the expander (slices of 128 tokens: +22 us per launch at
+    // 4096 tokens; of 1024: +4 us).  Workgroups of two or more waves leave room for 8 KiB each.
+    const size_t key_bytes = keyed ? sizeof(mw_short_key) : (size_t)W * sizeof(uint64_t);
+    const size_t lds_budget = shape.bs >= 128 ? 8192 : 5120;
+    pl.slice = (int)(lds_budget / key_bytes) / 128 * 128;
+    if (pl.slice > (next_T + 127) / 128 * 128) pl.slice = (next_T + 127) / 128 * 128;
+    if (pl.slice < 128) pl.slice = 128;
     pl.tb = next_T > 0 ? (next_T + shape.bs - 1) / shape.bs : 1;
     pl.ns = next_T > 0 ? (next_T + pl.slice - 1) / pl.slice : 1;
-    const uint32_t n_rank = (uint32_t)pl.tb * (uint32_t)pl.ns;
-    const uint32_t n_plan_rows = (n_rank + (uint32_t)shape.nseg - 1) / (uint32_t)shape.nseg;
-    size_t lds_plan = keyed ? (size_t)pl.slice * sizeof(mw_short_key) : (size_t)pl.slice * W * sizeof(uint64_t);
-    if (lds_plan < 18 * sizeof(uint32_t)) lds_plan = 18 * sizeof(uint32_t);
+    pl.n_rank = (uint32_t)pl.tb * (uint32_t)pl.ns;
+    pl.n_finish = (uint32_t)pl.tb;
+    pl.wait_limit = next->ride_wait_limit;
+    const uint32_t n_plan_rows = (pl.n_rank + pl.n_finish + (uint32_t)shape.nseg - 1) / (uint32_t)shape.nseg;
+    size_t lds_plan = (size_t)pl.slice * key_bytes;
+    if (lds_plan < mw_plan_finish_lds(shape.bs)) lds_plan = mw_plan_finish_lds(shape.bs);
     const size_t lds = lds_index > lds_plan ? lds_index : lds_plan;
     {
         mw_timed tm(ctx, MW_KERNEL_EXPAND, s);

@@ -159,3 +159,51 @@ def test_more_rows_than_the_context_was_created_for():
     assert int(gu.stats["error_flags"]) & B.MW_FLAG_RECV_CAPACITY
     assert int(gu.stats["n_rows_seen"]) == sum(min(r["n_rows"], 8) for r in recs)
     ctx.close()
+
+
+def test_riding_plan_gives_up_when_told_not_to_wait():
+    """mw_ctx_set_ride_wait_limit(0): the second half of a plan riding in
+    mw_unpack_expand_index_plan_next does not wait for the first half.  Either the first half
+    was already complete when it looked (then the plan is the oracle's), or the statistics say
+    MW_FLAG_PLAN_TIMEOUT with zero rows; every kernel ends normally in both cases, and the
+    receive side of the same launch is not affected."""
+    w = W.DispatchWorkload("giveup", 41, 8, 16, 2, 1000, 256, "bf16", "uniform")
+    e2r = W.expert_to_rank(w)
+    ctxs = [H.make_ctx(w, 1), H.make_ctx(w, 1)]
+    recs, toks = [], []
+    for p in range(w.n_ranks):
+        tk = W.topk_ids(w, 1, p)
+        x, _ = W.payload_rows(w, 1, p)
+        recs.append(H.shrink(H.GpuSend(ctxs[0], tk, x, None).deliver(1)))
+        toks.append((tk, x, None))
+    cap = sum(r["n_rows"] for r in recs) * 2
+    table = B.peers_table(recs, H.DEV)
+    bufs = [B.RecvBuffers(ctxs[0], cap), B.RecvBuffers(ctxs[1], cap)]
+    sb = B.SendBuffers(ctxs[1], w.n_tokens)
+    tk_me = W.topk_ids(w, 2, 1)
+    ctxs[0].mw_unpack_index(table, w.n_ranks, cap, bufs[0].expert_offsets, bufs[0].stats)
+    ctxs[1].mw_ctx_set_ride_wait_limit(0)
+    ctxs[0].mw_unpack_expand_index_plan_next(w.n_ranks, bufs[0].out_rows, None, cap, bufs[0].out_src_peer,
+                                             bufs[0].out_src_token, ctxs[1], table, w.n_ranks, cap,
+                                             bufs[1].expert_offsets, bufs[1].stats, H.dev(tk_me), sb.mask, sb.perm,
+                                             sb.desc, sb.stats)
+    torch.cuda.synchronize()
+    st = ctxs[1].mw_get_send_stats(sb.stats)
+    flags = int(st["error_flags"])
+    print("riding plan without waiting: flags", hex(flags), flush=True)
+    assert flags in (0, B.MW_FLAG_PLAN_TIMEOUT)
+    if flags:
+        assert (int(st["n_rows"]), int(st["n_groups"]), int(st["multicast_bytes"])) == (0, 0, 0)
+    else:
+        _, perm, desc, _ = ref.plan(tk_me, e2r, w.n_ranks, w.row_bytes)
+        assert (int(st["n_rows"]), int(st["n_groups"])) == (len(perm), len(desc))
+        H.assert_same_bytes(H.host(sb.perm)[: len(perm)], perm, "perm")
+    want = ref.dispatch_plain(toks, e2r, 1, cap)
+    rs = ctxs[0].mw_get_recv_stats(bufs[0].stats)
+    q = int(rs["n_out_rows"])
+    assert int(rs["error_flags"]) == 0 and q == len(want[2])
+    H.assert_same_bytes(H.host(bufs[0].out_rows)[:q], want[0], "out_rows beside a plan that gave up")
+    with pytest.raises(B.MwError):
+        ctxs[1].mw_ctx_set_ride_wait_limit(-1)
+    for c in ctxs:                                        # the plan state of ctxs[1] may be left dirty: not used again
+        c.close()
