@@ -351,6 +351,43 @@ def test_plan_of_the_next_batch_rides_with_the_expander(which):
         c.close()
 
 
+@pytest.mark.parametrize("which", ["c1", "c3"])
+def test_riding_plan_at_full_batch_size(which):
+    """The plan of a full-size batch (C1: 4096 tokens over 64 ranks; C3: 8192 tokens over 256
+    ranks, short keys) riding with the expander of a small batch: several slices per token, many
+    finishing workgroups; twice in a row on alternating contexts."""
+    base = W.C1 if which == "c1" else W.C3
+    w = W.scaled(base, hidden=1024 if which == "c1" else 256)
+    small = W.scaled(w, n_tokens=64)
+    my_rank = 3
+    _say("riding plan, full batch", w.name, "T", w.n_tokens)
+    ctxs = [H.make_ctx(w, my_rank, max_recv_rows=4096), H.make_ctx(w, my_rank, max_recv_rows=4096)]
+    recs = []
+    for p in range(2):
+        tk = W.topk_ids(small, 1, p)
+        x, sc = W.payload_rows(small, 1, p)
+        tk[::2, 0] = my_rank * small.experts_per_rank             # make sure something arrives
+        recs.append(H.shrink(H.GpuSend(ctxs[0], tk, x, sc).deliver(my_rank)))
+    cap = max(1, sum(r["n_rows"] for r in recs) * min(w.top_k, w.experts_per_rank))
+    table = B.peers_table(recs, H.DEV)
+    bufs = [B.RecvBuffers(ctxs[0], cap), B.RecvBuffers(ctxs[1], cap)]
+    ctxs[0].mw_unpack_index(table, 2, cap, bufs[0].expert_offsets, bufs[0].stats)
+    sends = [W.topk_ids(w, 21, my_rank), W.topk_ids(w, 22, my_rank)]
+    sends[1][::9] = -1
+    sbufs = [B.SendBuffers(ctxs[0], w.n_tokens) for _ in sends]
+    for i, tk in enumerate(sends):
+        cur, nxt = ctxs[i % 2], ctxs[(i + 1) % 2]
+        cur.mw_unpack_expand_index_plan_next(2, bufs[i % 2].out_rows, bufs[i % 2].out_scales, cap,
+                                             bufs[i % 2].out_src_peer, bufs[i % 2].out_src_token, nxt, table, 2, cap,
+                                             bufs[(i + 1) % 2].expert_offsets, bufs[(i + 1) % 2].stats, H.dev(tk),
+                                             sbufs[i].mask, sbufs[i].perm, sbufs[i].desc, sbufs[i].stats)
+    torch.cuda.synchronize()
+    for i, tk in enumerate(sends):
+        _check_plan_outputs(w, ctxs[0], sbufs[i], tk, "full-size riding plan %d" % i)
+    for c in ctxs:
+        c.close()
+
+
 def test_unpack_after_a_smaller_batch_strides_over_the_rows():
     """The expander's launch is sized from the row count seen at the last mw_get_recv_stats; a later,
     larger batch on the same context must still be expanded completely (and a smaller one too)."""
