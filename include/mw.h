@@ -332,7 +332,11 @@ MW_API int32_t mw_unpack_expand_index_next(mw_ctx *ctx, int32_t n_peers, void *o
  *     mw_pack(batch n);  mw_unpack_expand_index_plan_next(expand n; index n+1; plan n+1);
  *     mw_pack(batch n+1);  ...
  * The plan uses the plan part of next_ctx's workspace (see the conventions above); its outputs
- * are complete when this launch is, i.e. for every later call on the same stream.
+ * are complete when this launch is, i.e. for every later call on the same stream.  The riding
+ * plan ranks tokens all-pairs (as mw_plan does up to about 8000 tokens): it stays in the
+ * expander's shadow while that takes less time than the expander -- 4096 tokens beside 30000
+ * received rows of 14 KiB do, 8192 tokens over 256 ranks beside 20000 such rows do not (use
+ * mw_plan on a second stream there).
  * Inside the launch the plan's second half waits for its first half (workgroups that come
  * earlier in the same launch and wait for nothing themselves); the wait is bounded (about a
  * second by default, mw_ctx_set_ride_wait_limit).  Past the bound -- not observed, and not
