@@ -604,7 +604,28 @@ def bench_dispatch(args, name: str) -> dict:
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=side):
             step_d()
-        for label, fn in (("step_us", step_d), ("step_graph_replay_us", graph.replay)):
+        # and as two launches: the packer, then the expander with the next batch's index and plan
+        ctx_d2 = B.Context(R, w.n_experts, K, my_rank, w.hidden, fmt, Td, R * Td, e2r, device=dev)
+        rv_d2 = B.RecvBuffers(ctx_d2, cap_d)
+        ride_ctx, ride_rv, ride_n = (ctx_d, ctx_d2), (rv_d, rv_d2), {"n": 0}
+        ctx_d2.mw_unpack_index(table_d, R, cap_d, rv_d2.expert_offsets, rv_d2.stats)
+        ctx_d2.mw_get_recv_stats(rv_d2.stats)
+        ctx_d.mw_unpack_index(table_d, R, cap_d, rv_d.expert_offsets, rv_d.stats)
+        ctx_d.mw_plan(tk_s, sd0.mask, sd0.perm, sd0.desc, sd0.stats)
+
+        def step_ride():
+            n = ride_n["n"]
+            ride_n["n"] = n + 1
+            a, b = n % 2, (n + 1) % 2
+            ctx.mw_pack(x_s, sc_s, tk_s, sd0.perm, sd0.stats, sd0.packed, sd0.row_src_token, sd0.row_topk)
+            ride_ctx[a].mw_unpack_expand_index_plan_next(R, ride_rv[a].out_rows, ride_rv[a].out_scales, cap_d,
+                                                         ride_rv[a].out_src_peer, ride_rv[a].out_src_token,
+                                                         ride_ctx[b], table_d, R, cap_d, ride_rv[b].expert_offsets,
+                                                         ride_rv[b].stats, tk_s, sd0.mask, sd0.perm, sd0.desc,
+                                                         sd0.stats)
+
+        for label, fn in (("step_us", step_d), ("step_graph_replay_us", graph.replay),
+                          ("step_two_launches_us", step_ride)):
             for _ in range(10):
                 fn()
             (a, b), = new_events(torch, 1)
@@ -615,6 +636,7 @@ def bench_dispatch(args, name: str) -> dict:
             torch.cuda.synchronize()
             us[label] = round(10.0 * a.elapsed_time(b), 2)
         del graph
+        ctx_d2.close()
         decode["%d_tokens" % Td] = us
         ctx_d.close()
 
