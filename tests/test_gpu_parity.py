@@ -275,7 +275,7 @@ def _check_plan_outputs(w, ctx, sb, tk, what):
         assert int(st[f]) == int(ost[f]), what + " " + f
 
 
-@pytest.mark.parametrize("which", ["c1", "c2", "c3", "k12", "one_rank"])
+@pytest.mark.parametrize("which", ["c1", "c2", "c3", "k12", "one_rank", "wg512", "wg1024"])
 def test_plan_of_the_next_batch_rides_with_the_expander(which):
     """A stream of batches through mw_unpack_expand_index_plan_next on two contexts: the receive side
     of every batch against the plain definition, and the riding plan of every next batch -- bitmaps,
@@ -286,7 +286,10 @@ def test_plan_of_the_next_batch_rides_with_the_expander(which):
                   "c2": (W.scaled(W.C2, n_tokens=300, hidden=1024), 40),
                   "c3": (W.scaled(W.C3, n_tokens=257, hidden=256), 200),
                   "k12": (W.DispatchWorkload("k12", 22, 130, 260, 12, 200, 256, "bf16", "uniform"), 77),
-                  "one_rank": (W.DispatchWorkload("r1", 23, 1, 4, 2, 130, 256, "bf16", "uniform"), 0)}[which]
+                  "one_rank": (W.DispatchWorkload("r1", 23, 1, 4, 2, 130, 256, "bf16", "uniform"), 0),
+                  # rows of 462 and 1001 chunks: the launch's workgroups have 512 and 1024 lanes
+                  "wg512": (W.DispatchWorkload("wg512", 24, 8, 16, 2, 140, 7168, "fp8", "uniform"), 5),
+                  "wg1024": (W.DispatchWorkload("wg1024", 25, 8, 16, 3, 140, 8008, "bf16", "uniform"), 2)}[which]
     _say("riding plan", w.name)
     e2r = W.expert_to_rank(w)
     ctxs = [H.make_ctx(w, my_rank, max_tokens=1200), H.make_ctx(w, my_rank, max_tokens=1200)]
