@@ -184,7 +184,7 @@ struct mw_plan_args {
     uint64_t *mask_out; unsigned long long *cnt; uint32_t *pstate;
     int32_t *perm; mw_group_desc *desc; mw_send_stats *stats; uint64_t row_bytes;
     int tb, ns, slice;
-    uint32_t n_rank, n_finish, wait_limit;
+    uint32_t n_rank, n_finish, finish_rows, wait_limit;   // finish_rows: packed rows per finishing workgroup
 };
 
 __device__ __forceinline__ unsigned long long mw_ld_agent64(const unsigned long long *p)
@@ -196,11 +196,15 @@ __device__ __forceinline__ uint32_t mw_ld_agent32(const uint32_t *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// LDS a finishing workgroup of `bs` lanes needs, in bytes (counters, tokens, 19 scratch words)
-static inline size_t mw_plan_finish_lds(int bs) { return 12u * (size_t)bs + 19u * sizeof(uint32_t); }
+// Packed rows one finishing workgroup of `bs` lanes takes (a multiple of bs), and the LDS it
+// needs for them in bytes (counters, tokens, 19 scratch words).  Every finishing workgroup reads
+// all tokens' counters at device scope, which is not free beside a bandwidth-bound kernel: rows
+// of 512 instead of 128 per workgroup took 3 us off the launch at 4096 tokens.
+static inline uint32_t mw_plan_finish_rows(int bs) { return bs >= 512 ? (uint32_t)bs : 512u / (uint32_t)bs * (uint32_t)bs; }
+static inline size_t mw_plan_finish_lds(int bs) { return 12u * (size_t)mw_plan_finish_rows(bs) + 19u * sizeof(uint32_t); }
 
 // Second half of a riding plan: finishing workgroup `fb` (of n_finish, `bs` lanes each) owns
-// the packed rows [fb bs, fb bs + bs) -- what k_groups does in a launch of its own.  Here the
+// the packed rows [fb finish_rows, (fb + 1) finish_rows) -- what k_groups does in a launch of its own.  Here the
 // rank workgroups are part of the SAME launch, so:
 //  * it waits until all of them have reported (pstate[kPsDone] == n_rank).  They come before
 //    it in the launch's workgroup order, are dispatched before it, and wait for nothing, so
@@ -213,9 +217,10 @@ static inline size_t mw_plan_finish_lds(int bs) { return 12u * (size_t)bs + 19u 
 __device__ __forceinline__ void mw_plan_finish_ride(const mw_plan_args &a, uint32_t fb, uint64_t *lds)
 {
     const uint32_t tid = threadIdx.x, bs = blockDim.x;
-    unsigned long long *tokc = (unsigned long long *)lds;          // [bs] the row's counters
-    int32_t *tok = (int32_t *)(lds + bs);                          // [bs] token of packed row i0 + k
-    uint32_t *scratch = (uint32_t *)(lds + bs) + bs;               // [17] scans, [18] "the ranks are complete"
+    const uint32_t rpw = a.finish_rows;
+    unsigned long long *tokc = (unsigned long long *)lds;          // [rpw] the row's counters
+    int32_t *tok = (int32_t *)(lds + rpw);                         // [rpw] token of packed row i0 + k
+    uint32_t *scratch = (uint32_t *)(lds + rpw) + rpw;             // [17] scans, [18] "the ranks are complete"
     const uint32_t T = (uint32_t)a.T;
 
     if (tid == 0) {
@@ -237,8 +242,8 @@ __device__ __forceinline__ void mw_plan_finish_ride(const mw_plan_args &a, uint3
     }
 
     const uint32_t N = min(mw_ld_agent32(&a.pstate[kPsKept]), T), n_empty = T - N;
-    const uint32_t i0 = fb * bs;
-    tok[tid] = 0; tokc[tid] = 0;           // (a row no token claims -- corrupted counters only -- reads token 0)
+    const uint32_t i0 = fb * rpw;
+    for (uint32_t k = tid; k < rpw; k += bs) { tok[k] = 0; tokc[k] = 0; }   // (a row no token claims -- corrupted counters only -- reads token 0)
     mw_lds_barrier();
     // all tokens' counters: which land in this workgroup's rows, how many groups start before
     // its first row, how many groups there are (sixteen counters per lane in flight)
@@ -258,36 +263,39 @@ __device__ __forceinline__ void mw_plan_finish_ride(const mw_plan_args &a, uint3
             const uint32_t st = ((c >> 21) & kField) == 0 ? 1u : 0u;
             starts_total += st;
             starts_before += (st && p < i0) ? 1u : 0u;
-            if (p - i0 < bs && p < N) { tok[p - i0] = (int32_t)(t0 + u * bs + tid); tokc[p - i0] = c; }
+            if (p - i0 < rpw && p < N) { tok[p - i0] = (int32_t)(t0 + u * bs + tid); tokc[p - i0] = c; }
         }
     }
-    uint32_t g_base, G;
-    mw_block_exscan(starts_before, scratch, &g_base);
+    uint32_t g_next, G;
+    mw_block_exscan(starts_before, scratch, &g_next);
     mw_block_exscan(starts_total, scratch, &G);                // ends with a barrier: tok[] is complete
 
-    const uint32_t i = i0 + tid;
-    uint32_t st = 0;
-    int32_t t = 0;
-    unsigned long long c = 0;
-    if (i < N) {
-        t = tok[tid];
-        a.perm[i] = t;
-        c = tokc[tid];
-        st = ((c >> 21) & kField) == 0 ? 1u : 0u;
-    }
-    uint32_t local_total;
-    const uint32_t g = g_base + mw_block_exscan(st, scratch, &local_total);
-    if (st) {
-        const unsigned long long *m = (const unsigned long long *)(a.mask_out + (size_t)t * MW_MASK_WORDS);
-        mw_group_desc d;
-        uint32_t nd = 0;
+    for (uint32_t k0 = 0; k0 < rpw && i0 + k0 < N; k0 += bs) {  // (uniform bounds: every lane takes every turn)
+        const uint32_t i = i0 + k0 + tid;
+        uint32_t st = 0;
+        int32_t t = 0;
+        unsigned long long c = 0;
+        if (i < N) {
+            t = tok[k0 + tid];
+            a.perm[i] = t;
+            c = tokc[k0 + tid];
+            st = ((c >> 21) & kField) == 0 ? 1u : 0u;
+        }
+        uint32_t turn_total;
+        const uint32_t g = g_next + mw_block_exscan(st, scratch, &turn_total);
+        g_next += turn_total;
+        if (st) {
+            const unsigned long long *m = (const unsigned long long *)(a.mask_out + (size_t)t * MW_MASK_WORDS);
+            mw_group_desc d;
+            uint32_t nd = 0;
 #pragma unroll
-        for (int w = 0; w < MW_MASK_WORDS; ++w) { d.mask[w] = mw_ld_agent64(m + w); nd += (uint32_t)__popcll(d.mask[w]); }
-        d.row_offset = i;
-        d.row_count = (uint32_t)((c >> 42) & kField);
-        d.n_dest = nd;
-        d.reserved0 = 0;
-        a.desc[g] = d;
+            for (int w = 0; w < MW_MASK_WORDS; ++w) { d.mask[w] = mw_ld_agent64(m + w); nd += (uint32_t)__popcll(d.mask[w]); }
+            d.row_offset = i;
+            d.row_count = (uint32_t)((c >> 42) & kField);
+            d.n_dest = nd;
+            d.reserved0 = 0;
+            a.desc[g] = d;
+        }
     }
     if (fb == 0) {
         uint32_t dests = 0;

@@ -779,7 +779,8 @@ int32_t mw_launch_unpack_expand_index_plan_next(mw_ctx *ctx, int32_t P, void *ou
     pl.tb = next_T > 0 ? (next_T + shape.bs - 1) / shape.bs : 1;
     pl.ns = next_T > 0 ? (next_T + pl.slice - 1) / pl.slice : 1;
     pl.n_rank = (uint32_t)pl.tb * (uint32_t)pl.ns;
-    pl.n_finish = (uint32_t)pl.tb;
+    pl.finish_rows = mw_plan_finish_rows(shape.bs);
+    pl.n_finish = next_T > 0 ? ((uint32_t)next_T + pl.finish_rows - 1) / pl.finish_rows : 1u;
     pl.wait_limit = next->ride_wait_limit;
     const uint32_t n_plan_rows = (pl.n_rank + pl.n_finish + (uint32_t)shape.nseg - 1) / (uint32_t)shape.nseg;
     size_t lds_plan = (size_t)pl.slice * key_bytes;
