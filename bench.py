@@ -1,13 +1,15 @@
 #!/usr/bin/env python3
 """Benchmark of the MultiWrite dispatch hot path on one MI355X.
 
-A step is one pass of the whole path over one batch: mw_plan -> mw_pack -> mw_unpack, all
-through the C ABI, inputs resident in HBM.  The default workload is the DeepSeek-V3-shaped
+A step is one pass of the whole path over one batch: plan -> pack -> unpack (index, expand), all
+through the C ABI, inputs resident in HBM; batches follow each other as in a steady stream, and
+the default schedule lets the latency-bound parts of the next batch (its plan and its receive
+index) ride in the launch of this batch's expander (see step()).  The default workload is the DeepSeek-V3-shaped
 dispatch (64 simulated ranks, 256 experts, top-8 with group-limited routing, 4096 tokens of
 7168 bf16 on this rank; 64 peer receive regions).  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c0|c1|c2|c3|c4]
-                  [--schedule aligned|pipelined|one_stream|free|single] [--no-cpu-baseline]
+                  [--schedule auto|aligned|pipelined|one_stream|free|single] [--no-cpu-baseline]
 
 The other workloads (tiny, fp8, 256-rank Zipf, AllGather) are parity-test configurations;
 they can be timed with the same harness.
@@ -117,6 +119,10 @@ def bench_dispatch(args, name: str) -> dict:
     seed = W.BASE_SEED if args.seed is None else args.seed
     w = {"c0": W.C0, "c1": W.C1, "c2": W.C2, "c3": W.C3}[name]
     my_rank = W.zipf_median_rank(w, seed) if name == "c3" else 0
+    if args.schedule == "auto":
+        # the plan of the next batch rides with the expander where it stays in its shadow
+        # (up to 4096 tokens); beyond that it runs on a second stream
+        args.schedule = "one_stream" if w.n_tokens <= 4096 else "aligned"
     describe = {
         "c0": "C0 tiny dispatch: 8 simulated ranks, 16 experts, top-2 uniform, 128 tokens x 256 bf16, 8 peer "
               "receive regions (launch-latency bound, cache resident: its % of peak is not meaningful)",
@@ -216,7 +222,7 @@ def bench_dispatch(args, name: str) -> dict:
                       rv.expert_offsets, rv.stats)
 
     # Schedules of a step (all move the same bytes through the same kernels):
-    #  "aligned" (default)  the send side and the receive side are independent operations, each
+    #  "aligned"  the send side and the receive side are independent operations, each
     #            issued on its own stream; one cross-stream wait per step holds the packer back
     #            until the previous batch's expander has finished.  The packer (bandwidth-bound,
     #            short) then runs beside the receive index (latency-bound, moves almost nothing),
@@ -233,7 +239,8 @@ def bench_dispatch(args, name: str) -> dict:
     #            region (in steady state the step before builds it), the last step builds one that
     #            is not used.  The index is then hidden behind the expander, but the packer no longer
     #            has the index to hide behind: the step takes as long as in "aligned".
-    #  "one_stream"  two launches per batch on ONE stream and no event: the packer, then
+    #  "one_stream" (what "auto", the default, takes for batches of up to 4096 tokens; larger
+    #            ones get "aligned")  two launches per batch on ONE stream and no event: the packer, then
     #            mw_unpack_expand_index_plan_next -- the expander of this batch with the index AND the
     #            plan of the next batch riding along.  Nothing latency-bound stands alone any more,
     #            and nothing waits across streams.  Every step still does one plan, one pack, one
@@ -835,7 +842,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", choices=["c0", "c1", "c2", "c3", "c4"], default="c1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--schedule", choices=["aligned", "pipelined", "one_stream", "free", "single"], default="aligned",
+    ap.add_argument("--schedule", choices=["auto", "aligned", "pipelined", "one_stream", "free", "single"], default="auto",
                     help="how the send side and the receive side of a step are issued (see step())")
     ap.add_argument("--seed", type=int, default=None)
     args = ap.parse_args()
