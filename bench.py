@@ -121,8 +121,8 @@ def bench_dispatch(args, name: str) -> dict:
     my_rank = W.zipf_median_rank(w, seed) if name == "c3" else 0
     if args.schedule == "auto":
         # the plan of the next batch rides with the expander where it stays in its shadow
-        # (up to 4096 tokens); beyond that it runs on a second stream
-        args.schedule = "one_stream" if w.n_tokens <= 4096 else "aligned"
+        # (up to 4096 tokens); beyond that it runs on a second stream and only the index rides
+        args.schedule = "one_stream" if w.n_tokens <= 4096 else "pipelined"
     describe = {
         "c0": "C0 tiny dispatch: 8 simulated ranks, 16 experts, top-2 uniform, 128 tokens x 256 bf16, 8 peer "
               "receive regions (launch-latency bound, cache resident: its % of peak is not meaningful)",
@@ -240,7 +240,7 @@ def bench_dispatch(args, name: str) -> dict:
     #            is not used.  The index is then hidden behind the expander, but the packer no longer
     #            has the index to hide behind: the step takes as long as in "aligned".
     #  "one_stream" (what "auto", the default, takes for batches of up to 4096 tokens; larger
-    #            ones get "aligned")  two launches per batch on ONE stream and no event: the packer, then
+    #            ones get "pipelined")  two launches per batch on ONE stream and no event: the packer, then
     #            mw_unpack_expand_index_plan_next -- the expander of this batch with the index AND the
     #            plan of the next batch riding along.  Nothing latency-bound stands alone any more,
     #            and nothing waits across streams.  Every step still does one plan, one pack, one
