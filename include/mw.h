@@ -358,6 +358,32 @@ MW_API int32_t mw_unpack_expand_index_plan_next(mw_ctx *ctx, int32_t n_peers, vo
                                          void *stream);
 
 /*
+ * mw_stream_step: a whole step of a steady stream of batches in ONE launch -- what
+ *     mw_pack(ctx, x_dev, scales_dev, topk_ids_dev, perm_dev, stats_dev, n_tokens, packed_rows_dev,
+ *             row_src_token_dev, row_topk_dev)
+ * and
+ *     mw_unpack_expand_index_plan_next(ctx, n_peers, out_*, next_ctx, next_*)
+ * do, with exactly their outputs: this rank's next batch to send is packed (Section 5.1, send
+ * module) while an earlier received batch is expanded, the batch received after that is indexed
+ * (receive module) and the batch to send after this one is planned.  The two bandwidth-bound
+ * parts then run as one stream of small workgroups with no launch boundary between them, and
+ * the latency-bound parts ride along.  perm_dev and stats_dev must come from a plan that an
+ * EARLIER launch completed (mw_plan, or the plan half of the previous mw_stream_step); the
+ * payload rows (x_dev, scales_dev) and the row format are those of `ctx`.  Errors as for the
+ * two calls.
+ */
+MW_API int32_t mw_stream_step(mw_ctx *ctx, const void *x_dev, const float *scales_dev, const int32_t *topk_ids_dev,
+                       const int32_t *perm_dev, const mw_send_stats *stats_dev, int32_t n_tokens,
+                       void *packed_rows_dev, int32_t *row_src_token_dev, int32_t *row_topk_dev, int32_t n_peers,
+                       void *out_rows_dev, float *out_scales_dev, int64_t out_capacity_rows,
+                       int32_t *out_src_peer_dev, int32_t *out_src_token_dev, mw_ctx *next_ctx,
+                       const mw_recv_peer *next_peers_dev, int32_t next_n_peers, int64_t next_out_capacity_rows,
+                       int64_t *next_expert_offsets_dev, mw_recv_stats *next_recv_stats_dev,
+                       const int32_t *next_topk_ids_dev, int32_t next_n_tokens, uint64_t *next_mask_dev,
+                       int32_t *next_perm_dev, mw_group_desc *next_desc_dev, mw_send_stats *next_send_stats_dev,
+                       void *stream);
+
+/*
  * mw_combine_gather: the way back (Section 2.1, combine-style AlltoAll).  The paper notes that
  * the combine phase reduces and cannot use multicast (Section 2.3.2); what a rank can do
  * locally is the mirror image of "one copy per destination set": a token that reached h of

@@ -25,7 +25,7 @@ MW_FLAG_BAD_SRC_TOKEN, MW_FLAG_BAD_DESC, MW_FLAG_RECV_CAPACITY, MW_FLAG_DUP_SRC_
 EXPORTS = ["mw_workspace_bytes", "mw_ctx_create", "mw_ctx_destroy", "mw_plan", "mw_pack", "mw_plan_pack", "mw_pack_quantize",
            "mw_packet_header_bytes", "mw_pack_packets", "mw_unpack_packets",
            "mw_plan_allgather", "mw_pack_allgather", "mw_unpack", "mw_unpack_index", "mw_unpack_expand",
-           "mw_unpack_allgather", "mw_combine_gather", "mw_unpack_expand_index_next", "mw_unpack_expand_index_plan_next", "mw_ctx_set_ride_wait_limit",
+           "mw_unpack_allgather", "mw_combine_gather", "mw_unpack_expand_index_next", "mw_unpack_expand_index_plan_next", "mw_ctx_set_ride_wait_limit", "mw_stream_step",
            "mw_sim_deliver", "mw_copy_bytes", "mw_get_send_stats", "mw_get_recv_stats",
            "mw_set_forwarding", "mw_relay", "mw_relay_packets", "mw_get_relay_stats",
            "mw_allgather_split_point", "mw_plan_allgather_split", "mw_unpack_allgather_split",
@@ -275,6 +275,22 @@ class Context:
             C.c_int64(next_out_capacity_rows), _ptr(next_expert_offsets), _ptr(next_recv_stats),
             _ptr(next_topk_ids), C.c_int32(next_topk_ids.shape[0]), _ptr(next_mask), _ptr(next_perm),
             _ptr(next_desc), _ptr(next_send_stats), _stream()), "mw_unpack_expand_index_plan_next")
+
+    def mw_stream_step(self, x: torch.Tensor, scales: Optional[torch.Tensor], topk_ids: torch.Tensor,
+                       perm: torch.Tensor, stats: torch.Tensor, packed: torch.Tensor, row_src_token: torch.Tensor,
+                       row_topk: torch.Tensor, n_peers: int, out_rows: torch.Tensor,
+                       out_scales: Optional[torch.Tensor], out_capacity_rows: int, out_src_peer: torch.Tensor,
+                       out_src_token: torch.Tensor, next_ctx: "Context", next_peers: torch.Tensor,
+                       next_n_peers: int, next_out_capacity_rows: int, next_expert_offsets: torch.Tensor,
+                       next_recv_stats: torch.Tensor, next_topk_ids: torch.Tensor, next_mask: torch.Tensor,
+                       next_perm: torch.Tensor, next_desc: torch.Tensor, next_send_stats: torch.Tensor):
+        _check(load().mw_stream_step(
+            self._h, _ptr(x), _ptr(scales), _ptr(topk_ids), _ptr(perm), _ptr(stats), C.c_int32(topk_ids.shape[0]),
+            _ptr(packed), _ptr(row_src_token), _ptr(row_topk), C.c_int32(n_peers), _ptr(out_rows), _ptr(out_scales),
+            C.c_int64(out_capacity_rows), _ptr(out_src_peer), _ptr(out_src_token), next_ctx._h, _ptr(next_peers),
+            C.c_int32(next_n_peers), C.c_int64(next_out_capacity_rows), _ptr(next_expert_offsets),
+            _ptr(next_recv_stats), _ptr(next_topk_ids), C.c_int32(next_topk_ids.shape[0]), _ptr(next_mask),
+            _ptr(next_perm), _ptr(next_desc), _ptr(next_send_stats), _stream()), "mw_stream_step")
 
     def mw_ctx_set_ride_wait_limit(self, polls: int):
         _check(load().mw_ctx_set_ride_wait_limit(self._h, C.c_int64(polls)), "mw_ctx_set_ride_wait_limit")

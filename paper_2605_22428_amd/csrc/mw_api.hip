@@ -455,7 +455,49 @@ MW_API int32_t mw_unpack_expand_index_plan_next(mw_ctx *ctx, int32_t n_peers, vo
                                                    out_src_peer_dev, out_src_token_dev, next_ctx, next_peers_dev,
                                                    next_n_peers, next_out_capacity_rows, next_expert_offsets_dev,
                                                    next_recv_stats_dev, next_topk_ids_dev, next_n_tokens, next_mask_dev,
-                                                   next_perm_dev, next_desc_dev, next_send_stats_dev,
+                                                   next_perm_dev, next_desc_dev, next_send_stats_dev, nullptr,
+                                                   (hipStream_t)stream);
+}
+
+MW_API int32_t mw_stream_step(mw_ctx *ctx, const void *x_dev, const float *scales_dev, const int32_t *topk_ids_dev,
+                       const int32_t *perm_dev, const mw_send_stats *stats_dev, int32_t n_tokens,
+                       void *packed_rows_dev, int32_t *row_src_token_dev, int32_t *row_topk_dev, int32_t n_peers,
+                       void *out_rows_dev, float *out_scales_dev, int64_t out_capacity_rows,
+                       int32_t *out_src_peer_dev, int32_t *out_src_token_dev, mw_ctx *next_ctx,
+                       const mw_recv_peer *next_peers_dev, int32_t next_n_peers, int64_t next_out_capacity_rows,
+                       int64_t *next_expert_offsets_dev, mw_recv_stats *next_recv_stats_dev,
+                       const int32_t *next_topk_ids_dev, int32_t next_n_tokens, uint64_t *next_mask_dev,
+                       int32_t *next_perm_dev, mw_group_desc *next_desc_dev, mw_send_stats *next_send_stats_dev,
+                       void *stream)
+{
+    if (!ctx || !next_ctx || ctx == next_ctx || ctx->device != next_ctx->device) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
+    // the packer's arguments, as mw_pack checks them
+    if (!stats_dev || n_tokens < 0) return MW_ERR_INVALID_ARG;
+    if (n_tokens > ctx->cfg.max_tokens) return MW_ERR_CAPACITY;
+    if (n_tokens > 0) {
+        if (!x_dev || !topk_ids_dev || !perm_dev || !packed_rows_dev || !row_src_token_dev || !row_topk_dev)
+            return MW_ERR_INVALID_ARG;
+        if ((ctx->s_row_bytes > 0) != (scales_dev != nullptr)) return MW_ERR_INVALID_ARG;
+        if (((uintptr_t)x_dev | (uintptr_t)packed_rows_dev | (uintptr_t)scales_dev) & 15u) return MW_ERR_INVALID_ARG;
+    }
+    int32_t rc = check_unpack_expand(ctx, n_peers, out_rows_dev, out_scales_dev, out_capacity_rows, out_src_peer_dev,
+                                     out_src_token_dev);
+    if (rc == MW_OK)
+        rc = check_unpack_index(next_ctx, next_peers_dev, next_n_peers, next_out_capacity_rows, next_expert_offsets_dev,
+                                next_recv_stats_dev);
+    if (rc != MW_OK) return rc;
+    if (!next_send_stats_dev || next_n_tokens < 0) return MW_ERR_INVALID_ARG;
+    if (next_n_tokens > next_ctx->cfg.max_tokens) return MW_ERR_CAPACITY;
+    if (next_n_tokens > 0 && (!next_topk_ids_dev || !next_mask_dev || !next_perm_dev || !next_desc_dev))
+        return MW_ERR_INVALID_ARG;
+    const mw_pack_call pk = {x_dev, scales_dev, topk_ids_dev, perm_dev, stats_dev, n_tokens, packed_rows_dev,
+                             row_src_token_dev, row_topk_dev};
+    return mw_launch_unpack_expand_index_plan_next(ctx, n_peers, out_rows_dev, out_scales_dev, out_capacity_rows,
+                                                   out_src_peer_dev, out_src_token_dev, next_ctx, next_peers_dev,
+                                                   next_n_peers, next_out_capacity_rows, next_expert_offsets_dev,
+                                                   next_recv_stats_dev, next_topk_ids_dev, next_n_tokens, next_mask_dev,
+                                                   next_perm_dev, next_desc_dev, next_send_stats_dev, &pk,
                                                    (hipStream_t)stream);
 }
 

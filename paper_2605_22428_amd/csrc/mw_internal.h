@@ -208,13 +208,18 @@ int32_t mw_launch_unpack_expand_index_next(mw_ctx *ctx, int32_t P, void *out_row
                                            int32_t *out_src_peer, int32_t *out_src_token, mw_ctx *next,
                                            const mw_recv_peer *next_peers, int32_t next_P, int64_t next_cap,
                                            int64_t *next_expert_offsets, mw_recv_stats *next_stats, hipStream_t s);
+// the arguments of an mw_pack that rides in another launch (mw_stream_step)
+struct mw_pack_call {
+    const void *x; const float *scales; const int32_t *topk; const int32_t *perm; const mw_send_stats *stats;
+    int32_t n_tokens; void *packed; int32_t *row_src_token; int32_t *row_topk;
+};
 int32_t mw_launch_unpack_expand_index_plan_next(mw_ctx *ctx, int32_t P, void *out_rows, float *out_scales, int64_t cap,
                                                 int32_t *out_src_peer, int32_t *out_src_token, mw_ctx *next,
                                                 const mw_recv_peer *next_peers, int32_t next_P, int64_t next_cap,
                                                 int64_t *next_expert_offsets, mw_recv_stats *next_stats,
                                                 const int32_t *next_topk, int32_t next_T, uint64_t *next_mask,
                                                 int32_t *next_perm, mw_group_desc *next_desc,
-                                                mw_send_stats *next_send_stats, hipStream_t s);
+                                                mw_send_stats *next_send_stats, const mw_pack_call *pack, hipStream_t s);
 int32_t mw_launch_combine(mw_ctx *ctx, int32_t P, const void *y, int64_t cap, void *ret, int64_t ret_cap, hipStream_t s);
 int32_t mw_launch_plan_allgather(mw_ctx *ctx, int64_t shard_bytes, mw_group_desc *desc,
                                  mw_send_stats *stats, hipStream_t s);

@@ -11,13 +11,11 @@
 // follow the plain-copy ceiling more closely than fewer waves with several loads in flight.
 // Nothing is reused, so accesses are non-temporal.
 #include "mw_internal.h"
+#include "mw_pack_dev.h"
 
 namespace {
 
-// blockIdx.x = segment of blockDim.x chunks, blockIdx.y walks packed rows.  Chunks [0, xc) come
-// from x, chunks [xc, xc + sc) from the fp8 scale rows (sc == 0 otherwise).  The row count
-// and the row's token are wave-uniform and fetched together (perm has room for every row
-// the grid can reach, so the read is in bounds even past the last kept row).
+// blockIdx.x = segment of blockDim.x chunks, blockIdx.y walks packed rows.
 __global__ __launch_bounds__(1024) void k_pack(const u32x4 *__restrict__ x, const u32x4 *__restrict__ scales,
                                                     int xc, int sc, const int32_t *__restrict__ topk, int K,
                                                     const int32_t *__restrict__ perm,
@@ -25,28 +23,8 @@ __global__ __launch_bounds__(1024) void k_pack(const u32x4 *__restrict__ x, cons
                                                     u32x4 *__restrict__ packed, int32_t *__restrict__ row_src_token,
                                                     int32_t *__restrict__ row_topk)
 {
-    uint32_t gdim = gridDim.y, bdim = blockDim.x;
-    MW_PIN_S(gdim); MW_PIN_S(bdim); MW_PIN_S(xc); MW_PIN_S(sc); MW_PIN_S(K);
-    MW_PIN_PTR(x); MW_PIN_PTR(scales); MW_PIN_PTR(topk); MW_PIN_PTR(packed); MW_PIN_PTR(row_src_token);
-    MW_PIN_PTR(row_topk);
-    uint32_t i = blockIdx.y;
-    int32_t t = perm[i];
-    uint32_t n_rows = stats->n_rows;
-    MW_PIN_S(t); MW_PIN_S(n_rows);
-    const int n = xc + sc;
-    const int c = blockIdx.x * bdim + threadIdx.x;
-    while (i < n_rows) {
-        if (c < n) {
-            const u32x4 v = (c < xc) ? mw_ld16(x + (size_t)t * xc + c) : mw_ld16(scales + (size_t)t * sc + (c - xc));
-            mw_st16(packed + (size_t)i * n + c, v);
-        }
-        if (blockIdx.x == 0) {
-            if (threadIdx.x == 0) row_src_token[i] = t;
-            for (int j = threadIdx.x; j < K; j += bdim) row_topk[(size_t)i * K + j] = topk[(size_t)t * K + j];
-        }
-        i += gdim;
-        if (i < n_rows) t = perm[i];
-    }
+    mw_pack_body(x, scales, xc, sc, topk, K, perm, stats, packed, row_src_token, row_topk, blockIdx.x, blockIdx.y,
+                 gridDim.y);
 }
 
 // The packer for packets (Section 6.4: the bitmap embedded in front of the payload): packet i =

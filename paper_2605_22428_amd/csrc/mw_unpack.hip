@@ -31,6 +31,7 @@
 // k_combine is the expander's mirror image for the way back.
 #include "mw_internal.h"
 #include "mw_plan_dev.h"
+#include "mw_pack_dev.h"
 
 namespace {
 
@@ -546,20 +547,27 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
     const uint32_t *__restrict__ row_base, int P, int Kd, int xc, int sc,
     u32x4 *__restrict__ out_rows, u32x4 *__restrict__ out_scales, uint32_t cap,
     int32_t *__restrict__ out_src_peer, int32_t *__restrict__ out_src_token, const mw_index_args next,
-    const mw_plan_args plan, const uint32_t n_plan_rows)
+    const mw_plan_args plan, const uint32_t n_plan_rows, const mw_pack_args pack, const uint32_t n_pack_rows)
 {
     const uint32_t n_index = (uint32_t)next.P;
     if (blockIdx.y < n_index) {
         if (blockIdx.x == 0) recv_index_of<false>(next, (int)blockIdx.y);
         return;
     }
-    if (blockIdx.y < n_index + n_plan_rows) {
+    uint32_t y = blockIdx.y - n_index;
+    if (y < n_plan_rows) {
         extern __shared__ uint64_t plan_lds[];
-        mw_plan_ride<W, kKeyed>(plan, (blockIdx.y - n_index) * gridDim.x + blockIdx.x, plan_lds);
+        mw_plan_ride<W, kKeyed>(plan, y * gridDim.x + blockIdx.x, plan_lds);
+        return;
+    }
+    y -= n_plan_rows;
+    if (y < n_pack_rows) {              // (mw_stream_step: the packer of a batch planned by an earlier launch)
+        mw_pack_body(pack.x, pack.scales, pack.xc, pack.sc, pack.topk, pack.K, pack.perm, pack.stats, pack.packed,
+                     pack.row_src_token, pack.row_topk, blockIdx.x, y, n_pack_rows);
         return;
     }
     expand_body(recs, hits, base, row_base, P, Kd, xc, sc, out_rows, out_scales, cap, out_src_peer, out_src_token,
-                blockIdx.y - n_index - n_plan_rows, gridDim.y - n_index - n_plan_rows);
+                y - n_pack_rows, gridDim.y - n_index - n_plan_rows - n_pack_rows);
 }
 
 // The way back (Section 2.1, combine-style AlltoAll; Section 2.3.2: the combine phase reduces
@@ -745,7 +753,7 @@ int32_t mw_launch_unpack_expand_index_plan_next(mw_ctx *ctx, int32_t P, void *ou
                                                 int64_t *next_expert_offsets, mw_recv_stats *next_stats,
                                                 const int32_t *next_topk, int32_t next_T, uint64_t *next_mask,
                                                 int32_t *next_perm, mw_group_desc *next_desc,
-                                                mw_send_stats *next_send_stats, hipStream_t s)
+                                                mw_send_stats *next_send_stats, const mw_pack_call *pk, hipStream_t s)
 {
     const mw_config &c = ctx->cfg;
     if (c.max_recv_rows < 1) return MW_ERR_UNSUPPORTED;       // nothing to ride on
@@ -788,12 +796,24 @@ int32_t mw_launch_unpack_expand_index_plan_next(mw_ctx *ctx, int32_t P, void *ou
     const size_t lds = lds_index > lds_plan ? lds_index : lds_plan;
     {
         mw_timed tm(ctx, MW_KERNEL_EXPAND, s);
-        const dim3 grid(shape.nseg, gy + (uint32_t)next_P + n_plan_rows), block(shape.bs);
+        // the packer of this context's own rows, if asked for: same row shape as the expander
+        mw_pack_args pa = {};
+        uint32_t n_pack_rows = 0;
+        if (pk && pk->n_tokens > 0) {
+            pa.x = (const u32x4 *)pk->x; pa.scales = (const u32x4 *)pk->scales; pa.xc = xc; pa.sc = sc;
+            pa.topk = pk->topk; pa.K = c.top_k; pa.perm = pk->perm; pa.stats = pk->stats;
+            pa.packed = (u32x4 *)pk->packed; pa.row_src_token = pk->row_src_token; pa.row_topk = pk->row_topk;
+            n_pack_rows = (uint32_t)pk->n_tokens < 16384u ? (uint32_t)pk->n_tokens : 16384u;   // more by striding
+        }
+        // a grid has at most 65535 rows: the expander takes what the riders leave (more by striding)
+        const uint32_t riders = (uint32_t)next_P + n_plan_rows + n_pack_rows;      // <= 256 + 8192 + 16384
+        const uint32_t gy_fit = gy < 65535u - riders ? gy : 65535u - riders;
+        const dim3 grid(shape.nseg, gy_fit + riders), block(shape.bs);
         const uint32_t cap32 = (uint32_t)(cap < 0x7fffffffLL ? cap : 0x7fffffffLL);
 #define MW_RIDE(W_, KEYED_)                                                                                        \
     hipLaunchKernelGGL((k_expand_index_plan_next<W_, KEYED_>), grid, block, lds, s, ctx->d_recs, ctx->d_hits,      \
                        ctx->d_base, ctx->d_row_base, P, ctx->hit_slots, xc, sc, (u32x4 *)out_rows,                 \
-                       (u32x4 *)out_scales, cap32, out_src_peer, out_src_token, a, pl, n_plan_rows)
+                       (u32x4 *)out_scales, cap32, out_src_peer, out_src_token, a, pl, n_plan_rows, pa, n_pack_rows)
         if (keyed) MW_RIDE(4, true);
         else if (W == 1) MW_RIDE(1, false);
         else if (W == 2) MW_RIDE(2, false);

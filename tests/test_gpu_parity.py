@@ -391,6 +391,78 @@ def test_riding_plan_at_full_batch_size(which):
         c.close()
 
 
+@pytest.mark.parametrize("which", ["c1", "c2", "c3", "wg1024"])
+def test_stream_step_packs_expands_indexes_and_plans_in_one_launch(which):
+    """mw_stream_step over a stream of batches on two contexts: in step i the batch planned by
+    step i - 1 is packed, received batch i is expanded, received batch i + 1 indexed, and the
+    batch after that planned.  Every output of every step against the oracle / the plain definition."""
+    w, my_rank = {"c1": (W.scaled(W.C1, n_tokens=333, hidden=512), 3),
+                  "c2": (W.scaled(W.C2, n_tokens=300, hidden=1024), 40),
+                  "c3": (W.scaled(W.C3, n_tokens=257, hidden=256), 200),
+                  "wg1024": (W.DispatchWorkload("wg1024", 25, 8, 16, 3, 140, 8008, "bf16", "uniform"), 2)}[which]
+    _say("stream step", w.name)
+    e2r = W.expert_to_rank(w)
+    T, R = w.n_tokens, w.n_ranks
+    ctxs = [H.make_ctx(w, my_rank), H.make_ctx(w, my_rank)]
+    n_steps = 4
+    batches = []                                           # what this rank receives in step i
+    for seed in range(1, n_steps + 2):
+        recs, toks = [], []
+        for p in range(R):
+            tk = W.topk_ids(w, seed, p)
+            x, sc = W.payload_rows(w, seed, p)
+            recs.append(H.shrink(H.GpuSend(ctxs[0], tk, x, sc).deliver(my_rank)))
+            toks.append((tk, x, sc))
+        cap = max(1, sum(r["n_rows"] for r in recs) * min(w.top_k, w.experts_per_rank))
+        batches.append(dict(recs=recs, toks=toks, cap=cap, table=B.peers_table(recs, H.DEV)))
+    sends = []                                             # what this rank sends: batch j is planned in step j - 1
+    for j in range(n_steps + 1):
+        tk = W.topk_ids(w, 30 + j, my_rank)
+        if j == 2:
+            tk[::3] = -1                                   # fewer rows than tokens
+        x, sc = W.payload_rows(w, 30 + j, my_rank)
+        sends.append(dict(tk=tk, x=x, sc=sc, tk_d=H.dev(tk), x_d=H.dev(x), s_d=H.dev(sc), buf=B.SendBuffers(ctxs[0], T)))
+    bufs = [B.RecvBuffers(ctxs[i % 2], b["cap"]) for i, b in enumerate(batches)]
+    # before the first step: the plan of send batch 0 and the index of received batch 0
+    s0 = sends[0]
+    ctxs[0].mw_plan(s0["tk_d"], s0["buf"].mask, s0["buf"].perm, s0["buf"].desc, s0["buf"].stats)
+    ctxs[0].mw_unpack_index(batches[0]["table"], R, batches[0]["cap"], bufs[0].expert_offsets, bufs[0].stats)
+    for i in range(n_steps):
+        cur, nxt = ctxs[i % 2], ctxs[(i + 1) % 2]
+        sd, sn = sends[i], sends[i + 1]
+        b, nb = batches[i], batches[i + 1]
+        cur.mw_stream_step(sd["x_d"], sd["s_d"], sd["tk_d"], sd["buf"].perm, sd["buf"].stats, sd["buf"].packed,
+                           sd["buf"].row_src_token, sd["buf"].row_topk, R, bufs[i].out_rows, bufs[i].out_scales,
+                           b["cap"], bufs[i].out_src_peer, bufs[i].out_src_token, nxt, nb["table"], R, nb["cap"],
+                           bufs[i + 1].expert_offsets, bufs[i + 1].stats, sn["tk_d"], sn["buf"].mask, sn["buf"].perm,
+                           sn["buf"].desc, sn["buf"].stats)
+    torch.cuda.synchronize()
+    for i in range(n_steps):
+        b = batches[i]
+        want = ref.dispatch_plain(b["toks"], e2r, my_rank, b["cap"])
+        st = ctxs[i % 2].mw_get_recv_stats(bufs[i].stats)
+        q = int(st["n_out_rows"])
+        assert int(st["error_flags"]) == 0 and q == len(want[2])
+        H.assert_same_bytes(H.host(bufs[i].expert_offsets), want[4], "step %d expert_offsets" % i)
+        H.assert_same_bytes(H.host(bufs[i].out_src_peer)[:q], want[2], "step %d out_src_peer" % i)
+        H.assert_same_bytes(H.host(bufs[i].out_src_token)[:q], want[3], "step %d out_src_token" % i)
+        H.assert_same_bytes(H.host(bufs[i].out_rows)[:q], want[0], "step %d out_rows" % i)
+        if want[1] is not None:
+            H.assert_same_bytes(H.host(bufs[i].out_scales)[:q], want[1], "step %d out_scales" % i)
+    for j in range(n_steps + 1):
+        sd = sends[j]
+        _check_plan_outputs(w, ctxs[0], sd["buf"], sd["tk"], "send batch %d" % j)
+        if j < n_steps:                                    # packed in step j
+            _, perm, _, _ = ref.plan(sd["tk"], e2r, R, w.row_bytes)
+            packed, src, rtk = ref.pack(sd["x"], sd["sc"], sd["tk"], perm)
+            n = len(perm)
+            H.assert_same_bytes(H.host(sd["buf"].packed)[:n], packed, "send batch %d packed rows" % j)
+            H.assert_same_bytes(H.host(sd["buf"].row_src_token)[:n], src, "send batch %d row_src_token" % j)
+            H.assert_same_bytes(H.host(sd["buf"].row_topk)[:n], rtk, "send batch %d row_topk" % j)
+    for c in ctxs:
+        c.close()
+
+
 def test_unpack_after_a_smaller_batch_strides_over_the_rows():
     """The expander's launch is sized from the row count seen at the last mw_get_recv_stats; a later,
     larger batch on the same context must still be expanded completely (and a smaller one too)."""
