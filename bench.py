@@ -3,13 +3,14 @@
 
 A step is one pass of the whole path over one batch: plan -> pack -> unpack (index, expand), all
 through the C ABI, inputs resident in HBM; batches follow each other as in a steady stream, and
-the default schedule lets the latency-bound parts of the next batch (its plan and its receive
-index) ride in the launch of this batch's expander (see step()).  The default workload is the DeepSeek-V3-shaped
+the default schedule issues a whole step as one launch (mw_stream_step: packer and expander as one
+stream of workgroups, the latency-bound plan and receive index of the next batch riding along;
+see step()).  The default workload is the DeepSeek-V3-shaped
 dispatch (64 simulated ranks, 256 experts, top-8 with group-limited routing, 4096 tokens of
 7168 bf16 on this rank; 64 peer receive regions).  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c0|c1|c2|c3|c4]
-                  [--schedule auto|aligned|pipelined|one_stream|free|single] [--no-cpu-baseline]
+                  [--schedule auto|aligned|pipelined|one_stream|one_launch|free|single] [--no-cpu-baseline]
 
 The other workloads (tiny, fp8, 256-rank Zipf, AllGather) are parity-test configurations;
 they can be timed with the same harness.
@@ -122,7 +123,7 @@ def bench_dispatch(args, name: str) -> dict:
     if args.schedule == "auto":
         # the plan of the next batch rides with the expander where it stays in its shadow
         # (up to 4096 tokens); beyond that it runs on a second stream and only the index rides
-        args.schedule = "one_stream" if w.n_tokens <= 4096 else "pipelined"
+        args.schedule = "one_launch" if w.n_tokens <= 4096 else "pipelined"
     describe = {
         "c0": "C0 tiny dispatch: 8 simulated ranks, 16 experts, top-2 uniform, 128 tokens x 256 bf16, 8 peer "
               "receive regions (launch-latency bound, cache resident: its % of peak is not meaningful)",
@@ -239,13 +240,16 @@ def bench_dispatch(args, name: str) -> dict:
     #            region (in steady state the step before builds it), the last step builds one that
     #            is not used.  The index is then hidden behind the expander, but the packer no longer
     #            has the index to hide behind: the step takes as long as in "aligned".
-    #  "one_stream" (what "auto", the default, takes for batches of up to 4096 tokens; larger
-    #            ones get "pipelined")  two launches per batch on ONE stream and no event: the packer, then
+    #  "one_stream"  two launches per batch on ONE stream and no event: the packer, then
     #            mw_unpack_expand_index_plan_next -- the expander of this batch with the index AND the
     #            plan of the next batch riding along.  Nothing latency-bound stands alone any more,
     #            and nothing waits across streams.  Every step still does one plan, one pack, one
     #            index and one expand; the first batch's plan and index are made before the timed
     #            region, the last step makes ones that are not used.
+    #  "one_launch" (what "auto", the default, takes for batches of up to 4096 tokens; larger
+    #            ones get "pipelined")  mw_stream_step: the packer joins that launch too -- one
+    #            launch per batch, the two bandwidth-bound parts with no launch boundary between
+    #            them.  The launch's algorithmic bytes are then the packer's plus the expander's.
     ev_unpack_done = [DeviceEvent(torch) for _ in range(2)]
     state = {"n": 0}
     rctx = [ctx, ctx_b]
@@ -298,6 +302,17 @@ def bench_dispatch(args, name: str) -> dict:
                                                              rv.out_src_token, rctx[(n + 1) % 2], s_next["table"], R,
                                                              cap, rn.expert_offsets, rn.stats, topk_d, sdn.mask,
                                                              sdn.perm, sdn.desc, sdn.stats)
+        elif schedule == "one_launch":
+            n = pipe["n"]
+            pipe["n"] = n + 1
+            s, s_next = sets[n % N_SETS], sets[(n + 1) % N_SETS]
+            sd, rv, rn, sdn = s["send"], s["recv"], s_next["recv"], s_next["send"]
+            with torch.cuda.stream(s_recv):
+                rctx[n % 2].mw_stream_step(s["x"], s["sc"], topk_d, sd.perm, sd.stats, sd.packed, sd.row_src_token,
+                                           sd.row_topk, R, rv.out_rows, rv.out_scales, cap, rv.out_src_peer,
+                                           rv.out_src_token, rctx[(n + 1) % 2], s_next["table"], R, cap,
+                                           rn.expert_offsets, rn.stats, topk_d, sdn.mask, sdn.perm, sdn.desc,
+                                           sdn.stats)
         else:
             n = state["n"]
             state["n"] = n + 1
@@ -316,8 +331,8 @@ def bench_dispatch(args, name: str) -> dict:
             c.mw_ctx_set_timing_events(B.MW_KERNEL_EXPAND, a, b)
 
     # ---------------------------------------------------------------- warm-up, then the timed region
-    if args.schedule in ("pipelined", "one_stream"):
-        prime_pipeline(args.schedule == "one_stream")
+    if args.schedule in ("pipelined", "one_stream", "one_launch"):
+        prime_pipeline(args.schedule != "pipelined")
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -349,11 +364,11 @@ def bench_dispatch(args, name: str) -> dict:
     expand_avg_ms = sum(expand_ms) / len(expand_ms)
 
     other, other_issue = {}, {}
-    for sched in ("single", "free", "aligned", "pipelined", "one_stream"):      # the other schedules, for reference
+    for sched in ("single", "free", "aligned", "pipelined", "one_stream", "one_launch"):      # the other schedules, for reference
         if sched == args.schedule:
             continue
-        if sched in ("pipelined", "one_stream"):
-            prime_pipeline(sched == "one_stream")
+        if sched in ("pipelined", "one_stream", "one_launch"):
+            prime_pipeline(sched != "pipelined")
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(args.steps):
@@ -652,7 +667,9 @@ def bench_dispatch(args, name: str) -> dict:
     unpack_bytes = M * rb + Q * rb + M * (4 + 4 * K) + n_desc_total * 48 + Q * 8 + (L + 1) * 8
     expand_bytes = M * rb + Q * rb + Q * 8 + M * 4
     value = (pack_bytes + unpack_bytes) / (ms_per_step * 1e-3) / 1e9
-    achieved = expand_bytes / (expand_avg_ms * 1e-3) / 1e9
+    # the bracketed launch moves the expander's bytes -- and the packer's too in "one_launch"
+    launch_bytes = expand_bytes + (pack_bytes if args.schedule == "one_launch" else 0)
+    achieved = launch_bytes / (expand_avg_ms * 1e-3) / 1e9
     pu_us = kern_us["pack"] + kern_us["recv_index"] + kern_us["expand"]
     saved = 1.0 - int(st["multicast_bytes"]) / int(st["unicast_bytes"])
     # the same figure without this rank's own copy (Section 3.1's AllGather counts the OTHER nodes
@@ -673,7 +690,8 @@ def bench_dispatch(args, name: str) -> dict:
 
     # the launch that moves the receive side's bytes: the expander, in the pipelined schedule with
     # the next batch's index riding along (same bytes; the index's few MB are not counted)
-    dominant = {"pipelined": "k_expand_index_next", "one_stream": "k_expand_index_plan_next"}.get(args.schedule, "k_expand")
+    dominant = {"pipelined": "k_expand_index_next", "one_stream": "k_expand_index_plan_next",
+                "one_launch": "k_expand_index_plan_next"}.get(args.schedule, "k_expand")
     result = {
         "metric": METRIC,
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -682,7 +700,7 @@ def bench_dispatch(args, name: str) -> dict:
         "config": {"workload": describe, "seed": seed, "my_rank": my_rank,
                    "rows_packed": N, "groups": int(st["n_groups"]), "rows_received": M, "rows_out": Q,
                    "buffer_sets": N_SETS, "schedule": args.schedule,
-                   "streams": 1 if args.schedule in ("single", "one_stream") else 2},
+                   "streams": 1 if args.schedule in ("single", "one_stream", "one_launch") else 2},
         "other_schedules_ms_per_step": other,
         "host_issue_ms_per_step": dict(other_issue, **{args.schedule: round(issue_ms_per_step, 4)}),
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
@@ -696,7 +714,8 @@ def bench_dispatch(args, name: str) -> dict:
         "copy_ceiling": ceiling,
         "roofline": {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": traffic_from_profile(dominant, name.upper()), "bytes_per_launch": expand_bytes,
+                     "traffic": traffic_from_profile("mw_stream_step" if args.schedule == "one_launch" else dominant,
+                                                    name.upper()), "bytes_per_launch": launch_bytes,
                      "avg_launch_ms": round(expand_avg_ms, 4), "min_launch_ms": round(expand_ms[0], 4),
                      "launches_timed": len(expand_ms)},
     }
@@ -842,7 +861,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", choices=["c0", "c1", "c2", "c3", "c4"], default="c1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--schedule", choices=["auto", "aligned", "pipelined", "one_stream", "free", "single"], default="auto",
+    ap.add_argument("--schedule", choices=["auto", "aligned", "pipelined", "one_stream", "one_launch", "free", "single"], default="auto",
                     help="how the send side and the receive side of a step are issued (see step())")
     ap.add_argument("--seed", type=int, default=None)
     args = ap.parse_args()
