@@ -21,7 +21,7 @@ def _say(*a):
 
 
 def run_dispatch(w, seed, my_rank, check_all_senders=True, lazy=False, tier2=True, also_full=False,
-                 sample_peers=()):
+                 sample_peers=(), stream_step=False):
     """Every simulated peer runs plan+pack (GPU and oracle separately), the simulated network
     filters to my_rank, then unpack on both sides; compared at every stage."""
     _say("dispatch", w.name, "seed", seed, "my_rank", my_rank, "T", w.n_tokens, "H", w.hidden)
@@ -92,6 +92,42 @@ def run_dispatch(w, seed, my_rank, check_all_senders=True, lazy=False, tier2=Tru
     if also_full:
         gf = H.GpuUnpack(ctx, full_recs, cap)
         H.check_unpack(gf, o1, "complete sender buffers")
+    if stream_step:
+        # the same batch through mw_stream_step, the launch bench.py times by default: this rank's
+        # own tokens are packed, the received regions expanded, and the same regions / the same
+        # tokens indexed and planned again as "the next batch" in a second context
+        tk, x, sc = toks[my_rank]
+        g = H.GpuSend(ctx, tk, x, sc)                          # (plans; its packed rows are overwritten below)
+        ctx2 = H.make_ctx(w, my_rank)
+        rv, rv2 = B.RecvBuffers(ctx, cap), B.RecvBuffers(ctx2, cap)
+        nxt = B.SendBuffers(ctx2, w.n_tokens)
+        table = B.peers_table(recs, H.DEV)
+        ctx.mw_unpack_index(table, len(recs), cap, rv.expert_offsets, rv.stats)
+        g.buf.packed.zero_(); g.buf.row_src_token.fill_(-1); g.buf.row_topk.zero_()
+        ctx.mw_stream_step(g.x_d, g.s_d, g.topk_d, g.buf.perm, g.buf.stats, g.buf.packed, g.buf.row_src_token,
+                           g.buf.row_topk, len(recs), rv.out_rows, rv.out_scales, cap, rv.out_src_peer,
+                           rv.out_src_token, ctx2, table, len(recs), cap, rv2.expert_offsets, rv2.stats, g.topk_d,
+                           nxt.mask, nxt.perm, nxt.desc, nxt.stats)
+        ctx2.mw_unpack_expand(len(recs), rv2.out_rows, rv2.out_scales, cap, rv2.out_src_peer, rv2.out_src_token)
+        torch.cuda.synchronize()
+        H.check_send(w, g, tk, x, sc)                          # plan of before, rows packed by the step
+        for c_, b_, what in ((ctx, rv, "stream step: expanded"), (ctx2, rv2, "stream step: indexed for the next")):
+            gs = H.GpuUnpack.__new__(H.GpuUnpack)
+            gs.ctx, gs.buf = c_, b_
+            gs.stats = c_.mw_get_recv_stats(b_.stats)
+            gs.Q = int(gs.stats["n_out_rows"])
+            H.check_unpack(gs, o1, what)
+        g2 = H.GpuSend.__new__(H.GpuSend)                      # the plan the step made, in GpuSend's clothes
+        g2.ctx, g2.T, g2.buf = ctx2, w.n_tokens, nxt
+        g2.stats = ctx2.mw_get_send_stats(nxt.stats)
+        g2.N, g2.G = int(g2.stats["n_rows"]), int(g2.stats["n_groups"])
+        m_, perm_, desc_, st_ = ref.plan(tk, e2r, w.n_ranks, w.row_bytes)
+        gm, gperm, gdesc = g2.host_plan()
+        H.assert_same_bytes(gm, m_, "stream step: next mask")
+        H.assert_same_bytes(gperm, perm_, "stream step: next perm")
+        H.assert_same_bytes(gdesc.view(np.uint8), desc_.view(np.uint8), "stream step: next desc")
+        assert int(g2.stats["unicast_bytes"]) == int(st_["unicast_bytes"]) and int(g2.stats["error_flags"]) == 0
+        ctx2.close()
     _say("  rows received", m_rows, "output rows", gu.Q)
     ctx.close()
     return gu
@@ -101,18 +137,18 @@ def run_dispatch(w, seed, my_rank, check_all_senders=True, lazy=False, tier2=Tru
 @pytest.mark.parametrize("seed", SEEDS)
 @pytest.mark.parametrize("my_rank", [0, 5])
 def test_c0_tiny(seed, my_rank):
-    run_dispatch(W.C0, seed, my_rank, also_full=True)
+    run_dispatch(W.C0, seed, my_rank, also_full=True, stream_step=True)
 
 
 @pytest.mark.parametrize("seed", SEEDS)
 def test_c1_shape_reduced(seed):
     # 64 ranks, 256 experts, top-8, group-limited routing; 333 tokens (ragged), 1024-wide rows
-    run_dispatch(W.scaled(W.C1, n_tokens=333, hidden=1024), seed, 37, also_full=(seed == 1))
+    run_dispatch(W.scaled(W.C1, n_tokens=333, hidden=1024), seed, 37, also_full=(seed == 1), stream_step=True)
 
 
 @pytest.mark.parametrize("seed", SEEDS[:2])
 def test_c2_shape_reduced_fp8(seed):
-    run_dispatch(W.scaled(W.C2, n_tokens=333, hidden=1024), seed, 0, also_full=(seed == 1))
+    run_dispatch(W.scaled(W.C2, n_tokens=333, hidden=1024), seed, 0, also_full=(seed == 1), stream_step=True)
 
 
 @pytest.mark.parametrize("which", ["median", "hottest"])
@@ -130,11 +166,12 @@ def test_wide_rows_ragged_tail():
 
 # ------------------------------------------------------------------ full sizes
 def test_c1_full_size():
-    run_dispatch(W.C1, W.BASE_SEED, 0, check_all_senders=False, lazy=True, sample_peers=(7, 63))
+    run_dispatch(W.C1, W.BASE_SEED, 0, check_all_senders=False, lazy=True, sample_peers=(7, 63), stream_step=True)
 
 
 def test_c2_full_size_fp8():
-    run_dispatch(W.C2, W.BASE_SEED, 0, check_all_senders=False, lazy=True, tier2=False, sample_peers=(31,))
+    run_dispatch(W.C2, W.BASE_SEED, 0, check_all_senders=False, lazy=True, tier2=False, sample_peers=(31,),
+                 stream_step=True)
 
 
 def test_c3_full_size_send_side():
