@@ -121,9 +121,9 @@ def bench_dispatch(args, name: str) -> dict:
     w = {"c0": W.C0, "c1": W.C1, "c2": W.C2, "c3": W.C3}[name]
     my_rank = W.zipf_median_rank(w, seed) if name == "c3" else 0
     if args.schedule == "auto":
-        # the plan of the next batch rides with the expander where it stays in its shadow
-        # (up to 4096 tokens); beyond that it runs on a second stream and only the index rides
-        args.schedule = "one_launch" if w.n_tokens <= 4096 else "pipelined"
+        # the plan of the next batch rides in the step's one launch where it stays in the row
+        # movers' shadow (up to 4096 tokens); beyond that it runs on a second stream
+        args.schedule = "one_launch" if w.n_tokens <= 4096 else "launch_and_plan"
     describe = {
         "c0": "C0 tiny dispatch: 8 simulated ranks, 16 experts, top-2 uniform, 128 tokens x 256 bf16, 8 peer "
               "receive regions (launch-latency bound, cache resident: its % of peak is not meaningful)",
@@ -150,6 +150,7 @@ def bench_dispatch(args, name: str) -> dict:
     t_setup = time.time()
     ctx = B.Context(R, w.n_experts, K, my_rank, w.hidden, fmt, T, R * T, e2r, device=dev, max_hops=16)
     ctx_b = B.Context(R, w.n_experts, K, my_rank, w.hidden, fmt, T, R * T, e2r, device=dev)   # second receive index
+    ctx_p = B.Context(R, w.n_experts, K, my_rank, w.hidden, fmt, T, 1, e2r, device=dev)       # plans beside mw_stream_step
     topks = W.topk_ids_many(w, seed, range(R))
     x_me, s_me = W.payload_rows(w, seed, my_rank)
     topk_d = up(topks[my_rank])
@@ -246,11 +247,17 @@ def bench_dispatch(args, name: str) -> dict:
     #            and nothing waits across streams.  Every step still does one plan, one pack, one
     #            index and one expand; the first batch's plan and index are made before the timed
     #            region, the last step makes ones that are not used.
+    #  "launch_and_plan"  for batches whose plan would outlast the expander: mw_stream_step with an
+    #            empty next batch to plan (packer, expander and the next index in one launch) and
+    #            mw_plan of the real next batch on the second stream; the launch waits for the plan
+    #            made during the step before.
     #  "one_launch" (what "auto", the default, takes for batches of up to 4096 tokens; larger
-    #            ones get "pipelined")  mw_stream_step: the packer joins that launch too -- one
+    #            ones get "launch_and_plan")  mw_stream_step: the packer joins that launch too -- one
     #            launch per batch, the two bandwidth-bound parts with no launch boundary between
     #            them.  The launch's algorithmic bytes are then the packer's plus the expander's.
     ev_unpack_done = [DeviceEvent(torch) for _ in range(2)]
+    ev_plan_done = [DeviceEvent(torch) for _ in range(2)]
+    no_plan_stats = torch.zeros(B.SEND_STATS_BYTES, dtype=torch.uint8, device=dev)
     state = {"n": 0}
     rctx = [ctx, ctx_b]
     pipe = {"n": 0}
@@ -265,6 +272,7 @@ def bench_dispatch(args, name: str) -> dict:
             if with_plan:
                 sd = s["send"]
                 ctx.mw_plan(topk_d, sd.mask, sd.perm, sd.desc, sd.stats)
+                ev_plan_done[n % 2].record(s_recv)
 
     def step(i: int, schedule: str = args.schedule):
         s = sets[i % N_SETS]
@@ -313,6 +321,21 @@ def bench_dispatch(args, name: str) -> dict:
                                            rv.out_src_token, rctx[(n + 1) % 2], s_next["table"], R, cap,
                                            rn.expert_offsets, rn.stats, topk_d, sdn.mask, sdn.perm, sdn.desc,
                                            sdn.stats)
+        elif schedule == "launch_and_plan":
+            n = pipe["n"]
+            pipe["n"] = n + 1
+            s, s_next = sets[n % N_SETS], sets[(n + 1) % N_SETS]
+            sd, rv, rn, sdn = s["send"], s["recv"], s_next["recv"], s_next["send"]
+            with torch.cuda.stream(s_send):                      # the plan of the next batch, beside the launch
+                ctx_p.mw_plan(topk_d, sdn.mask, sdn.perm, sdn.desc, sdn.stats)     # (its own context: the launch's
+                                                                                   # empty plan uses ctx's or ctx_b's)
+                ev_plan_done[(n + 1) % 2].record(s_send)
+            with torch.cuda.stream(s_recv):
+                ev_plan_done[n % 2].make_wait(s_recv)            # (made during the step before: long complete)
+                rctx[n % 2].mw_stream_step(s["x"], s["sc"], topk_d, sd.perm, sd.stats, sd.packed, sd.row_src_token,
+                                           sd.row_topk, R, rv.out_rows, rv.out_scales, cap, rv.out_src_peer,
+                                           rv.out_src_token, rctx[(n + 1) % 2], s_next["table"], R, cap,
+                                           rn.expert_offsets, rn.stats, topk_d[:0], None, None, None, no_plan_stats)
         else:
             n = state["n"]
             state["n"] = n + 1
@@ -331,7 +354,7 @@ def bench_dispatch(args, name: str) -> dict:
             c.mw_ctx_set_timing_events(B.MW_KERNEL_EXPAND, a, b)
 
     # ---------------------------------------------------------------- warm-up, then the timed region
-    if args.schedule in ("pipelined", "one_stream", "one_launch"):
+    if args.schedule in ("pipelined", "one_stream", "one_launch", "launch_and_plan"):
         prime_pipeline(args.schedule != "pipelined")
     for i in range(args.warmup):
         step(i)
@@ -364,10 +387,10 @@ def bench_dispatch(args, name: str) -> dict:
     expand_avg_ms = sum(expand_ms) / len(expand_ms)
 
     other, other_issue = {}, {}
-    for sched in ("single", "free", "aligned", "pipelined", "one_stream", "one_launch"):      # the other schedules, for reference
-        if sched == args.schedule:
+    for sched in ("single", "free", "aligned", "pipelined", "one_stream", "one_launch", "launch_and_plan"):
+        if sched == args.schedule:                                 # the other schedules, for reference
             continue
-        if sched in ("pipelined", "one_stream", "one_launch"):
+        if sched in ("pipelined", "one_stream", "one_launch", "launch_and_plan"):
             prime_pipeline(sched != "pipelined")
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -668,7 +691,7 @@ def bench_dispatch(args, name: str) -> dict:
     expand_bytes = M * rb + Q * rb + Q * 8 + M * 4
     value = (pack_bytes + unpack_bytes) / (ms_per_step * 1e-3) / 1e9
     # the bracketed launch moves the expander's bytes -- and the packer's too in "one_launch"
-    launch_bytes = expand_bytes + (pack_bytes if args.schedule == "one_launch" else 0)
+    launch_bytes = expand_bytes + (pack_bytes if args.schedule in ("one_launch", "launch_and_plan") else 0)
     achieved = launch_bytes / (expand_avg_ms * 1e-3) / 1e9
     pu_us = kern_us["pack"] + kern_us["recv_index"] + kern_us["expand"]
     saved = 1.0 - int(st["multicast_bytes"]) / int(st["unicast_bytes"])
@@ -691,7 +714,8 @@ def bench_dispatch(args, name: str) -> dict:
     # the launch that moves the receive side's bytes: the expander, in the pipelined schedule with
     # the next batch's index riding along (same bytes; the index's few MB are not counted)
     dominant = {"pipelined": "k_expand_index_next", "one_stream": "k_expand_index_plan_next",
-                "one_launch": "k_expand_index_plan_next"}.get(args.schedule, "k_expand")
+                "one_launch": "k_expand_index_plan_next",
+                "launch_and_plan": "k_expand_index_plan_next"}.get(args.schedule, "k_expand")
     result = {
         "metric": METRIC,
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -714,7 +738,7 @@ def bench_dispatch(args, name: str) -> dict:
         "copy_ceiling": ceiling,
         "roofline": {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": traffic_from_profile("mw_stream_step" if args.schedule == "one_launch" else dominant,
+                     "traffic": traffic_from_profile("mw_stream_step" if args.schedule in ("one_launch", "launch_and_plan") else dominant,
                                                     name.upper()), "bytes_per_launch": launch_bytes,
                      "avg_launch_ms": round(expand_avg_ms, 4), "min_launch_ms": round(expand_ms[0], 4),
                      "launches_timed": len(expand_ms)},
@@ -861,7 +885,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", choices=["c0", "c1", "c2", "c3", "c4"], default="c1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--schedule", choices=["auto", "aligned", "pipelined", "one_stream", "one_launch", "free", "single"], default="auto",
+    ap.add_argument("--schedule", choices=["auto", "aligned", "pipelined", "one_stream", "one_launch", "launch_and_plan", "free", "single"], default="auto",
                     help="how the send side and the receive side of a step are issued (see step())")
     ap.add_argument("--seed", type=int, default=None)
     args = ap.parse_args()
