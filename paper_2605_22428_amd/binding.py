@@ -65,7 +65,7 @@ class MwConfig(C.Structure):
     _fields_ = [("n_ranks", C.c_int32), ("n_experts", C.c_int32), ("top_k", C.c_int32),
                 ("my_rank", C.c_int32), ("hidden", C.c_int32), ("row_format", C.c_int32),
                 ("row_bytes", C.c_int64), ("max_tokens", C.c_int32), ("max_hops", C.c_int32),
-                ("max_recv_rows", C.c_int64), ("expert_to_rank", C.c_void_p)]
+                ("max_recv_rows", C.c_int64), ("expert_to_rank", C.c_void_p), ("row_stride_bytes", C.c_int64)]
 
 
 class MwError(RuntimeError):
@@ -131,13 +131,13 @@ class Context:
     def __init__(self, n_ranks: int, n_experts: int, top_k: int, my_rank: int, hidden: int,
                  row_format: int, max_tokens: int, max_recv_rows: int,
                  expert_to_rank: Optional[np.ndarray], row_bytes: int = 0, device: str = "cuda:0",
-                 max_hops: int = 0):
+                 max_hops: int = 0, row_stride: int = 0):
         lib = load()
         self.device = torch.device(device)
         e2r = None if expert_to_rank is None else np.ascontiguousarray(expert_to_rank, dtype=np.int32)
         self._e2r = e2r
         cfg = MwConfig(n_ranks, n_experts, top_k, my_rank, hidden, row_format, row_bytes, max_tokens, max_hops,
-                       max_recv_rows, 0 if e2r is None else e2r.ctypes.data)
+                       max_recv_rows, 0 if e2r is None else e2r.ctypes.data, row_stride)
         need = C.c_int64(0)
         _check(lib.mw_workspace_bytes(C.byref(cfg), C.byref(need)), "mw_workspace_bytes")
         self.workspace = torch.zeros(need.value + 256, dtype=torch.uint8, device=self.device)
@@ -156,6 +156,7 @@ class Context:
         else:
             self.x_row_bytes, self.s_row_bytes = row_bytes, 0
         self.row_bytes = self.x_row_bytes + self.s_row_bytes
+        self.row_stride = row_stride if row_stride else self.row_bytes      # bytes from row to row in packed / received arrays
         self.n_local = 0 if e2r is None else int((e2r == my_rank).sum())
 
     def close(self):
@@ -379,7 +380,7 @@ class RelayChildren:
         d, n = ctx.device, max(capacity, 1)
         self.n_hops, self.capacity = n_hops, capacity
         self.desc = [torch.zeros((n, DESC_BYTES), dtype=torch.uint8, device=d) for _ in range(n_hops)]
-        self.rows = [torch.zeros((n, ctx.row_bytes), dtype=torch.uint8, device=d) for _ in range(n_hops)]
+        self.rows = [torch.zeros((n, ctx.row_stride), dtype=torch.uint8, device=d) for _ in range(n_hops)]
         self.row_src_token = [torch.full((n,), -1, dtype=torch.int32, device=d) for _ in range(n_hops)]
         self.row_topk = [torch.zeros((n, ctx.top_k), dtype=torch.int32, device=d) for _ in range(n_hops)]
         host = np.zeros(max(n_hops, 1), dtype=RELAY_CHILD_DTYPE)
@@ -404,7 +405,7 @@ class SendBuffers:
         self.perm = torch.full((n,), -1, dtype=torch.int32, device=d)
         self.desc = torch.zeros((n, DESC_BYTES), dtype=torch.uint8, device=d)
         self.stats = torch.zeros(SEND_STATS_BYTES, dtype=torch.uint8, device=d)
-        self.packed = torch.zeros((n, ctx.row_bytes), dtype=torch.uint8, device=d)
+        self.packed = torch.zeros((n, ctx.row_stride), dtype=torch.uint8, device=d)
         self.row_src_token = torch.full((n,), -1, dtype=torch.int32, device=d)
         self.row_topk = torch.zeros((n, ctx.top_k), dtype=torch.int32, device=d)
 

@@ -45,6 +45,10 @@ int32_t row_geometry(const mw_config &c, int64_t *x_bytes, int64_t *s_bytes)
     if (rb % 16 != 0 || *x_bytes % 16 != 0) return MW_ERR_UNSUPPORTED;
     if (rb / 16 > 0x7fffffffLL) return MW_ERR_UNSUPPORTED;
     if (c.row_format != MW_ROW_BYTES && c.row_bytes != 0 && c.row_bytes != rb) return MW_ERR_INVALID_ARG;
+    if (c.row_stride_bytes != 0) {
+        if (c.row_stride_bytes < rb) return MW_ERR_INVALID_ARG;
+        if (c.row_stride_bytes % 16 != 0 || c.row_stride_bytes / 16 > 0x7fffffffLL) return MW_ERR_UNSUPPORTED;
+    }
     return MW_OK;
 }
 
@@ -147,6 +151,7 @@ MW_API int32_t mw_ctx_create(const mw_config *cfg, void *workspace_dev, int64_t 
     ctx->hit_slots = (cfg->top_k < L ? cfg->top_k : L) > 0 ? (cfg->top_k < L ? cfg->top_k : L) : 1;
     ctx->mask_words = (cfg->n_ranks + 63) / 64;
     ctx->x_row_bytes = xb; ctx->s_row_bytes = sb; ctx->row_bytes = xb + sb;
+    ctx->row_stride = cfg->row_stride_bytes != 0 ? cfg->row_stride_bytes : xb + sb;
     char *b = (char *)workspace_dev;
     ctx->d_eslot = (int32_t *)(b + w.eslot);
     ctx->d_plan_cnt = (uint64_t *)(b + w.plan_cnt);

@@ -62,6 +62,7 @@ struct mw_ctx {
     int64_t x_row_bytes;    // payload part of a row
     int64_t s_row_bytes;    // scale part of a row (fp8) or 0
     int64_t row_bytes;
+    int64_t row_stride;     // bytes from one row to the next in packed / received row arrays (>= row_bytes)
     int device;
     int n_cu;
     // workspace slices

@@ -17,13 +17,13 @@ namespace {
 
 // blockIdx.x = segment of blockDim.x chunks, blockIdx.y walks packed rows.
 __global__ __launch_bounds__(1024) void k_pack(const u32x4 *__restrict__ x, const u32x4 *__restrict__ scales,
-                                                    int xc, int sc, const int32_t *__restrict__ topk, int K,
+                                                    int xc, int sc, int ns, const int32_t *__restrict__ topk, int K,
                                                     const int32_t *__restrict__ perm,
                                                     const mw_send_stats *__restrict__ stats,
                                                     u32x4 *__restrict__ packed, int32_t *__restrict__ row_src_token,
                                                     int32_t *__restrict__ row_topk)
 {
-    mw_pack_body(x, scales, xc, sc, topk, K, perm, stats, packed, row_src_token, row_topk, blockIdx.x, blockIdx.y,
+    mw_pack_body(x, scales, xc, sc, ns, topk, K, perm, stats, packed, row_src_token, row_topk, blockIdx.x, blockIdx.y,
                  gridDim.y);
 }
 
@@ -89,7 +89,7 @@ __global__ __launch_bounds__(1024) void k_pack_quant(const u32x4 *__restrict__ x
                                                      const int32_t *__restrict__ topk, int K,
                                                      const int32_t *__restrict__ perm,
                                                      const mw_send_stats *__restrict__ stats,
-                                                     unsigned char *__restrict__ packed, uint64_t row_bytes,
+                                                     unsigned char *__restrict__ packed, uint64_t row_stride,
                                                      int32_t *__restrict__ row_src_token, int32_t *__restrict__ row_topk)
 {
     const uint32_t gdim = gridDim.x, bdim = blockDim.x;
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(1024) void k_pack_quant(const u32x4 *__restrict__ x
     int32_t t = perm[i];
     const uint32_t n_rows = stats->n_rows;
     while (i < n_rows) {
-        unsigned char *row = packed + (size_t)i * row_bytes;
+        unsigned char *row = packed + (size_t)i * row_stride;
         // ic is a multiple of 64: whole waves.  A lane's U chunks are requested together.
         for (int c0 = threadIdx.x; c0 < ic; c0 += U * bdim) {
             u32x4 vv[U];
@@ -200,7 +200,8 @@ int32_t mw_launch_pack(mw_ctx *ctx, const void *x, const float *scales, const in
     {
         mw_timed tm(ctx, MW_KERNEL_PACK, s);
         hipLaunchKernelGGL(k_pack, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, (const u32x4 *)x, (const u32x4 *)scales, xc, sc,
-                           topk, ctx->cfg.top_k, perm, stats, (u32x4 *)packed, row_src_token, row_topk);
+                           (int)(ctx->row_stride / 16), topk, ctx->cfg.top_k, perm, stats, (u32x4 *)packed, row_src_token,
+                           row_topk);
     }
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;
@@ -241,7 +242,7 @@ int32_t mw_launch_pack_quantize(mw_ctx *ctx, const void *x_bf16, const int32_t *
     {
         mw_timed tm(ctx, MW_KERNEL_PACK_QUANT, s);
         hipLaunchKernelGGL(k_pack_quant<U>, dim3(gx), dim3(bs), 0, s, (const u32x4 *)x_bf16, ic, H, topk, ctx->cfg.top_k,
-                           perm, stats, (unsigned char *)packed, (uint64_t)ctx->row_bytes, row_src_token, row_topk);
+                           perm, stats, (unsigned char *)packed, (uint64_t)ctx->row_stride, row_src_token, row_topk);
     }
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;

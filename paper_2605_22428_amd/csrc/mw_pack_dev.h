@@ -9,17 +9,17 @@ namespace {
 
 // Workgroup `seg` of a packed row's segments (blockDim.x chunks each), rows i_first, i_first +
 // i_stride, ...  Chunks [0, xc) come from x, chunks [xc, xc + sc) from the fp8 scale rows
-// (sc == 0 otherwise).  The row count and the row's token are wave-uniform and fetched
+// (sc == 0 otherwise); packed row i starts ns chunks after row i - 1.  The row count and the row's token are wave-uniform and fetched
 // together (perm has room for every row the grid can reach, so the read is in bounds even
 // past the last kept row).
 struct mw_pack_args {
-    const u32x4 *x, *scales; int xc, sc; const int32_t *topk; int K;
+    const u32x4 *x, *scales; int xc, sc, ns; const int32_t *topk; int K;     // ns: chunks from one packed row to the next
     const int32_t *perm; const mw_send_stats *stats;
     u32x4 *packed; int32_t *row_src_token, *row_topk;
 };
 
 __device__ __forceinline__ void mw_pack_body(const u32x4 *__restrict__ x, const u32x4 *__restrict__ scales,
-                                             int xc, int sc, const int32_t *__restrict__ topk, int K,
+                                             int xc, int sc, int ns, const int32_t *__restrict__ topk, int K,
                                              const int32_t *__restrict__ perm,
                                              const mw_send_stats *__restrict__ stats,
                                              u32x4 *__restrict__ packed, int32_t *__restrict__ row_src_token,
@@ -27,7 +27,7 @@ __device__ __forceinline__ void mw_pack_body(const u32x4 *__restrict__ x, const 
                                              uint32_t i_stride)
 {
     uint32_t gdim = i_stride, bdim = blockDim.x;
-    MW_PIN_S(gdim); MW_PIN_S(bdim); MW_PIN_S(xc); MW_PIN_S(sc); MW_PIN_S(K);
+    MW_PIN_S(gdim); MW_PIN_S(bdim); MW_PIN_S(xc); MW_PIN_S(sc); MW_PIN_S(ns); MW_PIN_S(K);
     MW_PIN_PTR(x); MW_PIN_PTR(scales); MW_PIN_PTR(topk); MW_PIN_PTR(packed); MW_PIN_PTR(row_src_token);
     MW_PIN_PTR(row_topk);
     uint32_t i = i_first;
@@ -39,7 +39,7 @@ __device__ __forceinline__ void mw_pack_body(const u32x4 *__restrict__ x, const 
     while (i < n_rows) {
         if (c < n) {
             const u32x4 v = (c < xc) ? mw_ld16(x + (size_t)t * xc + c) : mw_ld16(scales + (size_t)t * sc + (c - xc));
-            mw_st16(packed + (size_t)i * n + c, v);
+            mw_st16(packed + (size_t)i * ns + c, v);
         }
         if (seg == 0) {
             if (threadIdx.x == 0) row_src_token[i] = t;

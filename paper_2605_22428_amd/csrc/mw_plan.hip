@@ -267,7 +267,7 @@ template <int W, bool kKeyed>
 __global__ __launch_bounds__(kBlock) void k_plan_pack(const int32_t *__restrict__ topk, int T, int K,
                                                       const int32_t *__restrict__ eslot, int E,
                                                       const u32x4 *__restrict__ x, const u32x4 *__restrict__ scales,
-                                                      int xc, int sc, uint64_t row_bytes,
+                                                      int xc, int sc, int ns, uint64_t row_bytes,
                                                       uint64_t *__restrict__ mask_out, int32_t *__restrict__ perm,
                                                       mw_group_desc *__restrict__ desc, mw_send_stats *__restrict__ stats,
                                                       u32x4 *__restrict__ packed, int32_t *__restrict__ row_src_token,
@@ -351,7 +351,7 @@ __global__ __launch_bounds__(kBlock) void k_plan_pack(const int32_t *__restrict_
         for (int ch = t; ch < n; ch += kBlock) {
             const u32x4 v = (ch < xc) ? mw_ld16(x + (size_t)tt * xc + ch)
                                       : mw_ld16(scales + (size_t)tt * sc + (ch - xc));
-            mw_st16(packed + (size_t)i * n + ch, v);
+            mw_st16(packed + (size_t)i * ns + ch, v);
         }
         if (t == 0) row_src_token[i] = tt;
         for (int j = t; j < K; j += kBlock) row_topk[(size_t)i * K + j] = topk[(size_t)tt * K + j];
@@ -679,7 +679,8 @@ int32_t mw_launch_plan_pack(mw_ctx *ctx, const int32_t *topk, int32_t T, const v
     mw_timed tm(ctx, MW_KERNEL_PLAN_PACK, s);
 #define MW_FUSED(W, KEYED)                                                                                        \
     hipLaunchKernelGGL((k_plan_pack<W, KEYED>), grid, block, 0, s, topk, T, K, ctx->d_eslot, E, (const u32x4 *)x, \
-                       (const u32x4 *)scales, xc, sc, rb, mask, perm, desc, stats, (u32x4 *)packed, row_src_token, \
+                       (const u32x4 *)scales, xc, sc, (int)(ctx->row_stride / 16), rb, mask, perm, desc, stats,       \
+                       (u32x4 *)packed, row_src_token,                                                           \
                        row_topk)
     const bool keyed = K <= 8;              // at most eight bits per bitmap: short keys
     switch (ctx->mask_words) {

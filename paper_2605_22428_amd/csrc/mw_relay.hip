@@ -173,7 +173,7 @@ __global__ __launch_bounds__(kBlock) void k_relay_index(
 // blockIdx.x selects a segment of blockDim.x chunks of a row, blockIdx.y walks input rows.
 __global__ __launch_bounds__(1024) void k_relay_copy(
     const mw_recv_peer *__restrict__ in, const mw_relay_child *__restrict__ children, int n_hops, int K, int n_chunks,
-    uint32_t max_tokens, uint64_t row_bytes, const int32_t *__restrict__ group_of_row,
+    int ns, uint32_t max_tokens, uint64_t row_bytes, const int32_t *__restrict__ group_of_row,
     const uint32_t *__restrict__ child_pos, uint32_t *relay_flags, mw_relay_stats *__restrict__ stats)
 {
     const mw_recv_peer src = in[0];
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(1024) void k_relay_copy(
         // the payload's address depends on the row alone: requested first, the group lookups
         // (two dependent round trips) are in flight beside it
         u32x4 v = {0u, 0u, 0u, 0u};
-        if (c < n_chunks) v = mw_ld16((const u32x4 *)src.rows + (size_t)i * n_chunks + c);
+        if (c < n_chunks) v = mw_ld16((const u32x4 *)src.rows + (size_t)i * ns + c);     // ns: chunks from row to row
         const int32_t st = src.row_src_token[i];
         const int32_t g = group_of_row[i];
         if (g < 0 || (uint32_t)g >= n_desc) continue;        // (stale or never written)
@@ -199,7 +199,7 @@ __global__ __launch_bounds__(1024) void k_relay_copy(
             hops &= hops - 1;
             const uint32_t dst = (uint32_t)__shfl((int)p, h, 64) + off;
             const mw_relay_child ch = children[h];
-            if (c < n_chunks) mw_st16((u32x4 *)ch.rows + (size_t)dst * n_chunks + c, v);
+            if (c < n_chunks) mw_st16((u32x4 *)ch.rows + (size_t)dst * ns + c, v);
             if (blockIdx.x == 0) {
                 if (threadIdx.x == 0) ch.row_src_token[dst] = st;
                 if ((int)threadIdx.x < K) ch.row_topk[(size_t)dst * K + threadIdx.x] = tk;
@@ -371,6 +371,7 @@ int32_t mw_launch_relay(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay_chil
         if (gy < 1) gy = 1;
         mw_timed tm(ctx, MW_KERNEL_RELAY_COPY, s);
         hipLaunchKernelGGL(k_relay_copy, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, in, children, ctx->n_hops, c.top_k, n_chunks,
+                           (int)(ctx->row_stride / 16),
                            (uint32_t)c.max_tokens, (uint64_t)ctx->row_bytes, ctx->d_group_of_row, ctx->d_child_pos,
                            ctx->d_relay_flags, stats);
     }

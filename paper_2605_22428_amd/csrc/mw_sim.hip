@@ -39,7 +39,7 @@ __global__ __launch_bounds__(kBlock) void k_deliver_index(const mw_group_desc *_
 }
 
 template <int U>
-__global__ __launch_bounds__(256) void k_deliver_copy(const u32x4 *__restrict__ rows, int n_chunks,
+__global__ __launch_bounds__(256) void k_deliver_copy(const u32x4 *__restrict__ rows, int n_chunks, int ns,
                                                       const int32_t *__restrict__ src_token,
                                                       const int32_t *__restrict__ topk, int K,
                                                       const int32_t *__restrict__ row_map,
@@ -51,8 +51,8 @@ __global__ __launch_bounds__(256) void k_deliver_copy(const u32x4 *__restrict__ 
     const uint32_t i = blockIdx.x;
     if (i >= counts[1]) return;
     const int32_t r = row_map[i];
-    const u32x4 *src = rows + (size_t)r * n_chunks;
-    u32x4 *dst = rows_out + (size_t)i * n_chunks;
+    const u32x4 *src = rows + (size_t)r * ns;          // ns: chunks from one row to the next, both sides
+    u32x4 *dst = rows_out + (size_t)i * ns;
     for (int c0 = threadIdx.x; c0 < n_chunks; c0 += U * 256) {
         u32x4 v[U];
 #pragma unroll
@@ -75,7 +75,7 @@ int32_t mw_launch_sim_deliver(mw_ctx *ctx, const mw_group_desc *desc, const mw_s
                        ctx->d_row_map, counts);
     if (T > 0) {
         hipLaunchKernelGGL(k_deliver_copy<4>, dim3(T), dim3(256), 0, s, (const u32x4 *)rows,
-                           (int)(ctx->row_bytes / 16), src_token, topk, ctx->cfg.top_k, ctx->d_row_map, counts,
+                           (int)(ctx->row_bytes / 16), (int)(ctx->row_stride / 16), src_token, topk, ctx->cfg.top_k, ctx->d_row_map, counts,
                            (u32x4 *)rows_out, src_token_out, topk_out);
     }
     MW_HIP_CHECK(hipGetLastError());

@@ -562,7 +562,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
     }
     y -= n_plan_rows;
     if (y < n_pack_rows) {              // (mw_stream_step: the packer of a batch planned by an earlier launch)
-        mw_pack_body(pack.x, pack.scales, pack.xc, pack.sc, pack.topk, pack.K, pack.perm, pack.stats, pack.packed,
+        mw_pack_body(pack.x, pack.scales, pack.xc, pack.sc, pack.ns, pack.topk, pack.K, pack.perm, pack.stats, pack.packed,
                      pack.row_src_token, pack.row_topk, blockIdx.x, y, n_pack_rows);
         return;
     }
@@ -660,7 +660,8 @@ static bool make_index_args(mw_ctx *ctx, const void *peers, bool packets, int32_
     *lds_bytes = ((size_t)wpl + 2 * (size_t)Lc * wpl + 64) * sizeof(uint32_t);
     const uint32_t hb = packets ? (uint32_t)mw_packet_header_bytes_of(c.top_k) : 0u;
     *a = mw_index_args{peers, P, ctx->d_eslot, c.n_experts, c.top_k, ctx->hit_slots, c.my_rank, L, Lc,
-                       (uint32_t)c.max_tokens, wpl, (uint32_t)c.max_recv_rows, (uint64_t)(hb + ctx->row_bytes), hb, cap,
+                       (uint32_t)c.max_tokens, wpl, (uint32_t)c.max_recv_rows,
+                       (uint64_t)(packets ? hb + ctx->row_bytes : ctx->row_stride), hb, cap,
                        ctx->d_cnt, ctx->d_row_base, ctx->d_addr_cnt, ctx->d_recs, ctx->d_hits, ctx->d_base,
                        expert_offsets, stats, ctx->d_flags};
     return true;
@@ -801,6 +802,7 @@ int32_t mw_launch_unpack_expand_index_plan_next(mw_ctx *ctx, int32_t P, void *ou
         uint32_t n_pack_rows = 0;
         if (pk && pk->n_tokens > 0) {
             pa.x = (const u32x4 *)pk->x; pa.scales = (const u32x4 *)pk->scales; pa.xc = xc; pa.sc = sc;
+            pa.ns = (int)(ctx->row_stride / 16);
             pa.topk = pk->topk; pa.K = c.top_k; pa.perm = pk->perm; pa.stats = pk->stats;
             pa.packed = (u32x4 *)pk->packed; pa.row_src_token = pk->row_src_token; pa.row_topk = pk->row_topk;
             n_pack_rows = (uint32_t)pk->n_tokens < 16384u ? (uint32_t)pk->n_tokens : 16384u;   // more by striding

@@ -20,12 +20,12 @@ def fmt_code(w: W.DispatchWorkload) -> int:
 
 
 def make_ctx(w: W.DispatchWorkload, my_rank: Optional[int] = None, max_recv_rows: Optional[int] = None,
-             max_tokens: Optional[int] = None) -> B.Context:
+             max_tokens: Optional[int] = None, row_stride: int = 0) -> B.Context:
     r = w.my_rank if my_rank is None else my_rank
     cap = max_recv_rows if max_recv_rows is not None else w.n_ranks * w.n_tokens
     return B.Context(w.n_ranks, w.n_experts, w.top_k, r, w.hidden, fmt_code(w),
                      max_tokens if max_tokens is not None else max(w.n_tokens, 1), cap,
-                     W.expert_to_rank(w), device=DEV)
+                     W.expert_to_rank(w), device=DEV, row_stride=row_stride)
 
 
 _SIGNED = {np.dtype(np.uint16): np.int16, np.dtype(np.uint32): np.int32, np.dtype(np.uint64): np.int64}
@@ -77,13 +77,14 @@ class GpuSend:
 
     def host_pack(self):
         b = self.buf
-        return host(b.packed)[: self.N], host(b.row_src_token)[: self.N], host(b.row_topk)[: self.N]
+        return (host(b.packed)[: self.N, : self.ctx.row_bytes], host(b.row_src_token)[: self.N],
+                host(b.row_topk)[: self.N])
 
     def deliver(self, dst_rank: int) -> dict:
         """mw_sim_deliver -> record for peers_table (device tensors, counts read back)."""
         ctx, b, n = self.ctx, self.buf, max(self.T, 1)
         out = dict(desc=torch.zeros((n, B.DESC_BYTES), dtype=torch.uint8, device=DEV),
-                   rows=torch.zeros((n, ctx.row_bytes), dtype=torch.uint8, device=DEV),
+                   rows=torch.zeros((n, ctx.row_stride), dtype=torch.uint8, device=DEV),
                    row_src_token=torch.full((n,), -1, dtype=torch.int32, device=DEV),
                    row_topk=torch.zeros((n, ctx.top_k), dtype=torch.int32, device=DEV))
         counts = torch.zeros(2, dtype=torch.int32, device=DEV)
@@ -99,10 +100,11 @@ class GpuSend:
                     n_desc=self.G, n_rows=self.N)
 
 
-def record_host(rec: dict):
-    """Host copy of a peer record as the oracle's (desc, rows, src_token, row_topk) tuple."""
+def record_host(rec: dict, row_bytes: Optional[int] = None):
+    """Host copy of a peer record as the oracle's (desc, rows, src_token, row_topk) tuple
+    (row_bytes: the rows' own length where the record's rows are further apart)."""
     g, n = rec["n_desc"], rec["n_rows"]
-    return (host(rec["desc"]).reshape(-1).view(B.DESC_DTYPE)[:g], host(rec["rows"])[:n],
+    return (host(rec["desc"]).reshape(-1).view(B.DESC_DTYPE)[:g], host(rec["rows"])[:n, :row_bytes],
             host(rec["row_src_token"])[:n], host(rec["row_topk"])[:n])
 
 
@@ -169,6 +171,8 @@ def check_send(w: W.DispatchWorkload, g: GpuSend, topk: np.ndarray, x: np.ndarra
     packed, src, rtk = ref.pack(x, scales, topk, perm)
     gp, gs, gt = g.host_pack()
     assert_same_bytes(gp, packed, "packed rows")
+    if g.ctx.row_stride > g.ctx.row_bytes:                 # the bytes between rows are never written
+        assert not host(g.buf.packed)[: g.N, g.ctx.row_bytes:].any(), "bytes between packed rows were written"
     assert_same_bytes(gs, src, "row_src_token")
     assert_same_bytes(gt, rtk, "row_topk")
     return perm, desc, packed, src, rtk

@@ -17,13 +17,13 @@ def _say(*a):
     print(*a, flush=True)
 
 
-def _one(w, seed, rank, edit=None):
+def _one(w, seed, rank, edit=None, row_stride=0):
     _say("fused", w.name, "seed", seed, "rank", rank, "T", w.n_tokens, "H", w.hidden, w.row_format)
     tk = W.topk_ids(w, seed, rank)
     if edit is not None:
         edit(tk)
     x, sc = W.payload_rows(w, seed, rank)
-    ctx = H.make_ctx(w, rank, max_recv_rows=1)
+    ctx = H.make_ctx(w, rank, max_recv_rows=1, row_stride=row_stride)
     g = H.GpuSend(ctx, tk, x, sc, fused=True)
     H.check_send(w, g, tk, x, sc)
     two = H.GpuSend(ctx, tk, x, sc)                      # the two-call path, whole buffers
@@ -55,6 +55,7 @@ def test_wide_bitmaps(T):
 
 
 def test_full_width_rows_bf16_and_fp8():
+    _one(W.scaled(W.C2, n_tokens=100, hidden=1024), 6, 3, row_stride=1152)      # rows of 1056 bytes, 1152 apart
     _one(W.scaled(W.C1, n_tokens=128), W.BASE_SEED, 0)
     _one(W.scaled(W.C2, n_tokens=64), W.BASE_SEED, 9)
     _one(W.scaled(W.C2, n_tokens=129, hidden=1024), 4, 9)

@@ -21,12 +21,12 @@ def _say(*a):
 
 
 def run_dispatch(w, seed, my_rank, check_all_senders=True, lazy=False, tier2=True, also_full=False,
-                 sample_peers=(), stream_step=False):
+                 sample_peers=(), stream_step=False, row_stride=0):
     """Every simulated peer runs plan+pack (GPU and oracle separately), the simulated network
     filters to my_rank, then unpack on both sides; compared at every stage."""
     _say("dispatch", w.name, "seed", seed, "my_rank", my_rank, "T", w.n_tokens, "H", w.hidden)
     e2r = W.expert_to_rank(w)
-    ctx = H.make_ctx(w, my_rank)
+    ctx = H.make_ctx(w, my_rank, row_stride=row_stride)
     recs, full_recs, bufs, toks = [], [], [], []
     topks = W.topk_ids_many(w, seed, range(w.n_ranks))
     x_dev = s_dev = None
@@ -67,7 +67,7 @@ def run_dispatch(w, seed, my_rank, check_all_senders=True, lazy=False, tier2=Tru
             bufs.append(obuf)
         rec = H.shrink(g.deliver(my_rank))
         if detailed:
-            got = H.record_host(rec)
+            got = H.record_host(rec, w.row_bytes)
             for a, b, name in zip(got, obuf, ("desc", "rows", "src_token", "row_topk")):
                 H.assert_same_bytes(a.view(np.uint8) if name == "desc" else a,
                                     b.view(np.uint8) if name == "desc" else b, "deliver %s peer %d" % (name, p))
@@ -98,7 +98,7 @@ def run_dispatch(w, seed, my_rank, check_all_senders=True, lazy=False, tier2=Tru
         # tokens indexed and planned again as "the next batch" in a second context
         tk, x, sc = toks[my_rank]
         g = H.GpuSend(ctx, tk, x, sc)                          # (plans; its packed rows are overwritten below)
-        ctx2 = H.make_ctx(w, my_rank)
+        ctx2 = H.make_ctx(w, my_rank, row_stride=row_stride)
         rv, rv2 = B.RecvBuffers(ctx, cap), B.RecvBuffers(ctx2, cap)
         nxt = B.SendBuffers(ctx2, w.n_tokens)
         table = B.peers_table(recs, H.DEV)
@@ -830,3 +830,17 @@ def test_opaque_byte_rows():
     gu = H.GpuUnpack(ctx, recs, cap)
     H.check_unpack(gu, ref.dispatch_plain(toks, e2r, my_rank, cap), "opaque rows")
     ctx.close()
+
+
+# ------------------------------------------------------------------ rows further apart than they are long
+@pytest.mark.parametrize("which", ["fp8", "bf16_odd", "c0"])
+def test_row_stride(which):
+    """mw_config.row_stride_bytes: packed, delivered and received rows start a stride apart (fp8 rows
+    of 1056 bytes every 1152, the next multiple of 128; bf16 rows of 1040 bytes every 1280; C0's rows
+    of 512 bytes every 528).  Every output is what it is with rows back to back, the bytes between
+    rows stay untouched, and mw_stream_step packs and expands with the same stride."""
+    w, stride, my_rank = {"fp8": (W.scaled(W.C2, n_tokens=200, hidden=1024), 1152, 9),
+                          "bf16_odd": (W.DispatchWorkload("odd", 96, 8, 16, 3, 150, 520, "bf16", "uniform"), 1280, 2),
+                          "c0": (W.C0, 528, 5)}[which]
+    assert stride > w.row_bytes
+    run_dispatch(w, 3, my_rank, also_full=True, stream_step=True, row_stride=stride)

@@ -32,13 +32,15 @@ def gpu_pack_quantize(ctx, tk, x_bits):
     ctx.mw_pack_quantize(x_d, tk_d, buf.perm, buf.stats, buf.packed, buf.row_src_token, buf.row_topk)
     st = ctx.mw_get_send_stats(buf.stats)
     n = int(st["n_rows"])
-    return H.host(buf.packed)[:n], H.host(buf.row_src_token)[:n], H.host(buf.row_topk)[:n], H.host(buf.perm)[:n]
+    whole = H.host(buf.packed)[:n]
+    assert not whole[:, ctx.row_bytes:].any(), "bytes between packed rows were written"
+    return whole[:, : ctx.row_bytes], H.host(buf.row_src_token)[:n], H.host(buf.row_topk)[:n], H.host(buf.perm)[:n]
 
 
-def check(w_fp8, tk, x_bits, rows=None):
+def check(w_fp8, tk, x_bits, rows=None, row_stride=0):
     """rows: check only these packed rows against the oracle (full sizes); None = all."""
     e2r = W.expert_to_rank(w_fp8)
-    ctx = H.make_ctx(w_fp8, 0, max_recv_rows=1, max_tokens=max(tk.shape[0], 1))
+    ctx = H.make_ctx(w_fp8, 0, max_recv_rows=1, max_tokens=max(tk.shape[0], 1), row_stride=row_stride)
     packed, src, rtk, perm_g = gpu_pack_quantize(ctx, tk, x_bits)
     _, perm, _, _ = ref.plan(tk, e2r, w_fp8.n_ranks, w_fp8.row_bytes)
     H.assert_same_bytes(perm_g, perm, "perm")
@@ -89,6 +91,7 @@ def test_full_width_rows_ragged_token_count():
     check(w, tk, x_bits)
     w = W.DispatchWorkload("narrow_fp8", 13, 8, 16, 2, 40, 512, "fp8", "uniform")
     check(w, *_inputs(w, 6))
+    check(w, *_inputs(w, 7), row_stride=640)              # rows of 528 bytes, 640 apart
 
 
 def test_every_code_and_every_exact_tie():

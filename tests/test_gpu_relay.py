@@ -18,11 +18,11 @@ def _say(*a):
     print(*a, flush=True)
 
 
-def _ctx(w, my_rank, max_hops, max_tokens=None, max_recv_rows=None):
+def _ctx(w, my_rank, max_hops, max_tokens=None, max_recv_rows=None, row_stride=0):
     return B.Context(w.n_ranks, w.n_experts, w.top_k, my_rank, w.hidden, H.fmt_code(w),
                      max_tokens if max_tokens is not None else w.n_tokens,
                      max_recv_rows if max_recv_rows is not None else w.n_ranks * w.n_tokens,
-                     W.expert_to_rank(w), device=H.DEV, max_hops=max_hops)
+                     W.expert_to_rank(w), device=H.DEV, max_hops=max_hops, row_stride=row_stride)
 
 
 def _in_record(rec):
@@ -39,9 +39,10 @@ def gpu_relay(ctx, rec, next_hop, n_hops, capacity):
     return ch, st, table
 
 
-def child_host(ch, st, h):
+def child_host(ch, st, h, row_bytes=None):
     g, n = int(st["groups_per_hop"][h]), int(st["rows_per_hop"][h])
-    return (H.host(ch.desc[h]).reshape(-1).view(B.DESC_DTYPE)[:g], H.host(ch.rows[h])[:n],
+    rb = ch.rows[h].shape[1] if row_bytes is None else row_bytes
+    return (H.host(ch.desc[h]).reshape(-1).view(B.DESC_DTYPE)[:g], H.host(ch.rows[h])[:n, :rb],
             H.host(ch.row_src_token[h])[:n], H.host(ch.row_topk[h])[:n])
 
 
@@ -49,7 +50,7 @@ def check_children(ch, st, parent_host, next_hop, n_hops, row_bytes, hops=None):
     desc, rows, src, rtk = parent_host
     for h in (range(n_hops) if hops is None else hops):
         want = ref.relay_child(desc, rows, src, rtk, next_hop, n_hops, h)
-        got = child_host(ch, st, h)
+        got = child_host(ch, st, h, row_bytes)
         H.assert_same_bytes(got[0].view(np.uint8), want[0].view(np.uint8), "child %d desc" % h)
         H.assert_same_bytes(got[1], want[1], "child %d rows" % h)
         H.assert_same_bytes(got[2], want[2], "child %d src_token" % h)
@@ -255,4 +256,21 @@ def test_relay_long_rows(hidden):
     tk, x, sc, g = _send(ctx, w, 2, 3)
     ch, st, _ = gpu_relay(ctx, g.full_record(), next_hop, 5, w.n_tokens)
     check_children(ch, st, H.oracle_send(w, tk, x, sc), next_hop, 5, w.row_bytes)
+    ctx.close()
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "fp8"])
+def test_relay_with_a_row_stride(fmt):
+    """Rows a stride apart on both sides of the relay (parent buffer and every child's)."""
+    w = W.scaled(W.C1 if fmt == "bf16" else W.C2, n_tokens=210, hidden=1024)
+    stride = (w.row_bytes + 127) // 128 * 128 + 128
+    next_hop = (np.arange(w.n_ranks) % 6).astype(np.int32)
+    ctx = _ctx(w, 7, 8, row_stride=stride)
+    tk, x, sc, g = _send(ctx, w, 4, 7)
+    H.check_send(w, g, tk, x, sc)
+    ch, st, _ = gpu_relay(ctx, g.full_record(), next_hop, 6, w.n_tokens)
+    check_children(ch, st, H.oracle_send(w, tk, x, sc), next_hop, 6, w.row_bytes)
+    for h in range(6):
+        n = int(st["rows_per_hop"][h])
+        assert not H.host(ch.rows[h])[:n, w.row_bytes:].any(), "bytes between a child's rows were written"
     ctx.close()
