@@ -134,6 +134,10 @@ def bench_dispatch(args, name: str) -> dict:
               "bf16, top-8 Zipf(1.1); receive side at the rank of the median-popularity expert",
     }[name]
     R, K, T, rb = w.n_ranks, w.top_k, w.n_tokens, w.row_bytes
+    # rows that are not whole cache lines lie a whole number of lines apart in the packed and the
+    # received arrays (mw_config.row_stride_bytes; fp8: 7392-byte rows every 7424 bytes): layout
+    # only -- the bytes moved and counted are the rows' own
+    stride = (rb + 127) // 128 * 128 if args.row_stride is None else args.row_stride
     e2r = W.expert_to_rank(w)
     L = w.experts_per_rank
     fp8 = w.row_format == "fp8"
@@ -148,9 +152,9 @@ def bench_dispatch(args, name: str) -> dict:
 
     # ---------------------------------------------------------------- set-up (untimed)
     t_setup = time.time()
-    ctx = B.Context(R, w.n_experts, K, my_rank, w.hidden, fmt, T, R * T, e2r, device=dev, max_hops=16)
-    ctx_b = B.Context(R, w.n_experts, K, my_rank, w.hidden, fmt, T, R * T, e2r, device=dev)   # second receive index
-    ctx_p = B.Context(R, w.n_experts, K, my_rank, w.hidden, fmt, T, 1, e2r, device=dev)       # plans beside mw_stream_step
+    ctx = B.Context(R, w.n_experts, K, my_rank, w.hidden, fmt, T, R * T, e2r, device=dev, max_hops=16, row_stride=stride)
+    ctx_b = B.Context(R, w.n_experts, K, my_rank, w.hidden, fmt, T, R * T, e2r, device=dev, row_stride=stride)   # second receive index
+    ctx_p = B.Context(R, w.n_experts, K, my_rank, w.hidden, fmt, T, 1, e2r, device=dev, row_stride=stride)       # plans beside mw_stream_step
     topks = W.topk_ids_many(w, seed, range(R))
     x_me, s_me = W.payload_rows(w, seed, my_rank)
     topk_d = up(topks[my_rank])
@@ -161,7 +165,7 @@ def bench_dispatch(args, name: str) -> dict:
     s_peer = torch.zeros((T, w.hidden // 128), dtype=torch.float32, device=dev) if fp8 else None
     sb = B.SendBuffers(ctx, T)
     out = dict(desc=torch.zeros((T, B.DESC_BYTES), dtype=torch.uint8, device=dev),
-               rows=torch.zeros((T, rb), dtype=torch.uint8, device=dev),
+               rows=torch.zeros((T, stride), dtype=torch.uint8, device=dev),
                row_src_token=torch.zeros(T, dtype=torch.int32, device=dev),
                row_topk=torch.zeros((T, K), dtype=torch.int32, device=dev))
     counts = torch.zeros(2, dtype=torch.int32, device=dev)
@@ -594,12 +598,12 @@ def bench_dispatch(args, name: str) -> dict:
             torch.cuda.synchronize()
             us[label] = round(10.0 * a.elapsed_time(b), 2)
         # the receive side of the same batch size: every peer sends its first Td tokens
-        ctx_d = B.Context(R, w.n_experts, K, my_rank, w.hidden, fmt, Td, R * Td, e2r, device=dev)
+        ctx_d = B.Context(R, w.n_experts, K, my_rank, w.hidden, fmt, Td, R * Td, e2r, device=dev, row_stride=stride)
         sb_d = B.SendBuffers(ctx_d, Td)
         x_d = torch.zeros((Td, w.hidden), dtype=xdt, device=dev)
         s_d = torch.zeros((Td, w.hidden // 128), dtype=torch.float32, device=dev) if fp8 else None
         o_d = dict(desc=torch.zeros((Td, B.DESC_BYTES), dtype=torch.uint8, device=dev),
-                   rows=torch.zeros((Td, rb), dtype=torch.uint8, device=dev),
+                   rows=torch.zeros((Td, stride), dtype=torch.uint8, device=dev),
                    row_src_token=torch.zeros(Td, dtype=torch.int32, device=dev),
                    row_topk=torch.zeros((Td, K), dtype=torch.int32, device=dev))
         recs_d = []
@@ -650,7 +654,7 @@ def bench_dispatch(args, name: str) -> dict:
         with torch.cuda.graph(graph, stream=side):
             step_d()
         # and as two launches: the packer, then the expander with the next batch's index and plan
-        ctx_d2 = B.Context(R, w.n_experts, K, my_rank, w.hidden, fmt, Td, R * Td, e2r, device=dev)
+        ctx_d2 = B.Context(R, w.n_experts, K, my_rank, w.hidden, fmt, Td, R * Td, e2r, device=dev, row_stride=stride)
         rv_d2 = B.RecvBuffers(ctx_d2, cap_d)
         ride_ctx, ride_rv, ride_n = (ctx_d, ctx_d2), (rv_d, rv_d2), {"n": 0}
         ctx_d2.mw_unpack_index(table_d, R, cap_d, rv_d2.expert_offsets, rv_d2.stats)
@@ -723,7 +727,7 @@ def bench_dispatch(args, name: str) -> dict:
         "vs_baseline": None, "dtype": "u8", "data": "synthetic",
         "config": {"workload": describe, "seed": seed, "my_rank": my_rank,
                    "rows_packed": N, "groups": int(st["n_groups"]), "rows_received": M, "rows_out": Q,
-                   "buffer_sets": N_SETS, "schedule": args.schedule,
+                   "buffer_sets": N_SETS, "schedule": args.schedule, "row_bytes": rb, "row_stride_bytes": stride,
                    "streams": 1 if args.schedule in ("single", "one_stream", "one_launch") else 2},
         "other_schedules_ms_per_step": other,
         "host_issue_ms_per_step": dict(other_issue, **{args.schedule: round(issue_ms_per_step, 4)}),
@@ -888,6 +892,8 @@ def main() -> int:
     ap.add_argument("--schedule", choices=["auto", "aligned", "pipelined", "one_stream", "one_launch", "launch_and_plan", "free", "single"], default="auto",
                     help="how the send side and the receive side of a step are issued (see step())")
     ap.add_argument("--seed", type=int, default=None)
+    ap.add_argument("--row-stride", type=int, default=None,
+                    help="bytes from row to row in packed / received arrays (default: row bytes rounded up to 128)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the other ranks of the dispatch are "
