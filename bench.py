@@ -36,9 +36,45 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+class TimingEvent:
+    """A HIP event with timing, created without the system-scope fence that torch's events end
+    with when they are recorded (a cache write-back and invalidation nothing here needs): the
+    pair around a launch then measures about 2 us less of its own making.  Same interface as
+    the part of torch.cuda.Event the bench uses."""
+    _hip = None
+
+    def __init__(self, torch):
+        import ctypes as C
+        if TimingEvent._hip is None:
+            TimingEvent._hip = C.CDLL("libamdhip64.so")
+        self._C, self._torch = C, torch
+        ev = C.c_void_p()
+        if TimingEvent._hip.hipEventCreateWithFlags(C.byref(ev), C.c_uint(0x20000000)) != 0:
+            raise OSError("hipEventCreateWithFlags failed")
+        self._ev = ev
+
+    @property
+    def cuda_event(self):
+        return self._ev.value
+
+    def record(self, stream=None):
+        st = self._torch.cuda.current_stream() if stream is None else stream
+        if TimingEvent._hip.hipEventRecord(self._ev, self._C.c_void_p(st.cuda_stream)) != 0:
+            raise RuntimeError("hipEventRecord failed")
+
+    def elapsed_time(self, other):
+        ms = self._C.c_float()
+        if TimingEvent._hip.hipEventElapsedTime(self._C.byref(ms), self._ev, other._ev) != 0:
+            raise RuntimeError("hipEventElapsedTime failed")
+        return float(ms.value)
+
+
 def new_events(torch, n):
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
-    for a, b in ev:          # torch creates the handles on first record
+    try:
+        ev = [(TimingEvent(torch), TimingEvent(torch)) for _ in range(n)]
+    except OSError:          # the HIP runtime library cannot be opened by name: torch's events
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    for a, b in ev:          # (torch creates its handles on first record)
         a.record(); b.record()
     torch.cuda.synchronize()
     return ev
