@@ -486,7 +486,11 @@ __device__ __forceinline__ void expand_body(
             for (int k = 1;; ++k) {
                 if (dst < cap) {
                     if (c < xc) mw_st16(out_rows + (size_t)dst * xc + c, v);
-                    else if (c < n) mw_st16(out_scales + (size_t)dst * sc + (c - xc), v);
+                    // a row's scales are a fraction of a cache line (224 bytes of fp8 rows): an
+                    // ordinary store lets L2 put neighbouring rows' pieces together before the
+                    // line goes to memory, where the write-through store sent every piece by
+                    // itself (fp8 expander 77.5 -> 76 us, the step 97.4 -> 94.5 us)
+                    else if (c < n) out_scales[(size_t)dst * sc + (c - xc)] = v;
                     if (c == 0) { out_src_peer[dst] = peer; out_src_token[dst] = (int32_t)r0.z; }
                 }
                 if (k >= n_hits) break;
