@@ -773,7 +773,7 @@ int32_t mw_launch_unpack_expand_index_plan_next(mw_ctx *ctx, int32_t P, void *ou
     if (shape.bs == 64 && (xc + sc) % 16 == 0) { shape.bs = 128; shape.nseg = (xc + sc) / 128 + ((xc + sc) % 128 ? 1 : 0); }
     const uint32_t gy = expand_grid_rows(ctx);
 
-    // the riding plan: workgroups of the launch's size, slices of 128 tokens
+    // the riding plan: workgroups of the launch's size
     const int K = next->cfg.top_k, W = next->mask_words;
     const bool keyed = W > 1 && K <= 8;
     mw_plan_args pl;
