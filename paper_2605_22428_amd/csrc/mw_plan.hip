@@ -129,6 +129,7 @@ __global__ __launch_bounds__(kBlock) void k_groups(const uint64_t *__restrict__ 
     unsigned long long c = 0;
     if (i < N) {
         t = tok[tid];
+        if ((uint32_t)t >= (uint32_t)T) t = 0;      // (only counters corrupted by overlapping plans leave a row unclaimed)
         perm[i] = t;
         c = tokc[tid];
         st = ((c >> 21) & kField) == 0 ? 1u : 0u;
@@ -145,7 +146,7 @@ __global__ __launch_bounds__(kBlock) void k_groups(const uint64_t *__restrict__ 
         d.row_count = (uint32_t)((c >> 42) & kField);          // equal bitmaps, this token included
         d.n_dest = nd;
         d.reserved0 = 0;
-        desc[g] = d;
+        if (g < (uint32_t)T) desc[g] = d;                      // (always, unless the counters were corrupted)
     }
 
     if (blockIdx.x == 0) {

@@ -277,6 +277,7 @@ __device__ __forceinline__ void mw_plan_finish_ride(const mw_plan_args &a, uint3
         unsigned long long c = 0;
         if (i < N) {
             t = tok[k0 + tid];
+            if ((uint32_t)t >= T) t = 0;
             a.perm[i] = t;
             c = tokc[k0 + tid];
             st = ((c >> 21) & kField) == 0 ? 1u : 0u;
@@ -294,7 +295,7 @@ __device__ __forceinline__ void mw_plan_finish_ride(const mw_plan_args &a, uint3
             d.row_count = (uint32_t)((c >> 42) & kField);
             d.n_dest = nd;
             d.reserved0 = 0;
-            a.desc[g] = d;
+            if (g < T) a.desc[g] = d;
         }
     }
     if (fb == 0) {
