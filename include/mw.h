@@ -191,8 +191,9 @@ MW_API int32_t mw_ctx_create(const mw_config *cfg, void *workspace_dev, int64_t 
 MW_API int32_t mw_ctx_destroy(mw_ctx *ctx);
 
 /*
- * Number of polls (about 3 us each) the second half of a plan riding in
- * mw_unpack_expand_index_plan_next waits for its first half before it gives up; default 262144.
+ * Number of polls (about half a microsecond each) the second half of a plan riding in
+ * mw_unpack_expand_index_plan_next or mw_stream_step waits for its first half before it gives
+ * up; default 2097152.
  * 0 makes it give up unless the first half is already complete when it looks: for tests of
  * that path.  Applies to later calls that plan with this context.
  */

@@ -171,7 +171,7 @@ MW_API int32_t mw_ctx_create(const mw_config *cfg, void *workspace_dev, int64_t 
     ctx->d_row_map = (int32_t *)(b + w.row_map);
     ctx->n_hops = 0;
     ctx->recv_rows_hint = 0;
-    ctx->ride_wait_limit = 1u << 18;
+    ctx->ride_wait_limit = 1u << 21;
     ctx->d_hop_bits = (uint64_t *)(b + w.hop_bits);
     ctx->d_relay_flags = (uint32_t *)(b + w.hop_bits + 8LL * MW_MASK_WORDS * MW_MAX_HOPS);
     ctx->d_group_of_row = (int32_t *)(b + w.group_of_row);

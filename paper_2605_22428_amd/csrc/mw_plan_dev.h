@@ -208,7 +208,7 @@ static inline size_t mw_plan_finish_lds(int bs) { return 12u * (size_t)mw_plan_f
 // rank workgroups are part of the SAME launch, so:
 //  * it waits until all of them have reported (pstate[kPsDone] == n_rank).  They come before
 //    it in the launch's workgroup order, are dispatched before it, and wait for nothing, so
-//    the wait ends; it is bounded all the same (wait_limit polls of ~3 us): past the bound
+//    the wait ends; it is bounded all the same (wait_limit polls of ~0.5 us): past the bound
 //    the plan is given up -- statistics with MW_FLAG_PLAN_TIMEOUT and zero rows, state left
 //    as it is -- and the workgroup exits;
 //  * what those workgroups wrote is read at device scope: the counters and the state are
@@ -226,7 +226,7 @@ __device__ __forceinline__ void mw_plan_finish_ride(const mw_plan_args &a, uint3
     if (tid == 0) {
         uint32_t polls = 0;
         while (mw_ld_agent32(&a.pstate[kPsDone]) < a.n_rank && polls < a.wait_limit) {
-            __builtin_amdgcn_s_sleep(127);
+            __builtin_amdgcn_s_sleep(16);
             ++polls;
         }
         scratch[18] = mw_ld_agent32(&a.pstate[kPsDone]) >= a.n_rank ? 1u : 0u;
