@@ -709,8 +709,23 @@ def bench_dispatch(args, name: str) -> dict:
                                                          ride_rv[b].stats, tk_s, sd0.mask, sd0.perm, sd0.desc,
                                                          sd0.stats)
 
+        # and as ONE launch (mw_stream_step); the plan riding in step n is the one step n + 1 packs from
+        sd_pair = (sd0, B.SendBuffers(ctx, Td))
+        for sd_ in sd_pair:
+            ctx.mw_plan(tk_s, sd_.mask, sd_.perm, sd_.desc, sd_.stats)
+
+        def step_one():
+            n = ride_n["n"]
+            ride_n["n"] = n + 1
+            a, b = n % 2, (n + 1) % 2
+            ride_ctx[a].mw_stream_step(x_s, sc_s, tk_s, sd_pair[a].perm, sd_pair[a].stats, sd_pair[a].packed,
+                                       sd_pair[a].row_src_token, sd_pair[a].row_topk, R, ride_rv[a].out_rows,
+                                       ride_rv[a].out_scales, cap_d, ride_rv[a].out_src_peer, ride_rv[a].out_src_token,
+                                       ride_ctx[b], table_d, R, cap_d, ride_rv[b].expert_offsets, ride_rv[b].stats,
+                                       tk_s, sd_pair[b].mask, sd_pair[b].perm, sd_pair[b].desc, sd_pair[b].stats)
+
         for label, fn in (("step_us", step_d), ("step_graph_replay_us", graph.replay),
-                          ("step_two_launches_us", step_ride)):
+                          ("step_two_launches_us", step_ride), ("step_one_launch_us", step_one)):
             for _ in range(10):
                 fn()
             (a, b), = new_events(torch, 1)
