@@ -252,6 +252,10 @@ def bench_dispatch(args, name: str) -> dict:
     # The send side (plan, pack of this rank's tokens) and the receive side (unpack of what the
     # peers sent) are independent operations on disjoint buffers and disjoint workspace.
     s_send, s_recv = torch.cuda.Stream(), torch.cuda.Stream()
+    for st_ in (s_send, s_recv):                 # both streams get their hardware queue now, not in the
+        with torch.cuda.stream(st_):             # middle of the schedule comparison
+            torch.zeros(1, device=dev)
+    torch.cuda.synchronize()
 
     def send_side(s):
         sd = s["send"]
