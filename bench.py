@@ -876,12 +876,22 @@ def bench_allgather(args) -> dict:
                          out=torch.empty(R * sbytes, dtype=torch.uint8, device=dev)))
     torch.cuda.synchronize()
 
-    def step(i):
+    # "one_launch" (auto): mw_allgather_step -- the shards received for one operation are
+    # assembled while this rank's shard of the next one is loaded into its send buffer and
+    # planned, in one launch; "single": the three calls one after the other.
+    sched = "one_launch" if args.schedule in ("auto", "one_launch") else "single"
+
+    def step_three(i):
         s = sets[i % N_SETS]
         ctx.mw_plan_allgather(sbytes, s["desc"], s["stats"])
         ctx.mw_pack_allgather(shard, sbytes, s["send"])
         ctx.mw_unpack_allgather(s["ptrs"], sbytes, s["out"])
 
+    def step_one(i):
+        s, sn = sets[i % N_SETS], sets[(i + 1) % N_SETS]
+        ctx.mw_allgather_step(shard, sbytes, sn["send"], sn["desc"], sn["stats"], s["ptrs"], s["out"])
+
+    step = step_one if sched == "one_launch" else step_three
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -906,14 +916,24 @@ def bench_allgather(args) -> dict:
     for i in range(n_b):
         for k, code in names.items():
             ctx.mw_ctx_set_timing_events(code, *evs[k][i])
-        step(i)
+        step_three(i)
     torch.cuda.synchronize()
     for code in names.values():
         ctx.mw_ctx_set_timing_events(code, None, None)
     kern_us = {k: 1e3 * sum(a.elapsed_time(b) for a, b in evs[k]) / n_b for k in names}
     pack_bytes, unpack_bytes = 2 * sbytes, 2 * R * sbytes
     value = (pack_bytes + unpack_bytes) / (ms_per_step * 1e-3) / 1e9
-    achieved = unpack_bytes / (g_avg * 1e-3) / 1e9
+    launch_bytes = unpack_bytes + (pack_bytes if sched == "one_launch" else 0)
+    achieved = launch_bytes / (g_avg * 1e-3) / 1e9
+    other_step = step_three if sched == "one_launch" else step_one
+    for i in range(5):
+        other_step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        other_step(i)
+    torch.cuda.synchronize()
+    other = {("single" if sched == "one_launch" else "one_launch"): round((time.perf_counter() - t0) * 1e3 / args.steps, 4)}
     result = {
         "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
@@ -921,15 +941,19 @@ def bench_allgather(args) -> dict:
         "config": {"workload": "C4 AllGather receive assembly: 128-rank group, 2 MiB bf16 shard per rank, one "
                                "descriptor naming all ranks, 128 received shards -> 256 MiB in rank order "
                                "(the 4 MiB pack is launch-latency bound)", "seed": seed, "buffer_sets": N_SETS,
-                   "schedule": "single", "streams": 1},
+                   "schedule": sched, "streams": 1},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "bytes_saved_vs_unicast": round(1.0 - int(st["multicast_bytes"]) / int(st["unicast_bytes"]), 4),
         "step_bytes": {"pack": pack_bytes, "unpack": unpack_bytes},
+        "ms_per_step_other_schedules": other,
         "kernel_us": {k: round(v, 2) for k, v in kern_us.items()},
         "copy_ceiling": copy_ceiling(torch, B, R * sbytes, dev),
-        "roofline": {"kernel": "k_gather_shards", "bound": "hbm", "achieved": round(achieved, 1),
+        "roofline": {"kernel": "k_allgather_step" if sched == "one_launch" else "k_gather_shards",
+                     "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": traffic_from_profile("k_gather_shards", "C4"), "bytes_per_launch": unpack_bytes,
+                     "traffic": traffic_from_profile("k_allgather_step" if sched == "one_launch"
+                                                     else "k_gather_shards", "C4"),
+                     "bytes_per_launch": launch_bytes,
                      "avg_launch_ms": round(g_avg, 4), "min_launch_ms": round(g_ms[0], 4),
                      "launches_timed": len(g_ms)},
     }

@@ -430,6 +430,19 @@ MW_API int32_t mw_unpack_allgather(mw_ctx *ctx, const void *const *peer_shards_d
                             void *out_dev, void *stream);
 
 /*
+ * mw_allgather_step: for a steady stream of AllGathers, one launch that does what
+ *     mw_unpack_allgather(ctx, peer_shards_dev, shard_bytes, out_dev),
+ *     mw_pack_allgather(ctx, shard_dev, shard_bytes, send_buf_dev) and
+ *     mw_plan_allgather(ctx, shard_bytes, desc_dev, stats_dev)
+ * do, with exactly their outputs: the shards received for one operation are assembled while
+ * this rank's shard of the next one is loaded into its send buffer (Section 5.2, steps 1 and
+ * 4) and its one-row plan is written.  Arguments and errors as for the three calls.
+ */
+MW_API int32_t mw_allgather_step(mw_ctx *ctx, const void *shard_dev, int64_t shard_bytes, void *send_buf_dev,
+                          mw_group_desc *desc_dev, mw_send_stats *stats_dev, const void *const *peer_shards_dev,
+                          void *out_dev, void *stream);
+
+/*
  * AllGather with a two-segment fragment (Section 5.2, modified workflow): each node splits
  * its fragment into a segment sent over the direct links by plain writes and a segment sent
  * once through the relay path as a MultiWrite; the ratio follows from the bandwidths of the

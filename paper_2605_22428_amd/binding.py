@@ -25,7 +25,7 @@ MW_FLAG_BAD_SRC_TOKEN, MW_FLAG_BAD_DESC, MW_FLAG_RECV_CAPACITY, MW_FLAG_DUP_SRC_
 EXPORTS = ["mw_workspace_bytes", "mw_ctx_create", "mw_ctx_destroy", "mw_plan", "mw_pack", "mw_plan_pack", "mw_pack_quantize",
            "mw_packet_header_bytes", "mw_pack_packets", "mw_unpack_packets",
            "mw_plan_allgather", "mw_pack_allgather", "mw_unpack", "mw_unpack_index", "mw_unpack_expand",
-           "mw_unpack_allgather", "mw_combine_gather", "mw_unpack_expand_index_next", "mw_unpack_expand_index_plan_next", "mw_ctx_set_ride_wait_limit", "mw_stream_step",
+           "mw_unpack_allgather", "mw_combine_gather", "mw_unpack_expand_index_next", "mw_unpack_expand_index_plan_next", "mw_ctx_set_ride_wait_limit", "mw_stream_step", "mw_allgather_step",
            "mw_sim_deliver", "mw_copy_bytes", "mw_get_send_stats", "mw_get_recv_stats",
            "mw_set_forwarding", "mw_relay", "mw_relay_packets", "mw_get_relay_stats",
            "mw_allgather_split_point", "mw_plan_allgather_split", "mw_unpack_allgather_split",
@@ -304,6 +304,11 @@ class Context:
     def mw_unpack_allgather(self, peer_shards: torch.Tensor, shard_bytes: int, out: torch.Tensor):
         _check(load().mw_unpack_allgather(self._h, _ptr(peer_shards), C.c_int64(shard_bytes), _ptr(out),
                                           _stream()), "mw_unpack_allgather")
+
+    def mw_allgather_step(self, shard: torch.Tensor, shard_bytes: int, send_buf: torch.Tensor, desc: torch.Tensor,
+                          stats: torch.Tensor, peer_shards: torch.Tensor, out: torch.Tensor):
+        _check(load().mw_allgather_step(self._h, _ptr(shard), C.c_int64(shard_bytes), _ptr(send_buf), _ptr(desc),
+                                        _ptr(stats), _ptr(peer_shards), _ptr(out), _stream()), "mw_allgather_step")
 
     # ---- relay ---------------------------------------------------------------------------
     def mw_set_forwarding(self, next_hop: np.ndarray, n_hops: int):

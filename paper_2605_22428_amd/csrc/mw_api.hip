@@ -550,6 +550,21 @@ MW_API int32_t mw_unpack_allgather(mw_ctx *ctx, const void *const *peer_shards_d
     return mw_launch_gather_shards(ctx, peer_shards_dev, shard_bytes, out_dev, (hipStream_t)stream);
 }
 
+MW_API int32_t mw_allgather_step(mw_ctx *ctx, const void *shard_dev, int64_t shard_bytes, void *send_buf_dev,
+                          mw_group_desc *desc_dev, mw_send_stats *stats_dev, const void *const *peer_shards_dev,
+                          void *out_dev, void *stream)
+{
+    if (!ctx || !desc_dev || !stats_dev || shard_bytes < 0) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
+    if (shard_bytes % 16 != 0) return MW_ERR_UNSUPPORTED;
+    if (shard_bytes > 0) {
+        if (!shard_dev || !send_buf_dev || !peer_shards_dev || !out_dev) return MW_ERR_INVALID_ARG;
+        if (((uintptr_t)shard_dev | (uintptr_t)send_buf_dev | (uintptr_t)out_dev) & 15u) return MW_ERR_INVALID_ARG;
+    }
+    return mw_launch_allgather_step(ctx, shard_dev, shard_bytes, send_buf_dev, desc_dev, stats_dev, peer_shards_dev,
+                                    out_dev, (hipStream_t)stream);
+}
+
 MW_API int32_t mw_sim_deliver(mw_ctx *ctx, const mw_group_desc *desc_dev, const mw_send_stats *stats_dev,
                        int32_t n_tokens, const void *packed_rows_dev, const int32_t *row_src_token_dev,
                        const int32_t *row_topk_dev, int32_t dst_rank, mw_group_desc *desc_out_dev,

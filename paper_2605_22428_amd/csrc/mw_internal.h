@@ -209,6 +209,9 @@ int32_t mw_launch_unpack_expand_index_next(mw_ctx *ctx, int32_t P, void *out_row
                                            int32_t *out_src_peer, int32_t *out_src_token, mw_ctx *next,
                                            const mw_recv_peer *next_peers, int32_t next_P, int64_t next_cap,
                                            int64_t *next_expert_offsets, mw_recv_stats *next_stats, hipStream_t s);
+int32_t mw_launch_allgather_step(mw_ctx *ctx, const void *own_shard, int64_t shard_bytes, void *send_buf,
+                                 mw_group_desc *desc, mw_send_stats *stats, const void *const *shards, void *out,
+                                 hipStream_t s);
 // the arguments of an mw_pack that rides in another launch (mw_stream_step)
 struct mw_pack_call {
     const void *x; const float *scales; const int32_t *topk; const int32_t *perm; const mw_send_stats *stats;

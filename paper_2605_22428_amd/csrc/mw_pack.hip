@@ -12,6 +12,7 @@
 // Nothing is reused, so accesses are non-temporal.
 #include "mw_internal.h"
 #include "mw_pack_dev.h"
+#include "mw_plan_dev.h"
 
 namespace {
 
@@ -157,6 +158,25 @@ __global__ __launch_bounds__(256) void k_gather_shards(const u32x4 *const *__res
     if (c < shard_chunks) mw_st16(dst + c, mw_ld16(src + c));
 }
 
+// A whole AllGather step of a stream of them in one launch (Section 5.2, steps 1 and 4, for two
+// consecutive operations): rows y < R of the grid assemble the shards received for one
+// operation, row R copies this rank's shard of the next one into its send buffer, and the first
+// workgroup of row R + 1 writes that operation's one-row plan.
+__global__ __launch_bounds__(256) void k_allgather_step(const u32x4 *const *__restrict__ shards,
+                                                        int64_t shard_chunks, u32x4 *__restrict__ out, int R,
+                                                        const u32x4 *__restrict__ own, u32x4 *__restrict__ send_buf,
+                                                        mw_group_desc *desc, mw_send_stats *stats)
+{
+    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if ((int)blockIdx.y < R) {
+        if (c < shard_chunks) mw_st16(out + (int64_t)blockIdx.y * shard_chunks + c, mw_ld16(shards[blockIdx.y] + c));
+    } else if ((int)blockIdx.y == R) {
+        if (c < shard_chunks) mw_st16(send_buf + c, mw_ld16(own + c));
+    } else if (blockIdx.x == 0) {
+        mw_plan_allgather_body(R, (uint64_t)shard_chunks * 16u, desc, stats);
+    }
+}
+
 // AllGather assembly of split fragments (Section 5.2): chunk c of shard p comes from the
 // direct piece while c < direct_chunks, else from the relayed piece.  blockIdx.y = p.
 __global__ __launch_bounds__(256) void k_gather_split(const u32x4 *const *__restrict__ direct,
@@ -275,6 +295,23 @@ int32_t mw_launch_gather_shards(mw_ctx *ctx, const void *const *shards, int64_t 
         mw_timed tm(ctx, MW_KERNEL_AG_GATHER, s);
         hipLaunchKernelGGL(k_gather_shards, dim3((uint32_t)gx, ctx->cfg.n_ranks), dim3(256), 0, s,
                            (const u32x4 *const *)shards, shard_chunks, (u32x4 *)out);
+    }
+    MW_HIP_CHECK(hipGetLastError());
+    return MW_OK;
+}
+
+int32_t mw_launch_allgather_step(mw_ctx *ctx, const void *own_shard, int64_t shard_bytes, void *send_buf,
+                                 mw_group_desc *desc, mw_send_stats *stats, const void *const *shards, void *out,
+                                 hipStream_t s)
+{
+    const int64_t shard_chunks = shard_bytes / 16;
+    const int64_t gx = shard_chunks > 0 ? (shard_chunks + 255) / 256 : 1;
+    if (gx > 0x7fffffffLL) return MW_ERR_UNSUPPORTED;
+    {
+        mw_timed tm(ctx, MW_KERNEL_AG_GATHER, s);
+        hipLaunchKernelGGL(k_allgather_step, dim3((uint32_t)gx, ctx->cfg.n_ranks + 2), dim3(256), 0, s,
+                           (const u32x4 *const *)shards, shard_chunks, (u32x4 *)out, ctx->cfg.n_ranks,
+                           (const u32x4 *)own_shard, (u32x4 *)send_buf, desc, stats);
     }
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;

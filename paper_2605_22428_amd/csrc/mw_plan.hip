@@ -194,22 +194,7 @@ __global__ __launch_bounds__(kBlock) void k_groups(const uint64_t *__restrict__ 
 __global__ __launch_bounds__(256) void k_plan_allgather(int R, uint64_t shard_bytes, mw_group_desc *desc,
                                                         mw_send_stats *stats)
 {
-    const int tid = threadIdx.x;
-    if (tid < MW_MAX_RANKS) stats->rows_per_dest[tid] = (tid < R) ? 1u : 0u;
-    if (tid == 0) {
-        mw_group_desc d;
-#pragma unroll
-        for (int w = 0; w < MW_MASK_WORDS; ++w) {
-            const int lo = w * 64;
-            d.mask[w] = (R >= lo + 64) ? ~0ull : (R > lo ? ((1ull << (R - lo)) - 1ull) : 0ull);
-        }
-        d.row_offset = 0; d.row_count = 1; d.n_dest = (uint32_t)R; d.reserved0 = 0;
-        *desc = d;
-        stats->n_rows = 1; stats->n_groups = 1;
-        stats->multicast_bytes = shard_bytes;
-        stats->unicast_bytes = shard_bytes * (uint64_t)R;
-        stats->error_flags = 0; stats->reserved0 = 0;
-    }
+    mw_plan_allgather_body(R, shard_bytes, desc, stats);
 }
 
 // Descriptor pair of a fragment split into a direct and a relayed segment (Section 5.2),

@@ -174,6 +174,29 @@ __device__ __forceinline__ void mw_rank_body(const int32_t *__restrict__ topk, i
 }
 
 
+// AllGather plan (Section 5.2): one row, one group, every rank a destination.  One workgroup
+// of at least MW_MAX_RANKS lanes.
+__device__ __forceinline__ void mw_plan_allgather_body(int R, uint64_t shard_bytes, mw_group_desc *desc,
+                                                       mw_send_stats *stats)
+{
+    const int tid = threadIdx.x;
+    if (tid < MW_MAX_RANKS) stats->rows_per_dest[tid] = (tid < R) ? 1u : 0u;
+    if (tid == 0) {
+        mw_group_desc d;
+#pragma unroll
+        for (int w = 0; w < MW_MASK_WORDS; ++w) {
+            const int lo = w * 64;
+            d.mask[w] = (R >= lo + 64) ? ~0ull : (R > lo ? ((1ull << (R - lo)) - 1ull) : 0ull);
+        }
+        d.row_offset = 0; d.row_count = 1; d.n_dest = (uint32_t)R; d.reserved0 = 0;
+        *desc = d;
+        stats->n_rows = 1; stats->n_groups = 1;
+        stats->multicast_bytes = shard_bytes;
+        stats->unicast_bytes = shard_bytes * (uint64_t)R;
+        stats->error_flags = 0; stats->reserved0 = 0;
+    }
+}
+
 // ---- the plan that rides along with another launch -------------------------------------
 // Everything the plan of one batch needs when it runs as extra workgroups of a launch that
 // does something else (one kernel argument).  The launch's workgroups `wg` = 0 .. n_rank - 1

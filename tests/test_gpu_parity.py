@@ -554,6 +554,18 @@ def test_allgather(w):
     ctx.mw_unpack_allgather(table, w.shard_bytes, out)
     torch.cuda.synchronize()
     H.assert_same_bytes(H.host(out).view(np.uint8), ref.unpack_allgather(shards), "gathered output")
+    # the same three as one launch (mw_allgather_step): the received shards of one operation are
+    # assembled while the shard of the next one (here: another rank's data) is loaded and planned
+    nxt = W.allgather_shard(w, W.BASE_SEED + 1, w.my_rank)
+    nxt_d, send2 = H.dev(nxt), torch.zeros_like(mine)
+    desc.zero_(); stats.zero_(); out.zero_()
+    ctx.mw_allgather_step(nxt_d, w.shard_bytes, send2, desc, stats, table, out)
+    torch.cuda.synchronize()
+    H.assert_same_bytes(H.host(out).view(np.uint8), ref.unpack_allgather(shards), "step: gathered output")
+    H.assert_same_bytes(H.host(send2), ref.pack_allgather(nxt).view(np.uint16), "step: send buffer")
+    H.assert_same_bytes(H.host(desc), od.view(np.uint8).reshape(-1), "step: desc")
+    H.assert_same_bytes(np.array([ctx.mw_get_send_stats(stats)]).view(np.uint8), np.array([ost]).view(np.uint8),
+                        "step: stats")
     ctx.close()
 
 
