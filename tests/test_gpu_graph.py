@@ -128,3 +128,53 @@ def test_captured_step_replays(fused):
             torch.cuda.synchronize()
             _check_send_buffers(w, sb, ctx, tk, x, None)
     ctx.close()
+
+
+def test_captured_allgather_step_replays():
+    """mw_allgather_step in a graph: three replays, the shard to send and the shards received
+    replaced before each, an eager AllGather plan of another size on the same context in between."""
+    w = W.AllGatherWorkload("ag_graph", 43, 8, 3000 * 8)
+    _say("graph replay allgather step", w.shard_bytes)
+    ctx = B.Context(w.n_ranks, 0, 1, w.my_rank, 0, B.MW_ROW_BYTES, 1, 0, None, row_bytes=w.shard_bytes,
+                    device=H.DEV)
+    own = torch.zeros(w.shard_elems, dtype=torch.int16, device=H.DEV)
+    send = torch.zeros_like(own)
+    recv = [torch.zeros_like(own) for _ in range(w.n_ranks)]
+    table = torch.tensor([t.data_ptr() for t in recv], dtype=torch.int64, device=H.DEV)
+    out = torch.zeros(w.n_ranks * w.shard_elems, dtype=torch.int16, device=H.DEV)
+    desc = torch.zeros(B.DESC_BYTES, dtype=torch.uint8, device=H.DEV)
+    stats = torch.zeros(B.SEND_STATS_BYTES, dtype=torch.uint8, device=H.DEV)
+    d2, s2 = torch.zeros_like(desc), torch.zeros_like(stats)
+
+    def step():
+        ctx.mw_allgather_step(own, w.shard_bytes, send, desc, stats, table, out)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    torch.cuda.synchronize()
+    od, ost = ref.plan_allgather(w.n_ranks, w.shard_bytes)
+    for rep in range(3):
+        shards = [W.allgather_shard(w, 20 + rep, r) for r in range(w.n_ranks)]
+        mine = W.allgather_shard(w, 30 + rep, w.my_rank)
+        for t, a in zip(recv, shards):
+            t.copy_(H.dev(a).view(torch.int16))
+        own.copy_(H.dev(mine).view(torch.int16))
+        ctx.mw_plan_allgather(4096, d2, s2)
+        _clear(send, out, desc, stats)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        _say("  replay", rep)
+        H.assert_same_bytes(H.host(out).view(np.uint8), ref.unpack_allgather(shards), "replay: gathered output")
+        H.assert_same_bytes(H.host(send), ref.pack_allgather(mine).view(np.uint16), "replay: send buffer")
+        H.assert_same_bytes(H.host(desc), od.view(np.uint8).reshape(-1), "replay: desc")
+        H.assert_same_bytes(np.array([ctx.mw_get_send_stats(stats)]).view(np.uint8),
+                            np.array([ost]).view(np.uint8), "replay: stats")
+    ctx.close()

@@ -566,6 +566,25 @@ def test_allgather(w):
     H.assert_same_bytes(H.host(desc), od.view(np.uint8).reshape(-1), "step: desc")
     H.assert_same_bytes(np.array([ctx.mw_get_send_stats(stats)]).view(np.uint8), np.array([ost]).view(np.uint8),
                         "step: stats")
+    # an empty shard: nothing moves, the plan is the oracle's plan of zero bytes
+    desc.zero_(); stats.zero_()
+    before = H.host(out).copy()
+    ctx.mw_allgather_step(None, 0, None, desc, stats, None, None)
+    torch.cuda.synchronize()
+    od0, ost0 = ref.plan_allgather(w.n_ranks, 0)
+    H.assert_same_bytes(H.host(desc), od0.view(np.uint8).reshape(-1), "step, empty shard: desc")
+    H.assert_same_bytes(np.array([ctx.mw_get_send_stats(stats)]).view(np.uint8), np.array([ost0]).view(np.uint8),
+                        "step, empty shard: stats")
+    H.assert_same_bytes(H.host(out), before, "step, empty shard: output untouched")
+    # argument errors are returned, nothing is launched
+    for args, want in [((nxt_d, w.shard_bytes - 8, send2, desc, stats, table, out), B.MW_ERR_UNSUPPORTED),
+                       ((nxt_d, -16, send2, desc, stats, table, out), B.MW_ERR_INVALID_ARG),
+                       ((None, w.shard_bytes, send2, desc, stats, table, out), B.MW_ERR_INVALID_ARG),
+                       ((nxt_d, w.shard_bytes, send2, desc, stats, None, out), B.MW_ERR_INVALID_ARG),
+                       ((nxt_d, w.shard_bytes, send2, None, stats, table, out), B.MW_ERR_INVALID_ARG)]:
+        with pytest.raises(B.MwError) as ei:
+            ctx.mw_allgather_step(*args)
+        assert ei.value.status == want
     ctx.close()
 
 
