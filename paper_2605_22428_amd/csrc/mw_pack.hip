@@ -140,21 +140,25 @@ __global__ __launch_bounds__(1024) void k_pack_quant(const u32x4 *__restrict__ x
     }
 }
 
+// Lanes per workgroup of the flat copies below: single waves (a plain copy of several hundred
+// megabytes runs about 2 % faster with 64-lane workgroups than with 256-lane ones).
+constexpr int kFlat = 64;
+
 // Flat streaming copy, one chunk per lane.
-__global__ __launch_bounds__(256) void k_copy(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
+__global__ __launch_bounds__(kFlat) void k_copy(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
                                               int64_t n_chunks)
 {
-    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t c = (int64_t)blockIdx.x * kFlat + threadIdx.x;
     if (c < n_chunks) mw_st16(dst + c, mw_ld16(src + c));
 }
 
 // AllGather receive assembly: shard p goes to out + p * shard_bytes.  blockIdx.y = p.
-__global__ __launch_bounds__(256) void k_gather_shards(const u32x4 *const *__restrict__ shards,
+__global__ __launch_bounds__(kFlat) void k_gather_shards(const u32x4 *const *__restrict__ shards,
                                                        int64_t shard_chunks, u32x4 *__restrict__ out)
 {
     const u32x4 *src = shards[blockIdx.y];
     u32x4 *dst = out + (int64_t)blockIdx.y * shard_chunks;
-    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t c = (int64_t)blockIdx.x * kFlat + threadIdx.x;
     if (c < shard_chunks) mw_st16(dst + c, mw_ld16(src + c));
 }
 
@@ -162,12 +166,12 @@ __global__ __launch_bounds__(256) void k_gather_shards(const u32x4 *const *__res
 // consecutive operations): rows y < R of the grid assemble the shards received for one
 // operation, row R copies this rank's shard of the next one into its send buffer, and the first
 // workgroup of row R + 1 writes that operation's one-row plan.
-__global__ __launch_bounds__(256) void k_allgather_step(const u32x4 *const *__restrict__ shards,
+__global__ __launch_bounds__(kFlat) void k_allgather_step(const u32x4 *const *__restrict__ shards,
                                                         int64_t shard_chunks, u32x4 *__restrict__ out, int R,
                                                         const u32x4 *__restrict__ own, u32x4 *__restrict__ send_buf,
                                                         mw_group_desc *desc, mw_send_stats *stats)
 {
-    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t c = (int64_t)blockIdx.x * kFlat + threadIdx.x;
     if ((int)blockIdx.y < R) {
         if (c < shard_chunks) mw_st16(out + (int64_t)blockIdx.y * shard_chunks + c, mw_ld16(shards[blockIdx.y] + c));
     } else if ((int)blockIdx.y == R) {
@@ -179,12 +183,12 @@ __global__ __launch_bounds__(256) void k_allgather_step(const u32x4 *const *__re
 
 // AllGather assembly of split fragments (Section 5.2): chunk c of shard p comes from the
 // direct piece while c < direct_chunks, else from the relayed piece.  blockIdx.y = p.
-__global__ __launch_bounds__(256) void k_gather_split(const u32x4 *const *__restrict__ direct,
+__global__ __launch_bounds__(kFlat) void k_gather_split(const u32x4 *const *__restrict__ direct,
                                                       const u32x4 *const *__restrict__ relayed,
                                                       int64_t shard_chunks, int64_t direct_chunks,
                                                       u32x4 *__restrict__ out)
 {
-    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t c = (int64_t)blockIdx.x * kFlat + threadIdx.x;
     if (c >= shard_chunks) return;
     const u32x4 *src = (c < direct_chunks) ? direct[blockIdx.y] + c : relayed[blockIdx.y] + (c - direct_chunks);
     mw_st16(out + (int64_t)blockIdx.y * shard_chunks + c, mw_ld16(src));
@@ -197,11 +201,11 @@ int32_t mw_launch_gather_split(mw_ctx *ctx, const void *const *direct, const voi
 {
     const int64_t shard_chunks = shard_bytes / 16;
     if (shard_chunks == 0) return MW_OK;
-    const int64_t gx = (shard_chunks + 255) / 256;
+    const int64_t gx = (shard_chunks + kFlat - 1) / kFlat;
     if (gx > 0x7fffffffLL) return MW_ERR_UNSUPPORTED;
     {
         mw_timed tm(ctx, MW_KERNEL_AG_GATHER, s);
-        hipLaunchKernelGGL(k_gather_split, dim3((uint32_t)gx, ctx->cfg.n_ranks), dim3(256), 0, s,
+        hipLaunchKernelGGL(k_gather_split, dim3((uint32_t)gx, ctx->cfg.n_ranks), dim3(kFlat), 0, s,
                            (const u32x4 *const *)direct, (const u32x4 *const *)relayed, shard_chunks, direct_bytes / 16,
                            (u32x4 *)out);
     }
@@ -272,13 +276,13 @@ int32_t mw_launch_copy(mw_ctx *ctx, void *dst, const void *src, int64_t n_bytes,
 {
     const int64_t n_chunks = n_bytes / 16;
     if (n_chunks == 0) return MW_OK;
-    const int64_t grid = (n_chunks + 255) / 256;
+    const int64_t grid = (n_chunks + kFlat - 1) / kFlat;
     if (grid > 0x7fffffffLL) return MW_ERR_UNSUPPORTED;
     if (ctx) {
         mw_timed tm(ctx, MW_KERNEL_AG_PACK, s);
-        hipLaunchKernelGGL(k_copy, dim3((uint32_t)grid), dim3(256), 0, s, (const u32x4 *)src, (u32x4 *)dst, n_chunks);
+        hipLaunchKernelGGL(k_copy, dim3((uint32_t)grid), dim3(kFlat), 0, s, (const u32x4 *)src, (u32x4 *)dst, n_chunks);
     } else {
-        hipLaunchKernelGGL(k_copy, dim3((uint32_t)grid), dim3(256), 0, s, (const u32x4 *)src, (u32x4 *)dst, n_chunks);
+        hipLaunchKernelGGL(k_copy, dim3((uint32_t)grid), dim3(kFlat), 0, s, (const u32x4 *)src, (u32x4 *)dst, n_chunks);
     }
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;
@@ -289,11 +293,11 @@ int32_t mw_launch_gather_shards(mw_ctx *ctx, const void *const *shards, int64_t 
 {
     const int64_t shard_chunks = shard_bytes / 16;
     if (shard_chunks == 0) return MW_OK;
-    const int64_t gx = (shard_chunks + 255) / 256;
+    const int64_t gx = (shard_chunks + kFlat - 1) / kFlat;
     if (gx > 0x7fffffffLL) return MW_ERR_UNSUPPORTED;
     {
         mw_timed tm(ctx, MW_KERNEL_AG_GATHER, s);
-        hipLaunchKernelGGL(k_gather_shards, dim3((uint32_t)gx, ctx->cfg.n_ranks), dim3(256), 0, s,
+        hipLaunchKernelGGL(k_gather_shards, dim3((uint32_t)gx, ctx->cfg.n_ranks), dim3(kFlat), 0, s,
                            (const u32x4 *const *)shards, shard_chunks, (u32x4 *)out);
     }
     MW_HIP_CHECK(hipGetLastError());
@@ -305,11 +309,11 @@ int32_t mw_launch_allgather_step(mw_ctx *ctx, const void *own_shard, int64_t sha
                                  hipStream_t s)
 {
     const int64_t shard_chunks = shard_bytes / 16;
-    const int64_t gx = shard_chunks > 0 ? (shard_chunks + 255) / 256 : 1;
+    const int64_t gx = shard_chunks > 0 ? (shard_chunks + kFlat - 1) / kFlat : 1;
     if (gx > 0x7fffffffLL) return MW_ERR_UNSUPPORTED;
     {
         mw_timed tm(ctx, MW_KERNEL_AG_GATHER, s);
-        hipLaunchKernelGGL(k_allgather_step, dim3((uint32_t)gx, ctx->cfg.n_ranks + 2), dim3(256), 0, s,
+        hipLaunchKernelGGL(k_allgather_step, dim3((uint32_t)gx, ctx->cfg.n_ranks + 2), dim3(kFlat), 0, s,
                            (const u32x4 *const *)shards, shard_chunks, (u32x4 *)out, ctx->cfg.n_ranks,
                            (const u32x4 *)own_shard, (u32x4 *)send_buf, desc, stats);
     }

@@ -175,12 +175,12 @@ __device__ __forceinline__ void mw_rank_body(const int32_t *__restrict__ topk, i
 
 
 // AllGather plan (Section 5.2): one row, one group, every rank a destination.  One workgroup
-// of at least MW_MAX_RANKS lanes.
+// of any size.
 __device__ __forceinline__ void mw_plan_allgather_body(int R, uint64_t shard_bytes, mw_group_desc *desc,
                                                        mw_send_stats *stats)
 {
     const int tid = threadIdx.x;
-    if (tid < MW_MAX_RANKS) stats->rows_per_dest[tid] = (tid < R) ? 1u : 0u;
+    for (int r = tid; r < MW_MAX_RANKS; r += (int)blockDim.x) stats->rows_per_dest[r] = (r < R) ? 1u : 0u;
     if (tid == 0) {
         mw_group_desc d;
 #pragma unroll
