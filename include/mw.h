@@ -574,6 +574,31 @@ MW_API int32_t mw_relay(mw_ctx *ctx, const mw_recv_peer *in_dev, const mw_relay_
                  int64_t child_capacity_rows, mw_relay_stats *stats_dev, void *stream);
 
 /*
+ * mw_relay as its two halves, for a node that relays one buffer after the other (Section 4.3.3;
+ * Section 5.1, relay module).  mw_relay_index builds the children's descriptor tables, the
+ * statistics except forward_bytes and error_flags, and -- in the context's workspace -- what
+ * the copy needs; mw_relay_copy moves the rows and completes the statistics.  mw_relay is
+ * mw_relay_index followed by mw_relay_copy with the same arguments.
+ * mw_relay_copy_index_next is mw_relay_copy(ctx, in_dev, children_dev, stats_dev) and
+ * mw_relay_index(next_ctx, next_in_dev, next_children_dev, next_child_capacity_rows,
+ * next_stats_dev) in ONE launch, with identical results: the index of the next buffer is a
+ * chain of memory round trips that moves almost nothing and runs beside the copy of this one.
+ * `next_ctx` is another context on the same device (its workspace holds the next index),
+ * with its own forwarding table; the two steps' children and statistics must not overlap.
+ * A stream of buffers alternates between two contexts:
+ *   mw_relay_index(A, buf0); mw_relay_copy_index_next(A, buf0, B, buf1);
+ *   mw_relay_copy_index_next(B, buf1, A, buf2); ... ; mw_relay_copy(last).
+ */
+MW_API int32_t mw_relay_index(mw_ctx *ctx, const mw_recv_peer *in_dev, const mw_relay_child *children_dev,
+                       int64_t child_capacity_rows, mw_relay_stats *stats_dev, void *stream);
+MW_API int32_t mw_relay_copy(mw_ctx *ctx, const mw_recv_peer *in_dev, const mw_relay_child *children_dev,
+                      mw_relay_stats *stats_dev, void *stream);
+MW_API int32_t mw_relay_copy_index_next(mw_ctx *ctx, const mw_recv_peer *in_dev, const mw_relay_child *children_dev,
+                                 mw_relay_stats *stats_dev, mw_ctx *next_ctx, const mw_recv_peer *next_in_dev,
+                                 const mw_relay_child *next_children_dev, int64_t next_child_capacity_rows,
+                                 mw_relay_stats *next_stats_dev, void *stream);
+
+/*
  * mw_relay_packets: the relay step for packets -- the paper's own form of it (Section 4.1,
  * "Replication and forwarding": the relay parses the bitmap in front of the payload, makes one
  * copy per distinct egress port and updates the in-packet metadata of each copy so that

@@ -641,6 +641,42 @@ MW_API int32_t mw_relay(mw_ctx *ctx, const mw_recv_peer *in_dev, const mw_relay_
     return mw_launch_relay(ctx, in_dev, children_dev, child_capacity_rows, stats_dev, (hipStream_t)stream);
 }
 
+MW_API int32_t mw_relay_index(mw_ctx *ctx, const mw_recv_peer *in_dev, const mw_relay_child *children_dev,
+                       int64_t child_capacity_rows, mw_relay_stats *stats_dev, void *stream)
+{
+    if (!ctx || !in_dev || !children_dev || !stats_dev || child_capacity_rows < 0) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
+    if (ctx->cfg.max_hops < 1 || ctx->n_hops < 1) return MW_ERR_INVALID_ARG;      // no forwarding table
+    if (child_capacity_rows > 0x7fffffffLL) return MW_ERR_UNSUPPORTED;
+    return mw_launch_relay_index(ctx, in_dev, children_dev, child_capacity_rows, stats_dev, (hipStream_t)stream);
+}
+
+MW_API int32_t mw_relay_copy(mw_ctx *ctx, const mw_recv_peer *in_dev, const mw_relay_child *children_dev,
+                      mw_relay_stats *stats_dev, void *stream)
+{
+    if (!ctx || !in_dev || !children_dev || !stats_dev) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
+    if (ctx->cfg.max_hops < 1 || ctx->n_hops < 1) return MW_ERR_INVALID_ARG;
+    return mw_launch_relay_copy(ctx, in_dev, children_dev, stats_dev, nullptr, nullptr, nullptr, 0, nullptr,
+                                (hipStream_t)stream);
+}
+
+MW_API int32_t mw_relay_copy_index_next(mw_ctx *ctx, const mw_recv_peer *in_dev, const mw_relay_child *children_dev,
+                                 mw_relay_stats *stats_dev, mw_ctx *next_ctx, const mw_recv_peer *next_in_dev,
+                                 const mw_relay_child *next_children_dev, int64_t next_child_capacity_rows,
+                                 mw_relay_stats *next_stats_dev, void *stream)
+{
+    if (!ctx || !in_dev || !children_dev || !stats_dev) return MW_ERR_INVALID_ARG;
+    if (!next_ctx || next_ctx == ctx || next_ctx->device != ctx->device) return MW_ERR_INVALID_ARG;
+    if (!next_in_dev || !next_children_dev || !next_stats_dev || next_child_capacity_rows < 0) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
+    if (ctx->cfg.max_hops < 1 || ctx->n_hops < 1 || next_ctx->cfg.max_hops < 1 || next_ctx->n_hops < 1)
+        return MW_ERR_INVALID_ARG;
+    if (next_child_capacity_rows > 0x7fffffffLL) return MW_ERR_UNSUPPORTED;
+    return mw_launch_relay_copy(ctx, in_dev, children_dev, stats_dev, next_ctx, next_in_dev, next_children_dev,
+                                next_child_capacity_rows, next_stats_dev, (hipStream_t)stream);
+}
+
 MW_API int32_t mw_relay_packets(mw_ctx *ctx, const mw_recv_packets *in_dev, void *const *children_dev,
                          int64_t child_capacity_rows, mw_relay_stats *stats_dev, void *stream)
 {

@@ -236,6 +236,12 @@ int32_t mw_launch_gather_shards(mw_ctx *ctx, const void *const *shards, int64_t 
                                 hipStream_t s);
 int32_t mw_launch_relay(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay_child *children, int64_t cap,
                         mw_relay_stats *stats, hipStream_t s);
+int32_t mw_launch_relay_index(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay_child *children, int64_t cap,
+                              mw_relay_stats *stats, hipStream_t s);
+int32_t mw_launch_relay_copy(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay_child *children,
+                             mw_relay_stats *stats, mw_ctx *next, const mw_recv_peer *next_in,
+                             const mw_relay_child *next_children, int64_t next_cap, mw_relay_stats *next_stats,
+                             hipStream_t s);
 int32_t mw_launch_relay_packets(mw_ctx *ctx, const mw_recv_packets *in, void *const *children, int64_t cap,
                                 mw_relay_stats *stats, hipStream_t s);
 int32_t mw_launch_sim_deliver(mw_ctx *ctx, const mw_group_desc *desc, const mw_send_stats *stats,

@@ -48,12 +48,22 @@ __device__ __forceinline__ grp_view load_group(const mw_group_desc *desc, uint32
     return v;
 }
 
-__global__ __launch_bounds__(kBlock) void k_relay_index(
+// Everything the index of one relay step needs (one kernel argument).
+struct mw_relay_index_args {
+    const mw_recv_peer *in; const mw_relay_child *children; int n_hops, n_ranks;
+    uint32_t max_tokens, cap; uint64_t row_bytes; const uint64_t *hop_bits;
+    int32_t *group_of_row; uint32_t *child_pos; uint32_t *relay_flags; mw_relay_stats *stats;
+};
+
+// Workgroup `wg` of the relay index: wg < n_hops builds child wg's descriptor table, wg == n_hops
+// maps rows to groups and does the accounting.  Any workgroup size that is a multiple of 64.
+__device__ __forceinline__ void relay_index_body(
     const mw_recv_peer *__restrict__ in, const mw_relay_child *__restrict__ children, int n_hops, int n_ranks,
     uint32_t max_tokens, uint32_t cap, uint64_t row_bytes, const uint64_t *__restrict__ hop_bits,
     int32_t *__restrict__ group_of_row, uint32_t *__restrict__ child_pos, uint32_t *relay_flags,
-    mw_relay_stats *__restrict__ stats)
+    mw_relay_stats *__restrict__ stats, const int wg)
 {
+    const uint32_t bs = blockDim.x;
     __shared__ uint32_t scratch[17];
     __shared__ uint32_t fit[2];                  // groups, rows of the child that fit its capacity
     __shared__ unsigned long long acc[2];        // rows taken, rows * destinations
@@ -64,9 +74,9 @@ __global__ __launch_bounds__(kBlock) void k_relay_index(
     const uint32_t G = min(src.n_desc, max_tokens), n_rows = min(src.n_rows, max_tokens);
     uint32_t err = (src.n_desc > max_tokens || src.n_rows > max_tokens) ? MW_FLAG_BAD_DESC : 0u;
 
-    if ((int)blockIdx.x < n_hops) {
+    if (wg < n_hops) {
         // ---- child descriptor table of next hop h
-        const int h = blockIdx.x;
+        const int h = wg;
         uint64_t hb[MW_MASK_WORDS];
 #pragma unroll
         for (int w = 0; w < MW_MASK_WORDS; ++w) hb[w] = hop_bits[(size_t)h * MW_MASK_WORDS + w];
@@ -75,10 +85,10 @@ __global__ __launch_bounds__(kBlock) void k_relay_index(
         mw_lds_barrier();
         uint32_t carry_g = 0, carry_r = 0;
         grp_view nxt = load_group(src.desc, tid, G, n_rows);
-        for (uint32_t g0 = 0; g0 < G; g0 += kBlock) {
+        for (uint32_t g0 = 0; g0 < G; g0 += bs) {
             const uint32_t g = g0 + tid;
             const grp_view v = nxt;
-            nxt = load_group(src.desc, g + kBlock, G, n_rows);     // in flight during the scans
+            nxt = load_group(src.desc, g + bs, G, n_rows);         // in flight during the scans
             uint64_t sub[MW_MASK_WORDS];
             uint32_t nd = 0;
 #pragma unroll
@@ -134,7 +144,7 @@ __global__ __launch_bounds__(kBlock) void k_relay_index(
         }
         unsigned long long rows_in = 0, dest_rows = 0;
         uint32_t groups_in = 0;
-        for (uint32_t g = tid; g < G; g += kBlock) {
+        for (uint32_t g = tid; g < G; g += bs) {
             const grp_view v = load_group(src.desc, g, G, n_rows);
             if (!v.valid) { err |= MW_FLAG_BAD_DESC; continue; }
             uint32_t nd = 0;
@@ -157,7 +167,7 @@ __global__ __launch_bounds__(kBlock) void k_relay_index(
         for (uint32_t q = 0; q < n_long; ++q) {
             const uint32_t g = long_groups[q];
             const uint32_t off = src.desc[g].row_offset, cnt = src.desc[g].row_count;
-            for (uint32_t r = tid; r < cnt; r += kBlock) group_of_row[off + r] = (int32_t)g;
+            for (uint32_t r = tid; r < cnt; r += bs) group_of_row[off + r] = (int32_t)g;
         }
         if (tid == 0) {
             stats->n_groups_in = tot_groups;
@@ -165,22 +175,29 @@ __global__ __launch_bounds__(kBlock) void k_relay_index(
             stats->unicast_bytes = (uint64_t)acc[1] * row_bytes;
             stats->reserved0 = 0;
         }
-        for (int h = n_hops + tid; h < MW_MAX_HOPS; h += kBlock) { stats->groups_per_hop[h] = 0; stats->rows_per_hop[h] = 0; }
+        for (int h = n_hops + (int)tid; h < MW_MAX_HOPS; h += (int)bs) { stats->groups_per_hop[h] = 0; stats->rows_per_hop[h] = 0; }
     }
     if (err) atomicOr(relay_flags, err);
 }
 
-// blockIdx.x selects a segment of blockDim.x chunks of a row, blockIdx.y walks input rows.
-__global__ __launch_bounds__(1024) void k_relay_copy(
+__global__ __launch_bounds__(kBlock) void k_relay_index(const mw_relay_index_args a)
+{
+    relay_index_body(a.in, a.children, a.n_hops, a.n_ranks, a.max_tokens, a.cap, a.row_bytes, a.hop_bits,
+                     a.group_of_row, a.child_pos, a.relay_flags, a.stats, (int)blockIdx.x);
+}
+
+// blockIdx.x selects a segment of blockDim.x chunks of a row; rows i_first, i_first + i_stride, ...
+__device__ __forceinline__ void relay_copy_body(
     const mw_recv_peer *__restrict__ in, const mw_relay_child *__restrict__ children, int n_hops, int K, int n_chunks,
     int ns, uint32_t max_tokens, uint64_t row_bytes, const int32_t *__restrict__ group_of_row,
-    const uint32_t *__restrict__ child_pos, uint32_t *relay_flags, mw_relay_stats *__restrict__ stats)
+    const uint32_t *__restrict__ child_pos, uint32_t *relay_flags, mw_relay_stats *__restrict__ stats,
+    const uint32_t i_first, const uint32_t i_stride)
 {
     const mw_recv_peer src = in[0];
     const uint32_t n_rows = min(src.n_rows, max_tokens), n_desc = min(src.n_desc, max_tokens);
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
     const int lane = threadIdx.x & 63;
-    for (uint32_t i = blockIdx.y; i < n_rows; i += gridDim.y) {
+    for (uint32_t i = i_first; i < n_rows; i += i_stride) {
         // the payload's address depends on the row alone: requested first, the group lookups
         // (two dependent round trips) are in flight beside it
         u32x4 v = {0u, 0u, 0u, 0u};
@@ -206,13 +223,46 @@ __global__ __launch_bounds__(1024) void k_relay_copy(
             }
         }
     }
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+    if (blockIdx.x == 0 && i_first == 0 && threadIdx.x == 0) {
         unsigned long long rows_out = 0;
         for (int h = 0; h < n_hops; ++h) rows_out += stats->rows_per_hop[h];
         stats->forward_bytes = rows_out * row_bytes;
         stats->error_flags = __hip_atomic_load(relay_flags, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(relay_flags, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next relay
     }
+}
+
+__global__ __launch_bounds__(1024) void k_relay_copy(
+    const mw_recv_peer *__restrict__ in, const mw_relay_child *__restrict__ children, int n_hops, int K, int n_chunks,
+    int ns, uint32_t max_tokens, uint64_t row_bytes, const int32_t *__restrict__ group_of_row,
+    const uint32_t *__restrict__ child_pos, uint32_t *relay_flags, mw_relay_stats *__restrict__ stats)
+{
+    relay_copy_body(in, children, n_hops, K, n_chunks, ns, max_tokens, row_bytes, group_of_row, child_pos, relay_flags,
+                    stats, blockIdx.y, gridDim.y);
+}
+
+// A stream of relay steps on one stream (Section 4.3.3; the relay module of Section 5.1 handles
+// one buffer after the other): the copy of this step's buffer and, in the first next.n_hops + 1
+// workgroup rows of the grid, the index of the NEXT step's buffer, written to another context's
+// workspace.  The index is a chain of memory round trips that moves almost nothing; as a launch
+// of its own it costs about 15 us in front of every copy.  Held to 64 registers so that the copy
+// keeps every wave slot.
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_relay_copy_index_next(
+    const mw_recv_peer *__restrict__ in, const mw_relay_child *__restrict__ children, int n_hops, int K, int n_chunks,
+    int ns, uint32_t max_tokens, uint64_t row_bytes, const int32_t *__restrict__ group_of_row,
+    const uint32_t *__restrict__ child_pos, uint32_t *relay_flags, mw_relay_stats *__restrict__ stats,
+    const mw_relay_index_args next)
+{
+    const uint32_t n_index = (uint32_t)next.n_hops + 1u;
+    if (blockIdx.y < n_index) {
+        if (blockIdx.x == 0)
+            relay_index_body(next.in, next.children, next.n_hops, next.n_ranks, next.max_tokens, next.cap, next.row_bytes,
+                             next.hop_bits, next.group_of_row, next.child_pos, next.relay_flags, next.stats,
+                             (int)blockIdx.y);
+        return;
+    }
+    relay_copy_body(in, children, n_hops, K, n_chunks, ns, max_tokens, row_bytes, group_of_row, child_pos, relay_flags,
+                    stats, blockIdx.y - n_index, gridDim.y - n_index);
 }
 
 // ---- the same step for packets (Section 4.1, "Replication and forwarding": the relay parses the
@@ -354,29 +404,66 @@ __global__ __launch_bounds__(1024) void k_relay_packets_copy(
 
 }  // namespace
 
-int32_t mw_launch_relay(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay_child *children, int64_t cap,
-                        mw_relay_stats *stats, hipStream_t s)
+static mw_relay_index_args relay_index_args(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay_child *children,
+                                            int64_t cap, mw_relay_stats *stats)
 {
-    const mw_config &c = ctx->cfg;
-    const int n_chunks = (int)(ctx->row_bytes / 16);
+    mw_relay_index_args a;
+    a.in = in; a.children = children; a.n_hops = ctx->n_hops; a.n_ranks = ctx->cfg.n_ranks;
+    a.max_tokens = (uint32_t)ctx->cfg.max_tokens; a.cap = (uint32_t)cap; a.row_bytes = (uint64_t)ctx->row_bytes;
+    a.hop_bits = ctx->d_hop_bits; a.group_of_row = ctx->d_group_of_row; a.child_pos = ctx->d_child_pos;
+    a.relay_flags = ctx->d_relay_flags; a.stats = stats;
+    return a;
+}
+
+int32_t mw_launch_relay_index(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay_child *children, int64_t cap,
+                              mw_relay_stats *stats, hipStream_t s)
+{
     {
         mw_timed tm(ctx, MW_KERNEL_RELAY_INDEX, s);
-        hipLaunchKernelGGL(k_relay_index, dim3(ctx->n_hops + 1), dim3(kBlock), 0, s, in, children, ctx->n_hops,
-                           c.n_ranks, (uint32_t)c.max_tokens, (uint32_t)cap, (uint64_t)ctx->row_bytes,
-                           ctx->d_hop_bits, ctx->d_group_of_row, ctx->d_child_pos, ctx->d_relay_flags, stats);
-    }
-    {
-        const mw_row_shape shape = mw_row_shape_of(n_chunks);
-        uint32_t gy = (uint32_t)c.max_tokens < kRowGridMax ? (uint32_t)c.max_tokens : kRowGridMax;
-        if (gy < 1) gy = 1;
-        mw_timed tm(ctx, MW_KERNEL_RELAY_COPY, s);
-        hipLaunchKernelGGL(k_relay_copy, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, in, children, ctx->n_hops, c.top_k, n_chunks,
-                           (int)(ctx->row_stride / 16),
-                           (uint32_t)c.max_tokens, (uint64_t)ctx->row_bytes, ctx->d_group_of_row, ctx->d_child_pos,
-                           ctx->d_relay_flags, stats);
+        hipLaunchKernelGGL(k_relay_index, dim3(ctx->n_hops + 1), dim3(kBlock), 0, s,
+                           relay_index_args(ctx, in, children, cap, stats));
     }
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;
+}
+
+// `next` != nullptr: the index of the next step's buffer rides in the same launch.
+int32_t mw_launch_relay_copy(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay_child *children,
+                             mw_relay_stats *stats, mw_ctx *next, const mw_recv_peer *next_in,
+                             const mw_relay_child *next_children, int64_t next_cap, mw_relay_stats *next_stats,
+                             hipStream_t s)
+{
+    const mw_config &c = ctx->cfg;
+    const int n_chunks = (int)(ctx->row_bytes / 16);
+    mw_row_shape shape = mw_row_shape_of(n_chunks);
+    uint32_t gy = (uint32_t)c.max_tokens < kRowGridMax ? (uint32_t)c.max_tokens : kRowGridMax;
+    if (gy < 1) gy = 1;
+    {
+        mw_timed tm(ctx, MW_KERNEL_RELAY_COPY, s);
+        if (!next) {
+            hipLaunchKernelGGL(k_relay_copy, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, in, children, ctx->n_hops,
+                               c.top_k, n_chunks, (int)(ctx->row_stride / 16), (uint32_t)c.max_tokens,
+                               (uint64_t)ctx->row_bytes, ctx->d_group_of_row, ctx->d_child_pos, ctx->d_relay_flags, stats);
+        } else {
+            // the index keeps 8 KiB of LDS per workgroup: two waves each, so that a CU still holds 32
+            if (shape.bs == 64 && n_chunks % 16 == 0) { shape.bs = 128; shape.nseg = n_chunks / 128 + (n_chunks % 128 ? 1 : 0); }
+            hipLaunchKernelGGL(k_relay_copy_index_next, dim3(shape.nseg, gy + (uint32_t)next->n_hops + 1u),
+                               dim3(shape.bs), 0, s, in, children, ctx->n_hops, c.top_k, n_chunks,
+                               (int)(ctx->row_stride / 16), (uint32_t)c.max_tokens, (uint64_t)ctx->row_bytes,
+                               ctx->d_group_of_row, ctx->d_child_pos, ctx->d_relay_flags, stats,
+                               relay_index_args(next, next_in, next_children, next_cap, next_stats));
+        }
+    }
+    MW_HIP_CHECK(hipGetLastError());
+    return MW_OK;
+}
+
+int32_t mw_launch_relay(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay_child *children, int64_t cap,
+                        mw_relay_stats *stats, hipStream_t s)
+{
+    const int32_t rc = mw_launch_relay_index(ctx, in, children, cap, stats, s);
+    if (rc != MW_OK) return rc;
+    return mw_launch_relay_copy(ctx, in, children, stats, nullptr, nullptr, nullptr, 0, nullptr, s);
 }
 
 int32_t mw_launch_relay_packets(mw_ctx *ctx, const mw_recv_packets *in, void *const *children, int64_t cap,

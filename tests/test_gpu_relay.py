@@ -274,3 +274,57 @@ def test_relay_with_a_row_stride(fmt):
         n = int(st["rows_per_hop"][h])
         assert not H.host(ch.rows[h])[:n, w.row_bytes:].any(), "bytes between a child's rows were written"
     ctx.close()
+
+
+@pytest.mark.parametrize("which", ["bf16_short_rows", "bf16_long_rows", "fp8"])
+def test_relay_stream_index_of_the_next_buffer_rides_with_the_copy(which):
+    """mw_relay_index + mw_relay_copy_index_next + mw_relay_copy over a stream of buffers on two
+    contexts with different forwarding tables: every step's children and statistics against the
+    oracle, whatever index ran beside its copy; one buffer is short and one is empty."""
+    w = {"bf16_short_rows": W.scaled(W.C1, n_tokens=300, hidden=1024),
+         "bf16_long_rows": W.scaled(W.C1, n_tokens=150, hidden=7168),
+         "fp8": W.scaled(W.C2, n_tokens=260, hidden=1024)}[which]
+    _say("relay stream", w.name)
+    rng = np.random.default_rng(5)
+    tables = [(rng.integers(0, 9, size=w.n_ranks).astype(np.int32), 9),
+              (rng.integers(0, 33, size=w.n_ranks).astype(np.int32), 33)]
+    ctxs = [_ctx(w, 0, 64), _ctx(w, 0, 64)]
+    for c, (nh, n) in zip(ctxs, tables):
+        c.mw_set_forwarding(nh, n)
+    sizes = [w.n_tokens, 77, 0, w.n_tokens, 130]
+    steps = []
+    for i, T in enumerate(sizes):
+        tk = W.topk_ids(w, 20 + i, i)[:T].copy()
+        x, sc = W.payload_rows(w, 20 + i, i)
+        x, sc = x[:T].copy(), (None if sc is None else sc[:T].copy())
+        g = H.GpuSend(ctxs[0], tk, x, sc)
+        nh, n = tables[i % 2]
+        steps.append(dict(tk=tk, x=x, sc=sc, g=g, table=_in_record(g.full_record()),
+                          ch=B.RelayChildren(ctxs[i % 2], n, w.n_tokens)))
+    s0 = steps[0]
+    ctxs[0].mw_relay_index(s0["table"], s0["ch"].table, w.n_tokens, s0["ch"].stats)
+    for i, st in enumerate(steps):
+        cur = ctxs[i % 2]
+        if i + 1 < len(steps):
+            nx = steps[i + 1]
+            cur.mw_relay_copy_index_next(st["table"], st["ch"].table, st["ch"].stats, ctxs[(i + 1) % 2], nx["table"],
+                                         nx["ch"].table, w.n_tokens, nx["ch"].stats)
+        else:
+            cur.mw_relay_copy(st["table"], st["ch"].table, st["ch"].stats)
+    torch.cuda.synchronize()
+    for i, st in enumerate(steps):
+        nh, n = tables[i % 2]
+        stats = ctxs[i % 2].mw_get_relay_stats(st["ch"].stats)
+        parent = H.oracle_send(w, st["tk"], st["x"], st["sc"])
+        check_children(st["ch"], stats, parent, nh, n, w.row_bytes)
+    # argument errors: the same context twice, a missing next buffer
+    with pytest.raises(B.MwError) as ei:
+        ctxs[0].mw_relay_copy_index_next(s0["table"], s0["ch"].table, s0["ch"].stats, ctxs[0], s0["table"],
+                                         s0["ch"].table, w.n_tokens, s0["ch"].stats)
+    assert ei.value.status == B.MW_ERR_INVALID_ARG
+    with pytest.raises(B.MwError) as ei:
+        ctxs[0].mw_relay_copy_index_next(s0["table"], s0["ch"].table, s0["ch"].stats, ctxs[1], None,
+                                         steps[1]["ch"].table, w.n_tokens, steps[1]["ch"].stats)
+    assert ei.value.status == B.MW_ERR_INVALID_ARG
+    for c in ctxs:
+        c.close()
