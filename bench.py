@@ -499,7 +499,36 @@ def bench_dispatch(args, name: str) -> dict:
                  "bytes_saved_vs_unicast": round(1.0 - int(rst["forward_bytes"]) / int(rst["unicast_bytes"]), 4),
                  "copy_bytes": relay_bytes, "copy_GBps": round(relay_bytes / relay_us["relay_copy"] / 1e3, 1),
                  "copy_pct_of_hbm_peak": round(100.0 * relay_bytes / relay_us["relay_copy"] / 1e3 / HBM_PEAK_GBPS, 2)}
-        del children
+        # a stream of buffers: the index of the next buffer rides in the launch that copies this one
+        # (two contexts in turn, their own children), against mw_relay call by call
+        ctx_r = B.Context(R, w.n_experts, K, my_rank, w.hidden, fmt, T, 1, e2r, device=dev, max_hops=16, row_stride=stride)
+        ctx_r.mw_set_forwarding(next_hop, n_hops)
+        kids = [children, B.RelayChildren(ctx_r, n_hops, T)]
+        rc = [ctx, ctx_r]
+        n_s = 40
+        for form in ("stream", "calls"):
+            if form == "stream":
+                ctx.mw_relay_index(in_rec, kids[0].table, T, kids[0].stats)
+            for i in range(n_s + 4):
+                if i == 4:
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                if form == "stream":
+                    rc[i % 2].mw_relay_copy_index_next(in_rec, kids[i % 2].table, kids[i % 2].stats, rc[(i + 1) % 2], in_rec,
+                                                       kids[(i + 1) % 2].table, T, kids[(i + 1) % 2].stats)
+                else:
+                    rc[i % 2].mw_relay(in_rec, kids[i % 2].table, T, kids[i % 2].stats)
+            torch.cuda.synchronize()
+            relay["step_us_" + form] = round((time.perf_counter() - t0) * 1e6 / n_s, 2)
+            if form == "stream":             # the buffer indexed by the last launch is copied too
+                rc[(n_s + 4) % 2].mw_relay_copy(in_rec, kids[(n_s + 4) % 2].table, kids[(n_s + 4) % 2].stats)
+        for c_, k_ in zip(rc, kids):
+            rs_ = c_.mw_get_relay_stats(k_.stats)
+            assert int(rs_["error_flags"]) == 0 and int(rs_["n_rows_in"]) == N and int(rs_["forward_bytes"]) == int(rst["forward_bytes"])
+        relay["step_GBps_stream"] = round(relay_bytes / relay["step_us_stream"] / 1e3, 1)
+        relay["step_pct_of_hbm_peak_stream"] = round(100.0 * relay_bytes / relay["step_us_stream"] / 1e3 / HBM_PEAK_GBPS, 2)
+        ctx_r.close()
+        del children, kids
 
     # ---------------------------------------------------------------- packet path (extra, untimed region)
     # The same step with the bitmap and the row metadata in a header in front of every row

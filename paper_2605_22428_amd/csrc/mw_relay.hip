@@ -445,8 +445,15 @@ int32_t mw_launch_relay_copy(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay
                                c.top_k, n_chunks, (int)(ctx->row_stride / 16), (uint32_t)c.max_tokens,
                                (uint64_t)ctx->row_bytes, ctx->d_group_of_row, ctx->d_child_pos, ctx->d_relay_flags, stats);
         } else {
-            // the index keeps 8 KiB of LDS per workgroup: two waves each, so that a CU still holds 32
-            if (shape.bs == 64 && n_chunks % 16 == 0) { shape.bs = 128; shape.nseg = n_chunks / 128 + (n_chunks % 128 ? 1 : 0); }
+            // Long rows of whole cache lines: a few large workgroups per row instead of single
+            // waves.  The riding index walks the groups a workgroup's width at a time, one memory
+            // round trip and two scans per step: 128 lanes took 32 steps for 4096 groups and
+            // outlasted the copy by half; and its 8 KiB of LDS per workgroup would leave a CU of
+            // single-wave workgroups 19 waves instead of 32.
+            if (shape.bs == 64 && n_chunks % 16 == 0) {
+                shape.nseg = (n_chunks + 511) / 512;
+                shape.bs = ((n_chunks + shape.nseg - 1) / shape.nseg + 63) / 64 * 64;
+            }
             hipLaunchKernelGGL(k_relay_copy_index_next, dim3(shape.nseg, gy + (uint32_t)next->n_hops + 1u),
                                dim3(shape.bs), 0, s, in, children, ctx->n_hops, c.top_k, n_chunks,
                                (int)(ctx->row_stride / 16), (uint32_t)c.max_tokens, (uint64_t)ctx->row_bytes,
