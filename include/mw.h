@@ -36,8 +36,10 @@
  *     (1) mw_plan (and the plan half of mw_unpack_expand_index_plan_next,
  *     in next_ctx); (2) mw_unpack, mw_unpack_packets, mw_unpack_index,
  *     mw_unpack_expand, mw_unpack_expand_index[_plan]_next (the part of `ctx` and,
- *     for the index, of `next_ctx`) and mw_combine_gather; (3) mw_relay and
- *     mw_relay_packets; (4) mw_sim_deliver.  Calls of one part race if they
+ *     for the index, of `next_ctx`) and mw_combine_gather; (3) mw_relay,
+ *     mw_relay_index, mw_relay_copy, mw_relay_copy_index_next (the part of `ctx`
+ *     and, for the index, of `next_ctx`) and mw_relay_packets; (4)
+ *     mw_sim_deliver.  Calls of one part race if they
  *     overlap on the device; calls of different parts, and the packers
  *     (mw_pack, mw_pack_quantize, mw_pack_packets, mw_plan_pack, the
  *     AllGather calls), which use no workspace, may run on different streams
