@@ -178,3 +178,97 @@ def test_captured_allgather_step_replays():
         H.assert_same_bytes(np.array([ctx.mw_get_send_stats(stats)]).view(np.uint8),
                             np.array([ost]).view(np.uint8), "replay: stats")
     ctx.close()
+
+
+def test_captured_stream_step_replays():
+    """mw_stream_step (pack, expand, the next batch's index and plan in one launch, with its
+    workgroups that wait for others of the same launch) in a graph: three replays with new tokens,
+    payload and received regions each time, the eager calls a stream needs around it in between
+    (plan of the batch it packs, index of the batch it expands, expander of the batch it indexed)."""
+    w = W.scaled(W.C1, n_tokens=200, hidden=512)
+    my_rank, e2r, T, R = 5, W.expert_to_rank(w), 200, W.C1.n_ranks
+    _say("graph replay stream step")
+    ctxs = [H.make_ctx(w, my_rank), H.make_ctx(w, my_rank)]
+    # two sets of received regions (device buffers stay, the graph's record table is overwritten)
+    sets = []
+    for seed in (1, 2):
+        recs, toks = [], []
+        for p in range(R):
+            tk = W.topk_ids(w, seed, p)
+            x, sc = W.payload_rows(w, seed, p)
+            recs.append(H.shrink(H.GpuSend(ctxs[0], tk, x, sc).deliver(my_rank)))
+            toks.append((tk, x, sc))
+        sets.append(dict(recs=recs, toks=toks, table=B.peers_table(recs, H.DEV)))
+    cap = max(sum(r["n_rows"] for r in s["recs"]) for s in sets) * 2
+    want = [ref.dispatch_plain(s["toks"], e2r, my_rank, cap) for s in sets]
+    cur_table, next_table = torch.zeros_like(sets[0]["table"]), torch.zeros_like(sets[0]["table"])
+    tk_d = torch.zeros((T, w.top_k), dtype=torch.int32, device=H.DEV)        # batch that is packed
+    x_d = torch.zeros((T, w.hidden), dtype=torch.int16, device=H.DEV)
+    tkn_d = torch.zeros((T, w.top_k), dtype=torch.int32, device=H.DEV)       # batch that is planned
+    sb, sn = B.SendBuffers(ctxs[0], T), B.SendBuffers(ctxs[1], T)
+    rv, rvn = B.RecvBuffers(ctxs[0], cap), B.RecvBuffers(ctxs[1], cap)
+
+    def step():
+        ctxs[0].mw_stream_step(x_d, None, tk_d, sb.perm, sb.stats, sb.packed, sb.row_src_token, sb.row_topk, R,
+                               rv.out_rows, rv.out_scales, cap, rv.out_src_peer, rv.out_src_token, ctxs[1], next_table,
+                               R, cap, rvn.expert_offsets, rvn.stats, tkn_d, sn.mask, sn.perm, sn.desc, sn.stats)
+
+    def eager_before(rep):
+        """What a stream has done before this step: inputs in place, this batch planned and indexed."""
+        tk, tkn = W.topk_ids(w, 40 + rep, my_rank), W.topk_ids(w, 50 + rep, my_rank)
+        if rep == 1:
+            tkn[::4] = -1
+        x, _ = W.payload_rows(w, 40 + rep, my_rank)
+        tk_d.copy_(H.dev(tk)); tkn_d.copy_(H.dev(tkn)); x_d.copy_(H.dev(x).view(torch.int16))
+        cur_table.copy_(sets[rep % 2]["table"]); next_table.copy_(sets[(rep + 1) % 2]["table"])
+        _clear(sb.packed, sb.row_topk, sn.mask, sn.desc, sn.stats, rv.out_rows, rvn.expert_offsets, rvn.stats)
+        sb.row_src_token.fill_(-1); sn.perm.fill_(-1); rv.out_src_peer.fill_(-1); rv.out_src_token.fill_(-1)
+        ctxs[0].mw_plan(tk_d, sb.mask, sb.perm, sb.desc, sb.stats)
+        ctxs[0].mw_unpack_index(cur_table, R, cap, rv.expert_offsets, rv.stats)
+        torch.cuda.synchronize()
+        return tk, tkn, x
+
+    side = torch.cuda.Stream()
+    eager_before(0)
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    eager_before(0)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    torch.cuda.synchronize()
+
+    class _Got:
+        pass
+
+    for rep in range(3):
+        tk, tkn, x = eager_before(rep)
+        graph.replay()
+        torch.cuda.synchronize()
+        _say("  replay", rep)
+        # packed: batch tk
+        _check_send_buffers(w, sb, ctxs[0], tk, x, None)
+        # planned: batch tkn
+        m, perm, desc, ost = ref.plan(tkn, e2r, R, w.row_bytes)
+        st = ctxs[1].mw_get_send_stats(sn.stats)
+        n, g_ = int(st["n_rows"]), int(st["n_groups"])
+        assert (n, g_, int(st["error_flags"])) == (len(perm), len(desc), 0)
+        H.assert_same_bytes(H.host(sn.mask).view(np.uint64)[:T], m, "replay: next mask")
+        H.assert_same_bytes(H.host(sn.perm)[:n], perm, "replay: next perm")
+        H.assert_same_bytes(H.host(sn.desc).reshape(-1).view(B.DESC_DTYPE)[:g_].view(np.uint8), desc.view(np.uint8),
+                            "replay: next desc")
+        # expanded: the set indexed eagerly; indexed: the other set, expanded eagerly now
+        ctxs[1].mw_unpack_expand(R, rvn.out_rows, rvn.out_scales, cap, rvn.out_src_peer, rvn.out_src_token)
+        torch.cuda.synchronize()
+        for c_, b_, wnt, what in ((ctxs[0], rv, want[rep % 2], "expanded"), (ctxs[1], rvn, want[(rep + 1) % 2], "indexed")):
+            g = _Got()
+            g.ctx, g.buf = c_, b_
+            g.stats = c_.mw_get_recv_stats(b_.stats)
+            g.Q = int(g.stats["n_out_rows"])
+            g.host_out = lambda g=g: H.GpuUnpack.host_out(g)
+            H.check_unpack(g, wnt, "replay %d %s" % (rep, what))
+    for c in ctxs:
+        c.close()
