@@ -38,7 +38,8 @@
  *     mw_unpack_expand, mw_unpack_expand_index[_plan]_next (the part of `ctx` and,
  *     for the index, of `next_ctx`) and mw_combine_gather; (3) mw_relay,
  *     mw_relay_index, mw_relay_copy, mw_relay_copy_index_next (the part of `ctx`
- *     and, for the index, of `next_ctx`) and mw_relay_packets; (4)
+ *     and, for the index, of `next_ctx`), mw_relay_packets and its three forms
+ *     of the same names; (4)
  *     mw_sim_deliver.  Calls of one part race if they
  *     overlap on the device; calls of different parts, and the packers
  *     (mw_pack, mw_pack_quantize, mw_pack_packets, mw_plan_pack, the
@@ -615,6 +616,23 @@ MW_API int32_t mw_relay_copy_index_next(mw_ctx *ctx, const mw_recv_peer *in_dev,
  */
 MW_API int32_t mw_relay_packets(mw_ctx *ctx, const mw_recv_packets *in_dev, void *const *children_dev,
                          int64_t child_capacity_rows, mw_relay_stats *stats_dev, void *stream);
+
+/*
+ * mw_relay_packets as its two halves and, for a stream of packet buffers, with the next
+ * buffer's index in the copy's launch: the packets' forms of mw_relay_index, mw_relay_copy and
+ * mw_relay_copy_index_next (Section 4.1, replication and forwarding; Section 5.1, relay
+ * module), with the same rules -- mw_relay_packets is the index followed by the copy, the
+ * one-launch form gives identical results, `next_ctx` is another context on the same device
+ * with its own forwarding table, and two contexts take turns.
+ */
+MW_API int32_t mw_relay_packets_index(mw_ctx *ctx, const mw_recv_packets *in_dev, int64_t child_capacity_rows,
+                               mw_relay_stats *stats_dev, void *stream);
+MW_API int32_t mw_relay_packets_copy(mw_ctx *ctx, const mw_recv_packets *in_dev, void *const *children_dev,
+                              mw_relay_stats *stats_dev, void *stream);
+MW_API int32_t mw_relay_packets_copy_index_next(mw_ctx *ctx, const mw_recv_packets *in_dev, void *const *children_dev,
+                                         mw_relay_stats *stats_dev, mw_ctx *next_ctx,
+                                         const mw_recv_packets *next_in_dev, int64_t next_child_capacity_rows,
+                                         mw_relay_stats *next_stats_dev, void *stream);
 
 /* ---- simulation and measurement helpers (not part of the dispatch path) ---------------- */
 

@@ -27,7 +27,7 @@ EXPORTS = ["mw_workspace_bytes", "mw_ctx_create", "mw_ctx_destroy", "mw_plan", "
            "mw_plan_allgather", "mw_pack_allgather", "mw_unpack", "mw_unpack_index", "mw_unpack_expand",
            "mw_unpack_allgather", "mw_combine_gather", "mw_unpack_expand_index_next", "mw_unpack_expand_index_plan_next", "mw_ctx_set_ride_wait_limit", "mw_stream_step", "mw_allgather_step",
            "mw_sim_deliver", "mw_copy_bytes", "mw_get_send_stats", "mw_get_recv_stats",
-           "mw_set_forwarding", "mw_relay", "mw_relay_index", "mw_relay_copy", "mw_relay_copy_index_next", "mw_relay_packets", "mw_get_relay_stats",
+           "mw_set_forwarding", "mw_relay", "mw_relay_index", "mw_relay_copy", "mw_relay_copy_index_next", "mw_relay_packets", "mw_relay_packets_index", "mw_relay_packets_copy", "mw_relay_packets_copy_index_next", "mw_get_relay_stats",
            "mw_allgather_split_point", "mw_plan_allgather_split", "mw_unpack_allgather_split",
            "mw_ctx_set_timing_events", "mw_status_string"]
 MW_KERNEL_PLAN_RANK, MW_KERNEL_PLAN_GROUPS, MW_KERNEL_PACK, MW_KERNEL_RECV_INDEX, MW_KERNEL_EXPAND = 0, 1, 2, 3, 4
@@ -341,6 +341,22 @@ class Context:
                          stats: torch.Tensor):
         _check(load().mw_relay_packets(self._h, _ptr(in_record), _ptr(children), C.c_int64(child_capacity_rows),
                                        _ptr(stats), _stream()), "mw_relay_packets")
+
+    def mw_relay_packets_index(self, in_record: torch.Tensor, child_capacity_rows: int, stats: torch.Tensor):
+        _check(load().mw_relay_packets_index(self._h, _ptr(in_record), C.c_int64(child_capacity_rows), _ptr(stats),
+                                             _stream()), "mw_relay_packets_index")
+
+    def mw_relay_packets_copy(self, in_record: torch.Tensor, children: torch.Tensor, stats: torch.Tensor):
+        _check(load().mw_relay_packets_copy(self._h, _ptr(in_record), _ptr(children), _ptr(stats), _stream()),
+               "mw_relay_packets_copy")
+
+    def mw_relay_packets_copy_index_next(self, in_record: torch.Tensor, children: torch.Tensor, stats: torch.Tensor,
+                                         next_ctx: "Context", next_in_record: torch.Tensor,
+                                         next_child_capacity_rows: int, next_stats: torch.Tensor):
+        _check(load().mw_relay_packets_copy_index_next(self._h, _ptr(in_record), _ptr(children), _ptr(stats),
+                                                       next_ctx._h, _ptr(next_in_record),
+                                                       C.c_int64(next_child_capacity_rows), _ptr(next_stats),
+                                                       _stream()), "mw_relay_packets_copy_index_next")
 
     def mw_get_relay_stats(self, stats: torch.Tensor) -> np.ndarray:
         host = np.zeros(1, dtype=RELAY_STATS_DTYPE)

@@ -688,6 +688,48 @@ MW_API int32_t mw_relay_packets(mw_ctx *ctx, const mw_recv_packets *in_dev, void
     return mw_launch_relay_packets(ctx, in_dev, children_dev, child_capacity_rows, stats_dev, (hipStream_t)stream);
 }
 
+static int32_t relay_packets_ready(const mw_ctx *ctx)
+{
+    if (ctx->cfg.max_hops < 1 || ctx->n_hops < 1) return MW_ERR_INVALID_ARG;      // no forwarding table
+    if (ctx->cfg.n_experts == 0) return MW_ERR_INVALID_ARG;
+    return MW_OK;
+}
+
+MW_API int32_t mw_relay_packets_index(mw_ctx *ctx, const mw_recv_packets *in_dev, int64_t child_capacity_rows,
+                               mw_relay_stats *stats_dev, void *stream)
+{
+    if (!ctx || !in_dev || !stats_dev || child_capacity_rows < 0) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
+    if (relay_packets_ready(ctx) != MW_OK) return MW_ERR_INVALID_ARG;
+    if (child_capacity_rows > 0x7fffffffLL) return MW_ERR_UNSUPPORTED;
+    return mw_launch_relay_packets_index(ctx, in_dev, child_capacity_rows, stats_dev, (hipStream_t)stream);
+}
+
+MW_API int32_t mw_relay_packets_copy(mw_ctx *ctx, const mw_recv_packets *in_dev, void *const *children_dev,
+                              mw_relay_stats *stats_dev, void *stream)
+{
+    if (!ctx || !in_dev || !children_dev || !stats_dev) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
+    if (relay_packets_ready(ctx) != MW_OK) return MW_ERR_INVALID_ARG;
+    return mw_launch_relay_packets_copy(ctx, in_dev, children_dev, stats_dev, nullptr, nullptr, 0, nullptr,
+                                        (hipStream_t)stream);
+}
+
+MW_API int32_t mw_relay_packets_copy_index_next(mw_ctx *ctx, const mw_recv_packets *in_dev, void *const *children_dev,
+                                         mw_relay_stats *stats_dev, mw_ctx *next_ctx,
+                                         const mw_recv_packets *next_in_dev, int64_t next_child_capacity_rows,
+                                         mw_relay_stats *next_stats_dev, void *stream)
+{
+    if (!ctx || !in_dev || !children_dev || !stats_dev) return MW_ERR_INVALID_ARG;
+    if (!next_ctx || next_ctx == ctx || next_ctx->device != ctx->device) return MW_ERR_INVALID_ARG;
+    if (!next_in_dev || !next_stats_dev || next_child_capacity_rows < 0) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
+    if (relay_packets_ready(ctx) != MW_OK || relay_packets_ready(next_ctx) != MW_OK) return MW_ERR_INVALID_ARG;
+    if (next_child_capacity_rows > 0x7fffffffLL) return MW_ERR_UNSUPPORTED;
+    return mw_launch_relay_packets_copy(ctx, in_dev, children_dev, stats_dev, next_ctx, next_in_dev,
+                                        next_child_capacity_rows, next_stats_dev, (hipStream_t)stream);
+}
+
 MW_API int32_t mw_get_relay_stats(mw_ctx *ctx, const mw_relay_stats *stats_dev, mw_relay_stats *host_out, void *stream)
 {
     if (!ctx || !stats_dev || !host_out) return MW_ERR_INVALID_ARG;

@@ -242,6 +242,11 @@ int32_t mw_launch_relay_copy(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay
                              mw_relay_stats *stats, mw_ctx *next, const mw_recv_peer *next_in,
                              const mw_relay_child *next_children, int64_t next_cap, mw_relay_stats *next_stats,
                              hipStream_t s);
+int32_t mw_launch_relay_packets_index(mw_ctx *ctx, const mw_recv_packets *in, int64_t cap, mw_relay_stats *stats,
+                                      hipStream_t s);
+int32_t mw_launch_relay_packets_copy(mw_ctx *ctx, const mw_recv_packets *in, void *const *children,
+                                     mw_relay_stats *stats, mw_ctx *next, const mw_recv_packets *next_in,
+                                     int64_t next_cap, mw_relay_stats *next_stats, hipStream_t s);
 int32_t mw_launch_relay_packets(mw_ctx *ctx, const mw_recv_packets *in, void *const *children, int64_t cap,
                                 mw_relay_stats *stats, hipStream_t s);
 int32_t mw_launch_sim_deliver(mw_ctx *ctx, const mw_group_desc *desc, const mw_send_stats *stats,

@@ -289,30 +289,38 @@ __device__ __forceinline__ pkt_view load_packet_header(const char *packets, uint
     return v;
 }
 
-__global__ __launch_bounds__(kBlock) void k_relay_packets_index(
+// Everything the index of one relay step of packets needs (one kernel argument).
+struct mw_relay_packets_index_args {
+    const mw_recv_packets *in; int n_hops, n_ranks; uint32_t K, max_tokens, cap; uint64_t packet_bytes;
+    const uint64_t *hop_bits; uint32_t *child_pos; uint32_t *relay_flags; mw_relay_stats *stats;
+};
+
+// Workgroup `wg` of the packets' relay index (wg < n_hops: hop wg's positions; wg == n_hops: the
+// accounting).  Any workgroup size that is a multiple of 64.
+__device__ __forceinline__ void relay_packets_index_body(
     const mw_recv_packets *__restrict__ in, int n_hops, int n_ranks, uint32_t K, uint32_t max_tokens, uint32_t cap,
     uint64_t packet_bytes, const uint64_t *__restrict__ hop_bits, uint32_t *__restrict__ child_pos,
-    uint32_t *relay_flags, mw_relay_stats *__restrict__ stats)
+    uint32_t *relay_flags, mw_relay_stats *__restrict__ stats, const int wg)
 {
     __shared__ uint32_t scratch[17];
     __shared__ unsigned long long acc[2];        // packets taken, destinations named
-    const uint32_t tid = threadIdx.x;
+    const uint32_t tid = threadIdx.x, bs = blockDim.x;
     const mw_recv_packets src = in[0];
     const char *packets = (const char *)src.packets;
     const uint32_t n_rows = min(src.n_rows, max_tokens);
     uint32_t err = src.n_rows > max_tokens ? MW_FLAG_BAD_DESC : 0u;
 
-    if ((int)blockIdx.x < n_hops) {
-        const int h = blockIdx.x;
+    if (wg < n_hops) {
+        const int h = wg;
         uint64_t hb[MW_MASK_WORDS];
 #pragma unroll
         for (int w = 0; w < MW_MASK_WORDS; ++w) hb[w] = hop_bits[(size_t)h * MW_MASK_WORDS + w];
         uint32_t carry = 0;
         pkt_view nxt = load_packet_header(packets, packet_bytes, tid, n_rows, K);
-        for (uint32_t i0 = 0; i0 < n_rows; i0 += kBlock) {
+        for (uint32_t i0 = 0; i0 < n_rows; i0 += bs) {
             const uint32_t i = i0 + tid;
             const pkt_view v = nxt;
-            nxt = load_packet_header(packets, packet_bytes, i + kBlock, n_rows, K);   // in flight during the scan
+            nxt = load_packet_header(packets, packet_bytes, i + bs, n_rows, K);       // in flight during the scan
             bool keep = false;
 #pragma unroll
             for (int w = 0; w < MW_MASK_WORDS; ++w) keep |= (v.m[w] & hb[w]) != 0;
@@ -340,7 +348,7 @@ __global__ __launch_bounds__(kBlock) void k_relay_packets_index(
             valid_ranks[w] = (n_ranks >= lo + 64) ? ~0ull : (n_ranks > lo ? ((1ull << (n_ranks - lo)) - 1ull) : 0ull);
         }
         uint32_t taken = 0, dests = 0;
-        for (uint32_t i = tid; i < n_rows; i += kBlock) {
+        for (uint32_t i = tid; i < n_rows; i += bs) {
             const pkt_view v = load_packet_header(packets, packet_bytes, i, n_rows, K);
             if (!v.valid) { err |= MW_FLAG_BAD_DESC; continue; }
 #pragma unroll
@@ -360,22 +368,29 @@ __global__ __launch_bounds__(kBlock) void k_relay_packets_index(
             stats->unicast_bytes = (uint64_t)acc[1] * packet_bytes;
             stats->reserved0 = 0;
         }
-        for (int h = n_hops + tid; h < MW_MAX_HOPS; h += kBlock) { stats->groups_per_hop[h] = 0; stats->rows_per_hop[h] = 0; }
+        for (int h = n_hops + (int)tid; h < MW_MAX_HOPS; h += (int)bs) { stats->groups_per_hop[h] = 0; stats->rows_per_hop[h] = 0; }
     }
     if (err) atomicOr(relay_flags, err);
 }
 
-// blockIdx.x selects a segment of blockDim.x chunks of a packet, blockIdx.y walks packets.
-__global__ __launch_bounds__(1024) void k_relay_packets_copy(
+__global__ __launch_bounds__(kBlock) void k_relay_packets_index(const mw_relay_packets_index_args a)
+{
+    relay_packets_index_body(a.in, a.n_hops, a.n_ranks, a.K, a.max_tokens, a.cap, a.packet_bytes, a.hop_bits,
+                             a.child_pos, a.relay_flags, a.stats, (int)blockIdx.x);
+}
+
+// blockIdx.x selects a segment of blockDim.x chunks of a packet; packets i_first, i_first + i_stride, ...
+__device__ __forceinline__ void relay_packets_copy_body(
     const mw_recv_packets *__restrict__ in, void *const *__restrict__ children, int n_hops, int n_chunks,
     uint32_t max_tokens, uint64_t packet_bytes, const uint64_t *__restrict__ hop_bits,
-    const uint32_t *__restrict__ child_pos, uint32_t *relay_flags, mw_relay_stats *__restrict__ stats)
+    const uint32_t *__restrict__ child_pos, uint32_t *relay_flags, mw_relay_stats *__restrict__ stats,
+    const uint32_t i_first, const uint32_t i_stride)
 {
     const mw_recv_packets src = in[0];
     const uint32_t n_rows = min(src.n_rows, max_tokens);
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
     const int lane = threadIdx.x & 63;
-    for (uint32_t i = blockIdx.y; i < n_rows; i += gridDim.y) {
+    for (uint32_t i = i_first; i < n_rows; i += i_stride) {
         u32x4 v = {0u, 0u, 0u, 0u};
         if (c < n_chunks) v = mw_ld16((const u32x4 *)src.packets + (size_t)i * n_chunks + c);
         const uint32_t p = (lane < n_hops) ? child_pos[(size_t)i * MW_MAX_HOPS + lane] : kNoChild;
@@ -393,13 +408,42 @@ __global__ __launch_bounds__(1024) void k_relay_packets_copy(
             if (c < n_chunks) mw_st16((u32x4 *)children[h] + (size_t)dst * n_chunks + c, o);
         }
     }
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+    if (blockIdx.x == 0 && i_first == 0 && threadIdx.x == 0) {
         unsigned long long rows_out = 0;
         for (int h = 0; h < n_hops; ++h) rows_out += stats->rows_per_hop[h];
         stats->forward_bytes = rows_out * packet_bytes;
         stats->error_flags = __hip_atomic_load(relay_flags, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(relay_flags, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next relay
     }
+}
+
+__global__ __launch_bounds__(1024) void k_relay_packets_copy(
+    const mw_recv_packets *__restrict__ in, void *const *__restrict__ children, int n_hops, int n_chunks,
+    uint32_t max_tokens, uint64_t packet_bytes, const uint64_t *__restrict__ hop_bits,
+    const uint32_t *__restrict__ child_pos, uint32_t *relay_flags, mw_relay_stats *__restrict__ stats)
+{
+    relay_packets_copy_body(in, children, n_hops, n_chunks, max_tokens, packet_bytes, hop_bits, child_pos, relay_flags,
+                            stats, blockIdx.y, gridDim.y);
+}
+
+// The packets' form of k_relay_copy_index_next: this buffer's copy with the next buffer's index
+// (another context's workspace) in the first next.n_hops + 1 workgroup rows.
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_relay_packets_copy_index_next(
+    const mw_recv_packets *__restrict__ in, void *const *__restrict__ children, int n_hops, int n_chunks,
+    uint32_t max_tokens, uint64_t packet_bytes, const uint64_t *__restrict__ hop_bits,
+    const uint32_t *__restrict__ child_pos, uint32_t *relay_flags, mw_relay_stats *__restrict__ stats,
+    const mw_relay_packets_index_args next)
+{
+    const uint32_t n_index = (uint32_t)next.n_hops + 1u;
+    if (blockIdx.y < n_index) {
+        if (blockIdx.x == 0)
+            relay_packets_index_body(next.in, next.n_hops, next.n_ranks, next.K, next.max_tokens, next.cap,
+                                     next.packet_bytes, next.hop_bits, next.child_pos, next.relay_flags, next.stats,
+                                     (int)blockIdx.y);
+        return;
+    }
+    relay_packets_copy_body(in, children, n_hops, n_chunks, max_tokens, packet_bytes, hop_bits, child_pos, relay_flags,
+                            stats, blockIdx.y - n_index, gridDim.y - n_index);
 }
 
 }  // namespace
@@ -473,27 +517,67 @@ int32_t mw_launch_relay(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay_chil
     return mw_launch_relay_copy(ctx, in, children, stats, nullptr, nullptr, nullptr, 0, nullptr, s);
 }
 
-int32_t mw_launch_relay_packets(mw_ctx *ctx, const mw_recv_packets *in, void *const *children, int64_t cap,
-                                mw_relay_stats *stats, hipStream_t s)
+static mw_relay_packets_index_args relay_packets_index_args(mw_ctx *ctx, const mw_recv_packets *in, int64_t cap,
+                                                            mw_relay_stats *stats)
+{
+    mw_relay_packets_index_args a;
+    a.in = in; a.n_hops = ctx->n_hops; a.n_ranks = ctx->cfg.n_ranks; a.K = (uint32_t)ctx->cfg.top_k;
+    a.max_tokens = (uint32_t)ctx->cfg.max_tokens; a.cap = (uint32_t)cap;
+    a.packet_bytes = (uint64_t)(mw_packet_header_bytes_of(ctx->cfg.top_k) + ctx->row_bytes);
+    a.hop_bits = ctx->d_hop_bits; a.child_pos = ctx->d_child_pos; a.relay_flags = ctx->d_relay_flags; a.stats = stats;
+    return a;
+}
+
+int32_t mw_launch_relay_packets_index(mw_ctx *ctx, const mw_recv_packets *in, int64_t cap, mw_relay_stats *stats,
+                                      hipStream_t s)
+{
+    {
+        mw_timed tm(ctx, MW_KERNEL_RELAY_INDEX, s);
+        hipLaunchKernelGGL(k_relay_packets_index, dim3(ctx->n_hops + 1), dim3(kBlock), 0, s,
+                           relay_packets_index_args(ctx, in, cap, stats));
+    }
+    MW_HIP_CHECK(hipGetLastError());
+    return MW_OK;
+}
+
+// `next` != nullptr: the index of the next step's packets rides in the same launch.
+int32_t mw_launch_relay_packets_copy(mw_ctx *ctx, const mw_recv_packets *in, void *const *children,
+                                     mw_relay_stats *stats, mw_ctx *next, const mw_recv_packets *next_in,
+                                     int64_t next_cap, mw_relay_stats *next_stats, hipStream_t s)
 {
     const mw_config &c = ctx->cfg;
     const uint64_t pb = (uint64_t)(mw_packet_header_bytes_of(c.top_k) + ctx->row_bytes);
     const int n_chunks = (int)(pb / 16);
+    mw_row_shape shape = mw_row_shape_of(n_chunks);
+    uint32_t gy = (uint32_t)c.max_tokens < kRowGridMax ? (uint32_t)c.max_tokens : kRowGridMax;
+    if (gy < 1) gy = 1;
     {
-        mw_timed tm(ctx, MW_KERNEL_RELAY_INDEX, s);
-        hipLaunchKernelGGL(k_relay_packets_index, dim3(ctx->n_hops + 1), dim3(kBlock), 0, s, in, ctx->n_hops, c.n_ranks,
-                           (uint32_t)c.top_k, (uint32_t)c.max_tokens, (uint32_t)cap, pb, ctx->d_hop_bits,
-                           ctx->d_child_pos, ctx->d_relay_flags, stats);
-    }
-    {
-        const mw_row_shape shape = mw_row_shape_of(n_chunks);
-        uint32_t gy = (uint32_t)c.max_tokens < kRowGridMax ? (uint32_t)c.max_tokens : kRowGridMax;
-        if (gy < 1) gy = 1;
         mw_timed tm(ctx, MW_KERNEL_RELAY_COPY, s);
-        hipLaunchKernelGGL(k_relay_packets_copy, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, in, children, ctx->n_hops,
-                           n_chunks, (uint32_t)c.max_tokens, pb, ctx->d_hop_bits, ctx->d_child_pos, ctx->d_relay_flags,
-                           stats);
+        if (!next) {
+            hipLaunchKernelGGL(k_relay_packets_copy, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, in, children, ctx->n_hops,
+                               n_chunks, (uint32_t)c.max_tokens, pb, ctx->d_hop_bits, ctx->d_child_pos,
+                               ctx->d_relay_flags, stats);
+        } else {
+            // long packets: a few large workgroups per packet instead of single waves, for the
+            // riding index's sake (see mw_launch_relay_copy); pieces stay whole cache lines
+            if (shape.bs == 64) {
+                shape.nseg = (n_chunks + 511) / 512;
+                shape.bs = ((n_chunks + shape.nseg - 1) / shape.nseg + 63) / 64 * 64;
+            }
+            hipLaunchKernelGGL(k_relay_packets_copy_index_next, dim3(shape.nseg, gy + (uint32_t)next->n_hops + 1u),
+                               dim3(shape.bs), 0, s, in, children, ctx->n_hops, n_chunks, (uint32_t)c.max_tokens, pb,
+                               ctx->d_hop_bits, ctx->d_child_pos, ctx->d_relay_flags, stats,
+                               relay_packets_index_args(next, next_in, next_cap, next_stats));
+        }
     }
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;
+}
+
+int32_t mw_launch_relay_packets(mw_ctx *ctx, const mw_recv_packets *in, void *const *children, int64_t cap,
+                                mw_relay_stats *stats, hipStream_t s)
+{
+    const int32_t rc = mw_launch_relay_packets_index(ctx, in, cap, stats, s);
+    if (rc != MW_OK) return rc;
+    return mw_launch_relay_packets_copy(ctx, in, children, stats, nullptr, nullptr, 0, nullptr, s);
 }

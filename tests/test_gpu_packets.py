@@ -332,3 +332,61 @@ def test_relay_packets_capacity_and_bad_headers():
     kids, st = gpu_relay_packets(ctx, g.packets, g.N, next_hop, 2, w.n_tokens)
     assert int(st["error_flags"]) == 0                    # flags do not stick
     ctx.close()
+
+
+@pytest.mark.parametrize("which", ["c1_reduced", "long_packets", "fp8"])
+def test_relay_packets_stream_index_of_the_next_buffer_rides_with_the_copy(which):
+    """mw_relay_packets_index + mw_relay_packets_copy_index_next + mw_relay_packets_copy over a
+    stream of packet buffers on two contexts with different forwarding tables: every step's
+    children and statistics against the oracle; one buffer is short and one is empty."""
+    w = {"c1_reduced": W.scaled(W.C1, n_tokens=300, hidden=1024),
+         "long_packets": W.scaled(W.C1, n_tokens=120, hidden=7168),      # 904 chunks: two workgroups per packet
+         "fp8": W.scaled(W.C2, n_tokens=200, hidden=1024)}[which]
+    _say("relay packets stream", w.name)
+    rng = np.random.default_rng(6)
+    tables = [(rng.integers(0, 7, size=w.n_ranks).astype(np.int32), 7),
+              (rng.integers(0, 20, size=w.n_ranks).astype(np.int32), 20)]
+    ctxs = [_relay_ctx(w, 0, 64), _relay_ctx(w, 0, 64)]
+    for c, (nh, n) in zip(ctxs, tables):
+        c.mw_set_forwarding(nh, n)
+    steps = []
+    for i, T in enumerate([w.n_tokens, 50, 0, w.n_tokens]):
+        tk = W.topk_ids(w, 60 + i, i)[:T].copy()
+        x, sc = W.payload_rows(w, 60 + i, i)
+        x, sc = x[:T].copy(), (None if sc is None else sc[:T].copy())
+        g = GpuPackets(ctxs[0], tk, x, sc)
+        n = tables[i % 2][1]
+        pb = g.packets.shape[1]
+        kids = [torch.zeros((w.n_tokens, pb), dtype=torch.uint8, device=H.DEV) for _ in range(n)]
+        steps.append(dict(tk=tk, x=x, sc=sc, g=g, kids=kids, rec=B.packets_table([g.packets], [g.N], H.DEV),
+                          table=torch.tensor([k.data_ptr() for k in kids], dtype=torch.int64, device=H.DEV),
+                          stats=torch.zeros(B.RELAY_STATS_BYTES, dtype=torch.uint8, device=H.DEV)))
+    ctxs[0].mw_relay_packets_index(steps[0]["rec"], w.n_tokens, steps[0]["stats"])
+    for i, st in enumerate(steps):
+        cur = ctxs[i % 2]
+        if i + 1 < len(steps):
+            nx = steps[i + 1]
+            cur.mw_relay_packets_copy_index_next(st["rec"], st["table"], st["stats"], ctxs[(i + 1) % 2], nx["rec"],
+                                                 w.n_tokens, nx["stats"])
+        else:
+            cur.mw_relay_packets_copy(st["rec"], st["table"], st["stats"])
+    torch.cuda.synchronize()
+    for i, st in enumerate(steps):
+        nh, n = tables[i % 2]
+        got = ctxs[i % 2].mw_get_relay_stats(st["stats"])
+        parent = H.oracle_packets(w, st["tk"], st["x"], st["sc"])
+        pb, total, copies, dests = st["g"].packets.shape[1], 0, 0, 0
+        for h in range(n):
+            want, copies, dests = ref.relay_packets_child(parent, nh, n, h)
+            k = int(got["rows_per_hop"][h])
+            assert k == len(want) == int(got["groups_per_hop"][h])
+            H.assert_same_bytes(H.host(st["kids"][h])[:k], want, "step %d child %d packets" % (i, h))
+            total += k
+        assert int(got["error_flags"]) == 0 and int(got["n_rows_in"]) == st["g"].N
+        assert int(got["forward_bytes"]) == copies * pb == total * pb and int(got["unicast_bytes"]) == dests * pb
+    with pytest.raises(B.MwError) as ei:
+        ctxs[0].mw_relay_packets_copy_index_next(steps[0]["rec"], steps[0]["table"], steps[0]["stats"], ctxs[0],
+                                                 steps[1]["rec"], w.n_tokens, steps[1]["stats"])
+    assert ei.value.status == B.MW_ERR_INVALID_ARG
+    for c in ctxs:
+        c.close()
