@@ -584,7 +584,35 @@ def bench_dispatch(args, name: str) -> dict:
         packets["relay"] = {"us": {k: round(v, 2) for k, v in rp_us.items()},
                             "copies_per_packet": round(int(rst["forward_bytes"]) / (hb + rb) / N, 4),
                             "copy_GBps": round(rp_bytes / rp_us["relay_copy"] / 1e3, 1)}
-        del pk_send, pk_table, kids
+        # a stream of packet buffers on two contexts against mw_relay_packets call by call
+        ctx_r = B.Context(R, w.n_experts, K, my_rank, w.hidden, fmt, T, 1, e2r, device=dev, max_hops=16, row_stride=stride)
+        ctx_r.mw_set_forwarding(next_hop, n_hops)
+        kids2 = [torch.zeros((T, hb + rb), dtype=torch.uint8, device=dev) for _ in range(n_hops)]
+        tabs = [kid_table, torch.tensor([k.data_ptr() for k in kids2], dtype=torch.int64, device=dev)]
+        sts, rc = [rstats, torch.zeros_like(rstats)], [ctx, ctx_r]
+        n_s = 40
+        for form in ("stream", "calls"):
+            if form == "stream":
+                ctx.mw_relay_packets_index(in_pk, T, sts[0])
+            for i in range(n_s + 4):
+                if i == 4:
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                if form == "stream":
+                    rc[i % 2].mw_relay_packets_copy_index_next(in_pk, tabs[i % 2], sts[i % 2], rc[(i + 1) % 2], in_pk, T,
+                                                               sts[(i + 1) % 2])
+                else:
+                    rc[i % 2].mw_relay_packets(in_pk, tabs[i % 2], T, sts[i % 2])
+            torch.cuda.synchronize()
+            packets["relay"]["step_us_" + form] = round((time.perf_counter() - t0) * 1e6 / n_s, 2)
+            if form == "stream":             # the buffer indexed by the last launch is copied too
+                rc[(n_s + 4) % 2].mw_relay_packets_copy(in_pk, tabs[(n_s + 4) % 2], sts[(n_s + 4) % 2])
+        for c_, s_ in zip(rc, sts):
+            rs_ = c_.mw_get_relay_stats(s_)
+            assert int(rs_["error_flags"]) == 0 and int(rs_["forward_bytes"]) == int(rst["forward_bytes"])
+        packets["relay"]["step_GBps_stream"] = round(rp_bytes / packets["relay"]["step_us_stream"] / 1e3, 1)
+        ctx_r.close()
+        del pk_send, pk_table, kids, kids2
     del pk_regions
 
     # ---------------------------------------------------------------- quantise-in-pack (extra, untimed region)
