@@ -67,6 +67,8 @@ extern "C" {
 #define MW_MAX_HOPS   64         /* next hops (egress ports) a relay's forwarding table may name */
 #define MW_FUSED_MAX_TOKENS 256  /* largest batch mw_plan_pack takes */
 #define MW_RIDE_MAX_TOKENS 8192  /* largest next batch mw_unpack_expand_index_plan_next plans */
+#define MW_STATIC_MAX_TOKENS 8192   /* largest batch mw_plan_static takes */
+#define MW_STATIC_MAX_EXPERTS 1024  /* most experts mw_plan_static takes */
 
 /* status codes */
 #define MW_OK                 0
@@ -220,6 +222,29 @@ MW_API int32_t mw_ctx_set_ride_wait_limit(mw_ctx *ctx, int64_t polls);
 MW_API int32_t mw_plan(mw_ctx *ctx, const int32_t *topk_ids_dev, int32_t n_tokens,
                 uint64_t *mask_dev, int32_t *perm_dev, mw_group_desc *desc_dev,
                 mw_send_stats *stats_dev, void *stream);
+
+/*
+ * mw_plan_static: mw_plan for callers that cannot allocate device memory or keep a workspace
+ * around -- code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * No context and no workspace: the plan's scratch memory (per-token counters, plan state, the
+ * expert table; 70912 bytes) is one array inside the library's device image, which every GPU the
+ * library runs on holds until the process ends.  The call allocates and frees nothing, on the
+ * host or on the device, and enqueues kernels only (one small one that clears the scratch and
+ * builds the expert table, then mw_plan's own).
+ *   cfg                 HOST; n_ranks, n_experts, top_k and the row format fields (hidden,
+ *                       row_format, row_bytes: for the byte accounting) are used as in mw_ctx_create,
+ *                       the other fields -- expert_to_rank included -- are ignored.
+ *   expert_to_rank_dev  DEVICE, [n_experts] int32, read by the enqueued work.  An entry outside
+ *                       [0, n_ranks) names no rank: that expert is ignored and the statistics carry
+ *                       MW_FLAG_BAD_EXPERT.
+ *   the other arguments, the outputs and the device-side flags are mw_plan's, bit for bit.
+ * Limits: n_tokens <= MW_STATIC_MAX_TOKENS and n_experts <= MW_STATIC_MAX_EXPERTS, else
+ * MW_ERR_CAPACITY and nothing is enqueued.  Every call on one GPU shares that GPU's array:
+ * calls that overlap on one GPU (two streams, two threads) race; calls on one stream do not.
+ */
+MW_API int32_t mw_plan_static(const mw_config *cfg, const int32_t *expert_to_rank_dev,
+                              const int32_t *topk_ids_dev, int32_t n_tokens, uint64_t *mask_dev,
+                              int32_t *perm_dev, mw_group_desc *desc_dev, mw_send_stats *stats_dev, void *stream);
 
 /*
  * mw_pack: every kept token's payload written once, in plan order

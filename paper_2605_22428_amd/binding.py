@@ -29,13 +29,14 @@ EXPORTS = ["mw_workspace_bytes", "mw_ctx_create", "mw_ctx_destroy", "mw_plan", "
            "mw_sim_deliver", "mw_copy_bytes", "mw_get_send_stats", "mw_get_recv_stats",
            "mw_set_forwarding", "mw_relay", "mw_relay_index", "mw_relay_copy", "mw_relay_copy_index_next", "mw_relay_packets", "mw_relay_packets_index", "mw_relay_packets_copy", "mw_relay_packets_copy_index_next", "mw_get_relay_stats",
            "mw_allgather_split_point", "mw_plan_allgather_split", "mw_unpack_allgather_split",
-           "mw_ctx_set_timing_events", "mw_status_string"]
+           "mw_ctx_set_timing_events", "mw_status_string", "mw_plan_static"]
 MW_KERNEL_PLAN_RANK, MW_KERNEL_PLAN_GROUPS, MW_KERNEL_PACK, MW_KERNEL_RECV_INDEX, MW_KERNEL_EXPAND = 0, 1, 2, 3, 4
 MW_KERNEL_AG_PACK, MW_KERNEL_AG_GATHER, MW_KERNEL_RELAY_INDEX, MW_KERNEL_RELAY_COPY = 5, 6, 7, 8
 MW_KERNEL_PLAN_PACK, MW_KERNEL_PACK_QUANT, MW_KERNEL_COMBINE = 9, 10, 11
 MW_MAX_HOPS = 64
 MW_FUSED_MAX_TOKENS = 256
 MW_RIDE_MAX_TOKENS = 8192
+MW_STATIC_MAX_TOKENS, MW_STATIC_MAX_EXPERTS = 8192, 1024
 MW_FLAG_BAD_RANK = 0x80
 MW_FLAG_PLAN_TIMEOUT = 0x100
 
@@ -123,6 +124,15 @@ def mw_allgather_split_point(shard_bytes: int, bw_direct: float, bw_relay: float
     _check(load().mw_allgather_split_point(C.c_int64(shard_bytes), C.c_double(bw_direct), C.c_double(bw_relay),
                                            C.c_int32(copies), C.byref(a)), "mw_allgather_split_point")
     return a.value
+
+
+def mw_plan_static(n_ranks: int, n_experts: int, top_k: int, hidden: int, row_format: int, row_bytes: int,
+                   expert_to_rank: torch.Tensor, topk_ids: torch.Tensor, mask: torch.Tensor, perm: torch.Tensor,
+                   desc: torch.Tensor, stats: torch.Tensor):
+    """mw_plan without a context or a workspace; expert_to_rank is a device tensor of int32."""
+    cfg = MwConfig(n_ranks, n_experts, top_k, 0, hidden, row_format, row_bytes, 0, 0, 0, 0, 0)
+    _check(load().mw_plan_static(C.byref(cfg), _ptr(expert_to_rank), _ptr(topk_ids), C.c_int32(topk_ids.shape[0]),
+                                 _ptr(mask), _ptr(perm), _ptr(desc), _ptr(stats), _stream()), "mw_plan_static")
 
 
 class Context:

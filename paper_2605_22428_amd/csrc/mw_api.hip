@@ -21,8 +21,10 @@ struct ws_layout {
         hop_bits, group_of_row, child_pos, sort_key, sort_sec, chunk_kept, row_cnt, row_start, total;
 };
 
+}  // namespace
+
 // Derived row geometry; returns a status.
-int32_t row_geometry(const mw_config &c, int64_t *x_bytes, int64_t *s_bytes)
+int32_t mw_row_geometry(const mw_config &c, int64_t *x_bytes, int64_t *s_bytes)
 {
     switch (c.row_format) {
     case MW_ROW_BF16:
@@ -51,6 +53,8 @@ int32_t row_geometry(const mw_config &c, int64_t *x_bytes, int64_t *s_bytes)
     }
     return MW_OK;
 }
+
+namespace {
 
 int32_t validate(const mw_config *c, int32_t *n_local)
 {
@@ -123,7 +127,7 @@ MW_API int32_t mw_workspace_bytes(const mw_config *cfg, int64_t *out_bytes)
     int32_t rc = validate(cfg, &L);
     if (rc != MW_OK) return rc;
     int64_t xb, sb;
-    rc = row_geometry(*cfg, &xb, &sb);
+    rc = mw_row_geometry(*cfg, &xb, &sb);
     if (rc != MW_OK) return rc;
     *out_bytes = layout(*cfg, L).total;
     return MW_OK;
@@ -137,7 +141,7 @@ MW_API int32_t mw_ctx_create(const mw_config *cfg, void *workspace_dev, int64_t 
     int32_t rc = validate(cfg, &L);
     if (rc != MW_OK) return rc;
     int64_t xb = 0, sb = 0;
-    rc = row_geometry(*cfg, &xb, &sb);
+    rc = mw_row_geometry(*cfg, &xb, &sb);
     if (rc != MW_OK) return rc;
     const ws_layout w = layout(*cfg, L);
     if (!workspace_dev || ((uintptr_t)workspace_dev & 255u) || workspace_bytes < w.total) return MW_ERR_WORKSPACE;

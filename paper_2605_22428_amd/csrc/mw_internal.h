@@ -186,6 +186,9 @@ __device__ __forceinline__ uint32_t mw_block_exscan(uint32_t v, uint32_t *wave_t
 }
 #endif
 
+// payload and scale bytes of a row of `c` (checks the row format's constraints); returns a status
+int32_t mw_row_geometry(const mw_config &c, int64_t *x_bytes, int64_t *s_bytes);
+
 // kernels' host launchers (one per source file)
 int32_t mw_launch_plan(mw_ctx *ctx, const int32_t *topk, int32_t T, uint64_t *mask, int32_t *perm,
                        mw_group_desc *desc, mw_send_stats *stats, hipStream_t s);
