@@ -93,7 +93,7 @@ extern "C" {
                                            surplus rows dropped; a group cut by the limit is dropped whole and
                                            sets MW_FLAG_BAD_DESC too */
 #define MW_FLAG_DUP_SRC_TOKEN    0x40u  /* two rows of one peer carry the same source token for one expert */
-#define MW_FLAG_PLAN_TIMEOUT     0x100u /* mw_unpack_expand_index_plan_next: the riding plan gave up waiting (see there) */
+#define MW_FLAG_PLAN_TIMEOUT     0x100u /* mw_unpack_expand_index_plan_next, mw_stream_step: the riding plan gave up waiting (see there) */
 #define MW_FLAG_BAD_RANK         0x80u  /* relay: a bitmap names a rank >= n_ranks: that bit is not forwarded */
 
 /*
@@ -384,9 +384,11 @@ MW_API int32_t mw_unpack_expand_index_next(mw_ctx *ctx, int32_t n_peers, void *o
  * Inside the launch the plan's second half waits for its first half (workgroups that come
  * earlier in the same launch and wait for nothing themselves); the wait is bounded (about a
  * second by default, mw_ctx_set_ride_wait_limit).  Past the bound -- not observed, and not
- * expected on hardware that starts a launch's workgroups in order -- next_send_stats_dev
- * reports MW_FLAG_PLAN_TIMEOUT with zero rows, the other plan outputs are undefined, and the plan
- * part of next_ctx's workspace is left in an undefined state: destroy that context.
+ * expected on hardware that starts a launch's workgroups in order -- the plan is given up:
+ * next_send_stats_dev reports MW_FLAG_PLAN_TIMEOUT with zero rows and the other plan outputs
+ * are undefined.  Nothing else is lost: the receive side of the launch is unaffected, the launch
+ * itself leaves the plan part of next_ctx's workspace clean once its last workgroup is done with
+ * it, and the next plan on next_ctx (riding or not) works as usual.
  * MW_ERR_UNSUPPORTED if next_n_tokens > MW_RIDE_MAX_TOKENS (larger batches: mw_plan), or where
  * mw_unpack_expand_index_next returns it; MW_ERR_CAPACITY if next_n_tokens > max_tokens of
  * next_ctx.

@@ -158,6 +158,49 @@ __device__ __forceinline__ void mw_lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// ---- publication between workgroups of ONE launch ------------------------------------------
+// A workgroup that has produced (or finished reading) data another workgroup of the same launch
+// depends on reports through a counter; the other side reads the counter and then the data.
+//   producer   every lane: its stores / atomics;  mw_publish_barrier();  one lane: mw_report(counter)
+//   consumer   one lane: reads the counter (mw_report's return value, or a poll followed by
+//              mw_acquire_after_poll());  workgroup barrier;  every lane: reads the data
+// In memory-model terms: the barrier orders every lane's accesses before the reporting lane's
+// (workgroup scope); the report is a release (and, as a read-modify-write whose value decides who
+// is last, an acquire) at agent scope; the consumer's counter read is an acquire at agent scope;
+// happens-before is transitive over the two scopes, so everything the producer's lanes did is
+// visible to every lane of the consumer after its barrier, whatever cache either side runs behind.
+// The data itself is additionally written and read with agent-scope atomics, which are performed
+// at the device's coherence point, so the release and acquire fences find next to nothing to
+// write back or invalidate on their own account.
+// MW_PUBLISH_FENCES 0 builds the same protocol from relaxed atomics and an explicit wait for all
+// outstanding memory operations of every lane (s_waitcnt vmcnt(0)) in front of the barrier:
+// correct on gfx950, where an agent-scope atomic or a write-through store is complete once
+// acknowledged, but an argument about this hardware rather than about the memory model.
+#ifndef MW_PUBLISH_FENCES
+#define MW_PUBLISH_FENCES 0
+#endif
+__device__ __forceinline__ void mw_publish_barrier()
+{
+#if !MW_PUBLISH_FENCES
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#endif
+    __syncthreads();
+}
+__device__ __forceinline__ uint32_t mw_report(uint32_t *counter)
+{
+#if MW_PUBLISH_FENCES
+    return __hip_atomic_fetch_add(counter, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+#else
+    return __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#endif
+}
+__device__ __forceinline__ void mw_acquire_after_poll()
+{
+#if MW_PUBLISH_FENCES
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+#endif
+}
+
 // Exclusive prefix sum over one value per thread of a block (blockDim.x multiple of 64,
 // at most 1024).  `wave_tot` is LDS scratch of 17 words.  Returns the exclusive prefix;
 // *total receives the block total.  Ends with a barrier so the scratch can be reused.  The

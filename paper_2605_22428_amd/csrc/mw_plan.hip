@@ -170,16 +170,14 @@ __global__ __launch_bounds__(kBlock) void k_groups(const uint64_t *__restrict__ 
 
     // Leave the counters and the plan state zero for the next plan.  Nobody may clear them
     // while a workgroup still reads them: every workgroup reports when it has read all it
-    // needs (its loads have returned: their values were used above, and the barrier waits for
-    // the rest), and the one that reports last does the clearing.  The counter of reports is a
-    // device-scope atomic; the zeros are ordinary stores, read by the next plan's kernels only.
-    // With row-indexed arrays this kernel does not read the counters at all, and every
-    // workgroup clears its own slice.
+    // needs (its loads have returned: their values were used above), and the one that reports
+    // last does the clearing (publication rules in mw_internal.h: the reports order every
+    // workgroup's reads before the last one's stores).  The zeros are ordinary stores, read by
+    // the next plan's kernels only.  With row-indexed arrays this kernel does not read the
+    // counters at all, and every workgroup clears its own slice.
     __shared__ uint32_t i_am_last;
-    __syncthreads();
-    if (tid == 0)
-        i_am_last = __hip_atomic_fetch_add(&pstate[kPsDone], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
-                    gridDim.x - 1u ? 1u : 0u;
+    mw_publish_barrier();
+    if (tid == 0) i_am_last = mw_report(&pstate[kPsDone]) == gridDim.x - 1u ? 1u : 0u;
     if constexpr (kByRow) {
         if (i0 + tid < (uint32_t)T) cnt[i0 + tid] = 0;
     }

@@ -226,16 +226,31 @@ __device__ __forceinline__ uint32_t mw_ld_agent32(const uint32_t *p)
 static inline uint32_t mw_plan_finish_rows(int bs) { return bs >= 512 ? (uint32_t)bs : 512u / (uint32_t)bs * (uint32_t)bs; }
 static inline size_t mw_plan_finish_lds(int bs) { return 12u * (size_t)mw_plan_finish_rows(bs) + 19u * sizeof(uint32_t); }
 
+// Clears the counters of `T` tokens and the plan state: what every plan expects to find.
+__device__ __forceinline__ void mw_plan_clear(unsigned long long *cnt, uint32_t *pstate, uint32_t T)
+{
+    for (uint32_t z = threadIdx.x; z < T; z += blockDim.x) cnt[z] = 0;
+    for (uint32_t r = threadIdx.x; r < MW_PLAN_STATE_WORDS; r += blockDim.x) pstate[r] = 0;
+}
+
 // Second half of a riding plan: finishing workgroup `fb` (of n_finish, `bs` lanes each) owns
 // the packed rows [fb finish_rows, (fb + 1) finish_rows) -- what k_groups does in a launch of its own.  Here the
 // rank workgroups are part of the SAME launch, so:
-//  * it waits until all of them have reported (pstate[kPsDone] == n_rank).  They come before
+//  * it waits until all of them have reported (pstate[kPsDone] >= n_rank).  They come before
 //    it in the launch's workgroup order, are dispatched before it, and wait for nothing, so
 //    the wait ends; it is bounded all the same (wait_limit polls of ~0.5 us): past the bound
-//    the plan is given up -- statistics with MW_FLAG_PLAN_TIMEOUT and zero rows, state left
-//    as it is -- and the workgroup exits;
+//    this workgroup gives the plan up -- it raises MW_FLAG_PLAN_TIMEOUT in the plan state and
+//    writes none of its rows;
 //  * what those workgroups wrote is read at device scope: the counters and the state are
 //    device-scope atomics anyway, the bitmaps were written through (mw_rank_body<.., true>).
+// The finishing workgroup that is last to be done (a second counter) writes the statistics: the
+// plan's, or -- if ANY finishing workgroup gave up -- MW_FLAG_PLAN_TIMEOUT with zero rows.  It
+// also leaves the counters and the state zero for the next plan.  After a give-up some rank
+// workgroups may still be running, and nobody may clear under them: the last finishing workgroup
+// then adds one more report to the rank workgroups' counter, and whoever brings that counter to
+// n_rank + 1 -- this workgroup if all ranks were done after all, else the rank workgroup that
+// reports last (mw_plan_ride) -- does the clearing.  Either way the launch leaves the context
+// ready for its next plan.
 // `lds`: mw_plan_finish_lds(bs) bytes.
 __device__ __forceinline__ void mw_plan_finish_ride(const mw_plan_args &a, uint32_t fb, uint64_t *lds)
 {
@@ -243,7 +258,7 @@ __device__ __forceinline__ void mw_plan_finish_ride(const mw_plan_args &a, uint3
     const uint32_t rpw = a.finish_rows;
     unsigned long long *tokc = (unsigned long long *)lds;          // [rpw] the row's counters
     int32_t *tok = (int32_t *)(lds + rpw);                         // [rpw] token of packed row i0 + k
-    uint32_t *scratch = (uint32_t *)(lds + rpw) + rpw;             // [17] scans, [18] "the ranks are complete"
+    uint32_t *scratch = (uint32_t *)(lds + rpw) + rpw;             // [17] scans, [18] one-lane decisions
     const uint32_t T = (uint32_t)a.T;
 
     if (tid == 0) {
@@ -252,102 +267,104 @@ __device__ __forceinline__ void mw_plan_finish_ride(const mw_plan_args &a, uint3
             __builtin_amdgcn_s_sleep(16);
             ++polls;
         }
-        scratch[18] = mw_ld_agent32(&a.pstate[kPsDone]) >= a.n_rank ? 1u : 0u;
+        const bool ready = mw_ld_agent32(&a.pstate[kPsDone]) >= a.n_rank;
+        if (ready) mw_acquire_after_poll();
+        else __hip_atomic_fetch_or(&a.pstate[kPsFlags], MW_FLAG_PLAN_TIMEOUT, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        scratch[18] = ready ? 1u : 0u;
     }
     __syncthreads();
-    if (!scratch[18]) {
-        if (fb == 0 && tid == 0) {
-            a.stats->n_rows = 0; a.stats->n_groups = 0;
-            a.stats->multicast_bytes = 0; a.stats->unicast_bytes = 0;
-            a.stats->error_flags = MW_FLAG_PLAN_TIMEOUT; a.stats->reserved0 = 0;
+    const bool ready = scratch[18] != 0;
+    uint32_t N = 0, G = 0;
+    if (ready) {
+        N = min(mw_ld_agent32(&a.pstate[kPsKept]), T);
+        const uint32_t n_empty = T - N;
+        const uint32_t i0 = fb * rpw;
+        for (uint32_t k = tid; k < rpw; k += bs) { tok[k] = 0; tokc[k] = 0; }   // (a row no token claims -- corrupted counters only -- reads token 0)
+        mw_lds_barrier();
+        // all tokens' counters: which land in this workgroup's rows, how many groups start before
+        // its first row, how many groups there are (sixteen counters per lane in flight)
+        uint32_t starts_before = 0, starts_total = 0;
+        for (uint32_t t0 = 0; t0 < T; t0 += 16 * bs) {
+            unsigned long long cc[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const uint32_t t = t0 + u * bs + tid;
+                cc[u] = t < T ? mw_ld_agent64(&a.cnt[t]) : 0ull;
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const unsigned long long c = cc[u];
+                if ((c >> 42) == 0) continue;                         // empty bitmap (or past the end)
+                const uint32_t p = (uint32_t)(c & kField) - n_empty;  // packed row of the token
+                const uint32_t st = ((c >> 21) & kField) == 0 ? 1u : 0u;
+                starts_total += st;
+                starts_before += (st && p < i0) ? 1u : 0u;
+                if (p - i0 < rpw && p < N) { tok[p - i0] = (int32_t)(t0 + u * bs + tid); tokc[p - i0] = c; }
+            }
         }
-        return;
-    }
+        uint32_t g_next;
+        mw_block_exscan(starts_before, scratch, &g_next);
+        mw_block_exscan(starts_total, scratch, &G);                // ends with a barrier: tok[] is complete
 
-    const uint32_t N = min(mw_ld_agent32(&a.pstate[kPsKept]), T), n_empty = T - N;
-    const uint32_t i0 = fb * rpw;
-    for (uint32_t k = tid; k < rpw; k += bs) { tok[k] = 0; tokc[k] = 0; }   // (a row no token claims -- corrupted counters only -- reads token 0)
-    mw_lds_barrier();
-    // all tokens' counters: which land in this workgroup's rows, how many groups start before
-    // its first row, how many groups there are (sixteen counters per lane in flight)
-    uint32_t starts_before = 0, starts_total = 0;
-    for (uint32_t t0 = 0; t0 < T; t0 += 16 * bs) {
-        unsigned long long cc[16];
+        for (uint32_t k0 = 0; k0 < rpw && i0 + k0 < N; k0 += bs) {  // (uniform bounds: every lane takes every turn)
+            const uint32_t i = i0 + k0 + tid;
+            uint32_t st = 0;
+            int32_t t = 0;
+            unsigned long long c = 0;
+            if (i < N) {
+                t = tok[k0 + tid];
+                if ((uint32_t)t >= T) t = 0;
+                a.perm[i] = t;
+                c = tokc[k0 + tid];
+                st = ((c >> 21) & kField) == 0 ? 1u : 0u;
+            }
+            uint32_t turn_total;
+            const uint32_t g = g_next + mw_block_exscan(st, scratch, &turn_total);
+            g_next += turn_total;
+            if (st) {
+                const unsigned long long *m = (const unsigned long long *)(a.mask_out + (size_t)t * MW_MASK_WORDS);
+                mw_group_desc d;
+                uint32_t nd = 0;
 #pragma unroll
-        for (int u = 0; u < 16; ++u) {
-            const uint32_t t = t0 + u * bs + tid;
-            cc[u] = t < T ? mw_ld_agent64(&a.cnt[t]) : 0ull;
-        }
-#pragma unroll
-        for (int u = 0; u < 16; ++u) {
-            const unsigned long long c = cc[u];
-            if ((c >> 42) == 0) continue;                         // empty bitmap (or past the end)
-            const uint32_t p = (uint32_t)(c & kField) - n_empty;  // packed row of the token
-            const uint32_t st = ((c >> 21) & kField) == 0 ? 1u : 0u;
-            starts_total += st;
-            starts_before += (st && p < i0) ? 1u : 0u;
-            if (p - i0 < rpw && p < N) { tok[p - i0] = (int32_t)(t0 + u * bs + tid); tokc[p - i0] = c; }
+                for (int w = 0; w < MW_MASK_WORDS; ++w) { d.mask[w] = mw_ld_agent64(m + w); nd += (uint32_t)__popcll(d.mask[w]); }
+                d.row_offset = i;
+                d.row_count = (uint32_t)((c >> 42) & kField);
+                d.n_dest = nd;
+                d.reserved0 = 0;
+                if (g < T) a.desc[g] = d;
+            }
         }
     }
-    uint32_t g_next, G;
-    mw_block_exscan(starts_before, scratch, &g_next);
-    mw_block_exscan(starts_total, scratch, &G);                // ends with a barrier: tok[] is complete
-
-    for (uint32_t k0 = 0; k0 < rpw && i0 + k0 < N; k0 += bs) {  // (uniform bounds: every lane takes every turn)
-        const uint32_t i = i0 + k0 + tid;
-        uint32_t st = 0;
-        int32_t t = 0;
-        unsigned long long c = 0;
-        if (i < N) {
-            t = tok[k0 + tid];
-            if ((uint32_t)t >= T) t = 0;
-            a.perm[i] = t;
-            c = tokc[k0 + tid];
-            st = ((c >> 21) & kField) == 0 ? 1u : 0u;
-        }
-        uint32_t turn_total;
-        const uint32_t g = g_next + mw_block_exscan(st, scratch, &turn_total);
-        g_next += turn_total;
-        if (st) {
-            const unsigned long long *m = (const unsigned long long *)(a.mask_out + (size_t)t * MW_MASK_WORDS);
-            mw_group_desc d;
-            uint32_t nd = 0;
-#pragma unroll
-            for (int w = 0; w < MW_MASK_WORDS; ++w) { d.mask[w] = mw_ld_agent64(m + w); nd += (uint32_t)__popcll(d.mask[w]); }
-            d.row_offset = i;
-            d.row_count = (uint32_t)((c >> 42) & kField);
-            d.n_dest = nd;
-            d.reserved0 = 0;
-            if (g < T) a.desc[g] = d;
-        }
-    }
-    if (fb == 0) {
-        uint32_t dests = 0;
-        for (uint32_t r = tid; r < MW_MAX_RANKS; r += bs) {
-            const uint32_t h = mw_ld_agent32(&a.pstate[r]);
-            a.stats->rows_per_dest[r] = h;
-            dests += h;
-        }
-        uint32_t D;
-        mw_block_exscan(dests, scratch, &D);
-        if (tid == 0) {
-            a.stats->n_rows = N;
-            a.stats->n_groups = G;
-            a.stats->multicast_bytes = (uint64_t)N * a.row_bytes;
-            a.stats->unicast_bytes = (uint64_t)D * a.row_bytes;
-            a.stats->error_flags = mw_ld_agent32(&a.pstate[kPsFlags]);
-            a.stats->reserved0 = 0;
-        }
-    }
-    // the finishing workgroup that is last to have read the counters and the state clears them
-    __syncthreads();
-    if (tid == 0)
-        scratch[18] = __hip_atomic_fetch_add(&a.pstate[kPsDone2], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
-                      a.n_finish - 1u ? 1u : 0u;
+    // Done with the counters and the state (the loads above have returned: their values were used).
+    mw_publish_barrier();
+    if (tid == 0) scratch[18] = mw_report(&a.pstate[kPsDone2]) == a.n_finish - 1u ? 1u : 0u;
     __syncthreads();
     if (!scratch[18]) return;
-    for (uint32_t z = tid; z < T; z += bs) a.cnt[z] = 0;
-    for (uint32_t r = tid; r < MW_PLAN_STATE_WORDS; r += bs) a.pstate[r] = 0;
+
+    // ---- the last finishing workgroup: statistics, then the state left zero for the next plan
+    const uint32_t flags = mw_ld_agent32(&a.pstate[kPsFlags]);
+    const bool gave_up = (flags & MW_FLAG_PLAN_TIMEOUT) != 0;      // (then `ready` may be false here, too)
+    uint32_t dests = 0;
+    for (uint32_t r = tid; r < MW_MAX_RANKS; r += bs) {
+        const uint32_t h = gave_up ? 0u : mw_ld_agent32(&a.pstate[r]);
+        a.stats->rows_per_dest[r] = h;
+        dests += h;
+    }
+    uint32_t D;
+    mw_block_exscan(dests, scratch, &D);
+    if (tid == 0) {
+        a.stats->n_rows = gave_up ? 0u : N;
+        a.stats->n_groups = gave_up ? 0u : G;
+        a.stats->multicast_bytes = gave_up ? 0ull : (uint64_t)N * a.row_bytes;
+        a.stats->unicast_bytes = gave_up ? 0ull : (uint64_t)D * a.row_bytes;
+        a.stats->error_flags = flags;
+        a.stats->reserved0 = 0;
+        // after a give-up: one more report on the rank workgroups' counter; n_rank reports found
+        // there means every rank workgroup is done and the clearing is this workgroup's
+        scratch[18] = (!gave_up || mw_report(&a.pstate[kPsDone]) == a.n_rank) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (scratch[18]) mw_plan_clear(a.cnt, a.pstate, T);
 }
 
 // One riding plan workgroup.  `lds` is the launch's dynamic LDS: the slice's keys for a rank
@@ -358,11 +375,15 @@ __device__ __forceinline__ void mw_plan_ride(const mw_plan_args &a, uint32_t wg,
     if (wg < a.n_rank) {
         mw_rank_body<W, kKeyed, true>(a.topk, a.T, a.K, a.eslot, a.E, a.slice, a.mask_out, a.cnt, a.pstate,
                                       (int)(wg % (uint32_t)a.tb), (int)(wg / (uint32_t)a.tb), (int)blockDim.x, lds);
-        // Reports when its atomics and write-through stores have been acknowledged (the barrier
-        // waits for them); the counter is a device-scope atomic, no fence is needed.
+        // Reports when all its lanes are done (publication rules in mw_internal.h).  A report
+        // that finds n_rank others -- all rank workgroups and the extra one of finishing
+        // workgroups that gave the plan up -- comes after everybody else is done with the
+        // counters and the state: this workgroup clears them (see mw_plan_finish_ride).
+        uint32_t *last = (uint32_t *)lds;
+        mw_publish_barrier();
+        if (threadIdx.x == 0) *last = mw_report(&a.pstate[kPsDone]) == a.n_rank ? 1u : 0u;
         __syncthreads();
-        if (threadIdx.x == 0)
-            __hip_atomic_fetch_add(&a.pstate[kPsDone], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (*last) mw_plan_clear(a.cnt, a.pstate, (uint32_t)a.T);
         return;
     }
     wg -= a.n_rank;

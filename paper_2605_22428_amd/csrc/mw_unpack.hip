@@ -414,17 +414,12 @@ __device__ __forceinline__ void recv_index_body(
 
     // ---- the workgroup that finishes last turns the counts into output bases ----------
     // Everything the last workgroup reads (counts, addressed-row counts, flags) is written and
-    // read with device-scope atomics, which are performed at the device's coherence point and
-    // bypass the per-XCD L2.  __syncthreads() makes every wave wait until its stores have been
-    // acknowledged there, so thread 0's counter increment is performed after them; no
-    // device-scope fence (a write-back of the whole L2) is needed.  The row records and hit
-    // slots, written with ordinary stores, are read by the next kernel only.
-    __syncthreads();
-    if (tid == 0) {
-        const bool last = __hip_atomic_fetch_add(&flags[2], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
-                          (uint32_t)P - 1u;
-        scratch[17] = last ? 1u : 0u;
-    }
+    // read with device-scope atomics, and every workgroup reports through one counter when all
+    // its lanes are done (publication rules in mw_internal.h); the workgroup whose report is the
+    // P-th has thereby acquired what all the others released.  The row records and hit slots,
+    // written with ordinary stores, are read by the next kernel only.
+    mw_publish_barrier();
+    if (tid == 0) scratch[17] = mw_report(&flags[2]) == (uint32_t)P - 1u ? 1u : 0u;
     __syncthreads();
     if (!scratch[17]) return;
     mw_finish_counts(cnt, addr_cnt, flags, row_base, (uint32_t)L, (uint32_t)P, out_cap, base, expert_offsets, stats,

@@ -300,6 +300,31 @@ def payload_full(w: DispatchWorkload, seed: int, peer: int,
     return x, s
 
 
+_POOLS: Dict[tuple, np.ndarray] = {}
+
+
+def payload_rows_pooled(w: DispatchWorkload, seed: int, peer: int,
+                        tokens: Optional[np.ndarray] = None, pool_rows: int = 2048) -> np.ndarray:
+    """bf16 payload for cases with so many rows that drawing each of them would take minutes
+    (a hundred thousand rows of 7168 values): row (peer, t) is row hash(peer, t) % pool_rows of
+    a pool of N(0,1) rows drawn once per (seed, workload), with its first four bf16 elements
+    replaced by the row's own 64-bit hash, so that no two rows of a run are equal and a row that
+    ends up in the wrong place shows.  uint16 [n][H] bit patterns.  bf16 workloads only."""
+    assert w.row_format == "bf16" and w.hidden >= 4
+    if tokens is None:
+        tokens = np.arange(w.n_tokens, dtype=np.int64)
+    tokens = np.asarray(tokens, dtype=np.int64)
+    key = (seed, w.wid, w.hidden, pool_rows)
+    if key not in _POOLS:
+        _POOLS.clear()                                  # one pool at a time: they are large
+        _POOLS[key] = f32_to_bf16_bits(_row_normals(w.wid, seed, 0x7FFFFFFF, np.arange(pool_rows), w.hidden))
+    pool = _POOLS[key]
+    h = _bits(_key(seed, w.wid, 0xB001, peer), tokens)
+    rows = pool[(h % _U64(pool_rows)).astype(np.int64)]        # (fancy indexing copies)
+    rows[:, :4] = h[:, None].view(np.uint16).reshape(len(tokens), 4)
+    return rows
+
+
 def allgather_shard(w: AllGatherWorkload, seed: int, rank: int) -> np.ndarray:
     """uint16 [shard_elems]: bf16 bit patterns of N(0,1) values of `rank`."""
     k = _key(seed, w.wid, 0xA6, rank)

@@ -52,12 +52,16 @@ class GpuSend:
 
     def __init__(self, ctx: B.Context, topk: np.ndarray, x: np.ndarray, scales: Optional[np.ndarray],
                  x_dev: Optional[torch.Tensor] = None, scales_dev: Optional[torch.Tensor] = None,
-                 fused: bool = False):
-        self.ctx, self.T = ctx, topk.shape[0]
+                 fused: bool = False, prefill: int = 0):
+        self.ctx, self.T, self.prefill = ctx, topk.shape[0], prefill
         self.topk_d = dev(topk.astype(np.int32))
         self.x_d = x_dev if x_dev is not None else dev(x)
         self.s_d = scales_dev if scales_dev is not None else dev(scales)
         self.buf = B.SendBuffers(ctx, self.T)
+        if prefill:          # a row the packer misses, or writes to the wrong place, then shows as the pattern
+            self.buf.packed.fill_(prefill)
+            self.buf.row_src_token.fill_(-prefill)
+            self.buf.row_topk.fill_(-prefill)
         if fused:
             ctx.mw_plan_pack(self.topk_d, self.x_d, self.s_d, self.buf.mask, self.buf.perm, self.buf.desc,
                              self.buf.stats, self.buf.packed, self.buf.row_src_token, self.buf.row_topk)
@@ -172,7 +176,9 @@ def check_send(w: W.DispatchWorkload, g: GpuSend, topk: np.ndarray, x: np.ndarra
     gp, gs, gt = g.host_pack()
     assert_same_bytes(gp, packed, "packed rows")
     if g.ctx.row_stride > g.ctx.row_bytes:                 # the bytes between rows are never written
-        assert not host(g.buf.packed)[: g.N, g.ctx.row_bytes:].any(), "bytes between packed rows were written"
+        assert (host(g.buf.packed)[: g.N, g.ctx.row_bytes:] == g.prefill).all(), "bytes between packed rows were written"
+    if g.prefill and g.N < g.T:                            # nor are the rows behind the last packed one
+        assert (host(g.buf.packed)[g.N:] == g.prefill).all(), "rows behind the last packed row were written"
     assert_same_bytes(gs, src, "row_src_token")
     assert_same_bytes(gt, rtk, "row_topk")
     return perm, desc, packed, src, rtk

@@ -161,49 +161,102 @@ def test_more_rows_than_the_context_was_created_for():
     ctx.close()
 
 
-def test_riding_plan_gives_up_when_told_not_to_wait():
-    """mw_ctx_set_ride_wait_limit(0): the second half of a plan riding in
-    mw_unpack_expand_index_plan_next does not wait for the first half.  Either the first half
-    was already complete when it looked (then the plan is the oracle's), or the statistics say
-    MW_FLAG_PLAN_TIMEOUT with zero rows; every kernel ends normally in both cases, and the
-    receive side of the same launch is not affected."""
-    w = W.DispatchWorkload("giveup", 41, 8, 16, 2, 1000, 256, "bf16", "uniform")
-    e2r = W.expert_to_rank(w)
-    ctxs = [H.make_ctx(w, 1), H.make_ctx(w, 1)]
+def _ride_setup(w, n_peers, peer_tokens, my_rank=1):
+    """Two contexts, a small received batch indexed in the first, buffers for a plan in the second."""
+    ctxs = [H.make_ctx(w, my_rank, max_recv_rows=n_peers * peer_tokens), H.make_ctx(w, my_rank, max_recv_rows=n_peers * peer_tokens)]
     recs, toks = [], []
-    for p in range(w.n_ranks):
-        tk = W.topk_ids(w, 1, p)
-        x, _ = W.payload_rows(w, 1, p)
-        recs.append(H.shrink(H.GpuSend(ctxs[0], tk, x, None).deliver(1)))
+    for p in range(n_peers):
+        tk = W.topk_ids(w, 1, p)[:peer_tokens]
+        x, _ = W.payload_rows(w, 1, p, np.arange(peer_tokens))
+        recs.append(H.shrink(H.GpuSend(ctxs[0], tk, x, None).deliver(my_rank)))
         toks.append((tk, x, None))
-    cap = sum(r["n_rows"] for r in recs) * 2
+    cap = max(1, sum(r["n_rows"] for r in recs) * min(w.top_k, w.experts_per_rank))
     table = B.peers_table(recs, H.DEV)
     bufs = [B.RecvBuffers(ctxs[0], cap), B.RecvBuffers(ctxs[1], cap)]
-    sb = B.SendBuffers(ctxs[1], w.n_tokens)
-    tk_me = W.topk_ids(w, 2, 1)
-    ctxs[0].mw_unpack_index(table, w.n_ranks, cap, bufs[0].expert_offsets, bufs[0].stats)
-    ctxs[1].mw_ctx_set_ride_wait_limit(0)
-    ctxs[0].mw_unpack_expand_index_plan_next(w.n_ranks, bufs[0].out_rows, None, cap, bufs[0].out_src_peer,
-                                             bufs[0].out_src_token, ctxs[1], table, w.n_ranks, cap,
-                                             bufs[1].expert_offsets, bufs[1].stats, H.dev(tk_me), sb.mask, sb.perm,
+    return ctxs, toks, cap, (table, recs), bufs      # (the table points into recs: both stay alive)
+
+
+def _ride(ctxs, w, n_peers, cap, table, bufs, tk_d, sb):
+    """Expander of ctxs[0]'s batch with the index and the plan of `tk_d` riding into ctxs[1]."""
+    table = table[0]
+    ctxs[0].mw_unpack_index(table, n_peers, cap, bufs[0].expert_offsets, bufs[0].stats)
+    ctxs[0].mw_unpack_expand_index_plan_next(n_peers, bufs[0].out_rows, None, cap, bufs[0].out_src_peer,
+                                             bufs[0].out_src_token, ctxs[1], table, n_peers, cap,
+                                             bufs[1].expert_offsets, bufs[1].stats, tk_d, sb.mask, sb.perm,
                                              sb.desc, sb.stats)
     torch.cuda.synchronize()
-    st = ctxs[1].mw_get_send_stats(sb.stats)
-    flags = int(st["error_flags"])
-    print("riding plan without waiting: flags", hex(flags), flush=True)
-    assert flags in (0, B.MW_FLAG_PLAN_TIMEOUT)
-    if flags:
-        assert (int(st["n_rows"]), int(st["n_groups"]), int(st["multicast_bytes"])) == (0, 0, 0)
-    else:
-        _, perm, desc, _ = ref.plan(tk_me, e2r, w.n_ranks, w.row_bytes)
-        assert (int(st["n_rows"]), int(st["n_groups"])) == (len(perm), len(desc))
-        H.assert_same_bytes(H.host(sb.perm)[: len(perm)], perm, "perm")
+    return ctxs[1].mw_get_send_stats(sb.stats)
+
+
+def _check_plan(w, sb, st, tk):
+    m, perm, desc, ost = ref.plan(tk, W.expert_to_rank(w), w.n_ranks, w.row_bytes)
+    assert int(st["error_flags"]) == 0
+    for f in ("n_rows", "n_groups", "multicast_bytes", "unicast_bytes"):
+        assert int(st[f]) == int(ost[f]), f
+    H.assert_same_bytes(st["rows_per_dest"], ost["rows_per_dest"], "rows_per_dest")
+    H.assert_same_bytes(H.host(sb.mask).view(np.uint64)[: len(tk)], m, "mask")
+    H.assert_same_bytes(H.host(sb.perm)[: len(perm)], perm, "perm")
+    H.assert_same_bytes(H.host(sb.desc).reshape(-1).view(B.DESC_DTYPE)[: len(desc)].view(np.uint8), desc.view(np.uint8), "desc")
+
+
+def test_riding_plan_gives_up_and_the_context_plans_again():
+    """mw_ctx_set_ride_wait_limit(0): the second half of a riding plan looks once and does not
+    wait.  The first half is made long by construction -- 8192 tokens over 256 ranks, a thousand
+    ranking workgroups of several memory round trips each, dispatched a fraction of a
+    microsecond before the finishing ones -- so the plan MUST be given up: the statistics say
+    MW_FLAG_PLAN_TIMEOUT with zero rows, every kernel ends normally, the receive side of the same
+    launch is exact.  The context is not lost: the launch leaves its plan state clean, and the
+    next plans on it -- mw_plan, then a riding plan with the default limit -- are the oracle's."""
+    w = W.DispatchWorkload("giveup", 41, 256, 256, 8, 8192, 256, "bf16", "uniform")
+    n_peers, peer_tokens = 6, 300
+    ctxs, toks, cap, table, bufs = _ride_setup(w, n_peers, peer_tokens)
+    sb = B.SendBuffers(ctxs[1], w.n_tokens)
+    tk_me = W.topk_ids(w, 2, 1)
+    tk_d = H.dev(tk_me)
+    ctxs[1].mw_ctx_set_ride_wait_limit(0)
+    st = _ride(ctxs, w, n_peers, cap, table, bufs, tk_d, sb)
+    assert int(st["error_flags"]) == B.MW_FLAG_PLAN_TIMEOUT
+    assert (int(st["n_rows"]), int(st["n_groups"]), int(st["multicast_bytes"]), int(st["unicast_bytes"])) == (0, 0, 0, 0)
+    assert not st["rows_per_dest"].any()
+    e2r = W.expert_to_rank(w)
     want = ref.dispatch_plain(toks, e2r, 1, cap)
-    rs = ctxs[0].mw_get_recv_stats(bufs[0].stats)
-    q = int(rs["n_out_rows"])
-    assert int(rs["error_flags"]) == 0 and q == len(want[2])
-    H.assert_same_bytes(H.host(bufs[0].out_rows)[:q], want[0], "out_rows beside a plan that gave up")
+    for c, b in zip(ctxs, bufs):                          # the expander of the launch and its riding index
+        if c is ctxs[1]:
+            c.mw_unpack_expand(n_peers, b.out_rows, None, cap, b.out_src_peer, b.out_src_token)
+        rs = c.mw_get_recv_stats(b.stats)
+        q = int(rs["n_out_rows"])
+        assert int(rs["error_flags"]) == 0 and q == len(want[2])
+        H.assert_same_bytes(H.host(b.out_rows)[:q], want[0], "out_rows beside a plan that gave up")
+        H.assert_same_bytes(H.host(b.out_src_token)[:q], want[3], "out_src_token beside a plan that gave up")
+    # the same context plans again: call by call ...
+    ctxs[1].mw_plan(tk_d, sb.mask, sb.perm, sb.desc, sb.stats)
+    _check_plan(w, sb, ctxs[1].mw_get_send_stats(sb.stats), tk_me)
+    # ... gives up once more, with another batch (nothing of the first attempt may linger) ...
+    tk2 = W.topk_ids(w, 3, 1)[:5000]
+    st = _ride(ctxs, w, n_peers, cap, table, bufs, H.dev(tk2), sb)
+    assert int(st["error_flags"]) == B.MW_FLAG_PLAN_TIMEOUT and int(st["n_rows"]) == 0
+    # ... and rides with the default limit
+    ctxs[1].mw_ctx_set_ride_wait_limit(1 << 21)
+    sb2 = B.SendBuffers(ctxs[1], w.n_tokens)
+    st = _ride(ctxs, w, n_peers, cap, table, bufs, tk_d, sb2)
+    _check_plan(w, sb2, st, tk_me)
     with pytest.raises(B.MwError):
         ctxs[1].mw_ctx_set_ride_wait_limit(-1)
-    for c in ctxs:                                        # the plan state of ctxs[1] may be left dirty: not used again
+    for c in ctxs:
+        c.close()
+
+
+def test_riding_plan_with_the_default_limit_is_the_oracles():
+    """The same launch with the default wait limit, batch after batch on one pair of contexts
+    (sizes going down and up again, so a finishing workgroup count that changes from launch to
+    launch finds clean state): every plan complete and exact, never a time-out flag."""
+    w = W.DispatchWorkload("ride", 42, 64, 256, 8, 4096, 256, "bf16", "uniform")
+    n_peers, peer_tokens = 5, 200
+    ctxs, toks, cap, table, bufs = _ride_setup(w, n_peers, peer_tokens)
+    for i, n in enumerate((4096, 700, 1, 0, 2049)):
+        tk = W.topk_ids(w, 10 + i, 1)[:n]
+        sb = B.SendBuffers(ctxs[1], max(n, 1))
+        st = _ride(ctxs, w, n_peers, cap, table, bufs, H.dev(tk) if n else torch.zeros((0, w.top_k), dtype=torch.int32, device=H.DEV), sb)
+        _check_plan(w, sb, st, tk)
+    for c in ctxs:
         c.close()

@@ -37,7 +37,12 @@ def run_dispatch(w, seed, my_rank, check_all_senders=True, lazy=False, tier2=Tru
             s_dev = torch.zeros((w.n_tokens, w.hidden // 128), dtype=torch.float32, device=H.DEV)
     for p in range(w.n_ranks):
         tk = topks[p]
-        if lazy:
+        detailed = check_all_senders or p == my_rank or p in sample_peers
+        pre = 0xA5 if detailed else 0
+        tokens = None
+        if lazy and not detailed:
+            # only the rows addressed to my_rank are drawn (the others are zero on both sides);
+            # the generator's choice of rows is checked against what is delivered further down
             tokens = W.tokens_for_rank(w, tk, my_rank)
             rows, sc_rows = W.payload_rows(w, seed, p, tokens)
             x = np.zeros((w.n_tokens, w.hidden), dtype=rows.dtype)
@@ -53,10 +58,10 @@ def run_dispatch(w, seed, my_rank, check_all_senders=True, lazy=False, tier2=Tru
                 s_dev[idx] = H.dev(sc_rows)
             g = H.GpuSend(ctx, tk, x, sc, x_dev=x_dev, scales_dev=s_dev)
         else:
+            # this rank's own batch and the sampled peers: every row drawn, every packed row compared
             x, sc = W.payload_rows(w, seed, p)
-            g = H.GpuSend(ctx, tk, x, sc)
+            g = H.GpuSend(ctx, tk, x, sc, prefill=pre)
         toks.append((tk, x, sc))
-        detailed = check_all_senders or p == my_rank or p in sample_peers
         if detailed or tier2:
             if detailed:
                 perm, desc, packed, src, rtk = H.check_send(w, g, tk, x, sc)
@@ -66,6 +71,8 @@ def run_dispatch(w, seed, my_rank, check_all_senders=True, lazy=False, tier2=Tru
             obuf = ref.deliver(desc, packed, src, rtk, my_rank)
             bufs.append(obuf)
         rec = H.shrink(g.deliver(my_rank))
+        if tokens is not None:
+            assert rec["n_rows"] == len(tokens), "payload was drawn for other rows than those delivered"
         if detailed:
             got = H.record_host(rec, w.row_bytes)
             for a, b, name in zip(got, obuf, ("desc", "rows", "src_token", "row_topk")):
@@ -191,6 +198,137 @@ def test_c3_full_size_receive_median_rank():
     r = W.zipf_median_rank(w, W.BASE_SEED)
     run_dispatch(W.scaled(w, my_rank=r), W.BASE_SEED, r, check_all_senders=False, lazy=True, tier2=False,
                  sample_peers=(0, 255))
+
+
+def _pooled_regions(w, seed, my_rank, ctx, sample_peers):
+    """Every peer's plan + pack + delivery to my_rank with pooled payload (every row drawn, no two
+    equal); the sampled peers' send side is compared with the oracle row by row."""
+    recs, toks = [], []
+    for p, tk in enumerate(W.topk_ids_many(w, seed, range(w.n_ranks))):
+        x = W.payload_rows_pooled(w, seed, p)
+        g = H.GpuSend(ctx, tk, x, None, prefill=0x5A if p in sample_peers else 0)
+        if p in sample_peers:
+            H.check_send(w, g, tk, x, None)
+        recs.append(H.shrink(g.deliver(my_rank)))
+        toks.append((tk, x, None))
+        del g
+    return recs, toks
+
+
+def test_c3_hottest_rank_512_tokens_per_peer_full_rows():
+    """The skew stress point of the large-EP configuration: the rank of the most popular expert
+    receives from 256 peers of 512 tokens each, rows of the full 14336 bytes -- more than a
+    hundred thousand rows (1.6 GB), one peer's region after the other nearly full, several times
+    more rows than the expander's grid has workgroup rows.  Whole output against the plain
+    definition."""
+    w = W.scaled(W.C3, n_tokens=512)
+    r = W.zipf_hottest_rank(w, W.BASE_SEED)
+    ctx = H.make_ctx(w, r)
+    recs, toks = _pooled_regions(w, W.BASE_SEED, r, ctx, sample_peers=(r, 17))
+    m_rows = sum(rec["n_rows"] for rec in recs)
+    _say("hottest rank", r, "rows received", m_rows)
+    assert m_rows > 3 * 32768                                  # (the point of the case)
+    cap = m_rows
+    want = ref.dispatch_plain(toks, W.expert_to_rank(w), r, cap)
+    gu = H.GpuUnpack(ctx, recs, cap)
+    H.check_unpack(gu, want, "hottest rank vs plain definition")
+    assert int(gu.stats["n_recv_rows"]) == m_rows == gu.Q
+    ctx.close()
+
+
+@pytest.mark.parametrize("schedule", ["launch_and_plan", "one_launch"])
+def test_stream_of_full_size_steps_as_the_bench_issues_them(schedule):
+    """The two schedules bench.py times, issued exactly as it issues them, for four steps in a row
+    without a synchronisation in between, at full size.  "launch_and_plan" (the large-EP
+    configuration, 8192 tokens over 256 ranks): mw_stream_step with an EMPTY batch to plan (NULL plan
+    outputs, a statistics block nobody reads) packs batch n, expands received batch n and indexes
+    received batch n + 1, while mw_plan of batch n + 1 runs on a third context on a second stream,
+    one event each way.  "one_launch" (the DeepSeek-V3-shaped configuration): the plan of batch
+    n + 1 rides in the launch.  Every batch this rank sends is different; everything each step
+    wrote is compared with the oracle afterwards."""
+    if schedule == "launch_and_plan":
+        w0 = W.C3
+        my_rank = W.zipf_median_rank(w0, W.BASE_SEED)
+        peer_tokens = 1024        # per peer on the receive side: 256 full regions would be minutes of oracle time
+    else:
+        w0, my_rank, peer_tokens = W.C1, 0, 1024
+    w = W.scaled(w0, my_rank=my_rank)
+    wr = W.scaled(w, n_tokens=peer_tokens)
+    e2r = W.expert_to_rank(w)
+    R, K, T = w.n_ranks, w.top_k, w.n_tokens
+    rctx = [H.make_ctx(w, my_rank), H.make_ctx(w, my_rank)]
+    ctx_p = H.make_ctx(w, my_rank, max_recv_rows=1)
+    recs, toks = _pooled_regions(wr, 5, my_rank, rctx[0], sample_peers=())
+    m_rows = sum(rec["n_rows"] for rec in recs)
+    cap = max(1, m_rows * min(K, w.experts_per_rank))
+    want = ref.dispatch_plain(toks, e2r, my_rank, cap)
+    table = B.peers_table(recs, H.DEV)
+    n_sets, n_steps = 3, 4
+    batches = []
+    for b in range(n_sets):
+        tk = W.topk_ids(w, 20 + b, my_rank)
+        if b == 1:
+            tk = tk[: T - 1000].copy()                    # a shorter batch, with a token that goes nowhere
+            tk[11, :] = -1
+        batches.append((tk, W.payload_rows_pooled(w, 20 + b, my_rank, np.arange(len(tk)))))
+    sets = []
+    for tk, x in batches:
+        sd = B.SendBuffers(rctx[0], T)
+        sd.packed.fill_(0x3C)
+        sets.append(dict(tk=H.dev(tk), x=H.dev(x), send=sd, recv=B.RecvBuffers(rctx[0], cap)))
+    s_send, s_recv = torch.cuda.Stream(), torch.cuda.Stream()
+    ev_plan = [torch.cuda.Event(), torch.cuda.Event()]
+    no_plan_stats = torch.zeros(B.SEND_STATS_BYTES, dtype=torch.uint8, device=H.DEV)
+    torch.cuda.synchronize()
+    # what the step before the first one leaves behind: index and plan of batch 0
+    with torch.cuda.stream(s_recv):
+        rctx[0].mw_unpack_index(table, R, cap, sets[0]["recv"].expert_offsets, sets[0]["recv"].stats)
+        sd = sets[0]["send"]
+        rctx[0].mw_plan(sets[0]["tk"], sd.mask, sd.perm, sd.desc, sd.stats)
+        ev_plan[0].record(s_recv)
+    ev_steps = []
+    for n in range(n_steps):
+        s, sn = sets[n % n_sets], sets[(n + 1) % n_sets]
+        sd, rv, rn, sdn = s["send"], s["recv"], sn["recv"], sn["send"]
+        if schedule == "launch_and_plan":
+            with torch.cuda.stream(s_send):
+                if n >= 2:
+                    s_send.wait_event(ev_steps[n - 2])    # the plan's buffers are those step n - 2 packed from
+                ctx_p.mw_plan(sn["tk"], sdn.mask, sdn.perm, sdn.desc, sdn.stats)
+                ev_plan[(n + 1) % 2].record(s_send)
+            with torch.cuda.stream(s_recv):
+                s_recv.wait_event(ev_plan[n % 2])
+                rctx[n % 2].mw_stream_step(s["x"], None, s["tk"], sd.perm, sd.stats, sd.packed, sd.row_src_token,
+                                           sd.row_topk, R, rv.out_rows, rv.out_scales, cap, rv.out_src_peer,
+                                           rv.out_src_token, rctx[(n + 1) % 2], table, R, cap, rn.expert_offsets,
+                                           rn.stats, sn["tk"][:0], None, None, None, no_plan_stats)
+                ev_steps.append(torch.cuda.Event())
+                ev_steps[n].record(s_recv)
+        else:
+            with torch.cuda.stream(s_recv):
+                rctx[n % 2].mw_stream_step(s["x"], None, s["tk"], sd.perm, sd.stats, sd.packed, sd.row_src_token,
+                                           sd.row_topk, R, rv.out_rows, rv.out_scales, cap, rv.out_src_peer,
+                                           rv.out_src_token, rctx[(n + 1) % 2], table, R, cap, rn.expert_offsets,
+                                           rn.stats, sn["tk"], sdn.mask, sdn.perm, sdn.desc, sdn.stats)
+    with torch.cuda.stream(s_recv):                       # the batch the last step indexed is expanded, too
+        n = n_steps
+        rv = sets[n % n_sets]["recv"]
+        rctx[n % 2].mw_unpack_expand(R, rv.out_rows, rv.out_scales, cap, rv.out_src_peer, rv.out_src_token)
+    torch.cuda.synchronize()
+    assert int(no_plan_stats.cpu().numpy().view(B.SEND_STATS_DTYPE)[0]["error_flags"]) == 0
+    for b, (s, (tk, x)) in enumerate(zip(sets, batches)):
+        g = H.GpuSend.__new__(H.GpuSend)                      # what the steps wrote, in GpuSend's clothes
+        g.ctx, g.T, g.buf, g.prefill = rctx[0], len(tk), s["send"], 0x3C
+        g.stats = rctx[0].mw_get_send_stats(s["send"].stats)
+        g.N, g.G = int(g.stats["n_rows"]), int(g.stats["n_groups"])
+        H.check_send(w, g, tk, x, None)
+        gs = H.GpuUnpack.__new__(H.GpuUnpack)
+        gs.ctx, gs.buf = rctx[0], s["recv"]
+        gs.stats = rctx[0].mw_get_recv_stats(s["recv"].stats)
+        gs.Q = int(gs.stats["n_out_rows"])
+        H.check_unpack(gs, want, "%s: received batch of set %d" % (schedule, b))
+    for c in rctx + [ctx_p]:
+        c.close()
 
 
 def test_unpack_in_two_calls_with_two_contexts_in_flight():
