@@ -5,15 +5,19 @@ A step is one pass of the whole path over one batch: plan -> pack -> unpack (ind
 through the C ABI, inputs resident in HBM; batches follow each other as in a steady stream, and
 the default schedule issues a whole step as one launch (mw_stream_step: packer and expander as one
 stream of workgroups, the latency-bound plan and receive index of the next batch riding along;
-see step()).  The default workload is the DeepSeek-V3-shaped
+see step()).  The headline workload is the DeepSeek-V3-shaped
 dispatch (64 simulated ranks, 256 experts, top-8 with group-limited routing, 4096 tokens of
 7168 bf16 on this rank; 64 peer receive regions).  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c0|c1|c2|c3|c4]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload all|c0|c1|c2|c3|c3_hot|c4]
                   [--schedule auto|aligned|pipelined|one_stream|one_launch|free|single] [--no-cpu-baseline]
 
-The other workloads (tiny, fp8, 256-rank Zipf, AllGather) are parity-test configurations;
-they can be timed with the same harness.
+Without --workload the line is C1's (with the variants measured on its shape and the oracle timed
+on the host cores) plus a `configs` object with a block per configuration -- C0 tiny, C1, C2 fp8,
+C3 256-rank Zipf, C3_HOT (its skew stress point) and C4 AllGather -- each timed briefly in the same
+process: step time, GB/s, % of the HBM peak, schedule, bytes saved, and the roofline of its dominant
+launch from at least 24 bracketed launches (average and median).  --workload cN times one
+configuration alone, in full.
 """
 from __future__ import annotations
 
@@ -146,7 +150,9 @@ def traffic_from_profile(kernel: str, workload: str):
 
 
 # ------------------------------------------------------------------------------------------ dispatch
-def bench_dispatch(args, name: str) -> dict:
+def bench_dispatch(args, name: str, brief: bool = False) -> dict:
+    """brief: the step, its launch brackets and the per-kernel breakdown only (the per-configuration
+    blocks of the default run); otherwise also the other schedules and the variants."""
     import numpy as np
     import torch
     from paper_2605_22428_amd import binding as B
@@ -154,12 +160,14 @@ def bench_dispatch(args, name: str) -> dict:
 
     dev = "cuda:0"
     seed = W.BASE_SEED if args.seed is None else args.seed
-    w = {"c0": W.C0, "c1": W.C1, "c2": W.C2, "c3": W.C3}[name]
-    my_rank = W.zipf_median_rank(w, seed) if name == "c3" else 0
-    if args.schedule == "auto":
+    w = {"c0": W.C0, "c1": W.C1, "c2": W.C2, "c3": W.C3, "c3_hot": W.scaled(W.C3, n_tokens=512)}[name]
+    my_rank = {"c3": W.zipf_median_rank(w, seed), "c3_hot": W.zipf_hottest_rank(w, seed)}.get(name, 0)
+    pooled = name == "c3_hot"      # 114 k received rows: payload rows come from a pool (see workloads.payload_rows_pooled)
+    sched0 = args.schedule
+    if sched0 == "auto":
         # the plan of the next batch rides in the step's one launch where it stays in the row
         # movers' shadow (up to 4096 tokens); beyond that it runs on a second stream
-        args.schedule = "one_launch" if w.n_tokens <= 4096 else "launch_and_plan"
+        sched0 = "one_launch" if w.n_tokens <= 4096 else "launch_and_plan"
     describe = {
         "c0": "C0 tiny dispatch: 8 simulated ranks, 16 experts, top-2 uniform, 128 tokens x 256 bf16, 8 peer "
               "receive regions (launch-latency bound, cache resident: its % of peak is not meaningful)",
@@ -168,6 +176,8 @@ def bench_dispatch(args, name: str) -> dict:
         "c2": "C2 = C1 with fp8 e4m3 payload + one fp32 scale per 128 elements (7392-byte rows)",
         "c3": "C3 large-EP skewed dispatch: 256 simulated ranks, 256 experts (1 per rank), 8192 tokens x 7168 "
               "bf16, top-8 Zipf(1.1); receive side at the rank of the median-popularity expert",
+        "c3_hot": "C3 skew stress point: the rank of the most popular expert, 256 peers x 512 tokens x 7168 bf16, "
+                  "top-8 Zipf(1.1) (this rank's own batch is 512 tokens too; payload rows drawn from a pool)",
     }[name]
     R, K, T, rb = w.n_ranks, w.top_k, w.n_tokens, w.row_bytes
     # rows that are not whole cache lines lie a whole number of lines apart in the packed and the
@@ -192,7 +202,10 @@ def bench_dispatch(args, name: str) -> dict:
     ctx_b = B.Context(R, w.n_experts, K, my_rank, w.hidden, fmt, T, R * T, e2r, device=dev, row_stride=stride)   # second receive index
     ctx_p = B.Context(R, w.n_experts, K, my_rank, w.hidden, fmt, T, 1, e2r, device=dev, row_stride=stride)       # plans beside mw_stream_step
     topks = W.topk_ids_many(w, seed, range(R))
-    x_me, s_me = W.payload_rows(w, seed, my_rank)
+    def draw(p, tokens=None):
+        return (W.payload_rows_pooled(w, seed, p, tokens), None) if pooled else W.payload_rows(w, seed, p, tokens)
+
+    x_me, s_me = draw(my_rank)
     topk_d = up(topks[my_rank])
     log("[bench] routing and local payload drawn in %.1fs" % (time.time() - t_setup))
 
@@ -207,13 +220,13 @@ def bench_dispatch(args, name: str) -> dict:
     counts = torch.zeros(2, dtype=torch.int32, device=dev)
     recs = []
     # the same peers' traffic as packets (header in front of every row), for the packet path
-    with_packets = name in ("c1", "c2")
+    with_packets = name in ("c1", "c2") and not brief
     hb = B.mw_packet_header_bytes(K)
     pk_all = torch.zeros((T, hb + rb), dtype=torch.uint8, device=dev) if with_packets else None
     pk_regions = []
     for p in range(R):
-        tokens = W.tokens_for_rank(w, topks[p], my_rank)
-        rows, sc = W.payload_rows(w, seed, p, tokens)
+        tokens = W.tokens_for_rank(w, topks[p], my_rank)     # (which rows are worth drawing; checked below)
+        rows, sc = draw(p, tokens)
         idx = torch.from_numpy(tokens).to(dev)
         x_peer.zero_()
         x_peer[idx] = up(rows).view(xdt)
@@ -226,6 +239,7 @@ def bench_dispatch(args, name: str) -> dict:
         ctx.mw_sim_deliver(sb.desc, sb.stats, T, sb.packed, sb.row_src_token, sb.row_topk, my_rank,
                            out["desc"], out["rows"], out["row_src_token"], out["row_topk"], counts)
         g, n = (int(v) for v in counts.cpu().numpy())
+        assert n == len(tokens), "payload was drawn for other rows than those delivered"
         if with_packets:
             ctx.mw_pack_packets(x_peer, s_peer, tk_d, sb.mask, sb.perm, sb.stats, pk_all)
             n_p = int(ctx.mw_get_send_stats(sb.stats)["n_rows"])
@@ -294,22 +308,26 @@ def bench_dispatch(args, name: str) -> dict:
     #  "launch_and_plan"  for batches whose plan would outlast the expander: mw_stream_step with an
     #            empty next batch to plan (packer, expander and the next index in one launch) and
     #            mw_plan of the real next batch on the second stream; the launch waits for the plan
-    #            made during the step before.
+    #            made during the step before, and the plan waits until the step that last packed
+    #            from its output buffers (the same buffer set, N_SETS - 1 steps ago) has finished.
     #  "one_launch" (what "auto", the default, takes for batches of up to 4096 tokens; larger
     #            ones get "launch_and_plan")  mw_stream_step: the packer joins that launch too -- one
     #            launch per batch, the two bandwidth-bound parts with no launch boundary between
     #            them.  The launch's algorithmic bytes are then the packer's plus the expander's.
     ev_unpack_done = [DeviceEvent(torch) for _ in range(2)]
     ev_plan_done = [DeviceEvent(torch) for _ in range(2)]
+    ev_step_done = [DeviceEvent(torch) for _ in range(N_SETS)]
     no_plan_stats = torch.zeros(B.SEND_STATS_BYTES, dtype=torch.uint8, device=dev)
     state = {"n": 0}
     rctx = [ctx, ctx_b]
     pipe = {"n": 0}
+    lap = {"n": 0}            # launch_and_plan steps issued since the pipeline was primed
 
     def prime_pipeline(with_plan=False):
         """Index (and, for "one_stream", plan) of the batch the next pipelined step works on; the
         other schedules use the same workspace in between."""
         n = pipe["n"]
+        lap["n"] = 0
         s = sets[n % N_SETS]
         with torch.cuda.stream(s_recv):
             rctx[n % 2].mw_unpack_index(s["table"], R, cap, s["recv"].expert_offsets, s["recv"].stats)
@@ -318,7 +336,7 @@ def bench_dispatch(args, name: str) -> dict:
                 ctx.mw_plan(topk_d, sd.mask, sd.perm, sd.desc, sd.stats)
                 ev_plan_done[n % 2].record(s_recv)
 
-    def step(i: int, schedule: str = args.schedule):
+    def step(i: int, schedule: str = sched0):
         s = sets[i % N_SETS]
         if schedule == "single":
             send_side(s)
@@ -371,6 +389,8 @@ def bench_dispatch(args, name: str) -> dict:
             s, s_next = sets[n % N_SETS], sets[(n + 1) % N_SETS]
             sd, rv, rn, sdn = s["send"], s["recv"], s_next["recv"], s_next["send"]
             with torch.cuda.stream(s_send):                      # the plan of the next batch, beside the launch
+                if lap["n"] >= N_SETS - 1:                       # its buffers: last packed from N_SETS - 1 steps ago
+                    ev_step_done[(n + 1) % N_SETS].make_wait(s_send)
                 ctx_p.mw_plan(topk_d, sdn.mask, sdn.perm, sdn.desc, sdn.stats)     # (its own context: the launch's
                                                                                    # empty plan uses ctx's or ctx_b's)
                 ev_plan_done[(n + 1) % 2].record(s_send)
@@ -380,6 +400,8 @@ def bench_dispatch(args, name: str) -> dict:
                                            sd.row_topk, R, rv.out_rows, rv.out_scales, cap, rv.out_src_peer,
                                            rv.out_src_token, rctx[(n + 1) % 2], s_next["table"], R, cap,
                                            rn.expert_offsets, rn.stats, topk_d[:0], None, None, None, no_plan_stats)
+                ev_step_done[n % N_SETS].record(s_recv)
+            lap["n"] += 1
         else:
             n = state["n"]
             state["n"] = n + 1
@@ -398,8 +420,8 @@ def bench_dispatch(args, name: str) -> dict:
             c.mw_ctx_set_timing_events(B.MW_KERNEL_EXPAND, a, b)
 
     # ---------------------------------------------------------------- warm-up, then the timed region
-    if args.schedule in ("pipelined", "one_stream", "one_launch", "launch_and_plan"):
-        prime_pipeline(args.schedule != "pipelined")
+    if sched0 in ("pipelined", "one_stream", "one_launch", "launch_and_plan"):
+        prime_pipeline(sched0 != "pipelined")
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -427,12 +449,23 @@ def bench_dispatch(args, name: str) -> dict:
     set_expand_events(None, None)
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     issue_ms_per_step = (t_issued - t0) * 1e3 / args.steps      # host time to enqueue a step
-    expand_ms = sorted(a.elapsed_time(b) for a, b in ev_expand)
+    region_ms = sorted(a.elapsed_time(b) for a, b in ev_expand)
+    # A further pass of the same steps with EVERY launch bracketed (not part of the timed region:
+    # the brackets' bubbles would be in `value`): the figures of the roofline block.
+    n_br = max(24, min(args.steps, 64))
+    ev_br = new_events(torch, n_br)
+    for i in range(n_br):
+        set_expand_events(*ev_br[i])
+        step(args.steps + i)
+    torch.cuda.synchronize()
+    set_expand_events(None, None)
+    expand_ms = sorted(a.elapsed_time(b) for a, b in ev_br)
     expand_avg_ms = sum(expand_ms) / len(expand_ms)
+    expand_med_ms = 0.5 * (expand_ms[(len(expand_ms) - 1) // 2] + expand_ms[len(expand_ms) // 2])
 
     other, other_issue = {}, {}
     for sched in ("single", "free", "aligned", "pipelined", "one_stream", "one_launch", "launch_and_plan"):
-        if sched == args.schedule:                                 # the other schedules, for reference
+        if sched == sched0 or brief:                        # the other schedules, for reference
             continue
         if sched in ("pipelined", "one_stream", "one_launch", "launch_and_plan"):
             prime_pipeline(sched != "pipelined")
@@ -466,7 +499,7 @@ def bench_dispatch(args, name: str) -> dict:
     # of 8 devices, direct links inside the server, one link per remote server (to its
     # same-index device).  One read of every row, one write per distinct next hop.
     relay = None
-    if name in ("c1", "c2"):
+    if name in ("c1", "c2") and not brief:
         n_per = 8
         next_hop = np.array([(r % n_per) if r // n_per == my_rank // n_per else n_per + (r // n_per) -
                              (1 if r // n_per > my_rank // n_per else 0) for r in range(R)], dtype=np.int32)
@@ -618,7 +651,7 @@ def bench_dispatch(args, name: str) -> dict:
     # ---------------------------------------------------------------- quantise-in-pack (extra, untimed region)
     # fp8 workload only: the packer fed with this rank's bf16 rows, quantising on the way.
     quant = None
-    if fp8:
+    if fp8 and not brief:
         import dataclasses
         xb, _ = W.payload_rows(dataclasses.replace(w, row_format="bf16"), seed, my_rank)
         xb_d = up(xb)
@@ -642,7 +675,7 @@ def bench_dispatch(args, name: str) -> dict:
     # bf16 workloads: one returned row per received row, the sum of its local experts' outputs
     # (here: the expanded rows themselves stand in for the experts' outputs).
     combine = None
-    if not fp8:
+    if not fp8 and not brief:
         rv = sets[0]["recv"]
         ctx.mw_unpack(sets[0]["table"], R, rv.out_rows, rv.out_scales, cap, rv.out_src_peer, rv.out_src_token,
                       rv.expert_offsets, rv.stats)
@@ -670,7 +703,7 @@ def bench_dispatch(args, name: str) -> dict:
     decode = {}
     sd0 = sets[0]["send"]
     for Td in (64, 128):
-        if Td > T:
+        if Td > T or brief:
             continue
         tk_s, x_s = topk_d[:Td], sets[0]["x"][:Td]
         sc_s = sets[0]["sc"][:Td] if fp8 else None
@@ -807,7 +840,7 @@ def bench_dispatch(args, name: str) -> dict:
     expand_bytes = M * rb + Q * rb + Q * 8 + M * 4
     value = (pack_bytes + unpack_bytes) / (ms_per_step * 1e-3) / 1e9
     # the bracketed launch moves the expander's bytes -- and the packer's too in "one_launch"
-    launch_bytes = expand_bytes + (pack_bytes if args.schedule in ("one_launch", "launch_and_plan") else 0)
+    launch_bytes = expand_bytes + (pack_bytes if sched0 in ("one_launch", "launch_and_plan") else 0)
     achieved = launch_bytes / (expand_avg_ms * 1e-3) / 1e9
     pu_us = kern_us["pack"] + kern_us["recv_index"] + kern_us["expand"]
     saved = 1.0 - int(st["multicast_bytes"]) / int(st["unicast_bytes"])
@@ -831,18 +864,34 @@ def bench_dispatch(args, name: str) -> dict:
     # the next batch's index riding along (same bytes; the index's few MB are not counted)
     dominant = {"pipelined": "k_expand_index_next", "one_stream": "k_expand_index_plan_next",
                 "one_launch": "k_expand_index_plan_next",
-                "launch_and_plan": "k_expand_index_plan_next"}.get(args.schedule, "k_expand")
+                "launch_and_plan": "k_expand_index_plan_next"}.get(sched0, "k_expand")
+    payload = "fp8 e4m3 codes + fp32 scales, moved as bytes" if fp8 else "bf16 payload, moved as bytes"
+    traffic_key = "mw_stream_step" if sched0 in ("one_launch", "launch_and_plan") else dominant
+    traffic = traffic_from_profile(traffic_key, name.upper())
+    roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": traffic,
+                "traffic_source": None if traffic is None else
+                "profiles/bench_%s_hbm_traffic.md: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, "
+                "not measured in this run" % name.upper(),
+                "bytes_per_launch": launch_bytes,
+                "avg_launch_ms": round(expand_avg_ms, 4), "median_launch_ms": round(expand_med_ms, 4),
+                "min_launch_ms": round(expand_ms[0], 4), "launches_timed": len(expand_ms),
+                "frac_of_median": round(launch_bytes / (expand_med_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                "brackets": "every launch of a pass of %d steps that follows the timed region" % len(expand_ms),
+                "in_timed_region": {"avg_launch_ms": round(sum(region_ms) / len(region_ms), 4),
+                                    "launches_timed": len(region_ms)}}
     result = {
         "metric": METRIC,
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "vs_baseline": None, "dtype": payload, "data": "synthetic",
         "config": {"workload": describe, "seed": seed, "my_rank": my_rank,
                    "rows_packed": N, "groups": int(st["n_groups"]), "rows_received": M, "rows_out": Q,
-                   "buffer_sets": N_SETS, "schedule": args.schedule, "row_bytes": rb, "row_stride_bytes": stride,
-                   "streams": 1 if args.schedule in ("single", "one_stream", "one_launch") else 2},
+                   "buffer_sets": N_SETS, "schedule": sched0, "row_bytes": rb, "row_stride_bytes": stride,
+                   "streams": 1 if sched0 in ("single", "one_stream", "one_launch") else 2},
         "other_schedules_ms_per_step": other,
-        "host_issue_ms_per_step": dict(other_issue, **{args.schedule: round(issue_ms_per_step, 4)}),
+        "host_issue_ms_per_step": dict(other_issue, **{sched0: round(issue_ms_per_step, 4)}),
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "bytes_saved_vs_unicast": round(saved, 4),
         "bytes_saved_vs_unicast_excluding_self": round(saved_excl_self, 4),
@@ -852,13 +901,19 @@ def bench_dispatch(args, name: str) -> dict:
                              "GBps": round((pack_bytes + unpack_bytes) / pu_us / 1e3, 1),
                              "pct_of_hbm_peak": round(100.0 * (pack_bytes + unpack_bytes) / pu_us / 1e3 / HBM_PEAK_GBPS, 2)},
         "copy_ceiling": ceiling,
-        "roofline": {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1),
-                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": traffic_from_profile("mw_stream_step" if args.schedule in ("one_launch", "launch_and_plan") else dominant,
-                                                    name.upper()), "bytes_per_launch": launch_bytes,
-                     "avg_launch_ms": round(expand_avg_ms, 4), "min_launch_ms": round(expand_ms[0], 4),
-                     "launches_timed": len(expand_ms)},
+        "roofline": roofline,
     }
+    if brief:
+        for c in (ctx, ctx_b, ctx_p):
+            c.close()
+        return {"workload": describe, "schedule": sched0, "dtype": payload,
+                "rows": {"packed": N, "received": M, "out": Q},
+                "ms_per_step": result["ms_per_step"], "GBps": result["value"],
+                "pct_of_hbm_peak": result["pct_of_hbm_peak"],
+                "bytes_saved_vs_unicast": result["bytes_saved_vs_unicast"],
+                "step_bytes": result["step_bytes"], "kernel_us": result["kernel_us"],
+                "pack_unpack_only": result["pack_unpack_only"], "copy_ceiling_GBps": ceiling["GBps"],
+                "roofline": roofline}
     if relay is not None:
         result["relay"] = relay
     if decode:
@@ -904,13 +959,35 @@ def bench_dispatch(args, name: str) -> dict:
             "ms": {"plan": round(1e3 * t_plan / reps, 2), "pack": round(1e3 * t_pack / reps, 2),
                    "unpack": round(1e3 * t_unpack / reps, 2)},
             "host_cores_visible": os.cpu_count()}
+        # the same step on all host cores: one independent step per thread (the oracle is single-threaded
+        # as written and stays so; its C routines run outside the interpreter lock)
+        from concurrent.futures import ThreadPoolExecutor
+        n_thr = max(1, min(int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or 16, os.cpu_count() or 1, 16))
+        step_s = spent / reps
+        rounds = max(1, min(6, int(6.0 / max(step_s, 1e-3))))
 
-    ctx.close()
+        def one_step(_):
+            _, perm_, _, _ = ref.plan(topks[my_rank], e2r, R, rb)
+            ref.pack(x_me, None, topks[my_rank], perm_)
+            return len(ref.unpack(bufs, K, e2r, my_rank, rb, 0, cap)[2])
+
+        a = time.perf_counter()
+        with ThreadPoolExecutor(n_thr) as ex:
+            qs = list(ex.map(one_step, range(n_thr * rounds)))
+        wall = time.perf_counter() - a
+        assert all(q == Q for q in qs)
+        result["cpu_baseline"]["all_cores"] = {
+            "value": round((pack_bytes + unpack_bytes) * len(qs) / wall / 1e9, 3), "unit": "GB/s", "cores": n_thr,
+            "sample": "%d independent C1 steps, one per thread at a time on %d threads, %.1f s wall"
+                      % (len(qs), n_thr, wall)}
+
+    for c in (ctx, ctx_b, ctx_p):
+        c.close()
     return result
 
 
 # ------------------------------------------------------------------------------------------ AllGather
-def bench_allgather(args) -> dict:
+def bench_allgather(args, brief: bool = False) -> dict:
     import numpy as np
     import torch
     from paper_2605_22428_amd import binding as B
@@ -965,8 +1042,18 @@ def bench_allgather(args) -> dict:
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     ctx.mw_ctx_set_timing_events(B.MW_KERNEL_AG_GATHER, None, None)
-    g_ms = sorted(a.elapsed_time(b) for a, b in ev)
+    region_ms = sorted(a.elapsed_time(b) for a, b in ev)
+    # a further pass with every launch bracketed (outside the timed region): the roofline's figures
+    n_br = max(24, min(args.steps, 64))
+    ev_br = new_events(torch, n_br)
+    for i in range(n_br):
+        ctx.mw_ctx_set_timing_events(B.MW_KERNEL_AG_GATHER, *ev_br[i])
+        step(args.steps + i)
+    torch.cuda.synchronize()
+    ctx.mw_ctx_set_timing_events(B.MW_KERNEL_AG_GATHER, None, None)
+    g_ms = sorted(a.elapsed_time(b) for a, b in ev_br)
     g_avg = sum(g_ms) / len(g_ms)
+    g_med = 0.5 * (g_ms[(len(g_ms) - 1) // 2] + g_ms[len(g_ms) // 2])
     names = {"pack_copy": B.MW_KERNEL_AG_PACK, "gather": B.MW_KERNEL_AG_GATHER}
     n_b = min(args.steps, 50)
     evs = {k: new_events(torch, n_b) for k in names}
@@ -991,10 +1078,11 @@ def bench_allgather(args) -> dict:
         other_step(i)
     torch.cuda.synchronize()
     other = {("single" if sched == "one_launch" else "one_launch"): round((time.perf_counter() - t0) * 1e3 / args.steps, 4)}
+    traffic = traffic_from_profile("k_allgather_step" if sched == "one_launch" else "k_gather_shards", "C4")
     result = {
         "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "vs_baseline": None, "dtype": "bf16 payload, moved as bytes", "data": "synthetic",
         "config": {"workload": "C4 AllGather receive assembly: 128-rank group, 2 MiB bf16 shard per rank, one "
                                "descriptor naming all ranks, 128 received shards -> 256 MiB in rank order "
                                "(the 4 MiB pack is launch-latency bound)", "seed": seed, "buffer_sets": N_SETS,
@@ -1008,12 +1096,25 @@ def bench_allgather(args) -> dict:
         "roofline": {"kernel": "k_allgather_step" if sched == "one_launch" else "k_gather_shards",
                      "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": traffic_from_profile("k_allgather_step" if sched == "one_launch"
-                                                     else "k_gather_shards", "C4"),
+                     "traffic": traffic,
+                     "traffic_source": None if traffic is None else
+                     "profiles/bench_C4_hbm_traffic.md: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this "
+                     "command, not measured in this run",
                      "bytes_per_launch": launch_bytes,
-                     "avg_launch_ms": round(g_avg, 4), "min_launch_ms": round(g_ms[0], 4),
-                     "launches_timed": len(g_ms)},
+                     "avg_launch_ms": round(g_avg, 4), "median_launch_ms": round(g_med, 4),
+                     "min_launch_ms": round(g_ms[0], 4), "launches_timed": len(g_ms),
+                     "frac_of_median": round(launch_bytes / (g_med * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                     "brackets": "every launch of a pass of %d steps that follows the timed region" % len(g_ms),
+                     "in_timed_region": {"avg_launch_ms": round(sum(region_ms) / len(region_ms), 4),
+                                         "launches_timed": len(region_ms)}},
     }
+    if brief:
+        result = {"workload": result["config"]["workload"], "schedule": sched, "dtype": result["dtype"],
+                  "ms_per_step": result["ms_per_step"], "GBps": result["value"],
+                  "pct_of_hbm_peak": result["pct_of_hbm_peak"],
+                  "bytes_saved_vs_unicast": result["bytes_saved_vs_unicast"], "step_bytes": result["step_bytes"],
+                  "kernel_us": result["kernel_us"], "copy_ceiling_GBps": result["copy_ceiling"]["GBps"],
+                  "roofline": result["roofline"]}
     ctx.close()
     return result
 
@@ -1023,7 +1124,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", choices=["c0", "c1", "c2", "c3", "c4"], default="c1")
+    ap.add_argument("--workload", choices=["all", "c0", "c1", "c2", "c3", "c3_hot", "c4"], default="all",
+                    help="all (default): C1 in full as the headline, then C0, C2, C3, the C3 stress point and C4 "
+                         "briefly, as per-configuration blocks of the same JSON line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--schedule", choices=["auto", "aligned", "pipelined", "one_stream", "one_launch", "launch_and_plan", "free", "single"], default="auto",
                     help="how the send side and the receive side of a step are issued (see step())")
@@ -1040,7 +1143,23 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
-    result = bench_allgather(args) if args.workload == "c4" else bench_dispatch(args, args.workload)
+    if args.workload == "all":
+        result = bench_dispatch(args, "c1")
+        configs = {"C1": {k: result[k] for k in ("ms_per_step", "pct_of_hbm_peak", "bytes_saved_vs_unicast", "roofline")}}
+        configs["C1"].update(GBps=result["value"], schedule=result["config"]["schedule"])
+        for name in ("c0", "c2", "c3", "c3_hot", "c4"):
+            import gc
+            gc.collect()
+            torch.cuda.empty_cache()
+            t0 = time.time()
+            configs[name.upper()] = bench_allgather(args, brief=True) if name == "c4" else bench_dispatch(args, name, brief=True)
+            log("[bench] %s done in %.1fs" % (name, time.time() - t0))
+        result["configs"] = {k: configs[k] for k in sorted(configs)}
+        result["configs_note"] = ("C0 and the 4 MiB pack of C4 are launch-latency bound: their percentages of the HBM "
+                                  "peak are not meaningful; C3_HOT is the skew stress point of C3 (hottest rank, 512 "
+                                  "tokens per peer)")
+    else:
+        result = bench_allgather(args) if args.workload == "c4" else bench_dispatch(args, args.workload)
     print(json.dumps(result), flush=True)
     return 0
 
