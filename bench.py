@@ -1128,6 +1128,8 @@ def main() -> int:
                     help="all (default): C1 in full as the headline, then C0, C2, C3, the C3 stress point and C4 "
                          "briefly, as per-configuration blocks of the same JSON line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--brief", action="store_true",
+                    help="with --workload cN: the configuration's block as the default run prints it (no variants)")
     ap.add_argument("--schedule", choices=["auto", "aligned", "pipelined", "one_stream", "one_launch", "launch_and_plan", "free", "single"], default="auto",
                     help="how the send side and the receive side of a step are issued (see step())")
     ap.add_argument("--seed", type=int, default=None)
@@ -1159,7 +1161,8 @@ def main() -> int:
                                   "peak are not meaningful; C3_HOT is the skew stress point of C3 (hottest rank, 512 "
                                   "tokens per peer)")
     else:
-        result = bench_allgather(args) if args.workload == "c4" else bench_dispatch(args, args.workload)
+        result = (bench_allgather(args, args.brief) if args.workload == "c4"
+                  else bench_dispatch(args, args.workload, args.brief))
     print(json.dumps(result), flush=True)
     return 0
 

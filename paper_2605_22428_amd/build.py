@@ -12,6 +12,9 @@ LIB = os.path.join(HERE, "libmw.so")
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # the first kernel argument words are in scalar registers when a wave starts (gfx950 preloads
+         # them; a kernel's hottest arguments come first): one memory round trip less per short-lived wave
+         "-mllvm", "-amdgpu-kernarg-preload-count=16",
          "-Wall", "-Wno-unused-function"]
 
 

@@ -17,12 +17,11 @@
 namespace {
 
 // blockIdx.x = segment of blockDim.x chunks, blockIdx.y walks packed rows.
-__global__ __launch_bounds__(1024) void k_pack(const u32x4 *__restrict__ x, const u32x4 *__restrict__ scales,
-                                                    int xc, int sc, int ns, const int32_t *__restrict__ topk, int K,
-                                                    const int32_t *__restrict__ perm,
-                                                    const mw_send_stats *__restrict__ stats,
-                                                    u32x4 *__restrict__ packed, int32_t *__restrict__ row_src_token,
-                                                    int32_t *__restrict__ row_topk)
+__global__ __launch_bounds__(1024) void k_pack(const int32_t *__restrict__ perm, const mw_send_stats *__restrict__ stats,
+                                               const u32x4 *__restrict__ x, const u32x4 *__restrict__ scales,
+                                               int xc, int sc, int ns, int K,      // (in registers when a wave starts)
+                                               const int32_t *__restrict__ topk, u32x4 *__restrict__ packed,
+                                               int32_t *__restrict__ row_src_token, int32_t *__restrict__ row_topk)
 {
     mw_pack_body(x, scales, xc, sc, ns, topk, K, perm, stats, packed, row_src_token, row_topk, blockIdx.x, blockIdx.y,
                  gridDim.y);
@@ -223,9 +222,9 @@ int32_t mw_launch_pack(mw_ctx *ctx, const void *x, const float *scales, const in
     const uint32_t gy = (uint32_t)T < kRowGridMax ? (uint32_t)T : kRowGridMax;
     {
         mw_timed tm(ctx, MW_KERNEL_PACK, s);
-        hipLaunchKernelGGL(k_pack, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, (const u32x4 *)x, (const u32x4 *)scales, xc, sc,
-                           (int)(ctx->row_stride / 16), topk, ctx->cfg.top_k, perm, stats, (u32x4 *)packed, row_src_token,
-                           row_topk);
+        hipLaunchKernelGGL(k_pack, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, perm, stats, (const u32x4 *)x,
+                           (const u32x4 *)scales, xc, sc, (int)(ctx->row_stride / 16), ctx->cfg.top_k, topk,
+                           (u32x4 *)packed, row_src_token, row_topk);
     }
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;

@@ -26,13 +26,14 @@ __device__ __forceinline__ void mw_pack_body(const u32x4 *__restrict__ x, const 
                                              int32_t *__restrict__ row_topk, uint32_t seg, uint32_t i_first,
                                              uint32_t i_stride)
 {
+    // the row's token and the row count are requested first, the remaining arguments beside them
+    uint32_t i = i_first;
+    int32_t t = perm[i];
+    uint32_t n_rows = stats->n_rows;
     uint32_t gdim = i_stride, bdim = blockDim.x;
     MW_PIN_S(gdim); MW_PIN_S(bdim); MW_PIN_S(xc); MW_PIN_S(sc); MW_PIN_S(ns); MW_PIN_S(K);
     MW_PIN_PTR(x); MW_PIN_PTR(scales); MW_PIN_PTR(topk); MW_PIN_PTR(packed); MW_PIN_PTR(row_src_token);
     MW_PIN_PTR(row_topk);
-    uint32_t i = i_first;
-    int32_t t = perm[i];
-    uint32_t n_rows = stats->n_rows;
     MW_PIN_S(t); MW_PIN_S(n_rows);
     const int n = xc + sc;
     const int c = seg * bdim + threadIdx.x;

@@ -251,7 +251,9 @@ __device__ __forceinline__ void mw_plan_clear(unsigned long long *cnt, uint32_t 
 // n_rank + 1 -- this workgroup if all ranks were done after all, else the rank workgroup that
 // reports last (mw_plan_ride) -- does the clearing.  Either way the launch leaves the context
 // ready for its next plan.
-// `lds`: mw_plan_finish_lds(bs) bytes.
+// `lds`: mw_plan_finish_lds(bs) bytes.  kInFlight: counters a lane requests before it looks at the
+// first (sixteen for the shortest chain; eight where the launch has to stay small in registers).
+template <int kInFlight = 16>
 __device__ __forceinline__ void mw_plan_finish_ride(const mw_plan_args &a, uint32_t fb, uint64_t *lds)
 {
     const uint32_t tid = threadIdx.x, bs = blockDim.x;
@@ -284,15 +286,15 @@ __device__ __forceinline__ void mw_plan_finish_ride(const mw_plan_args &a, uint3
         // all tokens' counters: which land in this workgroup's rows, how many groups start before
         // its first row, how many groups there are (sixteen counters per lane in flight)
         uint32_t starts_before = 0, starts_total = 0;
-        for (uint32_t t0 = 0; t0 < T; t0 += 16 * bs) {
-            unsigned long long cc[16];
+        for (uint32_t t0 = 0; t0 < T; t0 += kInFlight * bs) {
+            unsigned long long cc[kInFlight];
 #pragma unroll
-            for (int u = 0; u < 16; ++u) {
+            for (int u = 0; u < kInFlight; ++u) {
                 const uint32_t t = t0 + u * bs + tid;
                 cc[u] = t < T ? mw_ld_agent64(&a.cnt[t]) : 0ull;
             }
 #pragma unroll
-            for (int u = 0; u < 16; ++u) {
+            for (int u = 0; u < kInFlight; ++u) {
                 const unsigned long long c = cc[u];
                 if ((c >> 42) == 0) continue;                         // empty bitmap (or past the end)
                 const uint32_t p = (uint32_t)(c & kField) - n_empty;  // packed row of the token
@@ -369,7 +371,7 @@ __device__ __forceinline__ void mw_plan_finish_ride(const mw_plan_args &a, uint3
 
 // One riding plan workgroup.  `lds` is the launch's dynamic LDS: the slice's keys for a rank
 // workgroup, mw_plan_finish_lds(bs) bytes for a finishing one.
-template <int W, bool kKeyed>
+template <int W, bool kKeyed, int kInFlight = 16>
 __device__ __forceinline__ void mw_plan_ride(const mw_plan_args &a, uint32_t wg, uint64_t *lds)
 {
     if (wg < a.n_rank) {
@@ -387,7 +389,7 @@ __device__ __forceinline__ void mw_plan_ride(const mw_plan_args &a, uint32_t wg,
         return;
     }
     wg -= a.n_rank;
-    if (wg < a.n_finish) mw_plan_finish_ride(a, wg, lds);
+    if (wg < a.n_finish) mw_plan_finish_ride<kInFlight>(a, wg, lds);
 }
 
 }  // namespace

@@ -101,7 +101,11 @@ struct mw_index_args {
 };
 
 // The work of workgroup `p` (peer p) of the index; any workgroup size that is a multiple of 64.
-template <bool kPackets>
+// kCache: every thread keeps its first row (ids, rank-table entries, hits, record) in registers
+// from the first request to the final store, which takes two memory round trips off the chain
+// -- and about thirty registers; the launches that run the index beside the row movers and
+// must stay small do without (kCache = false).
+template <bool kPackets, bool kCache = true>
 __device__ __forceinline__ void recv_index_body(
     const void *__restrict__ peers_v, int P, const int32_t *__restrict__ eslot,
     int E, int K, int Kd, int my_rank, int L, int Lc,
@@ -156,7 +160,7 @@ __device__ __forceinline__ void recv_index_body(
     int32_t e_c[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) e_c[u] = -1;
-    if ((uint32_t)tid < mine) {
+    if (kCache && (uint32_t)tid < mine) {
         s_c = token_of((uint32_t)tid);
 #pragma unroll
         for (int u = 0; u < 8; ++u) if (u < K) e_c[u] = tk_c[u];
@@ -192,8 +196,8 @@ __device__ __forceinline__ void recv_index_body(
     bool bad_c = false;
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-        const bool ok = (uint32_t)e_c[u] < (uint32_t)E;
-        bad_c |= (e_c[u] != -1 && !ok);
+        const bool ok = kCache && (uint32_t)e_c[u] < (uint32_t)E;
+        bad_c |= (kCache && e_c[u] != -1 && !ok);
         q_c[u] = ok ? eslot[e_c[u]] : -1;
     }
     mw_lds_barrier();
@@ -264,25 +268,26 @@ __device__ __forceinline__ void recv_index_body(
         mw_hit *h = hits + (size_t)(rb + i) * Kd;
         const int32_t *tk = ids_of(i);
         int nk = 0;
-        for (int j0 = 0; j0 < K; j0 += 8) {
-            int32_t q[8];
+        constexpr int kB = kCache ? 8 : 4;         // ids looked up together
+        for (int j0 = 0; j0 < K; j0 += kB) {
+            int32_t q[kB];
             if (first && j0 == 0) {
 #pragma unroll
-                for (int u = 0; u < 8; ++u) q[u] = q_c[u];
+                for (int u = 0; u < kB; ++u) q[u] = q_c[u];
                 if (bad_c) err |= MW_FLAG_BAD_EXPERT;
             } else {
-                int32_t e[8];
+                int32_t e[kB];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) e[u] = (j0 + u < K) ? tk[j0 + u] : -1;
+                for (int u = 0; u < kB; ++u) e[u] = (j0 + u < K) ? tk[j0 + u] : -1;
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
+                for (int u = 0; u < kB; ++u) {
                     const bool ok = (uint32_t)e[u] < (uint32_t)E;
                     if (e[u] != -1 && !ok) err |= MW_FLAG_BAD_EXPERT;
                     q[u] = ok ? eslot[e[u]] : -1;
                 }
             }
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < kB; ++u) {
                 if (q[u] < 0 || (q[u] >> 16) != my_rank) continue;
                 const int le = q[u] & 0xffff;
                 bool dup = false;
@@ -324,7 +329,7 @@ __device__ __forceinline__ void recv_index_body(
     int f_c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     mw_row_rec rec_c = {nullptr, 0, p, 0, 0, 0, 0};
     for (uint32_t i = tid; i < n_rows; i += nthr) {
-        const bool first = i == (uint32_t)tid;
+        const bool first = kCache && i == (uint32_t)tid;
         mw_row_rec rec = {nullptr, 0, p, 0, 0, 0, 0};
         if ((addr[i >> 5] >> (i & 31)) & 1u) {
             const uint32_t s = first ? s_c : token_of(i);
@@ -383,7 +388,7 @@ __device__ __forceinline__ void recv_index_body(
 
         // stable rank of the row among the peer's rows for each of its experts in the chunk
         for (uint32_t i = tid; i < n_rows; i += nthr) {
-            const bool cached = one_chunk && i == (uint32_t)tid;
+            const bool cached = kCache && one_chunk && i == (uint32_t)tid;
             mw_hit *h = hits + (size_t)(rb + i) * Kd;
             uint32_t s = s_c; int nk = nk_c; int f[8];
 #pragma unroll
@@ -404,7 +409,7 @@ __device__ __forceinline__ void recv_index_body(
             }
         }
     }
-    if (one_chunk && (uint32_t)tid < n_rows) recs[rb + tid] = rec_c;
+    if (kCache && one_chunk && (uint32_t)tid < n_rows) recs[rb + tid] = rec_c;
     if (L == 0) {
         // no expert lives here: any addressed row is inconsistent
         for (uint32_t w = tid; w < wpl; w += nthr) if (addr[w]) err |= MW_FLAG_NO_LOCAL_EXPERT;
@@ -426,10 +431,10 @@ __device__ __forceinline__ void recv_index_body(
                      scratch);
 }
 
-template <bool kPackets>
+template <bool kPackets, bool kCache = true>
 __device__ __forceinline__ void recv_index_of(const mw_index_args &a, int p)
 {
-    recv_index_body<kPackets>(a.peers, a.P, a.eslot, a.E, a.K, a.Kd, a.my_rank, a.L, a.Lc, a.max_tokens, a.wpl,
+    recv_index_body<kPackets, kCache>(a.peers, a.P, a.eslot, a.E, a.K, a.Kd, a.my_rank, a.L, a.Lc, a.max_tokens, a.wpl,
                               a.cap_rows, a.row_bytes, a.header_bytes, a.out_cap, a.cnt, a.row_base, a.addr_cnt, a.recs,
                               a.hits, a.base, a.expert_offsets, a.stats, a.flags, p);
 }
@@ -453,21 +458,22 @@ __device__ __forceinline__ void expand_body(
     u32x4 *__restrict__ out_rows, u32x4 *__restrict__ out_scales, uint32_t cap,
     int32_t *__restrict__ out_src_peer, int32_t *__restrict__ out_src_token, uint32_t g_first, uint32_t g_stride)
 {
-    // Every kernel argument is fetched in the first batch, not after the first branch.
-    // Pointers are pinned through a copy of their low half, so the originals keep their
-    // address space.
-    uint32_t gdim = g_stride, bdim = blockDim.x;
-    MW_PIN_S(gdim); MW_PIN_S(bdim); MW_PIN_S(Kd); MW_PIN_S(xc); MW_PIN_S(sc); MW_PIN_S(cap);
-    MW_PIN_PTR(hits); MW_PIN_PTR(out_rows); MW_PIN_PTR(out_scales); MW_PIN_PTR(out_src_peer);
-    MW_PIN_PTR(out_src_token);
-    const int n = xc + sc;
-    const int c = blockIdx.x * bdim + threadIdx.x;
+    // The row's record and the row count are requested first -- their addresses need only
+    // arguments that are in registers when the wave starts -- and every other kernel argument is
+    // fetched beside them, not after the first branch: one wait for all of it.  Pointers are
+    // pinned through a copy of their low half, so the originals keep their address space.
     uint32_t g = g_first;
     // g_first < max_recv_rows, so the first record read is always inside the workspace
     const u32x4 *rp = (const u32x4 *)(recs + g);
     u32x4 r0 = rp[0], r1 = rp[1];
     uint32_t m_total = row_base[P];
-    MW_PIN_S4(r0); MW_PIN_S4(r1); MW_PIN_S(m_total);     // all three fetched together, one wait
+    uint32_t gdim = g_stride, bdim = blockDim.x;
+    MW_PIN_S(gdim); MW_PIN_S(bdim); MW_PIN_S(Kd); MW_PIN_S(xc); MW_PIN_S(sc); MW_PIN_S(cap);
+    MW_PIN_PTR(hits); MW_PIN_PTR(out_rows); MW_PIN_PTR(out_scales); MW_PIN_PTR(out_src_peer);
+    MW_PIN_PTR(out_src_token);
+    MW_PIN_S4(r0); MW_PIN_S4(r1); MW_PIN_S(m_total);
+    const int n = xc + sc;
+    const int c = blockIdx.x * bdim + threadIdx.x;
     while (g < m_total) {
         const int n_hits = (int)r1.x;
         if (n_hits > 0) {
@@ -499,8 +505,8 @@ __device__ __forceinline__ void expand_body(
 }
 
 __global__ __launch_bounds__(1024) void k_expand(
-    const mw_row_rec *__restrict__ recs, const mw_hit *__restrict__ hits, const uint32_t *__restrict__ base,
-    const uint32_t *__restrict__ row_base, int P, int Kd, int xc, int sc,
+    const mw_row_rec *__restrict__ recs, const uint32_t *__restrict__ row_base, const uint32_t *__restrict__ base,
+    const mw_hit *__restrict__ hits, int P, int Kd, int xc, int sc,     // (in registers when a wave starts)
     u32x4 *__restrict__ out_rows, u32x4 *__restrict__ out_scales, uint32_t cap,
     int32_t *__restrict__ out_src_peer, int32_t *__restrict__ out_src_token)
 {
@@ -516,19 +522,28 @@ __global__ __launch_bounds__(1024) void k_expand(
 // Here it rides along: its workgroups are dispatched first and finish long before the
 // expander's do, and the launch that expands the next batch is ordered after this one by the
 // stream, so no wait, flag or fence is needed.
+// kLean: every wave of a launch is given the registers (and the scratch space for spills) of the
+// launch's hungriest path, the row movers' waves included -- and with 64 registers a wave, or
+// with any scratch at all, the dispatcher refills the movers' wave slots more slowly (rocprofv3:
+// SPI_RA_VGPR_SIMD_FULL_CSN and SPI_RA_TMP_STALL_CSN appear, occupancy 7 % down; fp8 step 94.9
+// against 87.4 us with the riders compiled out).  Beside a large batch the riders therefore run
+// in a lean form that fits 56 registers without spilling (no first-row cache in the index, fewer
+// counters in flight in the plan's second half): a few microseconds slower, long inside the
+// movers' shadow.  Beside a small batch, where the riders ARE the step, they keep the fast form.
+template <bool kLean>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_expand_index_next(
-    const mw_row_rec *__restrict__ recs, const mw_hit *__restrict__ hits, const uint32_t *__restrict__ base,
-    const uint32_t *__restrict__ row_base, int P, int Kd, int xc, int sc,
+    const uint32_t first_expand_row, const uint32_t unused0, const mw_row_rec *__restrict__ recs,
+    const uint32_t *__restrict__ row_base, const uint32_t *__restrict__ base, const mw_hit *__restrict__ hits,
+    int P, int Kd, int xc, int sc,          // up to here: in registers when a wave starts
     u32x4 *__restrict__ out_rows, u32x4 *__restrict__ out_scales, uint32_t cap,
     int32_t *__restrict__ out_src_peer, int32_t *__restrict__ out_src_token, const mw_index_args next)
 {
-    const uint32_t n_index = (uint32_t)next.P;
-    if (blockIdx.y < n_index) {
-        if (blockIdx.x == 0) recv_index_of<false>(next, (int)blockIdx.y);
+    if (blockIdx.y >= first_expand_row) {
+        expand_body(recs, hits, base, row_base, P, Kd, xc, sc, out_rows, out_scales, cap, out_src_peer, out_src_token,
+                    blockIdx.y - first_expand_row, gridDim.y - first_expand_row);
         return;
     }
-    expand_body(recs, hits, base, row_base, P, Kd, xc, sc, out_rows, out_scales, cap, out_src_peer, out_src_token,
-                blockIdx.y - n_index, gridDim.y - n_index);
+    if (blockIdx.x == 0) recv_index_of<false, !kLean>(next, (int)blockIdx.y);
 }
 
 // The same launch with the PLAN of the next batch riding along as well (Section 5.1, send
@@ -540,33 +555,40 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
 // on a second stream and one event wait per batch (171 us); fp8 rows of half the size 101
 // against 105 us.  The riding plan is not free: its device-scope atomics and loads take
 // about 4 us of memory-channel time from the expander.
-template <int W, bool kKeyed>
+template <int W, bool kKeyed, bool kLean>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_expand_index_plan_next(
-    const mw_row_rec *__restrict__ recs, const mw_hit *__restrict__ hits, const uint32_t *__restrict__ base,
-    const uint32_t *__restrict__ row_base, int P, int Kd, int xc, int sc,
+    const uint32_t first_pack_row, const uint32_t first_expand_row, const mw_row_rec *__restrict__ recs,
+    const uint32_t *__restrict__ row_base, const uint32_t *__restrict__ base, const mw_hit *__restrict__ hits,
+    int P, int Kd, int xc, int sc,          // up to here: 14 words, in registers when a wave starts (build.py)
     u32x4 *__restrict__ out_rows, u32x4 *__restrict__ out_scales, uint32_t cap,
-    int32_t *__restrict__ out_src_peer, int32_t *__restrict__ out_src_token, const mw_index_args next,
-    const mw_plan_args plan, const uint32_t n_plan_rows, const mw_pack_args pack, const uint32_t n_pack_rows)
+    int32_t *__restrict__ out_src_peer, int32_t *__restrict__ out_src_token,
+    const mw_index_args next, const mw_plan_args plan, const mw_pack_args pack)
 {
+    // A row mover's wave lives for about a microsecond, and every dependent scalar fetch in front
+    // of its payload load is a tenth of that.  The movers' branches therefore come first, and
+    // what decides them and locates a wave's row record -- the two role boundaries, the record
+    // and row-count arrays -- are the kernel's first arguments: the library is built so that the
+    // first 14 argument words are in scalar registers when a wave starts (hardware preload).  An
+    // expander wave then has ONE round trip in front of its payload load (the record, with the
+    // remaining arguments fetched beside it) where decoding the roles one by one took five.
+    const uint32_t y_pack = first_pack_row, y_expand = first_expand_row;
+    if (blockIdx.y >= y_expand) {
+        expand_body(recs, hits, base, row_base, P, Kd, xc, sc, out_rows, out_scales, cap, out_src_peer, out_src_token,
+                    blockIdx.y - y_expand, gridDim.y - y_expand);
+        return;
+    }
+    if (blockIdx.y >= y_pack) {         // (mw_stream_step: the packer of a batch planned by an earlier launch)
+        mw_pack_body(pack.x, pack.scales, pack.xc, pack.sc, pack.ns, pack.topk, pack.K, pack.perm, pack.stats, pack.packed,
+                     pack.row_src_token, pack.row_topk, blockIdx.x, blockIdx.y - y_pack, y_expand - y_pack);
+        return;
+    }
     const uint32_t n_index = (uint32_t)next.P;
     if (blockIdx.y < n_index) {
-        if (blockIdx.x == 0) recv_index_of<false>(next, (int)blockIdx.y);
+        if (blockIdx.x == 0) recv_index_of<false, !kLean>(next, (int)blockIdx.y);
         return;
     }
-    uint32_t y = blockIdx.y - n_index;
-    if (y < n_plan_rows) {
-        extern __shared__ uint64_t plan_lds[];
-        mw_plan_ride<W, kKeyed>(plan, y * gridDim.x + blockIdx.x, plan_lds);
-        return;
-    }
-    y -= n_plan_rows;
-    if (y < n_pack_rows) {              // (mw_stream_step: the packer of a batch planned by an earlier launch)
-        mw_pack_body(pack.x, pack.scales, pack.xc, pack.sc, pack.ns, pack.topk, pack.K, pack.perm, pack.stats, pack.packed,
-                     pack.row_src_token, pack.row_topk, blockIdx.x, y, n_pack_rows);
-        return;
-    }
-    expand_body(recs, hits, base, row_base, P, Kd, xc, sc, out_rows, out_scales, cap, out_src_peer, out_src_token,
-                y - n_pack_rows, gridDim.y - n_index - n_plan_rows - n_pack_rows);
+    extern __shared__ uint64_t plan_lds[];
+    mw_plan_ride<W, kKeyed, kLean ? 8 : 16>(plan, (blockIdx.y - n_index) * gridDim.x + blockIdx.x, plan_lds);
 }
 
 // The way back (Section 2.1, combine-style AlltoAll; Section 2.3.2: the combine phase reduces
@@ -698,6 +720,13 @@ static uint32_t expand_grid_rows(const mw_ctx *ctx)
     return (uint32_t)(rows < kRowGridMax ? rows : kRowGridMax);
 }
 
+// Whether a launch that moves `grid_rows` received rows (more by striding) carries its riders in
+// the lean form: from 32 MiB of payload on, where the movers' time dwarfs the riders'.
+static bool riders_lean(const mw_ctx *ctx, uint32_t grid_rows)
+{
+    return (int64_t)grid_rows * ctx->row_bytes >= (32LL << 20);
+}
+
 int32_t mw_launch_unpack_expand(mw_ctx *ctx, int32_t P, void *out_rows, float *out_scales, int64_t cap,
                                 int32_t *out_src_peer, int32_t *out_src_token, hipStream_t s)
 {
@@ -707,8 +736,8 @@ int32_t mw_launch_unpack_expand(mw_ctx *ctx, int32_t P, void *out_rows, float *o
         const mw_row_shape shape = mw_row_shape_of(xc + sc);
         const uint32_t gy = expand_grid_rows(ctx);
         mw_timed tm(ctx, MW_KERNEL_EXPAND, s);
-        hipLaunchKernelGGL(k_expand, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, ctx->d_recs, ctx->d_hits, ctx->d_base,
-                           ctx->d_row_base, P, ctx->hit_slots, xc, sc, (u32x4 *)out_rows, (u32x4 *)out_scales,
+        hipLaunchKernelGGL(k_expand, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, ctx->d_recs, ctx->d_row_base, ctx->d_base,
+                           ctx->d_hits, P, ctx->hit_slots, xc, sc, (u32x4 *)out_rows, (u32x4 *)out_scales,
                            (uint32_t)(cap < 0x7fffffffLL ? cap : 0x7fffffffLL), out_src_peer, out_src_token);
     }
     MW_HIP_CHECK(hipGetLastError());
@@ -738,10 +767,17 @@ int32_t mw_launch_unpack_expand_index_next(mw_ctx *ctx, int32_t P, void *out_row
     const uint32_t gy = expand_grid_rows(ctx);
     {
         mw_timed tm(ctx, MW_KERNEL_EXPAND, s);
-        hipLaunchKernelGGL(k_expand_index_next, dim3(shape.nseg, gy + (uint32_t)next_P), dim3(shape.bs), lds_index, s,
-                           ctx->d_recs, ctx->d_hits, ctx->d_base, ctx->d_row_base, P, ctx->hit_slots, xc, sc,
-                           (u32x4 *)out_rows, (u32x4 *)out_scales, (uint32_t)(cap < 0x7fffffffLL ? cap : 0x7fffffffLL),
-                           out_src_peer, out_src_token, a);
+        const uint32_t cap32 = (uint32_t)(cap < 0x7fffffffLL ? cap : 0x7fffffffLL);
+        if (riders_lean(ctx, gy))
+            hipLaunchKernelGGL(k_expand_index_next<true>, dim3(shape.nseg, gy + (uint32_t)next_P), dim3(shape.bs), lds_index,
+                               s, (uint32_t)next_P, 0u, ctx->d_recs, ctx->d_row_base, ctx->d_base, ctx->d_hits, P,
+                               ctx->hit_slots, xc, sc, (u32x4 *)out_rows, (u32x4 *)out_scales, cap32, out_src_peer,
+                               out_src_token, a);
+        else
+            hipLaunchKernelGGL(k_expand_index_next<false>, dim3(shape.nseg, gy + (uint32_t)next_P), dim3(shape.bs), lds_index,
+                               s, (uint32_t)next_P, 0u, ctx->d_recs, ctx->d_row_base, ctx->d_base, ctx->d_hits, P,
+                               ctx->hit_slots, xc, sc, (u32x4 *)out_rows, (u32x4 *)out_scales, cap32, out_src_peer,
+                               out_src_token, a);
     }
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;
@@ -811,16 +847,20 @@ int32_t mw_launch_unpack_expand_index_plan_next(mw_ctx *ctx, int32_t P, void *ou
         const uint32_t gy_fit = gy < 65535u - riders ? gy : 65535u - riders;
         const dim3 grid(shape.nseg, gy_fit + riders), block(shape.bs);
         const uint32_t cap32 = (uint32_t)(cap < 0x7fffffffLL ? cap : 0x7fffffffLL);
-#define MW_RIDE(W_, KEYED_)                                                                                        \
-    hipLaunchKernelGGL((k_expand_index_plan_next<W_, KEYED_>), grid, block, lds, s, ctx->d_recs, ctx->d_hits,      \
-                       ctx->d_base, ctx->d_row_base, P, ctx->hit_slots, xc, sc, (u32x4 *)out_rows,                 \
-                       (u32x4 *)out_scales, cap32, out_src_peer, out_src_token, a, pl, n_plan_rows, pa, n_pack_rows)
+        const bool lean = riders_lean(ctx, gy_fit);
+#define MW_RIDE_(W_, KEYED_, LEAN_)                                                                                \
+    hipLaunchKernelGGL((k_expand_index_plan_next<W_, KEYED_, LEAN_>), grid, block, lds, s,                          \
+                       (uint32_t)next_P + n_plan_rows, (uint32_t)next_P + n_plan_rows + n_pack_rows, ctx->d_recs,   \
+                       ctx->d_row_base, ctx->d_base, ctx->d_hits, P, ctx->hit_slots, xc, sc, (u32x4 *)out_rows,     \
+                       (u32x4 *)out_scales, cap32, out_src_peer, out_src_token, a, pl, pa)
+#define MW_RIDE(W_, KEYED_) do { if (lean) MW_RIDE_(W_, KEYED_, true); else MW_RIDE_(W_, KEYED_, false); } while (0)
         if (keyed) MW_RIDE(4, true);
         else if (W == 1) MW_RIDE(1, false);
         else if (W == 2) MW_RIDE(2, false);
         else if (W == 3) MW_RIDE(3, false);
         else MW_RIDE(4, false);
 #undef MW_RIDE
+#undef MW_RIDE_
     }
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;
