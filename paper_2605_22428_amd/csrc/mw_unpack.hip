@@ -558,19 +558,21 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
 template <int W, bool kKeyed, bool kLean>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_expand_index_plan_next(
     const uint32_t first_pack_row, const uint32_t first_expand_row, const mw_row_rec *__restrict__ recs,
-    const uint32_t *__restrict__ row_base, const uint32_t *__restrict__ base, const mw_hit *__restrict__ hits,
-    int P, int Kd, int xc, int sc,          // up to here: 14 words, in registers when a wave starts (build.py)
+    const uint32_t *__restrict__ row_base, int P, int xc, const int32_t *__restrict__ pack_perm,
+    const mw_send_stats *__restrict__ pack_stats, int sc, int Kd,   // up to here: 14 words, in registers when a wave starts
+    const uint32_t *__restrict__ base, const mw_hit *__restrict__ hits,
     u32x4 *__restrict__ out_rows, u32x4 *__restrict__ out_scales, uint32_t cap,
     int32_t *__restrict__ out_src_peer, int32_t *__restrict__ out_src_token,
     const mw_index_args next, const mw_plan_args plan, const mw_pack_args pack)
 {
     // A row mover's wave lives for about a microsecond, and every dependent scalar fetch in front
     // of its payload load is a tenth of that.  The movers' branches therefore come first, and
-    // what decides them and locates a wave's row record -- the two role boundaries, the record
-    // and row-count arrays -- are the kernel's first arguments: the library is built so that the
-    // first 14 argument words are in scalar registers when a wave starts (hardware preload).  An
-    // expander wave then has ONE round trip in front of its payload load (the record, with the
-    // remaining arguments fetched beside it) where decoding the roles one by one took five.
+    // what decides them and locates a wave's row -- the two role boundaries, the expander's record
+    // and row-count arrays, the packer's row order and row count -- are the kernel's first
+    // arguments: the library is built so that the first 14 argument words are in scalar registers
+    // when a wave starts (hardware preload).  A mover's wave then has ONE round trip in front of its
+    // payload load (its row's record or token, with the remaining arguments fetched beside it)
+    // where decoding the roles one by one took five.
     const uint32_t y_pack = first_pack_row, y_expand = first_expand_row;
     if (blockIdx.y >= y_expand) {
         expand_body(recs, hits, base, row_base, P, Kd, xc, sc, out_rows, out_scales, cap, out_src_peer, out_src_token,
@@ -578,7 +580,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
         return;
     }
     if (blockIdx.y >= y_pack) {         // (mw_stream_step: the packer of a batch planned by an earlier launch)
-        mw_pack_body(pack.x, pack.scales, pack.xc, pack.sc, pack.ns, pack.topk, pack.K, pack.perm, pack.stats, pack.packed,
+        mw_pack_body(pack.x, pack.scales, pack.xc, pack.sc, pack.ns, pack.topk, pack.K, pack_perm, pack_stats, pack.packed,
                      pack.row_src_token, pack.row_topk, blockIdx.x, blockIdx.y - y_pack, y_expand - y_pack);
         return;
     }
@@ -851,8 +853,8 @@ int32_t mw_launch_unpack_expand_index_plan_next(mw_ctx *ctx, int32_t P, void *ou
 #define MW_RIDE_(W_, KEYED_, LEAN_)                                                                                \
     hipLaunchKernelGGL((k_expand_index_plan_next<W_, KEYED_, LEAN_>), grid, block, lds, s,                          \
                        (uint32_t)next_P + n_plan_rows, (uint32_t)next_P + n_plan_rows + n_pack_rows, ctx->d_recs,   \
-                       ctx->d_row_base, ctx->d_base, ctx->d_hits, P, ctx->hit_slots, xc, sc, (u32x4 *)out_rows,     \
-                       (u32x4 *)out_scales, cap32, out_src_peer, out_src_token, a, pl, pa)
+                       ctx->d_row_base, P, xc, pa.perm, pa.stats, sc, ctx->hit_slots, ctx->d_base, ctx->d_hits,     \
+                       (u32x4 *)out_rows, (u32x4 *)out_scales, cap32, out_src_peer, out_src_token, a, pl, pa)
 #define MW_RIDE(W_, KEYED_) do { if (lean) MW_RIDE_(W_, KEYED_, true); else MW_RIDE_(W_, KEYED_, false); } while (0)
         if (keyed) MW_RIDE(4, true);
         else if (W == 1) MW_RIDE(1, false);
