@@ -906,7 +906,7 @@ def bench_dispatch(args, name: str, brief: bool = False) -> dict:
     if brief:
         for c in (ctx, ctx_b, ctx_p):
             c.close()
-        return {"workload": describe, "schedule": sched0, "dtype": payload,
+        return {"workload": describe, "schedule": sched0, "dtype": payload, "steps": args.steps, "warmup": args.warmup,
                 "rows": {"packed": N, "received": M, "out": Q},
                 "ms_per_step": result["ms_per_step"], "GBps": result["value"],
                 "pct_of_hbm_peak": result["pct_of_hbm_peak"],
@@ -1110,7 +1110,7 @@ def bench_allgather(args, brief: bool = False) -> dict:
     }
     if brief:
         result = {"workload": result["config"]["workload"], "schedule": sched, "dtype": result["dtype"],
-                  "ms_per_step": result["ms_per_step"], "GBps": result["value"],
+                  "steps": args.steps, "warmup": args.warmup, "ms_per_step": result["ms_per_step"], "GBps": result["value"],
                   "pct_of_hbm_peak": result["pct_of_hbm_peak"],
                   "bytes_saved_vs_unicast": result["bytes_saved_vs_unicast"], "step_bytes": result["step_bytes"],
                   "kernel_us": result["kernel_us"], "copy_ceiling_GBps": result["copy_ceiling"]["GBps"],
@@ -1147,14 +1147,20 @@ def main() -> int:
     torch.cuda.set_device(0)
     if args.workload == "all":
         result = bench_dispatch(args, "c1")
-        configs = {"C1": {k: result[k] for k in ("ms_per_step", "pct_of_hbm_peak", "bytes_saved_vs_unicast", "roofline")}}
+        configs = {"C1": {k: result[k] for k in ("steps", "warmup", "ms_per_step", "pct_of_hbm_peak",
+                                                 "bytes_saved_vs_unicast", "roofline")}}
         configs["C1"].update(GBps=result["value"], schedule=result["config"]["schedule"])
+        import copy
+        import gc
+        args_b = copy.copy(args)          # the brief blocks time at least 100 steps each: at 0.1 ms a step the
+        args_b.steps = max(args.steps, 100)       # start and the end of a shorter timed region weigh over 1 %
+        args_b.warmup = max(args.warmup, 10)
         for name in ("c0", "c2", "c3", "c3_hot", "c4"):
-            import gc
             gc.collect()
             torch.cuda.empty_cache()
             t0 = time.time()
-            configs[name.upper()] = bench_allgather(args, brief=True) if name == "c4" else bench_dispatch(args, name, brief=True)
+            configs[name.upper()] = (bench_allgather(args_b, brief=True) if name == "c4"
+                                     else bench_dispatch(args_b, name, brief=True))
             log("[bench] %s done in %.1fs" % (name, time.time() - t0))
         result["configs"] = {k: configs[k] for k in sorted(configs)}
         result["configs_note"] = ("C0 and the 4 MiB pack of C4 are launch-latency bound: their percentages of the HBM "

@@ -248,21 +248,21 @@ __global__ __launch_bounds__(1024) void k_relay_copy(
 // of its own it costs about 15 us in front of every copy.  Held to 64 registers so that the copy
 // keeps every wave slot.
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_relay_copy_index_next(
+    const uint32_t first_copy_row, const uint32_t unused0,     // (the copy's arguments first: in registers when a wave starts)
     const mw_recv_peer *__restrict__ in, const mw_relay_child *__restrict__ children, int n_hops, int K, int n_chunks,
     int ns, uint32_t max_tokens, uint64_t row_bytes, const int32_t *__restrict__ group_of_row,
     const uint32_t *__restrict__ child_pos, uint32_t *relay_flags, mw_relay_stats *__restrict__ stats,
     const mw_relay_index_args next)
 {
-    const uint32_t n_index = (uint32_t)next.n_hops + 1u;
-    if (blockIdx.y < n_index) {
-        if (blockIdx.x == 0)
-            relay_index_body(next.in, next.children, next.n_hops, next.n_ranks, next.max_tokens, next.cap, next.row_bytes,
-                             next.hop_bits, next.group_of_row, next.child_pos, next.relay_flags, next.stats,
-                             (int)blockIdx.y);
+    if (blockIdx.y >= first_copy_row) {          // the copy's branch first: nothing to fetch in front of it
+        relay_copy_body(in, children, n_hops, K, n_chunks, ns, max_tokens, row_bytes, group_of_row, child_pos,
+                        relay_flags, stats, blockIdx.y - first_copy_row, gridDim.y - first_copy_row);
         return;
     }
-    relay_copy_body(in, children, n_hops, K, n_chunks, ns, max_tokens, row_bytes, group_of_row, child_pos, relay_flags,
-                    stats, blockIdx.y - n_index, gridDim.y - n_index);
+    if (blockIdx.x == 0)
+        relay_index_body(next.in, next.children, next.n_hops, next.n_ranks, next.max_tokens, next.cap, next.row_bytes,
+                         next.hop_bits, next.group_of_row, next.child_pos, next.relay_flags, next.stats,
+                         (int)blockIdx.y);
 }
 
 // ---- the same step for packets (Section 4.1, "Replication and forwarding": the relay parses the
@@ -429,21 +429,21 @@ __global__ __launch_bounds__(1024) void k_relay_packets_copy(
 // The packets' form of k_relay_copy_index_next: this buffer's copy with the next buffer's index
 // (another context's workspace) in the first next.n_hops + 1 workgroup rows.
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_relay_packets_copy_index_next(
+    const uint32_t first_copy_row, const uint32_t unused0,
     const mw_recv_packets *__restrict__ in, void *const *__restrict__ children, int n_hops, int n_chunks,
     uint32_t max_tokens, uint64_t packet_bytes, const uint64_t *__restrict__ hop_bits,
     const uint32_t *__restrict__ child_pos, uint32_t *relay_flags, mw_relay_stats *__restrict__ stats,
     const mw_relay_packets_index_args next)
 {
-    const uint32_t n_index = (uint32_t)next.n_hops + 1u;
-    if (blockIdx.y < n_index) {
-        if (blockIdx.x == 0)
-            relay_packets_index_body(next.in, next.n_hops, next.n_ranks, next.K, next.max_tokens, next.cap,
-                                     next.packet_bytes, next.hop_bits, next.child_pos, next.relay_flags, next.stats,
-                                     (int)blockIdx.y);
+    if (blockIdx.y >= first_copy_row) {
+        relay_packets_copy_body(in, children, n_hops, n_chunks, max_tokens, packet_bytes, hop_bits, child_pos,
+                                relay_flags, stats, blockIdx.y - first_copy_row, gridDim.y - first_copy_row);
         return;
     }
-    relay_packets_copy_body(in, children, n_hops, n_chunks, max_tokens, packet_bytes, hop_bits, child_pos, relay_flags,
-                            stats, blockIdx.y - n_index, gridDim.y - n_index);
+    if (blockIdx.x == 0)
+        relay_packets_index_body(next.in, next.n_hops, next.n_ranks, next.K, next.max_tokens, next.cap,
+                                 next.packet_bytes, next.hop_bits, next.child_pos, next.relay_flags, next.stats,
+                                 (int)blockIdx.y);
 }
 
 }  // namespace
@@ -499,7 +499,7 @@ int32_t mw_launch_relay_copy(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay
                 shape.bs = ((n_chunks + shape.nseg - 1) / shape.nseg + 63) / 64 * 64;
             }
             hipLaunchKernelGGL(k_relay_copy_index_next, dim3(shape.nseg, gy + (uint32_t)next->n_hops + 1u),
-                               dim3(shape.bs), 0, s, in, children, ctx->n_hops, c.top_k, n_chunks,
+                               dim3(shape.bs), 0, s, (uint32_t)next->n_hops + 1u, 0u, in, children, ctx->n_hops, c.top_k, n_chunks,
                                (int)(ctx->row_stride / 16), (uint32_t)c.max_tokens, (uint64_t)ctx->row_bytes,
                                ctx->d_group_of_row, ctx->d_child_pos, ctx->d_relay_flags, stats,
                                relay_index_args(next, next_in, next_children, next_cap, next_stats));
@@ -565,7 +565,7 @@ int32_t mw_launch_relay_packets_copy(mw_ctx *ctx, const mw_recv_packets *in, voi
                 shape.bs = ((n_chunks + shape.nseg - 1) / shape.nseg + 63) / 64 * 64;
             }
             hipLaunchKernelGGL(k_relay_packets_copy_index_next, dim3(shape.nseg, gy + (uint32_t)next->n_hops + 1u),
-                               dim3(shape.bs), 0, s, in, children, ctx->n_hops, n_chunks, (uint32_t)c.max_tokens, pb,
+                               dim3(shape.bs), 0, s, (uint32_t)next->n_hops + 1u, 0u, in, children, ctx->n_hops, n_chunks, (uint32_t)c.max_tokens, pb,
                                ctx->d_hop_bits, ctx->d_child_pos, ctx->d_relay_flags, stats,
                                relay_packets_index_args(next, next_in, next_cap, next_stats));
         }
