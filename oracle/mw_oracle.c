@@ -287,7 +287,6 @@ int ref_deliver(const ref_group_desc *desc, int32_t G, const uint8_t *rows, int6
     return REF_OK;
 }
 
-/* slot of expert e among the experts hosted by `rank`, in ascending id order; -1 if elsewhere */
 /* ------------------------------------------------------------------------ */
 /*
  * Relay step.  Section 4.3.3 (recursive execution model): a node that holds
@@ -348,9 +347,8 @@ int ref_relay_child(const ref_group_desc *desc, int32_t G, const uint8_t *rows, 
 }
 
 /*
- * Copies a relay makes, plainly (Section 4.1: the number of unique egress
- * ports determines how many copies of the packet are made): per group, the
- * number of distinct next hops among its destinations.
+ * Copies a relay makes, plainly (Section 4.1, local forwarding table): per
+ * group, one copy for every distinct next hop among its destinations.
  *   forward_bytes = row_bytes * sum over groups of rows * distinct hops
  *   unicast_bytes = row_bytes * sum over groups of rows * destinations
  *   rows_per_hop[h] = rows of the groups that use hop h
@@ -384,12 +382,58 @@ int ref_relay_accounting(const ref_group_desc *desc, int32_t G, int64_t row_byte
     return REF_OK;
 }
 
+/* slot of expert e among the experts hosted by `rank`, in ascending id order; -1 if elsewhere */
 static int32_t local_slot_of(const int32_t *expert_to_rank, int32_t e, int32_t rank)
 {
     if (expert_to_rank[e] != rank) return -1;
     int32_t s = 0;
     for (int32_t f = 0; f < e; ++f) s += (expert_to_rank[f] == rank);
     return s;
+}
+
+/*
+ * Relay step WITHOUT the metadata update (Section 4.1, last paragraph of
+ * "Replication and forwarding": where routing loops cannot occur and the end
+ * nodes drop repeated packets, a relay may forward the metadata as it came).
+ * The child for hop h keeps the same groups, rows and row metadata as
+ * ref_relay_child -- the copies made are the same -- but every kept group
+ * carries the PARENT's bitmap and its popcount: a node further down sees all
+ * the original destinations, the ones served over other hops included.
+ */
+int ref_relay_child_unmodified(const ref_group_desc *desc, int32_t G, const uint8_t *rows, int64_t row_bytes,
+                               const int32_t *row_src_token, const int32_t *row_topk, int32_t K,
+                               const int32_t *next_hop, int32_t R, int32_t n_hops, int32_t hop,
+                               ref_group_desc *desc_out, uint8_t *rows_out, int32_t *src_token_out,
+                               int32_t *topk_out, int32_t *G_out, int32_t *N_out)
+{
+    if (R < 1 || R > REF_MAX_RANKS || n_hops < 1 || hop < 0 || hop >= n_hops) return REF_ERR_ARG;
+    for (int32_t r = 0; r < R; ++r)
+        if (next_hop[r] < 0 || next_hop[r] >= n_hops) return REF_ERR_ARG;
+    int32_t g2 = 0, n2 = 0;
+    for (int32_t g = 0; g < G; ++g) {
+        int uses_hop = 0;
+        for (int r = 0; r < REF_MAX_RANKS; ++r) {
+            if (!mask_bit(desc[g].mask, r)) continue;
+            if (r >= R) return REF_ERR_INPUT;
+            if (next_hop[r] == hop) uses_hop = 1;
+        }
+        if (!uses_hop) continue;
+        for (int w = 0; w < REF_MASK_WORDS; ++w) desc_out[g2].mask[w] = desc[g].mask[w];
+        desc_out[g2].row_offset = (uint32_t)n2;
+        desc_out[g2].row_count = desc[g].row_count;
+        desc_out[g2].n_dest = (uint32_t)mask_popcount(desc[g].mask);
+        desc_out[g2].reserved0 = 0;
+        for (uint32_t i = 0; i < desc[g].row_count; ++i) {
+            const size_t s = (size_t)desc[g].row_offset + i;
+            memcpy(rows_out + (size_t)n2 * (size_t)row_bytes, rows + s * (size_t)row_bytes, (size_t)row_bytes);
+            src_token_out[n2] = row_src_token[s];
+            for (int32_t j = 0; j < K; ++j) topk_out[(size_t)n2 * K + j] = row_topk[s * K + j];
+            ++n2;
+        }
+        ++g2;
+    }
+    *G_out = g2; *N_out = n2;
+    return REF_OK;
 }
 
 static int32_t local_count(const int32_t *expert_to_rank, int32_t E, int32_t rank)
@@ -501,6 +545,85 @@ int ref_unpack(const ref_recv_peer *peers, int32_t P, int32_t K,
 done:
     for (int32_t p = 0; p < P; ++p) free(addr[p]);
     free(addr); free(cnt);
+    return rc;
+}
+
+/*
+ * Receive side with de-duplication (Section 4.1, last paragraph of
+ * "Replication and forwarding": end nodes that drop repeated packets).  A
+ * packet of this path is a (source peer, source token) pair; a peer's region
+ * may hold it more than once when relays forwarded without updating the
+ * metadata.  Reading used here: inside one peer's region, among the rows
+ * whose group names this rank, the FIRST row (lowest row index) of every
+ * source token is taken and the later ones are dropped; what is taken is
+ * then delivered as in ref_unpack: expert-major, inside an expert by (source
+ * peer, source token) ascending.  n_recv_rows counts the rows taken,
+ * n_dropped the repeats.  Written on its own, from the definition: for every
+ * local expert and peer, the taken rows that name the expert are put out in
+ * ascending source-token order.
+ */
+int ref_unpack_dedup(const ref_recv_peer *peers, int32_t P, int32_t K,
+                     const int32_t *expert_to_rank, int32_t E, int32_t my_rank,
+                     int64_t x_row_bytes, int64_t s_row_bytes, int64_t out_capacity_rows,
+                     uint8_t *out_rows, uint8_t *out_scales, int32_t *out_src_peer, int32_t *out_src_token,
+                     int64_t *expert_offsets /* [L+1] */, int64_t *n_recv_rows, int64_t *n_dropped)
+{
+    if (my_rank < 0 || my_rank >= REF_MAX_RANKS || P < 0) return REF_ERR_ARG;
+    const int32_t L = local_count(expert_to_rank, E, my_rank);
+    const int64_t rb = x_row_bytes + s_row_bytes;
+    int rc = REF_OK, bad = 0;
+    /* taken[p][i] = 1: row i of peer p is addressed to this rank and is the first row of its token */
+    uint8_t **taken = (uint8_t **)calloc((size_t)(P > 0 ? P : 1), sizeof(uint8_t *));
+    if (!taken) return REF_ERR_CAPACITY;
+    int64_t M = 0, D = 0, Q = 0;
+    for (int32_t p = 0; p < P; ++p) {
+        const ref_recv_peer *pr = &peers[p];
+        taken[p] = (uint8_t *)calloc((size_t)pr->n_rows + 1, 1);
+        for (uint32_t g = 0; g < pr->n_desc; ++g) {
+            const ref_group_desc *d = &pr->desc[g];
+            if ((uint64_t)d->row_offset + d->row_count > pr->n_rows) { rc = REF_ERR_INPUT; goto done; }
+            if (!mask_bit(d->mask, my_rank)) continue;
+            for (uint32_t i = 0; i < d->row_count; ++i) taken[p][d->row_offset + i] = 1;
+        }
+        for (uint32_t i = 0; i < pr->n_rows; ++i) {
+            if (!taken[p][i]) continue;
+            for (uint32_t i2 = 0; i2 < i; ++i2)
+                if (taken[p][i2] && pr->row_src_token[i2] == pr->row_src_token[i]) { taken[p][i] = 0; break; }
+            if (taken[p][i]) ++M; else ++D;
+        }
+    }
+    for (int32_t le = 0; le < L; ++le) {
+        expert_offsets[le] = Q;
+        for (int32_t p = 0; p < P; ++p) {
+            const ref_recv_peer *pr = &peers[p];
+            /* the taken rows of this peer that name expert le, smallest source token first */
+            int32_t last = INT32_MIN;
+            for (;;) {
+                int64_t best = -1;
+                for (uint32_t i = 0; i < pr->n_rows; ++i) {
+                    if (!taken[p][i] || pr->row_src_token[i] <= last) continue;
+                    if (!row_hits(pr->row_topk + (size_t)i * K, K, expert_to_rank, E, my_rank, le, &bad)) continue;
+                    if (best < 0 || pr->row_src_token[i] < pr->row_src_token[best]) best = (int64_t)i;
+                }
+                if (best < 0) break;
+                if (Q >= out_capacity_rows) { rc = REF_ERR_CAPACITY; goto done; }
+                const uint8_t *src = pr->rows + (size_t)best * (size_t)rb;
+                memcpy(out_rows + (size_t)Q * (size_t)x_row_bytes, src, (size_t)x_row_bytes);
+                if (s_row_bytes > 0)
+                    memcpy(out_scales + (size_t)Q * (size_t)s_row_bytes, src + x_row_bytes, (size_t)s_row_bytes);
+                out_src_peer[Q] = p;
+                out_src_token[Q] = pr->row_src_token[best];
+                last = pr->row_src_token[best];
+                ++Q;
+            }
+        }
+    }
+    expert_offsets[L] = Q;
+    if (bad) rc = REF_ERR_EXPERT;
+    *n_recv_rows = M; *n_dropped = D;
+done:
+    for (int32_t p = 0; p < P; ++p) free(taken[p]);
+    free(taken);
     return rc;
 }
 

@@ -58,7 +58,8 @@ def lib():
                      "ref_relay_child", "ref_relay_accounting", "ref_allgather_split_point",
                      "ref_plan_allgather_split", "ref_unpack_allgather_split",
                      "ref_pack_packets", "ref_deliver_packets", "ref_unpack_packets",
-                     "ref_quantize_e4m3_block128", "ref_combine_gather", "ref_relay_packets_child"):
+                     "ref_quantize_e4m3_block128", "ref_combine_gather", "ref_relay_packets_child",
+                     "ref_relay_child_unmodified", "ref_unpack_dedup"):
             getattr(_lib, name).restype = C.c_int
         _lib.ref_packet_header_bytes.restype = C.c_int64
     return _lib
@@ -155,8 +156,10 @@ def deliver(desc: np.ndarray, rows: np.ndarray, src_token, row_topk, dst_rank: i
     return d2[:g].copy(), r2[:n].copy(), s2[:n].copy(), t2[:n].copy()
 
 
-def relay_child(desc: np.ndarray, rows: np.ndarray, src_token, row_topk, next_hop, n_hops: int, hop: int):
-    """The child MultiWrite a relay starts towards next hop `hop` (same tuple layout as deliver)."""
+def relay_child(desc: np.ndarray, rows: np.ndarray, src_token, row_topk, next_hop, n_hops: int, hop: int,
+                update_metadata: bool = True):
+    """The child MultiWrite a relay starts towards next hop `hop` (same tuple layout as deliver);
+    update_metadata=False: the bitmaps are forwarded as they came (ref_relay_child_unmodified)."""
     desc = np.ascontiguousarray(desc, dtype=DESC)
     rows = np.ascontiguousarray(rows, dtype=np.uint8)
     src_token, row_topk, next_hop = _i32(src_token), _i32(row_topk), _i32(next_hop)
@@ -167,10 +170,11 @@ def relay_child(desc: np.ndarray, rows: np.ndarray, src_token, row_topk, next_ho
     s2 = np.zeros(max(N, 1), dtype=np.int32)
     t2 = np.zeros((max(N, 1), K), dtype=np.int32)
     g_out, n_out = C.c_int32(0), C.c_int32(0)
-    _check(lib().ref_relay_child(_p(desc), C.c_int32(G), _p(rows), C.c_int64(rb), _p(src_token),
-                                 _p(row_topk), C.c_int32(K), _p(next_hop), C.c_int32(len(next_hop)),
-                                 C.c_int32(n_hops), C.c_int32(hop), _p(d2), _p(r2), _p(s2), _p(t2),
-                                 C.byref(g_out), C.byref(n_out)), "ref_relay_child")
+    fn = lib().ref_relay_child if update_metadata else lib().ref_relay_child_unmodified
+    _check(fn(_p(desc), C.c_int32(G), _p(rows), C.c_int64(rb), _p(src_token),
+              _p(row_topk), C.c_int32(K), _p(next_hop), C.c_int32(len(next_hop)),
+              C.c_int32(n_hops), C.c_int32(hop), _p(d2), _p(r2), _p(s2), _p(t2),
+              C.byref(g_out), C.byref(n_out)), "ref_relay_child")
     g, n = g_out.value, n_out.value
     return d2[:g].copy(), r2[:n].copy(), s2[:n].copy(), t2[:n].copy()
 
@@ -218,6 +222,35 @@ def unpack(peers: Sequence[PeerBuf], top_k: int, e2r, my_rank: int, x_row_bytes:
                             C.byref(m)), "ref_unpack")
     Q = int(offs[L])
     return out[:Q], (osc[:Q] if osc is not None else None), sp[:Q], stok[:Q], offs, int(m.value)
+
+
+def unpack_dedup(peers: Sequence[PeerBuf], top_k: int, e2r, my_rank: int, x_row_bytes: int,
+                 s_row_bytes: int, out_capacity_rows: int):
+    """unpack with the end node's de-duplication: inside a peer's region the first row of every
+    source token is taken.  -> unpack's tuple with (rows taken, repeats dropped) as its last entry."""
+    e2r = _i32(e2r)
+    L = int((e2r == my_rank).sum())
+    keep: List[np.ndarray] = []
+    arr = (_RecvPeer * max(len(peers), 1))()
+    for i, (d, r, s, t) in enumerate(peers):
+        d = np.ascontiguousarray(d, dtype=DESC)
+        r = np.ascontiguousarray(r, dtype=np.uint8)
+        s, t = _i32(s), _i32(t)
+        keep += [d, r, s, t]
+        arr[i] = _RecvPeer(d.ctypes.data, len(d), r.shape[0], r.ctypes.data, s.ctypes.data, t.ctypes.data)
+    cap = max(int(out_capacity_rows), 1)
+    out = np.zeros((cap, x_row_bytes), dtype=np.uint8)
+    osc = np.zeros((cap, s_row_bytes), dtype=np.uint8) if s_row_bytes else None
+    sp = np.full(cap, -1, dtype=np.int32)
+    stok = np.full(cap, -1, dtype=np.int32)
+    offs = np.zeros(L + 1, dtype=np.int64)
+    m, dr = C.c_int64(0), C.c_int64(0)
+    _check(lib().ref_unpack_dedup(arr, C.c_int32(len(peers)), C.c_int32(top_k), _p(e2r), C.c_int32(len(e2r)),
+                                  C.c_int32(my_rank), C.c_int64(x_row_bytes), C.c_int64(s_row_bytes),
+                                  C.c_int64(out_capacity_rows), _p(out), _p(osc), _p(sp), _p(stok), _p(offs),
+                                  C.byref(m), C.byref(dr)), "ref_unpack_dedup")
+    Q = int(offs[L])
+    return out[:Q], (osc[:Q] if osc is not None else None), sp[:Q], stok[:Q], offs, (int(m.value), int(dr.value))
 
 
 PeerTok = Tuple[np.ndarray, np.ndarray, Optional[np.ndarray]]     # (topk, x, scales)
