@@ -1156,3 +1156,35 @@ int ref_relay_packets_child(const uint8_t *packets, int64_t n_packets, int64_t p
     if (dests) *dests = n_dests;
     return REF_OK;
 }
+
+/*
+ * Relay of packets WITHOUT the metadata update (Section 4.1, last paragraph
+ * of "Replication and forwarding"; see ref_relay_child_unmodified).  The
+ * child for hop h holds, in order, the packets ref_relay_packets_child keeps
+ * for it, each one byte for byte as it arrived: header bitmap included.
+ */
+int ref_relay_packets_child_unmodified(const uint8_t *packets, int64_t n_packets, int64_t packet_bytes,
+                                       const int32_t *next_hop, int32_t R, int32_t n_hops, int32_t hop,
+                                       uint8_t *out, int64_t *n_out)
+{
+    if (R < 1 || R > REF_MAX_RANKS || n_hops < 1 || hop < 0 || hop >= n_hops || packet_bytes < 128) return REF_ERR_ARG;
+    for (int32_t r = 0; r < R; ++r)
+        if (next_hop[r] < 0 || next_hop[r] >= n_hops) return REF_ERR_ARG;
+    int64_t n = 0;
+    for (int64_t i = 0; i < n_packets; ++i) {
+        const uint8_t *pk = packets + (size_t)i * (size_t)packet_bytes;
+        uint64_t mask[REF_MASK_WORDS];
+        for (int w = 0; w < REF_MASK_WORDS; ++w) mask[w] = get_le(pk + 8 * w, 8);
+        int wanted = 0;
+        for (int r = 0; r < REF_MAX_RANKS; ++r) {
+            if (!mask_bit(mask, r)) continue;
+            if (r >= R) return REF_ERR_INPUT;
+            if (next_hop[r] == hop) wanted = 1;
+        }
+        if (!wanted) continue;
+        memcpy(out + (size_t)n * (size_t)packet_bytes, pk, (size_t)packet_bytes);
+        ++n;
+    }
+    *n_out = n;
+    return REF_OK;
+}

@@ -59,7 +59,7 @@ def lib():
                      "ref_plan_allgather_split", "ref_unpack_allgather_split",
                      "ref_pack_packets", "ref_deliver_packets", "ref_unpack_packets",
                      "ref_quantize_e4m3_block128", "ref_combine_gather", "ref_relay_packets_child",
-                     "ref_relay_child_unmodified", "ref_unpack_dedup"):
+                     "ref_relay_packets_child_unmodified", "ref_relay_child_unmodified", "ref_unpack_dedup"):
             getattr(_lib, name).restype = C.c_int
         _lib.ref_packet_header_bytes.restype = C.c_int64
     return _lib
@@ -439,12 +439,20 @@ def combine_gather(peers: Sequence[PeerBuf], top_k: int, e2r, my_rank: int, y_bf
     return outs
 
 
-def relay_packets_child(packets: np.ndarray, next_hop, n_hops: int, hop: int):
-    """-> (child packets of next hop `hop`, packets written by the whole relay step, destinations named)"""
+def relay_packets_child(packets: np.ndarray, next_hop, n_hops: int, hop: int, update_metadata: bool = True):
+    """-> (child packets of next hop `hop`, packets written by the whole relay step, destinations named);
+    update_metadata=False: the kept packets as they arrived (-> child packets only)"""
     packets = np.ascontiguousarray(packets, dtype=np.uint8)
     next_hop = _i32(next_hop)
     out = np.zeros_like(packets)
     n, copies, dests = C.c_int64(0), C.c_uint64(0), C.c_uint64(0)
+    if not update_metadata:
+        _check(lib().ref_relay_packets_child_unmodified(_p(packets), C.c_int64(packets.shape[0]),
+                                                        C.c_int64(packets.shape[1]), _p(next_hop),
+                                                        C.c_int32(len(next_hop)), C.c_int32(n_hops), C.c_int32(hop),
+                                                        _p(out), C.byref(n)),
+               "ref_relay_packets_child_unmodified")
+        return out[: n.value].copy()
     _check(lib().ref_relay_packets_child(_p(packets), C.c_int64(packets.shape[0]), C.c_int64(packets.shape[1]),
                                          _p(next_hop), C.c_int32(len(next_hop)), C.c_int32(n_hops), C.c_int32(hop),
                                          _p(out), C.byref(n), C.byref(copies), C.byref(dests)),

@@ -165,3 +165,32 @@ def test_delivery_through_relays_that_do_not_update_equals_direct_delivery(seed)
             with pytest.raises(ref.OracleError):
                 ref.unpack(regions[d], w.top_k, e2r, d, w.row_bytes, 0, cap)
     assert n_dup_total > 0          # (the construction does produce repeats)
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_unmodified_packets_child_is_the_kept_parent_packets_verbatim(seed):
+    """Packets form of the option: per hop the same packets are kept as by the updating relay (a
+    packet travels to a hop iff its bitmap names a rank behind it, brute force over bits), each one
+    byte for byte the parent's; the updated child differs from it in the bitmap bytes only."""
+    rng = np.random.default_rng(seed)
+    w = W.DispatchWorkload("t", 36, 12, 24, 3, 50, 64, "bf16", "uniform")
+    e2r = W.expert_to_rank(w)
+    tk = W.topk_ids(w, seed, 0)
+    x, sc = W.payload_rows(w, seed, 0)
+    mask, perm, _, _ = ref.plan(tk, e2r, w.n_ranks, w.row_bytes)
+    pk = ref.pack_packets(x, sc, tk, mask, perm)
+    n_hops = 5
+    next_hop = rng.integers(0, n_hops, size=w.n_ranks).astype(np.int32)
+    total = 0
+    for h in range(n_hops):
+        raw = ref.relay_packets_child(pk, next_hop, n_hops, h, update_metadata=False)
+        upd, _, _ = ref.relay_packets_child(pk, next_hop, n_hops, h)
+        keep = [i for i in range(len(pk))
+                if any(next_hop[r] == h for r in range(w.n_ranks)
+                       if (int.from_bytes(pk[i, :32].tobytes(), "little") >> r) & 1)]
+        assert raw.tobytes() == pk[keep].tobytes()
+        assert upd[:, 32:].tobytes() == raw[:, 32:].tobytes()
+        total += len(raw)
+    assert total > len(pk)           # (some packet does travel over more than one hop)
+    with pytest.raises(ref.OracleError):
+        ref.relay_packets_child(pk, np.zeros(2, np.int32), 1, 0, update_metadata=False)    # bitmaps name ranks >= 2
