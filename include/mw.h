@@ -95,6 +95,7 @@ extern "C" {
 #define MW_FLAG_DUP_SRC_TOKEN    0x40u  /* two rows of one peer carry the same source token for one expert */
 #define MW_FLAG_PLAN_TIMEOUT     0x100u /* mw_unpack_expand_index_plan_next, mw_stream_step: the riding plan gave up waiting (see there) */
 #define MW_FLAG_BAD_RANK         0x80u  /* relay: a bitmap names a rank >= n_ranks: that bit is not forwarded */
+#define MW_FLAG_DUPLICATE_DROPPED 0x200u /* with MW_OPT_RECV_DEDUP: a repeated row was dropped (information, not an error) */
 
 /*
  * Destination bitmap, Section 4.1: ranks are numbered from zero and bit r says
@@ -203,6 +204,27 @@ MW_API int32_t mw_ctx_destroy(mw_ctx *ctx);
  * that path.  Applies to later calls that plan with this context.
  */
 MW_API int32_t mw_ctx_set_ride_wait_limit(mw_ctx *ctx, int64_t polls);
+
+/*
+ * Options of a context (Section 4.1, last paragraph of "Replication and forwarding": where routing
+ * loops cannot occur and the end nodes drop repeated packets, a relay may omit the update of the
+ * in-packet metadata; whether to do so is a deployment decision).  Host only; applies to later
+ * calls; 0 (the default) is the behaviour described at the entry points.
+ *   MW_OPT_RELAY_KEEP_METADATA  mw_relay, mw_relay_index and the packets' forms: every child keeps the
+ *       groups, rows and row metadata it would keep anyway -- the copies made are the same -- but its
+ *       bitmaps (and n_dest) are the parent's, not the parent's restricted to the hop's ranks.
+ *   MW_OPT_RECV_DEDUP  mw_unpack, mw_unpack_index, mw_unpack_packets and the launches that carry
+ *       the index: of the rows of one peer's region that are addressed to this rank and carry the
+ *       same source token, one is taken and the others are dropped (they are copies of one another,
+ *       so it does not matter which).  n_recv_rows counts the rows taken; MW_FLAG_DUPLICATE_DROPPED
+ *       says that something was dropped; MW_FLAG_DUP_SRC_TOKEN is never raised.
+ * Deployments of the first option need the second at the destinations, relays that forward once,
+ * and end nodes that never forward: a node further down sees destinations that were served
+ * over other hops as well.
+ */
+#define MW_OPT_RELAY_KEEP_METADATA 0x1u
+#define MW_OPT_RECV_DEDUP          0x2u
+MW_API int32_t mw_ctx_set_options(mw_ctx *ctx, uint32_t options);
 
 /* ---- send side (Section 5.1, send module: task decomposition) -------------------------- */
 

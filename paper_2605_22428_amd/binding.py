@@ -29,7 +29,7 @@ EXPORTS = ["mw_workspace_bytes", "mw_ctx_create", "mw_ctx_destroy", "mw_plan", "
            "mw_sim_deliver", "mw_copy_bytes", "mw_get_send_stats", "mw_get_recv_stats",
            "mw_set_forwarding", "mw_relay", "mw_relay_index", "mw_relay_copy", "mw_relay_copy_index_next", "mw_relay_packets", "mw_relay_packets_index", "mw_relay_packets_copy", "mw_relay_packets_copy_index_next", "mw_get_relay_stats",
            "mw_allgather_split_point", "mw_plan_allgather_split", "mw_unpack_allgather_split",
-           "mw_ctx_set_timing_events", "mw_status_string", "mw_plan_static"]
+           "mw_ctx_set_timing_events", "mw_status_string", "mw_plan_static", "mw_ctx_set_options"]
 MW_KERNEL_PLAN_RANK, MW_KERNEL_PLAN_GROUPS, MW_KERNEL_PACK, MW_KERNEL_RECV_INDEX, MW_KERNEL_EXPAND = 0, 1, 2, 3, 4
 MW_KERNEL_AG_PACK, MW_KERNEL_AG_GATHER, MW_KERNEL_RELAY_INDEX, MW_KERNEL_RELAY_COPY = 5, 6, 7, 8
 MW_KERNEL_PLAN_PACK, MW_KERNEL_PACK_QUANT, MW_KERNEL_COMBINE = 9, 10, 11
@@ -39,6 +39,8 @@ MW_RIDE_MAX_TOKENS = 8192
 MW_STATIC_MAX_TOKENS, MW_STATIC_MAX_EXPERTS = 8192, 1024
 MW_FLAG_BAD_RANK = 0x80
 MW_FLAG_PLAN_TIMEOUT = 0x100
+MW_FLAG_DUPLICATE_DROPPED = 0x200
+MW_OPT_RELAY_KEEP_METADATA, MW_OPT_RECV_DEDUP = 0x1, 0x2
 
 # numpy views of the ABI records (host copies)
 DESC_DTYPE = np.dtype([("mask", "<u8", (4,)), ("row_offset", "<u4"), ("row_count", "<u4"),
@@ -302,6 +304,9 @@ class Context:
             C.c_int32(next_n_peers), C.c_int64(next_out_capacity_rows), _ptr(next_expert_offsets),
             _ptr(next_recv_stats), _ptr(next_topk_ids), C.c_int32(next_topk_ids.shape[0]), _ptr(next_mask),
             _ptr(next_perm), _ptr(next_desc), _ptr(next_send_stats), _stream()), "mw_stream_step")
+
+    def mw_ctx_set_options(self, options: int):
+        _check(load().mw_ctx_set_options(self._h, C.c_uint32(options)), "mw_ctx_set_options")
 
     def mw_ctx_set_ride_wait_limit(self, polls: int):
         _check(load().mw_ctx_set_ride_wait_limit(self._h, C.c_int64(polls)), "mw_ctx_set_ride_wait_limit")

@@ -176,6 +176,7 @@ MW_API int32_t mw_ctx_create(const mw_config *cfg, void *workspace_dev, int64_t 
     ctx->n_hops = 0;
     ctx->recv_rows_hint = 0;
     ctx->ride_wait_limit = 1u << 21;
+    ctx->options = 0;
     ctx->d_hop_bits = (uint64_t *)(b + w.hop_bits);
     ctx->d_relay_flags = (uint32_t *)(b + w.hop_bits + 8LL * MW_MASK_WORDS * MW_MAX_HOPS);
     ctx->d_group_of_row = (int32_t *)(b + w.group_of_row);
@@ -747,6 +748,13 @@ MW_API int32_t mw_ctx_set_ride_wait_limit(mw_ctx *ctx, int64_t polls)
 {
     if (!ctx || polls < 0 || polls > 0x7fffffffLL) return MW_ERR_INVALID_ARG;
     ctx->ride_wait_limit = (uint32_t)polls;
+    return MW_OK;
+}
+
+MW_API int32_t mw_ctx_set_options(mw_ctx *ctx, uint32_t options)
+{
+    if (!ctx || (options & ~(uint32_t)(MW_OPT_RELAY_KEEP_METADATA | MW_OPT_RECV_DEDUP))) return MW_ERR_INVALID_ARG;
+    ctx->options = options;
     return MW_OK;
 }
 

@@ -75,6 +75,7 @@ struct mw_ctx {
     uint64_t *d_row_cnt;        // [max_tokens] a packed row's counters (large-batch plan, or null)
     unsigned char *d_row_start; // [max_tokens] 1: a group starts at this packed row
     uint32_t ride_wait_limit;   // polls a riding plan's second half waits for its first
+    uint32_t options;           // MW_OPT_*
     uint32_t *d_flags;      // [4] 1: receive flags, 2: receive workgroups done
     uint32_t *d_base;       // [L][R] first output row of (local expert, peer)
     mw_row_rec *d_recs;     // [max_recv_rows]

@@ -53,6 +53,7 @@ struct mw_relay_index_args {
     const mw_recv_peer *in; const mw_relay_child *children; int n_hops, n_ranks;
     uint32_t max_tokens, cap; uint64_t row_bytes; const uint64_t *hop_bits;
     int32_t *group_of_row; uint32_t *child_pos; uint32_t *relay_flags; mw_relay_stats *stats;
+    uint32_t keep_metadata;     // 1: children carry the parent's bitmaps (Section 4.1: the update may be omitted)
 };
 
 // Workgroup `wg` of the relay index: wg < n_hops builds child wg's descriptor table, wg == n_hops
@@ -61,7 +62,7 @@ __device__ __forceinline__ void relay_index_body(
     const mw_recv_peer *__restrict__ in, const mw_relay_child *__restrict__ children, int n_hops, int n_ranks,
     uint32_t max_tokens, uint32_t cap, uint64_t row_bytes, const uint64_t *__restrict__ hop_bits,
     int32_t *__restrict__ group_of_row, uint32_t *__restrict__ child_pos, uint32_t *relay_flags,
-    mw_relay_stats *__restrict__ stats, const int wg)
+    mw_relay_stats *__restrict__ stats, const uint32_t keep_metadata, const int wg)
 {
     const uint32_t bs = blockDim.x;
     __shared__ uint32_t scratch[17];
@@ -94,6 +95,16 @@ __device__ __forceinline__ void relay_index_body(
 #pragma unroll
             for (int w = 0; w < MW_MASK_WORDS; ++w) { sub[w] = v.m[w] & hb[w]; nd += (uint32_t)__popcll(sub[w]); }
             const bool keep = v.valid && nd > 0;
+            if (keep_metadata) {                 // the copy carries every destination the parent named
+                nd = 0;
+#pragma unroll
+                for (int w = 0; w < MW_MASK_WORDS; ++w) {
+                    const int lo = w * 64;
+                    const uint64_t ok = (n_ranks >= lo + 64) ? ~0ull : (n_ranks > lo ? ((1ull << (n_ranks - lo)) - 1ull) : 0ull);
+                    sub[w] = v.m[w] & ok;
+                    nd += (uint32_t)__popcll(sub[w]);
+                }
+            }
             uint32_t tot_g, tot_r;
             const uint32_t cg = carry_g + mw_block_exscan(keep ? 1u : 0u, scratch, &tot_g);
             const uint32_t cr = carry_r + mw_block_exscan(keep ? v.cnt : 0u, scratch, &tot_r);
@@ -183,7 +194,7 @@ __device__ __forceinline__ void relay_index_body(
 __global__ __launch_bounds__(kBlock) void k_relay_index(const mw_relay_index_args a)
 {
     relay_index_body(a.in, a.children, a.n_hops, a.n_ranks, a.max_tokens, a.cap, a.row_bytes, a.hop_bits,
-                     a.group_of_row, a.child_pos, a.relay_flags, a.stats, (int)blockIdx.x);
+                     a.group_of_row, a.child_pos, a.relay_flags, a.stats, a.keep_metadata, (int)blockIdx.x);
 }
 
 // blockIdx.x selects a segment of blockDim.x chunks of a row; rows i_first, i_first + i_stride, ...
@@ -262,7 +273,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
     if (blockIdx.x == 0)
         relay_index_body(next.in, next.children, next.n_hops, next.n_ranks, next.max_tokens, next.cap, next.row_bytes,
                          next.hop_bits, next.group_of_row, next.child_pos, next.relay_flags, next.stats,
-                         (int)blockIdx.y);
+                         next.keep_metadata, (int)blockIdx.y);
 }
 
 // ---- the same step for packets (Section 4.1, "Replication and forwarding": the relay parses the
@@ -384,7 +395,7 @@ __device__ __forceinline__ void relay_packets_copy_body(
     const mw_recv_packets *__restrict__ in, void *const *__restrict__ children, int n_hops, int n_chunks,
     uint32_t max_tokens, uint64_t packet_bytes, const uint64_t *__restrict__ hop_bits,
     const uint32_t *__restrict__ child_pos, uint32_t *relay_flags, mw_relay_stats *__restrict__ stats,
-    const uint32_t i_first, const uint32_t i_stride)
+    const uint32_t keep_metadata, const uint32_t i_first, const uint32_t i_stride)
 {
     const mw_recv_packets src = in[0];
     const uint32_t n_rows = min(src.n_rows, max_tokens);
@@ -400,7 +411,7 @@ __device__ __forceinline__ void relay_packets_copy_body(
             hops &= hops - 1;
             const uint32_t dst = (uint32_t)__shfl((int)p, h, 64);
             u32x4 o = v;
-            if (c < 2) {                                      // chunks 0 and 1 are the bitmap
+            if (c < 2 && !keep_metadata) {                    // chunks 0 and 1 are the bitmap: restricted to the hop's ranks
                 const uint64_t b0 = hop_bits[(size_t)h * MW_MASK_WORDS + 2 * c];
                 const uint64_t b1 = hop_bits[(size_t)h * MW_MASK_WORDS + 2 * c + 1];
                 o.x &= (uint32_t)b0; o.y &= (uint32_t)(b0 >> 32); o.z &= (uint32_t)b1; o.w &= (uint32_t)(b1 >> 32);
@@ -420,10 +431,11 @@ __device__ __forceinline__ void relay_packets_copy_body(
 __global__ __launch_bounds__(1024) void k_relay_packets_copy(
     const mw_recv_packets *__restrict__ in, void *const *__restrict__ children, int n_hops, int n_chunks,
     uint32_t max_tokens, uint64_t packet_bytes, const uint64_t *__restrict__ hop_bits,
-    const uint32_t *__restrict__ child_pos, uint32_t *relay_flags, mw_relay_stats *__restrict__ stats)
+    const uint32_t *__restrict__ child_pos, uint32_t *relay_flags, mw_relay_stats *__restrict__ stats,
+    const uint32_t keep_metadata)
 {
     relay_packets_copy_body(in, children, n_hops, n_chunks, max_tokens, packet_bytes, hop_bits, child_pos, relay_flags,
-                            stats, blockIdx.y, gridDim.y);
+                            stats, keep_metadata, blockIdx.y, gridDim.y);
 }
 
 // The packets' form of k_relay_copy_index_next: this buffer's copy with the next buffer's index
@@ -433,11 +445,12 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
     const mw_recv_packets *__restrict__ in, void *const *__restrict__ children, int n_hops, int n_chunks,
     uint32_t max_tokens, uint64_t packet_bytes, const uint64_t *__restrict__ hop_bits,
     const uint32_t *__restrict__ child_pos, uint32_t *relay_flags, mw_relay_stats *__restrict__ stats,
-    const mw_relay_packets_index_args next)
+    const uint32_t keep_metadata, const mw_relay_packets_index_args next)
 {
     if (blockIdx.y >= first_copy_row) {
         relay_packets_copy_body(in, children, n_hops, n_chunks, max_tokens, packet_bytes, hop_bits, child_pos,
-                                relay_flags, stats, blockIdx.y - first_copy_row, gridDim.y - first_copy_row);
+                                relay_flags, stats, keep_metadata, blockIdx.y - first_copy_row,
+                                gridDim.y - first_copy_row);
         return;
     }
     if (blockIdx.x == 0)
@@ -456,6 +469,7 @@ static mw_relay_index_args relay_index_args(mw_ctx *ctx, const mw_recv_peer *in,
     a.max_tokens = (uint32_t)ctx->cfg.max_tokens; a.cap = (uint32_t)cap; a.row_bytes = (uint64_t)ctx->row_bytes;
     a.hop_bits = ctx->d_hop_bits; a.group_of_row = ctx->d_group_of_row; a.child_pos = ctx->d_child_pos;
     a.relay_flags = ctx->d_relay_flags; a.stats = stats;
+    a.keep_metadata = (ctx->options & MW_OPT_RELAY_KEEP_METADATA) ? 1u : 0u;
     return a;
 }
 
@@ -548,6 +562,7 @@ int32_t mw_launch_relay_packets_copy(mw_ctx *ctx, const mw_recv_packets *in, voi
     const mw_config &c = ctx->cfg;
     const uint64_t pb = (uint64_t)(mw_packet_header_bytes_of(c.top_k) + ctx->row_bytes);
     const int n_chunks = (int)(pb / 16);
+    const uint32_t keep = (ctx->options & MW_OPT_RELAY_KEEP_METADATA) ? 1u : 0u;
     mw_row_shape shape = mw_row_shape_of(n_chunks);
     uint32_t gy = (uint32_t)c.max_tokens < kRowGridMax ? (uint32_t)c.max_tokens : kRowGridMax;
     if (gy < 1) gy = 1;
@@ -556,7 +571,7 @@ int32_t mw_launch_relay_packets_copy(mw_ctx *ctx, const mw_recv_packets *in, voi
         if (!next) {
             hipLaunchKernelGGL(k_relay_packets_copy, dim3(shape.nseg, gy), dim3(shape.bs), 0, s, in, children, ctx->n_hops,
                                n_chunks, (uint32_t)c.max_tokens, pb, ctx->d_hop_bits, ctx->d_child_pos,
-                               ctx->d_relay_flags, stats);
+                               ctx->d_relay_flags, stats, keep);
         } else {
             // long packets: a few large workgroups per packet instead of single waves, for the
             // riding index's sake (see mw_launch_relay_copy); pieces stay whole cache lines
@@ -566,7 +581,7 @@ int32_t mw_launch_relay_packets_copy(mw_ctx *ctx, const mw_recv_packets *in, voi
             }
             hipLaunchKernelGGL(k_relay_packets_copy_index_next, dim3(shape.nseg, gy + (uint32_t)next->n_hops + 1u),
                                dim3(shape.bs), 0, s, (uint32_t)next->n_hops + 1u, 0u, in, children, ctx->n_hops, n_chunks, (uint32_t)c.max_tokens, pb,
-                               ctx->d_hop_bits, ctx->d_child_pos, ctx->d_relay_flags, stats,
+                               ctx->d_hop_bits, ctx->d_child_pos, ctx->d_relay_flags, stats, keep,
                                relay_packets_index_args(next, next_in, next_cap, next_stats));
         }
     }

@@ -98,6 +98,7 @@ struct mw_index_args {
     uint32_t max_tokens, wpl, cap_rows; uint64_t row_bytes; uint32_t header_bytes; int64_t out_cap;
     uint32_t *cnt, *row_base, *addr_cnt; mw_row_rec *recs; mw_hit *hits; uint32_t *base;
     int64_t *expert_offsets; mw_recv_stats *stats; uint32_t *flags;
+    uint32_t dedup;     // 1: of the rows of one peer that carry the same source token only one is taken
 };
 
 // The work of workgroup `p` (peer p) of the index; any workgroup size that is a multiple of 64.
@@ -112,14 +113,15 @@ __device__ __forceinline__ void recv_index_body(
     uint32_t max_tokens, uint32_t wpl, uint32_t cap_rows, uint64_t row_bytes, uint32_t header_bytes, int64_t out_cap,
     uint32_t *cnt, uint32_t *row_base, uint32_t *addr_cnt, mw_row_rec *__restrict__ recs,
     mw_hit *__restrict__ hits, uint32_t *__restrict__ base, int64_t *__restrict__ expert_offsets,
-    mw_recv_stats *__restrict__ stats, uint32_t *flags, const int p)
+    mw_recv_stats *__restrict__ stats, uint32_t *flags, const uint32_t dedup, const int p)
 {
     extern __shared__ uint32_t lds[];
     uint32_t *addr = lds;                       // [wpl]      bit i: row i's group names this rank
     uint32_t *bits = addr + wpl;                // [Lc][wpl]  bit s of expert l: a row with source token s
     uint32_t *pre = bits + (size_t)Lc * wpl;    // [Lc][wpl]  running popcount before each word
     uint32_t *scratch = pre + (size_t)Lc * wpl; // [17] scan scratch, [17] "I am last", [18] addressed rows,
-                                                // [19] rows of the peers before this one
+                                                // [19] rows of the peers before this one, [20] repeats dropped
+    uint32_t *seen = scratch + 64;              // [wpl]      (dedup only) bit s: a row with source token s was taken
 
     const int tid = threadIdx.x, nthr = blockDim.x;
     mw_recv_peer pr;
@@ -183,8 +185,9 @@ __device__ __forceinline__ void recv_index_body(
     for (int q = tid; q < p; q += nthr) part += min(rows_of_peer(q), max_tokens);
 
     for (uint32_t w = tid; w < wpl; w += nthr) addr[w] = 0;
+    if (dedup) for (uint32_t w = tid; w < wpl; w += nthr) seen[w] = 0;
     if (one_chunk) for (uint32_t w = tid; w < (uint32_t)L * wpl; w += nthr) bits[w] = 0;
-    if (tid < 2) scratch[18 + tid] = 0;
+    if (tid < 3) scratch[18 + tid] = 0;
     mw_lds_barrier();
     // at most 256 peers of at most 65536 rows, so 32 bits are enough; a sum, so order-free
 #pragma unroll
@@ -335,6 +338,11 @@ __device__ __forceinline__ void recv_index_body(
             const uint32_t s = first ? s_c : token_of(i);
             if (s >= max_tokens) {
                 err |= MW_FLAG_BAD_SRC_TOKEN;
+            } else if (dedup && ((atomicOr(&seen[s >> 5], 1u << (s & 31)) >> (s & 31)) & 1u)) {
+                // a repeat of a row already taken (a relay forwarded without updating the metadata,
+                // Section 4.1): dropped.  Repeats are copies, so which of them is taken does not matter.
+                err |= MW_FLAG_DUPLICATE_DROPPED;
+                atomicAdd(&scratch[20], 1u);
             } else {
                 int f[8] = {0, 0, 0, 0, 0, 0, 0, 0};
                 const int nk = parse(i, first, f);
@@ -415,7 +423,7 @@ __device__ __forceinline__ void recv_index_body(
         for (uint32_t w = tid; w < wpl; w += nthr) if (addr[w]) err |= MW_FLAG_NO_LOCAL_EXPERT;
     }
     if (err) __hip_atomic_fetch_or(&flags[1], err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (tid == 0) st_agent(&addr_cnt[p], scratch[18]);
+    if (tid == 0) st_agent(&addr_cnt[p], scratch[18] - scratch[20]);    // (both complete: barriers in between)
 
     // ---- the workgroup that finishes last turns the counts into output bases ----------
     // Everything the last workgroup reads (counts, addressed-row counts, flags) is written and
@@ -436,7 +444,7 @@ __device__ __forceinline__ void recv_index_of(const mw_index_args &a, int p)
 {
     recv_index_body<kPackets, kCache>(a.peers, a.P, a.eslot, a.E, a.K, a.Kd, a.my_rank, a.L, a.Lc, a.max_tokens, a.wpl,
                               a.cap_rows, a.row_bytes, a.header_bytes, a.out_cap, a.cnt, a.row_base, a.addr_cnt, a.recs,
-                              a.hits, a.base, a.expert_offsets, a.stats, a.flags, p);
+                              a.hits, a.base, a.expert_offsets, a.stats, a.flags, a.dedup, p);
 }
 
 template <bool kPackets>
@@ -676,17 +684,19 @@ static bool make_index_args(mw_ctx *ctx, const void *peers, bool packets, int32_
     const mw_config &c = ctx->cfg;
     const int L = ctx->n_local;
     const uint32_t wpl = ((uint32_t)c.max_tokens + 31u) / 32u;
+    const uint32_t dedup = (ctx->options & MW_OPT_RECV_DEDUP) ? 1u : 0u;
+    if (dedup) lds_budget_words = lds_budget_words > wpl ? lds_budget_words - wpl : 0;     // the "taken" bitmap
     if (lds_budget_words < 3 * wpl + 64) return false;
     int Lc = (int)((lds_budget_words - 64 - wpl) / (2 * wpl));
     if (Lc < 1) return false;
     if (Lc > L) Lc = L > 0 ? L : 1;
-    *lds_bytes = ((size_t)wpl + 2 * (size_t)Lc * wpl + 64) * sizeof(uint32_t);
+    *lds_bytes = ((size_t)wpl + 2 * (size_t)Lc * wpl + 64 + (dedup ? wpl : 0)) * sizeof(uint32_t);
     const uint32_t hb = packets ? (uint32_t)mw_packet_header_bytes_of(c.top_k) : 0u;
     *a = mw_index_args{peers, P, ctx->d_eslot, c.n_experts, c.top_k, ctx->hit_slots, c.my_rank, L, Lc,
                        (uint32_t)c.max_tokens, wpl, (uint32_t)c.max_recv_rows,
                        (uint64_t)(packets ? hb + ctx->row_bytes : ctx->row_stride), hb, cap,
                        ctx->d_cnt, ctx->d_row_base, ctx->d_addr_cnt, ctx->d_recs, ctx->d_hits, ctx->d_base,
-                       expert_offsets, stats, ctx->d_flags};
+                       expert_offsets, stats, ctx->d_flags, dedup};
     return true;
 }
 
