@@ -369,35 +369,76 @@ MW_API int32_t mw_unpack_expand(mw_ctx *ctx, int32_t n_peers, void *out_rows_dev
                          int64_t out_capacity_rows, int32_t *out_src_peer_dev, int32_t *out_src_token_dev, void *stream);
 
 /*
+ * Batches of a steady stream, as the launches that handle several batches at once take them:
+ * three small records the caller fills in host memory (read during the call only; every *_dev
+ * member points to device memory and has the meaning, layout and ownership of the argument of
+ * the same name of the call named beside it; reserved members are zero).
+ */
+typedef struct mw_send_batch {       /* this rank's batch to send: the arguments of mw_pack */
+    const void *x_dev;
+    const float *scales_dev;
+    const int32_t *topk_ids_dev;
+    const int32_t *perm_dev;             /* from a plan that an EARLIER launch completed */
+    const mw_send_stats *stats_dev;      /* ditto */
+    void *packed_rows_dev;
+    int32_t *row_src_token_dev;
+    int32_t *row_topk_dev;
+    int32_t n_tokens;
+    int32_t reserved0;
+} mw_send_batch;
+
+typedef struct mw_recv_batch {       /* the received batch whose index the context holds: the arguments of mw_unpack_expand */
+    void *out_rows_dev;
+    float *out_scales_dev;
+    int32_t *out_src_peer_dev;
+    int32_t *out_src_token_dev;
+    int64_t out_capacity_rows;
+    int32_t n_peers;
+    int32_t reserved0;
+} mw_recv_batch;
+
+typedef struct mw_next_batch {       /* the batch after: the arguments of mw_unpack_index and of mw_plan on `ctx` */
+    mw_ctx *ctx;                         /* another context on the same device: its workspace takes the index (and the plan) */
+    const mw_recv_peer *peers_dev;       /* mw_unpack_index ... */
+    int64_t *expert_offsets_dev;
+    mw_recv_stats *recv_stats_dev;
+    int64_t out_capacity_rows;
+    int32_t n_peers;
+    int32_t n_tokens;                    /* mw_plan ... (the five members from here on are read by the calls that plan only) */
+    const int32_t *topk_ids_dev;
+    uint64_t *mask_dev;
+    int32_t *perm_dev;
+    mw_group_desc *desc_dev;
+    mw_send_stats *send_stats_dev;
+} mw_next_batch;
+
+/*
  * mw_unpack_expand_index_next: for a steady stream of batches.  One launch does what
- * mw_unpack_expand(ctx, ...) does for the batch whose index `ctx` holds, and what
- * mw_unpack_index(next_ctx, next_peers_dev, ...) does for the NEXT batch: the index, a
+ * mw_unpack_expand(ctx, recv->...) does for the batch whose index `ctx` holds, and what
+ * mw_unpack_index(next->ctx, next->peers_dev, ...) does for the NEXT batch: the index, a
  * latency-bound kernel that moves almost nothing, rides along with the bandwidth-bound
  * expander of the batch before it instead of standing in front of its own.  The call after
  * this one on the same stream (with the roles of the two contexts exchanged) finds the next
  * batch's index complete: launches on a stream are ordered.  Outputs of both halves are
- * exactly those of the separate calls.  `ctx` and `next_ctx` must be different contexts on
- * the same device (each holds one index in its workspace); arguments as for the two calls.
+ * exactly those of the separate calls.  `ctx` and `next->ctx` must be different contexts on
+ * the same device (each holds one index in its workspace); arguments as for the two calls
+ * (the plan members of `next` are not read).
  * MW_ERR_UNSUPPORTED if the next context's index needs more than 5 KiB of LDS per workgroup
  * (max_tokens above about 8000 with several local experts): use the separate calls then.
  */
-MW_API int32_t mw_unpack_expand_index_next(mw_ctx *ctx, int32_t n_peers, void *out_rows_dev, float *out_scales_dev,
-                                    int64_t out_capacity_rows, int32_t *out_src_peer_dev,
-                                    int32_t *out_src_token_dev, mw_ctx *next_ctx,
-                                    const mw_recv_peer *next_peers_dev, int32_t next_n_peers,
-                                    int64_t next_out_capacity_rows, int64_t *next_expert_offsets_dev,
-                                    mw_recv_stats *next_recv_stats_dev, void *stream);
+MW_API int32_t mw_unpack_expand_index_next(mw_ctx *ctx, const mw_recv_batch *recv, const mw_next_batch *next,
+                                           void *stream);
 
 /*
  * mw_unpack_expand_index_plan_next: mw_unpack_expand_index_next with the send-side plan of the
- * next batch in the same launch as well -- what mw_plan(next_ctx, next_topk_ids_dev,
- * next_n_tokens, next_mask_dev, next_perm_dev, next_desc_dev, next_send_stats_dev) does, with
- * exactly its outputs (Section 5.1, send module).  The plan, too, is a chain of memory round
+ * next batch in the same launch as well -- what mw_plan(next->ctx, next->topk_ids_dev,
+ * next->n_tokens, next->mask_dev, next->perm_dev, next->desc_dev, next->send_stats_dev) does,
+ * with exactly its outputs (Section 5.1, send module).  The plan, too, is a chain of memory round
  * trips that moves almost nothing; here it runs in the shadow of the expander.  A steady
  * stream of batches is then two launches per batch on ONE stream, with no event between them:
  *     mw_pack(batch n);  mw_unpack_expand_index_plan_next(expand n; index n+1; plan n+1);
  *     mw_pack(batch n+1);  ...
- * The plan uses the plan part of next_ctx's workspace (see the conventions above); its outputs
+ * The plan uses the plan part of next->ctx's workspace (see the conventions above); its outputs
  * are complete when this launch is, i.e. for every later call on the same stream.  The riding
  * plan ranks tokens all-pairs (as mw_plan does up to about 8000 tokens): it stays in the
  * expander's shadow while that takes less time than the expander -- 4096 tokens beside 30000
@@ -407,49 +448,31 @@ MW_API int32_t mw_unpack_expand_index_next(mw_ctx *ctx, int32_t n_peers, void *o
  * earlier in the same launch and wait for nothing themselves); the wait is bounded (about a
  * second by default, mw_ctx_set_ride_wait_limit).  Past the bound -- not observed, and not
  * expected on hardware that starts a launch's workgroups in order -- the plan is given up:
- * next_send_stats_dev reports MW_FLAG_PLAN_TIMEOUT with zero rows and the other plan outputs
+ * next->send_stats_dev reports MW_FLAG_PLAN_TIMEOUT with zero rows and the other plan outputs
  * are undefined.  Nothing else is lost: the receive side of the launch is unaffected, the launch
- * itself leaves the plan part of next_ctx's workspace clean once its last workgroup is done with
- * it, and the next plan on next_ctx (riding or not) works as usual.
- * MW_ERR_UNSUPPORTED if next_n_tokens > MW_RIDE_MAX_TOKENS (larger batches: mw_plan), or where
- * mw_unpack_expand_index_next returns it; MW_ERR_CAPACITY if next_n_tokens > max_tokens of
- * next_ctx.
+ * itself leaves the plan part of next->ctx's workspace clean once its last workgroup is done with
+ * it, and the next plan on next->ctx (riding or not) works as usual.
+ * MW_ERR_UNSUPPORTED if next->n_tokens > MW_RIDE_MAX_TOKENS (larger batches: mw_plan), or where
+ * mw_unpack_expand_index_next returns it; MW_ERR_CAPACITY if next->n_tokens > max_tokens of
+ * next->ctx.
  */
-MW_API int32_t mw_unpack_expand_index_plan_next(mw_ctx *ctx, int32_t n_peers, void *out_rows_dev, float *out_scales_dev,
-                                         int64_t out_capacity_rows, int32_t *out_src_peer_dev,
-                                         int32_t *out_src_token_dev, mw_ctx *next_ctx,
-                                         const mw_recv_peer *next_peers_dev, int32_t next_n_peers,
-                                         int64_t next_out_capacity_rows, int64_t *next_expert_offsets_dev,
-                                         mw_recv_stats *next_recv_stats_dev, const int32_t *next_topk_ids_dev,
-                                         int32_t next_n_tokens, uint64_t *next_mask_dev, int32_t *next_perm_dev,
-                                         mw_group_desc *next_desc_dev, mw_send_stats *next_send_stats_dev,
-                                         void *stream);
+MW_API int32_t mw_unpack_expand_index_plan_next(mw_ctx *ctx, const mw_recv_batch *recv, const mw_next_batch *next,
+                                                void *stream);
 
 /*
  * mw_stream_step: a whole step of a steady stream of batches in ONE launch -- what
- *     mw_pack(ctx, x_dev, scales_dev, topk_ids_dev, perm_dev, stats_dev, n_tokens, packed_rows_dev,
- *             row_src_token_dev, row_topk_dev)
- * and
- *     mw_unpack_expand_index_plan_next(ctx, n_peers, out_*, next_ctx, next_*)
+ *     mw_pack(ctx, send->...)   and   mw_unpack_expand_index_plan_next(ctx, recv, next)
  * do, with exactly their outputs: this rank's next batch to send is packed (Section 5.1, send
  * module) while an earlier received batch is expanded, the batch received after that is indexed
  * (receive module) and the batch to send after this one is planned.  The two bandwidth-bound
  * parts then run as one stream of small workgroups with no launch boundary between them, and
- * the latency-bound parts ride along.  perm_dev and stats_dev must come from a plan that an
- * EARLIER launch completed (mw_plan, or the plan half of the previous mw_stream_step); the
- * payload rows (x_dev, scales_dev) and the row format are those of `ctx`.  Errors as for the
- * two calls.
+ * the latency-bound parts ride along.  send->perm_dev and send->stats_dev must come from a plan
+ * that an EARLIER launch completed (mw_plan, or the plan half of the previous mw_stream_step);
+ * the payload rows (send->x_dev, send->scales_dev) and the row format are those of `ctx`.
+ * Errors as for the two calls.
  */
-MW_API int32_t mw_stream_step(mw_ctx *ctx, const void *x_dev, const float *scales_dev, const int32_t *topk_ids_dev,
-                       const int32_t *perm_dev, const mw_send_stats *stats_dev, int32_t n_tokens,
-                       void *packed_rows_dev, int32_t *row_src_token_dev, int32_t *row_topk_dev, int32_t n_peers,
-                       void *out_rows_dev, float *out_scales_dev, int64_t out_capacity_rows,
-                       int32_t *out_src_peer_dev, int32_t *out_src_token_dev, mw_ctx *next_ctx,
-                       const mw_recv_peer *next_peers_dev, int32_t next_n_peers, int64_t next_out_capacity_rows,
-                       int64_t *next_expert_offsets_dev, mw_recv_stats *next_recv_stats_dev,
-                       const int32_t *next_topk_ids_dev, int32_t next_n_tokens, uint64_t *next_mask_dev,
-                       int32_t *next_perm_dev, mw_group_desc *next_desc_dev, mw_send_stats *next_send_stats_dev,
-                       void *stream);
+MW_API int32_t mw_stream_step(mw_ctx *ctx, const mw_send_batch *send, const mw_recv_batch *recv,
+                              const mw_next_batch *next, void *stream);
 
 /*
  * mw_combine_gather: the way back (Section 2.1, combine-style AlltoAll).  The paper notes that

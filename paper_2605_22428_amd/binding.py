@@ -71,6 +71,29 @@ class MwConfig(C.Structure):
                 ("max_recv_rows", C.c_int64), ("expert_to_rank", C.c_void_p), ("row_stride_bytes", C.c_int64)]
 
 
+class MwSendBatch(C.Structure):
+    """mw_send_batch (include/mw.h)."""
+    _fields_ = [("x_dev", C.c_void_p), ("scales_dev", C.c_void_p), ("topk_ids_dev", C.c_void_p),
+                ("perm_dev", C.c_void_p), ("stats_dev", C.c_void_p), ("packed_rows_dev", C.c_void_p),
+                ("row_src_token_dev", C.c_void_p), ("row_topk_dev", C.c_void_p), ("n_tokens", C.c_int32),
+                ("reserved0", C.c_int32)]
+
+
+class MwRecvBatch(C.Structure):
+    """mw_recv_batch (include/mw.h)."""
+    _fields_ = [("out_rows_dev", C.c_void_p), ("out_scales_dev", C.c_void_p), ("out_src_peer_dev", C.c_void_p),
+                ("out_src_token_dev", C.c_void_p), ("out_capacity_rows", C.c_int64), ("n_peers", C.c_int32),
+                ("reserved0", C.c_int32)]
+
+
+class MwNextBatch(C.Structure):
+    """mw_next_batch (include/mw.h)."""
+    _fields_ = [("ctx", C.c_void_p), ("peers_dev", C.c_void_p), ("expert_offsets_dev", C.c_void_p),
+                ("recv_stats_dev", C.c_void_p), ("out_capacity_rows", C.c_int64), ("n_peers", C.c_int32),
+                ("n_tokens", C.c_int32), ("topk_ids_dev", C.c_void_p), ("mask_dev", C.c_void_p),
+                ("perm_dev", C.c_void_p), ("desc_dev", C.c_void_p), ("send_stats_dev", C.c_void_p)]
+
+
 class MwError(RuntimeError):
     def __init__(self, status: int, where: str):
         super().__init__("%s: %s (%d)" % (where, status_string(status), status))
@@ -135,6 +158,28 @@ def mw_plan_static(n_ranks: int, n_experts: int, top_k: int, hidden: int, row_fo
     cfg = MwConfig(n_ranks, n_experts, top_k, 0, hidden, row_format, row_bytes, 0, 0, 0, 0, 0)
     _check(load().mw_plan_static(C.byref(cfg), _ptr(expert_to_rank), _ptr(topk_ids), C.c_int32(topk_ids.shape[0]),
                                  _ptr(mask), _ptr(perm), _ptr(desc), _ptr(stats), _stream()), "mw_plan_static")
+
+
+def _addr(t: Optional[torch.Tensor]) -> int:
+    return 0 if t is None else t.data_ptr()
+
+
+def send_batch(x, scales, topk_ids, perm, stats, packed, row_src_token, row_topk) -> MwSendBatch:
+    return MwSendBatch(_addr(x), _addr(scales), _addr(topk_ids), _addr(perm), _addr(stats), _addr(packed),
+                       _addr(row_src_token), _addr(row_topk), int(topk_ids.shape[0]), 0)
+
+
+def recv_batch(n_peers, out_rows, out_scales, out_capacity_rows, out_src_peer, out_src_token) -> MwRecvBatch:
+    return MwRecvBatch(_addr(out_rows), _addr(out_scales), _addr(out_src_peer), _addr(out_src_token),
+                       int(out_capacity_rows), int(n_peers), 0)
+
+
+def next_batch(next_ctx, peers, n_peers, out_capacity_rows, expert_offsets, recv_stats, topk_ids=None, mask=None,
+               perm=None, desc=None, send_stats=None) -> MwNextBatch:
+    return MwNextBatch(next_ctx._h.value if next_ctx is not None else 0, _addr(peers), _addr(expert_offsets),
+                       _addr(recv_stats), int(out_capacity_rows), int(n_peers),
+                       0 if topk_ids is None else int(topk_ids.shape[0]), _addr(topk_ids), _addr(mask), _addr(perm),
+                       _addr(desc), _addr(send_stats))
 
 
 class Context:
@@ -268,11 +313,11 @@ class Context:
                                     next_ctx: "Context", next_peers: torch.Tensor, next_n_peers: int,
                                     next_out_capacity_rows: int, next_expert_offsets: torch.Tensor,
                                     next_recv_stats: torch.Tensor):
-        _check(load().mw_unpack_expand_index_next(
-            self._h, C.c_int32(n_peers), _ptr(out_rows), _ptr(out_scales), C.c_int64(out_capacity_rows),
-            _ptr(out_src_peer), _ptr(out_src_token), next_ctx._h, _ptr(next_peers), C.c_int32(next_n_peers),
-            C.c_int64(next_out_capacity_rows), _ptr(next_expert_offsets), _ptr(next_recv_stats), _stream()),
-            "mw_unpack_expand_index_next")
+        recv = recv_batch(n_peers, out_rows, out_scales, out_capacity_rows, out_src_peer, out_src_token)
+        nxt = next_batch(next_ctx, next_peers, next_n_peers, next_out_capacity_rows, next_expert_offsets,
+                         next_recv_stats)
+        _check(load().mw_unpack_expand_index_next(self._h, C.byref(recv), C.byref(nxt), _stream()),
+               "mw_unpack_expand_index_next")
 
     def mw_unpack_expand_index_plan_next(self, n_peers: int, out_rows: torch.Tensor,
                                          out_scales: Optional[torch.Tensor], out_capacity_rows: int,
@@ -282,12 +327,11 @@ class Context:
                                          next_recv_stats: torch.Tensor, next_topk_ids: torch.Tensor,
                                          next_mask: torch.Tensor, next_perm: torch.Tensor, next_desc: torch.Tensor,
                                          next_send_stats: torch.Tensor):
-        _check(load().mw_unpack_expand_index_plan_next(
-            self._h, C.c_int32(n_peers), _ptr(out_rows), _ptr(out_scales), C.c_int64(out_capacity_rows),
-            _ptr(out_src_peer), _ptr(out_src_token), next_ctx._h, _ptr(next_peers), C.c_int32(next_n_peers),
-            C.c_int64(next_out_capacity_rows), _ptr(next_expert_offsets), _ptr(next_recv_stats),
-            _ptr(next_topk_ids), C.c_int32(next_topk_ids.shape[0]), _ptr(next_mask), _ptr(next_perm),
-            _ptr(next_desc), _ptr(next_send_stats), _stream()), "mw_unpack_expand_index_plan_next")
+        recv = recv_batch(n_peers, out_rows, out_scales, out_capacity_rows, out_src_peer, out_src_token)
+        nxt = next_batch(next_ctx, next_peers, next_n_peers, next_out_capacity_rows, next_expert_offsets,
+                         next_recv_stats, next_topk_ids, next_mask, next_perm, next_desc, next_send_stats)
+        _check(load().mw_unpack_expand_index_plan_next(self._h, C.byref(recv), C.byref(nxt), _stream()),
+               "mw_unpack_expand_index_plan_next")
 
     def mw_stream_step(self, x: torch.Tensor, scales: Optional[torch.Tensor], topk_ids: torch.Tensor,
                        perm: torch.Tensor, stats: torch.Tensor, packed: torch.Tensor, row_src_token: torch.Tensor,
@@ -297,13 +341,12 @@ class Context:
                        next_n_peers: int, next_out_capacity_rows: int, next_expert_offsets: torch.Tensor,
                        next_recv_stats: torch.Tensor, next_topk_ids: torch.Tensor, next_mask: torch.Tensor,
                        next_perm: torch.Tensor, next_desc: torch.Tensor, next_send_stats: torch.Tensor):
-        _check(load().mw_stream_step(
-            self._h, _ptr(x), _ptr(scales), _ptr(topk_ids), _ptr(perm), _ptr(stats), C.c_int32(topk_ids.shape[0]),
-            _ptr(packed), _ptr(row_src_token), _ptr(row_topk), C.c_int32(n_peers), _ptr(out_rows), _ptr(out_scales),
-            C.c_int64(out_capacity_rows), _ptr(out_src_peer), _ptr(out_src_token), next_ctx._h, _ptr(next_peers),
-            C.c_int32(next_n_peers), C.c_int64(next_out_capacity_rows), _ptr(next_expert_offsets),
-            _ptr(next_recv_stats), _ptr(next_topk_ids), C.c_int32(next_topk_ids.shape[0]), _ptr(next_mask),
-            _ptr(next_perm), _ptr(next_desc), _ptr(next_send_stats), _stream()), "mw_stream_step")
+        send = send_batch(x, scales, topk_ids, perm, stats, packed, row_src_token, row_topk)
+        recv = recv_batch(n_peers, out_rows, out_scales, out_capacity_rows, out_src_peer, out_src_token)
+        nxt = next_batch(next_ctx, next_peers, next_n_peers, next_out_capacity_rows, next_expert_offsets,
+                         next_recv_stats, next_topk_ids, next_mask, next_perm, next_desc, next_send_stats)
+        _check(load().mw_stream_step(self._h, C.byref(send), C.byref(recv), C.byref(nxt), _stream()),
+               "mw_stream_step")
 
     def mw_ctx_set_options(self, options: int):
         _check(load().mw_ctx_set_options(self._h, C.c_uint32(options)), "mw_ctx_set_options")

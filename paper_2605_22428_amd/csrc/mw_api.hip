@@ -419,96 +419,85 @@ MW_API int32_t mw_unpack_packets(mw_ctx *ctx, const mw_recv_packets *peers_dev, 
                                    out_src_token_dev, (hipStream_t)stream);
 }
 
-MW_API int32_t mw_unpack_expand_index_next(mw_ctx *ctx, int32_t n_peers, void *out_rows_dev, float *out_scales_dev,
-                                    int64_t out_capacity_rows, int32_t *out_src_peer_dev,
-                                    int32_t *out_src_token_dev, mw_ctx *next_ctx,
-                                    const mw_recv_peer *next_peers_dev, int32_t next_n_peers,
-                                    int64_t next_out_capacity_rows, int64_t *next_expert_offsets_dev,
-                                    mw_recv_stats *next_recv_stats_dev, void *stream)
+// the members of the three batch records, as the calls they stand for check their arguments
+static int32_t check_recv_batch(mw_ctx *ctx, const mw_recv_batch *r)
 {
-    if (!ctx || !next_ctx || ctx == next_ctx || ctx->device != next_ctx->device) return MW_ERR_INVALID_ARG;
-    MW_ON_DEVICE(ctx);
-    int32_t rc = check_unpack_expand(ctx, n_peers, out_rows_dev, out_scales_dev, out_capacity_rows, out_src_peer_dev,
-                                     out_src_token_dev);
-    if (rc == MW_OK)
-        rc = check_unpack_index(next_ctx, next_peers_dev, next_n_peers, next_out_capacity_rows, next_expert_offsets_dev,
-                                next_recv_stats_dev);
-    if (rc != MW_OK) return rc;
-    return mw_launch_unpack_expand_index_next(ctx, n_peers, out_rows_dev, out_scales_dev, out_capacity_rows,
-                                              out_src_peer_dev, out_src_token_dev, next_ctx, next_peers_dev, next_n_peers,
-                                              next_out_capacity_rows, next_expert_offsets_dev, next_recv_stats_dev,
-                                              (hipStream_t)stream);
+    if (!r || r->reserved0 != 0) return MW_ERR_INVALID_ARG;
+    return check_unpack_expand(ctx, r->n_peers, r->out_rows_dev, r->out_scales_dev, r->out_capacity_rows,
+                               r->out_src_peer_dev, r->out_src_token_dev);
 }
 
-MW_API int32_t mw_unpack_expand_index_plan_next(mw_ctx *ctx, int32_t n_peers, void *out_rows_dev, float *out_scales_dev,
-                                         int64_t out_capacity_rows, int32_t *out_src_peer_dev,
-                                         int32_t *out_src_token_dev, mw_ctx *next_ctx,
-                                         const mw_recv_peer *next_peers_dev, int32_t next_n_peers,
-                                         int64_t next_out_capacity_rows, int64_t *next_expert_offsets_dev,
-                                         mw_recv_stats *next_recv_stats_dev, const int32_t *next_topk_ids_dev,
-                                         int32_t next_n_tokens, uint64_t *next_mask_dev, int32_t *next_perm_dev,
-                                         mw_group_desc *next_desc_dev, mw_send_stats *next_send_stats_dev, void *stream)
+static int32_t check_next_batch(mw_ctx *ctx, const mw_next_batch *n, bool with_plan)
 {
-    if (!ctx || !next_ctx || ctx == next_ctx || ctx->device != next_ctx->device) return MW_ERR_INVALID_ARG;
-    MW_ON_DEVICE(ctx);
-    int32_t rc = check_unpack_expand(ctx, n_peers, out_rows_dev, out_scales_dev, out_capacity_rows, out_src_peer_dev,
-                                     out_src_token_dev);
-    if (rc == MW_OK)
-        rc = check_unpack_index(next_ctx, next_peers_dev, next_n_peers, next_out_capacity_rows, next_expert_offsets_dev,
-                                next_recv_stats_dev);
-    if (rc != MW_OK) return rc;
-    if (!next_send_stats_dev || next_n_tokens < 0) return MW_ERR_INVALID_ARG;
-    if (next_n_tokens > next_ctx->cfg.max_tokens) return MW_ERR_CAPACITY;
-    if (next_n_tokens > 0 && (!next_topk_ids_dev || !next_mask_dev || !next_perm_dev || !next_desc_dev))
-        return MW_ERR_INVALID_ARG;
-    return mw_launch_unpack_expand_index_plan_next(ctx, n_peers, out_rows_dev, out_scales_dev, out_capacity_rows,
-                                                   out_src_peer_dev, out_src_token_dev, next_ctx, next_peers_dev,
-                                                   next_n_peers, next_out_capacity_rows, next_expert_offsets_dev,
-                                                   next_recv_stats_dev, next_topk_ids_dev, next_n_tokens, next_mask_dev,
-                                                   next_perm_dev, next_desc_dev, next_send_stats_dev, nullptr,
-                                                   (hipStream_t)stream);
+    if (!n || !n->ctx || n->ctx == ctx || n->ctx->device != ctx->device) return MW_ERR_INVALID_ARG;
+    const int32_t rc = check_unpack_index(n->ctx, n->peers_dev, n->n_peers, n->out_capacity_rows, n->expert_offsets_dev,
+                                          n->recv_stats_dev);
+    if (rc != MW_OK || !with_plan) return rc;
+    if (!n->send_stats_dev || n->n_tokens < 0) return MW_ERR_INVALID_ARG;
+    if (n->n_tokens > n->ctx->cfg.max_tokens) return MW_ERR_CAPACITY;
+    if (n->n_tokens > 0 && (!n->topk_ids_dev || !n->mask_dev || !n->perm_dev || !n->desc_dev)) return MW_ERR_INVALID_ARG;
+    return MW_OK;
 }
 
-MW_API int32_t mw_stream_step(mw_ctx *ctx, const void *x_dev, const float *scales_dev, const int32_t *topk_ids_dev,
-                       const int32_t *perm_dev, const mw_send_stats *stats_dev, int32_t n_tokens,
-                       void *packed_rows_dev, int32_t *row_src_token_dev, int32_t *row_topk_dev, int32_t n_peers,
-                       void *out_rows_dev, float *out_scales_dev, int64_t out_capacity_rows,
-                       int32_t *out_src_peer_dev, int32_t *out_src_token_dev, mw_ctx *next_ctx,
-                       const mw_recv_peer *next_peers_dev, int32_t next_n_peers, int64_t next_out_capacity_rows,
-                       int64_t *next_expert_offsets_dev, mw_recv_stats *next_recv_stats_dev,
-                       const int32_t *next_topk_ids_dev, int32_t next_n_tokens, uint64_t *next_mask_dev,
-                       int32_t *next_perm_dev, mw_group_desc *next_desc_dev, mw_send_stats *next_send_stats_dev,
-                       void *stream)
+MW_API int32_t mw_unpack_expand_index_next(mw_ctx *ctx, const mw_recv_batch *recv, const mw_next_batch *next,
+                                           void *stream)
 {
-    if (!ctx || !next_ctx || ctx == next_ctx || ctx->device != next_ctx->device) return MW_ERR_INVALID_ARG;
+    if (!ctx) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
+    int32_t rc = check_recv_batch(ctx, recv);
+    if (rc == MW_OK) rc = check_next_batch(ctx, next, false);
+    if (rc != MW_OK) return rc;
+    return mw_launch_unpack_expand_index_next(ctx, recv->n_peers, recv->out_rows_dev, recv->out_scales_dev,
+                                              recv->out_capacity_rows, recv->out_src_peer_dev, recv->out_src_token_dev,
+                                              next->ctx, next->peers_dev, next->n_peers, next->out_capacity_rows,
+                                              next->expert_offsets_dev, next->recv_stats_dev, (hipStream_t)stream);
+}
+
+static int32_t launch_expand_index_plan(mw_ctx *ctx, const mw_recv_batch *recv, const mw_next_batch *next,
+                                        const mw_pack_call *pk, void *stream)
+{
+    return mw_launch_unpack_expand_index_plan_next(ctx, recv->n_peers, recv->out_rows_dev, recv->out_scales_dev,
+                                                   recv->out_capacity_rows, recv->out_src_peer_dev,
+                                                   recv->out_src_token_dev, next->ctx, next->peers_dev, next->n_peers,
+                                                   next->out_capacity_rows, next->expert_offsets_dev,
+                                                   next->recv_stats_dev, next->topk_ids_dev, next->n_tokens,
+                                                   next->mask_dev, next->perm_dev, next->desc_dev, next->send_stats_dev,
+                                                   pk, (hipStream_t)stream);
+}
+
+MW_API int32_t mw_unpack_expand_index_plan_next(mw_ctx *ctx, const mw_recv_batch *recv, const mw_next_batch *next,
+                                                void *stream)
+{
+    if (!ctx) return MW_ERR_INVALID_ARG;
+    MW_ON_DEVICE(ctx);
+    int32_t rc = check_recv_batch(ctx, recv);
+    if (rc == MW_OK) rc = check_next_batch(ctx, next, true);
+    if (rc != MW_OK) return rc;
+    return launch_expand_index_plan(ctx, recv, next, nullptr, stream);
+}
+
+MW_API int32_t mw_stream_step(mw_ctx *ctx, const mw_send_batch *send, const mw_recv_batch *recv,
+                              const mw_next_batch *next, void *stream)
+{
+    if (!ctx || !send) return MW_ERR_INVALID_ARG;
     MW_ON_DEVICE(ctx);
     // the packer's arguments, as mw_pack checks them
-    if (!stats_dev || n_tokens < 0) return MW_ERR_INVALID_ARG;
-    if (n_tokens > ctx->cfg.max_tokens) return MW_ERR_CAPACITY;
-    if (n_tokens > 0) {
-        if (!x_dev || !topk_ids_dev || !perm_dev || !packed_rows_dev || !row_src_token_dev || !row_topk_dev)
+    if (!send->stats_dev || send->n_tokens < 0 || send->reserved0 != 0) return MW_ERR_INVALID_ARG;
+    if (send->n_tokens > ctx->cfg.max_tokens) return MW_ERR_CAPACITY;
+    if (send->n_tokens > 0) {
+        if (!send->x_dev || !send->topk_ids_dev || !send->perm_dev || !send->packed_rows_dev ||
+            !send->row_src_token_dev || !send->row_topk_dev)
             return MW_ERR_INVALID_ARG;
-        if ((ctx->s_row_bytes > 0) != (scales_dev != nullptr)) return MW_ERR_INVALID_ARG;
-        if (((uintptr_t)x_dev | (uintptr_t)packed_rows_dev | (uintptr_t)scales_dev) & 15u) return MW_ERR_INVALID_ARG;
+        if ((ctx->s_row_bytes > 0) != (send->scales_dev != nullptr)) return MW_ERR_INVALID_ARG;
+        if (((uintptr_t)send->x_dev | (uintptr_t)send->packed_rows_dev | (uintptr_t)send->scales_dev) & 15u)
+            return MW_ERR_INVALID_ARG;
     }
-    int32_t rc = check_unpack_expand(ctx, n_peers, out_rows_dev, out_scales_dev, out_capacity_rows, out_src_peer_dev,
-                                     out_src_token_dev);
-    if (rc == MW_OK)
-        rc = check_unpack_index(next_ctx, next_peers_dev, next_n_peers, next_out_capacity_rows, next_expert_offsets_dev,
-                                next_recv_stats_dev);
+    int32_t rc = check_recv_batch(ctx, recv);
+    if (rc == MW_OK) rc = check_next_batch(ctx, next, true);
     if (rc != MW_OK) return rc;
-    if (!next_send_stats_dev || next_n_tokens < 0) return MW_ERR_INVALID_ARG;
-    if (next_n_tokens > next_ctx->cfg.max_tokens) return MW_ERR_CAPACITY;
-    if (next_n_tokens > 0 && (!next_topk_ids_dev || !next_mask_dev || !next_perm_dev || !next_desc_dev))
-        return MW_ERR_INVALID_ARG;
-    const mw_pack_call pk = {x_dev, scales_dev, topk_ids_dev, perm_dev, stats_dev, n_tokens, packed_rows_dev,
-                             row_src_token_dev, row_topk_dev};
-    return mw_launch_unpack_expand_index_plan_next(ctx, n_peers, out_rows_dev, out_scales_dev, out_capacity_rows,
-                                                   out_src_peer_dev, out_src_token_dev, next_ctx, next_peers_dev,
-                                                   next_n_peers, next_out_capacity_rows, next_expert_offsets_dev,
-                                                   next_recv_stats_dev, next_topk_ids_dev, next_n_tokens, next_mask_dev,
-                                                   next_perm_dev, next_desc_dev, next_send_stats_dev, &pk,
-                                                   (hipStream_t)stream);
+    const mw_pack_call pk = {send->x_dev, send->scales_dev, send->topk_ids_dev, send->perm_dev, send->stats_dev,
+                             send->n_tokens, send->packed_rows_dev, send->row_src_token_dev, send->row_topk_dev};
+    return launch_expand_index_plan(ctx, recv, next, &pk, stream);
 }
 
 MW_API int32_t mw_combine_gather(mw_ctx *ctx, int32_t n_peers, const void *y_dev, int64_t out_capacity_rows,

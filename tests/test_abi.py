@@ -65,6 +65,31 @@ int main(void) {
                         B.RECV_PEER_DTYPE.fields["row_topk"][1], B.MwConfig.expert_to_rank.offset]
 
 
+def test_batch_records_match_the_header():
+    """mw_send_batch, mw_recv_batch, mw_next_batch: the binding's ctypes records have the size and
+    the member offsets the C compiler gives the header's."""
+    recs = [("mw_send_batch", B.MwSendBatch), ("mw_recv_batch", B.MwRecvBatch), ("mw_next_batch", B.MwNextBatch)]
+    lines = []
+    for cname, cls in recs:
+        lines.append('printf("%%zu", sizeof(%s));' % cname)
+        for f, _ in cls._fields_:
+            lines.append('printf(" %%zu", offsetof(%s, %s));' % (cname, f))
+        lines.append('printf("\\n");')
+    src = "#include <stdio.h>\n#include <stddef.h>\n#include \"mw.h\"\nint main(void) {\n%s\nreturn 0; }\n" % "\n".join(lines)
+    with tempfile.TemporaryDirectory() as d:
+        c = os.path.join(d, "t.c")
+        open(c, "w").write(src)
+        exe = os.path.join(d, "t")
+        subprocess.check_call(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), c, "-o", exe])
+        out = subprocess.check_output([exe]).decode().splitlines()
+    assert len(out) == len(recs)
+    for line, (cname, cls) in zip(out, recs):
+        vals = [int(v) for v in line.split()]
+        assert vals[0] == C.sizeof(cls), cname
+        assert vals[1:] == [getattr(cls, f).offset for f, _ in cls._fields_], cname
+    assert (C.sizeof(B.MwSendBatch), C.sizeof(B.MwRecvBatch), C.sizeof(B.MwNextBatch)) == (72, 48, 88)
+
+
 def _cfg(**kw):
     e2r = np.arange(16, dtype=np.int32) // 2
     base = dict(n_ranks=8, n_experts=16, top_k=2, my_rank=0, hidden=256, row_format=B.MW_ROW_BF16,
