@@ -233,19 +233,6 @@ __global__ __launch_bounds__(256) void k_plan_allgather_split(int R, uint64_t sh
 constexpr int kFusedMax = MW_FUSED_MAX_TOKENS;
 static_assert(kFusedMax == kBlock, "one token per lane");
 
-// a < b for bitmaps of W words, word W - 1 most significant
-template <int W>
-__device__ __forceinline__ bool mask_less(const uint64_t *a, const uint64_t *b)
-{
-    bool lt = false, eq = true;
-#pragma unroll
-    for (int w = W - 1; w >= 0; --w) {
-        lt = lt || (eq && a[w] < b[w]);
-        eq = eq && (a[w] == b[w]);
-    }
-    return lt;
-}
-
 // kKeyed (bitmaps of more than one word, top_k <= 8): the all-pairs walk compares short keys.
 template <int W, bool kKeyed>
 __global__ __launch_bounds__(kBlock) void k_plan_pack(const int32_t *__restrict__ topk, int T, int K,
@@ -258,78 +245,17 @@ __global__ __launch_bounds__(kBlock) void k_plan_pack(const int32_t *__restrict_
                                                       int32_t *__restrict__ row_topk)
 {
     __shared__ uint64_t smask[kFusedMax * W];
-    __shared__ int32_t tok[kFusedMax];            // token of packed row i
-    __shared__ uint32_t gstart[kFusedMax + 1];    // first packed row of group g
+    __shared__ int32_t tok[kFusedMax];
+    __shared__ uint32_t gstart[kFusedMax + 1];
     __shared__ uint32_t hist[MW_MAX_RANKS];
-    __shared__ uint32_t scratch[17];
-    __shared__ uint32_t any_bad;
-    const int t = threadIdx.x, lane = t & 63;
-    bool bad = false;
-    uint64_t m[MW_MASK_WORDS] = {0, 0, 0, 0};
-    if (t < T) token_mask(topk + (size_t)t * K, K, eslot, E, m, bad);
-#pragma unroll
-    for (int w = 0; w < W; ++w) smask[t * W + w] = m[w];
+    __shared__ uint32_t scratch[18];
     __shared__ mw_short_key skey[kKeyed ? kFusedMax : 1];
-    mw_short_key mk = {0ull, 0u, 0u};
-    if constexpr (kKeyed) { mk = short_key(m); skey[t] = mk; }
-    hist[t] = 0;
-    if (t == 0) any_bad = 0;
-    const bool any = (m[0] | m[1] | m[2] | m[3]) != 0;
-    uint32_t N;
-    mw_block_exscan(any ? 1u : 0u, scratch, &N);          // its barriers also publish smask
-    if (bad) atomicOr(&any_bad, 1u);
-
-    // Packed row of token t = number of kept tokens u with (bitmap, u) < (bitmap, t).  The
-    // walk takes eight tokens at a time -- eight LDS reads in flight, then eight compares --
-    // because a compare is a few cycles and an LDS round trip about a hundred.  Whether u < t
-    // is the same for the whole wavefront except among its own 64 tokens: "bitmap <= mine"
-    // before them, the full test among them, "bitmap < mine" after them.  Slots from T up to
-    // the next multiple of eight hold empty bitmaps (their lanes wrote zeros); an empty bitmap is
-    // below every kept one: all of them are counted and taken off again.
-    const int T8 = (T + 7) & ~7;
-    const int w0 = t & ~63, w1 = w0 + 64;
-    uint32_t c = 0;
-    for (int u0 = 0; u0 < T8; u0 += 8) {
-        bool lt[8], eq[8];
-        if constexpr (kKeyed) {
-            mw_short_key q[8];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) q[k] = skey[u0 + k];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const bool keq = q[k].key == mk.key;
-                lt[k] = q[k].key < mk.key || (keq && q[k].flag < mk.flag);
-                eq[k] = keq && q[k].flag == mk.flag;
-            }
-        } else {
-            uint64_t q[8][W];
-#pragma unroll
-            for (int k = 0; k < 8; ++k)
-#pragma unroll
-                for (int w = 0; w < W; ++w) q[k][w] = smask[(u0 + k) * W + w];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                lt[k] = mask_less<W>(q[k], m);
-                eq[k] = !lt[k] && !mask_less<W>(m, q[k]);
-            }
-        }
-        if (u0 + 8 <= w0) {                         // wave-uniform: all eight before this wave's tokens
-#pragma unroll
-            for (int k = 0; k < 8; ++k) c += (lt[k] || eq[k]) ? 1u : 0u;
-        } else if (u0 >= w1) {                      // all eight after them
-#pragma unroll
-            for (int k = 0; k < 8; ++k) c += lt[k] ? 1u : 0u;
-        } else {
-#pragma unroll
-            for (int k = 0; k < 8; ++k) c += (lt[k] || (eq[k] && u0 + k < t)) ? 1u : 0u;
-        }
-    }
-    const uint32_t p = c - ((uint32_t)T8 - N);
-    if (any) tok[p] = t;
-    mw_lds_barrier();
+    const mw_small_plan_lds lds = {smask, tok, gstart, hist, scratch, skey};
+    const int t = threadIdx.x;
+    const mw_small_plan_rank r = mw_small_plan_ranks<W, kKeyed>(topk, T, K, eslot, E, lds);
 
     const uint32_t i = blockIdx.x;
-    if (i < N) {
+    if (i < r.N) {
         const int32_t tt = tok[i];
         const int n = xc + sc;
         for (int ch = t; ch < n; ch += kBlock) {
@@ -342,69 +268,7 @@ __global__ __launch_bounds__(kBlock) void k_plan_pack(const int32_t *__restrict_
     }
     const bool writes_plan = blockIdx.x == 0, writes_stats = blockIdx.x == gridDim.x - 1;
     if (!writes_plan && !writes_stats) return;
-
-    // groups: lane i looks at packed row i; a group starts where the bitmap differs from the
-    // row before
-    bool start = false;
-    if ((uint32_t)t < N) {
-        const uint64_t *q = smask + tok[t] * W;
-        start = t == 0 || mask_less<W>(smask + tok[t - 1] * W, q);
-    }
-    uint32_t G;
-    const uint32_t g = mw_block_exscan(start ? 1u : 0u, scratch, &G);
-    if (writes_plan) {
-        if (start) gstart[g] = (uint32_t)t;
-        if (t == 0) gstart[G] = N;
-        if (t < T) {
-            uint64_t *o = mask_out + (size_t)t * MW_MASK_WORDS;
-#pragma unroll
-            for (int q = 0; q < MW_MASK_WORDS; ++q) o[q] = m[q];
-        }
-        if (any) perm[p] = t;
-        mw_lds_barrier();
-        if (start) {
-            const uint64_t *q = smask + tok[t] * W;
-            mw_group_desc d;
-            uint32_t nd = 0;
-#pragma unroll
-            for (int w = 0; w < MW_MASK_WORDS; ++w) {
-                d.mask[w] = (w < W) ? q[w < W ? w : 0] : 0ull;
-                nd += (uint32_t)__popcll(d.mask[w]);
-            }
-            d.row_offset = (uint32_t)t;
-            d.row_count = gstart[g + 1] - (uint32_t)t;
-            d.n_dest = nd;
-            d.reserved0 = 0;
-            desc[g] = d;
-        }
-    }
-    if (writes_stats) {
-        // rows per destination: a wavefront ballot of bit b over 64 tokens, popcounted, is the
-        // number of those tokens that name rank 64 q + b; lane b keeps it
-#pragma unroll
-        for (int q = 0; q < W; ++q) {
-            if (__ballot(m[q] != 0) == 0) continue;      // wave-uniform
-            uint32_t mine = 0;
-            for (int b = 0; b < 64; ++b) {
-                const uint32_t n_b = (uint32_t)__popcll(__ballot((m[q] >> b) & 1ull));
-                if (lane == b) mine = n_b;
-            }
-            if (mine) atomicAdd(&hist[q * 64 + lane], mine);
-        }
-        mw_lds_barrier();
-        const uint32_t h = hist[t];
-        stats->rows_per_dest[t] = h;
-        uint32_t D;
-        mw_block_exscan(h, scratch, &D);
-        if (t == 0) {
-            stats->n_rows = N;
-            stats->n_groups = G;
-            stats->multicast_bytes = (uint64_t)N * row_bytes;
-            stats->unicast_bytes = (uint64_t)D * row_bytes;
-            stats->error_flags = any_bad ? MW_FLAG_BAD_EXPERT : 0u;
-            stats->reserved0 = 0;
-        }
-    }
+    mw_small_plan_finish<W>(r, T, row_bytes, mask_out, perm, desc, stats, lds, writes_plan, writes_stats);
 }
 
 // ---- ordering of large batches: sorted chunks, then ranks by binary search ------------------

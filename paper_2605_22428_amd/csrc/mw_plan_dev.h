@@ -66,6 +66,182 @@ __device__ __forceinline__ mw_short_key short_key(const uint64_t m[MW_MASK_WORDS
     return k;
 }
 
+// a < b for bitmaps of W words, word W - 1 most significant
+template <int W>
+__device__ __forceinline__ bool mask_less(const uint64_t *a, const uint64_t *b)
+{
+    bool lt = false, eq = true;
+#pragma unroll
+    for (int w = W - 1; w >= 0; --w) {
+        lt = lt || (eq && a[w] < b[w]);
+        eq = eq && (a[w] == b[w]);
+    }
+    return lt;
+}
+
+// ---- the whole plan of a small batch inside ONE workgroup of MW_FUSED_MAX_TOKENS lanes, one token
+// per lane (Section 5.1, send module: task decomposition): bitmaps, the packed order, groups and
+// statistics without any global scratch or any other workgroup.  Two halves, so that a caller can
+// put work between them that needs only the order (mw_plan_pack moves its row there).
+// LDS of the caller: smask [MW_FUSED_MAX_TOKENS * W] bitmaps, tok [..] token of packed row i,
+// gstart [.. + 1] first packed row of group g, hist [MW_MAX_RANKS], scratch [18] (17 of the scan,
+// one flag word), skey [MW_FUSED_MAX_TOKENS] short keys (kKeyed only).
+struct mw_small_plan_lds {
+    uint64_t *smask; int32_t *tok; uint32_t *gstart; uint32_t *hist; uint32_t *scratch; mw_short_key *skey;
+};
+struct mw_small_plan_rank {
+    uint64_t m[MW_MASK_WORDS];     // this lane's token's bitmap
+    uint32_t p, N;                 // its packed row (if kept), kept tokens
+    bool any;                      // the token has a destination
+};
+
+// Bitmaps and the packed order: fills smask and tok; every barrier of the workgroup is inside.
+// kKeyed (bitmaps of more than one word, top_k <= 8): the all-pairs walk compares short keys.
+template <int W, bool kKeyed>
+__device__ __forceinline__ mw_small_plan_rank mw_small_plan_ranks(const int32_t *__restrict__ topk, int T, int K,
+                                                                  const int32_t *__restrict__ eslot, int E,
+                                                                  const mw_small_plan_lds &l)
+{
+    const int t = threadIdx.x;
+    mw_small_plan_rank r;
+    bool bad = false;
+#pragma unroll
+    for (int w = 0; w < MW_MASK_WORDS; ++w) r.m[w] = 0;
+    if (t < T) token_mask(topk + (size_t)t * K, K, eslot, E, r.m, bad);
+#pragma unroll
+    for (int w = 0; w < W; ++w) l.smask[t * W + w] = r.m[w];
+    mw_short_key mk = {0ull, 0u, 0u};
+    if constexpr (kKeyed) { mk = short_key(r.m); l.skey[t] = mk; }
+    l.hist[t] = 0;
+    if (t == 0) l.scratch[17] = 0;
+    r.any = (r.m[0] | r.m[1] | r.m[2] | r.m[3]) != 0;
+    mw_block_exscan(r.any ? 1u : 0u, l.scratch, &r.N);          // its barriers also publish smask
+    if (bad) atomicOr(&l.scratch[17], 1u);
+
+    // Packed row of token t = number of kept tokens u with (bitmap, u) < (bitmap, t).  The
+    // walk takes eight tokens at a time -- eight LDS reads in flight, then eight compares --
+    // because a compare is a few cycles and an LDS round trip about a hundred.  Whether u < t
+    // is the same for the whole wavefront except among its own 64 tokens: "bitmap <= mine"
+    // before them, the full test among them, "bitmap < mine" after them.  Slots from T up to
+    // the next multiple of eight hold empty bitmaps (their lanes wrote zeros); an empty bitmap is
+    // below every kept one: all of them are counted and taken off again.
+    const int T8 = (T + 7) & ~7;
+    const int w0 = t & ~63, w1 = w0 + 64;
+    uint32_t c = 0;
+    for (int u0 = 0; u0 < T8; u0 += 8) {
+        bool lt[8], eq[8];
+        if constexpr (kKeyed) {
+            mw_short_key q[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) q[k] = l.skey[u0 + k];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const bool keq = q[k].key == mk.key;
+                lt[k] = q[k].key < mk.key || (keq && q[k].flag < mk.flag);
+                eq[k] = keq && q[k].flag == mk.flag;
+            }
+        } else {
+            uint64_t q[8][W];
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+#pragma unroll
+                for (int w = 0; w < W; ++w) q[k][w] = l.smask[(u0 + k) * W + w];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                lt[k] = mask_less<W>(q[k], r.m);
+                eq[k] = !lt[k] && !mask_less<W>(r.m, q[k]);
+            }
+        }
+        if (u0 + 8 <= w0) {                         // wave-uniform: all eight before this wave's tokens
+#pragma unroll
+            for (int k = 0; k < 8; ++k) c += (lt[k] || eq[k]) ? 1u : 0u;
+        } else if (u0 >= w1) {                      // all eight after them
+#pragma unroll
+            for (int k = 0; k < 8; ++k) c += lt[k] ? 1u : 0u;
+        } else {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) c += (lt[k] || (eq[k] && u0 + k < t)) ? 1u : 0u;
+        }
+    }
+    r.p = c - ((uint32_t)T8 - r.N);
+    if (r.any) l.tok[r.p] = t;
+    mw_lds_barrier();
+    return r;
+}
+
+// Groups, descriptors, bitmaps and perm (writes_plan) and the statistics (writes_stats).
+template <int W>
+__device__ __forceinline__ void mw_small_plan_finish(const mw_small_plan_rank &r, int T, uint64_t row_bytes,
+                                                     uint64_t *__restrict__ mask_out, int32_t *__restrict__ perm,
+                                                     mw_group_desc *__restrict__ desc, mw_send_stats *__restrict__ stats,
+                                                     const mw_small_plan_lds &l, bool writes_plan, bool writes_stats)
+{
+    const int t = threadIdx.x, lane = t & 63;
+    const uint32_t N = r.N;
+    // groups: lane i looks at packed row i; a group starts where the bitmap differs from the
+    // row before
+    bool start = false;
+    if ((uint32_t)t < N) {
+        const uint64_t *q = l.smask + l.tok[t] * W;
+        start = t == 0 || mask_less<W>(l.smask + l.tok[t - 1] * W, q);
+    }
+    uint32_t G;
+    const uint32_t g = mw_block_exscan(start ? 1u : 0u, l.scratch, &G);
+    if (writes_plan) {
+        if (start) l.gstart[g] = (uint32_t)t;
+        if (t == 0) l.gstart[G] = N;
+        if (t < T) {
+            uint64_t *o = mask_out + (size_t)t * MW_MASK_WORDS;
+#pragma unroll
+            for (int q = 0; q < MW_MASK_WORDS; ++q) o[q] = r.m[q];
+        }
+        if (r.any) perm[r.p] = t;
+        mw_lds_barrier();
+        if (start) {
+            const uint64_t *q = l.smask + l.tok[t] * W;
+            mw_group_desc d;
+            uint32_t nd = 0;
+#pragma unroll
+            for (int w = 0; w < MW_MASK_WORDS; ++w) {
+                d.mask[w] = (w < W) ? q[w < W ? w : 0] : 0ull;
+                nd += (uint32_t)__popcll(d.mask[w]);
+            }
+            d.row_offset = (uint32_t)t;
+            d.row_count = l.gstart[g + 1] - (uint32_t)t;
+            d.n_dest = nd;
+            d.reserved0 = 0;
+            desc[g] = d;
+        }
+    }
+    if (writes_stats) {
+        // rows per destination: a wavefront ballot of bit b over 64 tokens, popcounted, is the
+        // number of those tokens that name rank 64 q + b; lane b keeps it
+#pragma unroll
+        for (int q = 0; q < W; ++q) {
+            if (__ballot(r.m[q] != 0) == 0) continue;      // wave-uniform
+            uint32_t mine = 0;
+            for (int b = 0; b < 64; ++b) {
+                const uint32_t n_b = (uint32_t)__popcll(__ballot((r.m[q] >> b) & 1ull));
+                if (lane == b) mine = n_b;
+            }
+            if (mine) atomicAdd(&l.hist[q * 64 + lane], mine);
+        }
+        mw_lds_barrier();
+        const uint32_t h = l.hist[t];
+        stats->rows_per_dest[t] = h;
+        uint32_t D;
+        mw_block_exscan(h, l.scratch, &D);
+        if (t == 0) {
+            stats->n_rows = N;
+            stats->n_groups = G;
+            stats->multicast_bytes = (uint64_t)N * row_bytes;
+            stats->unicast_bytes = (uint64_t)D * row_bytes;
+            stats->error_flags = l.scratch[17] ? MW_FLAG_BAD_EXPERT : 0u;
+            stats->reserved0 = 0;
+        }
+    }
+}
+
 // cnt[t] += (#smaller | #equal before << 21 | #equal at-or-after << 42) over this slice, where
 // "smaller" means (bitmap, index) < (bitmap[t], t).  Empty bitmaps compare below every kept
 // token; k_groups subtracts their number.  A kept token always has a non-zero third field.

@@ -271,6 +271,7 @@ __device__ __forceinline__ void recv_index_body(
         mw_hit *h = hits + (size_t)(rb + i) * Kd;
         const int32_t *tk = ids_of(i);
         int nk = 0;
+        uint64_t seen = 0;                         // (kCache) local experts below 64 the row has named so far
         constexpr int kB = kCache ? 8 : 4;         // ids looked up together
         for (int j0 = 0; j0 < K; j0 += kB) {
             int32_t q[kB];
@@ -294,9 +295,14 @@ __device__ __forceinline__ void recv_index_body(
                 if (q[u] < 0 || (q[u] >> 16) != my_rank) continue;
                 const int le = q[u] & 0xffff;
                 bool dup = false;
+                if (kCache && le < 64) {               // one bit test instead of a walk over the row's experts
+                    dup = (seen >> le) & 1ull;
+                    seen |= 1ull << le;
+                } else {
 #pragma unroll
-                for (int k = 0; k < 8; ++k) dup |= (k < nk && f[k] == le);
-                for (int k = 8; k < nk; ++k) dup |= (h[k].le == le);
+                    for (int k = 0; k < 8; ++k) dup |= (k < nk && f[k] == le);
+                    for (int k = 8; k < nk; ++k) dup |= (h[k].le == le);
+                }
                 if (dup) continue;
 #pragma unroll
                 for (int k = 0; k < 8; ++k) if (k == nk) f[k] = le;
@@ -453,6 +459,309 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(const mw_index_args 
     recv_index_of<kPackets>(a, blockIdx.x);
 }
 
+// ---- the index of a SMALL batch in one workgroup ------------------------------------------------
+// With a few hundred received rows the index above is nothing but its chain of memory round
+// trips, and three of them -- the wait for a workgroup's stores, its report, the last workgroup's
+// reads of everybody's counts -- exist only because the peers are spread over workgroups.  Here one
+// workgroup handles all peers: records, then descriptors beside the rows' tokens and ids, then the
+// rank table, and the rest is LDS.  One bitmap over (expert, peer, source token) in output order
+// holds a bit per delivered (row, expert) pair; a running popcount over it is every pair's output
+// row at once: expert offsets, per-(expert, peer) bases and ranks are read off the same array.
+// Same outputs and flags as recv_index_body + mw_finish_counts (records, not packets; no
+// de-duplication); cnt and addr_cnt, which only those two exchange, are not written.
+// LDS words: see mw_small_index_lds_words.  P <= blockDim.x.
+constexpr int kSmallBlock = MW_FUSED_MAX_TOKENS;      // lanes of the small launches' workgroups
+
+static inline size_t mw_small_index_lds_words(int P, int L, uint32_t wpl, uint32_t max_tokens, uint32_t cap_rows)
+{
+    const uint64_t m_max = (uint64_t)P * max_tokens < cap_rows ? (uint64_t)P * max_tokens : cap_rows;
+    const size_t wa = (size_t)((m_max + 31) / 32), n_w = (size_t)L * (size_t)P * wpl;
+    return 10 * (size_t)P + 3 * ((size_t)P + 1) + wa + 2 * n_w + 1 + 24;
+}
+
+// kSmallRows: rows (and descriptors) a lane keeps in registers; further ones go through memory.
+template <int kSmallRows>
+__device__ __forceinline__ void recv_index_small(const mw_index_args &a, uint32_t *lds)
+{
+    const uint32_t tid = threadIdx.x, nthr = blockDim.x;
+    const uint32_t P = (uint32_t)a.P, L = (uint32_t)a.L, wpl = a.wpl, K = (uint32_t)a.K, Kd = (uint32_t)a.Kd;
+    const uint32_t E = (uint32_t)a.E, my_rank = (uint32_t)a.my_rank, max_tokens = a.max_tokens, cap_rows = a.cap_rows;
+    const uint64_t m_max = (uint64_t)P * max_tokens < cap_rows ? (uint64_t)P * max_tokens : cap_rows;
+    const uint32_t wa = (uint32_t)((m_max + 31) / 32), n_w = L * P * wpl;
+    mw_recv_peer *pinfo = (mw_recv_peer *)lds;          // [P]      the peers' records
+    uint32_t *rbase = lds + 10 * P;                     // [P + 1]  first row (over all peers) of peer q
+    uint32_t *nrow = rbase + P + 1;                     // [P + 1]  rows taken from peer q
+    uint32_t *dbase = nrow + P + 1;                     // [P + 1]  first descriptor (over all peers) of peer q
+    uint32_t *addr = dbase + P + 1;                     // [wa]     bit r: row r's group names this rank
+    uint32_t *bits = addr + wa;                         // [n_w]    (expert, peer, source token) in output order
+    uint32_t *pre = bits + n_w;                         // [n_w + 1] running popcount in front of each word
+    uint32_t *scratch = pre + n_w + 1;                  // [17] scan scratch, [17] flags, [18] addressed rows
+    const mw_recv_peer *peers = (const mw_recv_peer *)a.peers;
+    uint32_t err = 0;
+
+    // ---- round trip 1: the records
+    uint32_t nq = 0, dq = 0;
+    if (tid < P) {
+        const mw_recv_peer pr = peers[tid];
+        pinfo[tid] = pr;
+        nq = min(pr.n_rows, max_tokens);
+        dq = min(pr.n_desc, 65536u);
+        if (pr.n_rows > max_tokens) err |= MW_FLAG_RECV_CAPACITY;
+    }
+    for (uint32_t w = tid; w < wa; w += nthr) addr[w] = 0;
+    for (uint32_t w = tid; w < n_w; w += nthr) bits[w] = 0;
+    if (tid < 2) scratch[17 + tid] = 0;
+    uint32_t tot;
+    const uint32_t before = mw_block_exscan(nq, scratch, &tot);
+    const uint32_t dbefore = mw_block_exscan(dq, scratch, &tot);
+    if (tid < P) {
+        if (before + nq > cap_rows) err |= MW_FLAG_RECV_CAPACITY;
+        const uint32_t rb = min(before, cap_rows), nr = min(before + nq, cap_rows) - rb;
+        rbase[tid] = rb; nrow[tid] = nr; dbase[tid] = dbefore;
+        a.row_base[tid] = rb;
+        if (tid == P - 1) { rbase[P] = rb + nr; dbase[P] = dbefore + dq; a.row_base[P] = rb + nr; }
+    }
+    mw_lds_barrier();
+    const uint32_t M = rbase[P], D = dbase[P];
+    // the peer whose range [base[q], base[q + 1]) holds v (ranges may be empty; v < base[P])
+    auto peer_of = [&](const uint32_t *base, uint32_t v) -> uint32_t {
+        uint32_t lo = 0, hi = P;                        // base[lo] <= v < base[hi]
+        while (hi - lo > 1) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (base[mid] <= v) lo = mid; else hi = mid;
+        }
+        return lo;
+    };
+
+    // ---- round trip 2: the lane's first rows (source token, first eight ids) and descriptors, all
+    // requested together; their peers by four binary searches side by side
+    uint32_t q_r[kSmallRows], i_r[kSmallRows], s_r[kSmallRows];
+    int32_t e_r[kSmallRows][8];
+    uint32_t q_d[kSmallRows];
+    uint64_t dm_d[kSmallRows];
+    uint32_t off_d[kSmallRows], cnt_d[kSmallRows];
+    {
+        uint32_t lo[2 * kSmallRows], hi[2 * kSmallRows];
+#pragma unroll
+        for (int c = 0; c < 2 * kSmallRows; ++c) { lo[c] = 0; hi[c] = P; }
+        while (hi[0] - lo[0] > 1) {                     // (the same number of steps for every search)
+#pragma unroll
+            for (int c = 0; c < 2 * kSmallRows; ++c) {
+                const uint32_t v = tid + (uint32_t)(c % kSmallRows) * nthr, mid = (lo[c] + hi[c]) >> 1;
+                const uint32_t bm = (c < kSmallRows ? rbase : dbase)[mid];
+                if (bm <= v) lo[c] = mid; else hi[c] = mid;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kSmallRows; ++j) { q_r[j] = lo[j]; q_d[j] = lo[kSmallRows + j]; }
+    }
+#pragma unroll
+    for (int j = 0; j < kSmallRows; ++j) {
+        const uint32_t r = tid + (uint32_t)j * nthr;
+        i_r[j] = 0; s_r[j] = 0;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) e_r[j][u] = -1;
+        if (r < M) {
+            i_r[j] = r - rbase[q_r[j]];
+            const mw_recv_peer &pr = pinfo[q_r[j]];
+            s_r[j] = (uint32_t)pr.row_src_token[i_r[j]];
+            const int32_t *tk = pr.row_topk + (size_t)i_r[j] * K;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) if ((uint32_t)u < K) e_r[j][u] = tk[u];
+        }
+        dm_d[j] = 0; off_d[j] = 0; cnt_d[j] = 0;
+        if (r < D) {
+            const mw_group_desc *dd = pinfo[q_d[j]].desc + (r - dbase[q_d[j]]);
+            dm_d[j] = dd->mask[my_rank >> 6]; off_d[j] = dd->row_offset; cnt_d[j] = dd->row_count;
+        }
+    }
+    // ---- round trip 3: rank-table entries of those ids, requested before the descriptors are looked at
+    int32_t t_r[kSmallRows][8];
+    bool bad_r[kSmallRows];
+#pragma unroll
+    for (int j = 0; j < kSmallRows; ++j) {
+        bad_r[j] = false;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const bool ok = (uint32_t)e_r[j][u] < E;
+            bad_r[j] |= (e_r[j][u] != -1 && !ok);
+            t_r[j][u] = ok ? a.eslot[e_r[j][u]] : -1;
+        }
+    }
+    // addressed rows: the row ranges of the groups whose bitmap has this rank's bit
+    auto address = [&](uint32_t q, uint64_t dm, uint64_t b, uint64_t cnt) {
+        const uint64_t e = b + cnt;
+        if (!((dm >> (my_rank & 63u)) & 1ull)) return;
+        if (e > nrow[q]) { err |= MW_FLAG_BAD_DESC; return; }
+        if (e <= b) return;
+        const uint64_t gb = rbase[q] + b, ge = rbase[q] + e;        // over all peers
+        for (uint64_t w = gb >> 5; w <= ((ge - 1) >> 5); ++w) {
+            const uint64_t wlo = w << 5;
+            uint32_t m = 0xffffffffu;
+            if (gb > wlo) m &= 0xffffffffu << (gb - wlo);
+            if (ge < wlo + 32) m &= 0xffffffffu >> (wlo + 32 - ge);
+            atomicOr(&addr[w], m);
+        }
+    };
+#pragma unroll
+    for (int j = 0; j < kSmallRows; ++j)
+        if (tid + (uint32_t)j * nthr < D) address(q_d[j], dm_d[j], off_d[j], cnt_d[j]);
+    for (uint32_t d = tid + kSmallRows * nthr; d < D; d += nthr) {
+        const uint32_t q = peer_of(dbase, d);
+        const mw_group_desc *dd = pinfo[q].desc + (d - dbase[q]);
+        address(q, dd->mask[my_rank >> 6], dd->row_offset, dd->row_count);
+    }
+    mw_lds_barrier();
+    {
+        uint32_t n = 0;
+        for (uint32_t w = tid; w < wa; w += nthr) n += __popc(addr[w]);
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) n += __shfl_xor(n, d, 64);
+        if ((tid & 63u) == 0 && n) atomicAdd(&scratch[18], n);
+        if (L == 0) for (uint32_t w = tid; w < wa; w += nthr) if (addr[w]) err |= MW_FLAG_NO_LOCAL_EXPERT;
+    }
+
+    // ---- per row: its distinct local experts in top-k order (duplicate ids count once; at most 64
+    // local experts here, so "seen before" is one bit test); one bit per (expert, peer, source token).
+    // Slot k of the row's hit slots receives expert k; the first eight also stay in `les`, a byte each.
+    // `cached`: the row's token and the rank-table entries of its first eight ids are in registers.
+    auto parse_mark = [&](uint32_t r, uint32_t q, uint32_t i, uint32_t s, bool cached, const int32_t (&tc)[8], bool badc,
+                          mw_row_rec &rec, uint64_t &les) {
+        rec = mw_row_rec{nullptr, 0, (int32_t)q, 0, 0, 0, 0};
+        les = 0;
+        if (!((addr[r >> 5] >> (r & 31u)) & 1u)) return;
+        if (s >= max_tokens) { err |= MW_FLAG_BAD_SRC_TOKEN; return; }
+        const mw_recv_peer &pr = pinfo[q];
+        mw_hit *h = a.hits + (size_t)r * Kd;
+        const int32_t *tk = pr.row_topk + (size_t)i * K;
+        uint64_t seen = 0;
+        int nk = 0;
+        for (uint32_t j0 = 0; j0 < K; j0 += 8) {
+            int32_t t8[8];
+            if (cached && j0 == 0) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) t8[u] = tc[u];
+                if (badc) err |= MW_FLAG_BAD_EXPERT;
+            } else {
+                int32_t e8[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) e8[u] = (j0 + u < K) ? tk[j0 + u] : -1;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const bool ok = (uint32_t)e8[u] < E;
+                    if (e8[u] != -1 && !ok) err |= MW_FLAG_BAD_EXPERT;
+                    t8[u] = ok ? a.eslot[e8[u]] : -1;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (t8[u] < 0 || (uint32_t)(t8[u] >> 16) != my_rank) continue;
+                const uint32_t le = (uint32_t)t8[u] & 63u;             // (L <= 64)
+                if ((seen >> le) & 1ull) continue;
+                seen |= 1ull << le;
+                if (nk < 8) les |= (uint64_t)le << (8 * nk);
+                h[nk++] = mw_hit{(int32_t)le, 0};
+            }
+        }
+        // the row's bits: every atomic issued before the first result is looked at
+        {
+            uint32_t was[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                was[k] = 0;
+                if (k < nk) {
+                    const uint32_t le = (uint32_t)(les >> (8 * k)) & 0xffu;
+                    was[k] = atomicOr(&bits[(le * P + q) * wpl + (s >> 5)], 1u << (s & 31u));
+                }
+            }
+            uint32_t any_was = 0;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) any_was |= was[k];
+            for (int k = 8; k < nk; ++k) any_was |= atomicOr(&bits[((uint32_t)h[k].le * P + q) * wpl + (s >> 5)], 1u << (s & 31u));
+            if ((any_was >> (s & 31u)) & 1u) err |= MW_FLAG_DUP_SRC_TOKEN;
+        }
+        if (nk == 0) err |= MW_FLAG_NO_LOCAL_EXPERT;
+        rec.src = (const char *)pr.rows + (size_t)i * a.row_bytes;
+        rec.src_token = (int32_t)s;
+        rec.n_hits = nk;
+        rec.le0 = (int32_t)(les & 0xffu);
+    };
+    mw_row_rec rec_r[kSmallRows];
+    uint64_t les_r[kSmallRows];
+#pragma unroll
+    for (int j = 0; j < kSmallRows; ++j) {
+        rec_r[j] = mw_row_rec{nullptr, 0, 0, 0, 0, 0, 0};
+        les_r[j] = 0;
+        const uint32_t r = tid + (uint32_t)j * nthr;
+        if (r < M) parse_mark(r, q_r[j], i_r[j], s_r[j], true, t_r[j], bad_r[j], rec_r[j], les_r[j]);
+    }
+    for (uint32_t r = tid + kSmallRows * nthr; r < M; r += nthr) {        // further rows: through memory
+        const uint32_t q = peer_of(rbase, r), i = r - rbase[q];
+        const uint32_t s = (uint32_t)pinfo[q].row_src_token[i];
+        const int32_t none[8] = {-1, -1, -1, -1, -1, -1, -1, -1};
+        mw_row_rec rec;
+        uint64_t les;
+        parse_mark(r, q, i, s, false, none, false, rec, les);
+        a.recs[r] = rec;
+    }
+    mw_lds_barrier();
+
+    // ---- running popcount over the bitmap: consecutive words per lane, one scan of the lanes' sums
+    {
+        const uint32_t per = (n_w + nthr - 1) / nthr;
+        const uint32_t w0 = min(n_w, tid * per), w1 = min(n_w, w0 + per);
+        uint32_t sum = 0;
+        for (uint32_t w = w0; w < w1; ++w) sum += __popc(bits[w]);
+        uint32_t run = mw_block_exscan(sum, scratch, &tot);
+        for (uint32_t w = w0; w < w1; ++w) { pre[w] = run; run += __popc(bits[w]); }
+        if (tid == 0) pre[n_w] = tot;
+    }
+    mw_lds_barrier();
+    const uint32_t Q = pre[n_w];
+    for (uint32_t f = tid; f < L * P; f += nthr) {
+        const uint32_t b = pre[f * wpl];
+        a.base[f] = b;
+        if (f % P == 0) a.expert_offsets[f / P] = (int64_t)b;
+    }
+    // ---- ranks: output row of (row, expert) minus the base of its (expert, peer)
+    auto rank_of = [&](uint32_t q, uint32_t s, int le) -> int32_t {
+        const uint32_t w0 = ((uint32_t)le * P + q) * wpl, wi = w0 + (s >> 5);
+        return (int32_t)(pre[wi] + __popc(bits[wi] & ((1u << (s & 31u)) - 1u)) - pre[w0]);
+    };
+#pragma unroll
+    for (int j = 0; j < kSmallRows; ++j) {
+        const uint32_t r = tid + (uint32_t)j * nthr;
+        if (r >= M) continue;
+        mw_hit *h = a.hits + (size_t)r * Kd;
+        const int nk = rec_r[j].n_hits;
+        for (int k = 0; k < nk; ++k) {
+            const int le = k < 8 ? (int)((les_r[j] >> (8 * k)) & 0xffu) : h[k].le;
+            const int32_t rk = rank_of(q_r[j], s_r[j], le);
+            if (k == 0) rec_r[j].rank0 = rk; else h[k].rank = rk;
+        }
+        a.recs[r] = rec_r[j];
+    }
+    for (uint32_t r = tid + kSmallRows * nthr; r < M; r += nthr) {
+        mw_row_rec *rc = a.recs + r;
+        mw_hit *h = a.hits + (size_t)r * Kd;
+        const int nk = rc->n_hits;
+        const uint32_t q = (uint32_t)rc->peer, s = (uint32_t)rc->src_token;
+        for (int k = 0; k < nk; ++k) {
+            const int32_t rk = rank_of(q, s, h[k].le);
+            if (k == 0) rc->rank0 = rk; else h[k].rank = rk;
+        }
+    }
+    if (err) atomicOr(&scratch[17], err);
+    mw_lds_barrier();
+    if (tid == 0) {
+        a.expert_offsets[L] = (int64_t)Q;
+        a.stats->n_recv_rows = scratch[18];
+        a.stats->n_out_rows = Q;
+        a.stats->error_flags = scratch[17] | (((int64_t)Q > a.out_cap) ? MW_FLAG_OUT_CAPACITY : 0u);
+        a.stats->n_rows_seen = M;
+    }
+}
+
 // blockIdx.x selects a segment of blockDim.x chunks of the row; blockIdx.y walks rows.  All
 // index reads are wave-uniform (scalar loads).  The dependent chain in front of a row's
 // payload is what a one-shot workgroup cannot hide, so it is kept to two steps: the row
@@ -599,6 +908,52 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
     }
     extern __shared__ uint64_t plan_lds[];
     mw_plan_ride<W, kKeyed, kLean ? 8 : 16>(plan, (blockIdx.y - n_index) * gridDim.x + blockIdx.x, plan_lds);
+}
+
+// A whole step of a stream of SMALL batches in one launch (the batch sizes of Section 6.3's
+// dispatch experiment, 64 and 128 tokens a rank): what k_expand_index_plan_next does, with the
+// riders in their one-workgroup forms -- grid row 0 indexes the next received batch
+// (recv_index_small), row 1, if there is a plan to make, plans the next batch to send
+// (mw_small_plan_ranks / mw_small_plan_finish, the plan of mw_plan_pack) -- then the packer's rows
+// and the expander's.  At these sizes the step is the riders' chain of memory round trips, and the
+// forms that spread a batch over workgroups spend half of theirs on talking to one another.
+template <int W, bool kKeyed, int kRows>
+__global__ __launch_bounds__(kSmallBlock) void k_small_step(
+    const uint32_t first_pack_row, const uint32_t first_expand_row, const mw_row_rec *__restrict__ recs,
+    const uint32_t *__restrict__ row_base, int P, int xc, const int32_t *__restrict__ pack_perm,
+    const mw_send_stats *__restrict__ pack_stats, int sc, int Kd,
+    const uint32_t *__restrict__ base, const mw_hit *__restrict__ hits,
+    u32x4 *__restrict__ out_rows, u32x4 *__restrict__ out_scales, uint32_t cap,
+    int32_t *__restrict__ out_src_peer, int32_t *__restrict__ out_src_token,
+    const mw_index_args next, const mw_plan_args plan, const mw_pack_args pack)
+{
+    if (blockIdx.y >= first_expand_row) {
+        expand_body(recs, hits, base, row_base, P, Kd, xc, sc, out_rows, out_scales, cap, out_src_peer, out_src_token,
+                    blockIdx.y - first_expand_row, gridDim.y - first_expand_row);
+        return;
+    }
+    if (blockIdx.y >= first_pack_row) {
+        mw_pack_body(pack.x, pack.scales, pack.xc, pack.sc, pack.ns, pack.topk, pack.K, pack_perm, pack_stats, pack.packed,
+                     pack.row_src_token, pack.row_topk, blockIdx.x, blockIdx.y - first_pack_row,
+                     first_expand_row - first_pack_row);
+        return;
+    }
+    if (blockIdx.x != 0) return;
+    extern __shared__ uint64_t small_lds[];
+    if (blockIdx.y == 0) {
+        recv_index_small<kRows>(next, (uint32_t *)small_lds);
+        return;
+    }
+    // LDS of the plan: bitmaps, short keys, then the 32-bit arrays
+    uint64_t *smask = small_lds;
+    mw_short_key *skey = (mw_short_key *)(smask + kSmallBlock * W);
+    int32_t *tok = (int32_t *)(skey + (kKeyed ? kSmallBlock : 0));
+    uint32_t *gstart = (uint32_t *)(tok + kSmallBlock);
+    uint32_t *hist = gstart + kSmallBlock + 1;
+    uint32_t *scratch = hist + MW_MAX_RANKS;
+    const mw_small_plan_lds l = {smask, tok, gstart, hist, scratch, skey};
+    const mw_small_plan_rank r = mw_small_plan_ranks<W, kKeyed>(plan.topk, plan.T, plan.K, plan.eslot, plan.E, l);
+    mw_small_plan_finish<W>(r, plan.T, plan.row_bytes, plan.mask_out, plan.perm, plan.desc, plan.stats, l, true, true);
 }
 
 // The way back (Section 2.1, combine-style AlltoAll; Section 2.3.2: the combine phase reduces
@@ -756,6 +1111,81 @@ int32_t mw_launch_unpack_expand(mw_ctx *ctx, int32_t P, void *out_rows, float *o
     return MW_OK;
 }
 
+// Whether a step is small enough for k_small_step -- this batch's rows (received and to pack) under
+// 24 MiB, so that the riders and not the movers are the step; the next batch's index in one
+// workgroup's LDS and at most MW_FUSED_MAX_TOKENS tokens to plan -- and, if so, its launch.
+// with_plan: the launch plans next_T tokens (possibly none); pk: rows to pack, or null.
+static bool small_step_fits(const mw_ctx *ctx, const mw_ctx *next, int32_t next_P, int32_t next_T, const mw_pack_call *pk,
+                            uint32_t gy)
+{
+    static_assert(kSmallBlock == MW_MAX_RANKS, "one lane per peer record, one lane per rank in the statistics");
+    if (next->options & MW_OPT_RECV_DEDUP) return false;
+    const int64_t rows = (int64_t)gy + (pk ? pk->n_tokens : 0);
+    if (rows * ctx->row_bytes > (24LL << 20)) return false;
+    if (next_T > MW_FUSED_MAX_TOKENS || next_P > kSmallBlock || next->n_local > 64) return false;
+    if ((int64_t)next_P * next->cfg.max_tokens > 8192) return false;
+    const uint32_t wpl = ((uint32_t)next->cfg.max_tokens + 31u) / 32u;
+    return mw_small_index_lds_words(next_P, next->n_local, wpl, (uint32_t)next->cfg.max_tokens,
+                                    (uint32_t)next->cfg.max_recv_rows) * 4 <= 40960;
+}
+
+static int32_t launch_small_step(mw_ctx *ctx, int32_t P, void *out_rows, float *out_scales, int64_t cap,
+                                 int32_t *out_src_peer, int32_t *out_src_token, mw_ctx *next, const mw_index_args &a,
+                                 bool with_plan, const int32_t *next_topk, int32_t next_T, uint64_t *next_mask,
+                                 int32_t *next_perm, mw_group_desc *next_desc, mw_send_stats *next_send_stats,
+                                 const mw_pack_call *pk, uint32_t gy, hipStream_t s)
+{
+    const mw_config &c = ctx->cfg;
+    const int xc = (int)(ctx->x_row_bytes / 16), sc = (int)(ctx->s_row_bytes / 16);
+    const int nseg = (xc + sc + kSmallBlock - 1) / kSmallBlock;
+    const int K = next->cfg.top_k, W = next->mask_words;
+    const bool keyed = W > 1 && K <= 8;
+    mw_plan_args pl = {};
+    pl.topk = next_topk; pl.T = next_T; pl.K = K; pl.E = next->cfg.n_experts; pl.eslot = next->d_eslot;
+    pl.mask_out = next_mask; pl.perm = next_perm; pl.desc = next_desc; pl.stats = next_send_stats;
+    pl.row_bytes = (uint64_t)next->row_bytes;
+    mw_pack_args pa = {};
+    uint32_t n_pack_rows = 0;
+    if (pk && pk->n_tokens > 0) {
+        pa.x = (const u32x4 *)pk->x; pa.scales = (const u32x4 *)pk->scales; pa.xc = xc; pa.sc = sc;
+        pa.ns = (int)(ctx->row_stride / 16);
+        pa.topk = pk->topk; pa.K = c.top_k; pa.perm = pk->perm; pa.stats = pk->stats;
+        pa.packed = (u32x4 *)pk->packed; pa.row_src_token = pk->row_src_token; pa.row_topk = pk->row_topk;
+        n_pack_rows = (uint32_t)pk->n_tokens;
+    }
+    const uint32_t wpl = ((uint32_t)next->cfg.max_tokens + 31u) / 32u;
+    const size_t lds_index = 4 * mw_small_index_lds_words(a.P, next->n_local, wpl, (uint32_t)next->cfg.max_tokens,
+                                                          (uint32_t)next->cfg.max_recv_rows);
+    const int Wk = keyed ? 4 : W;
+    const size_t lds_plan = (size_t)kSmallBlock * Wk * 8 + (keyed ? (size_t)kSmallBlock * sizeof(mw_short_key) : 0) +
+                            4 * ((size_t)kSmallBlock + kSmallBlock + 1 + MW_MAX_RANKS + 18);
+    const size_t lds = (with_plan && lds_plan > lds_index ? lds_plan : lds_index) + 16;
+    const uint32_t riders = with_plan ? 2u : 1u;
+    const dim3 grid(nseg, riders + n_pack_rows + gy), block(kSmallBlock);
+    const uint32_t cap32 = (uint32_t)(cap < 0x7fffffffLL ? cap : 0x7fffffffLL);
+    {
+        mw_timed tm(ctx, MW_KERNEL_EXPAND, s);
+        // rows a lane of the index keeps in registers: two for up to 512 received rows (as many as the
+        // next context saw last time, if the caller has asked for the statistics), else four
+        const bool few = next->recv_rows_hint > 0 ? next->recv_rows_hint <= 2 * kSmallBlock
+                                                  : (int64_t)a.P * next->cfg.max_tokens <= 2 * kSmallBlock;
+#define MW_SMALL_(W_, KEYED_, ROWS_)                                                                                   \
+    hipLaunchKernelGGL((k_small_step<W_, KEYED_, ROWS_>), grid, block, lds, s, riders, riders + n_pack_rows, ctx->d_recs, \
+                       ctx->d_row_base, P, xc, pa.perm, pa.stats, sc, ctx->hit_slots, ctx->d_base, ctx->d_hits,         \
+                       (u32x4 *)out_rows, (u32x4 *)out_scales, cap32, out_src_peer, out_src_token, a, pl, pa)
+#define MW_SMALL(W_, KEYED_) do { if (few) MW_SMALL_(W_, KEYED_, 2); else MW_SMALL_(W_, KEYED_, 4); } while (0)
+        if (keyed) MW_SMALL(4, true);
+        else if (W == 1) MW_SMALL(1, false);
+        else if (W == 2) MW_SMALL(2, false);
+        else if (W == 3) MW_SMALL(3, false);
+        else MW_SMALL(4, false);
+#undef MW_SMALL
+#undef MW_SMALL_
+    }
+    MW_HIP_CHECK(hipGetLastError());
+    return MW_OK;
+}
+
 int32_t mw_launch_unpack_expand_index_next(mw_ctx *ctx, int32_t P, void *out_rows, float *out_scales, int64_t cap,
                                            int32_t *out_src_peer, int32_t *out_src_token, mw_ctx *next,
                                            const mw_recv_peer *next_peers, int32_t next_P, int64_t next_cap,
@@ -770,6 +1200,9 @@ int32_t mw_launch_unpack_expand_index_next(mw_ctx *ctx, int32_t P, void *out_row
     if (!make_index_args(next, next_peers, false, next_P, next_cap, next_expert_offsets, next_stats, 1280, &a,
                          &lds_index))
         return MW_ERR_UNSUPPORTED;
+    if (small_step_fits(ctx, next, next_P, 0, nullptr, expand_grid_rows(ctx)))
+        return launch_small_step(ctx, P, out_rows, out_scales, cap, out_src_peer, out_src_token, next, a, false, nullptr,
+                                 0, nullptr, nullptr, nullptr, nullptr, nullptr, expand_grid_rows(ctx), s);
     const int xc = (int)(ctx->x_row_bytes / 16), sc = (int)(ctx->s_row_bytes / 16);
     mw_row_shape shape = mw_row_shape_of(xc + sc);
     // Rows of whole cache lines: two-wave workgroups here.  The expander runs as fast with them
@@ -811,10 +1244,13 @@ int32_t mw_launch_unpack_expand_index_plan_next(mw_ctx *ctx, int32_t P, void *ou
     if (!make_index_args(next, next_peers, false, next_P, next_cap, next_expert_offsets, next_stats, 1280, &a,
                          &lds_index))
         return MW_ERR_UNSUPPORTED;
+    const uint32_t gy = expand_grid_rows(ctx);
+    if (small_step_fits(ctx, next, next_P, next_T, pk, gy))
+        return launch_small_step(ctx, P, out_rows, out_scales, cap, out_src_peer, out_src_token, next, a, true, next_topk,
+                                 next_T, next_mask, next_perm, next_desc, next_send_stats, pk, gy, s);
     const int xc = (int)(ctx->x_row_bytes / 16), sc = (int)(ctx->s_row_bytes / 16);
     mw_row_shape shape = mw_row_shape_of(xc + sc);
     if (shape.bs == 64 && (xc + sc) % 16 == 0) { shape.bs = 128; shape.nseg = (xc + sc) / 128 + ((xc + sc) % 128 ? 1 : 0); }
-    const uint32_t gy = expand_grid_rows(ctx);
 
     // the riding plan: workgroups of the launch's size
     const int K = next->cfg.top_k, W = next->mask_words;
