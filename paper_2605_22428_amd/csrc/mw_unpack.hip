@@ -544,7 +544,8 @@ __device__ __forceinline__ void recv_index_small(const mw_index_args &a, uint32_
         uint32_t lo[2 * kSmallRows], hi[2 * kSmallRows];
 #pragma unroll
         for (int c = 0; c < 2 * kSmallRows; ++c) { lo[c] = 0; hi[c] = P; }
-        while (hi[0] - lo[0] > 1) {                     // (the same number of steps for every search)
+        // ceil(log2 P) steps: an interval of one entry stays as it is (mid == lo, and base[lo] <= v)
+        for (uint32_t span = P; span > 1; span = (span + 1) >> 1) {
 #pragma unroll
             for (int c = 0; c < 2 * kSmallRows; ++c) {
                 const uint32_t v = tid + (uint32_t)(c % kSmallRows) * nthr, mid = (lo[c] + hi[c]) >> 1;
