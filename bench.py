@@ -560,6 +560,32 @@ def bench_dispatch(args, name: str, brief: bool = False) -> dict:
             assert int(rs_["error_flags"]) == 0 and int(rs_["n_rows_in"]) == N and int(rs_["forward_bytes"]) == int(rst["forward_bytes"])
         relay["step_GBps_stream"] = round(relay_bytes / relay["step_us_stream"] / 1e3, 1)
         relay["step_pct_of_hbm_peak_stream"] = round(100.0 * relay_bytes / relay["step_us_stream"] / 1e3 / HBM_PEAK_GBPS, 2)
+        # several buffers a launch (mw_relay_batch): NB copies and the next NB indexes, 2 NB contexts in turn
+        for NB in (2, 4):
+            cs = [ctx, ctx_r] + [B.Context(R, w.n_experts, K, my_rank, w.hidden, fmt, T, 1, e2r, device=dev, max_hops=16,
+                                           row_stride=stride) for _ in range(2 * NB - 2)]
+            for c_ in cs[2:]:
+                c_.mw_set_forwarding(next_hop, n_hops)
+            kb = kids + [B.RelayChildren(c_, n_hops, T) for c_ in cs[2:]]
+            jobs = [B.relay_job(c_, in_rec, k_.table, T, k_.stats) for c_, k_ in zip(cs, kb)]
+            for c_, k_ in zip(cs[:NB], kb[:NB]):
+                c_.mw_relay_index(in_rec, k_.table, T, k_.stats)
+            for i in range(n_s + 4):
+                if i == 4:
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                B.mw_relay_batch(*((jobs[:NB], jobs[NB:]) if i % 2 == 0 else (jobs[NB:], jobs[:NB])))
+            torch.cuda.synchronize()
+            per = (time.perf_counter() - t0) * 1e6 / n_s / NB
+            B.mw_relay_batch(jobs[:NB] if (n_s + 4) % 2 == 0 else jobs[NB:], [])
+            for c_, k_ in zip(cs, kb):
+                rs_ = c_.mw_get_relay_stats(k_.stats)
+                assert int(rs_["error_flags"]) == 0 and int(rs_["forward_bytes"]) == int(rst["forward_bytes"])
+            relay["us_per_buffer_batch_of_%d" % NB] = round(per, 2)
+            relay["pct_of_hbm_peak_batch_of_%d" % NB] = round(100.0 * relay_bytes / per / 1e3 / HBM_PEAK_GBPS, 2)
+            for c_ in cs[2:]:
+                c_.close()
+            del kb, jobs
         ctx_r.close()
         del children, kids
 

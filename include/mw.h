@@ -674,6 +674,37 @@ MW_API int32_t mw_relay_copy_index_next(mw_ctx *ctx, const mw_recv_peer *in_dev,
                                  mw_relay_stats *next_stats_dev, void *stream);
 
 /*
+ * mw_relay_batch: for a relay that has more than one buffer waiting (Section 5.1, relay module:
+ * buffers are relayed one after the other; Section 4.3.3).  ONE launch does
+ *     mw_relay_copy(copy[j].ctx, copy[j].in_dev, copy[j].children_dev, copy[j].stats_dev)   for j < n_copy
+ * and
+ *     mw_relay_index(index[k].ctx, index[k].in_dev, index[k].children_dev,
+ *                    index[k].child_capacity_rows, index[k].stats_dev)                      for k < n_index
+ * with identical results.  A relay's copy of a 50-megabyte buffer is short enough for what a
+ * launch costs by itself (its first waves' dependent fetches, its last waves' tail, the gap to
+ * the next launch) to be a sixth of it; with two buffers per launch that cost is paid once for
+ * both.  The price is latency: the first buffer of a batch waits for the second.
+ * copy, index: HOST arrays (read during the call only) of at most MW_RELAY_BATCH_MAX jobs each;
+ * 1 <= n_copy, 0 <= n_index.  All contexts are distinct, on one device, have a forwarding table,
+ * and the copy jobs' contexts have the same row size, row stride, top_k and max_tokens.  Every
+ * copy job's index must have been made by an EARLIER launch (mw_relay_index, or the index part
+ * of an earlier mw_relay_batch or mw_relay_copy_index_next); child_capacity_rows of a copy job
+ * is not read.  A stream of buffers over four contexts, two buffers a launch:
+ *     mw_relay_index(A, b0); mw_relay_index(B, b1);
+ *     mw_relay_batch(copy {A b0, B b1}, index {C b2, D b3}); mw_relay_batch(copy {C, D}, index {A b4, B b5}); ...
+ */
+#define MW_RELAY_BATCH_MAX 4
+typedef struct mw_relay_job {
+    mw_ctx *ctx;
+    const mw_recv_peer *in_dev;
+    const mw_relay_child *children_dev;
+    int64_t child_capacity_rows;
+    mw_relay_stats *stats_dev;
+} mw_relay_job;
+MW_API int32_t mw_relay_batch(const mw_relay_job *copy, int32_t n_copy, const mw_relay_job *index, int32_t n_index,
+                              void *stream);
+
+/*
  * mw_relay_packets: the relay step for packets -- the paper's own form of it (Section 4.1,
  * "Replication and forwarding": the relay parses the bitmap in front of the payload, makes one
  * copy per distinct egress port and updates the in-packet metadata of each copy so that

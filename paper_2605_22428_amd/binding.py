@@ -29,7 +29,7 @@ EXPORTS = ["mw_workspace_bytes", "mw_ctx_create", "mw_ctx_destroy", "mw_plan", "
            "mw_sim_deliver", "mw_copy_bytes", "mw_get_send_stats", "mw_get_recv_stats",
            "mw_set_forwarding", "mw_relay", "mw_relay_index", "mw_relay_copy", "mw_relay_copy_index_next", "mw_relay_packets", "mw_relay_packets_index", "mw_relay_packets_copy", "mw_relay_packets_copy_index_next", "mw_get_relay_stats",
            "mw_allgather_split_point", "mw_plan_allgather_split", "mw_unpack_allgather_split",
-           "mw_ctx_set_timing_events", "mw_status_string", "mw_plan_static", "mw_ctx_set_options"]
+           "mw_ctx_set_timing_events", "mw_status_string", "mw_plan_static", "mw_ctx_set_options", "mw_relay_batch"]
 MW_KERNEL_PLAN_RANK, MW_KERNEL_PLAN_GROUPS, MW_KERNEL_PACK, MW_KERNEL_RECV_INDEX, MW_KERNEL_EXPAND = 0, 1, 2, 3, 4
 MW_KERNEL_AG_PACK, MW_KERNEL_AG_GATHER, MW_KERNEL_RELAY_INDEX, MW_KERNEL_RELAY_COPY = 5, 6, 7, 8
 MW_KERNEL_PLAN_PACK, MW_KERNEL_PACK_QUANT, MW_KERNEL_COMBINE = 9, 10, 11
@@ -92,6 +92,12 @@ class MwNextBatch(C.Structure):
                 ("recv_stats_dev", C.c_void_p), ("out_capacity_rows", C.c_int64), ("n_peers", C.c_int32),
                 ("n_tokens", C.c_int32), ("topk_ids_dev", C.c_void_p), ("mask_dev", C.c_void_p),
                 ("perm_dev", C.c_void_p), ("desc_dev", C.c_void_p), ("send_stats_dev", C.c_void_p)]
+
+
+class MwRelayJob(C.Structure):
+    """mw_relay_job (include/mw.h)."""
+    _fields_ = [("ctx", C.c_void_p), ("in_dev", C.c_void_p), ("children_dev", C.c_void_p),
+                ("child_capacity_rows", C.c_int64), ("stats_dev", C.c_void_p)]
 
 
 class MwError(RuntimeError):
@@ -180,6 +186,21 @@ def next_batch(next_ctx, peers, n_peers, out_capacity_rows, expert_offsets, recv
                        _addr(recv_stats), int(out_capacity_rows), int(n_peers),
                        0 if topk_ids is None else int(topk_ids.shape[0]), _addr(topk_ids), _addr(mask), _addr(perm),
                        _addr(desc), _addr(send_stats))
+
+
+MW_RELAY_BATCH_MAX = 4
+
+
+def relay_job(ctx: "Context", in_record: torch.Tensor, children: torch.Tensor, child_capacity_rows: int,
+              stats: torch.Tensor) -> MwRelayJob:
+    return MwRelayJob(ctx._h.value, _addr(in_record), _addr(children), int(child_capacity_rows), _addr(stats))
+
+
+def mw_relay_batch(copy_jobs: Sequence[MwRelayJob], index_jobs: Sequence[MwRelayJob]):
+    ca = (MwRelayJob * max(len(copy_jobs), 1))(*copy_jobs)
+    ia = (MwRelayJob * max(len(index_jobs), 1))(*index_jobs)
+    _check(load().mw_relay_batch(ca, C.c_int32(len(copy_jobs)), ia, C.c_int32(len(index_jobs)), _stream()),
+           "mw_relay_batch")
 
 
 class Context:

@@ -671,6 +671,39 @@ MW_API int32_t mw_relay_copy_index_next(mw_ctx *ctx, const mw_recv_peer *in_dev,
                                 next_child_capacity_rows, next_stats_dev, (hipStream_t)stream);
 }
 
+MW_API int32_t mw_relay_batch(const mw_relay_job *copy, int32_t n_copy, const mw_relay_job *index, int32_t n_index,
+                              void *stream)
+{
+    if (!copy || n_copy < 1 || n_copy > MW_RELAY_BATCH_MAX || n_index < 0 || n_index > MW_RELAY_BATCH_MAX)
+        return MW_ERR_INVALID_ARG;
+    if (n_index > 0 && !index) return MW_ERR_INVALID_ARG;
+    const mw_ctx *seen[2 * MW_RELAY_BATCH_MAX];
+    int n_seen = 0;
+    for (int pass = 0; pass < 2; ++pass) {
+        const mw_relay_job *jobs = pass == 0 ? copy : index;
+        const int n = pass == 0 ? n_copy : n_index;
+        for (int j = 0; j < n; ++j) {
+            const mw_relay_job &q = jobs[j];
+            if (!q.ctx || !q.in_dev || !q.children_dev || !q.stats_dev) return MW_ERR_INVALID_ARG;
+            if (q.ctx->device != copy[0].ctx->device) return MW_ERR_INVALID_ARG;
+            if (q.ctx->cfg.max_hops < 1 || q.ctx->n_hops < 1) return MW_ERR_INVALID_ARG;       // no forwarding table
+            for (int k = 0; k < n_seen; ++k) if (seen[k] == q.ctx) return MW_ERR_INVALID_ARG;
+            seen[n_seen++] = q.ctx;
+            if (pass == 1 && (q.child_capacity_rows < 0)) return MW_ERR_INVALID_ARG;
+            if (pass == 1 && q.child_capacity_rows > 0x7fffffffLL) return MW_ERR_UNSUPPORTED;
+        }
+    }
+    const mw_ctx *a = copy[0].ctx;
+    for (int j = 1; j < n_copy; ++j) {
+        const mw_ctx *x = copy[j].ctx;
+        if (x->row_bytes != a->row_bytes || x->row_stride != a->row_stride || x->cfg.top_k != a->cfg.top_k ||
+            x->cfg.max_tokens != a->cfg.max_tokens)
+            return MW_ERR_INVALID_ARG;
+    }
+    MW_ON_DEVICE(copy[0].ctx);
+    return mw_launch_relay_batch(copy, n_copy, index, n_index, (hipStream_t)stream);
+}
+
 MW_API int32_t mw_relay_packets(mw_ctx *ctx, const mw_recv_packets *in_dev, void *const *children_dev,
                          int64_t child_capacity_rows, mw_relay_stats *stats_dev, void *stream)
 {

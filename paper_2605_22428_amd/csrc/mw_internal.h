@@ -281,6 +281,8 @@ int32_t mw_launch_gather_split(mw_ctx *ctx, const void *const *direct, const voi
 int32_t mw_launch_copy(mw_ctx *ctx, void *dst, const void *src, int64_t n_bytes, hipStream_t s);
 int32_t mw_launch_gather_shards(mw_ctx *ctx, const void *const *shards, int64_t shard_bytes, void *out,
                                 hipStream_t s);
+int32_t mw_launch_relay_batch(const mw_relay_job *copy, int32_t n_copy, const mw_relay_job *index, int32_t n_index,
+                              hipStream_t s);
 int32_t mw_launch_relay(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay_child *children, int64_t cap,
                         mw_relay_stats *stats, hipStream_t s);
 int32_t mw_launch_relay_index(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay_child *children, int64_t cap,

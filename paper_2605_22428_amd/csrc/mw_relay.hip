@@ -276,6 +276,39 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
                          next.keep_metadata, (int)blockIdx.y);
 }
 
+// Several buffers in one launch (mw_relay_batch): the copies of n_copy buffers, `rows_per_copy`
+// grid rows each, behind the index rows of n_index further buffers.  A copy workgroup finds its
+// buffer by one division and reads that buffer's arguments from the kernel arguments.
+struct mw_relay_copy_args {
+    const mw_recv_peer *in; const mw_relay_child *children; const int32_t *group_of_row; const uint32_t *child_pos;
+    uint32_t *relay_flags; mw_relay_stats *stats; int n_hops; int reserved0;
+};
+struct mw_relay_batch_args {
+    mw_relay_copy_args copy[MW_RELAY_BATCH_MAX];
+    mw_relay_index_args index[MW_RELAY_BATCH_MAX];
+    uint32_t index_first_row[MW_RELAY_BATCH_MAX + 1];      // grid rows [first[k], first[k + 1]) index buffer k
+};
+
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_relay_batch(
+    const uint32_t first_copy_row, const uint32_t rows_per_copy, int K, int n_chunks, int ns, uint32_t max_tokens,
+    uint64_t row_bytes, const mw_relay_batch_args b)
+{
+    if (blockIdx.y >= first_copy_row) {
+        const uint32_t y = blockIdx.y - first_copy_row, j = y / rows_per_copy;
+        const mw_relay_copy_args &c = b.copy[j];
+        relay_copy_body(c.in, c.children, c.n_hops, K, n_chunks, ns, max_tokens, row_bytes, c.group_of_row, c.child_pos,
+                        c.relay_flags, c.stats, y - j * rows_per_copy, rows_per_copy);
+        return;
+    }
+    if (blockIdx.x != 0) return;
+    int k = 0;
+#pragma unroll
+    for (int q = 1; q < MW_RELAY_BATCH_MAX; ++q) k += (blockIdx.y >= b.index_first_row[q]) ? 1 : 0;
+    const mw_relay_index_args &a = b.index[k];
+    relay_index_body(a.in, a.children, a.n_hops, a.n_ranks, a.max_tokens, a.cap, a.row_bytes, a.hop_bits, a.group_of_row,
+                     a.child_pos, a.relay_flags, a.stats, a.keep_metadata, (int)(blockIdx.y - b.index_first_row[k]));
+}
+
 // ---- the same step for packets (Section 4.1, "Replication and forwarding": the relay parses the
 // bitmap in front of the payload, makes one copy per distinct egress port and updates the
 // in-packet metadata of each copy).  Every packet is its own group, so there is no row -> group
@@ -518,6 +551,46 @@ int32_t mw_launch_relay_copy(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay
                                ctx->d_group_of_row, ctx->d_child_pos, ctx->d_relay_flags, stats,
                                relay_index_args(next, next_in, next_children, next_cap, next_stats));
         }
+    }
+    MW_HIP_CHECK(hipGetLastError());
+    return MW_OK;
+}
+
+int32_t mw_launch_relay_batch(const mw_relay_job *copy, int32_t n_copy, const mw_relay_job *index, int32_t n_index,
+                              hipStream_t s)
+{
+    mw_ctx *ctx = copy[0].ctx;
+    const mw_config &c = ctx->cfg;
+    const int n_chunks = (int)(ctx->row_bytes / 16);
+    mw_row_shape shape = mw_row_shape_of(n_chunks);
+    // long rows of whole cache lines: a few large workgroups per row beside a riding index (see mw_launch_relay_copy)
+    if (n_index > 0 && shape.bs == 64 && n_chunks % 16 == 0) {
+        shape.nseg = (n_chunks + 511) / 512;
+        shape.bs = ((n_chunks + shape.nseg - 1) / shape.nseg + 63) / 64 * 64;
+    }
+    uint32_t gy = (uint32_t)c.max_tokens < 8192u ? (uint32_t)c.max_tokens : 8192u;      // per buffer; more rows by striding
+    if (gy < 1) gy = 1;
+    mw_relay_batch_args b = {};
+    for (int j = 0; j < n_copy; ++j) {
+        mw_ctx *x = copy[j].ctx;
+        b.copy[j] = mw_relay_copy_args{copy[j].in_dev, copy[j].children_dev, x->d_group_of_row, x->d_child_pos,
+                                       x->d_relay_flags, copy[j].stats_dev, x->n_hops, 0};
+    }
+    uint32_t first = 0;
+    for (int k = 0; k < MW_RELAY_BATCH_MAX; ++k) {
+        b.index_first_row[k] = first;
+        if (k < n_index) {
+            b.index[k] = relay_index_args(index[k].ctx, index[k].in_dev, index[k].children_dev,
+                                          index[k].child_capacity_rows, index[k].stats_dev);
+            first += (uint32_t)index[k].ctx->n_hops + 1u;
+        }
+    }
+    b.index_first_row[MW_RELAY_BATCH_MAX] = first;
+    {
+        mw_timed tm(ctx, MW_KERNEL_RELAY_COPY, s);
+        hipLaunchKernelGGL(k_relay_batch, dim3(shape.nseg, first + gy * (uint32_t)n_copy), dim3(shape.bs), 0, s, first, gy,
+                           c.top_k, n_chunks, (int)(ctx->row_stride / 16), (uint32_t)c.max_tokens,
+                           (uint64_t)ctx->row_bytes, b);
     }
     MW_HIP_CHECK(hipGetLastError());
     return MW_OK;

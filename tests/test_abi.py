@@ -66,9 +66,10 @@ int main(void) {
 
 
 def test_batch_records_match_the_header():
-    """mw_send_batch, mw_recv_batch, mw_next_batch: the binding's ctypes records have the size and
+    """mw_send_batch, mw_recv_batch, mw_next_batch, mw_relay_job: the binding's ctypes records have the size and
     the member offsets the C compiler gives the header's."""
-    recs = [("mw_send_batch", B.MwSendBatch), ("mw_recv_batch", B.MwRecvBatch), ("mw_next_batch", B.MwNextBatch)]
+    recs = [("mw_send_batch", B.MwSendBatch), ("mw_recv_batch", B.MwRecvBatch), ("mw_next_batch", B.MwNextBatch),
+            ("mw_relay_job", B.MwRelayJob)]
     lines = []
     for cname, cls in recs:
         lines.append('printf("%%zu", sizeof(%s));' % cname)
@@ -87,7 +88,7 @@ def test_batch_records_match_the_header():
         vals = [int(v) for v in line.split()]
         assert vals[0] == C.sizeof(cls), cname
         assert vals[1:] == [getattr(cls, f).offset for f, _ in cls._fields_], cname
-    assert (C.sizeof(B.MwSendBatch), C.sizeof(B.MwRecvBatch), C.sizeof(B.MwNextBatch)) == (72, 48, 88)
+    assert (C.sizeof(B.MwSendBatch), C.sizeof(B.MwRecvBatch), C.sizeof(B.MwNextBatch), C.sizeof(B.MwRelayJob)) == (72, 48, 88, 40)
 
 
 def _cfg(**kw):

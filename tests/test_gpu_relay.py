@@ -329,3 +329,51 @@ def test_relay_stream_index_of_the_next_buffer_rides_with_the_copy(which):
     assert ei.value.status == B.MW_ERR_INVALID_ARG
     for c in ctxs:
         c.close()
+
+
+@pytest.mark.parametrize("which", ["bf16_long_rows", "fp8", "bf16_short_rows"])
+def test_relay_batch_two_buffers_a_launch(which):
+    """mw_relay_batch over a stream of seven buffers on four contexts with two forwarding tables: two
+    copies and the next two indexes per launch, then a launch with one copy and no index; every
+    buffer's children and statistics against the oracle.  One buffer is short, one is empty."""
+    w = {"bf16_short_rows": W.scaled(W.C1, n_tokens=300, hidden=1024),
+         "bf16_long_rows": W.scaled(W.C1, n_tokens=150, hidden=7168),
+         "fp8": W.scaled(W.C2, n_tokens=260, hidden=1024)}[which]
+    _say("relay batch", w.name)
+    rng = np.random.default_rng(6)
+    tables = [(rng.integers(0, 9, size=w.n_ranks).astype(np.int32), 9),
+              (rng.integers(0, 33, size=w.n_ranks).astype(np.int32), 33)]
+    ctxs = [_ctx(w, 0, 64) for _ in range(4)]
+    for i, c in enumerate(ctxs):
+        c.mw_set_forwarding(*tables[i % 2])
+    sizes = [w.n_tokens, 77, 0, w.n_tokens, 130, w.n_tokens, 5]
+    steps = []
+    for i, T in enumerate(sizes):
+        tk = W.topk_ids(w, 40 + i, i)[:T].copy()
+        x, sc = W.payload_rows(w, 40 + i, i)
+        x, sc = x[:T].copy(), (None if sc is None else sc[:T].copy())
+        g = H.GpuSend(ctxs[0], tk, x, sc)
+        c = ctxs[i % 4]
+        ch = B.RelayChildren(c, tables[i % 2][1], w.n_tokens)
+        table = _in_record(g.full_record())
+        steps.append(dict(tk=tk, x=x, sc=sc, g=g, table=table, ch=ch, ctx=c,
+                          job=B.relay_job(c, table, ch.table, w.n_tokens, ch.stats)))
+    for st in steps[:2]:
+        st["ctx"].mw_relay_index(st["table"], st["ch"].table, w.n_tokens, st["ch"].stats)
+    B.mw_relay_batch([steps[0]["job"], steps[1]["job"]], [steps[2]["job"], steps[3]["job"]])
+    B.mw_relay_batch([steps[2]["job"], steps[3]["job"]], [steps[4]["job"], steps[5]["job"]])
+    B.mw_relay_batch([steps[4]["job"], steps[5]["job"]], [steps[6]["job"]])
+    B.mw_relay_batch([steps[6]["job"]], [])
+    torch.cuda.synchronize()
+    for i, st in enumerate(steps):
+        nh, n = tables[i % 2]
+        stats = st["ctx"].mw_get_relay_stats(st["ch"].stats)
+        check_children(st["ch"], stats, H.oracle_send(w, st["tk"], st["x"], st["sc"]), nh, n, w.row_bytes)
+    # argument errors: a context twice, too many jobs, none to copy
+    for bad in (([steps[0]["job"], steps[0]["job"]], []), ([steps[0]["job"]], [steps[0]["job"]]),
+                ([s_["job"] for s_ in steps[:5]], []), ([], [steps[1]["job"]])):
+        with pytest.raises(B.MwError) as ei:
+            B.mw_relay_batch(*bad)
+        assert ei.value.status == B.MW_ERR_INVALID_ARG
+    for c in ctxs:
+        c.close()
