@@ -1124,7 +1124,7 @@ static bool small_step_fits(const mw_ctx *ctx, const mw_ctx *next, int32_t next_
     const int64_t rows = (int64_t)gy + (pk ? pk->n_tokens : 0);
     if (rows * ctx->row_bytes > (24LL << 20)) return false;
     if (next_T > MW_FUSED_MAX_TOKENS || next_P > kSmallBlock || next->n_local > 64) return false;
-    if ((int64_t)next_P * next->cfg.max_tokens > 8192) return false;
+    if ((int64_t)next_P * next->cfg.max_tokens > 16384) return false;
     const uint32_t wpl = ((uint32_t)next->cfg.max_tokens + 31u) / 32u;
     return mw_small_index_lds_words(next_P, next->n_local, wpl, (uint32_t)next->cfg.max_tokens,
                                     (uint32_t)next->cfg.max_recv_rows) * 4 <= 40960;

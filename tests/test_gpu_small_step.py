@@ -47,6 +47,7 @@ SHAPES = {
     # bitmaps of two and four words (short keys), and more than eight ids a token (no short keys)
     "r128": (W.DispatchWorkload("r128", 63, 128, 256, 8, 40, 256, "bf16", "uniform"), 77, None),
     "r256": (W.scaled(W.C3, n_tokens=24, hidden=256), 200, None),
+    "c3_64": (W.scaled(W.C3, n_tokens=64, hidden=256), 17, None),
     "k12": (W.DispatchWorkload("k12", 64, 4, 64, 12, 100, 256, "bf16", "uniform"), 1, None),
     "k9_r130": (W.DispatchWorkload("k9", 65, 130, 260, 9, 30, 256, "bf16", "uniform"), 100, None),
 }
