@@ -103,16 +103,19 @@ __device__ __forceinline__ mw_small_plan_rank mw_small_plan_ranks(const int32_t 
                                                                   const mw_small_plan_lds &l)
 {
     const int t = threadIdx.x;
+    const bool slot = t < MW_FUSED_MAX_TOKENS;      // (a wider workgroup's further lanes only take part in scans and barriers)
     mw_small_plan_rank r;
     bool bad = false;
 #pragma unroll
     for (int w = 0; w < MW_MASK_WORDS; ++w) r.m[w] = 0;
     if (t < T) token_mask(topk + (size_t)t * K, K, eslot, E, r.m, bad);
-#pragma unroll
-    for (int w = 0; w < W; ++w) l.smask[t * W + w] = r.m[w];
     mw_short_key mk = {0ull, 0u, 0u};
-    if constexpr (kKeyed) { mk = short_key(r.m); l.skey[t] = mk; }
-    l.hist[t] = 0;
+    if (slot) {
+#pragma unroll
+        for (int w = 0; w < W; ++w) l.smask[t * W + w] = r.m[w];
+        if constexpr (kKeyed) { mk = short_key(r.m); l.skey[t] = mk; }
+        l.hist[t] = 0;
+    }
     if (t == 0) l.scratch[17] = 0;
     r.any = (r.m[0] | r.m[1] | r.m[2] | r.m[3]) != 0;
     mw_block_exscan(r.any ? 1u : 0u, l.scratch, &r.N);          // its barriers also publish smask
@@ -125,7 +128,7 @@ __device__ __forceinline__ mw_small_plan_rank mw_small_plan_ranks(const int32_t 
     // before them, the full test among them, "bitmap < mine" after them.  Slots from T up to
     // the next multiple of eight hold empty bitmaps (their lanes wrote zeros); an empty bitmap is
     // below every kept one: all of them are counted and taken off again.
-    const int T8 = (T + 7) & ~7;
+    const int T8 = slot ? (T + 7) & ~7 : 0;
     const int w0 = t & ~63, w1 = w0 + 64;
     uint32_t c = 0;
     for (int u0 = 0; u0 < T8; u0 += 8) {
@@ -164,7 +167,7 @@ __device__ __forceinline__ mw_small_plan_rank mw_small_plan_ranks(const int32_t 
         }
     }
     r.p = c - ((uint32_t)T8 - r.N);
-    if (r.any) l.tok[r.p] = t;
+    if (r.any) l.tok[r.p] = t;                      // (any: t < T <= MW_FUSED_MAX_TOKENS)
     mw_lds_barrier();
     return r;
 }
@@ -227,8 +230,8 @@ __device__ __forceinline__ void mw_small_plan_finish(const mw_small_plan_rank &r
             if (mine) atomicAdd(&l.hist[q * 64 + lane], mine);
         }
         mw_lds_barrier();
-        const uint32_t h = l.hist[t];
-        stats->rows_per_dest[t] = h;
+        const uint32_t h = t < MW_MAX_RANKS ? l.hist[t] : 0u;
+        if (t < MW_MAX_RANKS) stats->rows_per_dest[t] = h;
         uint32_t D;
         mw_block_exscan(h, l.scratch, &D);
         if (t == 0) {

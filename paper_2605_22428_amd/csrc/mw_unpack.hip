@@ -470,7 +470,8 @@ __global__ __launch_bounds__(kIndexBlock) void k_recv_index(const mw_index_args 
 // Same outputs and flags as recv_index_body + mw_finish_counts (records, not packets; no
 // de-duplication); cnt and addr_cnt, which only those two exchange, are not written.
 // LDS words: see mw_small_index_lds_words.  P <= blockDim.x.
-constexpr int kSmallBlock = MW_FUSED_MAX_TOKENS;      // lanes of the small launches' workgroups
+constexpr int kSmallBlock = MW_FUSED_MAX_TOKENS;      // token slots of the one-workgroup plan
+constexpr int kSmallLanes = 512;                      // lanes of the small launches' workgroups (index: one or two rows a lane up to 1024 rows)
 
 static inline size_t mw_small_index_lds_words(int P, int L, uint32_t wpl, uint32_t max_tokens, uint32_t cap_rows)
 {
@@ -919,7 +920,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
 // and the expander's.  At these sizes the step is the riders' chain of memory round trips, and the
 // forms that spread a batch over workgroups spend half of theirs on talking to one another.
 template <int W, bool kKeyed, int kRows>
-__global__ __launch_bounds__(kSmallBlock) void k_small_step(
+__global__ __launch_bounds__(kSmallLanes) void k_small_step(
     const uint32_t first_pack_row, const uint32_t first_expand_row, const mw_row_rec *__restrict__ recs,
     const uint32_t *__restrict__ row_base, int P, int xc, const int32_t *__restrict__ pack_perm,
     const mw_send_stats *__restrict__ pack_stats, int sc, int Kd,
@@ -1138,7 +1139,7 @@ static int32_t launch_small_step(mw_ctx *ctx, int32_t P, void *out_rows, float *
 {
     const mw_config &c = ctx->cfg;
     const int xc = (int)(ctx->x_row_bytes / 16), sc = (int)(ctx->s_row_bytes / 16);
-    const int nseg = (xc + sc + kSmallBlock - 1) / kSmallBlock;
+    const int nseg = (xc + sc + kSmallLanes - 1) / kSmallLanes;
     const int K = next->cfg.top_k, W = next->mask_words;
     const bool keyed = W > 1 && K <= 8;
     mw_plan_args pl = {};
@@ -1162,14 +1163,14 @@ static int32_t launch_small_step(mw_ctx *ctx, int32_t P, void *out_rows, float *
                             4 * ((size_t)kSmallBlock + kSmallBlock + 1 + MW_MAX_RANKS + 18);
     const size_t lds = (with_plan && lds_plan > lds_index ? lds_plan : lds_index) + 16;
     const uint32_t riders = with_plan ? 2u : 1u;
-    const dim3 grid(nseg, riders + n_pack_rows + gy), block(kSmallBlock);
+    const dim3 grid(nseg, riders + n_pack_rows + gy), block(kSmallLanes);
     const uint32_t cap32 = (uint32_t)(cap < 0x7fffffffLL ? cap : 0x7fffffffLL);
     {
         mw_timed tm(ctx, MW_KERNEL_EXPAND, s);
-        // rows a lane of the index keeps in registers: two for up to 512 received rows (as many as the
+        // rows a lane of the index keeps in registers: two for up to 1024 received rows (as many as the
         // next context saw last time, if the caller has asked for the statistics), else four
-        const bool few = next->recv_rows_hint > 0 ? next->recv_rows_hint <= 2 * kSmallBlock
-                                                  : (int64_t)a.P * next->cfg.max_tokens <= 2 * kSmallBlock;
+        const bool few = next->recv_rows_hint > 0 ? next->recv_rows_hint <= 2 * kSmallLanes
+                                                  : (int64_t)a.P * next->cfg.max_tokens <= 2 * kSmallLanes;
 #define MW_SMALL_(W_, KEYED_, ROWS_)                                                                                   \
     hipLaunchKernelGGL((k_small_step<W_, KEYED_, ROWS_>), grid, block, lds, s, riders, riders + n_pack_rows, ctx->d_recs, \
                        ctx->d_row_base, P, xc, pa.perm, pa.stats, sc, ctx->hit_slots, ctx->d_base, ctx->d_hits,         \
