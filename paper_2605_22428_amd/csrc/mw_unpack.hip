@@ -958,6 +958,14 @@ __global__ __launch_bounds__(kSmallLanes) void k_small_step(
     mw_small_plan_finish<W>(r, plan.T, plan.row_bytes, plan.mask_out, plan.perm, plan.desc, plan.stats, l, true, true);
 }
 
+// The one-workgroup index as a launch of its own (mw_unpack_index, mw_unpack of a small batch).
+template <int kRows>
+__global__ __launch_bounds__(kSmallLanes) void k_recv_index_small(const mw_index_args a)
+{
+    extern __shared__ uint64_t small_index_lds[];
+    recv_index_small<kRows>(a, (uint32_t *)small_index_lds);
+}
+
 // The way back (Section 2.1, combine-style AlltoAll; Section 2.3.2: the combine phase reduces
 // and cannot be multicast).  The mirror image of the expander: a received row that went to h
 // local experts gets ONE row back, the sum of those h expert outputs, so the return traffic is
@@ -1057,6 +1065,26 @@ static bool make_index_args(mw_ctx *ctx, const void *peers, bool packets, int32_
     return true;
 }
 
+// the index of `P` peers' regions on `ctx` fits the one-workgroup form
+static bool small_index_fits(const mw_ctx *ctx, int32_t P)
+{
+    static_assert(kSmallBlock == MW_MAX_RANKS, "one lane per peer record, one lane per rank in the statistics");
+    if (ctx->options & MW_OPT_RECV_DEDUP) return false;
+    if (P > kSmallBlock || ctx->n_local > 64) return false;
+    if ((int64_t)P * ctx->cfg.max_tokens > 16384) return false;
+    const uint32_t wpl = ((uint32_t)ctx->cfg.max_tokens + 31u) / 32u;
+    return mw_small_index_lds_words(P, ctx->n_local, wpl, (uint32_t)ctx->cfg.max_tokens,
+                                    (uint32_t)ctx->cfg.max_recv_rows) * 4 <= 40960;
+}
+
+// rows a lane of the one-workgroup index keeps in registers: two for up to 1024 received rows (as many
+// as the context saw last time, if the caller has asked for the statistics), else four
+static bool small_index_few_rows(const mw_ctx *ctx, int32_t P)
+{
+    return ctx->recv_rows_hint > 0 ? ctx->recv_rows_hint <= 2 * kSmallLanes
+                                   : (int64_t)P * ctx->cfg.max_tokens <= 2 * kSmallLanes;
+}
+
 int32_t mw_launch_unpack_index(mw_ctx *ctx, const void *peers, bool packets, int32_t P, int64_t cap,
                                int64_t *expert_offsets, mw_recv_stats *stats, hipStream_t s)
 {
@@ -1069,6 +1097,16 @@ int32_t mw_launch_unpack_index(mw_ctx *ctx, const void *peers, bool packets, int
     const int ib = ctx->cfg.max_tokens <= 2048 ? 256 : kIndexBlock;
     {
         mw_timed tm(ctx, MW_KERNEL_RECV_INDEX, s);
+        const int64_t expected = ctx->recv_rows_hint > 0 ? ctx->recv_rows_hint : (int64_t)P * ctx->cfg.max_tokens;
+        if (!packets && expected <= kSmallLanes && small_index_fits(ctx, P)) {
+            // a row a lane at most: one workgroup for all peers, nothing to exchange between workgroups
+            // (9.6 against 10.9 us at 443 rows; with two rows a lane the workgroup-per-peer form is ahead)
+            const uint32_t wpl = ((uint32_t)ctx->cfg.max_tokens + 31u) / 32u;
+            const size_t lds = 4 * mw_small_index_lds_words(P, ctx->n_local, wpl, (uint32_t)ctx->cfg.max_tokens,
+                                                            (uint32_t)ctx->cfg.max_recv_rows) + 16;
+            if (small_index_few_rows(ctx, P)) hipLaunchKernelGGL(k_recv_index_small<2>, dim3(1), dim3(kSmallLanes), lds, s, a);
+            else hipLaunchKernelGGL(k_recv_index_small<4>, dim3(1), dim3(kSmallLanes), lds, s, a);
+        } else
         if (packets) hipLaunchKernelGGL(k_recv_index<true>, dim3(P), dim3(ib), lds_index, s, a);
         else hipLaunchKernelGGL(k_recv_index<false>, dim3(P), dim3(ib), lds_index, s, a);
     }
@@ -1120,15 +1158,10 @@ int32_t mw_launch_unpack_expand(mw_ctx *ctx, int32_t P, void *out_rows, float *o
 static bool small_step_fits(const mw_ctx *ctx, const mw_ctx *next, int32_t next_P, int32_t next_T, const mw_pack_call *pk,
                             uint32_t gy)
 {
-    static_assert(kSmallBlock == MW_MAX_RANKS, "one lane per peer record, one lane per rank in the statistics");
-    if (next->options & MW_OPT_RECV_DEDUP) return false;
     const int64_t rows = (int64_t)gy + (pk ? pk->n_tokens : 0);
     if (rows * ctx->row_bytes > (24LL << 20)) return false;
-    if (next_T > MW_FUSED_MAX_TOKENS || next_P > kSmallBlock || next->n_local > 64) return false;
-    if ((int64_t)next_P * next->cfg.max_tokens > 16384) return false;
-    const uint32_t wpl = ((uint32_t)next->cfg.max_tokens + 31u) / 32u;
-    return mw_small_index_lds_words(next_P, next->n_local, wpl, (uint32_t)next->cfg.max_tokens,
-                                    (uint32_t)next->cfg.max_recv_rows) * 4 <= 40960;
+    if (next_T > MW_FUSED_MAX_TOKENS) return false;
+    return small_index_fits(next, next_P);
 }
 
 static int32_t launch_small_step(mw_ctx *ctx, int32_t P, void *out_rows, float *out_scales, int64_t cap,
@@ -1167,10 +1200,7 @@ static int32_t launch_small_step(mw_ctx *ctx, int32_t P, void *out_rows, float *
     const uint32_t cap32 = (uint32_t)(cap < 0x7fffffffLL ? cap : 0x7fffffffLL);
     {
         mw_timed tm(ctx, MW_KERNEL_EXPAND, s);
-        // rows a lane of the index keeps in registers: two for up to 1024 received rows (as many as the
-        // next context saw last time, if the caller has asked for the statistics), else four
-        const bool few = next->recv_rows_hint > 0 ? next->recv_rows_hint <= 2 * kSmallLanes
-                                                  : (int64_t)a.P * next->cfg.max_tokens <= 2 * kSmallLanes;
+        const bool few = small_index_few_rows(next, a.P);
 #define MW_SMALL_(W_, KEYED_, ROWS_)                                                                                   \
     hipLaunchKernelGGL((k_small_step<W_, KEYED_, ROWS_>), grid, block, lds, s, riders, riders + n_pack_rows, ctx->d_recs, \
                        ctx->d_row_base, P, xc, pa.perm, pa.stats, sc, ctx->hit_slots, ctx->d_base, ctx->d_hits,         \
