@@ -321,6 +321,8 @@ def bench_dispatch(args, name: str, brief: bool = False) -> dict:
     state = {"n": 0}
     rctx = [ctx, ctx_b]
     pipe = {"n": 0}
+    step_records = {}
+    s_recv_handle = s_recv.cuda_stream
     lap = {"n": 0}            # launch_and_plan steps issued since the pipeline was primed
 
     def prime_pipeline(with_plan=False):
@@ -375,14 +377,16 @@ def bench_dispatch(args, name: str, brief: bool = False) -> dict:
         elif schedule == "one_launch":
             n = pipe["n"]
             pipe["n"] = n + 1
-            s, s_next = sets[n % N_SETS], sets[(n + 1) % N_SETS]
-            sd, rv, rn, sdn = s["send"], s["recv"], s_next["recv"], s_next["send"]
-            with torch.cuda.stream(s_recv):
-                rctx[n % 2].mw_stream_step(s["x"], s["sc"], topk_d, sd.perm, sd.stats, sd.packed, sd.row_src_token,
-                                           sd.row_topk, R, rv.out_rows, rv.out_scales, cap, rv.out_src_peer,
-                                           rv.out_src_token, rctx[(n + 1) % 2], s_next["table"], R, cap,
-                                           rn.expert_offsets, rn.stats, topk_d, sdn.mask, sdn.perm, sdn.desc,
-                                           sdn.stats)
+            key = (n % N_SETS, n % 2)
+            if key not in step_records:     # the batch records of this (buffer set, context) pair: built once
+                s, s_next = sets[n % N_SETS], sets[(n + 1) % N_SETS]
+                sd, rv, rn, sdn = s["send"], s["recv"], s_next["recv"], s_next["send"]
+                step_records[key] = (B.send_batch(s["x"], s["sc"], topk_d, sd.perm, sd.stats, sd.packed, sd.row_src_token,
+                                                  sd.row_topk),
+                                     B.recv_batch(R, rv.out_rows, rv.out_scales, cap, rv.out_src_peer, rv.out_src_token),
+                                     B.next_batch(rctx[(n + 1) % 2], s_next["table"], R, cap, rn.expert_offsets, rn.stats,
+                                                  topk_d, sdn.mask, sdn.perm, sdn.desc, sdn.stats))
+            rctx[n % 2].mw_stream_step_records(*step_records[key], stream_handle=s_recv_handle)
         elif schedule == "launch_and_plan":
             n = pipe["n"]
             pipe["n"] = n + 1
@@ -834,15 +838,21 @@ def bench_dispatch(args, name: str, brief: bool = False) -> dict:
         for sd_ in sd_pair:
             ctx.mw_plan(tk_s, sd_.mask, sd_.perm, sd_.desc, sd_.stats)
 
+        # (the batch records are built once: the loop marshals nothing, as a C caller's would not)
+        recs_one = []
+        for a in (0, 1):
+            b = 1 - a
+            recs_one.append((B.send_batch(x_s, sc_s, tk_s, sd_pair[a].perm, sd_pair[a].stats, sd_pair[a].packed,
+                                          sd_pair[a].row_src_token, sd_pair[a].row_topk),
+                             B.recv_batch(R, ride_rv[a].out_rows, ride_rv[a].out_scales, cap_d, ride_rv[a].out_src_peer,
+                                          ride_rv[a].out_src_token),
+                             B.next_batch(ride_ctx[b], table_d, R, cap_d, ride_rv[b].expert_offsets, ride_rv[b].stats,
+                                          tk_s, sd_pair[b].mask, sd_pair[b].perm, sd_pair[b].desc, sd_pair[b].stats)))
+
         def step_one():
             n = ride_n["n"]
             ride_n["n"] = n + 1
-            a, b = n % 2, (n + 1) % 2
-            ride_ctx[a].mw_stream_step(x_s, sc_s, tk_s, sd_pair[a].perm, sd_pair[a].stats, sd_pair[a].packed,
-                                       sd_pair[a].row_src_token, sd_pair[a].row_topk, R, ride_rv[a].out_rows,
-                                       ride_rv[a].out_scales, cap_d, ride_rv[a].out_src_peer, ride_rv[a].out_src_token,
-                                       ride_ctx[b], table_d, R, cap_d, ride_rv[b].expert_offsets, ride_rv[b].stats,
-                                       tk_s, sd_pair[b].mask, sd_pair[b].perm, sd_pair[b].desc, sd_pair[b].stats)
+            ride_ctx[n % 2].mw_stream_step_records(*recs_one[n % 2])
 
         for label, fn in (("step_us", step_d), ("step_graph_replay_us", graph.replay),
                           ("step_two_launches_us", step_ride), ("step_one_launch_us", step_one)):

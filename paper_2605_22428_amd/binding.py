@@ -369,6 +369,14 @@ class Context:
         _check(load().mw_stream_step(self._h, C.byref(send), C.byref(recv), C.byref(nxt), _stream()),
                "mw_stream_step")
 
+    def mw_stream_step_records(self, send: MwSendBatch, recv: MwRecvBatch, nxt: MwNextBatch,
+                               stream_handle: Optional[int] = None):
+        """mw_stream_step on records the caller built once (send_batch, recv_batch, next_batch) and keeps,
+        together with the tensors they point to: a loop over the same buffers then marshals nothing.
+        stream_handle: a stream's raw handle (torch.cuda.Stream.cuda_stream); default: the current stream."""
+        st = _stream() if stream_handle is None else C.c_void_p(stream_handle)
+        _check(load().mw_stream_step(self._h, C.byref(send), C.byref(recv), C.byref(nxt), st), "mw_stream_step")
+
     def mw_ctx_set_options(self, options: int):
         _check(load().mw_ctx_set_options(self._h, C.c_uint32(options)), "mw_ctx_set_options")
 
