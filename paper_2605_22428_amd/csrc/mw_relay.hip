@@ -494,6 +494,21 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
 
 }  // namespace
 
+// Workgroup shape of a copy that carries a riding index, for long rows that would otherwise move
+// as single waves.  The index walks the groups a workgroup's width at a time (one memory round
+// trip and two scans per step: 128 lanes took 32 steps for 4096 groups and outlasted the copy by
+// half) and its 8 KiB of LDS per workgroup would leave a CU of single-wave workgroups 19 waves
+// instead of 32, so the launch wants wide workgroups; the copy wants narrow ones.  Measured on
+// 14336-byte rows (per step of a stream, 15 next hops): 128 lanes 80 us, 192: 67, 256: 63, 320: 55.3,
+// 384: 55.8, 448: 57.4, 512: 61, 896: 57.2.  An even number of unequal segments would hand the short
+// segment to the same XCDs every row (256 lanes: four segments, the last half empty).
+static mw_row_shape relay_stream_shape(int n_chunks)
+{
+    int nseg = (n_chunks + 383) / 384;
+    if (nseg > 1 && nseg % 2 == 0) ++nseg;
+    return mw_row_shape{((n_chunks + nseg - 1) / nseg + 63) / 64 * 64, nseg};
+}
+
 static mw_relay_index_args relay_index_args(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay_child *children,
                                             int64_t cap, mw_relay_stats *stats)
 {
@@ -536,15 +551,7 @@ int32_t mw_launch_relay_copy(mw_ctx *ctx, const mw_recv_peer *in, const mw_relay
                                c.top_k, n_chunks, (int)(ctx->row_stride / 16), (uint32_t)c.max_tokens,
                                (uint64_t)ctx->row_bytes, ctx->d_group_of_row, ctx->d_child_pos, ctx->d_relay_flags, stats);
         } else {
-            // Long rows of whole cache lines: a few large workgroups per row instead of single
-            // waves.  The riding index walks the groups a workgroup's width at a time, one memory
-            // round trip and two scans per step: 128 lanes took 32 steps for 4096 groups and
-            // outlasted the copy by half; and its 8 KiB of LDS per workgroup would leave a CU of
-            // single-wave workgroups 19 waves instead of 32.
-            if (shape.bs == 64 && n_chunks % 16 == 0) {
-                shape.nseg = (n_chunks + 511) / 512;
-                shape.bs = ((n_chunks + shape.nseg - 1) / shape.nseg + 63) / 64 * 64;
-            }
+            if (shape.bs == 64 && n_chunks % 16 == 0) shape = relay_stream_shape(n_chunks);
             hipLaunchKernelGGL(k_relay_copy_index_next, dim3(shape.nseg, gy + (uint32_t)next->n_hops + 1u),
                                dim3(shape.bs), 0, s, (uint32_t)next->n_hops + 1u, 0u, in, children, ctx->n_hops, c.top_k, n_chunks,
                                (int)(ctx->row_stride / 16), (uint32_t)c.max_tokens, (uint64_t)ctx->row_bytes,
@@ -564,10 +571,7 @@ int32_t mw_launch_relay_batch(const mw_relay_job *copy, int32_t n_copy, const mw
     const int n_chunks = (int)(ctx->row_bytes / 16);
     mw_row_shape shape = mw_row_shape_of(n_chunks);
     // long rows of whole cache lines: a few large workgroups per row beside a riding index (see mw_launch_relay_copy)
-    if (n_index > 0 && shape.bs == 64 && n_chunks % 16 == 0) {
-        shape.nseg = (n_chunks + 511) / 512;
-        shape.bs = ((n_chunks + shape.nseg - 1) / shape.nseg + 63) / 64 * 64;
-    }
+    if (n_index > 0 && shape.bs == 64 && n_chunks % 16 == 0) shape = relay_stream_shape(n_chunks);
     uint32_t gy = (uint32_t)c.max_tokens < 8192u ? (uint32_t)c.max_tokens : 8192u;      // per buffer; more rows by striding
     if (gy < 1) gy = 1;
     mw_relay_batch_args b = {};
@@ -646,12 +650,9 @@ int32_t mw_launch_relay_packets_copy(mw_ctx *ctx, const mw_recv_packets *in, voi
                                n_chunks, (uint32_t)c.max_tokens, pb, ctx->d_hop_bits, ctx->d_child_pos,
                                ctx->d_relay_flags, stats, keep);
         } else {
-            // long packets: a few large workgroups per packet instead of single waves, for the
-            // riding index's sake (see mw_launch_relay_copy); pieces stay whole cache lines
-            if (shape.bs == 64) {
-                shape.nseg = (n_chunks + 511) / 512;
-                shape.bs = ((n_chunks + shape.nseg - 1) / shape.nseg + 63) / 64 * 64;
-            }
+            // long packets: a few larger workgroups per packet instead of single waves, for the
+            // riding index's sake (see relay_stream_shape); pieces stay whole cache lines
+            if (shape.bs == 64) shape = relay_stream_shape(n_chunks);
             hipLaunchKernelGGL(k_relay_packets_copy_index_next, dim3(shape.nseg, gy + (uint32_t)next->n_hops + 1u),
                                dim3(shape.bs), 0, s, (uint32_t)next->n_hops + 1u, 0u, in, children, ctx->n_hops, n_chunks, (uint32_t)c.max_tokens, pb,
                                ctx->d_hop_bits, ctx->d_child_pos, ctx->d_relay_flags, stats, keep,
