@@ -205,7 +205,9 @@ __device__ __forceinline__ void mw_acquire_after_poll()
 // Exclusive prefix sum over one value per thread of a block (blockDim.x multiple of 64,
 // at most 1024).  `wave_tot` is LDS scratch of 17 words.  Returns the exclusive prefix;
 // *total receives the block total.  Ends with a barrier so the scratch can be reused.  The
-// barriers order LDS only.
+// barriers order LDS only.  Every wave adds up the waves' totals for itself (one LDS read a
+// lane and a 16-lane scan): a single thread walking them took a dependent LDS round trip per
+// wave, a microsecond for 1024 lanes.
 __device__ __forceinline__ uint32_t mw_block_exscan(uint32_t v, uint32_t *wave_tot, uint32_t *total)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_wave = blockDim.x >> 6;
@@ -217,16 +219,16 @@ __device__ __forceinline__ uint32_t mw_block_exscan(uint32_t v, uint32_t *wave_t
     }
     if (lane == 63) wave_tot[wave] = inc;
     mw_lds_barrier();
-    if (threadIdx.x == 0) {
-        uint32_t run = 0;
-        for (int w = 0; w < n_wave; ++w) { uint32_t t = wave_tot[w]; wave_tot[w] = run; run += t; }
-        wave_tot[16] = run;
+    uint32_t t = (lane < n_wave) ? wave_tot[lane] : 0u;
+#pragma unroll
+    for (int d = 1; d < 16; d <<= 1) {
+        uint32_t o = __shfl_up(t, d, 64);
+        if (lane >= d) t += o;
     }
+    const uint32_t before = (wave > 0) ? (uint32_t)__shfl((int)t, wave - 1, 64) : 0u;
+    *total = (uint32_t)__shfl((int)t, n_wave - 1, 64);
     mw_lds_barrier();
-    const uint32_t ex = wave_tot[wave] + inc - v;
-    *total = wave_tot[16];
-    mw_lds_barrier();
-    return ex;
+    return before + inc - v;
 }
 #endif
 
