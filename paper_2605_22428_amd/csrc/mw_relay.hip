@@ -27,27 +27,6 @@ constexpr int kBlock = 1024;
 constexpr uint32_t kNoChild = 0xffffffffu;
 constexpr uint32_t kLongGroup = 32;          // rows; longer groups are filled cooperatively
 
-struct grp_view { uint64_t m[MW_MASK_WORDS]; uint32_t off, cnt; bool valid; };
-
-// Descriptor g of the input with its validity: a non-empty row range inside the buffer that
-// starts at or after the end of the previous descriptor's range.
-__device__ __forceinline__ grp_view load_group(const mw_group_desc *desc, uint32_t g, uint32_t G, uint32_t n_rows)
-{
-    grp_view v;
-#pragma unroll
-    for (int w = 0; w < MW_MASK_WORDS; ++w) v.m[w] = 0;
-    v.off = v.cnt = 0; v.valid = false;
-    if (g >= G) return v;
-    const mw_group_desc *d = desc + g;
-#pragma unroll
-    for (int w = 0; w < MW_MASK_WORDS; ++w) v.m[w] = d->mask[w];
-    v.off = d->row_offset; v.cnt = d->row_count;
-    uint64_t prev_end = 0;
-    if (g > 0) prev_end = (uint64_t)desc[g - 1].row_offset + desc[g - 1].row_count;
-    v.valid = v.cnt >= 1 && (uint64_t)v.off + v.cnt <= n_rows && v.off >= prev_end;
-    return v;
-}
-
 // Everything the index of one relay step needs (one kernel argument).
 struct mw_relay_index_args {
     const mw_recv_peer *in; const mw_relay_child *children; int n_hops, n_ranks;
@@ -55,6 +34,114 @@ struct mw_relay_index_args {
     int32_t *group_of_row; uint32_t *child_pos; uint32_t *relay_flags; mw_relay_stats *stats;
     uint32_t keep_metadata;     // 1: children carry the parent's bitmaps (Section 4.1: the update may be omitted)
 };
+
+// The bitmap of ranks below n_ranks, word w.
+__device__ __forceinline__ uint64_t valid_rank_word(int n_ranks, int w)
+{
+    const int lo = w * 64;
+    return (n_ranks >= lo + 64) ? ~0ull : (n_ranks > lo ? ((1ull << (n_ranks - lo)) - 1ull) : 0ull);
+}
+
+// Child descriptor table of next hop h, by one workgroup.  A lane takes KP consecutive groups a
+// step and reads of each what the ranking needs: the NW bitmap words that can name a rank
+// (ranks < 64 NW; the hop's rank set and the valid ranks have nothing above them), the row range,
+// and the end of the range in front (a descriptor is valid if its row range is not empty, lies
+// inside the buffer and starts at or after the end of the previous descriptor's).  All of a step's loads are
+// issued before the first is used -- addresses are clamped instead of branched around -- so a
+// step is one memory round trip whatever KP; then one scan of the lanes' kept groups and one
+// of their rows place every kept group in parent order.
+template <int NW, int KP>
+__device__ __forceinline__ uint32_t relay_index_hop(
+    const mw_recv_peer &src, const uint32_t G, const uint32_t n_rows, mw_group_desc *__restrict__ cdesc, const int h,
+    const int n_ranks, const uint32_t cap, const uint64_t *__restrict__ hop_bits, uint32_t *__restrict__ child_pos,
+    mw_relay_stats *__restrict__ stats, const uint32_t keep_metadata, uint32_t *scratch, uint32_t *fit)
+{
+    const uint32_t bs = blockDim.x, tid = threadIdx.x;
+    uint32_t err = 0;
+    uint64_t hb[NW], ok[NW];
+#pragma unroll
+    for (int w = 0; w < NW; ++w) { hb[w] = hop_bits[(size_t)h * MW_MASK_WORDS + w]; ok[w] = valid_rank_word(n_ranks, w); }
+    if (tid < 2) fit[tid] = 0;
+    mw_lds_barrier();
+    uint32_t carry_g = 0, carry_r = 0;
+    for (uint32_t g0 = 0; g0 < G; g0 += bs * KP) {
+        const uint32_t gl = g0 + tid * KP;           // this lane's first group
+        uint64_t m[KP][NW];
+        uint2 oc[KP];
+#pragma unroll
+        for (int k = 0; k < KP; ++k) {
+            const mw_group_desc *d = src.desc + min(gl + (uint32_t)k, G - 1u);
+#pragma unroll
+            for (int w = 0; w < NW; ++w) m[k][w] = d->mask[w];
+            oc[k] = *(const uint2 *)&d->row_offset;  // (row_offset, row_count)
+        }
+        const uint2 po = *(const uint2 *)&src.desc[min(gl > 0 ? gl - 1u : 0u, G - 1u)].row_offset;
+        uint64_t prev_end = gl > 0 ? (uint64_t)po.x + po.y : 0ull;
+        bool keep[KP];
+        uint32_t nd[KP], lg = 0, lr = 0;
+#pragma unroll
+        for (int k = 0; k < KP; ++k) {
+            const uint32_t off = oc[k].x, cnt = oc[k].y;
+            const bool valid = gl + k < G && cnt >= 1 && (uint64_t)off + cnt <= n_rows && off >= prev_end;
+            prev_end = (uint64_t)off + cnt;
+            uint32_t n = 0;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) n += (uint32_t)__popcll(m[k][w] & hb[w]);
+            keep[k] = valid && n > 0;
+            if (keep_metadata) {                     // the copy carries every destination the parent named
+                n = 0;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) { m[k][w] &= ok[w]; n += (uint32_t)__popcll(m[k][w]); }
+            } else {
+#pragma unroll
+                for (int w = 0; w < NW; ++w) m[k][w] &= hb[w];
+            }
+            nd[k] = n;
+            lg += keep[k] ? 1u : 0u;
+            lr += keep[k] ? cnt : 0u;
+        }
+        uint32_t tot_g, tot_r;
+        uint32_t cg = carry_g + mw_block_exscan(lg, scratch, &tot_g);
+        uint32_t cr = carry_r + mw_block_exscan(lr, scratch, &tot_r);
+        uint32_t fit_g = 0, fit_r = 0;
+#pragma unroll
+        for (int k = 0; k < KP; ++k) {
+            if (gl + k >= G) continue;
+            const uint32_t cnt = oc[k].y;
+            uint32_t pos = kNoChild;
+            if (keep[k]) {
+                if ((uint64_t)cr + cnt <= cap) {
+                    mw_group_desc d;
+#pragma unroll
+                    for (int w = 0; w < MW_MASK_WORDS; ++w) d.mask[w] = 0;
+#pragma unroll
+                    for (int w = 0; w < NW; ++w) d.mask[w] = m[k][w];
+                    d.row_offset = cr; d.row_count = cnt; d.n_dest = nd[k]; d.reserved0 = 0;
+                    cdesc[cg] = d;
+                    pos = cr;
+                    fit_g = cg + 1u; fit_r = cr + cnt;
+                } else {
+                    err |= MW_FLAG_OUT_CAPACITY;
+                }
+                ++cg; cr += cnt;
+            }
+            child_pos[(size_t)(gl + k) * MW_MAX_HOPS + h] = pos;
+        }
+        // kept groups that fit are a prefix of the kept groups: the largest (index + 1, end
+        // row) pair describes the child.  Reduced over the wave first: same-address LDS
+        // atomics of a whole workgroup would serialise.
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            fit_g = max(fit_g, (uint32_t)__shfl_xor((int)fit_g, d, 64));
+            fit_r = max(fit_r, (uint32_t)__shfl_xor((int)fit_r, d, 64));
+        }
+        if ((tid & 63) == 0 && fit_g) { atomicMax(&fit[0], fit_g); atomicMax(&fit[1], fit_r); }
+        carry_g += tot_g; carry_r += tot_r;
+    }
+    mw_lds_barrier();
+    if (tid == 0) { stats->groups_per_hop[h] = fit[0]; stats->rows_per_hop[h] = fit[1]; }
+    return err;
+}
 
 // Workgroup `wg` of the relay index: wg < n_hops builds child wg's descriptor table, wg == n_hops
 // maps rows to groups and does the accounting.  Any workgroup size that is a multiple of 64.
@@ -76,100 +163,62 @@ __device__ __forceinline__ void relay_index_body(
     uint32_t err = (src.n_desc > max_tokens || src.n_rows > max_tokens) ? MW_FLAG_BAD_DESC : 0u;
 
     if (wg < n_hops) {
-        // ---- child descriptor table of next hop h
-        const int h = wg;
-        uint64_t hb[MW_MASK_WORDS];
-#pragma unroll
-        for (int w = 0; w < MW_MASK_WORDS; ++w) hb[w] = hop_bits[(size_t)h * MW_MASK_WORDS + w];
-        mw_group_desc *cdesc = children[h].desc;
-        if (tid < 2) fit[tid] = 0;
-        mw_lds_barrier();
-        uint32_t carry_g = 0, carry_r = 0;
-        grp_view nxt = load_group(src.desc, tid, G, n_rows);
-        for (uint32_t g0 = 0; g0 < G; g0 += bs) {
-            const uint32_t g = g0 + tid;
-            const grp_view v = nxt;
-            nxt = load_group(src.desc, g + bs, G, n_rows);         // in flight during the scans
-            uint64_t sub[MW_MASK_WORDS];
-            uint32_t nd = 0;
-#pragma unroll
-            for (int w = 0; w < MW_MASK_WORDS; ++w) { sub[w] = v.m[w] & hb[w]; nd += (uint32_t)__popcll(sub[w]); }
-            const bool keep = v.valid && nd > 0;
-            if (keep_metadata) {                 // the copy carries every destination the parent named
-                nd = 0;
-#pragma unroll
-                for (int w = 0; w < MW_MASK_WORDS; ++w) {
-                    const int lo = w * 64;
-                    const uint64_t ok = (n_ranks >= lo + 64) ? ~0ull : (n_ranks > lo ? ((1ull << (n_ranks - lo)) - 1ull) : 0ull);
-                    sub[w] = v.m[w] & ok;
-                    nd += (uint32_t)__popcll(sub[w]);
-                }
-            }
-            uint32_t tot_g, tot_r;
-            const uint32_t cg = carry_g + mw_block_exscan(keep ? 1u : 0u, scratch, &tot_g);
-            const uint32_t cr = carry_r + mw_block_exscan(keep ? v.cnt : 0u, scratch, &tot_r);
-            uint32_t fit_g = 0, fit_r = 0;
-            if (g < G) {
-                uint32_t pos = kNoChild;
-                if (keep) {
-                    if ((uint64_t)cr + v.cnt <= cap) {
-                        mw_group_desc d;
-#pragma unroll
-                        for (int w = 0; w < MW_MASK_WORDS; ++w) d.mask[w] = sub[w];
-                        d.row_offset = cr; d.row_count = v.cnt; d.n_dest = nd; d.reserved0 = 0;
-                        cdesc[cg] = d;
-                        pos = cr;
-                        fit_g = cg + 1u; fit_r = cr + v.cnt;
-                    } else {
-                        err |= MW_FLAG_OUT_CAPACITY;
-                    }
-                }
-                child_pos[(size_t)g * MW_MAX_HOPS + h] = pos;
-            }
-            // kept groups that fit are a prefix of the kept groups: the largest (index + 1, end
-            // row) pair describes the child.  Reduced over the wave first: same-address LDS
-            // atomics of a whole workgroup would serialise.
-#pragma unroll
-            for (int d = 32; d >= 1; d >>= 1) {
-                fit_g = max(fit_g, (uint32_t)__shfl_xor((int)fit_g, d, 64));
-                fit_r = max(fit_r, (uint32_t)__shfl_xor((int)fit_r, d, 64));
-            }
-            if ((tid & 63) == 0 && fit_g) { atomicMax(&fit[0], fit_g); atomicMax(&fit[1], fit_r); }
-            carry_g += tot_g; carry_r += tot_r;
-        }
-        mw_lds_barrier();
-        if (tid == 0) { stats->groups_per_hop[h] = fit[0]; stats->rows_per_hop[h] = fit[1]; }
+        // ---- child descriptor table of next hop wg: three groups a lane and step where one bitmap
+        // word holds every rank, two for two words
+        mw_group_desc *cdesc = children[wg].desc;
+        if (n_ranks <= 64)
+            err |= relay_index_hop<1, 3>(src, G, n_rows, cdesc, wg, n_ranks, cap, hop_bits, child_pos, stats, keep_metadata, scratch, fit);
+        else if (n_ranks <= 128)
+            err |= relay_index_hop<2, 2>(src, G, n_rows, cdesc, wg, n_ranks, cap, hop_bits, child_pos, stats, keep_metadata, scratch, fit);
+        else
+            err |= relay_index_hop<MW_MASK_WORDS, 1>(src, G, n_rows, cdesc, wg, n_ranks, cap, hop_bits, child_pos, stats, keep_metadata, scratch, fit);
     } else {
-        // ---- rows -> groups, accounting.  A group's thread writes the group's index over its
-        // rows; groups longer than kLongGroup rows are queued in LDS and filled by the whole
-        // workgroup.  Rows of no valid group keep whatever the array held: the copy kernel
-        // checks every entry against the descriptors.
+        // ---- rows -> groups, accounting, two groups a lane and step.  A group's thread writes the
+        // group's index over its rows; groups longer than kLongGroup rows are queued in LDS and
+        // filled by the whole workgroup.  Rows of no valid group keep whatever the array held: the
+        // copy kernel checks every entry against the descriptors.
         if (tid < 2) acc[tid] = 0;
         if (tid == 0) n_long = 0;
         mw_lds_barrier();
         uint64_t valid_ranks[MW_MASK_WORDS];
 #pragma unroll
-        for (int w = 0; w < MW_MASK_WORDS; ++w) {
-            const int lo = w * 64;
-            valid_ranks[w] = (n_ranks >= lo + 64) ? ~0ull : (n_ranks > lo ? ((1ull << (n_ranks - lo)) - 1ull) : 0ull);
-        }
+        for (int w = 0; w < MW_MASK_WORDS; ++w) valid_ranks[w] = valid_rank_word(n_ranks, w);
         unsigned long long rows_in = 0, dest_rows = 0;
         uint32_t groups_in = 0;
-        for (uint32_t g = tid; g < G; g += bs) {
-            const grp_view v = load_group(src.desc, g, G, n_rows);
-            if (!v.valid) { err |= MW_FLAG_BAD_DESC; continue; }
-            uint32_t nd = 0;
+        constexpr int KA = 2;
+        for (uint32_t g0 = 0; g0 < G; g0 += bs * KA) {
+            const uint32_t gl = g0 + tid * KA;
+            uint64_t m[KA][MW_MASK_WORDS];
+            uint2 oc[KA];
 #pragma unroll
-            for (int w = 0; w < MW_MASK_WORDS; ++w) {
-                if (v.m[w] & ~valid_ranks[w]) err |= MW_FLAG_BAD_RANK;
-                nd += (uint32_t)__popcll(v.m[w] & valid_ranks[w]);
+            for (int k = 0; k < KA; ++k) {
+                const mw_group_desc *d = src.desc + min(gl + (uint32_t)k, G - 1u);
+#pragma unroll
+                for (int w = 0; w < MW_MASK_WORDS; ++w) m[k][w] = d->mask[w];
+                oc[k] = *(const uint2 *)&d->row_offset;
             }
-            if (v.cnt <= kLongGroup) {
-                for (uint32_t r = 0; r < v.cnt; ++r) group_of_row[v.off + r] = (int32_t)g;
-            } else {
-                long_groups[atomicAdd(&n_long, 1u)] = g;      // at most max_tokens / kLongGroup of them
+            const uint2 po = *(const uint2 *)&src.desc[min(gl > 0 ? gl - 1u : 0u, G - 1u)].row_offset;
+            uint64_t prev_end = gl > 0 ? (uint64_t)po.x + po.y : 0ull;
+#pragma unroll
+            for (int k = 0; k < KA; ++k) {
+                const uint32_t g = gl + k, off = oc[k].x, cnt = oc[k].y;
+                const bool valid = cnt >= 1 && (uint64_t)off + cnt <= n_rows && off >= prev_end;
+                prev_end = (uint64_t)off + cnt;
+                if (g >= G) continue;
+                if (!valid) { err |= MW_FLAG_BAD_DESC; continue; }
+                uint32_t nd = 0;
+#pragma unroll
+                for (int w = 0; w < MW_MASK_WORDS; ++w) {
+                    if (m[k][w] & ~valid_ranks[w]) err |= MW_FLAG_BAD_RANK;
+                    nd += (uint32_t)__popcll(m[k][w] & valid_ranks[w]);
+                }
+                if (cnt <= kLongGroup) {
+                    for (uint32_t r = 0; r < cnt; ++r) group_of_row[off + r] = (int32_t)g;
+                } else {
+                    long_groups[atomicAdd(&n_long, 1u)] = g;      // at most max_tokens / kLongGroup of them
+                }
+                rows_in += cnt; dest_rows += (unsigned long long)cnt * nd; ++groups_in;
             }
-            rows_in += v.cnt; dest_rows += (unsigned long long)v.cnt * nd; ++groups_in;
         }
         if (rows_in) atomicAdd(&acc[0], rows_in);            // integer sums: order-free
         if (dest_rows) atomicAdd(&acc[1], dest_rows);
@@ -315,29 +364,66 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
 // map: workgroup h ranks the packets that hop h keeps (child position = exclusive count), the
 // extra workgroup does the accounting, and the copy kernel reads a packet once and stores it
 // once per hop with the first 32 bytes -- the bitmap -- replaced by its restriction to that hop.
-struct pkt_view { uint64_t m[MW_MASK_WORDS]; bool valid; };
-
-__device__ __forceinline__ pkt_view load_packet_header(const char *packets, uint64_t packet_bytes, uint32_t i,
-                                                       uint32_t n_rows, uint32_t K)
-{
-    pkt_view v;
-#pragma unroll
-    for (int w = 0; w < MW_MASK_WORDS; ++w) v.m[w] = 0;
-    v.valid = false;
-    if (i >= n_rows) return v;
-    const char *hd = packets + (size_t)i * packet_bytes;
-    const u32x4 a = *(const u32x4 *)hd, b = *(const u32x4 *)(hd + 16);
-    v.m[0] = ((uint64_t)a.y << 32) | a.x; v.m[1] = ((uint64_t)a.w << 32) | a.z;
-    v.m[2] = ((uint64_t)b.y << 32) | b.x; v.m[3] = ((uint64_t)b.w << 32) | b.z;
-    v.valid = *(const uint32_t *)(hd + 36) == K;
-    return v;
-}
-
 // Everything the index of one relay step of packets needs (one kernel argument).
 struct mw_relay_packets_index_args {
     const mw_recv_packets *in; int n_hops, n_ranks; uint32_t K, max_tokens, cap; uint64_t packet_bytes;
     const uint64_t *hop_bits; uint32_t *child_pos; uint32_t *relay_flags; mw_relay_stats *stats;
 };
+
+// Positions of the packets that next hop h keeps, by one workgroup: KP consecutive packets a
+// lane and step, of each header the NW bitmap words that can name a rank and the id count, all
+// loads of a step issued before the first is used (as relay_index_hop).
+template <int NW, int KP>
+__device__ __forceinline__ uint32_t relay_packets_index_hop(
+    const char *__restrict__ packets, const uint64_t packet_bytes, const uint32_t n_rows, const uint32_t K, const int h,
+    const uint32_t cap, const uint64_t *__restrict__ hop_bits, uint32_t *__restrict__ child_pos,
+    mw_relay_stats *__restrict__ stats, uint32_t *scratch)
+{
+    const uint32_t tid = threadIdx.x, bs = blockDim.x;
+    uint32_t err = 0;
+    uint64_t hb[NW];
+#pragma unroll
+    for (int w = 0; w < NW; ++w) hb[w] = hop_bits[(size_t)h * MW_MASK_WORDS + w];
+    uint32_t carry = 0;
+    for (uint32_t i0 = 0; i0 < n_rows; i0 += bs * KP) {
+        const uint32_t il = i0 + tid * KP;
+        uint64_t m[KP][NW];
+        uint32_t nid[KP];
+#pragma unroll
+        for (int k = 0; k < KP; ++k) {
+            const char *hd = packets + (size_t)min(il + (uint32_t)k, n_rows - 1u) * packet_bytes;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) m[k][w] = *(const uint64_t *)(hd + 8 * w);
+            nid[k] = *(const uint32_t *)(hd + 36);
+        }
+        bool keep[KP];
+        uint32_t lk = 0;
+#pragma unroll
+        for (int k = 0; k < KP; ++k) {
+            bool any = false;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) any |= (m[k][w] & hb[w]) != 0;
+            keep[k] = any && il + k < n_rows && nid[k] == K;
+            lk += keep[k] ? 1u : 0u;
+        }
+        uint32_t tot;
+        uint32_t pos = carry + mw_block_exscan(lk, scratch, &tot);
+#pragma unroll
+        for (int k = 0; k < KP; ++k) {
+            if (il + k >= n_rows) continue;
+            const bool fits = keep[k] && pos < cap;
+            if (keep[k] && !fits) err |= MW_FLAG_OUT_CAPACITY;
+            child_pos[(size_t)(il + k) * MW_MAX_HOPS + h] = fits ? pos : kNoChild;
+            pos += keep[k] ? 1u : 0u;
+        }
+        carry += tot;
+    }
+    if (tid == 0) {
+        const uint32_t fit = min(carry, cap);      // the packets that fit are a prefix of the kept ones
+        stats->groups_per_hop[h] = fit; stats->rows_per_hop[h] = fit;
+    }
+    return err;
+}
 
 // Workgroup `wg` of the packets' relay index (wg < n_hops: hop wg's positions; wg == n_hops: the
 // accounting).  Any workgroup size that is a multiple of 64.
@@ -355,52 +441,41 @@ __device__ __forceinline__ void relay_packets_index_body(
     uint32_t err = src.n_rows > max_tokens ? MW_FLAG_BAD_DESC : 0u;
 
     if (wg < n_hops) {
-        const int h = wg;
-        uint64_t hb[MW_MASK_WORDS];
-#pragma unroll
-        for (int w = 0; w < MW_MASK_WORDS; ++w) hb[w] = hop_bits[(size_t)h * MW_MASK_WORDS + w];
-        uint32_t carry = 0;
-        pkt_view nxt = load_packet_header(packets, packet_bytes, tid, n_rows, K);
-        for (uint32_t i0 = 0; i0 < n_rows; i0 += bs) {
-            const uint32_t i = i0 + tid;
-            const pkt_view v = nxt;
-            nxt = load_packet_header(packets, packet_bytes, i + bs, n_rows, K);       // in flight during the scan
-            bool keep = false;
-#pragma unroll
-            for (int w = 0; w < MW_MASK_WORDS; ++w) keep |= (v.m[w] & hb[w]) != 0;
-            keep = keep && v.valid;
-            uint32_t tot;
-            const uint32_t pos = carry + mw_block_exscan(keep ? 1u : 0u, scratch, &tot);
-            if (i < n_rows) {
-                const bool fits = keep && pos < cap;
-                if (keep && !fits) err |= MW_FLAG_OUT_CAPACITY;
-                child_pos[(size_t)i * MW_MAX_HOPS + h] = fits ? pos : kNoChild;
-            }
-            carry += tot;
-        }
-        if (tid == 0) {
-            const uint32_t fit = min(carry, cap);      // the packets that fit are a prefix of the kept ones
-            stats->groups_per_hop[h] = fit; stats->rows_per_hop[h] = fit;
-        }
+        if (n_ranks <= 64)
+            err |= relay_packets_index_hop<1, 4>(packets, packet_bytes, n_rows, K, wg, cap, hop_bits, child_pos, stats, scratch);
+        else if (n_ranks <= 128)
+            err |= relay_packets_index_hop<2, 4>(packets, packet_bytes, n_rows, K, wg, cap, hop_bits, child_pos, stats, scratch);
+        else
+            err |= relay_packets_index_hop<MW_MASK_WORDS, 2>(packets, packet_bytes, n_rows, K, wg, cap, hop_bits, child_pos, stats, scratch);
     } else {
         if (tid < 2) acc[tid] = 0;
         mw_lds_barrier();
         uint64_t valid_ranks[MW_MASK_WORDS];
 #pragma unroll
-        for (int w = 0; w < MW_MASK_WORDS; ++w) {
-            const int lo = w * 64;
-            valid_ranks[w] = (n_ranks >= lo + 64) ? ~0ull : (n_ranks > lo ? ((1ull << (n_ranks - lo)) - 1ull) : 0ull);
-        }
+        for (int w = 0; w < MW_MASK_WORDS; ++w) valid_ranks[w] = valid_rank_word(n_ranks, w);
         uint32_t taken = 0, dests = 0;
-        for (uint32_t i = tid; i < n_rows; i += bs) {
-            const pkt_view v = load_packet_header(packets, packet_bytes, i, n_rows, K);
-            if (!v.valid) { err |= MW_FLAG_BAD_DESC; continue; }
+        constexpr int KA = 2;                       // two headers a lane in flight
+        for (uint32_t i0 = 0; i0 < n_rows; i0 += bs * KA) {
+            uint64_t m[KA][MW_MASK_WORDS];
+            uint32_t nid[KA];
 #pragma unroll
-            for (int w = 0; w < MW_MASK_WORDS; ++w) {
-                if (v.m[w] & ~valid_ranks[w]) err |= MW_FLAG_BAD_RANK;
-                dests += (uint32_t)__popcll(v.m[w] & valid_ranks[w]);
+            for (int k = 0; k < KA; ++k) {
+                const char *hd = packets + (size_t)min(i0 + k * bs + tid, n_rows - 1u) * packet_bytes;
+#pragma unroll
+                for (int w = 0; w < MW_MASK_WORDS; ++w) m[k][w] = *(const uint64_t *)(hd + 8 * w);
+                nid[k] = *(const uint32_t *)(hd + 36);
             }
-            ++taken;
+#pragma unroll
+            for (int k = 0; k < KA; ++k) {
+                if (i0 + k * bs + tid >= n_rows) continue;
+                if (nid[k] != K) { err |= MW_FLAG_BAD_DESC; continue; }
+#pragma unroll
+                for (int w = 0; w < MW_MASK_WORDS; ++w) {
+                    if (m[k][w] & ~valid_ranks[w]) err |= MW_FLAG_BAD_RANK;
+                    dests += (uint32_t)__popcll(m[k][w] & valid_ranks[w]);
+                }
+                ++taken;
+            }
         }
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) { taken += __shfl_xor(taken, d, 64); dests += __shfl_xor(dests, d, 64); }
@@ -472,8 +547,11 @@ __global__ __launch_bounds__(1024) void k_relay_packets_copy(
 }
 
 // The packets' form of k_relay_copy_index_next: this buffer's copy with the next buffer's index
-// (another context's workspace) in the first next.n_hops + 1 workgroup rows.
-__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_relay_packets_copy_index_next(
+// (another context's workspace) in the first next.n_hops + 1 workgroup rows.  Held to 64 scalar
+// registers as well: with the 69 the index's branch would take, the copy's step is 6 % longer
+// (56.9 -> 60.4 us; forcing the count up with nothing else changed shows the same), the four
+// values over the limit live in lanes of a vector register instead.
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8), amdgpu_num_sgpr(64))) void k_relay_packets_copy_index_next(
     const uint32_t first_copy_row, const uint32_t unused0,
     const mw_recv_packets *__restrict__ in, void *const *__restrict__ children, int n_hops, int n_chunks,
     uint32_t max_tokens, uint64_t packet_bytes, const uint64_t *__restrict__ hop_bits,
