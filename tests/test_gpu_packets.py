@@ -237,10 +237,14 @@ def gpu_relay_packets(ctx, packets, n_rows, next_hop, n_hops, capacity):
     return kids, st
 
 
-@pytest.mark.parametrize("which", ["c0", "c1_reduced", "c3_reduced", "fp8"])
+@pytest.mark.parametrize("which", ["c0", "c1_reduced", "c3_reduced", "fp8", "ep96", "ep200"])
 def test_relay_packets_children_and_accounting(which):
+    import dataclasses
     w = {"c0": W.C0, "c1_reduced": W.scaled(W.C1, n_tokens=333, hidden=1024),
          "c3_reduced": W.scaled(W.C3, n_tokens=200, hidden=512),
+         # bitmaps of two words and of four with the last partly used (the index reads only the words that can name a rank)
+         "ep96": dataclasses.replace(W.C3, name="ep96", n_ranks=96, n_experts=192, n_tokens=300, hidden=512),
+         "ep200": dataclasses.replace(W.C3, name="ep200", n_ranks=200, n_experts=200, n_tokens=1100, hidden=256),
          "fp8": W.scaled(W.C2, n_tokens=150, hidden=1024)}[which]
     _say("relay packets", w.name)
     n_per = 8

@@ -377,3 +377,61 @@ def test_relay_batch_two_buffers_a_launch(which):
         assert ei.value.status == B.MW_ERR_INVALID_ARG
     for c in ctxs:
         c.close()
+
+
+def _wide(n_ranks, n_experts, n_tokens=300, hidden=512):
+    """A Zipf-routed workload over more than 64 ranks: bitmaps of two to four words."""
+    import dataclasses
+    return dataclasses.replace(W.C3, name="ep%d" % n_ranks, n_ranks=n_ranks, n_experts=n_experts,
+                               n_tokens=n_tokens, hidden=hidden)
+
+
+@pytest.mark.parametrize("n_ranks,n_experts,n_hops,keep", [(96, 192, 11, False), (128, 256, 40, True),
+                                                            (200, 200, 7, False), (256, 256, 64, True),
+                                                            (65, 130, 3, False)])
+def test_relay_bitmaps_of_more_than_one_word(n_ranks, n_experts, n_hops, keep):
+    """The index reads only the bitmap words that can name a rank (one, two or four): every width,
+    with a last word that is partly used, in both forms of the metadata update, and the same
+    index riding in a stream's copy launch."""
+    w = _wide(n_ranks, n_experts)
+    _say("relay over", n_ranks, "ranks,", n_hops, "hops, metadata kept:", keep)
+    rng = np.random.default_rng(n_ranks)
+    next_hop = rng.integers(0, n_hops, size=w.n_ranks).astype(np.int32)
+    next_hop[rng.integers(0, w.n_ranks, size=n_hops)] = np.arange(n_hops)      # every hop in use
+    ctx = _ctx(w, 0, 64)
+    ctx.mw_ctx_set_options(B.MW_OPT_RELAY_KEEP_METADATA if keep else 0)
+    tk, x, sc, g = _send(ctx, w, 5, 0)
+    parent = H.oracle_send(w, tk, x, sc)
+    ch, st, table = gpu_relay(ctx, g.full_record(), next_hop, n_hops, w.n_tokens)
+
+    def check(ch, st):
+        for h in range(n_hops):
+            want = ref.relay_child(*parent, next_hop, n_hops, h, update_metadata=not keep)
+            got = child_host(ch, st, h, w.row_bytes)
+            for a, b, what in zip(got, want, ("desc", "rows", "src_token", "row_topk")):
+                H.assert_same_bytes(a.view(np.uint8), b.view(np.uint8), "child %d %s" % (h, what))
+        fwd, uni, rph = ref.relay_accounting(parent[0], w.row_bytes, next_hop, n_hops)
+        assert int(st["error_flags"]) == 0
+        assert (int(st["forward_bytes"]), int(st["unicast_bytes"])) == (fwd, uni)
+        assert st["rows_per_hop"][:n_hops].tolist() == rph.tolist()
+        assert int(st["n_groups_in"]) == len(parent[0]) and int(st["n_rows_in"]) == len(parent[1])
+
+    check(ch, st)
+    # the same index as a rider: context 2 indexes in the launch that copies for context 1
+    ctx2 = _ctx(w, 0, 64)
+    ctx2.mw_ctx_set_options(B.MW_OPT_RELAY_KEEP_METADATA if keep else 0)
+    ctx2.mw_set_forwarding(next_hop, n_hops)
+    ch2 = B.RelayChildren(ctx2, n_hops, w.n_tokens)
+    ctx.mw_relay_index(table, ch.table, w.n_tokens, ch.stats)
+    ctx.mw_relay_copy_index_next(table, ch.table, ch.stats, ctx2, table, ch2.table, w.n_tokens, ch2.stats)
+    ctx2.mw_relay_copy(table, ch2.table, ch2.stats)
+    check(ch, ctx.mw_get_relay_stats(ch.stats))
+    check(ch2, ctx2.mw_get_relay_stats(ch2.stats))
+    # a bit for a rank that does not exist, in the last word that is partly used and beyond it
+    if n_ranks % 64:
+        bad = H.host(g.buf.desc).copy().reshape(-1).view(B.DESC_DTYPE)
+        bad["mask"][1][n_ranks // 64] |= np.uint64(1) << np.uint64(n_ranks % 64)
+        rec = dict(g.full_record()); rec["desc"] = H.dev(bad.view(np.uint8).reshape(-1, B.DESC_BYTES))
+        ch3, st3, _ = gpu_relay(ctx, rec, next_hop, n_hops, w.n_tokens)
+        assert int(st3["error_flags"]) & B.MW_FLAG_BAD_RANK
+    ctx.close(); ctx2.close()
