@@ -344,7 +344,7 @@ def test_relay_packets_stream_index_of_the_next_buffer_rides_with_the_copy(which
     stream of packet buffers on two contexts with different forwarding tables: every step's
     children and statistics against the oracle; one buffer is short and one is empty."""
     w = {"c1_reduced": W.scaled(W.C1, n_tokens=300, hidden=1024),
-         "long_packets": W.scaled(W.C1, n_tokens=120, hidden=7168),      # 904 chunks: two workgroups per packet
+         "long_packets": W.scaled(W.C1, n_tokens=120, hidden=7168),      # 904 chunks: three 320-lane workgroups per packet
          "fp8": W.scaled(W.C2, n_tokens=200, hidden=1024)}[which]
     _say("relay packets stream", w.name)
     rng = np.random.default_rng(6)

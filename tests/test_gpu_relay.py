@@ -282,7 +282,7 @@ def test_relay_stream_index_of_the_next_buffer_rides_with_the_copy(which):
     contexts with different forwarding tables: every step's children and statistics against the
     oracle, whatever index ran beside its copy; one buffer is short and one is empty."""
     w = {"bf16_short_rows": W.scaled(W.C1, n_tokens=300, hidden=1024),
-         "bf16_long_rows": W.scaled(W.C1, n_tokens=150, hidden=7168),      # two 448-lane workgroups per row
+         "bf16_long_rows": W.scaled(W.C1, n_tokens=150, hidden=7168),      # three 320-lane workgroups per row
          "bf16_single_waves": W.scaled(W.C1, n_tokens=100, hidden=5184),   # 648 chunks: 64-lane workgroups
          "fp8": W.scaled(W.C2, n_tokens=260, hidden=1024)}[which]
     _say("relay stream", w.name)
